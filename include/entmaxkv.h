@@ -1,0 +1,197 @@
+/* entmaxkv.h -- C ABI of the MI355X (gfx950) decode hot path of EntmaxKV:
+ * support-aware sparse alpha-entmax attention over a paged KV cache.
+ *
+ * One decode step (paper Sec. 4.1, Sec. 4.4) is, per sequence b and query head h:
+ *   stats (build once / append per token) -> score pages -> select pages -> sparse entmax decode,
+ * with a dense full-cache entmax decode alongside as the baseline.
+ *
+ * Conventions (all entry points):
+ *  - plain C, no exceptions; every call returns an ekv_status.
+ *  - every pointer named in a *_view or marked "device" is a DEVICE pointer owned by the caller,
+ *    16-byte aligned; the library allocates no device memory.  Scratch comes from the caller's
+ *    workspace (size from ekv_workspace_bytes).  Config structs are HOST pointers.
+ *  - calls enqueue kernels on `stream` (a hipStream_t passed as void*; NULL = default stream) and
+ *    return without synchronising; no device data is read on the host.
+ *  - variable-length results are (indices, count) pairs on the device with fixed capacity.
+ *  - the same inputs give bit-identical outputs from run to run (fixed reduction orders, no
+ *    floating-point atomics).
+ *  - outputs must not alias inputs.
+ *
+ * Shapes use: B batch, Hq query heads, Hkv KV heads, G=Hq/Hkv, d head_dim (=128), P page_size,
+ * Mmax = max_pages_per_seq, cap = max_sel_pages, n_b = seq_lens[b], M_b = ceil(n_b/P),
+ * a = alpha-1, beta = 1/a.  Query head h reads KV head h / G.
+ */
+#ifndef ENTMAXKV_H
+#define ENTMAXKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  EKV_OK = 0,
+  EKV_ERR_INVALID_ARG = 1, /* null/misaligned pointer, non-positive size, inconsistent config      */
+  EKV_ERR_UNSUPPORTED = 2, /* head_dim / page_size / dtype / alpha this build has no kernel for    */
+  EKV_ERR_WORKSPACE = 3,   /* workspace pointer NULL or smaller than ekv_workspace_bytes reports   */
+  EKV_ERR_HIP = 4          /* a HIP runtime call failed; ekv_last_hip_error() returns its code     */
+} ekv_status;
+
+typedef enum { EKV_F32 = 0, EKV_BF16 = 1 } ekv_dtype;
+
+/* Which page scores ekv_score_pages writes. */
+typedef enum { EKV_SCORE_BOX = 1, EKV_SCORE_GAUSS = 2, EKV_SCORE_BOTH = 3 } ekv_score_mode;
+
+/* Operations a workspace can be sized for. */
+typedef enum {
+  EKV_OP_SELECT_TOPK = 0,
+  EKV_OP_SELECT_GAUSS = 1,
+  EKV_OP_DECODE_SPARSE = 2,
+  EKV_OP_DECODE_FULL = 3,
+  EKV_OP_DECODE_SPARSE_SOFTMAX = 4
+} ekv_op;
+
+/* Problem description (host struct).  head_dim must be 128; page_size a multiple of 4 in [4,64];
+ * n_q_heads a multiple of n_kv_heads with G in {1,2,4,8}; alpha > 1 (beta = 1/(alpha-1) need not
+ * be an integer for the decode calls; ekv_select_gauss needs beta in {1,2,3,4}, paper App. D). */
+typedef struct {
+  int32_t batch;
+  int32_t n_q_heads;
+  int32_t n_kv_heads;
+  int32_t head_dim;
+  int32_t page_size;
+  int32_t kv_dtype;          /* ekv_dtype of K/V pools, q and the page statistics                  */
+  float alpha;               /* entmax alpha (paper Eq. 2)                                         */
+  float scale;               /* score multiplier; the paper's 1/sqrt(d) (Eq. 1)                    */
+  int32_t max_pages_per_seq; /* Mmax: row length of block_table and of the per-page score arrays   */
+  int32_t max_sel_pages;     /* cap: row length of page_idx                                        */
+} ekv_config;
+
+/* Paged KV cache (paper Sec. 4.2: block layout of PagedAttention).  Physical page `phys` of KV head h
+ * is the contiguous block pool[((phys*Hkv + h)*P + t)*d + i], t < P, i < d, element type kv_dtype.
+ * block_table[b*Mmax + p] = physical page of logical page p of sequence b (0 <= phys < n_phys_pages;
+ * entries with p >= M_b are never read).  seq_lens[b] = n_b >= 1. */
+typedef struct {
+  void* k_pool;
+  void* v_pool;
+  const int32_t* block_table;
+  const int32_t* seq_lens;
+  int32_t n_phys_pages;
+} ekv_cache_view;
+
+/* Page statistics (paper Sec. 4.2), stored per SEQUENCE in logical page order so that scoring is a
+ * pure stream:  box  [B][Hkv][Mmax][2][d]  = (k_min, k_max)   element-wise over the page's tokens,
+ *               gauss[B][Hkv][Mmax][2][d]  = (k_avg, k_std)   population mean and standard deviation,
+ * both in kv_dtype.  Rows of pages p >= M_b are not defined.  Either pointer may be NULL in calls
+ * that do not need it (scoring with a mode that does not read it). */
+typedef struct {
+  void* box;
+  void* gauss;
+} ekv_stats_view;
+
+/* a1 -- bulk statistics build (Sec. 4.2).  For every sequence b, KV head and logical page p < M_b,
+ * computes k_min, k_max, k_avg and k_std = sqrt(max(m2 - k_avg^2, 0)) over the page's cnt tokens
+ * (cnt = P, or n_b - pP for the last page) and writes both stats arrays (both must be non-NULL). */
+ekv_status ekv_stats_build(const ekv_config* cfg, const ekv_cache_view* cache,
+                           const ekv_stats_view* stats, void* stream);
+
+/* a2 -- append one token per sequence and bring its page's statistics up to date (Sec. 4.2).
+ * k_new [B][Hkv][d] (device, kv_dtype) is written to slot n_b of the cache (logical page n_b/P,
+ * token n_b%P; that page must already be mapped in block_table and n_b < Mmax*P); v_new likewise
+ * when not NULL.  The statistics of that page are recomputed over its n_b%P + 1 tokens with the
+ * same arithmetic as ekv_stats_build, so append-then-query equals rebuild-then-query bit for bit.
+ * seq_lens is NOT modified: the caller adds 1 to every entry after this call. */
+ekv_status ekv_stats_append(const ekv_config* cfg, const ekv_cache_view* cache,
+                            const ekv_stats_view* stats, const void* k_new, const void* v_new,
+                            void* stream);
+
+/* a3/a4 -- query-aware page scoring (Sec. 4.2 Eq. 9; Sec. 4.3 page moments).
+ * q [B][Hq][d] device, kv_dtype.  Outputs, each f32 [B][Hq][Mmax] (device) or NULL if not requested:
+ *   box[b,h,p]   = scale * sum_i max(q_i kmin_i, q_i kmax_i)          (mode & EKV_SCORE_BOX)
+ *   mu[b,h,p]    = scale * q . k_avg                                   (mode & EKV_SCORE_GAUSS)
+ *   sigma[b,h,p] = scale * sqrt(sum_i q_i^2 k_std,i^2)                 (mode & EKV_SCORE_GAUSS)
+ * Entries p >= M_b are written as -inf (box, mu) and 0 (sigma). */
+ekv_status ekv_score_pages(const ekv_config* cfg, const void* q, const ekv_stats_view* stats,
+                           const int32_t* seq_lens, int32_t mode, float* box, float* mu,
+                           float* sigma, void* stream);
+
+/* a5 -- fixed-budget top-k page selection (Sec. 4.3).  For each (b,h): the min(k_pages, M_b) pages
+ * of largest box score among p < M_b; equal scores are resolved towards the lower page index.
+ * page_idx int32 [B][Hq][cap] receives the logical page indices in ASCENDING order, n_sel int32
+ * [B][Hq] their number.  Requires 1 <= k_pages <= cap. */
+ekv_status ekv_select_topk(const ekv_config* cfg, const float* box, const int32_t* seq_lens,
+                           int32_t k_pages, int32_t* page_idx, int32_t* n_sel, void* workspace,
+                           size_t workspace_bytes, void* stream);
+
+/* a6 -- Gaussian-aware selector (Sec. 4.3 Eq. 10-12, App. D).  Per (b,h): solves
+ *   sum_{p<M_b} cnt_p E[(a S_p - tau)_+^beta] = 1,  S_p ~ N(mu_p, sigma_p^2)      (Eq. 10)
+ * for tau_hat (closed-form truncated Gaussian moments, iterated to float32 convergence), then keeps
+ * page p iff a*(mu_p + sigma_p * PhiInv(q_page^(1/cnt_p))) > tau_hat - margin       (Eq. 11-12).
+ * An empty result is replaced by the single best page; more than cap pages keeps the cap pages of
+ * largest estimate (lower index first on ties) and sets overflow[b,h]=1 (else 0).
+ * tau_hat f32 [B][Hq]; page_idx/n_sel as in ekv_select_topk; overflow int32 [B][Hq].
+ * 0 < q_page < 1, margin >= 0.  beta must be 1, 2, 3 or 4. */
+ekv_status ekv_select_gauss(const ekv_config* cfg, const float* mu, const float* sigma,
+                            const int32_t* seq_lens, float q_page, float margin, float* tau_hat,
+                            int32_t* page_idx, int32_t* n_sel, int32_t* overflow, void* workspace,
+                            size_t workspace_bytes, void* stream);
+
+/* Optional side outputs of the decode calls (all device pointers, any may be NULL).
+ *   support_tokens int32 [B][Hq][support_cap]: logical token indices j with p_j > 0, in candidate
+ *       order (ascending when page_idx is ascending); only the first support_cap are written.
+ *   tau_ref f32 [B][Hq] (input): a reference threshold (normally the full-cache tau); when given,
+ *       kept_mass_ref[b,h] = sum_{j in candidates} (z_j - tau_ref)_+^beta   (1 - dropped mass, Eq. 4)
+ *       kept_supp_ref[b,h] = #{j in candidates : z_j > tau_ref}             (numerator of Eq. 7)
+ *   lse f32 [B][Hq] (ekv_decode_full only): log sum_j exp(scale q.k_j) over the whole cache. */
+typedef struct {
+  int32_t* support_tokens;
+  int32_t support_cap;
+  const float* tau_ref;
+  float* kept_mass_ref;
+  int32_t* kept_supp_ref;
+  float* lse;
+} ekv_decode_extras;
+
+/* a7 -- sparse alpha-entmax attention over the selected pages (Sec. 4.1, Sec. 4.4).
+ * Candidates of (b,h): tokens j < n_b of the pages page_idx[b,h,0..n_sel[b,h]).  z_j = a*scale*q.k_j;
+ * tau is the EXACT root of sum_j (z_j - tau)_+^beta = 1 over the candidates (float32 arithmetic);
+ * p_j = (z_j - tau)_+^beta; out = sum_j p_j v_j.  V rows are read only where p_j > 0.
+ * out f32 [B][Hq][d]; tau f32 [B][Hq]; supp int32 [B][Hq] = #{j: z_j > tau}.  extras may be NULL. */
+ekv_status ekv_decode_sparse(const ekv_config* cfg, const void* q, const ekv_cache_view* cache,
+                             const int32_t* page_idx, const int32_t* n_sel, float* out, float* tau,
+                             int32_t* supp, const ekv_decode_extras* extras, void* workspace,
+                             size_t workspace_bytes, void* stream);
+
+/* a8 -- dense full-cache alpha-entmax decode (Sec. 2.1 Eq. 1 with pi = entmax): ekv_decode_sparse
+ * with every page p < M_b selected.  K is streamed once per KV head for its G query heads. */
+ekv_status ekv_decode_full(const ekv_config* cfg, const void* q, const ekv_cache_view* cache,
+                           float* out, float* tau, int32_t* supp, const ekv_decode_extras* extras,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/* a9 -- softmax attention restricted to the same selected pages (the sparse softmax baseline of
+ * Sec. 5.5 / App. E.1), with its kept mass against the full-cache normaliser (Eq. 8):
+ * out f32 [B][Hq][d] = sum_j softmax(scale q.k_j over candidates) v_j; lse_sel f32 [B][Hq] = log-sum-exp
+ * over the candidates (so kept softmax mass = exp(lse_sel - lse_full)). */
+ekv_status ekv_decode_sparse_softmax(const ekv_config* cfg, const void* q,
+                                     const ekv_cache_view* cache, const int32_t* page_idx,
+                                     const int32_t* n_sel, float* out, float* lse_sel,
+                                     void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of workspace `op` needs under cfg (host computation, no HIP calls). */
+ekv_status ekv_workspace_bytes(const ekv_config* cfg, int32_t op, size_t* bytes);
+
+/* Name of a status code (static string). */
+const char* ekv_status_string(int32_t status);
+
+/* hipError_t code of the most recent failing HIP call on this thread (0 if none). */
+int32_t ekv_last_hip_error(void);
+
+/* Library version, e.g. 100 for 0.1.0. */
+int32_t ekv_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ENTMAXKV_H */

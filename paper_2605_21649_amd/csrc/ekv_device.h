@@ -1,0 +1,164 @@
+// Device-side helpers shared by the gfx950 kernels: 16-byte row loads, wavefront (64-lane)
+// reductions built on DPP row operations, order-preserving float<->uint keys.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ekv {
+
+constexpr int kD = 128;            // head_dim the kernels are written for
+constexpr int kLanesPerRow = 16;   // 16 lanes x 8 channels cover one 128-channel row
+constexpr int kRowsPerWave = 4;    // a 64-lane wavefront covers 4 rows per step
+constexpr int kWave = 64;
+
+struct bf16_t { uint16_t bits; };
+
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
+
+// round-to-nearest-even float -> bf16 bits (finite inputs; NaN is kept quiet)
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+// Load 8 consecutive channels (one lane's share of a 128-channel row) as float.
+template <typename T> __device__ __forceinline__ void load8(const T* p, float (&x)[8]);
+
+template <> __device__ __forceinline__ void load8<float>(const float* p, float (&x)[8]) {
+  const float4 a = *reinterpret_cast<const float4*>(p);
+  const float4 b = *reinterpret_cast<const float4*>(p + 4);
+  x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
+  x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+}
+
+template <> __device__ __forceinline__ void load8<bf16_t>(const bf16_t* p, float (&x)[8]) {
+  const uint4 a = *reinterpret_cast<const uint4*>(p);     // one 16-byte load: 8 bf16
+  x[0] = __uint_as_float(a.x << 16); x[1] = __uint_as_float(a.x & 0xffff0000u);
+  x[2] = __uint_as_float(a.y << 16); x[3] = __uint_as_float(a.y & 0xffff0000u);
+  x[4] = __uint_as_float(a.z << 16); x[5] = __uint_as_float(a.z & 0xffff0000u);
+  x[6] = __uint_as_float(a.w << 16); x[7] = __uint_as_float(a.w & 0xffff0000u);
+}
+
+template <typename T> __device__ __forceinline__ void store8(T* p, const float (&x)[8]);
+
+template <> __device__ __forceinline__ void store8<float>(float* p, const float (&x)[8]) {
+  *reinterpret_cast<float4*>(p) = make_float4(x[0], x[1], x[2], x[3]);
+  *reinterpret_cast<float4*>(p + 4) = make_float4(x[4], x[5], x[6], x[7]);
+}
+
+template <> __device__ __forceinline__ void store8<bf16_t>(bf16_t* p, const float (&x)[8]) {
+  uint4 a;
+  a.x = float_to_bf16_bits(x[0]) | ((uint32_t)float_to_bf16_bits(x[1]) << 16);
+  a.y = float_to_bf16_bits(x[2]) | ((uint32_t)float_to_bf16_bits(x[3]) << 16);
+  a.z = float_to_bf16_bits(x[4]) | ((uint32_t)float_to_bf16_bits(x[5]) << 16);
+  a.w = float_to_bf16_bits(x[6]) | ((uint32_t)float_to_bf16_bits(x[7]) << 16);
+  *reinterpret_cast<uint4*>(p) = a;
+}
+
+// ---- DPP cross-lane moves (no LDS traffic) -------------------------------------------------
+template <int CTRL> __device__ __forceinline__ float dpp_move(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+template <int CTRL> __device__ __forceinline__ int dpp_move_i(int v) {
+  return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true);
+}
+
+// Sum over each aligned group of 16 lanes (a DPP "row"); every lane of the row gets the total.
+// Fixed butterfly order: xor 1, xor 2, half-row mirror, row mirror.
+__device__ __forceinline__ float row16_sum(float v) {
+  v += dpp_move<0xB1>(v);    // quad_perm [1,0,3,2]
+  v += dpp_move<0x4E>(v);    // quad_perm [2,3,0,1]
+  v += dpp_move<0x141>(v);   // row_half_mirror
+  v += dpp_move<0x140>(v);   // row_mirror
+  return v;
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+  v = row16_sum(v);
+  v += __shfl_xor(v, 16);
+  v += __shfl_xor(v, 32);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+  v = fmaxf(v, dpp_move<0xB1>(v));
+  v = fmaxf(v, dpp_move<0x4E>(v));
+  v = fmaxf(v, dpp_move<0x141>(v));
+  v = fmaxf(v, dpp_move<0x140>(v));
+  v = fmaxf(v, __shfl_xor(v, 16));
+  v = fmaxf(v, __shfl_xor(v, 32));
+  return v;
+}
+__device__ __forceinline__ int wave_sum_i(int v) {
+  v += dpp_move_i<0xB1>(v);
+  v += dpp_move_i<0x4E>(v);
+  v += dpp_move_i<0x141>(v);
+  v += dpp_move_i<0x140>(v);
+  v += __shfl_xor(v, 16);
+  v += __shfl_xor(v, 32);
+  return v;
+}
+
+// Block-wide reductions through a small LDS array (one slot per wavefront); all threads get the
+// result.  The combination order is fixed (wavefront 0,1,2,...), so results are reproducible.
+// `buf` must hold blockDim.x/64 floats and must not be in use by a pending reduction.
+__device__ __forceinline__ float block_sum(float v, float* buf) {
+  v = wave_sum(v);
+  const int w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) buf[w] = v;
+  __syncthreads();
+  float t = 0.f;
+  for (int i = 0; i < nw; ++i) t += buf[i];
+  return t;
+}
+__device__ __forceinline__ float block_max(float v, float* buf) {
+  v = wave_max(v);
+  const int w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) buf[w] = v;
+  __syncthreads();
+  float t = buf[0];
+  for (int i = 1; i < nw; ++i) t = fmaxf(t, buf[i]);
+  return t;
+}
+__device__ __forceinline__ int block_sum_i(int v, int* buf) {
+  v = wave_sum_i(v);
+  const int w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) buf[w] = v;
+  __syncthreads();
+  int t = 0;
+  for (int i = 0; i < nw; ++i) t += buf[i];
+  return t;
+}
+
+// Order-preserving map float -> uint32 (larger float <=> larger key); -inf maps near 0.
+__device__ __forceinline__ uint32_t float_to_key(float f) {
+  const uint32_t u = __float_as_uint(f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// x^beta for x > 0 with the small integer exponents special-cased (exact products).
+__device__ __forceinline__ float pow_beta(float x, float beta, int ibeta) {
+  switch (ibeta) {
+    case 1: return x;
+    case 2: return x * x;
+    case 3: return x * x * x;
+    case 4: { const float y = x * x; return y * y; }
+    default: return __builtin_exp2f(beta * __builtin_log2f(x));
+  }
+}
+// x^(beta-1)
+__device__ __forceinline__ float pow_beta_m1(float x, float beta, int ibeta) {
+  switch (ibeta) {
+    case 1: return 1.f;
+    case 2: return x;
+    case 3: return x * x;
+    case 4: return x * x * x;
+    default: return __builtin_exp2f((beta - 1.f) * __builtin_log2f(x));
+  }
+}
+
+}  // namespace ekv

@@ -1,0 +1,48 @@
+// Host-side launcher declarations (internal to the library).  Arguments are validated in api.hip
+// before any launcher is called; launchers only enqueue kernels on the given stream.
+#pragma once
+#include <hip/hip_runtime.h>
+#include "../../include/entmaxkv.h"
+
+namespace ekv {
+
+struct Dims {
+  int B, Hq, Hkv, G, P, Mmax, cap;
+  int dtype;          // ekv_dtype
+  float alpha, scale;
+  float a;            // alpha - 1
+  float beta;         // 1 / a
+  int ibeta;          // beta if it is 1,2,3,4 (within 1e-6), else 0
+};
+
+// decode scratch layout (shared by api.hip and decode.hip)
+constexpr int kPagesPerScoreBlock = 8;   // pages handled by one workgroup of the score pass
+
+struct DecodeWorkspace {
+  float* z;        // [B*Hq][zstride] candidate scores z_j (or -inf where masked)
+  float* pmax;     // [B*Hq][n_chunks_max] per-chunk maxima of z
+  size_t zstride;  // floats per (b,h) row of z
+  int n_chunks_max;
+};
+
+void launch_stats_build(const Dims& dm, const ekv_cache_view& c, const ekv_stats_view& s, hipStream_t st);
+void launch_stats_append(const Dims& dm, const ekv_cache_view& c, const ekv_stats_view& s,
+                         const void* k_new, const void* v_new, hipStream_t st);
+void launch_score_pages(const Dims& dm, const void* q, const ekv_stats_view& s, const int32_t* seq_lens,
+                        int mode, float* box, float* mu, float* sigma, hipStream_t st);
+void launch_select_topk(const Dims& dm, const float* box, const int32_t* seq_lens, int k_pages,
+                        int32_t* page_idx, int32_t* n_sel, hipStream_t st);
+void launch_select_gauss(const Dims& dm, const float* mu, const float* sigma, const int32_t* seq_lens,
+                         const float* zq_table, float margin, float* tau_hat, int32_t* page_idx,
+                         int32_t* n_sel, int32_t* overflow, void* ws, hipStream_t st);
+void launch_decode(const Dims& dm, bool dense, const void* q, const ekv_cache_view& c,
+                   const int32_t* page_idx, const int32_t* n_sel, float* out, float* tau, int32_t* supp,
+                   const ekv_decode_extras& ex, const DecodeWorkspace& ws, hipStream_t st);
+void launch_decode_sparse_softmax(const Dims& dm, const void* q, const ekv_cache_view& c,
+                                  const int32_t* page_idx, const int32_t* n_sel, float* out,
+                                  float* lse_sel, void* ws, hipStream_t st);
+
+size_t select_gauss_ws_bytes(const Dims& dm);
+size_t softmax_ws_bytes(const Dims& dm);
+
+}  // namespace ekv

@@ -1,0 +1,132 @@
+// Page-statistics builder (paper Sec. 4.2): per page k_min, k_max, k_avg, k_std.
+// One 64-lane wavefront per (sequence, KV head, page); a page is a contiguous P x 128 block, read
+// with 16-byte loads (lane = 4 rows x 16 column groups).  HBM-bound stream over K.
+#include "ekv_device.h"
+#include "ekv_internal.h"
+
+namespace ekv {
+
+// Statistics of one page, computed by one wavefront.  `kpage` points at the page's [P][128] block;
+// tokens [0,cnt) are valid.  If ov_row != nullptr, token `ov_slot` takes its values from ov_row[128]
+// instead of the cache (the token being appended).  Sums are taken relative to the first token's
+// value so that m2 - avg^2 does not cancel for channels with a large common offset.
+template <typename T>
+__device__ __forceinline__ void page_stats_wave(const T* __restrict__ kpage, int cnt, int P,
+                                                const T* __restrict__ ov_row, int ov_slot,
+                                                T* __restrict__ box_out, T* __restrict__ gauss_out) {
+  const int lane = threadIdx.x & 63;
+  const int r = lane >> 4, c = lane & 15;
+  float k0[8];
+  load8<T>((ov_row != nullptr && ov_slot == 0 ? ov_row : kpage) + 8 * c, k0);
+  float mn[8], mx[8], s1[8], s2[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) { mn[i] = INFINITY; mx[i] = -INFINITY; s1[i] = 0.f; s2[i] = 0.f; }
+  for (int t0 = 0; t0 < P; t0 += kRowsPerWave) {
+    const int row = t0 + r;
+    if (row < cnt) {
+      float x[8];
+      load8<T>((ov_row != nullptr && row == ov_slot ? ov_row : kpage + (size_t)row * kD) + 8 * c, x);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        mn[i] = fminf(mn[i], x[i]);
+        mx[i] = fmaxf(mx[i], x[i]);
+        const float dx = x[i] - k0[i];
+        s1[i] += dx;
+        s2[i] = fmaf(dx, dx, s2[i]);
+      }
+    }
+  }
+  const float inv_n = 1.0f / (float)cnt;
+  float avg[8], sd[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    mn[i] = fminf(mn[i], __shfl_xor(mn[i], 16)); mn[i] = fminf(mn[i], __shfl_xor(mn[i], 32));
+    mx[i] = fmaxf(mx[i], __shfl_xor(mx[i], 16)); mx[i] = fmaxf(mx[i], __shfl_xor(mx[i], 32));
+    s1[i] += __shfl_xor(s1[i], 16); s1[i] += __shfl_xor(s1[i], 32);
+    s2[i] += __shfl_xor(s2[i], 16); s2[i] += __shfl_xor(s2[i], 32);
+    const float m1 = s1[i] * inv_n;
+    const float var = fmaxf(fmaf(-m1, m1, s2[i] * inv_n), 0.f);
+    avg[i] = k0[i] + m1;
+    sd[i] = sqrtf(var);
+  }
+  if (r == 0) {
+    store8<T>(box_out + 8 * c, mn);
+    store8<T>(box_out + kD + 8 * c, mx);
+    store8<T>(gauss_out + 8 * c, avg);
+    store8<T>(gauss_out + kD + 8 * c, sd);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void stats_build_kernel(const T* __restrict__ k_pool,
+                                                          const int32_t* __restrict__ block_table,
+                                                          const int32_t* __restrict__ seq_lens,
+                                                          T* __restrict__ box, T* __restrict__ gauss,
+                                                          int Hkv, int P, int Mmax) {
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int p = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int n = seq_lens[b];
+  const int M = (n + P - 1) / P;
+  if (p >= M) return;
+  const int cnt = min(P, n - p * P);
+  const int phys = block_table[(size_t)b * Mmax + p];
+  const T* kpage = k_pool + ((size_t)phys * Hkv + h) * P * kD;
+  const size_t rec = (((size_t)b * Hkv + h) * Mmax + p) * 2 * kD;
+  page_stats_wave<T>(kpage, cnt, P, nullptr, -1, box + rec, gauss + rec);
+}
+
+// One wavefront per (sequence, KV head): write the new token into slot n_b and refresh its page.
+template <typename T>
+__global__ __launch_bounds__(64) void stats_append_kernel(T* __restrict__ k_pool, T* __restrict__ v_pool,
+                                                          const int32_t* __restrict__ block_table,
+                                                          const int32_t* __restrict__ seq_lens,
+                                                          const T* __restrict__ k_new,
+                                                          const T* __restrict__ v_new,
+                                                          T* __restrict__ box, T* __restrict__ gauss,
+                                                          int Hkv, int P, int Mmax) {
+  const int b = blockIdx.y, h = blockIdx.x;
+  const int pos = seq_lens[b];
+  const int p = pos / P, slot = pos - p * P;
+  if (p >= Mmax) return;                       // no room: validated against on the host where possible
+  const int phys = block_table[(size_t)b * Mmax + p];
+  const size_t page_off = ((size_t)phys * Hkv + h) * P * kD;
+  const T* knew = k_new + ((size_t)b * Hkv + h) * kD;
+  const int lane = threadIdx.x;
+  if (lane < 16) {
+    float x[8];
+    load8<T>(knew + 8 * lane, x);
+    store8<T>(k_pool + page_off + (size_t)slot * kD + 8 * lane, x);
+  } else if (lane < 32 && v_new != nullptr) {
+    float x[8];
+    const int c = lane - 16;
+    load8<T>(v_new + ((size_t)b * Hkv + h) * kD + 8 * c, x);
+    store8<T>(v_pool + page_off + (size_t)slot * kD + 8 * c, x);
+  }
+  const size_t rec = (((size_t)b * Hkv + h) * Mmax + p) * 2 * kD;
+  page_stats_wave<T>(k_pool + page_off, slot + 1, P, knew, slot, box + rec, gauss + rec);
+}
+
+void launch_stats_build(const Dims& dm, const ekv_cache_view& c, const ekv_stats_view& s, hipStream_t st) {
+  dim3 grid((dm.Mmax + 3) / 4, dm.Hkv, dm.B), block(256);
+  if (dm.dtype == EKV_F32)
+    hipLaunchKernelGGL(stats_build_kernel<float>, grid, block, 0, st, (const float*)c.k_pool, c.block_table,
+                       c.seq_lens, (float*)s.box, (float*)s.gauss, dm.Hkv, dm.P, dm.Mmax);
+  else
+    hipLaunchKernelGGL(stats_build_kernel<bf16_t>, grid, block, 0, st, (const bf16_t*)c.k_pool, c.block_table,
+                       c.seq_lens, (bf16_t*)s.box, (bf16_t*)s.gauss, dm.Hkv, dm.P, dm.Mmax);
+}
+
+void launch_stats_append(const Dims& dm, const ekv_cache_view& c, const ekv_stats_view& s,
+                         const void* k_new, const void* v_new, hipStream_t st) {
+  dim3 grid(dm.Hkv, dm.B), block(64);
+  if (dm.dtype == EKV_F32)
+    hipLaunchKernelGGL(stats_append_kernel<float>, grid, block, 0, st, (float*)c.k_pool, (float*)c.v_pool,
+                       c.block_table, c.seq_lens, (const float*)k_new, (const float*)v_new, (float*)s.box,
+                       (float*)s.gauss, dm.Hkv, dm.P, dm.Mmax);
+  else
+    hipLaunchKernelGGL(stats_append_kernel<bf16_t>, grid, block, 0, st, (bf16_t*)c.k_pool, (bf16_t*)c.v_pool,
+                       c.block_table, c.seq_lens, (const bf16_t*)k_new, (const bf16_t*)v_new, (bf16_t*)s.box,
+                       (bf16_t*)s.gauss, dm.Hkv, dm.P, dm.Mmax);
+}
+
+}  // namespace ekv

@@ -1,0 +1,92 @@
+"""CPU-only checks of the C-ABI boundary: the library loads, exports every symbol the header declares,
+and rejects bad arguments on the host (no kernel is launched, no GPU is needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2605_21649_amd import binding as ekv
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_symbols():
+    text = open(os.path.join(ROOT, "include", "entmaxkv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ekv_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = ekv.load_library()
+    syms = header_symbols()
+    assert set(syms) == set(ekv.EXPORTS)
+    for s in syms:
+        assert hasattr(lib, s), s
+    assert lib.ekv_version() >= 100
+    assert lib.ekv_status_string(0) == b"EKV_OK"
+    assert lib.ekv_status_string(3) == b"EKV_ERR_WORKSPACE"
+
+
+def good_cfg(**kw):
+    base = dict(batch=1, n_q_heads=32, n_kv_heads=8, head_dim=128, page_size=16, kv_dtype="bf16", alpha=1.5,
+                scale=0.088, max_pages_per_seq=65536, max_sel_pages=2622)
+    base.update(kw)
+    return ekv.make_config(**base)
+
+
+def test_workspace_sizes():
+    cfg = good_cfg()
+    sparse = ekv.ekv_workspace_bytes(cfg, ekv.EKV_OP_DECODE_SPARSE)
+    full = ekv.ekv_workspace_bytes(cfg, ekv.EKV_OP_DECODE_FULL)
+    # scores: 4 B per candidate token and query head, plus one maximum per 8-page chunk
+    assert sparse >= 32 * 2622 * 16 * 4 and sparse < 1.1 * 32 * 2622 * 16 * 4
+    assert full >= 32 * 65536 * 16 * 4 and full < 1.1 * 32 * 65536 * 16 * 4
+    assert ekv.ekv_workspace_bytes(cfg, ekv.EKV_OP_SELECT_GAUSS) > 0
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(head_dim=64), 2), (dict(page_size=10), 2), (dict(n_q_heads=24, n_kv_heads=8), 2),
+    (dict(n_q_heads=30), 1), (dict(alpha=1.0), 1), (dict(scale=0.0), 1), (dict(batch=0), 1),
+    (dict(kv_dtype=7), 2), (dict(max_sel_pages=70000), 1),
+])
+def test_bad_config_is_rejected(kw, code):
+    lib = ekv.load_library()
+    cfg = good_cfg(**kw)
+    n = ctypes.c_size_t(0)
+    assert lib.ekv_workspace_bytes(ctypes.byref(cfg), ekv.EKV_OP_DECODE_FULL, ctypes.byref(n)) == code
+
+
+def test_null_and_misaligned_pointers_are_rejected_before_any_launch():
+    lib = ekv.load_library()
+    cfg = good_cfg()
+    cache = ekv.ekv_cache_view(None, None, None, None, 0)
+    stats = ekv.ekv_stats_view(None, None)
+    assert lib.ekv_stats_build(ctypes.byref(cfg), ctypes.byref(cache), ctypes.byref(stats), None) == 1
+    assert lib.ekv_stats_build(None, ctypes.byref(cache), ctypes.byref(stats), None) == 1
+    cache = ekv.ekv_cache_view(0x1008, 0x2000, 0x3000, 0x4000, 4)      # k_pool not 16-byte aligned
+    stats = ekv.ekv_stats_view(0x5000, 0x6000)
+    assert lib.ekv_stats_build(ctypes.byref(cfg), ctypes.byref(cache), ctypes.byref(stats), None) == 1
+    assert lib.ekv_score_pages(ctypes.byref(cfg), 0x1000, ctypes.byref(stats), 0x4000, 0, 0x7000, None, None,
+                               None) == 1                               # mode 0
+    assert lib.ekv_select_topk(ctypes.byref(cfg), 0x1000, 0x2000, 0, 0x3000, 0x4000, None, 0, None) == 1
+    assert lib.ekv_select_topk(ctypes.byref(cfg), 0x1000, 0x2000, 5000, 0x3000, 0x4000, None, 0, None) == 1
+    # workspace too small / missing
+    cache = ekv.ekv_cache_view(0x1000, 0x2000, 0x3000, 0x4000, 4)
+    assert lib.ekv_decode_full(ctypes.byref(cfg), 0x1000, ctypes.byref(cache), 0x5000, 0x6000, 0x7000, None,
+                               None, 0, None) == 3
+    assert lib.ekv_decode_sparse(ctypes.byref(cfg), 0x1000, ctypes.byref(cache), 0x8000, 0x9000, 0x5000, 0x6000,
+                                 0x7000, None, 0xA000, 1024, None) == 3
+    # Gaussian selector: q_page outside (0,1); non-integer beta
+    assert lib.ekv_select_gauss(ctypes.byref(cfg), 0x1000, 0x2000, 0x3000, 1.5, 0.0, 0x4000, 0x5000, 0x6000, 0x7000,
+                                0x8000, 4096, None) == 1
+    cfg17 = good_cfg(alpha=1.7)
+    assert lib.ekv_select_gauss(ctypes.byref(cfg17), 0x1000, 0x2000, 0x3000, 0.9, 0.0, 0x4000, 0x5000, 0x6000,
+                                0x7000, 0x8000, 4096, None) == 2
+
+
+def test_binding_raises_without_fallback(monkeypatch):
+    monkeypatch.setattr(ekv, "_lib", None)
+    monkeypatch.setattr(ekv, "LIB_PATH", "/nonexistent/libentmaxkv.so")
+    with pytest.raises(ekv.EkvError):
+        ekv.load_library()
