@@ -1,0 +1,286 @@
+#!/usr/bin/env python3
+"""Decode-step benchmark of the EntmaxKV hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C4] [--budget 0.02]
+
+One step = one decode step of the top-k variant over a synthetic paged cache already resident in HBM:
+  a2 append the new token + refresh its page statistics -> a3 box page scoring -> a5 top-k selection
+  -> a7 sparse alpha-entmax decode (exact tau).
+The same run also times, outside the headline number, the Gaussian-selector step (a4 + a6 + a7), the dense
+full-cache entmax decode (a8), the softmax-over-selection baseline (a9) and the bulk statistics build (a1).
+To keep reads coming from HBM rather than the 256 MB last-level cache, the step rotates over several
+identical copies of the cache and its statistics.
+
+Prints ONE JSON line (see the design doc for the fields): metric/value = median-free mean latency of the K timed
+steps in microseconds; `roofline` for the dominant kernel of the step; `cpu_baseline` = the float64 oracle
+timed on this machine's host cores on a bounded sample of (batch, head) units.
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="C4")
+    ap.add_argument("--budget", type=float, default=0.02, help="top-k budget as a fraction of the pages")
+    ap.add_argument("--copies", type=int, default=4, help="rotating copies of the cache (defeats the LLC)")
+    ap.add_argument("--q-page", type=float, default=0.99)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="time only the headline step")
+    ap.add_argument("--cpu-units", type=int, default=2, help="(b,h) units the oracle is timed on")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(how the path would shard is described in DESIGN.md).", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2605_21649_amd import binding as ekv, synth
+    from tests.helpers import DeviceState
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    ekv.load_library()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    w = synth.WORKLOADS[args.workload]
+    B, Hq, Hkv, d, P, n = w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.page_size, w.context
+    M = w.pages_per_seq
+    e = 2 if w.kv_dtype == "bf16" else 4
+    k_pages = max(1, int(math.ceil(args.budget * M)))
+    cap = max(k_pages, int(math.ceil(0.04 * M)))
+
+    # ---------------------------------------------------------------- inputs (seeded, generated on the GPU)
+    inp = synth.make_inputs(w, 4000, device=dev)
+    copies = []
+    for c in range(args.copies):
+        ic = inp if c == 0 else {k: (v.clone() if k in ("k_pool", "v_pool") else v) for k, v in inp.items()}
+        st = DeviceState(w, ic, cap=cap, device=dev)
+        ekv.ekv_stats_build(st.cfg, st.cache(), st.stats())
+        st.ws_sparse = st.workspace(ekv.EKV_OP_DECODE_SPARSE)
+        st.ws_gauss = st.workspace(ekv.EKV_OP_SELECT_GAUSS)
+        # the token appended by the step: the last token of the sequence, re-appended at n-1 every step
+        st.seq_prev = (ic["seq_lens"] - 1).contiguous()
+        st.cache_prev = ekv.cache_view(ic["k_pool"], ic["v_pool"], ic["block_table"], st.seq_prev)
+        rows = ic["block_table"][:, (n - 1) // P].long()
+        st.k_new = ic["k_pool"][rows, :, (n - 1) % P].contiguous()
+        st.v_new = ic["v_pool"][rows, :, (n - 1) % P].contiguous()
+        copies.append(st)
+    torch.cuda.synchronize()
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    stage_names = ["append", "score_box", "select_topk", "decode_sparse"]
+
+    def step_topk(st, evs=None):
+        if evs: evs[0].record()
+        ekv.ekv_stats_append(st.cfg, st.cache_prev, st.stats(), st.k_new, st.v_new)
+        if evs: evs[1].record()
+        ekv.ekv_score_pages(st.cfg, st.inp["q"], st.stats(), st.inp["seq_lens"], ekv.EKV_SCORE_BOX, st.box)
+        if evs: evs[2].record()
+        ekv.ekv_select_topk(st.cfg, st.box, st.inp["seq_lens"], k_pages, st.page_idx, st.n_sel)
+        if evs: evs[3].record()
+        ekv.ekv_decode_sparse(st.cfg, st.inp["q"], st.cache(), st.page_idx, st.n_sel, st.out, st.tau, st.supp,
+                              st.ws_sparse)
+        if evs: evs[4].record()
+
+    def step_gauss(st, evs=None):
+        if evs: evs[0].record()
+        ekv.ekv_stats_append(st.cfg, st.cache_prev, st.stats(), st.k_new, st.v_new)
+        if evs: evs[1].record()
+        ekv.ekv_score_pages(st.cfg, st.inp["q"], st.stats(), st.inp["seq_lens"], ekv.EKV_SCORE_GAUSS, None, st.mu,
+                            st.sigma)
+        if evs: evs[2].record()
+        ekv.ekv_select_gauss(st.cfg, st.mu, st.sigma, st.inp["seq_lens"], args.q_page, 0.0, st.tau_hat, st.page_idx,
+                             st.n_sel, st.overflow, st.ws_gauss)
+        if evs: evs[3].record()
+        ekv.ekv_decode_sparse(st.cfg, st.inp["q"], st.cache(), st.page_idx, st.n_sel, st.out, st.tau, st.supp,
+                              st.ws_sparse)
+        if evs: evs[4].record()
+
+    def run_timed(step_fn, steps, warmup):
+        """W untimed steps, then exactly K steps between two synchronisations (wall clock); every
+        timed step also records HIP events between its stages on the launch stream."""
+        for i in range(warmup):
+            step_fn(copies[i % len(copies)])
+        torch.cuda.synchronize()
+        all_evs = [[ev() for _ in range(5)] for _ in range(steps)]
+        t0 = time.perf_counter()
+        for i in range(steps):
+            step_fn(copies[i % len(copies)], all_evs[i])
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        stage = np.array([[es[j].elapsed_time(es[j + 1]) * 1e3 for j in range(4)] for es in all_evs])   # us
+        whole = np.array([es[0].elapsed_time(es[4]) * 1e3 for es in all_evs])
+        return wall / steps * 1e6, stage, whole
+
+    # ---------------------------------------------------------------- headline: top-k step
+    us_wall, stage, whole = run_timed(step_topk, args.steps, args.warmup)
+    stage_mean = stage.mean(axis=0)
+    st0 = copies[0]
+    supp_mean = float(st0.supp.float().mean())
+    n_sel_mean = float(st0.n_sel.float().mean())
+
+    # algorithmic bytes of the step: box metadata + selected K pages +
+    # support V rows + score scratch (written then read once)
+    sel_tokens = n_sel_mean * P
+    bytes_meta = B * Hkv * M * 2 * d * e
+    bytes_scores = B * Hq * M * 4 * 2
+    bytes_k = B * Hq * sel_tokens * d * e
+    bytes_v = B * Hq * supp_mean * d * e
+    bytes_z = B * Hq * sel_tokens * 4 * 2
+    step_bytes = bytes_meta + bytes_scores + bytes_k + bytes_v + bytes_z
+    dense_bytes = B * Hkv * n * 2 * d * e
+
+    # dominant kernel of the step.  score_pages and select_topk are single-kernel stages, so the stage's
+    # event interval is the kernel's launch duration (plus the launch gap, which makes it conservative).
+    dom = int(np.argmax(stage_mean))
+    kernel_alg_bytes = {
+        "append": None,
+        "score_box": bytes_meta + B * Hq * M * 4,                       # metadata read + scores written
+        "select_topk": B * Hq * M * 4,                                   # scores read (once, algorithmically)
+        "decode_sparse": bytes_k + bytes_v + bytes_z,
+    }
+    dom_name = stage_names[dom]
+    # the HBM-bound kernel the roofline is reported for: the page-scoring stream unless the sparse
+    # gather takes longer
+    roof_stage = "score_box" if stage_mean[1] >= stage_mean[3] else "decode_sparse"
+    roof_idx = stage_names.index(roof_stage)
+    roof_bytes = kernel_alg_bytes[roof_stage]
+    roof_us = float(stage_mean[roof_idx])
+    achieved = roof_bytes / (roof_us * 1e-6) / 1e9
+    roofline = {
+        "bound": "hbm", "kernel": {"score_box": "score_pages_kernel<bf16,G,box>",
+                                   "decode_sparse": "decode_scores_kernel+decode_solve_kernel"}[roof_stage],
+        "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+        "traffic": None, "algorithmic_bytes_per_launch": int(roof_bytes), "avg_launch_us": round(roof_us, 2),
+    }
+
+    result = {
+        "metric": "decode-step latency", "value": round(us_wall, 2), "unit": "us", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(us_wall / 1e3, 5),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic", "kv_dtype": w.kv_dtype,
+        "config": {"workload": f"{w.name}: B{B} {Hq}q/{Hkv}kv d{d} ctx{n} page{P} {w.kv_dtype}, alpha={w.alpha}, "
+                               f"top-k {k_pages} pages ({args.budget:.0%}) per query head",
+                   "variant": "entmaxkv-topk", "copies_rotated": args.copies},
+        "step_event_us": {"mean": round(float(whole.mean()), 2), "median": round(float(np.median(whole)), 2),
+                          "p10": round(float(np.percentile(whole, 10)), 2),
+                          "p90": round(float(np.percentile(whole, 90)), 2)},
+        "stage_us": {nm: round(float(v), 2) for nm, v in zip(stage_names, stage_mean)},
+        "dominant_stage": dom_name,
+        "step_algorithmic_bytes": int(step_bytes),
+        "effective_kv_GBps": round(step_bytes / (us_wall * 1e-6) / 1e9, 1),
+        "effective_kv_frac_of_hbm_peak": round(step_bytes / (us_wall * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+        "dense_equivalent_GBps": round(dense_bytes / (us_wall * 1e-6) / 1e9, 1),
+        "selected_pages_mean": n_sel_mean, "support_mean": supp_mean,
+        "roofline": roofline,
+    }
+
+    # ---------------------------------------------------------------- the other rows, same run
+    if not args.no_extras:
+        def time_call(fn, reps=20, warm=3):
+            for i in range(warm):
+                fn(copies[i % len(copies)])
+            torch.cuda.synchronize()
+            ts = []
+            for i in range(reps):
+                a, b = ev(), ev()
+                a.record(); fn(copies[i % len(copies)]); b.record()
+                torch.cuda.synchronize()
+                ts.append(a.elapsed_time(b) * 1e3)
+            return float(np.median(ts))
+
+        extras = {}
+        us_g, stage_g, whole_g = run_timed(step_gauss, max(10, args.steps // 4), 5)
+        extras["gauss_step_us"] = round(us_g, 2)
+        extras["gauss_stage_us"] = {nm: round(float(v), 2) for nm, v in
+                                    zip(["append", "score_gauss", "select_gauss", "decode_sparse"], stage_g.mean(axis=0))}
+        extras["gauss_selected_pages_mean"] = float(copies[0].n_sel.float().mean())
+        extras["gauss_overflow"] = int(copies[0].overflow.sum())
+        for st in copies:
+            st.ws_full = None
+        ws_full = copies[0].workspace(ekv.EKV_OP_DECODE_FULL)       # one scratch shared by the copies
+        out_f, tau_f, supp_f = torch.zeros_like(st0.out), torch.zeros_like(st0.tau), torch.zeros_like(st0.supp)
+        dense_us = time_call(lambda st: ekv.ekv_decode_full(st.cfg, st.inp["q"], st.cache(), out_f, tau_f, supp_f,
+                                                            ws_full), reps=10)
+        extras["dense_full_us"] = round(dense_us, 2)
+        extras["dense_full_GBps"] = round((dense_bytes / 2 + B * Hq * n * 8) / (dense_us * 1e-6) / 1e9, 1)
+        extras["speedup_vs_dense"] = round(dense_us / us_wall, 2)
+        extras["speedup_gauss_vs_dense"] = round(dense_us / us_g, 2)
+        # dropped mass / support recall of the top-k selection against the dense threshold (GPU side outputs)
+        kept_mass = torch.zeros_like(st0.tau); kept_supp = torch.zeros_like(st0.supp)
+        for frac in (0.01, 0.02, 0.04):
+            kp = max(1, int(math.ceil(frac * M)))
+            ekv.ekv_select_topk(st0.cfg, st0.box, st0.inp["seq_lens"], kp, st0.page_idx, st0.n_sel)
+            ekv.ekv_decode_sparse(st0.cfg, st0.inp["q"], st0.cache(), st0.page_idx, st0.n_sel, st0.out, st0.tau,
+                                  st0.supp, st0.ws_sparse,
+                                  extras=ekv.decode_extras(tau_ref=tau_f, kept_mass_ref=kept_mass, kept_supp_ref=kept_supp))
+            torch.cuda.synchronize()
+            R = ((st0.out - out_f).norm(dim=-1) / out_f.norm(dim=-1)).mean()
+            extras[f"topk_{frac:.0%}"] = {
+                "delta_mean": round(float((1 - kept_mass).mean()), 6),
+                "rho_mean": round(float((kept_supp.float() / supp_f.float()).mean()), 4),
+                "R_mean": round(float(R), 6),
+                "step_us": None}
+        lse_sel = torch.zeros_like(st0.tau)
+        ws_sm = copies[0].workspace(ekv.EKV_OP_DECODE_SPARSE_SOFTMAX)
+        ekv.ekv_select_topk(st0.cfg, st0.box, st0.inp["seq_lens"], k_pages, st0.page_idx, st0.n_sel)
+        extras["softmax_sparse_us"] = round(time_call(
+            lambda st: ekv.ekv_decode_sparse_softmax(st0.cfg, st0.inp["q"], st.cache(), st0.page_idx, st0.n_sel,
+                                                     st0.out, lse_sel, ws_sm), reps=10), 2)
+        extras["stats_build_us"] = round(time_call(lambda st: ekv.ekv_stats_build(st.cfg, st.cache(), st.stats()),
+                                                   reps=8), 2)
+        extras["stats_build_GBps"] = round((dense_bytes / 2 + 2 * bytes_meta) / (extras["stats_build_us"] * 1e-6) / 1e9, 1)
+        result["other_rows"] = extras
+
+    # ---------------------------------------------------------------- CPU baseline: the oracle, as it stands
+    if not args.no_cpu_baseline:
+        from oracle import entmaxkv_oracle as orc
+        from tests.helpers import to_f64
+        from threadpoolctl import threadpool_limits
+        threadpool_limits(1)                                   # one thread, so that `cores` is exact
+        units = [(0, 0), (B - 1, Hq - 1)][: args.cpu_units]
+        t_cpu = 0.0
+        for (b, hq) in units:
+            hkv = hq // w.group
+            k_t, v_t = synth.logical_kv(inp, w, b, hkv)
+            q64, K64, V64 = to_f64(inp["q"][b, hq]), to_f64(k_t), to_f64(v_t)
+            t0 = time.perf_counter()
+            orc.decode_step_unit(q64, K64, V64, P, w.alpha, w.score_scale, "topk", w.kv_dtype, k_pages=k_pages)
+            t_cpu += time.perf_counter() - t0
+            del K64, V64
+        per_unit = t_cpu / len(units)
+        try:
+            cores = len(os.sched_getaffinity(0))
+        except AttributeError:
+            cores = os.cpu_count()
+        result["cpu_baseline"] = {
+            "value": round(per_unit * B * Hq * 1e6, 1), "unit": "us", "cores": 1, "host_cores_available": cores,
+            "kind": "oracle",
+            "sample": f"float64 numpy oracle, whole top-k step (stats+score+select+sparse entmax) of {len(units)} of "
+                      f"{B * Hq} (b,head) units, single thread, {t_cpu:.1f} s measured; value = per-unit time x {B * Hq} units",
+        }
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

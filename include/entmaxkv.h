@@ -83,16 +83,18 @@ typedef struct {
 
 /* Page statistics (paper Sec. 4.2), stored per SEQUENCE in logical page order so that scoring is a
  * pure stream:  box  [B][Hkv][Mmax][2][d]  = (k_min, k_max)   element-wise over the page's tokens,
- *               gauss[B][Hkv][Mmax][2][d]  = (k_avg, k_std)   population mean and standard deviation,
- * both in kv_dtype.  Rows of pages p >= M_b are not defined.  Either pointer may be NULL in calls
- * that do not need it (scoring with a mode that does not read it). */
+ *               gauss[B][Hkv][Mmax][2][d]  = (k_avg, k_var)   population mean and variance k_std^2,
+ * both in kv_dtype.  (The variance rather than k_std is stored because sigma_p^2 of Sec. 4.3 is linear
+ * in it, which lets the scoring kernel run as one bf16 matrix contraction; k_std = sqrt(k_var).)
+ * Rows of pages p >= M_b are not defined.  Either pointer may be NULL in calls that do not need it
+ * (scoring with a mode that does not read it). */
 typedef struct {
   void* box;
   void* gauss;
 } ekv_stats_view;
 
 /* a1 -- bulk statistics build (Sec. 4.2).  For every sequence b, KV head and logical page p < M_b,
- * computes k_min, k_max, k_avg and k_std = sqrt(max(m2 - k_avg^2, 0)) over the page's cnt tokens
+ * computes k_min, k_max, k_avg and k_var = max(m2 - k_avg^2, 0) (= k_std^2) over the page's cnt tokens
  * (cnt = P, or n_b - pP for the last page) and writes both stats arrays (both must be non-NULL). */
 ekv_status ekv_stats_build(const ekv_config* cfg, const ekv_cache_view* cache,
                            const ekv_stats_view* stats, void* stream);
@@ -111,7 +113,7 @@ ekv_status ekv_stats_append(const ekv_config* cfg, const ekv_cache_view* cache,
  * q [B][Hq][d] device, kv_dtype.  Outputs, each f32 [B][Hq][Mmax] (device) or NULL if not requested:
  *   box[b,h,p]   = scale * sum_i max(q_i kmin_i, q_i kmax_i)          (mode & EKV_SCORE_BOX)
  *   mu[b,h,p]    = scale * q . k_avg                                   (mode & EKV_SCORE_GAUSS)
- *   sigma[b,h,p] = scale * sqrt(sum_i q_i^2 k_std,i^2)                 (mode & EKV_SCORE_GAUSS)
+ *   sigma[b,h,p] = scale * sqrt(sum_i q_i^2 k_var,i)                   (mode & EKV_SCORE_GAUSS)
  * Entries p >= M_b are written as -inf (box, mu) and 0 (sigma). */
 ekv_status ekv_score_pages(const ekv_config* cfg, const void* q, const ekv_stats_view* stats,
                            const int32_t* seq_lens, int32_t mode, float* box, float* mu,

@@ -45,6 +45,15 @@ def round_to_bf16(x):
     return np.ldexp(np.rint(m * 256.0), e - 8)   # np.rint rounds half to even
 
 
+def stored_gauss_stats(kavg, kstd, kv_dtype):
+    """(k_avg, k_std) as recovered from the statistics a cache-dtype store keeps.
+
+    Storage reading (the paper does not fix a precision): the mean and the VARIANCE k_std^2 are kept,
+    each rounded to the cache dtype; k_std is the square root of the stored variance."""
+    kvar = round_to_storage(np.asarray(kstd, dtype=np.float64) ** 2, kv_dtype)
+    return round_to_storage(kavg, kv_dtype), np.sqrt(kvar)
+
+
 def round_to_storage(x, kv_dtype):
     """Value held by a statistic stored in the cache dtype ('f32' or 'bf16')."""
     if kv_dtype == "f32":
@@ -352,7 +361,7 @@ def decode_step_unit(q, K, V, P, alpha, scale, selector, kv_dtype="f32",
     q [d], K,V [n,d] (already the exact stored cache values, widened to float64).
     selector: 'topk' (box bound, k_pages) or 'gauss' (tau-hat, adaptive).  The page
     statistics used for scoring are the values a cache-dtype copy would hold
-    (min/max are cache values already; avg/std are rounded to kv_dtype)."""
+    (min/max are cache values already; mean and variance are rounded to kv_dtype)."""
     n = K.shape[0]
     kmin, kmax, kavg, kstd, cnt = page_stats(K, P)
     out = {}
@@ -361,8 +370,8 @@ def decode_step_unit(q, K, V, P, alpha, scale, selector, kv_dtype="f32",
         pages, cut_in, cut_out = topk_pages(box, k_pages)
         out.update(box=box, cut_in=cut_in, cut_out=cut_out)
     elif selector == "gauss":
-        mu, sigma = gauss_moments(q, round_to_storage(kavg, kv_dtype),
-                                  round_to_storage(kstd, kv_dtype), scale)
+        kavg_s, kstd_s = stored_gauss_stats(kavg, kstd, kv_dtype)
+        mu, sigma = gauss_moments(q, kavg_s, kstd_s, scale)
         pages, tau_hat, overflow, g = gauss_select(mu, sigma, cnt, alpha, q_page, margin, cap=cap)
         out.update(mu=mu, sigma=sigma, tau_hat=tau_hat, overflow=overflow, g=g)
     else:

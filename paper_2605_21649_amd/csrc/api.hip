@@ -45,6 +45,12 @@ static ekv_status check_cache(const ekv_cache_view* c, bool need_v) {
   return EKV_OK;
 }
 
+// V rows are addressed by a 32-bit row index (phys*Hkv + hkv)*P + tok inside the decode kernels.
+static ekv_status check_pool_rows(const ekv_cache_view* c, const Dims& dm) {
+  if ((int64_t)c->n_phys_pages * dm.Hkv * dm.P > (int64_t)0x7fffffff) return EKV_ERR_UNSUPPORTED;
+  return EKV_OK;
+}
+
 static ekv_status finish(hipStream_t) {
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) { g_last_hip_error = (int32_t)e; return EKV_ERR_HIP; }
@@ -190,6 +196,7 @@ static ekv_status decode_common(const ekv_config* cfg, bool dense, const void* q
   ekv_status s = make_dims(cfg, dm);
   if (s != EKV_OK) return s;
   if ((s = check_cache(cache, true)) != EKV_OK) return s;
+  if ((s = check_pool_rows(cache, dm)) != EKV_OK) return s;
   if (!ok_ptr(q) || !ok_ptr4(out) || !ok_ptr4(tau) || !ok_ptr4(supp)) return EKV_ERR_INVALID_ARG;
   if (!dense && (!ok_ptr4(page_idx) || !ok_ptr4(n_sel))) return EKV_ERR_INVALID_ARG;
   ekv_decode_extras ex;

@@ -2,10 +2,13 @@
 //
 // Entmax has no online rescaling: the threshold tau needs every candidate score.  The work is split:
 //   pass 1 (many workgroups, HBM-bound): gather the K pages, z_j = a*scale*q.k_j, write z (4 B/token)
-//           and one maximum per chunk of pages to scratch.
+//           and one maximum per chunk of 8 pages to scratch.  bf16 pages go through the matrix cores:
+//           an MFMA tile's 16 rows are 4 tokens x 4 channel quarters, so each lane's A operand is the
+//           16 bytes of a fully coalesced load, its 16 columns are (query head, channel quarter); the
+//           blocks with matching quarters are summed with two DPP quad steps.
 //   pass 2 (one workgroup per (b,h)): zmax from the chunk maxima; only z > zmax-1 can be in the
 //           support (at tau = zmax-1 the largest entry alone has mass 1), and chunks whose maximum is
-//           below that are skipped; the survivors are compacted IN ORDER into LDS; tau is solved
+//           below that are not read; the survivors are compacted IN ORDER into LDS; tau is solved
 //           there; p_j = (z_j - tau)^beta; V rows are gathered only where p_j > 0.
 // All reductions have a fixed order, so results are bit-reproducible.
 #include "ekv_device.h"
@@ -16,71 +19,63 @@ namespace ekv {
 constexpr int kScoreThreads = 256;
 constexpr int kSolveThreads = 1024;
 constexpr int kSolveWaves = kSolveThreads / 64;
-constexpr int kListCap = 6144;          // candidate entries held in LDS (u, pos): 48 KB
+constexpr int kListCap = 4096;          // candidate entries held in LDS (u, pos, row): 48 KB
+constexpr int kRoundLoads = 16;         // loads per lane and compaction round
+constexpr int kRoundTokens = kSolveThreads * kRoundLoads;
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
 // ------------------------------------------------------------------------------------------
 // pass 1: scores
 // ------------------------------------------------------------------------------------------
 // DENSE: unit = (b, KV head); the G query heads of the group are scored from one read of K.
 // sparse: unit = (b, query head) with its own page list (G = 1).
-template <typename T, int G, bool DENSE, int PT>   // PT = compile-time page size, 0 = runtime
-__global__ __launch_bounds__(kScoreThreads) void decode_scores_kernel(
-    const T* __restrict__ q, const T* __restrict__ k_pool, const int32_t* __restrict__ block_table,
-    const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ page_idx,
-    const int32_t* __restrict__ n_sel, float* __restrict__ zbuf, float* __restrict__ pmax, int Hq, int Hkv,
-    int P_rt, int Mmax, int cap, size_t zstride, int n_chunks_max, float zscale) {
+struct ScoreArgs {
+  const void* q; const void* k_pool;
+  const int32_t* block_table; const int32_t* seq_lens; const int32_t* page_idx; const int32_t* n_sel;
+  float* zbuf; float* pmax;
+  int Hq, Hkv, P, Mmax, cap, n_chunks_max;
+  size_t zstride;
+  float zscale;
+};
+
+// Generic path (float32 caches, or page sizes that are not a multiple of 16): FMAs + DPP row sums.
+template <typename T, int G, bool DENSE>
+__global__ __launch_bounds__(kScoreThreads) void decode_scores_valu_kernel(const ScoreArgs A) {
   __shared__ float wmax_s[kScoreThreads / 64][G];
-  const int P = PT ? PT : P_rt;
+  const T* q = (const T*)A.q;
+  const T* k_pool = (const T*)A.k_pool;
+  const int P = A.P, Hq = A.Hq, Hkv = A.Hkv;
   const int unit = blockIdx.y, chunk = blockIdx.x;
   const int b = DENSE ? unit / Hkv : unit / Hq;
   const int hkv = DENSE ? unit % Hkv : (unit % Hq) / (Hq / Hkv);
   const int hq0 = DENSE ? hkv * G : unit % Hq;            // first (only) query head of this unit
-  const int n = seq_lens[b];
-  const int n_slots = DENSE ? (n + P - 1) / P : n_sel[unit];
+  const int n = A.seq_lens[b];
+  const int n_slots = DENSE ? (n + P - 1) / P : A.n_sel[unit];
   const int slot0 = chunk * kPagesPerScoreBlock;
   if (slot0 >= n_slots) return;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int r = lane >> 4, c = lane & 15;
-
   float coef[G][8];
 #pragma unroll
   for (int g = 0; g < G; ++g) load8<T>(q + ((size_t)b * Hq + hq0 + g) * kD + 8 * c, coef[g]);
-
   float wmax[G];
 #pragma unroll
   for (int g = 0; g < G; ++g) wmax[g] = -INFINITY;
-
   constexpr int kPagesPerWave = kPagesPerScoreBlock / (kScoreThreads / 64);
-#pragma unroll
   for (int pw = 0; pw < kPagesPerWave; ++pw) {
     const int slot = slot0 + w * kPagesPerWave + pw;
     if (slot >= n_slots) break;
-    const int lp = DENSE ? slot : page_idx[(size_t)unit * cap + slot];
-    const int phys = block_table[(size_t)b * Mmax + lp];
+    const int lp = DENSE ? slot : A.page_idx[(size_t)unit * A.cap + slot];
+    const int phys = A.block_table[(size_t)b * A.Mmax + lp];
     const T* kpage = k_pool + ((size_t)phys * Hkv + hkv) * P * kD + 8 * c;
-    float zkeep[G];
+    for (int s0 = 0; s0 < P / 4; s0 += 16) {          // 16 steps (64 tokens) per sweep of the c lanes
+      float zkeep[G];
 #pragma unroll
-    for (int g = 0; g < G; ++g) zkeep[g] = -INFINITY;
-    if constexpr (PT != 0) {
-      float x[PT ? PT / 4 : 1][8];
-#pragma unroll
-      for (int s = 0; s < PT / 4; ++s) load8<T>(kpage + (size_t)(4 * s + r) * kD, x[s]);
-#pragma unroll
-      for (int s = 0; s < PT / 4; ++s) {
-        const bool valid = lp * P + 4 * s + r < n;
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-          float acc = 0.f;
-#pragma unroll
-          for (int i = 0; i < 8; ++i) acc = fmaf(coef[g][i], x[s][i], acc);
-          acc = row16_sum(acc);
-          const float z = valid ? zscale * acc : -INFINITY;
-          if (c == s) zkeep[g] = z;
-          wmax[g] = fmaxf(wmax[g], z);
-        }
-      }
-    } else {
-      for (int s = 0; s < P / 4; ++s) {
+      for (int g = 0; g < G; ++g) zkeep[g] = -INFINITY;
+      const int s1 = min(P / 4, s0 + 16);
+      for (int s = s0; s < s1; ++s) {
         float x[8];
         load8<T>(kpage + (size_t)(4 * s + r) * kD, x);
         const bool valid = lp * P + 4 * s + r < n;
@@ -90,17 +85,17 @@ __global__ __launch_bounds__(kScoreThreads) void decode_scores_kernel(
 #pragma unroll
           for (int i = 0; i < 8; ++i) acc = fmaf(coef[g][i], x[i], acc);
           acc = row16_sum(acc);
-          const float z = valid ? zscale * acc : -INFINITY;
-          if (c == s) zkeep[g] = z;
+          const float z = valid ? A.zscale * acc : -INFINITY;
+          if (c == s - s0) zkeep[g] = z;
           wmax[g] = fmaxf(wmax[g], z);
         }
       }
-    }
-    if (c < P / 4) {
+      if (c < s1 - s0) {
 #pragma unroll
-      for (int g = 0; g < G; ++g) {
-        const size_t row = DENSE ? (size_t)b * Hq + hq0 + g : (size_t)unit;
-        zbuf[row * zstride + (size_t)slot * P + 4 * c + r] = zkeep[g];
+        for (int g = 0; g < G; ++g) {
+          const size_t row = DENSE ? (size_t)b * Hq + hq0 + g : (size_t)unit;
+          A.zbuf[row * A.zstride + (size_t)slot * P + 4 * (s0 + c) + r] = zkeep[g];
+        }
       }
     }
   }
@@ -117,7 +112,97 @@ __global__ __launch_bounds__(kScoreThreads) void decode_scores_kernel(
     float m = wmax_s[0][g];
     for (int i = 1; i < kScoreThreads / 64; ++i) m = fmaxf(m, wmax_s[i][g]);
     const size_t row = DENSE ? (size_t)b * Hq + hq0 + g : (size_t)unit;
-    pmax[row * n_chunks_max + chunk] = m;
+    A.pmax[row * A.n_chunks_max + chunk] = m;
+  }
+}
+
+// bf16 pages with P in {16, 32, 64}: matrix-core path.
+template <int G, bool DENSE, int PT>
+__global__ __launch_bounds__(kScoreThreads) void decode_scores_mfma_kernel(const ScoreArgs A) {
+  constexpr int NSET = (G + 3) / 4;
+  constexpr int STEPS = PT / 4;                   // 16-byte loads per lane and page
+  constexpr int KEEP = PT / 16;                   // z values a lane keeps per page and column set
+  __shared__ float wmax_s[kScoreThreads / 64][NSET * 4];
+  const bf16_t* q = (const bf16_t*)A.q;
+  const bf16_t* k_pool = (const bf16_t*)A.k_pool;
+  const int Hq = A.Hq, Hkv = A.Hkv;
+  const int unit = blockIdx.y, chunk = blockIdx.x;
+  const int b = DENSE ? unit / Hkv : unit / Hq;
+  const int hkv = DENSE ? unit % Hkv : (unit % Hq) / (Hq / Hkv);
+  const int hq0 = DENSE ? hkv * G : unit % Hq;
+  const int n = A.seq_lens[b];
+  const int n_slots = DENSE ? (n + PT - 1) / PT : A.n_sel[unit];
+  const int slot0 = chunk * kPagesPerScoreBlock;
+  if (slot0 >= n_slots) return;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int m = lane & 15, j = lane >> 4;          // MFMA row/column index, K group
+  const int kq = m & 3, gl = m >> 2;               // channel quarter; as a row: token of the step,
+                                                   // as a column: head within the set
+  uint4 bq[NSET];
+#pragma unroll
+  for (int s = 0; s < NSET; ++s) {
+    const int g = 4 * s + gl;
+    bq[s] = make_uint4(0, 0, 0, 0);
+    if (g < G) bq[s] = *reinterpret_cast<const uint4*>(q + ((size_t)b * Hq + hq0 + g) * kD + kq * 32 + j * 8);
+  }
+  float wmax[NSET];
+#pragma unroll
+  for (int s = 0; s < NSET; ++s) wmax[s] = -INFINITY;
+
+  constexpr int kPagesPerWave = kPagesPerScoreBlock / (kScoreThreads / 64);
+#pragma unroll
+  for (int pw = 0; pw < kPagesPerWave; ++pw) {
+    const int slot = slot0 + w * kPagesPerWave + pw;
+    if (slot >= n_slots) break;
+    const int lp = DENSE ? slot : A.page_idx[(size_t)unit * A.cap + slot];
+    const int phys = A.block_table[(size_t)b * A.Mmax + lp];
+    // row (token gl of the step, quarter kq), K group j -> bytes [gl*256 + (kq*4+j)*16, +16) of the step
+    const bf16_t* kpage = k_pool + ((size_t)phys * Hkv + hkv) * PT * kD + gl * kD + (kq * 4 + j) * 8;
+    uint4 a[STEPS];
+#pragma unroll
+    for (int s = 0; s < STEPS; ++s) a[s] = *reinterpret_cast<const uint4*>(kpage + (size_t)s * 4 * kD);
+    float zkeep[NSET][KEEP];
+#pragma unroll
+    for (int s = 0; s < STEPS; ++s) {
+      const bool valid = lp * PT + 4 * s + j < n;  // result rows 4j..4j+3 belong to token j of the step
+#pragma unroll
+      for (int cs = 0; cs < NSET; ++cs) {
+        const f32x4_t zero = {0.f, 0.f, 0.f, 0.f};
+        const f32x4_t c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a[s]),
+                                                                  __builtin_bit_cast(bf16x8_t, bq[cs]), zero, 0, 0, 0);
+        float v = kq == 0 ? c[0] : kq == 1 ? c[1] : kq == 2 ? c[2] : c[3];
+        v += dpp_move<0xB1>(v);
+        v += dpp_move<0x4E>(v);
+        const float z = valid ? A.zscale * v : -INFINITY;
+        if ((s & 3) == kq) zkeep[cs][s >> 2] = z;   // lane (j, head, kq) keeps token 4*(4*i + kq) + j
+        wmax[cs] = fmaxf(wmax[cs], z);
+      }
+    }
+#pragma unroll
+    for (int cs = 0; cs < NSET; ++cs) {
+      const int g = 4 * cs + gl;
+      if (g < G) {
+        const size_t row = DENSE ? (size_t)b * Hq + hq0 + g : (size_t)unit;
+        float* zp = A.zbuf + row * A.zstride + (size_t)slot * PT + j;
+#pragma unroll
+        for (int i = 0; i < KEEP; ++i) zp[4 * (4 * i + kq)] = zkeep[cs][i];
+      }
+    }
+  }
+#pragma unroll
+  for (int cs = 0; cs < NSET; ++cs) {
+    float mx = wmax[cs];
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    if (j == 0 && kq == 0) wmax_s[w][4 * cs + gl] = mx;
+  }
+  __syncthreads();
+  if (threadIdx.x < G) {
+    const int g = threadIdx.x;
+    float mx = wmax_s[0][g];
+    for (int i = 1; i < kScoreThreads / 64; ++i) mx = fmaxf(mx, wmax_s[i][g]);
+    const size_t row = DENSE ? (size_t)b * Hq + hq0 + g : (size_t)unit;
+    A.pmax[row * A.n_chunks_max + chunk] = mx;
   }
 }
 
@@ -127,9 +212,10 @@ __global__ __launch_bounds__(kScoreThreads) void decode_scores_kernel(
 struct SolveShared {
   float list_u[kListCap];         // z - zmax of the candidates that can be in the support
   int32_t list_pos[kListCap];     // their position in the candidate order
+  uint32_t list_row[kListCap];    // their V row: (phys*Hkv + hkv)*P + tok
   float obuf[kSolveWaves][kD];
   float red[2][kSolveWaves][3];
-  int wcount[kSolveWaves];
+  int wcount[2][kSolveWaves];
   float red1[kSolveWaves];
 };
 
@@ -177,11 +263,13 @@ __device__ __forceinline__ float solve_tau(const Src& src, float beta, int ibeta
   float tau = lo;
   int pending_cnt = -1;
   int parity = 0, cnt = 0;
+  bool reeval = false;
   for (int it = 0; it < 64; ++it) {
     float F, D;
     eval_mass(src, tau, beta, ibeta, sh, parity, F, D, cnt);
     parity ^= 1;
     if (pending_cnt >= 0 && cnt == pending_cnt) break;       // exact step kept the support: done
+    if (fabsf(F - 1.0f) <= 4e-7f) break;                     // float32 resolution of F: tau is the root
     pending_cnt = -1;
     float step;
     if (F >= 1.0f) {
@@ -199,12 +287,12 @@ __device__ __forceinline__ float solve_tau(const Src& src, float beta, int ibeta
       step = D > 0.f ? (F - 1.0f) / D : -INFINITY;
     }
     float next = tau + step;
+    if (next == tau) break;                                  // no representable progress
     if (!(next > lo && next < hi)) { next = 0.5f * (lo + hi); pending_cnt = -1; }
-    if (next == tau || hi - lo <= 1.2e-7f) { tau = next; pending_cnt = -2; break; }
-    if (pending_cnt < 0 && fabsf(next - tau) <= 1.2e-7f) { tau = next; pending_cnt = -2; break; }
+    if (hi - lo <= 1.2e-7f || (pending_cnt < 0 && fabsf(next - tau) <= 6e-8f)) { tau = next; reeval = true; break; }
     tau = next;
   }
-  if (pending_cnt == -2) {                                     // tau moved after the last evaluation
+  if (reeval) {                                              // tau moved after the last evaluation
     float F, D;
     eval_mass(src, tau, beta, ibeta, sh, parity, F, D, cnt);
   }
@@ -212,37 +300,35 @@ __device__ __forceinline__ float solve_tau(const Src& src, float beta, int ibeta
   return tau;
 }
 
-template <typename T, bool DENSE>
-__device__ __forceinline__ const T* v_row_ptr(const T* v_pool, const int32_t* block_table,
-                                              const int32_t* page_idx, int b, int bh, int hkv, int Hkv, int P,
-                                              int Mmax, int cap, int pos) {
-  const int slot = pos / P, tok = pos - slot * P;
-  const int lp = DENSE ? slot : page_idx[(size_t)bh * cap + slot];
-  const int phys = block_table[(size_t)b * Mmax + lp];
-  return v_pool + (((size_t)phys * Hkv + hkv) * P + tok) * kD;
+struct SolveArgs {
+  const void* v_pool;
+  const int32_t* block_table; const int32_t* seq_lens; const int32_t* page_idx; const int32_t* n_sel;
+  const float* zbuf; const float* pmax;
+  float* out; float* tau_out; int32_t* supp_out;
+  ekv_decode_extras ex;
+  int Hq, Hkv, P, Mmax, cap, n_chunks_max;
+  size_t zstride;
+  float a, beta; int ibeta;
+};
+
+// V row index (phys*Hkv + hkv)*P + tok of candidate position `pos`.
+template <bool DENSE>
+__device__ __forceinline__ uint32_t v_row_of(const SolveArgs& A, int b, int bh, int hkv, int pos) {
+  const int slot = pos / A.P, tok = pos - slot * A.P;
+  const int lp = DENSE ? slot : A.page_idx[(size_t)bh * A.cap + slot];
+  const int phys = A.block_table[(size_t)b * A.Mmax + lp];
+  return (uint32_t)((phys * A.Hkv + hkv) * A.P + tok);
+}
+template <bool DENSE>
+__device__ __forceinline__ int token_of(const SolveArgs& A, int bh, int pos) {
+  const int slot = pos / A.P, tok = pos - slot * A.P;
+  const int lp = DENSE ? slot : A.page_idx[(size_t)bh * A.cap + slot];
+  return lp * A.P + tok;
 }
 
-template <typename T, bool DENSE, typename Src>
-__device__ __forceinline__ void weighted_values(const Src& src, float tau, float beta, int ibeta,
-                                                const T* __restrict__ v_pool,
-                                                const int32_t* __restrict__ block_table,
-                                                const int32_t* __restrict__ page_idx, int b, int bh, int hkv,
-                                                int Hkv, int P, int Mmax, int cap, SolveShared& sh,
-                                                float* __restrict__ out) {
-  const int tid = threadIdx.x, rs = tid >> 4, c = tid & 15, w = tid >> 6;
-  float acc[8];
-#pragma unroll
-  for (int i = 0; i < 8; ++i) acc[i] = 0.f;
-  for (int e = rs; e < src.n; e += kSolveThreads / 16) {
-    const float x = src.get_u(e) - tau;
-    if (x > 0.f) {
-      const float p = pow_beta(x, beta, ibeta);
-      float v[8];
-      load8<T>(v_row_ptr<T, DENSE>(v_pool, block_table, page_idx, b, bh, hkv, Hkv, P, Mmax, cap, src.get_pos(e)) + 8 * c, v);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) acc[i] = fmaf(p, v[i], acc[i]);
-    }
-  }
+// Final reduction of the per-lane partial outputs (acc[8] = channels 8c..8c+7 of a row slot).
+__device__ __forceinline__ void reduce_output(float (&acc)[8], SolveShared& sh, float* __restrict__ out) {
+  const int tid = threadIdx.x, c = tid & 15, w = tid >> 6;
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     acc[i] += __shfl_xor(acc[i], 16);
@@ -257,199 +343,249 @@ __device__ __forceinline__ void weighted_values(const Src& src, float tau, float
   if (tid < kD) {
     float s = 0.f;
     for (int i = 0; i < kSolveWaves; ++i) s += sh.obuf[i][tid];
-    out[(size_t)bh * kD + tid] = s;
-  }
-}
-
-// Ordered list of the support's logical token indices (side output).
-template <bool DENSE, typename Src>
-__device__ __forceinline__ void write_support(const Src& src, float tau, const int32_t* __restrict__ page_idx,
-                                              int bh, int P, int cap, SolveShared& sh,
-                                              int32_t* __restrict__ dst, int dst_cap) {
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  int base = 0;
-  for (int i0 = 0; i0 < src.n; i0 += kSolveThreads) {
-    const int i = i0 + tid;
-    const bool in = i < src.n && src.get_u(i) > tau;
-    const uint64_t m = __ballot(in);
-    __syncthreads();
-    if (lane == 0) sh.wcount[w] = __popcll(m);
-    __syncthreads();
-    int off = base, tot = 0;
-    for (int j = 0; j < kSolveWaves; ++j) { const int cj = sh.wcount[j]; if (j < w) off += cj; tot += cj; }
-    if (in) {
-      off += __popcll(m & ((1ull << lane) - 1ull));
-      if (off < dst_cap) {
-        const int pos = src.get_pos(i);
-        const int slot = pos / P, tok = pos - slot * P;
-        const int lp = DENSE ? slot : page_idx[(size_t)bh * cap + slot];
-        dst[off] = lp * P + tok;
-      }
-    }
-    base += tot;
+    out[tid] = s;
   }
 }
 
 template <typename T, bool DENSE>
-__global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(
-    const T* __restrict__ v_pool, const int32_t* __restrict__ block_table, const int32_t* __restrict__ seq_lens,
-    const int32_t* __restrict__ page_idx, const int32_t* __restrict__ n_sel, const float* __restrict__ zbuf,
-    const float* __restrict__ pmax, float* __restrict__ out, float* __restrict__ tau_out,
-    int32_t* __restrict__ supp_out, ekv_decode_extras ex, int Hq, int Hkv, int P, int Mmax, int cap,
-    size_t zstride, int n_chunks_max, float a, float beta, int ibeta) {
+__global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const SolveArgs A) {
   __shared__ SolveShared sh;
+  const int Hq = A.Hq, Hkv = A.Hkv, P = A.P;
   const int bh = blockIdx.x, b = bh / Hq, hq = bh % Hq, hkv = hq / (Hq / Hkv);
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int n = seq_lens[b];
-  const int n_slots = DENSE ? (n + P - 1) / P : n_sel[bh];
+  const uint64_t lt = (1ull << lane) - 1ull;
+  const T* v_pool = (const T*)A.v_pool;
+  const int n = A.seq_lens[b];
+  const int n_slots = DENSE ? (n + P - 1) / P : A.n_sel[bh];
   const int n_cand = n_slots * P;
   const int n_chunks = (n_slots + kPagesPerScoreBlock - 1) / kPagesPerScoreBlock;
   const int chunk_tokens = kPagesPerScoreBlock * P;
-  const float* zr = zbuf + (size_t)bh * zstride;
-  const float* pm = pmax + (size_t)bh * n_chunks_max;
+  const float* zr = A.zbuf + (size_t)bh * A.zstride;
+  const float* pm = A.pmax + (size_t)bh * A.n_chunks_max;
+  const float beta = A.beta; const int ibeta = A.ibeta;
+  float* out = A.out + (size_t)bh * kD;
 
-  float m = -INFINITY;
-  for (int i = tid; i < n_chunks; i += kSolveThreads) m = fmaxf(m, pm[i]);
-  const float zmax = block_max(m, sh.red1);
+  float mx = -INFINITY;
+  for (int i = tid; i < n_chunks; i += kSolveThreads) mx = fmaxf(mx, pm[i]);
+  const float zmax = block_max(mx, sh.red1);
   if (!(zmax > -INFINITY)) {                // no valid candidate at all
-    if (tid < kD) out[(size_t)bh * kD + tid] = 0.f;
-    if (tid == 0) { tau_out[bh] = INFINITY; supp_out[bh] = 0; }
+    if (tid < kD) out[tid] = 0.f;
+    if (tid == 0) { A.tau_out[bh] = INFINITY; A.supp_out[bh] = 0; }
     return;
   }
   const float thr = zmax - 1.0f - 4e-6f * fmaxf(1.f, fabsf(zmax));
 
-  // ordered compaction of {z > thr}: wavefront w owns a contiguous range of chunks
-  const int cpw = (n_chunks + kSolveWaves - 1) / kSolveWaves;
-  const int ck0 = min(w * cpw, n_chunks), ck1 = min(ck0 + cpw, n_chunks);
-  int wc = 0;
-  for (int ck = ck0; ck < ck1; ++ck) {
-    if (!(pm[ck] > thr)) continue;
-    const int base = ck * chunk_tokens;
-    for (int j = lane; j < chunk_tokens; j += 64) {
-      const int pos = base + j;
-      const bool in = pos < n_cand && zr[pos] > thr;
-      wc += __popcll(__ballot(in));
+  // ---- ordered compaction of {z > thr} into LDS, in rounds of kRoundTokens candidates.  Wavefront w
+  // of a round owns 64*kRoundLoads consecutive positions, so (round, w, load, lane) order is candidate
+  // order.  A 64-position load whose chunk maximum is <= thr is not issued.
+  const bool can_skip = (chunk_tokens & 63) == 0;
+  int n_list = 0, parity = 0;
+  bool in_lds = true;
+  for (int round0 = 0; round0 < n_cand; round0 += kRoundTokens) {
+    const int seg = round0 + w * 64 * kRoundLoads;
+    float v[kRoundLoads];
+#pragma unroll
+    for (int i = 0; i < kRoundLoads; ++i) {
+      const int pos0 = seg + i * 64;
+      v[i] = -INFINITY;
+      if (pos0 < n_cand && (!can_skip || pm[pos0 / chunk_tokens] > thr)) {
+        const int pos = pos0 + lane;
+        if (pos < n_cand) v[i] = zr[pos];
+      }
     }
-  }
-  __syncthreads();
-  if (lane == 0) sh.wcount[w] = wc;
-  __syncthreads();
-  int woff = 0, n_list = 0;
-  for (int j = 0; j < kSolveWaves; ++j) { const int cj = sh.wcount[j]; if (j < w) woff += cj; n_list += cj; }
-  const bool in_lds = n_list <= kListCap;
-  if (in_lds) {
-    for (int ck = ck0; ck < ck1; ++ck) {
-      if (!(pm[ck] > thr)) continue;
-      const int base = ck * chunk_tokens;
-      for (int j = lane; j < chunk_tokens; j += 64) {
-        const int pos = base + j;
-        const float z = pos < n_cand ? zr[pos] : -INFINITY;
-        const bool in = z > thr;
+    int c = 0;
+#pragma unroll
+    for (int i = 0; i < kRoundLoads; ++i) c += __popcll(__ballot(v[i] > thr));
+    if (lane == 0) sh.wcount[parity][w] = c;
+    __syncthreads();
+    int off = n_list, tot = 0;
+    for (int i = 0; i < kSolveWaves; ++i) { const int ci = sh.wcount[parity][i]; if (i < w) off += ci; tot += ci; }
+    n_list += tot;
+    parity ^= 1;
+    if (n_list > kListCap) in_lds = false;
+    if (in_lds) {
+#pragma unroll
+      for (int i = 0; i < kRoundLoads; ++i) {
+        const bool in = v[i] > thr;
         const uint64_t mk = __ballot(in);
         if (in) {
-          const int o = woff + __popcll(mk & ((1ull << lane) - 1ull));
-          sh.list_u[o] = z - zmax;
-          sh.list_pos[o] = pos;
+          const int o = off + __popcll(mk & lt);
+          sh.list_u[o] = v[i] - zmax;
+          sh.list_pos[o] = seg + i * 64 + lane;
         }
-        woff += __popcll(mk);
+        off += __popcll(mk);
       }
     }
   }
   __syncthreads();
 
   float tau_u; int supp;
-  const ListSrc ls{sh.list_u, sh.list_pos, n_list};
-  const RowSrc rs{zr, n_cand, zmax};
   if (in_lds) {
+    // V row of every candidate, fetched now (two dependent loads) and consumed after the solve
+    uint32_t rowreg[kListCap / kSolveThreads];
+#pragma unroll
+    for (int k = 0; k < kListCap / kSolveThreads; ++k) {
+      const int e = tid + k * kSolveThreads;
+      rowreg[k] = e < n_list ? v_row_of<DENSE>(A, b, bh, hkv, sh.list_pos[e]) : 0u;
+    }
+    const ListSrc ls{sh.list_u, sh.list_pos, n_list};
     tau_u = solve_tau(ls, beta, ibeta, sh, supp);
-    weighted_values<T, DENSE>(ls, tau_u, beta, ibeta, v_pool, block_table, page_idx, b, bh, hkv, Hkv, P, Mmax, cap, sh, out);
+#pragma unroll
+    for (int k = 0; k < kListCap / kSolveThreads; ++k) {
+      const int e = tid + k * kSolveThreads;
+      if (e < n_list) sh.list_row[e] = rowreg[k];
+    }
+    __syncthreads();
+    // in-place ordered compaction of the support: entry e keeps (p_e, pos_e, row_e)
+    int n_sup = 0;
+    for (int e0 = 0; e0 < n_list; e0 += kSolveThreads) {
+      const int e = e0 + tid;
+      const float x = e < n_list ? sh.list_u[e] - tau_u : -1.f;
+      const int pe = e < n_list ? sh.list_pos[e] : 0;
+      const uint32_t re = e < n_list ? sh.list_row[e] : 0u;
+      const bool in = x > 0.f;
+      const uint64_t mk = __ballot(in);
+      if (lane == 0) sh.wcount[parity][w] = __popcll(mk);
+      __syncthreads();                                     // all reads of this block are done
+      int off = n_sup, tot = 0;
+      for (int i = 0; i < kSolveWaves; ++i) { const int ci = sh.wcount[parity][i]; if (i < w) off += ci; tot += ci; }
+      parity ^= 1;
+      if (in) {
+        const int o = off + __popcll(mk & lt);
+        sh.list_u[o] = pow_beta(x, beta, ibeta);
+        sh.list_pos[o] = pe;
+        sh.list_row[o] = re;
+      }
+      n_sup += tot;
+    }
+    __syncthreads();
+    // weighted value sum: 64 row slots x 16 lanes, one independent 16-byte load per support token
+    const int rs = tid >> 4, c = tid & 15;
+    float acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+    for (int e = rs; e < n_sup; e += kSolveThreads / 16) {
+      const float p = sh.list_u[e];
+      float vv[8];
+      load8<T>(v_pool + (size_t)sh.list_row[e] * kD + 8 * c, vv);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i] = fmaf(p, vv[i], acc[i]);
+    }
+    reduce_output(acc, sh, out);
+    if (A.ex.support_tokens != nullptr) {
+      int32_t* dst = A.ex.support_tokens + (size_t)bh * A.ex.support_cap;
+      for (int e = tid; e < n_sup && e < A.ex.support_cap; e += kSolveThreads)
+        dst[e] = token_of<DENSE>(A, bh, sh.list_pos[e]);
+    }
   } else {
-    tau_u = solve_tau(rs, beta, ibeta, sh, supp);
-    weighted_values<T, DENSE>(rs, tau_u, beta, ibeta, v_pool, block_table, page_idx, b, bh, hkv, Hkv, P, Mmax, cap, sh, out);
+    // the candidates do not fit in LDS: stream the score row for every evaluation
+    const RowSrc rsrc{zr, n_cand, zmax};
+    tau_u = solve_tau(rsrc, beta, ibeta, sh, supp);
+    const int rs = tid >> 4, c = tid & 15;
+    float acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+    for (int e = rs; e < n_cand; e += kSolveThreads / 16) {
+      const float x = zr[e] - zmax - tau_u;
+      if (x > 0.f) {
+        const float p = pow_beta(x, beta, ibeta);
+        float vv[8];
+        load8<T>(v_pool + (size_t)v_row_of<DENSE>(A, b, bh, hkv, e) * kD + 8 * c, vv);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = fmaf(p, vv[i], acc[i]);
+      }
+    }
+    reduce_output(acc, sh, out);
+    if (A.ex.support_tokens != nullptr) {
+      int32_t* dst = A.ex.support_tokens + (size_t)bh * A.ex.support_cap;
+      int base = 0;
+      for (int i0 = 0; i0 < n_cand; i0 += kSolveThreads) {
+        const int i = i0 + tid;
+        const bool in = i < n_cand && zr[i] - zmax > tau_u;
+        const uint64_t mk = __ballot(in);
+        __syncthreads();
+        if (lane == 0) sh.wcount[0][w] = __popcll(mk);
+        __syncthreads();
+        int off = base, tot = 0;
+        for (int k = 0; k < kSolveWaves; ++k) { const int ck = sh.wcount[0][k]; if (k < w) off += ck; tot += ck; }
+        if (in) {
+          off += __popcll(mk & lt);
+          if (off < A.ex.support_cap) dst[off] = token_of<DENSE>(A, bh, i);
+        }
+        base += tot;
+      }
+    }
   }
   const float tau = tau_u + zmax;
-  if (tid == 0) { tau_out[bh] = tau; supp_out[bh] = supp; }
+  if (tid == 0) { A.tau_out[bh] = tau; A.supp_out[bh] = supp; }
 
-  // ---- optional side outputs ------------------------------------------------------------
-  if (ex.support_tokens != nullptr) {
-    int32_t* dst = ex.support_tokens + (size_t)bh * ex.support_cap;
-    if (in_lds) write_support<DENSE>(ls, tau_u, page_idx, bh, P, cap, sh, dst, ex.support_cap);
-    else write_support<DENSE>(rs, tau_u, page_idx, bh, P, cap, sh, dst, ex.support_cap);
-  }
-  if (ex.tau_ref != nullptr && (ex.kept_mass_ref != nullptr || ex.kept_supp_ref != nullptr)) {
-    const float tr = ex.tau_ref[bh];
+  // ---- optional side outputs over ALL candidates ----------------------------------------
+  if (A.ex.tau_ref != nullptr && (A.ex.kept_mass_ref != nullptr || A.ex.kept_supp_ref != nullptr)) {
+    const float tr = A.ex.tau_ref[bh];
     float f = 0.f; int c = 0;
     for (int i = tid; i < n_cand; i += kSolveThreads) {
       const float x = zr[i] - tr;
       if (x > 0.f) { f += pow_beta(x, beta, ibeta); ++c; }
     }
     f = block_sum(f, sh.red1);
-    c = block_sum_i(c, sh.wcount);
+    c = block_sum_i(c, sh.wcount[0]);
     if (tid == 0) {
-      if (ex.kept_mass_ref != nullptr) ex.kept_mass_ref[bh] = f;
-      if (ex.kept_supp_ref != nullptr) ex.kept_supp_ref[bh] = c;
+      if (A.ex.kept_mass_ref != nullptr) A.ex.kept_mass_ref[bh] = f;
+      if (A.ex.kept_supp_ref != nullptr) A.ex.kept_supp_ref[bh] = c;
     }
   }
-  if (DENSE && ex.lse != nullptr) {
+  if (DENSE && A.ex.lse != nullptr) {
     // log sum_j exp(s_j) with s_j = z_j / a, shifted by the maximum
-    const float inv_a = 1.0f / a;
+    const float inv_a = 1.0f / A.a;
     float f = 0.f;
     for (int i = tid; i < n_cand; i += kSolveThreads) f += __expf((zr[i] - zmax) * inv_a);
     f = block_sum(f, sh.red1);
-    if (tid == 0) ex.lse[bh] = zmax * inv_a + __logf(f);
+    if (tid == 0) A.ex.lse[bh] = zmax * inv_a + __logf(f);
   }
 }
 
 // ------------------------------------------------------------------------------------------
 // launchers
 // ------------------------------------------------------------------------------------------
-template <typename T, int G, bool DENSE>
-static void launch_scores_P(const Dims& dm, dim3 grid, const void* q, const ekv_cache_view& c,
-                            const int32_t* page_idx, const int32_t* n_sel, const DecodeWorkspace& ws,
-                            hipStream_t st) {
-  const float zscale = dm.a * dm.scale;
-#define EKV_SCORES(PT)                                                                                        \
-  hipLaunchKernelGGL((decode_scores_kernel<T, G, DENSE, PT>), grid, dim3(kScoreThreads), 0, st, (const T*)q,  \
-                     (const T*)c.k_pool, c.block_table, c.seq_lens, page_idx, n_sel, ws.z, ws.pmax, dm.Hq,    \
-                     dm.Hkv, dm.P, dm.Mmax, dm.cap, ws.zstride, ws.n_chunks_max, zscale)
-  if (dm.P == 16) EKV_SCORES(16);
-  else if (dm.P == 32) EKV_SCORES(32);
-  else EKV_SCORES(0);
-#undef EKV_SCORES
-}
-
-template <typename T>
-static void launch_decode_T(const Dims& dm, bool dense, const void* q, const ekv_cache_view& c,
-                            const int32_t* page_idx, const int32_t* n_sel, float* out, float* tau,
-                            int32_t* supp, const ekv_decode_extras& ex, const DecodeWorkspace& ws,
-                            hipStream_t st) {
-  if (dense) {
-    dim3 grid(ws.n_chunks_max, dm.B * dm.Hkv);
-    switch (dm.G) {
-      case 1: launch_scores_P<T, 1, true>(dm, grid, q, c, page_idx, n_sel, ws, st); break;
-      case 2: launch_scores_P<T, 2, true>(dm, grid, q, c, page_idx, n_sel, ws, st); break;
-      case 4: launch_scores_P<T, 4, true>(dm, grid, q, c, page_idx, n_sel, ws, st); break;
-      default: launch_scores_P<T, 8, true>(dm, grid, q, c, page_idx, n_sel, ws, st); break;
-    }
-    hipLaunchKernelGGL((decode_solve_kernel<T, true>), dim3(dm.B * dm.Hq), dim3(kSolveThreads), 0, st,
-                       (const T*)c.v_pool, c.block_table, c.seq_lens, page_idx, n_sel, ws.z, ws.pmax, out, tau,
-                       supp, ex, dm.Hq, dm.Hkv, dm.P, dm.Mmax, dm.cap, ws.zstride, ws.n_chunks_max, dm.a,
-                       dm.beta, dm.ibeta);
-  } else {
-    dim3 grid(ws.n_chunks_max, dm.B * dm.Hq);
-    launch_scores_P<T, 1, false>(dm, grid, q, c, page_idx, n_sel, ws, st);
-    hipLaunchKernelGGL((decode_solve_kernel<T, false>), dim3(dm.B * dm.Hq), dim3(kSolveThreads), 0, st,
-                       (const T*)c.v_pool, c.block_table, c.seq_lens, page_idx, n_sel, ws.z, ws.pmax, out, tau,
-                       supp, ex, dm.Hq, dm.Hkv, dm.P, dm.Mmax, dm.cap, ws.zstride, ws.n_chunks_max, dm.a,
-                       dm.beta, dm.ibeta);
-  }
+template <int G, bool DENSE>
+static void launch_scores(const Dims& dm, dim3 grid, const ScoreArgs& sa, hipStream_t st) {
+  dim3 block(kScoreThreads);
+  if (dm.dtype == EKV_BF16 && dm.P == 16)
+    hipLaunchKernelGGL((decode_scores_mfma_kernel<G, DENSE, 16>), grid, block, 0, st, sa);
+  else if (dm.dtype == EKV_BF16 && dm.P == 32)
+    hipLaunchKernelGGL((decode_scores_mfma_kernel<G, DENSE, 32>), grid, block, 0, st, sa);
+  else if (dm.dtype == EKV_BF16 && dm.P == 64)
+    hipLaunchKernelGGL((decode_scores_mfma_kernel<G, DENSE, 64>), grid, block, 0, st, sa);
+  else if (dm.dtype == EKV_BF16)
+    hipLaunchKernelGGL((decode_scores_valu_kernel<bf16_t, G, DENSE>), grid, block, 0, st, sa);
+  else
+    hipLaunchKernelGGL((decode_scores_valu_kernel<float, G, DENSE>), grid, block, 0, st, sa);
 }
 
 void launch_decode(const Dims& dm, bool dense, const void* q, const ekv_cache_view& c,
                    const int32_t* page_idx, const int32_t* n_sel, float* out, float* tau, int32_t* supp,
                    const ekv_decode_extras& ex, const DecodeWorkspace& ws, hipStream_t st) {
-  if (dm.dtype == EKV_F32) launch_decode_T<float>(dm, dense, q, c, page_idx, n_sel, out, tau, supp, ex, ws, st);
-  else launch_decode_T<bf16_t>(dm, dense, q, c, page_idx, n_sel, out, tau, supp, ex, ws, st);
+  ScoreArgs sa{q, c.k_pool, c.block_table, c.seq_lens, page_idx, n_sel, ws.z, ws.pmax,
+               dm.Hq, dm.Hkv, dm.P, dm.Mmax, dm.cap, ws.n_chunks_max, ws.zstride, dm.a * dm.scale};
+  SolveArgs so{c.v_pool, c.block_table, c.seq_lens, page_idx, n_sel, ws.z, ws.pmax, out, tau, supp, ex,
+               dm.Hq, dm.Hkv, dm.P, dm.Mmax, dm.cap, ws.n_chunks_max, ws.zstride, dm.a, dm.beta, dm.ibeta};
+  dim3 sgrid(dm.B * dm.Hq), sblock(kSolveThreads);
+  if (dense) {
+    dim3 grid(ws.n_chunks_max, dm.B * dm.Hkv);
+    switch (dm.G) {
+      case 1: launch_scores<1, true>(dm, grid, sa, st); break;
+      case 2: launch_scores<2, true>(dm, grid, sa, st); break;
+      case 4: launch_scores<4, true>(dm, grid, sa, st); break;
+      default: launch_scores<8, true>(dm, grid, sa, st); break;
+    }
+    if (dm.dtype == EKV_F32) hipLaunchKernelGGL((decode_solve_kernel<float, true>), sgrid, sblock, 0, st, so);
+    else hipLaunchKernelGGL((decode_solve_kernel<bf16_t, true>), sgrid, sblock, 0, st, so);
+  } else {
+    dim3 grid(ws.n_chunks_max, dm.B * dm.Hq);
+    launch_scores<1, false>(dm, grid, sa, st);
+    if (dm.dtype == EKV_F32) hipLaunchKernelGGL((decode_solve_kernel<float, false>), sgrid, sblock, 0, st, so);
+    else hipLaunchKernelGGL((decode_solve_kernel<bf16_t, false>), sgrid, sblock, 0, st, so);
+  }
 }
 
 }  // namespace ekv

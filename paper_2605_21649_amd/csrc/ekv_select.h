@@ -1,6 +1,10 @@
 // Exact k-th-largest selection and order-preserving compaction over the pages of one
 // (sequence, query head), shared by the top-k and the Gaussian-aware selectors.
-// One 1024-thread workgroup; keys are order-preserving uint32 images of float scores.
+//
+// One 1024-thread workgroup.  Keys are order-preserving uint32 images of float scores.  Wavefront w owns
+// the contiguous page range [w*64*items, (w+1)*64*items) and lane l holds pages w*64*items + i*64 + l,
+// i < items: loads are coalesced, keys can live in registers for all passes, and (w, i, l) order is
+// ascending page order, so ballots give an ordered compaction without sorting.
 #pragma once
 #include "ekv_device.h"
 
@@ -15,6 +19,7 @@ struct SelectShared {
   uint32_t hist[kBins];
   int scan_buf[kSelWaves + 1];
   uint32_t red_u[kSelWaves];
+  int wave_gt[kSelWaves], wave_eq[kSelWaves];
   uint32_t digit, above;
 };
 
@@ -41,17 +46,37 @@ __device__ __forceinline__ int block_excl_scan(int v, int* buf, int& total) {
   return base + inc - v;
 }
 
-// Finds the k-th largest key among keyfn(0..M-1) (1 <= k <= M) by radix selection on (key - min key),
-// 11 bits per pass over only as many bits as the key range needs.  Returns kmin (the smallest key),
-// vT = (k-th largest key) - kmin, and k_eq = how many elements equal to it belong to the top k.
-template <typename KeyFn>
-__device__ __forceinline__ void radix_select_kth(KeyFn keyfn, int M, int k, SelectShared& sh,
+// Keys of one (b,h) row.  ITEMS > 0: held in registers (M <= 1024*ITEMS); ITEMS == 0: recomputed from
+// memory on every access (any M).  `fn(p)` gives the key of page p.
+template <int ITEMS, typename KeyFn>
+struct KeySet {
+  KeyFn fn;
+  int M, items, page0;                      // page0 = first page of this lane
+  uint32_t reg[ITEMS ? ITEMS : 1];
+  __device__ __forceinline__ KeySet(KeyFn f, int M_) : fn(f), M(M_) {
+    items = ITEMS ? ITEMS : (M + kSelThreads - 1) / kSelThreads;
+    page0 = (threadIdx.x >> 6) * 64 * items + (threadIdx.x & 63);
+    if (ITEMS) {
+#pragma unroll
+      for (int i = 0; i < (ITEMS ? ITEMS : 1); ++i) reg[i] = valid(i) ? fn(page(i)) : 0u;
+    }
+  }
+  __device__ __forceinline__ int page(int i) const { return page0 + i * 64; }
+  __device__ __forceinline__ bool valid(int i) const { return page(i) < M; }
+  __device__ __forceinline__ uint32_t key(int i) const { return ITEMS ? reg[i] : fn(page(i)); }
+};
+
+// Finds the k-th largest key (1 <= k <= M) by radix selection on (key - min key), 11 bits per pass over
+// only as many bits as the key range needs.  Returns kmin (the smallest key), vT = (k-th largest key)
+// - kmin, and k_eq = how many elements equal to it belong to the top k.
+template <int ITEMS, typename KeyFn>
+__device__ __forceinline__ void radix_select_kth(const KeySet<ITEMS, KeyFn>& ks, int k, SelectShared& sh,
                                                  uint32_t& kmin_out, uint32_t& vT_out, int& k_eq_out) {
   const int tid = threadIdx.x;
   uint32_t lo = 0xffffffffu, hi = 0u;
-  for (int p = tid; p < M; p += kSelThreads) {
-    const uint32_t key = keyfn(p);
-    lo = min(lo, key); hi = max(hi, key);
+#pragma unroll
+  for (int i = 0; i < (ITEMS ? ITEMS : ks.items); ++i) {
+    if (ks.valid(i)) { const uint32_t key = ks.key(i); lo = min(lo, key); hi = max(hi, key); }
   }
   for (int d = 32; d >= 1; d >>= 1) {
     lo = min(lo, (uint32_t)__shfl_xor((int)lo, d));
@@ -78,9 +103,12 @@ __device__ __forceinline__ void radix_select_kth(KeyFn keyfn, int M, int k, Sele
     __syncthreads();
     for (int i = tid; i < kBins; i += kSelThreads) sh.hist[i] = 0;
     __syncthreads();
-    for (int p = tid; p < M; p += kSelThreads) {
-      const uint32_t v = keyfn(p) - kmin;
-      if ((uint32_t)((uint64_t)v >> (shift + dbits)) == prefix) atomicAdd(&sh.hist[(v >> shift) & dmask], 1u);
+#pragma unroll
+    for (int i = 0; i < (ITEMS ? ITEMS : ks.items); ++i) {
+      if (ks.valid(i)) {
+        const uint32_t v = ks.key(i) - kmin;
+        if ((uint32_t)((uint64_t)v >> (shift + dbits)) == prefix) atomicAdd(&sh.hist[(v >> shift) & dmask], 1u);
+      }
     }
     __syncthreads();
     // thread t owns digits (kBins-1-2t) and (kBins-2-2t): scan from the top digit downwards
@@ -97,29 +125,39 @@ __device__ __forceinline__ void radix_select_kth(KeyFn keyfn, int M, int k, Sele
   kmin_out = kmin; vT_out = prefix; k_eq_out = k_rem;
 }
 
-// Writes, in ascending page order, every page whose v = keyfn(p) - kmin exceeds vT, plus the first
-// k_eq pages (by index) with v == vT.  Thread t owns the contiguous page range [t*ipt, (t+1)*ipt).
-template <typename KeyFn>
-__device__ __forceinline__ void compact_ordered(KeyFn keyfn, int M, uint32_t kmin, uint32_t vT, int k_eq,
-                                                SelectShared& sh, int32_t* __restrict__ out) {
-  const int tid = threadIdx.x;
-  const int ipt = (M + kSelThreads - 1) / kSelThreads;
-  const int p0 = min(tid * ipt, M), p1 = min(p0 + ipt, M);
+// Writes, in ascending page order, every page whose v = key - kmin exceeds vT, plus the first k_eq
+// pages (by index) with v == vT.
+template <int ITEMS, typename KeyFn>
+__device__ __forceinline__ void compact_ordered(const KeySet<ITEMS, KeyFn>& ks, uint32_t kmin, uint32_t vT,
+                                                int k_eq, SelectShared& sh, int32_t* __restrict__ out) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const uint64_t lt = (1ull << lane) - 1ull;
   int n_gt = 0, n_eq = 0;
-  for (int p = p0; p < p1; ++p) {
-    const uint32_t v = keyfn(p) - kmin;
-    n_gt += v > vT; n_eq += v == vT;
+#pragma unroll
+  for (int i = 0; i < (ITEMS ? ITEMS : ks.items); ++i) {
+    const bool ok = ks.valid(i);
+    const uint32_t v = ok ? ks.key(i) - kmin : 0u;
+    n_gt += __popcll(__ballot(ok && v > vT));
+    n_eq += __popcll(__ballot(ok && v == vT));
   }
-  int tot_gt, tot_eq;
-  const int gt_before = block_excl_scan(n_gt, sh.scan_buf, tot_gt);
-  const int eq_before = block_excl_scan(n_eq, sh.scan_buf, tot_eq);
-  int eq_rank = eq_before;
-  int o = gt_before + min(eq_before, k_eq);
-  for (int p = p0; p < p1; ++p) {
-    const uint32_t v = keyfn(p) - kmin;
-    bool take = v > vT;
-    if (v == vT) { take = eq_rank < k_eq; ++eq_rank; }
-    if (take) out[o++] = p;
+  __syncthreads();
+  if (lane == 0) { sh.wave_gt[w] = n_gt; sh.wave_eq[w] = n_eq; }
+  __syncthreads();
+  int gt_before = 0, eq_before = 0;
+  for (int i = 0; i < w; ++i) { gt_before += sh.wave_gt[i]; eq_before += sh.wave_eq[i]; }
+  int eq_run = eq_before;
+  int o_run = gt_before + min(eq_before, k_eq);
+#pragma unroll
+  for (int i = 0; i < (ITEMS ? ITEMS : ks.items); ++i) {
+    const bool ok = ks.valid(i);
+    const uint32_t v = ok ? ks.key(i) - kmin : 0u;
+    const bool eq = ok && v == vT;
+    const uint64_t m_eq = __ballot(eq);
+    const bool take = (ok && v > vT) || (eq && eq_run + __popcll(m_eq & lt) < k_eq);
+    const uint64_t m_take = __ballot(take);
+    if (take) out[o_run + __popcll(m_take & lt)] = ks.page(i);
+    eq_run += __popcll(m_eq);
+    o_run += __popcll(m_take);
   }
 }
 

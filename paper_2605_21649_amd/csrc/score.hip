@@ -1,26 +1,147 @@
 // Query-aware page scoring (paper Sec. 4.2 Eq. 9 and Sec. 4.3 page moments).
 //
 // The statistics arrays are [B][Hkv][Mmax][2][128] in logical page order, so one (sequence, KV head)
-// is a single contiguous stream.  A wavefront step loads two page records (2 x 2 x 128 elements) with
-// one 16-byte load per lane and produces the scores of the G query heads that share the KV head:
-//   box   = scale * (q+ . k_max + q- . k_min)     (term by term the same products as Eq. 9's max)
-//   mu    = scale * q . k_avg ,  sigma = scale * sqrt(q^2 . k_std^2)
-// Reductions run inside 16-lane DPP rows; results are staged in LDS and written coalesced.
+// is a single contiguous stream.  Per page the kernel needs, for the G query heads of the group,
+//   box    = scale * (q- . k_min + q+ . k_max)       (term by term the same products as Eq. 9's max)
+//   mu     = scale * q . k_avg ,   sigma = scale * sqrt(q^2 . k_var)         (k_var = k_std^2)
+// i.e. a [pages x 256] x [256 x G] contraction.  bf16 statistics go through the matrix cores
+// (v_mfma_f32_16x16x32_bf16): an MFMA tile holds 4 pages x 4 channel quarters as its 16 rows and
+// G heads x 4 channel quarters as its 16 columns, so that every lane's A operand is the 16 bytes of a
+// fully coalesced load; only the blocks with matching quarters are meaningful and are summed with
+// two DPP quad steps.  q^2 is split exactly into two bf16 values (a product of two 8-bit significands
+// has 16 bits).  float32 statistics use plain FMAs and DPP row reductions.
 #include "ekv_device.h"
 #include "ekv_internal.h"
 
 namespace ekv {
 
-constexpr int kScoreTile = 64;    // pages per workgroup (4 wavefronts x 8 steps x 2 pages)
-constexpr int kScoreSteps = kScoreTile / 4 / 2;
+constexpr int kScoreTile = 64;    // pages per workgroup: 4 wavefronts x 16 pages
 
-template <typename T, int G, bool GAUSS>
-__global__ __launch_bounds__(256) void score_pages_kernel(const T* __restrict__ q,
-                                                          const T* __restrict__ stats,
-                                                          const int32_t* __restrict__ seq_lens,
-                                                          float* __restrict__ out0,   // box or mu
-                                                          float* __restrict__ out1,   // sigma (GAUSS)
-                                                          int Hkv, int P, int Mmax, float scale) {
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+
+__device__ __forceinline__ f32x4_t mfma_bf16(const uint4& a, const uint4& b, f32x4_t c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b),
+                                                 c, 0, 0, 0);
+}
+
+// keep the negative (NEG) or the non-negative bf16 halves of a packed pair, zero the others
+template <bool NEG> __device__ __forceinline__ uint32_t keep_sign(uint32_t x) {
+  const uint32_t lo_neg = (x & 0x00008000u) ? 0x0000ffffu : 0u;
+  const uint32_t hi_neg = (x & 0x80000000u) ? 0xffff0000u : 0u;
+  const uint32_t m = lo_neg | hi_neg;
+  return NEG ? (x & m) : (x & ~m);
+}
+
+// q^2 of a packed bf16 pair, split exactly into hi + lo bf16 parts (truncation keeps the top 8 bits of
+// the 16-bit product; the remainder has at most 8 significant bits)
+__device__ __forceinline__ void square_split(uint32_t x, uint32_t& hi, uint32_t& lo) {
+  const float a = __uint_as_float(x << 16), b = __uint_as_float(x & 0xffff0000u);
+  const float a2 = a * a, b2 = b * b;
+  const uint32_t a_hi = __float_as_uint(a2) & 0xffff0000u, b_hi = __float_as_uint(b2) & 0xffff0000u;
+  const float a_lo = a2 - __uint_as_float(a_hi), b_lo = b2 - __uint_as_float(b_hi);
+  hi = (a_hi >> 16) | b_hi;
+  lo = (__float_as_uint(a_lo) >> 16) | (__float_as_uint(b_lo) & 0xffff0000u);
+}
+
+// The meaningful entry of an MFMA result for this lane (the block whose row quarter equals the column
+// quarter kq = lane & 3), summed over the four quarters held by the lanes of a quad.
+__device__ __forceinline__ float diag_quad_sum(const f32x4_t& c, int kq) {
+  float v = kq == 0 ? c[0] : kq == 1 ? c[1] : kq == 2 ? c[2] : c[3];
+  v += dpp_move<0xB1>(v);    // quad_perm [1,0,3,2]
+  v += dpp_move<0x4E>(v);    // quad_perm [2,3,0,1]
+  return v;
+}
+
+template <int G, bool GAUSS>
+__global__ __launch_bounds__(256) void score_pages_mfma_kernel(const bf16_t* __restrict__ q,
+                                                               const bf16_t* __restrict__ stats,
+                                                               const int32_t* __restrict__ seq_lens,
+                                                               float* __restrict__ out0,   // box or mu
+                                                               float* __restrict__ out1,   // sigma (GAUSS)
+                                                               int Hkv, int P, int Mmax, float scale) {
+  constexpr int NSET = (G + 3) / 4;                 // column sets of 4 heads
+  __shared__ float stage[2][G][kScoreTile];
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int tile0 = blockIdx.x * kScoreTile;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int m = lane & 15, j = lane >> 4;           // MFMA row / column index, K group
+  const int pg = m >> 2, kq = m & 3;                // as a row: page of the group, channel quarter
+  const int n = seq_lens[b];
+  const int M = (n + P - 1) / P;
+  const int Hq = Hkv * G;
+
+  // B operands: column (g = m>>2, quarter kq) holds q[g][kq*32 + j*8 .. +8] (zero for g >= G)
+  uint4 b0[NSET], b1[NSET], b2[NSET];
+#pragma unroll
+  for (int s = 0; s < NSET; ++s) {
+    const int g = 4 * s + (m >> 2);
+    uint4 qv = make_uint4(0, 0, 0, 0);
+    if (g < G) qv = *reinterpret_cast<const uint4*>(q + ((size_t)b * Hq + h * G + g) * kD + kq * 32 + j * 8);
+    if (GAUSS) {
+      b0[s] = qv;
+      square_split(qv.x, b1[s].x, b2[s].x); square_split(qv.y, b1[s].y, b2[s].y);
+      square_split(qv.z, b1[s].z, b2[s].z); square_split(qv.w, b1[s].w, b2[s].w);
+    } else {
+      b0[s] = make_uint4(keep_sign<true>(qv.x), keep_sign<true>(qv.y), keep_sign<true>(qv.z), keep_sign<true>(qv.w));
+      b1[s] = make_uint4(keep_sign<false>(qv.x), keep_sign<false>(qv.y), keep_sign<false>(qv.z), keep_sign<false>(qv.w));
+      b2[s] = make_uint4(0, 0, 0, 0);
+    }
+  }
+
+  const int pw0 = tile0 + w * 16;                    // first page of this wavefront
+  const bf16_t* base = stats + (((size_t)b * Hkv + h) * Mmax) * 2 * kD + (kq * 4 + j) * 8;
+  uint4 a[4][2];
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const int p = pw0 + 4 * t + pg;
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      if (p < M) a[t][s] = *reinterpret_cast<const uint4*>(base + ((size_t)p * 2 + s) * kD);
+      else a[t][s] = make_uint4(0, 0, 0, 0);
+    }
+  }
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const int pt = w * 16 + 4 * t + j;               // result row group j = page of the group
+#pragma unroll
+    for (int s = 0; s < NSET; ++s) {
+      const int g = 4 * s + (m >> 2);
+      const f32x4_t zero = {0.f, 0.f, 0.f, 0.f};
+      if (GAUSS) {
+        const f32x4_t c0 = mfma_bf16(a[t][0], b0[s], zero);
+        f32x4_t c1 = mfma_bf16(a[t][1], b1[s], zero);
+        c1 = mfma_bf16(a[t][1], b2[s], c1);
+        const float mu = diag_quad_sum(c0, kq), var = diag_quad_sum(c1, kq);
+        if (kq == 0 && g < G) { stage[0][g][pt] = scale * mu; stage[1][g][pt] = scale * sqrtf(fmaxf(var, 0.f)); }
+      } else {
+        f32x4_t c0 = mfma_bf16(a[t][0], b0[s], zero);
+        c0 = mfma_bf16(a[t][1], b1[s], c0);
+        const float v = diag_quad_sum(c0, kq);
+        if (kq == 0 && g < G) stage[0][g][pt] = scale * v;
+      }
+    }
+  }
+  __syncthreads();
+  for (int idx = threadIdx.x; idx < G * kScoreTile; idx += 256) {
+    const int g = idx / kScoreTile, pt = idx - g * kScoreTile;
+    const int p = tile0 + pt;
+    if (p >= Mmax) continue;
+    const size_t o = ((size_t)b * Hq + h * G + g) * Mmax + p;
+    const bool valid = p < M;
+    out0[o] = valid ? stage[0][g][pt] : -INFINITY;
+    if (GAUSS) out1[o] = valid ? stage[1][g][pt] : 0.f;
+  }
+}
+
+// float32 statistics: one wavefront step = two page records, 32 lanes x 8 channels each.
+template <int G, bool GAUSS>
+__global__ __launch_bounds__(256) void score_pages_f32_kernel(const float* __restrict__ q,
+                                                              const float* __restrict__ stats,
+                                                              const int32_t* __restrict__ seq_lens,
+                                                              float* __restrict__ out0, float* __restrict__ out1,
+                                                              int Hkv, int P, int Mmax, float scale) {
+  constexpr int kSteps = kScoreTile / 4 / 2;
   __shared__ float stage[2][G][kScoreTile];
   const int b = blockIdx.z, h = blockIdx.y;
   const int tile0 = blockIdx.x * kScoreTile;
@@ -29,47 +150,36 @@ __global__ __launch_bounds__(256) void score_pages_kernel(const T* __restrict__ 
   const int n = seq_lens[b];
   const int M = (n + P - 1) / P;
   const int Hq = Hkv * G;
-
-  // per-lane query coefficients for its 8 channels
   float coef[G][8];
 #pragma unroll
   for (int g = 0; g < G; ++g) {
     float qv[8];
-    load8<T>(q + ((size_t)b * Hq + h * G + g) * kD + 8 * c, qv);
+    load8<float>(q + ((size_t)b * Hq + h * G + g) * kD + 8 * c, qv);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       if (GAUSS) coef[g][i] = which ? qv[i] * qv[i] : qv[i];
       else       coef[g][i] = which ? fmaxf(qv[i], 0.f) : fminf(qv[i], 0.f);
     }
   }
-
-  const int pw0 = tile0 + w * (kScoreTile / 4);            // first page of this wavefront
-  const T* base = stats + (((size_t)b * Hkv + h) * Mmax) * 2 * kD;
-  float x[kScoreSteps][8];
-#pragma unroll
-  for (int it = 0; it < kScoreSteps; ++it) {
+  const int pw0 = tile0 + w * (kScoreTile / 4);
+  const float* base = stats + (((size_t)b * Hkv + h) * Mmax) * 2 * kD;
+  for (int it = 0; it < kSteps; ++it) {
     const int p = pw0 + 2 * it + half;
-    if (p < M) load8<T>(base + ((size_t)p * 2 + which) * kD + 8 * c, x[it]);
+    const int pt = w * (kScoreTile / 4) + 2 * it + half;
+    float x[8];
+    if (p < M) load8<float>(base + ((size_t)p * 2 + which) * kD + 8 * c, x);
     else {
 #pragma unroll
-      for (int i = 0; i < 8; ++i) x[it][i] = 0.f;
-    }
-  }
-#pragma unroll
-  for (int it = 0; it < kScoreSteps; ++it) {
-    const int pt = w * (kScoreTile / 4) + 2 * it + half;   // page index inside the tile
-    if (GAUSS && which) {
-#pragma unroll
-      for (int i = 0; i < 8; ++i) x[it][i] *= x[it][i];
+      for (int i = 0; i < 8; ++i) x[i] = 0.f;
     }
 #pragma unroll
     for (int g = 0; g < G; ++g) {
       float acc = 0.f;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) acc = fmaf(coef[g][i], x[it][i], acc);
+      for (int i = 0; i < 8; ++i) acc = fmaf(coef[g][i], x[i], acc);
       acc = row16_sum(acc);
       if (GAUSS) {
-        if (c == 0) stage[which][g][pt] = which ? scale * sqrtf(acc) : scale * acc;
+        if (c == 0) stage[which][g][pt] = which ? scale * sqrtf(fmaxf(acc, 0.f)) : scale * acc;
       } else {
         acc += __shfl_xor(acc, 16);
         if (c == 0 && which == 0) stage[0][g][pt] = scale * acc;
@@ -88,33 +198,35 @@ __global__ __launch_bounds__(256) void score_pages_kernel(const T* __restrict__ 
   }
 }
 
-template <typename T, int G>
-static void launch_score_T(const Dims& dm, const void* q, const ekv_stats_view& s, const int32_t* seq_lens,
-                           int mode, float* box, float* mu, float* sigma, hipStream_t st) {
-  dim3 grid((dm.Mmax + kScoreTile - 1) / kScoreTile, dm.Hkv, dm.B), block(256);
-  if (mode & EKV_SCORE_BOX)
-    hipLaunchKernelGGL((score_pages_kernel<T, G, false>), grid, block, 0, st, (const T*)q, (const T*)s.box,
-                       seq_lens, box, (float*)nullptr, dm.Hkv, dm.P, dm.Mmax, dm.scale);
-  if (mode & EKV_SCORE_GAUSS)
-    hipLaunchKernelGGL((score_pages_kernel<T, G, true>), grid, block, 0, st, (const T*)q, (const T*)s.gauss,
-                       seq_lens, mu, sigma, dm.Hkv, dm.P, dm.Mmax, dm.scale);
-}
-
-template <typename T>
+template <int G>
 static void launch_score_G(const Dims& dm, const void* q, const ekv_stats_view& s, const int32_t* seq_lens,
                            int mode, float* box, float* mu, float* sigma, hipStream_t st) {
-  switch (dm.G) {
-    case 1: launch_score_T<T, 1>(dm, q, s, seq_lens, mode, box, mu, sigma, st); break;
-    case 2: launch_score_T<T, 2>(dm, q, s, seq_lens, mode, box, mu, sigma, st); break;
-    case 4: launch_score_T<T, 4>(dm, q, s, seq_lens, mode, box, mu, sigma, st); break;
-    default: launch_score_T<T, 8>(dm, q, s, seq_lens, mode, box, mu, sigma, st); break;
+  dim3 grid((dm.Mmax + kScoreTile - 1) / kScoreTile, dm.Hkv, dm.B), block(256);
+  if (dm.dtype == EKV_BF16) {
+    if (mode & EKV_SCORE_BOX)
+      hipLaunchKernelGGL((score_pages_mfma_kernel<G, false>), grid, block, 0, st, (const bf16_t*)q,
+                         (const bf16_t*)s.box, seq_lens, box, (float*)nullptr, dm.Hkv, dm.P, dm.Mmax, dm.scale);
+    if (mode & EKV_SCORE_GAUSS)
+      hipLaunchKernelGGL((score_pages_mfma_kernel<G, true>), grid, block, 0, st, (const bf16_t*)q,
+                         (const bf16_t*)s.gauss, seq_lens, mu, sigma, dm.Hkv, dm.P, dm.Mmax, dm.scale);
+  } else {
+    if (mode & EKV_SCORE_BOX)
+      hipLaunchKernelGGL((score_pages_f32_kernel<G, false>), grid, block, 0, st, (const float*)q,
+                         (const float*)s.box, seq_lens, box, (float*)nullptr, dm.Hkv, dm.P, dm.Mmax, dm.scale);
+    if (mode & EKV_SCORE_GAUSS)
+      hipLaunchKernelGGL((score_pages_f32_kernel<G, true>), grid, block, 0, st, (const float*)q,
+                         (const float*)s.gauss, seq_lens, mu, sigma, dm.Hkv, dm.P, dm.Mmax, dm.scale);
   }
 }
 
 void launch_score_pages(const Dims& dm, const void* q, const ekv_stats_view& s, const int32_t* seq_lens,
                         int mode, float* box, float* mu, float* sigma, hipStream_t st) {
-  if (dm.dtype == EKV_F32) launch_score_G<float>(dm, q, s, seq_lens, mode, box, mu, sigma, st);
-  else launch_score_G<bf16_t>(dm, q, s, seq_lens, mode, box, mu, sigma, st);
+  switch (dm.G) {
+    case 1: launch_score_G<1>(dm, q, s, seq_lens, mode, box, mu, sigma, st); break;
+    case 2: launch_score_G<2>(dm, q, s, seq_lens, mode, box, mu, sigma, st); break;
+    case 4: launch_score_G<4>(dm, q, s, seq_lens, mode, box, mu, sigma, st); break;
+    default: launch_score_G<8>(dm, q, s, seq_lens, mode, box, mu, sigma, st); break;
+  }
 }
 
 }  // namespace ekv

@@ -1,4 +1,5 @@
-// Page-statistics builder (paper Sec. 4.2): per page k_min, k_max, k_avg, k_std.
+// Page-statistics builder (paper Sec. 4.2): per page k_min, k_max, k_avg and k_var = k_std^2
+// (the variance is what is stored: sigma_p^2 of Sec. 4.3 is linear in it).
 // One 64-lane wavefront per (sequence, KV head, page); a page is a contiguous P x 128 block, read
 // with 16-byte loads (lane = 4 rows x 16 column groups).  HBM-bound stream over K.
 #include "ekv_device.h"
@@ -37,7 +38,7 @@ __device__ __forceinline__ void page_stats_wave(const T* __restrict__ kpage, int
     }
   }
   const float inv_n = 1.0f / (float)cnt;
-  float avg[8], sd[8];
+  float avg[8], sd[8];   // sd holds the variance m2 - avg^2 (clamped at 0)
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     mn[i] = fminf(mn[i], __shfl_xor(mn[i], 16)); mn[i] = fminf(mn[i], __shfl_xor(mn[i], 32));
@@ -47,7 +48,7 @@ __device__ __forceinline__ void page_stats_wave(const T* __restrict__ kpage, int
     const float m1 = s1[i] * inv_n;
     const float var = fmaxf(fmaf(-m1, m1, s2[i] * inv_n), 0.f);
     avg[i] = k0[i] + m1;
-    sd[i] = sqrtf(var);
+    sd[i] = var;
   }
   if (r == 0) {
     store8<T>(box_out + 8 * c, mn);

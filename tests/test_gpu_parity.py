@@ -1,13 +1,13 @@
 """GPU parity: every C-ABI entry point against the float64 oracle on the same seeded inputs.
 
 Acceptance rules (written out here; derivations in the design doc):
-  * page statistics: min/max bit-exact; avg/std within 1 ulp of the storage dtype (bf16) or 2e-6
-    relative to the page's value range (f32);
+  * page statistics: min/max bit-exact; mean and variance within 1 ulp of the storage dtype (bf16) or
+    2e-6 relative to the page's value range (f32);
   * page scores: |gpu - oracle| <= 1e-5 * max(1, |score|);
   * selected page sets: identical, except pages whose score lies within 1e-5*max(1,|cut|) of the cut;
   * tau, tau_hat: |gpu - oracle| <= 4e-6 * max(1, |tau|);
-  * supports: identical token lists (tokens with |z - tau| below 2e-6 would be exempt; the seeded
-    inputs contain none, which the tests assert);
+  * supports: identical token lists; a token with |z - tau| <= 2e-6*max(1,|tau|) (float32 resolution
+    of the score) may fall on either side -- the float32-cache inputs contain none (asserted);
   * outputs: ||gpu - oracle||_2 / ||oracle||_2 <= 1e-5 (f32 cache) or 2e-3 (bf16 cache);
   * dropped mass delta: 1e-4 absolute.
 """
@@ -72,13 +72,14 @@ def test_stats_build(w):
             M = len(cnt)
             np.testing.assert_array_equal(box[b, h, :M, 0], kmin)
             np.testing.assert_array_equal(box[b, h, :M, 1], kmax)
+            kvar = kstd ** 2                               # the variance is what the library stores
             if w.kv_dtype == "bf16":
-                tol_avg = storage_ulp(kavg, "bf16"); tol_std = storage_ulp(kstd, "bf16")
+                tol_avg = storage_ulp(kavg, "bf16"); tol_var = storage_ulp(kvar, "bf16")
             else:
                 rng_ = (kmax - kmin) + 1e-30
-                tol_avg = 2e-6 * np.maximum(np.abs(kavg), rng_); tol_std = 2e-6 * rng_
+                tol_avg = 2e-6 * np.maximum(np.abs(kavg), rng_); tol_var = 4e-6 * rng_ ** 2
             assert np.all(np.abs(gauss[b, h, :M, 0] - kavg) <= tol_avg)
-            assert np.all(np.abs(gauss[b, h, :M, 1] - kstd) <= tol_std)
+            assert np.all(np.abs(gauss[b, h, :M, 1] - kvar) <= tol_var)
 
 
 @pytest.mark.parametrize("w", [W1R, W2], ids=["C1-ragged", "C2-8k"])
@@ -123,12 +124,13 @@ def upload_oracle_stats(st, w, inp):
     for b in range(w.batch):
         for h in range(w.n_kv_heads):
             kmin, kmax, kavg, kstd, cnt = oracle_stats(inp, w, b, h)
-            kavg = orc.round_to_storage(kavg, w.kv_dtype); kstd = orc.round_to_storage(kstd, w.kv_dtype)
+            kavg, kstd = orc.stored_gauss_stats(kavg, kstd, w.kv_dtype)
+            kvar = orc.round_to_storage(kstd ** 2, w.kv_dtype)     # exactly the stored variance again
             M = len(cnt)
             st.box_stats[b, h, :M, 0] = torch.from_numpy(kmin).to(dt).to(st.box.device)
             st.box_stats[b, h, :M, 1] = torch.from_numpy(kmax).to(dt).to(st.box.device)
             st.gauss_stats[b, h, :M, 0] = torch.from_numpy(kavg).to(dt).to(st.box.device)
-            st.gauss_stats[b, h, :M, 1] = torch.from_numpy(kstd).to(dt).to(st.box.device)
+            st.gauss_stats[b, h, :M, 1] = torch.from_numpy(kvar).to(dt).to(st.box.device)
             stats[(b, h)] = (kmin, kmax, kavg, kstd, cnt)
     return stats
 
@@ -250,11 +252,17 @@ def test_select_gauss_empty_and_overflow():
 def check_decode_unit(w, got_out, got_tau, got_supp, got_tokens, ref):
     tol = OUT_TOL[w.kv_dtype]
     assert abs(got_tau - ref["tau"]) <= 4e-6 * max(1.0, abs(ref["tau"])), (got_tau, ref["tau"])
+    # tokens whose z sits within float32 resolution of tau may fall on either side; everything else
+    # must match exactly.  On the float32-cache workloads the seeded inputs have no such token.
     z = (w.alpha - 1.0) * ref["s"]
-    assert np.min(np.abs(z - ref["tau"])) > 2e-6, "seeded input has a token on the support boundary"
-    assert got_supp == len(ref["support"])
+    boundary = set(ref["tokens"][np.abs(z - ref["tau"]) <= 2e-6 * max(1.0, abs(ref["tau"]))].tolist())
+    if w.kv_dtype == "f32":
+        assert not boundary, "seeded float32 input has a token on the support boundary"
+    assert abs(got_supp - len(ref["support"])) <= len(boundary)
     if got_tokens is not None:
-        np.testing.assert_array_equal(got_tokens[: got_supp], ref["support"])
+        diff = set(got_tokens[:got_supp].tolist()).symmetric_difference(ref["support"].tolist())
+        assert diff.issubset(boundary), sorted(diff)
+        assert np.all(np.diff(got_tokens[:got_supp]) > 0)
     assert rel_err(got_out, ref["o"]) <= tol, rel_err(got_out, ref["o"])
 
 
@@ -449,7 +457,7 @@ def test_tiny_sequences_and_all_pages_selected():
 
 def test_candidate_list_larger_than_lds_uses_the_streaming_path():
     """Nearly flat scores: every token is within 1 of the maximum, so 8192 candidates exceed the LDS
-    list (6144) and the solver must stream the score row instead."""
+    list (4096) and the solver must stream the score row instead."""
     w = synth.C1.scaled(name="C1-flat", context=8192, n_planted=0, scale=0.02 / math.sqrt(128.0), n_q_heads=2,
                         n_kv_heads=2)
     inp = synth.make_inputs(w, 4242, device="cpu")
@@ -460,7 +468,8 @@ def test_candidate_list_larger_than_lds_uses_the_streaming_path():
     for hq in range(2):
         q, K, V = unit_kv(inp, w, 0, hq)
         ref = orc.entmax_attention(q, K, V, w.alpha, w.score_scale)
-        assert len(ref["support"]) > 6144
+        z = (w.alpha - 1.0) * ref["s"]
+        assert np.sum(z > z.max() - 1.0) > 4096 and len(ref["support"]) > 4096
         assert abs(float(tau_f[0, hq]) - ref["tau"]) <= 4e-6 * max(1.0, abs(ref["tau"]))
         assert abs(int(supp_f[0, hq]) - len(ref["support"])) <= 2
         assert rel_err(out_f[0, hq].cpu().numpy(), ref["o"]) <= 2e-5
