@@ -179,10 +179,15 @@ ekv_status ekv_select_gauss(const ekv_config* cfg, const float* mu, const float*
     return EKV_ERR_INVALID_ARG;
   if (!(q_page > 0.f && q_page < 1.f) || !(margin >= 0.f) || !std::isfinite(margin)) return EKV_ERR_INVALID_ARG;
   if (workspace == nullptr || workspace_bytes < select_gauss_ws_bytes(dm)) return EKV_ERR_WORKSPACE;
-  float zq[65];
-  zq[0] = 0.f;
-  const double lq = std::log((double)q_page);
-  for (int c = 1; c <= 64; ++c) zq[c] = (float)phi_inv(lq / (double)c);   // PhiInv(q_page^(1/c)), Eq. 11
+  // PhiInv(q_page^(1/c)), Eq. 11, for every possible page fill c; cached per thread for the last q_page
+  static thread_local float zq[65];
+  static thread_local float zq_for = -1.f;
+  if (zq_for != q_page) {
+    zq[0] = 0.f;
+    const double lq = std::log((double)q_page);
+    for (int c = 1; c <= 64; ++c) zq[c] = (float)phi_inv(lq / (double)c);
+    zq_for = q_page;
+  }
   launch_select_gauss(dm, mu, sigma, seq_lens, zq, margin, tau_hat, page_idx, n_sel, overflow, workspace,
                       (hipStream_t)stream);
   return finish((hipStream_t)stream);

@@ -217,6 +217,8 @@ struct SolveShared {
   float red[2][kSolveWaves][3];
   int wcount[2][kSolveWaves];
   float red1[kSolveWaves];
+  int hist[64];                   // candidates per 1/64 slice of [thr, zmax] (threshold tightening)
+  int level;
 };
 
 // Candidate source: the compacted LDS list, or (when it does not fit) the score row itself.
@@ -252,14 +254,16 @@ __device__ __forceinline__ void eval_mass(const Src& src, float tau, float beta,
   F = Fs; D = beta * Ds; cnt = Cs;
 }
 
-// Root of sum (u - tau)_+^beta = 1 for u <= 0 with max u = 0: tau in [-1, 0).
+// Root of sum (u - tau)_+^beta = 1 for u <= 0 with max u = 0: tau in [lo_init, 0), where lo_init >= -1
+// is any point with mass >= 1.
 // Safeguarded iteration inside a bracket [lo,hi], F(lo) >= 1 > F(hi).  From a left point the step is
 // the exact root for the current support when beta is 1 or 2 (closed forms), Newton otherwise; from a
 // right point a Newton step (F is convex, so it lands left of the root).  For beta in {1,2} the root is
 // accepted as exact once a closed-form step leaves the support count unchanged.
 template <typename Src>
-__device__ __forceinline__ float solve_tau(const Src& src, float beta, int ibeta, SolveShared& sh, int& supp) {
-  float lo = -1.0f - 4e-6f, hi = 0.f;
+__device__ __forceinline__ float solve_tau(const Src& src, float lo_init, float beta, int ibeta, SolveShared& sh,
+                                           int& supp) {
+  float lo = lo_init, hi = 0.f;
   float tau = lo;
   int pending_cnt = -1;
   int parity = 0, cnt = 0;
@@ -373,49 +377,85 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
     if (tid == 0) { A.tau_out[bh] = INFINITY; A.supp_out[bh] = 0; }
     return;
   }
-  const float thr = zmax - 1.0f - 4e-6f * fmaxf(1.f, fabsf(zmax));
-
-  // ---- ordered compaction of {z > thr} into LDS, in rounds of kRoundTokens candidates.  Wavefront w
-  // of a round owns 64*kRoundLoads consecutive positions, so (round, w, load, lane) order is candidate
-  // order.  A 64-position load whose chunk maximum is <= thr is not issued.
+  // Only z > zmax - 1 can be in the support.  That set is compacted IN ORDER into LDS in rounds of
+  // kRoundTokens candidates: wavefront w of a round owns 64*kRoundLoads consecutive positions, so
+  // (round, w, load, lane) order is candidate order.  A 64-position load whose chunk maximum is <= thr is
+  // not issued.  The same pass histograms the candidates over 64 slices of [thr, zmax]; counts alone give
+  // a lower bound of the mass at every slice boundary (an entry of slice j lies at least j-i slices above
+  // boundary i), hence a tighter valid threshold: it becomes the starting point of the solve, and, if the
+  // candidates did not fit in LDS, the threshold of one more compaction pass.
+  float thr = zmax - 1.0f - 4e-6f * fmaxf(1.f, fabsf(zmax));
+  float lo_u = thr - zmax;
   const bool can_skip = (chunk_tokens & 63) == 0;
   int n_list = 0, parity = 0;
   bool in_lds = true;
-  for (int round0 = 0; round0 < n_cand; round0 += kRoundTokens) {
-    const int seg = round0 + w * 64 * kRoundLoads;
-    float v[kRoundLoads];
-#pragma unroll
-    for (int i = 0; i < kRoundLoads; ++i) {
-      const int pos0 = seg + i * 64;
-      v[i] = -INFINITY;
-      if (pos0 < n_cand && (!can_skip || pm[pos0 / chunk_tokens] > thr)) {
-        const int pos = pos0 + lane;
-        if (pos < n_cand) v[i] = zr[pos];
-      }
-    }
-    int c = 0;
-#pragma unroll
-    for (int i = 0; i < kRoundLoads; ++i) c += __popcll(__ballot(v[i] > thr));
-    if (lane == 0) sh.wcount[parity][w] = c;
+  for (int pass = 0; pass < 3; ++pass) {
+    const float width = zmax - thr, slice = width * (1.0f / 64.0f), inv_slice = 64.0f / width;
+    if (tid < 64) sh.hist[tid] = 0;
+    n_list = 0; in_lds = true;
     __syncthreads();
-    int off = n_list, tot = 0;
-    for (int i = 0; i < kSolveWaves; ++i) { const int ci = sh.wcount[parity][i]; if (i < w) off += ci; tot += ci; }
-    n_list += tot;
-    parity ^= 1;
-    if (n_list > kListCap) in_lds = false;
-    if (in_lds) {
+    for (int round0 = 0; round0 < n_cand; round0 += kRoundTokens) {
+      const int seg = round0 + w * 64 * kRoundLoads;
+      // The chunk maxima of the round are fetched first as one batch (clamped, unconditional), then the
+      // score loads of the chunks that can hold a candidate are issued back to back; nothing is consumed
+      // before all of them are in flight.
+      float pmv[kRoundLoads];
+#pragma unroll
+      for (int i = 0; i < kRoundLoads; ++i) pmv[i] = pm[min(seg + i * 64, n_cand - 1) / chunk_tokens];
+      float v[kRoundLoads];
+#pragma unroll
+      for (int i = 0; i < kRoundLoads; ++i) {
+        const int pos0 = seg + i * 64;
+        const float pmu = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(pmv[i])));
+        v[i] = -INFINITY;
+        if (pos0 < n_cand && (!can_skip || pmu > thr)) v[i] = zr[min(pos0 + lane, n_cand - 1)];
+      }
+#pragma unroll
+      for (int i = 0; i < kRoundLoads; ++i) v[i] = seg + i * 64 + lane < n_cand ? v[i] : -INFINITY;
+      int c = 0;
 #pragma unroll
       for (int i = 0; i < kRoundLoads; ++i) {
         const bool in = v[i] > thr;
-        const uint64_t mk = __ballot(in);
-        if (in) {
-          const int o = off + __popcll(mk & lt);
-          sh.list_u[o] = v[i] - zmax;
-          sh.list_pos[o] = seg + i * 64 + lane;
+        c += __popcll(__ballot(in));
+        if (in) atomicAdd(&sh.hist[min(63, (int)((v[i] - thr) * inv_slice))], 1);
+      }
+      if (lane == 0) sh.wcount[parity][w] = c;
+      __syncthreads();
+      int off = n_list, tot = 0;
+      for (int i = 0; i < kSolveWaves; ++i) { const int ci = sh.wcount[parity][i]; if (i < w) off += ci; tot += ci; }
+      n_list += tot;
+      parity ^= 1;
+      if (n_list > kListCap) in_lds = false;
+      if (in_lds) {
+#pragma unroll
+        for (int i = 0; i < kRoundLoads; ++i) {
+          const bool in = v[i] > thr;
+          const uint64_t mk = __ballot(in);
+          if (in) {
+            const int o = off + __popcll(mk & lt);
+            sh.list_u[o] = v[i] - zmax;
+            sh.list_pos[o] = seg + i * 64 + lane;
+          }
+          off += __popcll(mk);
         }
-        off += __popcll(mk);
       }
     }
+    __syncthreads();
+    // highest slice boundary whose counted lower bound of the mass is still >= 1
+    if (tid < 64) {
+      float lb = 0.f;
+      for (int jj = tid + 1; jj < 64; ++jj)
+        lb += (float)sh.hist[jj] * pow_beta(((float)(jj - tid) - 0.02f) * slice, beta, ibeta);
+      const uint64_t okm = __ballot(lb >= 1.0001f);
+      if (tid == 0) sh.level = okm ? 63 - __clzll(okm) : 0;
+    }
+    __syncthreads();
+    const int level = sh.level;
+    const float thr2 = thr + (float)level * slice;
+    if (in_lds) { lo_u = fminf(thr2 - zmax, -1e-7f); break; }
+    if (level == 0) break;                       // no tighter threshold from counts: stream the row
+    thr = thr2;
+    lo_u = thr - zmax;
   }
   __syncthreads();
 
@@ -425,11 +465,11 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
     uint32_t rowreg[kListCap / kSolveThreads];
 #pragma unroll
     for (int k = 0; k < kListCap / kSolveThreads; ++k) {
-      const int e = tid + k * kSolveThreads;
-      rowreg[k] = e < n_list ? v_row_of<DENSE>(A, b, bh, hkv, sh.list_pos[e]) : 0u;
+      const int e = min(tid + k * kSolveThreads, n_list - 1);      // clamped: loads stay unconditional
+      rowreg[k] = v_row_of<DENSE>(A, b, bh, hkv, sh.list_pos[e]);
     }
     const ListSrc ls{sh.list_u, sh.list_pos, n_list};
-    tau_u = solve_tau(ls, beta, ibeta, sh, supp);
+    tau_u = solve_tau(ls, lo_u, beta, ibeta, sh, supp);
 #pragma unroll
     for (int k = 0; k < kListCap / kSolveThreads; ++k) {
       const int e = tid + k * kSolveThreads;
@@ -480,7 +520,7 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
   } else {
     // the candidates do not fit in LDS: stream the score row for every evaluation
     const RowSrc rsrc{zr, n_cand, zmax};
-    tau_u = solve_tau(rsrc, beta, ibeta, sh, supp);
+    tau_u = solve_tau(rsrc, lo_u, beta, ibeta, sh, supp);
     const int rs = tid >> 4, c = tid & 15;
     float acc[8];
 #pragma unroll

@@ -47,31 +47,54 @@ __device__ __forceinline__ int block_excl_scan(int v, int* buf, int& total) {
 }
 
 // Keys of one (b,h) row.  ITEMS > 0: held in registers (M <= 1024*ITEMS); ITEMS == 0: recomputed from
-// memory on every access (any M).  `fn(p)` gives the key of page p.
+// memory on every access (any M).  `fn(p)` gives the key of page p.  Slots past M hold the value 0.
+// After rebase(kmin) every key is stored relative to kmin (so only one register array is live).
 template <int ITEMS, typename KeyFn>
 struct KeySet {
   KeyFn fn;
   int M, items, page0;                      // page0 = first page of this lane
+  uint32_t base;                            // subtracted from every key
   uint32_t reg[ITEMS ? ITEMS : 1];
-  __device__ __forceinline__ KeySet(KeyFn f, int M_) : fn(f), M(M_) {
+  __device__ __forceinline__ KeySet(KeyFn f, int M_) : fn(f), M(M_), base(0u) {
     items = ITEMS ? ITEMS : (M + kSelThreads - 1) / kSelThreads;
     page0 = (threadIdx.x >> 6) * 64 * items + (threadIdx.x & 63);
     if (ITEMS) {
+      // unconditional loads from clamped pages (a load inside a divergent branch is waited for at
+      // once, which would serialise all ITEMS loads), masked afterwards
 #pragma unroll
-      for (int i = 0; i < (ITEMS ? ITEMS : 1); ++i) reg[i] = valid(i) ? fn(page(i)) : 0u;
+      for (int i = 0; i < (ITEMS ? ITEMS : 1); ++i) reg[i] = fn(min(page(i), M - 1));
+#pragma unroll
+      for (int i = 0; i < (ITEMS ? ITEMS : 1); ++i) reg[i] = page(i) < M ? reg[i] : 0u;
     }
   }
   __device__ __forceinline__ int page(int i) const { return page0 + i * 64; }
-  __device__ __forceinline__ bool valid(int i) const { return page(i) < M; }
-  __device__ __forceinline__ uint32_t key(int i) const { return ITEMS ? reg[i] : fn(page(i)); }
+  // before rebase(): slots past M hold 0 and no real key is 0 (checking the register instead of the page
+  // index keeps the 128 page indices from being held in registers)
+  __device__ __forceinline__ bool valid(int i) const { return ITEMS ? reg[i] != 0u : page(i) < M; }
+  // key of slot i relative to `base`; slots past M (and keys below base) give 0
+  __device__ __forceinline__ uint32_t key(int i) const {
+    if (ITEMS) return reg[i];
+    const uint32_t k0 = fn(min(page(i), M - 1));
+    const uint32_t k = page(i) < M ? k0 : 0u;
+    return max(k, base) - base;
+  }
+  __device__ __forceinline__ void rebase(uint32_t kmin) {
+    base = kmin;
+    if (ITEMS) {
+#pragma unroll
+      for (int i = 0; i < (ITEMS ? ITEMS : 1); ++i) reg[i] = max(reg[i], kmin) - kmin;
+    }
+  }
 };
 
 // Finds the k-th largest key (1 <= k <= M) by radix selection on (key - min key), 11 bits per pass over
-// only as many bits as the key range needs.  Returns kmin (the smallest key), vT = (k-th largest key)
-// - kmin, and k_eq = how many elements equal to it belong to the top k.
+// only as many bits as the key range needs.  Rebases the key set to the smallest valid key and returns
+// vT = the k-th largest rebased key and k_eq = how many elements equal to it belong to the top k.
+// Slots past M count as copies of the smallest key with the highest page indices, which never changes
+// the answer for k <= M.
 template <int ITEMS, typename KeyFn>
-__device__ __forceinline__ void radix_select_kth(const KeySet<ITEMS, KeyFn>& ks, int k, SelectShared& sh,
-                                                 uint32_t& kmin_out, uint32_t& vT_out, int& k_eq_out) {
+__device__ __forceinline__ void radix_select_kth(KeySet<ITEMS, KeyFn>& ks, int k, SelectShared& sh,
+                                                 uint32_t& vT_out, int& k_eq_out) {
   const int tid = threadIdx.x;
   uint32_t lo = 0xffffffffu, hi = 0u;
 #pragma unroll
@@ -90,9 +113,9 @@ __device__ __forceinline__ void radix_select_kth(const KeySet<ITEMS, KeyFn>& ks,
   if ((tid & 63) == 0) sh.red_u[tid >> 6] = hi;
   __syncthreads();
   for (int i = 0; i < kSelWaves; ++i) hi = max(hi, sh.red_u[i]);
-  const uint32_t kmin = lo;
   const uint32_t range = hi - lo;
-  int shift = range ? 32 - __clz(range) : 0;     // significant bits of (key - kmin)
+  ks.rebase(lo);
+  int shift = range ? 32 - __clz(range) : 0;     // significant bits of the rebased keys
 
   uint32_t prefix = 0;       // high bits of the answer fixed so far: (v >> shift) == prefix
   int k_rem = k;             // rank of the answer among the elements sharing that prefix
@@ -100,15 +123,15 @@ __device__ __forceinline__ void radix_select_kth(const KeySet<ITEMS, KeyFn>& ks,
     const int dbits = min(kDigitBits, shift);
     shift -= dbits;
     const uint32_t dmask = (1u << dbits) - 1u;
+    const int up = shift + dbits;                  // bits above the current digit: (v >> up) must equal prefix
+    const bool first = up >= 32;                   // first pass of a full 32-bit range: every key matches
     __syncthreads();
     for (int i = tid; i < kBins; i += kSelThreads) sh.hist[i] = 0;
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < (ITEMS ? ITEMS : ks.items); ++i) {
-      if (ks.valid(i)) {
-        const uint32_t v = ks.key(i) - kmin;
-        if ((uint32_t)((uint64_t)v >> (shift + dbits)) == prefix) atomicAdd(&sh.hist[(v >> shift) & dmask], 1u);
-      }
+      const uint32_t v = ks.key(i);
+      if (first || (v >> up) == prefix) atomicAdd(&sh.hist[(v >> shift) & dmask], 1u);
     }
     __syncthreads();
     // thread t owns digits (kBins-1-2t) and (kBins-2-2t): scan from the top digit downwards
@@ -122,24 +145,25 @@ __device__ __forceinline__ void radix_select_kth(const KeySet<ITEMS, KeyFn>& ks,
     prefix = (prefix << dbits) | sh.digit;
     k_rem -= (int)sh.above;
   }
-  kmin_out = kmin; vT_out = prefix; k_eq_out = k_rem;
+  vT_out = prefix; k_eq_out = k_rem;
 }
 
-// Writes, in ascending page order, every page whose v = key - kmin exceeds vT, plus the first k_eq
-// pages (by index) with v == vT.
+// Writes, in ascending page order, every page whose (rebased) key exceeds vT, plus the first k_eq
+// pages (by index) whose key equals vT.  Slots past M are never written.
 template <int ITEMS, typename KeyFn>
-__device__ __forceinline__ void compact_ordered(const KeySet<ITEMS, KeyFn>& ks, uint32_t kmin, uint32_t vT,
-                                                int k_eq, SelectShared& sh, int32_t* __restrict__ out) {
+__device__ __forceinline__ void compact_ordered(const KeySet<ITEMS, KeyFn>& ks, uint32_t vT, int k_eq,
+                                                SelectShared& sh, int32_t* __restrict__ out) {
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const uint64_t lt = (1ull << lane) - 1ull;
   int n_gt = 0, n_eq = 0;
 #pragma unroll
   for (int i = 0; i < (ITEMS ? ITEMS : ks.items); ++i) {
-    const bool ok = ks.valid(i);
-    const uint32_t v = ok ? ks.key(i) - kmin : 0u;
-    n_gt += __popcll(__ballot(ok && v > vT));
-    n_eq += __popcll(__ballot(ok && v == vT));
+    const uint32_t v = ks.key(i);       // per-lane counts (no ballots here: they would all be kept
+    n_gt += v > vT;                     // alive for the second loop and exhaust the scalar registers)
+    n_eq += v == vT;
   }
+  n_gt = wave_sum_i(n_gt);
+  n_eq = wave_sum_i(n_eq);
   __syncthreads();
   if (lane == 0) { sh.wave_gt[w] = n_gt; sh.wave_eq[w] = n_eq; }
   __syncthreads();
@@ -149,16 +173,16 @@ __device__ __forceinline__ void compact_ordered(const KeySet<ITEMS, KeyFn>& ks, 
   int o_run = gt_before + min(eq_before, k_eq);
 #pragma unroll
   for (int i = 0; i < (ITEMS ? ITEMS : ks.items); ++i) {
-    const bool ok = ks.valid(i);
-    const uint32_t v = ok ? ks.key(i) - kmin : 0u;
-    const bool eq = ok && v == vT;
+    const uint32_t v = ks.key(i);
+    const bool eq = v == vT;
     const uint64_t m_eq = __ballot(eq);
-    const bool take = (ok && v > vT) || (eq && eq_run + __popcll(m_eq & lt) < k_eq);
+    const bool take = v > vT || (eq && eq_run + __popcll(m_eq & lt) < k_eq);
     const uint64_t m_take = __ballot(take);
     if (take) out[o_run + __popcll(m_take & lt)] = ks.page(i);
     eq_run += __popcll(m_eq);
     o_run += __popcll(m_take);
-  }
+    __builtin_amdgcn_sched_barrier(0);    // keep the iterations in order: hoisting every compare first
+  }                                       // needs two scalar register pairs per key
 }
 
 }  // namespace ekv

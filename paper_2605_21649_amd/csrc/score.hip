@@ -94,12 +94,9 @@ __global__ __launch_bounds__(256) void score_pages_mfma_kernel(const bf16_t* __r
   uint4 a[4][2];
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
-    const int p = pw0 + 4 * t + pg;
+    const int p = min(pw0 + 4 * t + pg, M - 1);     // clamped: pages past the end are masked on output
 #pragma unroll
-    for (int s = 0; s < 2; ++s) {
-      if (p < M) a[t][s] = *reinterpret_cast<const uint4*>(base + ((size_t)p * 2 + s) * kD);
-      else a[t][s] = make_uint4(0, 0, 0, 0);
-    }
+    for (int s = 0; s < 2; ++s) a[t][s] = *reinterpret_cast<const uint4*>(base + ((size_t)p * 2 + s) * kD);
   }
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
@@ -164,14 +161,10 @@ __global__ __launch_bounds__(256) void score_pages_f32_kernel(const float* __res
   const int pw0 = tile0 + w * (kScoreTile / 4);
   const float* base = stats + (((size_t)b * Hkv + h) * Mmax) * 2 * kD;
   for (int it = 0; it < kSteps; ++it) {
-    const int p = pw0 + 2 * it + half;
+    const int p = min(pw0 + 2 * it + half, M - 1);  // clamped: pages past the end are masked on output
     const int pt = w * (kScoreTile / 4) + 2 * it + half;
     float x[8];
-    if (p < M) load8<float>(base + ((size_t)p * 2 + which) * kD + 8 * c, x);
-    else {
-#pragma unroll
-      for (int i = 0; i < 8; ++i) x[i] = 0.f;
-    }
+    load8<float>(base + ((size_t)p * 2 + which) * kD + 8 * c, x);
 #pragma unroll
     for (int g = 0; g < G; ++g) {
       float acc = 0.f;

@@ -228,7 +228,7 @@ __global__ __launch_bounds__(kGaussEvalThreads) void gauss_eval_kernel(const flo
 struct ZqTable { float z[65]; };   // z[c] = PhiInv(q_page^(1/c)), c = 1..64
 
 template <int NB, int ITEMS>
-__global__ __launch_bounds__(kSelThreads) void gauss_select_kernel(
+__global__ __launch_bounds__(kSelThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void gauss_select_kernel(
     const float* __restrict__ mu, const float* __restrict__ sigma, const int32_t* __restrict__ seq_lens,
     GaussWs ws, ZqTable zq, float margin, float a, float* __restrict__ tau_hat, int32_t* __restrict__ page_idx,
     int32_t* __restrict__ n_sel, int32_t* __restrict__ overflow, int Hq, int P, int Mmax, int cap, int BH) {
@@ -260,24 +260,24 @@ __global__ __launch_bounds__(kSelThreads) void gauss_select_kernel(
   const float thr = tau - margin;
   const float z_full = zq.z[P], z_last = zq.z[cnt_last];
   auto keyfn = [=](int p) { return float_to_key(a * fmaf(sg_r[p], p == M - 1 ? z_last : z_full, mu_r[p])); };
-  const KeySet<ITEMS, decltype(keyfn)> ks(keyfn, M);
-  const uint32_t kthr = float_to_key(thr);
+  KeySet<ITEMS, decltype(keyfn)> ks(keyfn, M);
+  const uint32_t kthr = float_to_key(thr);      // > 0, so empty slots (key 0) never pass
   int c = 0;
 #pragma unroll
-  for (int i = 0; i < (ITEMS ? ITEMS : ks.items); ++i) c += ks.valid(i) && ks.key(i) > kthr;
+  for (int i = 0; i < (ITEMS ? ITEMS : ks.items); ++i) c += ks.key(i) > kthr;
   const int count = block_sum_i(c, sh.scan_buf);
   int32_t* out = page_idx + (size_t)bh * cap;
   int n_out, ovf = 0;
   if (count >= 1 && count <= cap) {
-    compact_ordered(ks, 0u, kthr, 0, sh, out);
+    compact_ordered(ks, kthr, 0, sh, out);
     n_out = count;
   } else {
     // nothing passed: the single best page; too many: the cap best pages (lower index on ties)
     const int k = count == 0 ? 1 : cap;
     ovf = count > cap;
-    uint32_t kmin, vT; int k_eq;
-    radix_select_kth(ks, k, sh, kmin, vT, k_eq);
-    compact_ordered(ks, kmin, vT, k_eq, sh, out);
+    uint32_t vT; int k_eq;
+    radix_select_kth(ks, k, sh, vT, k_eq);
+    compact_ordered(ks, vT, k_eq, sh, out);
     n_out = k;
   }
   if (tid == 0) { n_sel[bh] = n_out; overflow[bh] = ovf; }

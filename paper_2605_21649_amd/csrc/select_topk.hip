@@ -9,7 +9,7 @@
 namespace ekv {
 
 template <int ITEMS>
-__global__ __launch_bounds__(kSelThreads) void select_topk_kernel(const float* __restrict__ box,
+__global__ __launch_bounds__(kSelThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void select_topk_kernel(const float* __restrict__ box,
                                                                   const int32_t* __restrict__ seq_lens,
                                                                   int k_pages, int32_t* __restrict__ page_idx,
                                                                   int32_t* __restrict__ n_sel, int Hq, int P,
@@ -22,10 +22,10 @@ __global__ __launch_bounds__(kSelThreads) void select_topk_kernel(const float* _
   const float* s = box + (size_t)bh * Mmax;
   auto keyfn = [s](int p) { return float_to_key(s[p]); };
   if (k > 0) {
-    const KeySet<ITEMS, decltype(keyfn)> ks(keyfn, M);
-    uint32_t kmin, vT; int k_eq;
-    radix_select_kth(ks, k, sh, kmin, vT, k_eq);
-    compact_ordered(ks, kmin, vT, k_eq, sh, page_idx + (size_t)bh * cap);
+    KeySet<ITEMS, decltype(keyfn)> ks(keyfn, M);
+    uint32_t vT; int k_eq;
+    radix_select_kth(ks, k, sh, vT, k_eq);
+    compact_ordered(ks, vT, k_eq, sh, page_idx + (size_t)bh * cap);
   }
   if (threadIdx.x == 0) n_sel[bh] = k;
 }

@@ -24,17 +24,17 @@ __device__ __forceinline__ void page_stats_wave(const T* __restrict__ kpage, int
   for (int i = 0; i < 8; ++i) { mn[i] = INFINITY; mx[i] = -INFINITY; s1[i] = 0.f; s2[i] = 0.f; }
   for (int t0 = 0; t0 < P; t0 += kRowsPerWave) {
     const int row = t0 + r;
-    if (row < cnt) {
-      float x[8];
-      load8<T>((ov_row != nullptr && row == ov_slot ? ov_row : kpage + (size_t)row * kD) + 8 * c, x);
+    const bool ok = row < cnt;
+    const int rc = ok ? row : 0;                    // rows past cnt re-read row 0 and are masked
+    float x[8];
+    load8<T>((ov_row != nullptr && rc == ov_slot ? ov_row : kpage + (size_t)rc * kD) + 8 * c, x);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        mn[i] = fminf(mn[i], x[i]);
-        mx[i] = fmaxf(mx[i], x[i]);
-        const float dx = x[i] - k0[i];
-        s1[i] += dx;
-        s2[i] = fmaf(dx, dx, s2[i]);
-      }
+    for (int i = 0; i < 8; ++i) {
+      mn[i] = fminf(mn[i], ok ? x[i] : INFINITY);
+      mx[i] = fmaxf(mx[i], ok ? x[i] : -INFINITY);
+      const float dx = ok ? x[i] - k0[i] : 0.f;
+      s1[i] += dx;
+      s2[i] = fmaf(dx, dx, s2[i]);
     }
   }
   const float inv_n = 1.0f / (float)cnt;
