@@ -25,7 +25,7 @@ constexpr float kInvSqrt2 = 0.70710678118654752f;
 constexpr float kInvSqrt2Pi = 0.39894228040143268f;
 constexpr int kGaussEvalThreads = 256;
 constexpr int kGaussMaxSplits = 64;
-constexpr int kGaussIters = 12;           // evaluation launches per call (converged ones return at once)
+constexpr int kGaussIters = 8;            // evaluation launches per call (converged ones return at once)
 
 // h_n(t) = E[(t + Z)_+^n], Z ~ N(0,1), for n = NB and NB-1 (so that M_n = sigma^n h_n).
 // t >= -2.5: forward recurrence h_n = t h_{n-1} + (n-1) h_{n-2} from h_0 = Phi(t), h_1 = t Phi + phi.

@@ -11,10 +11,11 @@ namespace ekv {
 // tokens [0,cnt) are valid.  If ov_row != nullptr, token `ov_slot` takes its values from ov_row[128]
 // instead of the cache (the token being appended).  Sums are taken relative to the first token's
 // value so that m2 - avg^2 does not cancel for channels with a large common offset.
-template <typename T>
-__device__ __forceinline__ void page_stats_wave(const T* __restrict__ kpage, int cnt, int P,
+template <typename T, int PT>   // PT = compile-time page size (all row loads issued as one batch), 0 = runtime
+__device__ __forceinline__ void page_stats_wave(const T* __restrict__ kpage, int cnt, int P_rt,
                                                 const T* __restrict__ ov_row, int ov_slot,
                                                 T* __restrict__ box_out, T* __restrict__ gauss_out) {
+  const int P = PT ? PT : P_rt;
   const int lane = threadIdx.x & 63;
   const int r = lane >> 4, c = lane & 15;
   float k0[8];
@@ -22,12 +23,8 @@ __device__ __forceinline__ void page_stats_wave(const T* __restrict__ kpage, int
   float mn[8], mx[8], s1[8], s2[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) { mn[i] = INFINITY; mx[i] = -INFINITY; s1[i] = 0.f; s2[i] = 0.f; }
-  for (int t0 = 0; t0 < P; t0 += kRowsPerWave) {
-    const int row = t0 + r;
-    const bool ok = row < cnt;
-    const int rc = ok ? row : 0;                    // rows past cnt re-read row 0 and are masked
-    float x[8];
-    load8<T>((ov_row != nullptr && rc == ov_slot ? ov_row : kpage + (size_t)rc * kD) + 8 * c, x);
+  // rows past cnt re-read row 0 (loads stay unconditional) and are masked out of every statistic
+  auto accumulate = [&](const float (&x)[8], bool ok) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       mn[i] = fminf(mn[i], ok ? x[i] : INFINITY);
@@ -35,6 +32,25 @@ __device__ __forceinline__ void page_stats_wave(const T* __restrict__ kpage, int
       const float dx = ok ? x[i] - k0[i] : 0.f;
       s1[i] += dx;
       s2[i] = fmaf(dx, dx, s2[i]);
+    }
+  };
+  if constexpr (PT != 0) {
+    float x[PT / 4][8];
+#pragma unroll
+    for (int s = 0; s < PT / 4; ++s) {
+      const int row = 4 * s + r;
+      const int rc = row < cnt ? row : 0;
+      load8<T>((ov_row != nullptr && rc == ov_slot ? ov_row : kpage + (size_t)rc * kD) + 8 * c, x[s]);
+    }
+#pragma unroll
+    for (int s = 0; s < PT / 4; ++s) accumulate(x[s], 4 * s + r < cnt);
+  } else {
+    for (int t0 = 0; t0 < P; t0 += kRowsPerWave) {
+      const int row = t0 + r;
+      const int rc = row < cnt ? row : 0;
+      float x[8];
+      load8<T>((ov_row != nullptr && rc == ov_slot ? ov_row : kpage + (size_t)rc * kD) + 8 * c, x);
+      accumulate(x, row < cnt);
     }
   }
   const float inv_n = 1.0f / (float)cnt;
@@ -58,7 +74,7 @@ __device__ __forceinline__ void page_stats_wave(const T* __restrict__ kpage, int
   }
 }
 
-template <typename T>
+template <typename T, int PT>
 __global__ __launch_bounds__(256) void stats_build_kernel(const T* __restrict__ k_pool,
                                                           const int32_t* __restrict__ block_table,
                                                           const int32_t* __restrict__ seq_lens,
@@ -73,11 +89,11 @@ __global__ __launch_bounds__(256) void stats_build_kernel(const T* __restrict__ 
   const int phys = block_table[(size_t)b * Mmax + p];
   const T* kpage = k_pool + ((size_t)phys * Hkv + h) * P * kD;
   const size_t rec = (((size_t)b * Hkv + h) * Mmax + p) * 2 * kD;
-  page_stats_wave<T>(kpage, cnt, P, nullptr, -1, box + rec, gauss + rec);
+  page_stats_wave<T, PT>(kpage, cnt, P, nullptr, -1, box + rec, gauss + rec);
 }
 
 // One wavefront per (sequence, KV head): write the new token into slot n_b and refresh its page.
-template <typename T>
+template <typename T, int PT>
 __global__ __launch_bounds__(64) void stats_append_kernel(T* __restrict__ k_pool, T* __restrict__ v_pool,
                                                           const int32_t* __restrict__ block_table,
                                                           const int32_t* __restrict__ seq_lens,
@@ -104,30 +120,36 @@ __global__ __launch_bounds__(64) void stats_append_kernel(T* __restrict__ k_pool
     store8<T>(v_pool + page_off + (size_t)slot * kD + 8 * c, x);
   }
   const size_t rec = (((size_t)b * Hkv + h) * Mmax + p) * 2 * kD;
-  page_stats_wave<T>(k_pool + page_off, slot + 1, P, knew, slot, box + rec, gauss + rec);
+  page_stats_wave<T, PT>(k_pool + page_off, slot + 1, P, knew, slot, box + rec, gauss + rec);
+}
+
+template <typename T, int PT>
+static void launch_build_T(const Dims& dm, const ekv_cache_view& c, const ekv_stats_view& s, hipStream_t st) {
+  dim3 grid((dm.Mmax + 3) / 4, dm.Hkv, dm.B), block(256);
+  hipLaunchKernelGGL((stats_build_kernel<T, PT>), grid, block, 0, st, (const T*)c.k_pool, c.block_table, c.seq_lens,
+                     (T*)s.box, (T*)s.gauss, dm.Hkv, dm.P, dm.Mmax);
+}
+template <typename T, int PT>
+static void launch_append_T(const Dims& dm, const ekv_cache_view& c, const ekv_stats_view& s, const void* k_new,
+                            const void* v_new, hipStream_t st) {
+  dim3 grid(dm.Hkv, dm.B), block(64);
+  hipLaunchKernelGGL((stats_append_kernel<T, PT>), grid, block, 0, st, (T*)c.k_pool, (T*)c.v_pool, c.block_table,
+                     c.seq_lens, (const T*)k_new, (const T*)v_new, (T*)s.box, (T*)s.gauss, dm.Hkv, dm.P, dm.Mmax);
 }
 
 void launch_stats_build(const Dims& dm, const ekv_cache_view& c, const ekv_stats_view& s, hipStream_t st) {
-  dim3 grid((dm.Mmax + 3) / 4, dm.Hkv, dm.B), block(256);
-  if (dm.dtype == EKV_F32)
-    hipLaunchKernelGGL(stats_build_kernel<float>, grid, block, 0, st, (const float*)c.k_pool, c.block_table,
-                       c.seq_lens, (float*)s.box, (float*)s.gauss, dm.Hkv, dm.P, dm.Mmax);
-  else
-    hipLaunchKernelGGL(stats_build_kernel<bf16_t>, grid, block, 0, st, (const bf16_t*)c.k_pool, c.block_table,
-                       c.seq_lens, (bf16_t*)s.box, (bf16_t*)s.gauss, dm.Hkv, dm.P, dm.Mmax);
+  const bool f32 = dm.dtype == EKV_F32;
+  if (dm.P == 16) { if (f32) launch_build_T<float, 16>(dm, c, s, st); else launch_build_T<bf16_t, 16>(dm, c, s, st); }
+  else if (dm.P == 32) { if (f32) launch_build_T<float, 32>(dm, c, s, st); else launch_build_T<bf16_t, 32>(dm, c, s, st); }
+  else { if (f32) launch_build_T<float, 0>(dm, c, s, st); else launch_build_T<bf16_t, 0>(dm, c, s, st); }
 }
 
 void launch_stats_append(const Dims& dm, const ekv_cache_view& c, const ekv_stats_view& s,
                          const void* k_new, const void* v_new, hipStream_t st) {
-  dim3 grid(dm.Hkv, dm.B), block(64);
-  if (dm.dtype == EKV_F32)
-    hipLaunchKernelGGL(stats_append_kernel<float>, grid, block, 0, st, (float*)c.k_pool, (float*)c.v_pool,
-                       c.block_table, c.seq_lens, (const float*)k_new, (const float*)v_new, (float*)s.box,
-                       (float*)s.gauss, dm.Hkv, dm.P, dm.Mmax);
-  else
-    hipLaunchKernelGGL(stats_append_kernel<bf16_t>, grid, block, 0, st, (bf16_t*)c.k_pool, (bf16_t*)c.v_pool,
-                       c.block_table, c.seq_lens, (const bf16_t*)k_new, (const bf16_t*)v_new, (bf16_t*)s.box,
-                       (bf16_t*)s.gauss, dm.Hkv, dm.P, dm.Mmax);
+  const bool f32 = dm.dtype == EKV_F32;
+  if (dm.P == 16) { if (f32) launch_append_T<float, 16>(dm, c, s, k_new, v_new, st); else launch_append_T<bf16_t, 16>(dm, c, s, k_new, v_new, st); }
+  else if (dm.P == 32) { if (f32) launch_append_T<float, 32>(dm, c, s, k_new, v_new, st); else launch_append_T<bf16_t, 32>(dm, c, s, k_new, v_new, st); }
+  else { if (f32) launch_append_T<float, 0>(dm, c, s, k_new, v_new, st); else launch_append_T<bf16_t, 0>(dm, c, s, k_new, v_new, st); }
 }
 
 }  // namespace ekv
