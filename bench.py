@@ -96,7 +96,7 @@ def main():
         if evs: evs[1].record()
         ekv.ekv_score_pages(st.cfg, st.inp["q"], st.stats(), st.inp["seq_lens"], ekv.EKV_SCORE_BOX, st.box)
         if evs: evs[2].record()
-        ekv.ekv_select_topk(st.cfg, st.box, st.inp["seq_lens"], k_pages, st.page_idx, st.n_sel)
+        ekv.ekv_select_topk(st.cfg, st.box, st.inp["seq_lens"], k_pages, st.page_idx, st.n_sel, st.workspace(ekv.EKV_OP_SELECT_TOPK))
         if evs: evs[3].record()
         ekv.ekv_decode_sparse(st.cfg, st.inp["q"], st.cache(), st.page_idx, st.n_sel, st.out, st.tau, st.supp,
                               st.ws_sparse)
@@ -230,7 +230,7 @@ def main():
         kept_mass = torch.zeros_like(st0.tau); kept_supp = torch.zeros_like(st0.supp)
         for frac in (0.01, 0.02, 0.04):
             kp = max(1, int(math.ceil(frac * M)))
-            ekv.ekv_select_topk(st0.cfg, st0.box, st0.inp["seq_lens"], kp, st0.page_idx, st0.n_sel)
+            ekv.ekv_select_topk(st0.cfg, st0.box, st0.inp["seq_lens"], kp, st0.page_idx, st0.n_sel, st0.workspace(ekv.EKV_OP_SELECT_TOPK))
             ekv.ekv_decode_sparse(st0.cfg, st0.inp["q"], st0.cache(), st0.page_idx, st0.n_sel, st0.out, st0.tau,
                                   st0.supp, st0.ws_sparse,
                                   extras=ekv.decode_extras(tau_ref=tau_f, kept_mass_ref=kept_mass, kept_supp_ref=kept_supp))
@@ -243,7 +243,7 @@ def main():
                 "step_us": None}
         lse_sel = torch.zeros_like(st0.tau)
         ws_sm = copies[0].workspace(ekv.EKV_OP_DECODE_SPARSE_SOFTMAX)
-        ekv.ekv_select_topk(st0.cfg, st0.box, st0.inp["seq_lens"], k_pages, st0.page_idx, st0.n_sel)
+        ekv.ekv_select_topk(st0.cfg, st0.box, st0.inp["seq_lens"], k_pages, st0.page_idx, st0.n_sel, st0.workspace(ekv.EKV_OP_SELECT_TOPK))
         extras["softmax_sparse_us"] = round(time_call(
             lambda st: ekv.ekv_decode_sparse_softmax(st0.cfg, st0.inp["q"], st.cache(), st0.page_idx, st0.n_sel,
                                                      st0.out, lse_sel, ws_sm), reps=10), 2)

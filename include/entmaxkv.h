@@ -122,7 +122,9 @@ ekv_status ekv_score_pages(const ekv_config* cfg, const void* q, const ekv_stats
 /* a5 -- fixed-budget top-k page selection (Sec. 4.3).  For each (b,h): the min(k_pages, M_b) pages
  * of largest box score among p < M_b; equal scores are resolved towards the lower page index.
  * page_idx int32 [B][Hq][cap] receives the logical page indices in ASCENDING order, n_sel int32
- * [B][Hq] their number.  Requires 1 <= k_pages <= cap. */
+ * [B][Hq] their number.  Requires 1 <= k_pages <= cap and a workspace of
+ * ekv_workspace_bytes(EKV_OP_SELECT_TOPK) bytes (long contexts are split over several workgroups per
+ * head, which exchange histograms through it). */
 ekv_status ekv_select_topk(const ekv_config* cfg, const float* box, const int32_t* seq_lens,
                            int32_t k_pages, int32_t* page_idx, int32_t* n_sel, void* workspace,
                            size_t workspace_bytes, void* stream);

@@ -147,8 +147,8 @@ def ekv_score_pages(cfg, q, stats, seq_lens, mode, box=None, mu=None, sigma=None
                                           _ptr(mu), _ptr(sigma), _stream(stream)))
 
 
-def ekv_select_topk(cfg, box, seq_lens, k_pages, page_idx, n_sel, workspace=None, stream=None):
-    nbytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+def ekv_select_topk(cfg, box, seq_lens, k_pages, page_idx, n_sel, workspace, stream=None):
+    nbytes = workspace.numel() * workspace.element_size()
     _check(load_library().ekv_select_topk(byref(cfg), _ptr(box), _ptr(seq_lens), k_pages, _ptr(page_idx),
                                           _ptr(n_sel), _ptr(workspace), nbytes, _stream(stream)))
 

@@ -107,7 +107,7 @@ ekv_status ekv_workspace_bytes(const ekv_config* cfg, int32_t op, size_t* bytes)
   if (bytes == nullptr) return EKV_ERR_INVALID_ARG;
   size_t zs; int nc; size_t b = 0;
   switch (op) {
-    case EKV_OP_SELECT_TOPK: b = 256; break;
+    case EKV_OP_SELECT_TOPK: b = select_topk_ws_bytes(dm); break;
     case EKV_OP_SELECT_GAUSS: b = select_gauss_ws_bytes(dm); break;
     case EKV_OP_DECODE_SPARSE: decode_ws_layout(dm, false, zs, nc, b); break;
     case EKV_OP_DECODE_FULL: decode_ws_layout(dm, true, zs, nc, b); break;
@@ -156,14 +156,16 @@ ekv_status ekv_score_pages(const ekv_config* cfg, const void* q, const ekv_stats
 }
 
 ekv_status ekv_select_topk(const ekv_config* cfg, const float* box, const int32_t* seq_lens, int32_t k_pages,
-                           int32_t* page_idx, int32_t* n_sel, void* /*workspace*/, size_t /*workspace_bytes*/,
+                           int32_t* page_idx, int32_t* n_sel, void* workspace, size_t workspace_bytes,
                            void* stream) {
   Dims dm;
   const ekv_status s = make_dims(cfg, dm);
   if (s != EKV_OK) return s;
   if (!ok_ptr4(box) || !ok_ptr4(seq_lens) || !ok_ptr4(page_idx) || !ok_ptr4(n_sel)) return EKV_ERR_INVALID_ARG;
   if (k_pages < 1 || k_pages > dm.cap) return EKV_ERR_INVALID_ARG;
-  launch_select_topk(dm, box, seq_lens, k_pages, page_idx, n_sel, (hipStream_t)stream);
+  if (workspace == nullptr || !aligned16(workspace) || workspace_bytes < select_topk_ws_bytes(dm))
+    return EKV_ERR_WORKSPACE;
+  launch_select_topk(dm, box, seq_lens, k_pages, page_idx, n_sel, workspace, (hipStream_t)stream);
   return finish((hipStream_t)stream);
 }
 

@@ -31,7 +31,7 @@ void launch_stats_append(const Dims& dm, const ekv_cache_view& c, const ekv_stat
 void launch_score_pages(const Dims& dm, const void* q, const ekv_stats_view& s, const int32_t* seq_lens,
                         int mode, float* box, float* mu, float* sigma, hipStream_t st);
 void launch_select_topk(const Dims& dm, const float* box, const int32_t* seq_lens, int k_pages,
-                        int32_t* page_idx, int32_t* n_sel, hipStream_t st);
+                        int32_t* page_idx, int32_t* n_sel, void* ws, hipStream_t st);
 void launch_select_gauss(const Dims& dm, const float* mu, const float* sigma, const int32_t* seq_lens,
                          const float* zq_table, float margin, float* tau_hat, int32_t* page_idx,
                          int32_t* n_sel, int32_t* overflow, void* ws, hipStream_t st);
@@ -42,6 +42,7 @@ void launch_decode_sparse_softmax(const Dims& dm, const void* q, const ekv_cache
                                   const int32_t* page_idx, const int32_t* n_sel, float* out,
                                   float* lse_sel, void* ws, hipStream_t st);
 
+size_t select_topk_ws_bytes(const Dims& dm);
 size_t select_gauss_ws_bytes(const Dims& dm);
 size_t softmax_ws_bytes(const Dims& dm);
 

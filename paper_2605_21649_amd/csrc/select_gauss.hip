@@ -237,6 +237,7 @@ __global__ __launch_bounds__(kSelThreads) __attribute__((amdgpu_waves_per_eu(4, 
   const int bh = blockIdx.x, b = bh / Hq, tid = threadIdx.x;
   const int n = seq_lens[b];
   const int M = (n + P - 1) / P;
+  if (M <= 0) { if (tid == 0) { n_sel[bh] = 0; overflow[bh] = 0; tau_hat[bh] = 0.f; } return; }
   const int cnt_last = n - (M - 1) * P;
   const float* mu_r = mu + (size_t)bh * Mmax;
   const float* sg_r = sigma + (size_t)bh * Mmax;

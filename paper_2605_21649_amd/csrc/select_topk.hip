@@ -1,20 +1,34 @@
 // Fixed-budget top-k page selection (paper Sec. 4.3): the k pages of largest box score per
 // (sequence, query head), ties towards the lower page index, written in ascending page order.
-// One 1024-thread workgroup per (b,h): the scores are read once (coalesced) into registers as
-// order-preserving keys, the k-th largest is found exactly by radix selection (LDS integer histograms)
-// and one ballot-based ordered compaction writes the indices.
+//
+// Small page counts (M <= 16384): one 1024-thread workgroup per (b,h) holds the scores in registers as
+// order-preserving keys, finds the k-th largest exactly by radix selection (LDS integer histograms) and
+// writes the indices with a ballot-based ordered compaction.
+//
+// Long contexts: a single compute unit per head is the bottleneck (the paper's "explicit top-k
+// bottleneck"), so the work is split over slices of 4096 pages and three launches:
+//   hist     (slices x heads workgroups)  2048-bin histogram of each slice over a key range estimated from
+//                                         the first 1024 pages (keys outside are clamped into the edge bins,
+//                                         which keeps the binning monotone), stored as counts-above per bin;
+//   find     (one workgroup per head)     bin of the k-th largest from the summed counts, its members are
+//                                         gathered and ranked exactly -> the k-th key, the tie quota and the
+//                                         output offset of every slice;
+//   compact  (slices x heads workgroups)  ordered compaction of each slice against that key.
+// If the bin of the k-th key holds more members than the ranking list, the heads concerned are redone by
+// the single-workgroup algorithm (a fourth launch whose workgroups return at once otherwise).
 #include "ekv_select.h"
 #include "ekv_internal.h"
 
 namespace ekv {
 
+// ------------------------------------------------------------------------------------------
+// single-workgroup algorithm
+// ------------------------------------------------------------------------------------------
 template <int ITEMS>
-__global__ __launch_bounds__(kSelThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void select_topk_kernel(const float* __restrict__ box,
-                                                                  const int32_t* __restrict__ seq_lens,
-                                                                  int k_pages, int32_t* __restrict__ page_idx,
-                                                                  int32_t* __restrict__ n_sel, int Hq, int P,
-                                                                  int Mmax, int cap) {
-  __shared__ SelectShared sh;
+__device__ __forceinline__ void topk_single(const float* __restrict__ box, const int32_t* __restrict__ seq_lens,
+                                            int k_pages, int32_t* __restrict__ page_idx,
+                                            int32_t* __restrict__ n_sel, int Hq, int P, int Mmax, int cap,
+                                            SelectShared& sh) {
   const int bh = blockIdx.x, b = bh / Hq;
   const int n = seq_lens[b];
   const int M = (n + P - 1) / P;
@@ -30,17 +44,333 @@ __global__ __launch_bounds__(kSelThreads) __attribute__((amdgpu_waves_per_eu(4, 
   if (threadIdx.x == 0) n_sel[bh] = k;
 }
 
+template <int ITEMS>
+__global__ __launch_bounds__(kSelThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void select_topk_kernel(
+    const float* __restrict__ box, const int32_t* __restrict__ seq_lens, int k_pages,
+    int32_t* __restrict__ page_idx, int32_t* __restrict__ n_sel, int Hq, int P, int Mmax, int cap) {
+  __shared__ SelectShared sh;
+  topk_single<ITEMS>(box, seq_lens, k_pages, page_idx, n_sel, Hq, P, Mmax, cap, sh);
+}
+
+// ------------------------------------------------------------------------------------------
+// sliced kernels
+// ------------------------------------------------------------------------------------------
+constexpr int kTkThreads = 256;
+constexpr int kTkWaves = kTkThreads / 64;
+constexpr int kTkItems = 16;                                  // keys per lane
+constexpr int kTkSlice = kTkThreads * kTkItems;               // pages per slice: 4096
+constexpr int kTkSample = 1024;                               // pages the key range is estimated from
+constexpr int kTkMembers = 1024;                              // ranking list of the find kernel
+constexpr int kTkMaxSlices = 64;
+
+struct TopkHead {             // per (b,h) state passed between the launches
+  uint32_t lo;                // bin(key) = key <= lo ? 0 : min(kBins-1, (key - lo) >> shift)
+  int32_t shift;
+  uint32_t key_t;             // the k-th largest key
+  int32_t k_eq;               // how many pages with key == key_t are taken (lowest indices first)
+  int32_t redo;               // 1: the single-workgroup algorithm must redo this head
+  int32_t pad[3];
+};
+struct TopkWs {
+  TopkHead* head;             // [BH]
+  uint32_t* above;            // [BH][S][kBins]   pages of the slice in bins above this one
+  int32_t* slice_off;         // [BH][S]          output offset of the slice
+  int32_t* slice_eq;          // [BH][S]          pages with key == key_t in earlier slices
+  int S;
+};
+
+__device__ __forceinline__ int topk_bin(uint32_t key, uint32_t lo, int shift) {
+  return key <= lo ? 0 : (int)min((uint32_t)(kBins - 1), (key - lo) >> shift);
+}
+
+// The 16 keys of this lane: wavefront w of slice s owns pages s*4096 + w*1024 + i*64 + lane (ascending in
+// (w, i, lane) order).  Unconditional clamped loads; slots past M are flagged invalid.
+__device__ __forceinline__ void load_slice_keys(const float* __restrict__ s, int M, int page0,
+                                                uint32_t (&key)[kTkItems], uint32_t& valid_mask) {
+  float raw[kTkItems];
+#pragma unroll
+  for (int i = 0; i < kTkItems; ++i) raw[i] = s[min(page0 + i * 64, M - 1)];
+  valid_mask = 0;
+#pragma unroll
+  for (int i = 0; i < kTkItems; ++i) {
+    key[i] = float_to_key(raw[i]);
+    if (page0 + i * 64 < M) valid_mask |= 1u << i;
+  }
+}
+
+__global__ __launch_bounds__(kTkThreads) void topk_hist_kernel(const float* __restrict__ box,
+                                                               const int32_t* __restrict__ seq_lens, TopkWs ws,
+                                                               int Hq, int P, int Mmax) {
+  __shared__ uint32_t hist[kBins];
+  __shared__ uint32_t red[2][kTkWaves];
+  __shared__ int wsum[kTkWaves];
+  const int bh = blockIdx.y, slice = blockIdx.x, b = bh / Hq, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int n = seq_lens[b];
+  const int M = (n + P - 1) / P;
+  const float* s = box + (size_t)bh * Mmax;
+  if (slice * kTkSlice >= M) {            // empty slice: all counts are zero
+    for (int i = tid; i < kBins; i += kTkThreads) ws.above[((size_t)bh * ws.S + slice) * kBins + i] = 0;
+    return;
+  }
+  // key range of the first kTkSample pages, widened by half its width on both sides
+  uint32_t lo = 0xffffffffu, hi = 0u;
+  {
+    float sv[kTkSample / kTkThreads];
+#pragma unroll
+    for (int i = 0; i < kTkSample / kTkThreads; ++i) sv[i] = s[min(tid + i * kTkThreads, M - 1)];
+#pragma unroll
+    for (int i = 0; i < kTkSample / kTkThreads; ++i) {
+      const uint32_t kk = float_to_key(sv[i]);
+      lo = min(lo, kk); hi = max(hi, kk);
+    }
+  }
+  for (int d = 32; d >= 1; d >>= 1) {
+    lo = min(lo, (uint32_t)__shfl_xor((int)lo, d));
+    hi = max(hi, (uint32_t)__shfl_xor((int)hi, d));
+  }
+  if (lane == 0) { red[0][w] = lo; red[1][w] = hi; }
+  for (int i = tid; i < kBins; i += kTkThreads) hist[i] = 0;
+  __syncthreads();
+  for (int i = 0; i < kTkWaves; ++i) { lo = min(lo, red[0][i]); hi = max(hi, red[1][i]); }
+  const uint32_t half = (hi - lo) >> 1;
+  const uint32_t lo_w = lo > half ? lo - half : 0u;
+  const uint32_t hi_w = hi + half >= hi ? hi + half : 0xffffffffu;
+  const uint32_t range = hi_w - lo_w;
+  const int bits = range ? 32 - __clz(range) : 0;
+  const int shift = max(bits - kDigitBits, 0);
+  if (slice == 0 && tid == 0) { ws.head[bh].lo = lo_w; ws.head[bh].shift = shift; ws.head[bh].redo = 0; }
+
+  uint32_t key[kTkItems], vmask;
+  load_slice_keys(s, M, slice * kTkSlice + w * (kTkSlice / kTkWaves) + lane, key, vmask);
+#pragma unroll
+  for (int i = 0; i < kTkItems; ++i)
+    if (vmask & (1u << i)) atomicAdd(&hist[topk_bin(key[i], lo_w, shift)], 1u);
+  __syncthreads();
+  // counts above each bin: thread t owns the 8 bins [8t, 8t+8); suffix sums over the block
+  constexpr int BPT = kBins / kTkThreads;
+  uint32_t c[BPT];
+  int tot = 0;
+#pragma unroll
+  for (int i = 0; i < BPT; ++i) { c[i] = hist[tid * BPT + i]; tot += (int)c[i]; }
+  int inc = tot;                                   // inclusive sum over this and all HIGHER lanes
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) { const int t = __shfl_down(inc, d); if (lane + d < 64) inc += t; }
+  if (lane == 0) wsum[w] = inc;
+  __syncthreads();
+  int higher = 0;                                  // pages in bins owned by higher wavefronts
+  for (int i = w + 1; i < kTkWaves; ++i) higher += wsum[i];
+  uint32_t run = (uint32_t)(higher + inc - tot);   // pages in bins above this thread's highest bin
+  uint32_t ab[BPT];
+#pragma unroll
+  for (int i = BPT - 1; i >= 0; --i) { ab[i] = run; run += c[i]; }
+  uint32_t* out = ws.above + ((size_t)bh * ws.S + slice) * kBins + tid * BPT;
+#pragma unroll
+  for (int i = 0; i < BPT; ++i) out[i] = ab[i];
+}
+
+__global__ __launch_bounds__(kSelThreads) void topk_find_kernel(const float* __restrict__ box,
+                                                                const int32_t* __restrict__ seq_lens, int k_pages,
+                                                                TopkWs ws, int32_t* __restrict__ n_sel, int Hq, int P,
+                                                                int Mmax, int cap) {
+  __shared__ uint32_t tot_above[kBins];                // summed over the slices
+  __shared__ uint32_t mem_key[kTkMembers];
+  __shared__ int32_t mem_page[kTkMembers];
+  __shared__ int s_gt[kTkMaxSlices], s_eq[kTkMaxSlices];
+  __shared__ int s_bin, s_cnt, s_m;
+  __shared__ uint32_t s_keyt;
+  const int bh = blockIdx.x, b = bh / Hq, tid = threadIdx.x;
+  const int n = seq_lens[b];
+  const int M = (n + P - 1) / P;
+  const int k = min(min(k_pages, M), cap);
+  const int S = ws.S;
+  const float* s = box + (size_t)bh * Mmax;
+  if (M <= 0) { if (tid == 0) n_sel[bh] = 0; return; }
+  const TopkHead hd = ws.head[bh];
+
+  // counts above each bin, summed over the slices (thread t owns bins 2t and 2t+1)
+  uint32_t a0 = 0, a1 = 0;
+  {
+    const uint32_t* ab = ws.above + (size_t)bh * S * kBins + 2 * tid;
+    for (int s0 = 0; s0 < S; s0 += 8) {
+      uint2 v[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] = *reinterpret_cast<const uint2*>(ab + (size_t)min(s0 + i, S - 1) * kBins);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) if (s0 + i < S) { a0 += v[i].x; a1 += v[i].y; }
+    }
+  }
+  tot_above[2 * tid] = a0; tot_above[2 * tid + 1] = a1;
+  if (tid == 0) { s_m = 0; s_bin = 0; s_cnt = 0; s_keyt = 0u; }
+  if (tid < kTkMaxSlices) { s_gt[tid] = 0; s_eq[tid] = 0; }
+  __syncthreads();
+  // bin b1 of the k-th largest: above[b1] < k <= above[b1 - 1]   (above[-1] := M)
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int bin = 2 * tid + i;
+    const uint32_t ab = tot_above[bin];
+    const uint32_t below = bin == 0 ? (uint32_t)M : tot_above[bin - 1];
+    if (ab < (uint32_t)k && (uint32_t)k <= below) { s_bin = bin; s_cnt = (int)(below - ab); }
+  }
+  __syncthreads();
+  const int b1 = s_bin, m = s_cnt;
+  const int k_rem = k - (int)tot_above[b1];            // rank of the answer inside bin b1 (1-based)
+  if (m > kTkMembers) {                                // too many (near-)ties for the ranking list
+    if (tid == 0) ws.head[bh].redo = 1;
+    return;
+  }
+  // gather the members of bin b1: one scan of the scores in batches of 16 clamped loads per lane
+  const int per_wave = ((M + kSelWaves - 1) / kSelWaves + 63) & ~63;
+  const int wbase = (tid >> 6) * per_wave + (tid & 63);
+  for (int i0 = 0; i0 < per_wave; i0 += 16 * 64) {
+    float raw[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) raw[i] = s[min(wbase + i0 + i * 64, M - 1)];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int p = wbase + i0 + i * 64;
+      const uint32_t kk = float_to_key(raw[i]);
+      if (i0 + i * 64 < per_wave && p < M && topk_bin(kk, hd.lo, hd.shift) == b1) {
+        const int slot = atomicAdd(&s_m, 1);           // arrival order is irrelevant: ranks below are exact
+        if (slot < kTkMembers) { mem_key[slot] = kk; mem_page[slot] = p; }
+      }
+    }
+  }
+  __syncthreads();
+  // exact rank of every member: larger key first, lower page first among equal keys
+  if (tid < m) {
+    const uint32_t kk = mem_key[tid]; const int pp = mem_page[tid];
+    int rank = 0;
+    for (int jj = 0; jj < m; ++jj) {
+      const uint32_t kj = mem_key[jj];
+      rank += (kj > kk) || (kj == kk && mem_page[jj] < pp);
+    }
+    if (rank == k_rem - 1) s_keyt = kk;                // the k-th largest key overall
+  }
+  __syncthreads();
+  const uint32_t key_t = s_keyt;
+  if (tid < m) {
+    const uint32_t kk = mem_key[tid];
+    const int sl = mem_page[tid] / kTkSlice;
+    if (kk > key_t) atomicAdd(&s_gt[sl], 1);
+    else if (kk == key_t) atomicAdd(&s_eq[sl], 1);
+  }
+  __syncthreads();
+  if (tid == 0) {
+    int gt_members = 0;
+    for (int i = 0; i < S; ++i) gt_members += s_gt[i];
+    const int k_eq = k_rem - gt_members;               // pages equal to key_t that are taken
+    int off = 0, eq_before = 0;
+    for (int i = 0; i < S; ++i) {
+      ws.slice_off[(size_t)bh * S + i] = off;
+      ws.slice_eq[(size_t)bh * S + i] = eq_before;
+      const int above_i = (int)ws.above[((size_t)bh * S + i) * kBins + b1];
+      const int take_eq = max(0, min(s_eq[i], k_eq - eq_before));
+      off += above_i + s_gt[i] + take_eq;
+      eq_before += s_eq[i];
+    }
+    ws.head[bh].key_t = key_t; ws.head[bh].k_eq = k_eq;
+    n_sel[bh] = k;
+  }
+}
+
+__global__ __launch_bounds__(kTkThreads) void topk_compact_kernel(const float* __restrict__ box,
+                                                                  const int32_t* __restrict__ seq_lens, TopkWs ws,
+                                                                  int32_t* __restrict__ page_idx, int Hq, int P,
+                                                                  int Mmax, int cap) {
+  __shared__ int w_take[kTkWaves], w_eq[kTkWaves];
+  const int bh = blockIdx.y, slice = blockIdx.x, b = bh / Hq, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int n = seq_lens[b];
+  const int M = (n + P - 1) / P;
+  if (slice * kTkSlice >= M) return;
+  const TopkHead hd = ws.head[bh];
+  if (hd.redo) return;
+  const float* s = box + (size_t)bh * Mmax;
+  const int page0 = slice * kTkSlice + w * (kTkSlice / kTkWaves) + lane;
+  uint32_t key[kTkItems], vmask;
+  load_slice_keys(s, M, page0, key, vmask);
+  const uint64_t lt = (1ull << lane) - 1ull;
+  // per-wavefront totals of (key > key_t) and (key == key_t)
+  int n_gt = 0, n_eq = 0;
+#pragma unroll
+  for (int i = 0; i < kTkItems; ++i) {
+    const bool ok = vmask & (1u << i);
+    n_gt += ok && key[i] > hd.key_t;
+    n_eq += ok && key[i] == hd.key_t;
+  }
+  n_gt = wave_sum_i(n_gt); n_eq = wave_sum_i(n_eq);
+  if (lane == 0) { w_take[w] = n_gt; w_eq[w] = n_eq; }
+  __syncthreads();
+  int eq_run = ws.slice_eq[(size_t)bh * ws.S + slice];
+  int o_run = ws.slice_off[(size_t)bh * ws.S + slice];
+  for (int i = 0; i < w; ++i) {
+    const int take_eq = max(0, min(w_eq[i], hd.k_eq - eq_run));
+    o_run += w_take[i] + take_eq;
+    eq_run += w_eq[i];
+  }
+  int32_t* out = page_idx + (size_t)bh * cap;
+#pragma unroll
+  for (int i = 0; i < kTkItems; ++i) {
+    const bool ok = vmask & (1u << i);
+    const bool eq = ok && key[i] == hd.key_t;
+    const uint64_t m_eq = __ballot(eq);
+    const bool take = (ok && key[i] > hd.key_t) || (eq && eq_run + __popcll(m_eq & lt) < hd.k_eq);
+    const uint64_t m_take = __ballot(take);
+    if (take) out[o_run + __popcll(m_take & lt)] = page0 + i * 64;
+    eq_run += __popcll(m_eq);
+    o_run += __popcll(m_take);
+  }
+}
+
+// Heads flagged by the find kernel are redone from scratch by the single-workgroup algorithm (scores
+// re-read from memory in every pass).
+__global__ __launch_bounds__(kSelThreads) void select_topk_redo_kernel(const float* __restrict__ box,
+                                                                       const int32_t* __restrict__ seq_lens,
+                                                                       int k_pages, int32_t* __restrict__ page_idx,
+                                                                       int32_t* __restrict__ n_sel, TopkWs ws, int Hq,
+                                                                       int P, int Mmax, int cap) {
+  __shared__ SelectShared sh;
+  if (ws.head[blockIdx.x].redo == 0) return;
+  topk_single<0>(box, seq_lens, k_pages, page_idx, n_sel, Hq, P, Mmax, cap, sh);
+}
+
+static int topk_slices(const Dims& dm) { return (dm.Mmax + kTkSlice - 1) / kTkSlice; }
+static bool topk_sliced(const Dims& dm) { return dm.Mmax > 16 * kSelThreads && topk_slices(dm) <= kTkMaxSlices; }
+
+size_t select_topk_ws_bytes(const Dims& dm) {
+  if (!topk_sliced(dm)) return 256;
+  const size_t BH = (size_t)dm.B * dm.Hq, S = topk_slices(dm);
+  size_t b = BH * sizeof(TopkHead) + BH * S * kBins * sizeof(uint32_t) + 2 * BH * S * sizeof(int32_t);
+  return (b + 255) & ~(size_t)255;
+}
+
 void launch_select_topk(const Dims& dm, const float* box, const int32_t* seq_lens, int k_pages,
-                        int32_t* page_idx, int32_t* n_sel, hipStream_t st) {
+                        int32_t* page_idx, int32_t* n_sel, void* workspace, hipStream_t st) {
   dim3 grid(dm.B * dm.Hq), block(kSelThreads);
-#define EKV_TOPK(ITEMS)                                                                                  \
-  hipLaunchKernelGGL(select_topk_kernel<ITEMS>, grid, block, 0, st, box, seq_lens, k_pages, page_idx, n_sel, \
-                     dm.Hq, dm.P, dm.Mmax, dm.cap)
-  if (dm.Mmax <= 4 * kSelThreads) EKV_TOPK(4);
-  else if (dm.Mmax <= 16 * kSelThreads) EKV_TOPK(16);
-  else if (dm.Mmax <= 64 * kSelThreads) EKV_TOPK(64);
-  else EKV_TOPK(0);
+#define EKV_TOPK(ITEMS)                                                                                        \
+  hipLaunchKernelGGL(select_topk_kernel<ITEMS>, grid, block, 0, st, box, seq_lens, k_pages, page_idx, n_sel, dm.Hq, \
+                     dm.P, dm.Mmax, dm.cap)
+  if (!topk_sliced(dm)) {
+    if (dm.Mmax <= 4 * kSelThreads) EKV_TOPK(4);
+    else if (dm.Mmax <= 16 * kSelThreads) EKV_TOPK(16);
+    else EKV_TOPK(0);
+    return;
+  }
 #undef EKV_TOPK
+  const size_t BH = (size_t)dm.B * dm.Hq;
+  TopkWs ws;
+  ws.S = topk_slices(dm);
+  ws.head = (TopkHead*)workspace;
+  ws.above = (uint32_t*)(ws.head + BH);
+  ws.slice_off = (int32_t*)(ws.above + BH * ws.S * kBins);
+  ws.slice_eq = ws.slice_off + BH * ws.S;
+  dim3 sgrid(ws.S, dm.B * dm.Hq), sblock(kTkThreads);
+  hipLaunchKernelGGL(topk_hist_kernel, sgrid, sblock, 0, st, box, seq_lens, ws, dm.Hq, dm.P, dm.Mmax);
+  hipLaunchKernelGGL(topk_find_kernel, grid, block, 0, st, box, seq_lens, k_pages, ws, n_sel, dm.Hq, dm.P, dm.Mmax,
+                     dm.cap);
+  hipLaunchKernelGGL(topk_compact_kernel, sgrid, sblock, 0, st, box, seq_lens, ws, page_idx, dm.Hq, dm.P, dm.Mmax,
+                     dm.cap);
+  hipLaunchKernelGGL(select_topk_redo_kernel, grid, block, 0, st, box, seq_lens, k_pages, page_idx, n_sel, ws, dm.Hq,
+                     dm.P, dm.Mmax, dm.cap);
 }
 
 }  // namespace ekv

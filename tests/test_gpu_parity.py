@@ -173,7 +173,7 @@ def test_select_topk_on_shared_scores(w):
     scores[0, 0, :] = 1.25                                   # all equal: lowest indices win
     scores[0, 1, : M // 2] = np.round(scores[0, 1, : M // 2], 1)   # many ties around the cut
     st.box.copy_(torch.from_numpy(scores))
-    ekv.ekv_select_topk(st.cfg, st.box, st.inp["seq_lens"], k, st.page_idx, st.n_sel)
+    ekv.ekv_select_topk(st.cfg, st.box, st.inp["seq_lens"], k, st.page_idx, st.n_sel, st.workspace(ekv.EKV_OP_SELECT_TOPK))
     torch.cuda.synchronize()
     idx, ns = st.page_idx.cpu().numpy(), st.n_sel.cpu().numpy()
     for b in range(w.batch):
@@ -181,6 +181,70 @@ def test_select_topk_on_shared_scores(w):
             ref, _, _ = orc.topk_pages(scores[b, hq, :M].astype(np.float64), k)
             assert ns[b, hq] == len(ref)
             np.testing.assert_array_equal(idx[b, hq, : ns[b, hq]], ref)
+
+
+@pytest.mark.parametrize("M,k", [(40000 - 3, 1311), (65536, 2622), (20000, 20000), (17000, 1)])
+def test_select_topk_long_context(M, k):
+    """More than 16384 pages: the selection is split over slices of 4096 pages and several launches.
+    Synthetic float32 scores (no cache needed); heads with massive ties take the redo path."""
+    P, B, Hq = 16, 1, 8
+    Mmax = -(-M // 64) * 64
+    cfg = ekv.make_config(B, Hq, Hq, 128, P, "bf16", 1.5, 0.1, Mmax, k)
+    dev = torch.device("cuda")
+    rng = np.random.default_rng(M + k)
+    scores = (rng.normal(size=(B, Hq, Mmax)) * 3.0 + 17.0).astype(np.float32)
+    scores[0, 1] = 2.5                                             # all equal -> redo path
+    scores[0, 2] = np.round(scores[0, 2], 1)                       # ~100 distinct values, heavy ties
+    scores[0, 3, :1024] = 1.0; scores[0, 3, 1024:] += 40.0         # range estimate from the first pages is off
+    scores[0, 4] = np.abs(scores[0, 4]) * 1e-3 * rng.choice([-1.0, 1.0], size=Mmax)   # both signs
+    scores[0, 5, ::2] = scores[0, 5, 1::2]                         # every value twice
+    box = torch.from_numpy(scores).to(dev)
+    seq_lens = torch.full((B,), M * P - 5, dtype=torch.int32, device=dev)
+    page_idx = torch.full((B, Hq, k), -1, dtype=torch.int32, device=dev)
+    n_sel = torch.zeros(B, Hq, dtype=torch.int32, device=dev)
+    ws = torch.empty(ekv.ekv_workspace_bytes(cfg, ekv.EKV_OP_SELECT_TOPK), dtype=torch.uint8, device=dev)
+    for rep in range(2):                                           # second call reuses a dirty workspace
+        ekv.ekv_select_topk(cfg, box, seq_lens, k, page_idx, n_sel, ws)
+        torch.cuda.synchronize()
+        idx, ns = page_idx.cpu().numpy(), n_sel.cpu().numpy()
+        for hq in range(Hq):
+            ref, _, _ = orc.topk_pages(scores[0, hq, :M].astype(np.float64), k)
+            assert ns[0, hq] == len(ref)
+            np.testing.assert_array_equal(idx[0, hq, : ns[0, hq]], ref)
+
+
+def test_select_gauss_long_context():
+    """Gaussian selector with 65536 pages per head (keys held in registers, 64 per lane)."""
+    P, B, Hq, M = 16, 1, 4, 65536
+    cap = 3000
+    cfg = ekv.make_config(B, Hq, Hq, 128, P, "bf16", 1.5, 0.1, M, cap)
+    dev = torch.device("cuda")
+    rng = np.random.default_rng(99)
+    mu = (rng.normal(size=(B, Hq, M)) * 0.25 + 1.0).astype(np.float32)
+    sg = (np.abs(rng.normal(size=(B, Hq, M))) * 0.1 + 0.9).astype(np.float32)
+    mu[0, 1, rng.choice(M, 50, replace=False)] += 3.0              # a few hot pages
+    seq_lens = torch.full((B,), M * P - 7, dtype=torch.int32, device=dev)
+    t = lambda a: torch.from_numpy(a).to(dev)
+    tau_hat = torch.zeros(B, Hq, device=dev); page_idx = torch.zeros(B, Hq, cap, dtype=torch.int32, device=dev)
+    n_sel = torch.zeros(B, Hq, dtype=torch.int32, device=dev); ovf = torch.zeros_like(n_sel)
+    ws = torch.empty(ekv.ekv_workspace_bytes(cfg, ekv.EKV_OP_SELECT_GAUSS), dtype=torch.uint8, device=dev)
+    cnt = np.full(M, P); cnt[-1] = P - 7
+    for q_page, margin in ((0.99, 0.0), (0.999, 0.02)):
+        ekv.ekv_select_gauss(cfg, t(mu), t(sg), seq_lens, q_page, margin, tau_hat, page_idx, n_sel, ovf, ws)
+        torch.cuda.synchronize()
+        for hq in range(Hq):
+            pages, th, o, g = orc.gauss_select(mu[0, hq].astype(np.float64), sg[0, hq].astype(np.float64), cnt, 1.5,
+                                               q_page, margin, cap=cap)
+            assert abs(float(tau_hat[0, hq]) - th) <= 4e-6 * max(1.0, abs(th)), (float(tau_hat[0, hq]), th)
+            assert int(ovf[0, hq]) == int(o)
+            got = page_idx[0, hq, : int(n_sel[0, hq])].cpu().numpy()
+            if not o:
+                cut = th - margin
+                ok, bad = sets_equal_up_to_cut(got, pages, g, cut, 1e-5 * max(1.0, abs(cut)))
+                assert ok, (hq, bad[:5], len(pages), len(got))
+            else:
+                assert len(got) == cap
+            assert np.all(np.diff(got) > 0)
 
 
 # ---------------------------------------------------------------------------- a6
@@ -384,7 +448,7 @@ def run_step(st, w, selector, k=None, q_page=0.99, margin=0.0):
     ekv.ekv_stats_build(st.cfg, st.cache(), st.stats())
     if selector == "topk":
         ekv.ekv_score_pages(st.cfg, st.inp["q"], st.stats(), st.inp["seq_lens"], ekv.EKV_SCORE_BOX, st.box)
-        ekv.ekv_select_topk(st.cfg, st.box, st.inp["seq_lens"], k, st.page_idx, st.n_sel)
+        ekv.ekv_select_topk(st.cfg, st.box, st.inp["seq_lens"], k, st.page_idx, st.n_sel, st.workspace(ekv.EKV_OP_SELECT_TOPK))
     else:
         ekv.ekv_score_pages(st.cfg, st.inp["q"], st.stats(), st.inp["seq_lens"], ekv.EKV_SCORE_GAUSS, None, st.mu,
                             st.sigma)
