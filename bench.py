@@ -41,6 +41,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="time only the headline step")
     ap.add_argument("--cpu-units", type=int, default=2, help="(b,h) units the oracle is timed on")
+    ap.add_argument("--pmc-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (calibrates rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     return ap.parse_args()
 
 
@@ -131,6 +133,14 @@ def main():
         stage = np.array([[es[j].elapsed_time(es[j + 1]) * 1e3 for j in range(4)] for es in all_evs])   # us
         whole = np.array([es[0].elapsed_time(es[4]) * 1e3 for es in all_evs])
         return wall / steps * 1e6, stage, whole
+
+    if args.pmc_copy:
+        # a plain copy of known size: 1 GiB read + 1 GiB written by one elementwise kernel
+        src = torch.empty(256 * 1024 * 1024, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---------------------------------------------------------------- headline: top-k step
     us_wall, stage, whole = run_timed(step_topk, args.steps, args.warmup)

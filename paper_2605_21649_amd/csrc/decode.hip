@@ -386,7 +386,9 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
   // candidates did not fit in LDS, the threshold of one more compaction pass.
   float thr = zmax - 1.0f - 4e-6f * fmaxf(1.f, fabsf(zmax));
   float lo_u = thr - zmax;
-  const bool can_skip = (chunk_tokens & 63) == 0;
+  // chunk skipping pays only when there is a lot to skip (dense rows); short candidate lists are read whole,
+  // which saves the dependent load of the chunk maxima in every round
+  const bool can_skip = (chunk_tokens & 63) == 0 && n_cand > 4 * kRoundTokens;
   int n_list = 0, parity = 0;
   bool in_lds = true;
   for (int pass = 0; pass < 3; ++pass) {
@@ -401,7 +403,7 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
       // before all of them are in flight.
       float pmv[kRoundLoads];
 #pragma unroll
-      for (int i = 0; i < kRoundLoads; ++i) pmv[i] = pm[min(seg + i * 64, n_cand - 1) / chunk_tokens];
+      for (int i = 0; i < kRoundLoads; ++i) pmv[i] = can_skip ? pm[min(seg + i * 64, n_cand - 1) / chunk_tokens] : INFINITY;
       float v[kRoundLoads];
 #pragma unroll
       for (int i = 0; i < kRoundLoads; ++i) {

@@ -255,21 +255,28 @@ __global__ __launch_bounds__(kSelThreads) void topk_find_kernel(const float* __r
     else if (kk == key_t) atomicAdd(&s_eq[sl], 1);
   }
   __syncthreads();
+  // per-slice output offsets: the global loads are done in parallel, the short serial prefix runs on LDS
+  __shared__ int s_above[kTkMaxSlices], s_off[kTkMaxSlices], s_eqb[kTkMaxSlices];
+  if (tid < S) s_above[tid] = (int)ws.above[((size_t)bh * S + tid) * kBins + b1];
+  __syncthreads();
   if (tid == 0) {
     int gt_members = 0;
     for (int i = 0; i < S; ++i) gt_members += s_gt[i];
     const int k_eq = k_rem - gt_members;               // pages equal to key_t that are taken
     int off = 0, eq_before = 0;
     for (int i = 0; i < S; ++i) {
-      ws.slice_off[(size_t)bh * S + i] = off;
-      ws.slice_eq[(size_t)bh * S + i] = eq_before;
-      const int above_i = (int)ws.above[((size_t)bh * S + i) * kBins + b1];
+      s_off[i] = off; s_eqb[i] = eq_before;
       const int take_eq = max(0, min(s_eq[i], k_eq - eq_before));
-      off += above_i + s_gt[i] + take_eq;
+      off += s_above[i] + s_gt[i] + take_eq;
       eq_before += s_eq[i];
     }
     ws.head[bh].key_t = key_t; ws.head[bh].k_eq = k_eq;
     n_sel[bh] = k;
+  }
+  __syncthreads();
+  if (tid < S) {
+    ws.slice_off[(size_t)bh * S + tid] = s_off[tid];
+    ws.slice_eq[(size_t)bh * S + tid] = s_eqb[tid];
   }
 }
 
