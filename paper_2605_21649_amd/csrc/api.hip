@@ -175,7 +175,7 @@ ekv_status ekv_select_gauss(const ekv_config* cfg, const float* mu, const float*
   Dims dm;
   const ekv_status s = make_dims(cfg, dm);
   if (s != EKV_OK) return s;
-  if (dm.ibeta == 0) return EKV_ERR_UNSUPPORTED;
+  if (dm.ibeta == 0 || !select_gauss_supported(dm)) return EKV_ERR_UNSUPPORTED;
   if (!ok_ptr4(mu) || !ok_ptr4(sigma) || !ok_ptr4(seq_lens) || !ok_ptr4(tau_hat) || !ok_ptr4(page_idx) ||
       !ok_ptr4(n_sel) || !ok_ptr4(overflow))
     return EKV_ERR_INVALID_ARG;

@@ -44,6 +44,7 @@ void launch_decode_sparse_softmax(const Dims& dm, const void* q, const ekv_cache
 
 size_t select_topk_ws_bytes(const Dims& dm);
 size_t select_gauss_ws_bytes(const Dims& dm);
+bool select_gauss_supported(const Dims& dm);
 size_t softmax_ws_bytes(const Dims& dm);
 
 }  // namespace ekv

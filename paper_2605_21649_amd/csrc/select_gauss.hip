@@ -5,39 +5,55 @@
 // keep the pages whose estimated maximum a*(mu_p + sigma_p*z_cnt) exceeds tau_hat - margin and write
 // them in ascending order.
 //
-// One evaluation of F costs an erfc and an exp per page, so the pages of a head are split over many
-// workgroups.  The root iteration is a fixed sequence of launches without host involvement: launch k
-// first advances the iteration state from the partial sums of launch k-1 (every workgroup repeats the
-// same few scalar operations), then evaluates its slice at the new tau; once converged the remaining
-// launches return at once.  A last kernel applies the selection rule.
+// One evaluation of F costs an exp and two short polynomials per page, so the pages of a head are split
+// over many workgroups.  The root iteration is a fixed sequence of launches without host involvement:
+// launch k first advances the iteration state from the partial sums of launch k-1 (every workgroup
+// repeats the same few scalar operations), then evaluates its slice at the new tau; once converged the
+// remaining launches return at once.  A head that has not converged after the last of them is finished
+// by one workgroup iterating alone (rare; that launch returns at once otherwise).  The selection rule is
+// then applied per slice of 4096 pages in parallel and the per-slice lists are concatenated in order.
 //
 // Root finding: F is positive, decreasing and convex.  The start is the root of the same equation for a
 // single Gaussian with the pooled mean and variance of all pages; the iteration is Newton on log F
-// kept inside a bracket [lo, hi] with F(lo) >= 1 > F(hi) (a step that leaves it is replaced by
-// bisection).  The left end a*mu_max - 1 is valid because cnt*E[(Y)_+^beta] >= cnt*(E Y)_+^beta >= 1
-// there (Jensen).
+// kept inside a bracket [lo, hi] with F(lo) >= 1 > F(hi) (a step that leaves it falls back to Newton on
+// F, then to bisection).  The left end a*mu_max - 1 is valid because cnt*E[(Y)_+^beta] >=
+// cnt*(E Y)_+^beta >= 1 there (Jensen).
 #include "ekv_select.h"
 #include "ekv_internal.h"
 
 namespace ekv {
 
+#include "trunc_tail_coeffs.inc"
+
 constexpr float kInvSqrt2 = 0.70710678118654752f;
 constexpr float kInvSqrt2Pi = 0.39894228040143268f;
 constexpr int kGaussEvalThreads = 256;
 constexpr int kGaussMaxSplits = 64;
-constexpr int kGaussIters = 8;            // evaluation launches per call (converged ones return at once)
+constexpr int kGaussIters = 6;            // evaluation launches per call (converged ones return at once)
+constexpr int kGsThreads = 256;           // selection slices: 256 threads x 16 pages
+constexpr int kGsItems = 16;
+constexpr int kGsSlice = kGsThreads * kGsItems;
+constexpr int kGsMaxSlices = 1024;
+
+template <int IV, int N>
+__device__ __forceinline__ float horner_tail(float s) {
+  float acc = kTailCoef[IV][N][kTailDeg];
+#pragma unroll
+  for (int k = kTailDeg - 1; k >= 0; --k) acc = fmaf(acc, s, kTailCoef[IV][N][k]);
+  return acc;
+}
 
 // h_n(t) = E[(t + Z)_+^n], Z ~ N(0,1), for n = NB and NB-1 (so that M_n = sigma^n h_n).
-// t >= -2.5: forward recurrence h_n = t h_{n-1} + (n-1) h_{n-2} from h_0 = Phi(t), h_1 = t Phi + phi.
-// t <  -2.5: the forward recurrence cancels catastrophically; the same three-term recurrence run
-// backwards from a high index (h_{n-2} = (h_n - t h_{n-1})/(n-1), all terms positive) and normalised
-// by h_0 = Phi(t) is stable there (Miller's algorithm).
+// t >= -2.5: forward recurrence h_n = t h_{n-1} + (n-1) h_{n-2} from h_0 = Phi(t), h_1 = t Phi + phi
+//            (the closed forms the paper prints for n = 1, 2, 3).
+// t <  -2.5: those forms cancel catastrophically in float32; there h_n(t) = phi(t) * |t|^-(n+1) * P_n(1/t^2)
+//            with fitted degree-8 polynomials (relative error 2e-7, see gen_trunc_tail_coeffs.py).
 template <int NB>
 __device__ __forceinline__ void trunc_h(float t, float& h_nb, float& h_nbm1) {
-  if (t < -13.f) { h_nb = 0.f; h_nbm1 = 0.f; return; }      // below float32 resolution of the sum
-  const float Phi = 0.5f * erfcf(-t * kInvSqrt2);
-  if (t >= -2.5f) {
-    const float phi = expf(-0.5f * t * t) * kInvSqrt2Pi;
+  if (t < -kTailXHi) { h_nb = 0.f; h_nbm1 = 0.f; return; }      // below float32 resolution of the sum
+  const float phi = expf(-0.5f * t * t) * kInvSqrt2Pi;
+  if (t >= -kTailXLo) {
+    const float Phi = 0.5f * erfcf(-t * kInvSqrt2);
     float h[5];
     h[0] = Phi;
     h[1] = fmaf(t, Phi, phi);
@@ -45,18 +61,20 @@ __device__ __forceinline__ void trunc_h(float t, float& h_nb, float& h_nbm1) {
     for (int n = 2; n <= NB; ++n) h[n] = fmaf(t, h[n - 1], (float)(n - 1) * h[n - 2]);
     h_nb = h[NB]; h_nbm1 = h[NB - 1];
   } else {
-    constexpr int N = 26;
-    float hn1 = 0.f, hn = 1.f;            // h_{n}, h_{n-1} at n = N + 1
-    float cap_nb = 0.f, cap_nbm1 = 0.f;
-#pragma unroll
-    for (int n = N + 1; n >= 2; --n) {
-      const float hm = (hn1 - t * hn) * (1.0f / (float)(n - 1));    // h_{n-2}
-      hn1 = hn; hn = hm;
-      if (n - 2 == NB) cap_nb = hn;
-      if (n - 2 == NB - 1) cap_nbm1 = hn;
+    const float inv = 1.0f / -t, u = inv * inv;
+    float p_nb, p_m1;
+    if (-t < kTailXSplit) {
+      const float s = (u - kTailMid[0]) * kTailInvHalf[0];
+      p_nb = horner_tail<0, NB>(s); p_m1 = horner_tail<0, NB - 1>(s);
+    } else {
+      const float s = (u - kTailMid[1]) * kTailInvHalf[1];
+      p_nb = horner_tail<1, NB>(s); p_m1 = horner_tail<1, NB - 1>(s);
     }
-    const float s = Phi / hn;             // hn = unnormalised h_0
-    h_nb = cap_nb * s; h_nbm1 = cap_nbm1 * s;
+    float ip = phi;                        // phi * x^-NB
+#pragma unroll
+    for (int i = 0; i < NB; ++i) ip *= inv;
+    h_nbm1 = ip * p_m1;
+    h_nb = ip * inv * p_nb;
   }
 }
 
@@ -84,19 +102,12 @@ __device__ __forceinline__ void page_mass(float muY, float sY, float cnt, float&
 // Iteration state of one (b,h): the point the next evaluation is taken at, and its bracket.
 struct GaussState { float tau, lo, hi; int done; };
 
-// workspace: state[2][BH], init partials [BH][S][4], eval partials [2][BH][S][2]
+// workspace: state[2][BH], init partials [BH][S][4], eval partials [2][BH][S][2],
+//            per selection slice: count [BH][NS] and page list [BH][NS][kGsSlice]
 struct GaussWs {
-  GaussState* state; float* init_part; float* eval_part; int S;
+  GaussState* state; float* init_part; float* eval_part; int32_t* sel_cnt; int32_t* sel_list;
+  int S, NS;
 };
-
-__device__ __forceinline__ float bcast_wave0_sum(float v, float* slot) {
-  // sum over the lanes of wavefront 0 (fixed order), broadcast to the block
-  v = wave_sum(v);
-  __syncthreads();
-  if (threadIdx.x == 0) *slot = v;
-  __syncthreads();
-  return *slot;
-}
 
 // Launch 0 of a call: slice partials of max a*mu and of the pooled first and second moments.
 __global__ __launch_bounds__(kGaussEvalThreads) void gauss_init_kernel(const float* __restrict__ mu,
@@ -128,21 +139,28 @@ __global__ __launch_bounds__(kGaussEvalThreads) void gauss_init_kernel(const flo
   }
 }
 
-// Scalar solve of n * sd^NB * h_NB((m - tau)/sd) = 1 (the pooled single-Gaussian model), started at `lo`.
+// Scalar solve of n * sd^NB * h_NB((m - tau)/sd) = 1 (the pooled single-Gaussian model): a starting point
+// for the real iteration, so a loose tolerance is enough.  Starts from the leading-order tail estimate
+// t0 = -sqrt(2 ln(n sd^NB)) and iterates Newton on the logarithm.
 template <int NB>
 __device__ float pooled_guess(float n, float m, float sd, float lo) {
-  float tau = lo, hi = INFINITY, l = lo;
-  for (int it = 0; it < 24; ++it) {
+  if (!(sd > 1e-20f)) return lo;
+  float sp = n;
+#pragma unroll
+  for (int i = 0; i < NB; ++i) sp *= sd;
+  float tau = sp > 1.f ? m + sd * sqrtf(2.f * __logf(sp)) : lo;
+  tau = fmaxf(tau, lo);
+  for (int it = 0; it < 8; ++it) {
     float f, d;
     page_mass<NB>(m - tau, sd, n, f, d);
     d *= (float)NB;
-    if (f >= 1.f) l = tau; else hi = tau;
-    float next = (f > 0.f && d > 0.f) ? tau + f * __logf(f) / d : 0.5f * (l + tau);
-    if (hi < INFINITY && !(next > l && next < hi)) next = 0.5f * (l + hi);
-    if (fabsf(next - tau) <= 1e-4f) { tau = next; break; }
+    if (!(f > 0.f && d > 0.f)) break;
+    const float next = fmaxf(tau + f * __logf(f) / d, lo);
+    const bool close = fabsf(next - tau) <= 1e-3f * sd;
     tau = next;
+    if (close) break;
   }
-  return fmaxf(tau, lo);
+  return tau;
 }
 
 // Advance the iteration state with the result (F, D = -dF/dtau) of the evaluation at st.tau.
@@ -161,6 +179,22 @@ __device__ __forceinline__ GaussState advance_state(GaussState st, float F, floa
   if (fabsf(next - st.tau) <= 3e-7f * fmaxf(1.f, fabsf(next))) st.done = 1;
   st.tau = next;
   return st;
+}
+
+// Sum of the S slice partials (F, D) of evaluation launch k, fixed order, broadcast to the block.
+__device__ __forceinline__ void sum_eval_partials(const GaussWs& ws, int k, int bh, int BH, float* bc, float& F,
+                                                  float& D) {
+  const int tid = threadIdx.x;
+  float f = 0.f, d = 0.f;
+  if (tid < ws.S) {
+    const float* o = ws.eval_part + (((size_t)(k & 1) * BH + bh) * ws.S + tid) * 2;
+    f = o[0]; d = o[1];
+  }
+  if (tid < 64) { f = wave_sum(f); d = wave_sum(d); }
+  __syncthreads();
+  if (tid == 0) { bc[0] = f; bc[1] = d; }
+  __syncthreads();
+  F = bc[0]; D = bc[1];
 }
 
 template <int NB>
@@ -192,16 +226,9 @@ __global__ __launch_bounds__(kGaussEvalThreads) void gauss_eval_kernel(const flo
     st.lo = mx - 1.0f; st.hi = INFINITY; st.done = 0;
     st.tau = pooled_guess<NB>(s0, mean, sqrtf(var), st.lo);
   } else {
-    st = ws.state[(size_t)((k - 1) & 1) * BH + bh];
-    float F = 0.f, D = 0.f;
-    if (tid < ws.S) {
-      const float* o = ws.eval_part + (((size_t)((k - 1) & 1) * BH + bh) * ws.S + tid) * 2;
-      F = o[0]; D = o[1];
-    }
-    if (tid < 64) { F = wave_sum(F); D = wave_sum(D); }
-    if (tid == 0) { bc[0] = F; bc[1] = D; }
-    __syncthreads();
-    st = advance_state(st, bc[0], (float)NB * bc[1]);
+    float F, D;
+    sum_eval_partials(ws, k - 1, bh, BH, bc, F, D);
+    st = advance_state(ws.state[(size_t)((k - 1) & 1) * BH + bh], F, (float)NB * D);
   }
   if (s == 0 && tid == 0) ws.state[(size_t)(k & 1) * BH + bh] = st;
   if (st.done) return;
@@ -225,63 +252,133 @@ __global__ __launch_bounds__(kGaussEvalThreads) void gauss_eval_kernel(const flo
   }
 }
 
-struct ZqTable { float z[65]; };   // z[c] = PhiInv(q_page^(1/c)), c = 1..64
-
-template <int NB, int ITEMS>
-__global__ __launch_bounds__(kSelThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void gauss_select_kernel(
-    const float* __restrict__ mu, const float* __restrict__ sigma, const int32_t* __restrict__ seq_lens,
-    GaussWs ws, ZqTable zq, float margin, float a, float* __restrict__ tau_hat, int32_t* __restrict__ page_idx,
-    int32_t* __restrict__ n_sel, int32_t* __restrict__ overflow, int Hq, int P, int Mmax, int cap, int BH) {
-  __shared__ SelectShared sh;
-  __shared__ float bc[2];
+// After the last evaluation launch: final state of every head goes to state[kGaussIters & 1].  A head that
+// has not converged is iterated to convergence here by one workgroup evaluating all pages itself.
+template <int NB>
+__global__ __launch_bounds__(kSelThreads) void gauss_finish_kernel(const float* __restrict__ mu,
+                                                                   const float* __restrict__ sigma,
+                                                                   const int32_t* __restrict__ seq_lens, GaussWs ws,
+                                                                   float a, float* __restrict__ tau_hat, int Hq, int P,
+                                                                   int Mmax, int BH) {
+  __shared__ float bc[4];
+  __shared__ float red_f[kSelWaves];
   const int bh = blockIdx.x, b = bh / Hq, tid = threadIdx.x;
   const int n = seq_lens[b];
   const int M = (n + P - 1) / P;
-  if (M <= 0) { if (tid == 0) { n_sel[bh] = 0; overflow[bh] = 0; tau_hat[bh] = 0.f; } return; }
-  const int cnt_last = n - (M - 1) * P;
+  const float cnt_last = (float)(n - (M - 1) * P);
+  float F, D;
+  sum_eval_partials(ws, kGaussIters - 1, bh, BH, bc, F, D);
+  GaussState st = advance_state(ws.state[(size_t)((kGaussIters - 1) & 1) * BH + bh], F, (float)NB * D);
+  for (int it = 0; it < 48 && !st.done; ++it) {
+    float f = 0.f, d = 0.f;
+    for (int p = tid; p < M; p += kSelThreads) {
+      float fp, dp;
+      page_mass<NB>(fmaf(a, mu[(size_t)bh * Mmax + p], -st.tau), a * sigma[(size_t)bh * Mmax + p],
+                    p == M - 1 ? cnt_last : (float)P, fp, dp);
+      f += fp; d += dp;
+    }
+    const float Fs = block_sum(f, red_f);
+    const float Ds = block_sum(d, red_f);
+    st = advance_state(st, Fs, (float)NB * Ds);
+  }
+  if (tid == 0) {
+    st.done = 1;
+    ws.state[(size_t)(kGaussIters & 1) * BH + bh] = st;
+    tau_hat[bh] = st.tau;
+  }
+}
+
+struct ZqTable { float z[65]; };   // z[c] = PhiInv(q_page^(1/c)), c = 1..64
+
+// Selection rule on one slice of 4096 pages: passing pages in ascending order + their count.
+__global__ __launch_bounds__(kGsThreads) void gauss_mark_kernel(const float* __restrict__ mu,
+                                                                const float* __restrict__ sigma,
+                                                                const int32_t* __restrict__ seq_lens, GaussWs ws,
+                                                                ZqTable zq, float margin, float a, int Hq, int P,
+                                                                int Mmax, int BH) {
+  __shared__ int wcnt[kGsThreads / 64];
+  const int bh = blockIdx.y, slice = blockIdx.x, b = bh / Hq, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int n = seq_lens[b];
+  const int M = (n + P - 1) / P;
+  int32_t* cnt_out = ws.sel_cnt + (size_t)bh * ws.NS + slice;
+  if (slice * kGsSlice >= M) { if (tid == 0) *cnt_out = 0; return; }
+  const float thr = ws.state[(size_t)(kGaussIters & 1) * BH + bh].tau - margin;
+  const float z_full = zq.z[P], z_last = zq.z[n - (M - 1) * P];
   const float* mu_r = mu + (size_t)bh * Mmax;
   const float* sg_r = sigma + (size_t)bh * Mmax;
-
-  // last state update (the evaluation of launch kGaussIters-1)
-  constexpr int kl = kGaussIters - 1;
-  GaussState st = ws.state[(size_t)(kl & 1) * BH + bh];
-  float F = 0.f, D = 0.f;
-  if (tid < ws.S) {
-    const float* o = ws.eval_part + (((size_t)(kl & 1) * BH + bh) * ws.S + tid) * 2;
-    F = o[0]; D = o[1];
-  }
-  if (tid < 64) { F = wave_sum(F); D = wave_sum(D); }
-  if (tid == 0) { bc[0] = F; bc[1] = D; }
-  __syncthreads();
-  st = advance_state(st, bc[0], (float)NB * bc[1]);
-  const float tau = st.tau;
-  if (tid == 0) tau_hat[bh] = tau;
-
-  // selection: keep p iff a*(mu_p + sigma_p z_cnt) > tau - margin
-  const float thr = tau - margin;
-  const float z_full = zq.z[P], z_last = zq.z[cnt_last];
-  auto keyfn = [=](int p) { return float_to_key(a * fmaf(sg_r[p], p == M - 1 ? z_last : z_full, mu_r[p])); };
-  KeySet<ITEMS, decltype(keyfn)> ks(keyfn, M);
-  const uint32_t kthr = float_to_key(thr);      // > 0, so empty slots (key 0) never pass
+  const int page0 = slice * kGsSlice + w * (kGsSlice / (kGsThreads / 64)) + lane;
+  float mv[kGsItems], sv[kGsItems];
+#pragma unroll
+  for (int i = 0; i < kGsItems; ++i) { const int p = min(page0 + i * 64, M - 1); mv[i] = mu_r[p]; sv[i] = sg_r[p]; }
+  uint32_t pass = 0;
   int c = 0;
 #pragma unroll
-  for (int i = 0; i < (ITEMS ? ITEMS : ks.items); ++i) c += ks.key(i) > kthr;
-  const int count = block_sum_i(c, sh.scan_buf);
-  int32_t* out = page_idx + (size_t)bh * cap;
-  int n_out, ovf = 0;
-  if (count >= 1 && count <= cap) {
-    compact_ordered(ks, kthr, 0, sh, out);
-    n_out = count;
-  } else {
-    // nothing passed: the single best page; too many: the cap best pages (lower index on ties)
-    const int k = count == 0 ? 1 : cap;
-    ovf = count > cap;
-    uint32_t vT; int k_eq;
-    radix_select_kth(ks, k, sh, vT, k_eq);
-    compact_ordered(ks, vT, k_eq, sh, out);
-    n_out = k;
+  for (int i = 0; i < kGsItems; ++i) {
+    const int p = page0 + i * 64;
+    const bool in = p < M && a * fmaf(sv[i], p == M - 1 ? z_last : z_full, mv[i]) > thr;
+    pass |= (uint32_t)in << i;
+    c += in;
   }
-  if (tid == 0) { n_sel[bh] = n_out; overflow[bh] = ovf; }
+  c = wave_sum_i(c);
+  if (lane == 0) wcnt[w] = c;
+  __syncthreads();
+  int o_run = 0, tot = 0;
+  for (int i = 0; i < kGsThreads / 64; ++i) { if (i < w) o_run += wcnt[i]; tot += wcnt[i]; }
+  int32_t* list = ws.sel_list + ((size_t)bh * ws.NS + slice) * kGsSlice;
+  const uint64_t lt = (1ull << lane) - 1ull;
+#pragma unroll
+  for (int i = 0; i < kGsItems; ++i) {
+    const bool in = (pass >> i) & 1u;
+    const uint64_t mk = __ballot(in);
+    if (in) list[o_run + __popcll(mk & lt)] = page0 + i * 64;
+    o_run += __popcll(mk);
+  }
+  if (tid == 0) *cnt_out = tot;
+}
+
+// Concatenates the slice lists in order.  Nothing passed -> the single best page; more than cap pages ->
+// the cap best estimates (lower index on ties), flagged: both by exact selection over all pages.
+template <int ITEMS>
+__global__ __launch_bounds__(kSelThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void gauss_gather_kernel(
+    const float* __restrict__ mu, const float* __restrict__ sigma, const int32_t* __restrict__ seq_lens,
+    GaussWs ws, ZqTable zq, float a, int32_t* __restrict__ page_idx, int32_t* __restrict__ n_sel,
+    int32_t* __restrict__ overflow, int Hq, int P, int Mmax, int cap) {
+  __shared__ SelectShared sh;
+  __shared__ int s_off[kGsMaxSlices + 1];
+  const int bh = blockIdx.x, b = bh / Hq, tid = threadIdx.x;
+  const int n = seq_lens[b];
+  const int M = (n + P - 1) / P;
+  int32_t* out = page_idx + (size_t)bh * cap;
+  if (M <= 0) { if (tid == 0) { n_sel[bh] = 0; overflow[bh] = 0; } return; }
+  const int NS = ws.NS;
+  for (int i = tid; i < NS; i += kSelThreads) s_off[i] = ws.sel_cnt[(size_t)bh * NS + i];
+  __syncthreads();
+  if (tid == 0) {
+    int run = 0;
+    for (int i = 0; i < NS; ++i) { const int c = s_off[i]; s_off[i] = run; run += c; }
+    s_off[NS] = run;
+  }
+  __syncthreads();
+  const int count = s_off[NS];
+  if (count >= 1 && count <= cap) {
+    for (int sl = 0; sl < NS; ++sl) {
+      const int o = s_off[sl], c = s_off[sl + 1] - o;
+      const int32_t* list = ws.sel_list + ((size_t)bh * NS + sl) * kGsSlice;
+      for (int i = tid; i < c; i += kSelThreads) out[o + i] = list[i];
+    }
+    if (tid == 0) { n_sel[bh] = count; overflow[bh] = 0; }
+    return;
+  }
+  const float z_full = zq.z[P], z_last = zq.z[n - (M - 1) * P];
+  const float* mu_r = mu + (size_t)bh * Mmax;
+  const float* sg_r = sigma + (size_t)bh * Mmax;
+  auto keyfn = [=](int p) { return float_to_key(a * fmaf(sg_r[p], p == M - 1 ? z_last : z_full, mu_r[p])); };
+  KeySet<ITEMS, decltype(keyfn)> ks(keyfn, M);
+  const int k = count == 0 ? 1 : cap;
+  uint32_t vT; int k_eq;
+  radix_select_kth(ks, k, sh, vT, k_eq);
+  compact_ordered(ks, vT, k_eq, sh, out);
+  if (tid == 0) { n_sel[bh] = k; overflow[bh] = count > cap; }
 }
 
 static int gauss_splits(const Dims& dm) {
@@ -293,12 +390,16 @@ static int gauss_splits(const Dims& dm) {
   if (S < 1) S = 1;
   return S;
 }
+static int gauss_sel_slices(const Dims& dm) { return (dm.Mmax + kGsSlice - 1) / kGsSlice; }
 
 size_t select_gauss_ws_bytes(const Dims& dm) {
-  const size_t BH = (size_t)dm.B * dm.Hq, S = gauss_splits(dm);
-  size_t b = 2 * BH * sizeof(GaussState) + BH * S * 4 * sizeof(float) + 2 * BH * S * 2 * sizeof(float);
+  const size_t BH = (size_t)dm.B * dm.Hq, S = gauss_splits(dm), NS = gauss_sel_slices(dm);
+  size_t b = 2 * BH * sizeof(GaussState) + BH * S * 4 * sizeof(float) + 2 * BH * S * 2 * sizeof(float) +
+             BH * NS * sizeof(int32_t) + BH * NS * kGsSlice * sizeof(int32_t);
   return (b + 255) & ~(size_t)255;
 }
+
+bool select_gauss_supported(const Dims& dm) { return gauss_sel_slices(dm) <= kGsMaxSlices; }
 
 template <int NB>
 static void launch_gauss_NB(const Dims& dm, const float* mu, const float* sigma, const int32_t* seq_lens,
@@ -310,15 +411,18 @@ static void launch_gauss_NB(const Dims& dm, const float* mu, const float* sigma,
   for (int k = 0; k < kGaussIters; ++k)
     hipLaunchKernelGGL(gauss_eval_kernel<NB>, egrid, eblock, 0, st, mu, sigma, seq_lens, ws, k, dm.a, dm.Hq, dm.P,
                        dm.Mmax, BH);
-  dim3 sgrid(BH), sblock(kSelThreads);
-#define EKV_GSEL(ITEMS)                                                                                         \
-  hipLaunchKernelGGL((gauss_select_kernel<NB, ITEMS>), sgrid, sblock, 0, st, mu, sigma, seq_lens, ws, zq, margin, \
-                     dm.a, tau_hat, page_idx, n_sel, overflow, dm.Hq, dm.P, dm.Mmax, dm.cap, BH)
-  if (dm.Mmax <= 4 * kSelThreads) EKV_GSEL(4);
-  else if (dm.Mmax <= 16 * kSelThreads) EKV_GSEL(16);
-  else if (dm.Mmax <= 64 * kSelThreads) EKV_GSEL(64);
-  else EKV_GSEL(0);
-#undef EKV_GSEL
+  dim3 hgrid(BH), hblock(kSelThreads);
+  hipLaunchKernelGGL(gauss_finish_kernel<NB>, hgrid, hblock, 0, st, mu, sigma, seq_lens, ws, dm.a, tau_hat, dm.Hq,
+                     dm.P, dm.Mmax, BH);
+  hipLaunchKernelGGL(gauss_mark_kernel, dim3(ws.NS, BH), dim3(kGsThreads), 0, st, mu, sigma, seq_lens, ws, zq, margin,
+                     dm.a, dm.Hq, dm.P, dm.Mmax, BH);
+#define EKV_GGATHER(ITEMS)                                                                                          \
+  hipLaunchKernelGGL(gauss_gather_kernel<ITEMS>, hgrid, hblock, 0, st, mu, sigma, seq_lens, ws, zq, dm.a, page_idx, \
+                     n_sel, overflow, dm.Hq, dm.P, dm.Mmax, dm.cap)
+  if (dm.Mmax <= 4 * kSelThreads) EKV_GGATHER(4);
+  else if (dm.Mmax <= 16 * kSelThreads) EKV_GGATHER(16);
+  else EKV_GGATHER(0);
+#undef EKV_GGATHER
 }
 
 void launch_select_gauss(const Dims& dm, const float* mu, const float* sigma, const int32_t* seq_lens,
@@ -329,9 +433,12 @@ void launch_select_gauss(const Dims& dm, const float* mu, const float* sigma, co
   const size_t BH = (size_t)dm.B * dm.Hq;
   GaussWs ws;
   ws.S = gauss_splits(dm);
+  ws.NS = gauss_sel_slices(dm);
   ws.state = (GaussState*)workspace;
   ws.init_part = (float*)(ws.state + 2 * BH);
   ws.eval_part = ws.init_part + BH * ws.S * 4;
+  ws.sel_cnt = (int32_t*)(ws.eval_part + 2 * BH * ws.S * 2);
+  ws.sel_list = ws.sel_cnt + BH * ws.NS;
   switch (dm.ibeta) {
     case 1: launch_gauss_NB<1>(dm, mu, sigma, seq_lens, zq, margin, tau_hat, page_idx, n_sel, overflow, ws, st); break;
     case 2: launch_gauss_NB<2>(dm, mu, sigma, seq_lens, zq, margin, tau_hat, page_idx, n_sel, overflow, ws, st); break;
