@@ -9,9 +9,9 @@
 // over many workgroups.  The root iteration is a fixed sequence of launches without host involvement:
 // launch k first advances the iteration state from the partial sums of launch k-1 (every workgroup
 // repeats the same few scalar operations), then evaluates its slice at the new tau; once converged the
-// remaining launches return at once.  A head that has not converged after the last of them is finished
-// by one workgroup iterating alone (rare; that launch returns at once otherwise).  The selection rule is
-// then applied per slice of 4096 pages in parallel and the per-slice lists are concatenated in order.
+// remaining launches return at once.  The selection rule is then applied per slice of 4096 pages in
+// parallel and the per-slice lists are concatenated in order; a head that has not converged by then is
+// finished by the concatenating workgroup iterating alone (rare).
 //
 // Root finding: F is positive, decreasing and convex.  The start is the root of the same equation for a
 // single Gaussian with the pooled mean and variance of all pages; the iteration is Newton on log F
@@ -29,7 +29,7 @@ constexpr float kInvSqrt2 = 0.70710678118654752f;
 constexpr float kInvSqrt2Pi = 0.39894228040143268f;
 constexpr int kGaussEvalThreads = 256;
 constexpr int kGaussMaxSplits = 64;
-constexpr int kGaussIters = 6;            // evaluation launches per call (converged ones return at once)
+constexpr int kGaussIters = 5;            // evaluation launches per call (converged ones return at once)
 constexpr int kGsThreads = 256;           // selection slices: 256 threads x 16 pages
 constexpr int kGsItems = 16;
 constexpr int kGsSlice = kGsThreads * kGsItems;
@@ -235,12 +235,23 @@ __global__ __launch_bounds__(kGaussEvalThreads) void gauss_eval_kernel(const flo
 
   const int per = (M + ws.S - 1) / ws.S;
   const int p0 = s * per, p1 = min(p0 + per, M);
+  const float* mu_r = mu + (size_t)bh * Mmax;
+  const float* sg_r = sigma + (size_t)bh * Mmax;
   float f = 0.f, d = 0.f;
-  for (int p = p0 + tid; p < p1; p += kGaussEvalThreads) {
-    float fp, dp;
-    page_mass<NB>(fmaf(a, mu[(size_t)bh * Mmax + p], -st.tau), a * sigma[(size_t)bh * Mmax + p],
-                  p == M - 1 ? cnt_last : (float)P, fp, dp);
-    f += fp; d += dp;
+  for (int pb = p0 + tid; pb < p1; pb += 4 * kGaussEvalThreads) {     // 4 pages per lane and batch
+    float mv[4], sv[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int p = min(pb + j * kGaussEvalThreads, M - 1);           // clamped: loads stay unconditional
+      mv[j] = mu_r[p]; sv[j] = sg_r[p];
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int p = pb + j * kGaussEvalThreads;
+      float fp, dp;
+      page_mass<NB>(fmaf(a, mv[j], -st.tau), a * sv[j], p == M - 1 ? cnt_last : (float)P, fp, dp);
+      if (p < p1) { f += fp; d += dp; }
+    }
   }
   f = wave_sum(f); d = wave_sum(d);
   if ((tid & 63) == 0) { red[tid >> 6][0] = f; red[tid >> 6][1] = d; }
@@ -252,57 +263,34 @@ __global__ __launch_bounds__(kGaussEvalThreads) void gauss_eval_kernel(const flo
   }
 }
 
-// After the last evaluation launch: final state of every head goes to state[kGaussIters & 1].  A head that
-// has not converged is iterated to convergence here by one workgroup evaluating all pages itself.
-template <int NB>
-__global__ __launch_bounds__(kSelThreads) void gauss_finish_kernel(const float* __restrict__ mu,
-                                                                   const float* __restrict__ sigma,
-                                                                   const int32_t* __restrict__ seq_lens, GaussWs ws,
-                                                                   float a, float* __restrict__ tau_hat, int Hq, int P,
-                                                                   int Mmax, int BH) {
-  __shared__ float bc[4];
-  __shared__ float red_f[kSelWaves];
-  const int bh = blockIdx.x, b = bh / Hq, tid = threadIdx.x;
-  const int n = seq_lens[b];
-  const int M = (n + P - 1) / P;
-  const float cnt_last = (float)(n - (M - 1) * P);
-  float F, D;
-  sum_eval_partials(ws, kGaussIters - 1, bh, BH, bc, F, D);
-  GaussState st = advance_state(ws.state[(size_t)((kGaussIters - 1) & 1) * BH + bh], F, (float)NB * D);
-  for (int it = 0; it < 48 && !st.done; ++it) {
-    float f = 0.f, d = 0.f;
-    for (int p = tid; p < M; p += kSelThreads) {
-      float fp, dp;
-      page_mass<NB>(fmaf(a, mu[(size_t)bh * Mmax + p], -st.tau), a * sigma[(size_t)bh * Mmax + p],
-                    p == M - 1 ? cnt_last : (float)P, fp, dp);
-      f += fp; d += dp;
-    }
-    const float Fs = block_sum(f, red_f);
-    const float Ds = block_sum(d, red_f);
-    st = advance_state(st, Fs, (float)NB * Ds);
-  }
-  if (tid == 0) {
-    st.done = 1;
-    ws.state[(size_t)(kGaussIters & 1) * BH + bh] = st;
-    tau_hat[bh] = st.tau;
-  }
-}
-
 struct ZqTable { float z[65]; };   // z[c] = PhiInv(q_page^(1/c)), c = 1..64
 
-// Selection rule on one slice of 4096 pages: passing pages in ascending order + their count.
+// Selection rule on one slice of 4096 pages: passing pages in ascending order + their count.  Every
+// workgroup first takes the last state update itself (a few scalar operations); the slice-0 workgroup
+// publishes it.  If the iteration has not converged the head is left to the gather kernel (count -1).
 __global__ __launch_bounds__(kGsThreads) void gauss_mark_kernel(const float* __restrict__ mu,
                                                                 const float* __restrict__ sigma,
                                                                 const int32_t* __restrict__ seq_lens, GaussWs ws,
-                                                                ZqTable zq, float margin, float a, int Hq, int P,
-                                                                int Mmax, int BH) {
+                                                                ZqTable zq, float margin, float a, int nb,
+                                                                float* __restrict__ tau_hat, int Hq, int P, int Mmax,
+                                                                int BH) {
   __shared__ int wcnt[kGsThreads / 64];
+  __shared__ float bc[4];
   const int bh = blockIdx.y, slice = blockIdx.x, b = bh / Hq, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int n = seq_lens[b];
   const int M = (n + P - 1) / P;
   int32_t* cnt_out = ws.sel_cnt + (size_t)bh * ws.NS + slice;
+  if (M <= 0) { if (tid == 0) *cnt_out = 0; return; }
+  float F, D;
+  sum_eval_partials(ws, kGaussIters - 1, bh, BH, bc, F, D);
+  const GaussState st = advance_state(ws.state[(size_t)((kGaussIters - 1) & 1) * BH + bh], F, (float)nb * D);
+  if (slice == 0 && tid == 0) {
+    ws.state[(size_t)(kGaussIters & 1) * BH + bh] = st;
+    if (st.done) tau_hat[bh] = st.tau;
+  }
+  if (!st.done) { if (tid == 0) *cnt_out = -1; return; }
   if (slice * kGsSlice >= M) { if (tid == 0) *cnt_out = 0; return; }
-  const float thr = ws.state[(size_t)(kGaussIters & 1) * BH + bh].tau - margin;
+  const float thr = st.tau - margin;
   const float z_full = zq.z[P], z_last = zq.z[n - (M - 1) * P];
   const float* mu_r = mu + (size_t)bh * Mmax;
   const float* sg_r = sigma + (size_t)bh * Mmax;
@@ -336,44 +324,76 @@ __global__ __launch_bounds__(kGsThreads) void gauss_mark_kernel(const float* __r
   if (tid == 0) *cnt_out = tot;
 }
 
-// Concatenates the slice lists in order.  Nothing passed -> the single best page; more than cap pages ->
-// the cap best estimates (lower index on ties), flagged: both by exact selection over all pages.
-template <int ITEMS>
+// Concatenates the slice lists in order.  Rare cases are handled here by one workgroup per head over all
+// pages: an iteration that has not converged is continued to convergence; nothing passed -> the single
+// best page; more than cap pages -> the cap best estimates (lower index on ties), flagged.
+template <int NB, int ITEMS>
 __global__ __launch_bounds__(kSelThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void gauss_gather_kernel(
     const float* __restrict__ mu, const float* __restrict__ sigma, const int32_t* __restrict__ seq_lens,
-    GaussWs ws, ZqTable zq, float a, int32_t* __restrict__ page_idx, int32_t* __restrict__ n_sel,
-    int32_t* __restrict__ overflow, int Hq, int P, int Mmax, int cap) {
+    GaussWs ws, ZqTable zq, float margin, float a, float* __restrict__ tau_hat, int32_t* __restrict__ page_idx,
+    int32_t* __restrict__ n_sel, int32_t* __restrict__ overflow, int Hq, int P, int Mmax, int cap, int BH) {
   __shared__ SelectShared sh;
   __shared__ int s_off[kGsMaxSlices + 1];
+  __shared__ float red_f[kSelWaves];
   const int bh = blockIdx.x, b = bh / Hq, tid = threadIdx.x;
   const int n = seq_lens[b];
   const int M = (n + P - 1) / P;
   int32_t* out = page_idx + (size_t)bh * cap;
-  if (M <= 0) { if (tid == 0) { n_sel[bh] = 0; overflow[bh] = 0; } return; }
+  if (M <= 0) { if (tid == 0) { n_sel[bh] = 0; overflow[bh] = 0; tau_hat[bh] = 0.f; } return; }
   const int NS = ws.NS;
-  for (int i = tid; i < NS; i += kSelThreads) s_off[i] = ws.sel_cnt[(size_t)bh * NS + i];
-  __syncthreads();
-  if (tid == 0) {
-    int run = 0;
-    for (int i = 0; i < NS; ++i) { const int c = s_off[i]; s_off[i] = run; run += c; }
-    s_off[NS] = run;
-  }
-  __syncthreads();
-  const int count = s_off[NS];
-  if (count >= 1 && count <= cap) {
-    for (int sl = 0; sl < NS; ++sl) {
-      const int o = s_off[sl], c = s_off[sl + 1] - o;
-      const int32_t* list = ws.sel_list + ((size_t)bh * NS + sl) * kGsSlice;
-      for (int i = tid; i < c; i += kSelThreads) out[o + i] = list[i];
+  GaussState st = ws.state[(size_t)(kGaussIters & 1) * BH + bh];
+  int count = -1;
+  if (st.done) {
+    for (int i = tid; i < NS; i += kSelThreads) s_off[i] = ws.sel_cnt[(size_t)bh * NS + i];
+    __syncthreads();
+    if (tid == 0) {
+      int run = 0;
+      for (int i = 0; i < NS; ++i) { const int c = s_off[i]; s_off[i] = run; run += c; }
+      s_off[NS] = run;
     }
-    if (tid == 0) { n_sel[bh] = count; overflow[bh] = 0; }
-    return;
+    __syncthreads();
+    count = s_off[NS];
+    if (count >= 1 && count <= cap) {
+      // output position j belongs to the slice sl with s_off[sl] <= j < s_off[sl+1]
+      for (int j = tid; j < count; j += kSelThreads) {
+        int lo = 0, hi = NS;                               // invariant: s_off[lo] <= j < s_off[hi]
+        while (hi - lo > 1) { const int mid = (lo + hi) >> 1; if (s_off[mid] <= j) lo = mid; else hi = mid; }
+        out[j] = ws.sel_list[((size_t)bh * NS + lo) * kGsSlice + (j - s_off[lo])];
+      }
+      if (tid == 0) { n_sel[bh] = count; overflow[bh] = 0; }
+      return;
+    }
   }
-  const float z_full = zq.z[P], z_last = zq.z[n - (M - 1) * P];
+  const float cnt_last = (float)(n - (M - 1) * P);
   const float* mu_r = mu + (size_t)bh * Mmax;
   const float* sg_r = sigma + (size_t)bh * Mmax;
+  for (int it = 0; it < 64 && !st.done; ++it) {            // finish the root iteration alone
+    float f = 0.f, d = 0.f;
+    for (int p = tid; p < M; p += kSelThreads) {
+      float fp, dp;
+      page_mass<NB>(fmaf(a, mu_r[p], -st.tau), a * sg_r[p], p == M - 1 ? cnt_last : (float)P, fp, dp);
+      f += fp; d += dp;
+    }
+    const float Fs = block_sum(f, red_f);
+    const float Ds = block_sum(d, red_f);
+    st = advance_state(st, Fs, (float)NB * Ds);
+  }
+  if (tid == 0) tau_hat[bh] = st.tau;
+  const float z_full = zq.z[P], z_last = zq.z[n - (M - 1) * P];
   auto keyfn = [=](int p) { return float_to_key(a * fmaf(sg_r[p], p == M - 1 ? z_last : z_full, mu_r[p])); };
   KeySet<ITEMS, decltype(keyfn)> ks(keyfn, M);
+  if (count < 0) {                                         // the slices were not marked: count here
+    const uint32_t kthr = float_to_key(st.tau - margin);
+    int c = 0;
+#pragma unroll
+    for (int i = 0; i < (ITEMS ? ITEMS : ks.items); ++i) c += ks.key(i) > kthr;
+    count = block_sum_i(c, sh.scan_buf);
+    if (count >= 1 && count <= cap) {
+      compact_ordered(ks, kthr, 0, sh, out);
+      if (tid == 0) { n_sel[bh] = count; overflow[bh] = 0; }
+      return;
+    }
+  }
   const int k = count == 0 ? 1 : cap;
   uint32_t vT; int k_eq;
   radix_select_kth(ks, k, sh, vT, k_eq);
@@ -412,13 +432,11 @@ static void launch_gauss_NB(const Dims& dm, const float* mu, const float* sigma,
     hipLaunchKernelGGL(gauss_eval_kernel<NB>, egrid, eblock, 0, st, mu, sigma, seq_lens, ws, k, dm.a, dm.Hq, dm.P,
                        dm.Mmax, BH);
   dim3 hgrid(BH), hblock(kSelThreads);
-  hipLaunchKernelGGL(gauss_finish_kernel<NB>, hgrid, hblock, 0, st, mu, sigma, seq_lens, ws, dm.a, tau_hat, dm.Hq,
-                     dm.P, dm.Mmax, BH);
   hipLaunchKernelGGL(gauss_mark_kernel, dim3(ws.NS, BH), dim3(kGsThreads), 0, st, mu, sigma, seq_lens, ws, zq, margin,
-                     dm.a, dm.Hq, dm.P, dm.Mmax, BH);
+                     dm.a, NB, tau_hat, dm.Hq, dm.P, dm.Mmax, BH);
 #define EKV_GGATHER(ITEMS)                                                                                          \
-  hipLaunchKernelGGL(gauss_gather_kernel<ITEMS>, hgrid, hblock, 0, st, mu, sigma, seq_lens, ws, zq, dm.a, page_idx, \
-                     n_sel, overflow, dm.Hq, dm.P, dm.Mmax, dm.cap)
+  hipLaunchKernelGGL((gauss_gather_kernel<NB, ITEMS>), hgrid, hblock, 0, st, mu, sigma, seq_lens, ws, zq, margin, dm.a, \
+                     tau_hat, page_idx, n_sel, overflow, dm.Hq, dm.P, dm.Mmax, dm.cap, BH)
   if (dm.Mmax <= 4 * kSelThreads) EKV_GGATHER(4);
   else if (dm.Mmax <= 16 * kSelThreads) EKV_GGATHER(16);
   else EKV_GGATHER(0);

@@ -14,8 +14,8 @@
 //                                         gathered and ranked exactly -> the k-th key, the tie quota and the
 //                                         output offset of every slice;
 //   compact  (slices x heads workgroups)  ordered compaction of each slice against that key.
-// If the bin of the k-th key holds more members than the ranking list, the heads concerned are redone by
-// the single-workgroup algorithm (a fourth launch whose workgroups return at once otherwise).
+// If the bin of the k-th key holds more members than the ranking list (massive ties), the find workgroup
+// does that head by the single-workgroup algorithm itself and the compaction launch skips it.
 #include "ekv_select.h"
 #include "ekv_internal.h"
 
@@ -170,8 +170,9 @@ __global__ __launch_bounds__(kTkThreads) void topk_hist_kernel(const float* __re
 
 __global__ __launch_bounds__(kSelThreads) void topk_find_kernel(const float* __restrict__ box,
                                                                 const int32_t* __restrict__ seq_lens, int k_pages,
-                                                                TopkWs ws, int32_t* __restrict__ n_sel, int Hq, int P,
-                                                                int Mmax, int cap) {
+                                                                TopkWs ws, int32_t* __restrict__ page_idx,
+                                                                int32_t* __restrict__ n_sel, int Hq, int P, int Mmax,
+                                                                int cap) {
   __shared__ uint32_t tot_above[kBins];                // summed over the slices
   __shared__ uint32_t mem_key[kTkMembers];
   __shared__ int32_t mem_page[kTkMembers];
@@ -214,19 +215,21 @@ __global__ __launch_bounds__(kSelThreads) void topk_find_kernel(const float* __r
   __syncthreads();
   const int b1 = s_bin, m = s_cnt;
   const int k_rem = k - (int)tot_above[b1];            // rank of the answer inside bin b1 (1-based)
-  if (m > kTkMembers) {                                // too many (near-)ties for the ranking list
-    if (tid == 0) ws.head[bh].redo = 1;
+  if (m > kTkMembers) {                                // too many (near-)ties for the ranking list:
+    if (tid == 0) ws.head[bh].redo = 1;                // this head is done here by the single-workgroup
+    __shared__ SelectShared sh;                        // algorithm and skipped by the compaction launch
+    topk_single<0>(box, seq_lens, k_pages, page_idx, n_sel, Hq, P, Mmax, cap, sh);
     return;
   }
-  // gather the members of bin b1: one scan of the scores in batches of 16 clamped loads per lane
+  // gather the members of bin b1: one scan of the scores in batches of 32 clamped loads per lane
   const int per_wave = ((M + kSelWaves - 1) / kSelWaves + 63) & ~63;
   const int wbase = (tid >> 6) * per_wave + (tid & 63);
-  for (int i0 = 0; i0 < per_wave; i0 += 16 * 64) {
-    float raw[16];
+  for (int i0 = 0; i0 < per_wave; i0 += 32 * 64) {
+    float raw[32];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) raw[i] = s[min(wbase + i0 + i * 64, M - 1)];
+    for (int i = 0; i < 32; ++i) raw[i] = s[min(wbase + i0 + i * 64, M - 1)];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
+    for (int i = 0; i < 32; ++i) {
       const int p = wbase + i0 + i * 64;
       const uint32_t kk = float_to_key(raw[i]);
       if (i0 + i * 64 < per_wave && p < M && topk_bin(kk, hd.lo, hd.shift) == b1) {
@@ -328,18 +331,6 @@ __global__ __launch_bounds__(kTkThreads) void topk_compact_kernel(const float* _
   }
 }
 
-// Heads flagged by the find kernel are redone from scratch by the single-workgroup algorithm (scores
-// re-read from memory in every pass).
-__global__ __launch_bounds__(kSelThreads) void select_topk_redo_kernel(const float* __restrict__ box,
-                                                                       const int32_t* __restrict__ seq_lens,
-                                                                       int k_pages, int32_t* __restrict__ page_idx,
-                                                                       int32_t* __restrict__ n_sel, TopkWs ws, int Hq,
-                                                                       int P, int Mmax, int cap) {
-  __shared__ SelectShared sh;
-  if (ws.head[blockIdx.x].redo == 0) return;
-  topk_single<0>(box, seq_lens, k_pages, page_idx, n_sel, Hq, P, Mmax, cap, sh);
-}
-
 static int topk_slices(const Dims& dm) { return (dm.Mmax + kTkSlice - 1) / kTkSlice; }
 static bool topk_sliced(const Dims& dm) { return dm.Mmax > 16 * kSelThreads && topk_slices(dm) <= kTkMaxSlices; }
 
@@ -372,12 +363,10 @@ void launch_select_topk(const Dims& dm, const float* box, const int32_t* seq_len
   ws.slice_eq = ws.slice_off + BH * ws.S;
   dim3 sgrid(ws.S, dm.B * dm.Hq), sblock(kTkThreads);
   hipLaunchKernelGGL(topk_hist_kernel, sgrid, sblock, 0, st, box, seq_lens, ws, dm.Hq, dm.P, dm.Mmax);
-  hipLaunchKernelGGL(topk_find_kernel, grid, block, 0, st, box, seq_lens, k_pages, ws, n_sel, dm.Hq, dm.P, dm.Mmax,
-                     dm.cap);
+  hipLaunchKernelGGL(topk_find_kernel, grid, block, 0, st, box, seq_lens, k_pages, ws, page_idx, n_sel, dm.Hq, dm.P,
+                     dm.Mmax, dm.cap);
   hipLaunchKernelGGL(topk_compact_kernel, sgrid, sblock, 0, st, box, seq_lens, ws, page_idx, dm.Hq, dm.P, dm.Mmax,
                      dm.cap);
-  hipLaunchKernelGGL(select_topk_redo_kernel, grid, block, 0, st, box, seq_lens, k_pages, page_idx, n_sel, ws, dm.Hq,
-                     dm.P, dm.Mmax, dm.cap);
 }
 
 }  // namespace ekv

@@ -223,6 +223,9 @@ def test_select_gauss_long_context():
     mu = (rng.normal(size=(B, Hq, M)) * 0.25 + 1.0).astype(np.float32)
     sg = (np.abs(rng.normal(size=(B, Hq, M))) * 0.1 + 0.9).astype(np.float32)
     mu[0, 1, rng.choice(M, 50, replace=False)] += 3.0              # a few hot pages
+    mu[0, 2, : M // 2] -= 12.0                                      # bimodal: the pooled start is far off
+    sg[0, 2, : M // 2] *= 0.05
+    mu[0, 3, rng.choice(M, 3, replace=False)] += 9.0; sg[0, 3] *= 0.02   # three pages carry all the mass
     seq_lens = torch.full((B,), M * P - 7, dtype=torch.int32, device=dev)
     t = lambda a: torch.from_numpy(a).to(dev)
     tau_hat = torch.zeros(B, Hq, device=dev); page_idx = torch.zeros(B, Hq, cap, dtype=torch.int32, device=dev)
