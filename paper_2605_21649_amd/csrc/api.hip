@@ -60,7 +60,7 @@ static ekv_status finish(hipStream_t) {
 static void decode_ws_layout(const Dims& dm, bool dense, size_t& zstride, int& n_chunks_max, size_t& bytes) {
   const int slots = dense ? dm.Mmax : dm.cap;
   zstride = (size_t)slots * dm.P;
-  n_chunks_max = (slots + kPagesPerScoreBlock - 1) / kPagesPerScoreBlock;
+  n_chunks_max = (slots + pmax_pages(dm.P) - 1) / pmax_pages(dm.P);
   const size_t rows = (size_t)dm.B * dm.Hq;
   bytes = rows * zstride * sizeof(float) + rows * (size_t)n_chunks_max * sizeof(float);
   bytes = (bytes + 255) & ~(size_t)255;

@@ -2,7 +2,7 @@
 //
 // Entmax has no online rescaling: the threshold tau needs every candidate score.  The work is split:
 //   pass 1 (many workgroups, HBM-bound): gather the K pages, z_j = a*scale*q.k_j, write z (4 B/token)
-//           and one maximum per chunk of 8 pages to scratch.  bf16 pages go through the matrix cores:
+//           and one maximum per group of pages (64 tokens) to scratch.  bf16 pages go through the matrix cores:
 //           an MFMA tile's 16 rows are 4 tokens x 4 channel quarters, so each lane's A operand is the
 //           16 bytes of a fully coalesced load, its 16 columns are (query head, channel quarter); the
 //           blocks with matching quarters are summed with two DPP quad steps.
@@ -35,84 +35,87 @@ struct ScoreArgs {
   const void* q; const void* k_pool;
   const int32_t* block_table; const int32_t* seq_lens; const int32_t* page_idx; const int32_t* n_sel;
   float* zbuf; float* pmax;
-  int Hq, Hkv, P, Mmax, cap, n_chunks_max;
+  int Hq, Hkv, P, Mmax, cap, n_chunks_max, n_phys;
   size_t zstride;
   float zscale;
 };
 
-// Generic path (float32 caches, or page sizes that are not a multiple of 16): FMAs + DPP row sums.
+// A wavefront covers kGroupsPerWave groups of pmax_pages(P) consecutive page slots (64 tokens when P
+// divides 64) and writes each group's maximum straight to pmax (no LDS, no barrier); a workgroup is four
+// such wavefronts.  Page indices are resolved first (wave-uniform loads, clamped into range so that
+// nothing depends on n_sel), then all K loads of the wavefront are issued before any is consumed.
+constexpr int kGroupsPerWave = 1;
+constexpr int kScoreWaves = kScoreThreads / 64;
+
+__device__ __forceinline__ int clampi(int x, int lo, int hi) { return min(max(x, lo), hi); }
+
+// Generic path (float32 caches, or page sizes that are not 16, 32 or 64): FMAs + DPP row sums.
 template <typename T, int G, bool DENSE>
 __global__ __launch_bounds__(kScoreThreads) void decode_scores_valu_kernel(const ScoreArgs A) {
-  __shared__ float wmax_s[kScoreThreads / 64][G];
   const T* q = (const T*)A.q;
   const T* k_pool = (const T*)A.k_pool;
   const int P = A.P, Hq = A.Hq, Hkv = A.Hkv;
-  const int unit = blockIdx.y, chunk = blockIdx.x;
+  const int unit = blockIdx.y;
   const int b = DENSE ? unit / Hkv : unit / Hq;
   const int hkv = DENSE ? unit % Hkv : (unit % Hq) / (Hq / Hkv);
   const int hq0 = DENSE ? hkv * G : unit % Hq;            // first (only) query head of this unit
   const int n = A.seq_lens[b];
   const int n_slots = DENSE ? (n + P - 1) / P : A.n_sel[unit];
-  const int slot0 = chunk * kPagesPerScoreBlock;
-  if (slot0 >= n_slots) return;
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int gp = pmax_pages(P);
   const int r = lane >> 4, c = lane & 15;
   float coef[G][8];
 #pragma unroll
   for (int g = 0; g < G; ++g) load8<T>(q + ((size_t)b * Hq + hq0 + g) * kD + 8 * c, coef[g]);
-  float wmax[G];
+  for (int gi = 0; gi < kGroupsPerWave; ++gi) {
+    const int grp = (blockIdx.x * kScoreWaves + w) * kGroupsPerWave + gi;
+    if (grp * gp >= n_slots) break;
+    float wmax[G];
 #pragma unroll
-  for (int g = 0; g < G; ++g) wmax[g] = -INFINITY;
-  constexpr int kPagesPerWave = kPagesPerScoreBlock / (kScoreThreads / 64);
-  for (int pw = 0; pw < kPagesPerWave; ++pw) {
-    const int slot = slot0 + w * kPagesPerWave + pw;
-    if (slot >= n_slots) break;
-    const int lp = DENSE ? slot : A.page_idx[(size_t)unit * A.cap + slot];
-    const int phys = A.block_table[(size_t)b * A.Mmax + lp];
-    const T* kpage = k_pool + ((size_t)phys * Hkv + hkv) * P * kD + 8 * c;
-    for (int s0 = 0; s0 < P / 4; s0 += 16) {          // 16 steps (64 tokens) per sweep of the c lanes
-      float zkeep[G];
+    for (int g = 0; g < G; ++g) wmax[g] = -INFINITY;
+    for (int pg = 0; pg < gp; ++pg) {
+      const int slot = grp * gp + pg;
+      if (slot >= n_slots) break;
+      const int lp = clampi(DENSE ? slot : A.page_idx[(size_t)unit * A.cap + slot], 0, A.Mmax - 1);
+      const int phys = clampi(A.block_table[(size_t)b * A.Mmax + lp], 0, A.n_phys - 1);
+      const T* kpage = k_pool + ((size_t)phys * Hkv + hkv) * P * kD + 8 * c;
+      for (int s0 = 0; s0 < P / 4; s0 += 16) {          // 16 steps (64 tokens) per sweep of the c lanes
+        float zkeep[G];
 #pragma unroll
-      for (int g = 0; g < G; ++g) zkeep[g] = -INFINITY;
-      const int s1 = min(P / 4, s0 + 16);
-      for (int s = s0; s < s1; ++s) {
-        float x[8];
-        load8<T>(kpage + (size_t)(4 * s + r) * kD, x);
-        const bool valid = lp * P + 4 * s + r < n;
+        for (int g = 0; g < G; ++g) zkeep[g] = -INFINITY;
+        const int s1 = min(P / 4, s0 + 16);
+        for (int s = s0; s < s1; ++s) {
+          float x[8];
+          load8<T>(kpage + (size_t)(4 * s + r) * kD, x);
+          const bool valid = lp * P + 4 * s + r < n;
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
-          float acc = 0.f;
+          for (int g = 0; g < G; ++g) {
+            float acc = 0.f;
 #pragma unroll
-          for (int i = 0; i < 8; ++i) acc = fmaf(coef[g][i], x[i], acc);
-          acc = row16_sum(acc);
-          const float z = valid ? A.zscale * acc : -INFINITY;
-          if (c == s - s0) zkeep[g] = z;
-          wmax[g] = fmaxf(wmax[g], z);
+            for (int i = 0; i < 8; ++i) acc = fmaf(coef[g][i], x[i], acc);
+            acc = row16_sum(acc);
+            const float z = valid ? A.zscale * acc : -INFINITY;
+            if (c == s - s0) zkeep[g] = z;
+            wmax[g] = fmaxf(wmax[g], z);
+          }
         }
-      }
-      if (c < s1 - s0) {
+        if (c < s1 - s0) {
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
-          const size_t row = DENSE ? (size_t)b * Hq + hq0 + g : (size_t)unit;
-          A.zbuf[row * A.zstride + (size_t)slot * P + 4 * (s0 + c) + r] = zkeep[g];
+          for (int g = 0; g < G; ++g) {
+            const size_t row = DENSE ? (size_t)b * Hq + hq0 + g : (size_t)unit;
+            A.zbuf[row * A.zstride + (size_t)slot * P + 4 * (s0 + c) + r] = zkeep[g];
+          }
         }
       }
     }
-  }
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
-    float m = wmax[g];
-    m = fmaxf(m, __shfl_xor(m, 16));
-    m = fmaxf(m, __shfl_xor(m, 32));
-    if (lane == 0) wmax_s[w][g] = m;
-  }
-  __syncthreads();
-  if (threadIdx.x < G) {
-    const int g = threadIdx.x;
-    float m = wmax_s[0][g];
-    for (int i = 1; i < kScoreThreads / 64; ++i) m = fmaxf(m, wmax_s[i][g]);
-    const size_t row = DENSE ? (size_t)b * Hq + hq0 + g : (size_t)unit;
-    A.pmax[row * A.n_chunks_max + chunk] = m;
+    for (int g = 0; g < G; ++g) {
+      float m = wmax[g];                                   // equal over the 16 lanes of a row
+      m = fmaxf(m, __shfl_xor(m, 16));
+      m = fmaxf(m, __shfl_xor(m, 32));
+      const size_t row = DENSE ? (size_t)b * Hq + hq0 + g : (size_t)unit;
+      if (lane == 0) A.pmax[row * A.n_chunks_max + grp] = m;
+    }
   }
 }
 
@@ -122,87 +125,101 @@ __global__ __launch_bounds__(kScoreThreads) void decode_scores_mfma_kernel(const
   constexpr int NSET = (G + 3) / 4;
   constexpr int STEPS = PT / 4;                   // 16-byte loads per lane and page
   constexpr int KEEP = PT / 16;                   // z values a lane keeps per page and column set
-  __shared__ float wmax_s[kScoreThreads / 64][NSET * 4];
+  constexpr int GP = 64 / PT;                     // pages per pmax group
+  constexpr int SW = GP * kGroupsPerWave;         // page slots per wavefront
   const bf16_t* q = (const bf16_t*)A.q;
   const bf16_t* k_pool = (const bf16_t*)A.k_pool;
   const int Hq = A.Hq, Hkv = A.Hkv;
-  const int unit = blockIdx.y, chunk = blockIdx.x;
+  const int unit = blockIdx.y;
   const int b = DENSE ? unit / Hkv : unit / Hq;
   const int hkv = DENSE ? unit % Hkv : (unit % Hq) / (Hq / Hkv);
   const int hq0 = DENSE ? hkv * G : unit % Hq;
-  const int n = A.seq_lens[b];
-  const int n_slots = DENSE ? (n + PT - 1) / PT : A.n_sel[unit];
-  const int slot0 = chunk * kPagesPerScoreBlock;
-  if (slot0 >= n_slots) return;
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wslot0 = (blockIdx.x * kScoreWaves + w) * SW;
   const int m = lane & 15, j = lane >> 4;          // MFMA row/column index, K group
   const int kq = m & 3, gl = m >> 2;               // channel quarter; as a row: token of the step,
                                                    // as a column: head within the set
+  // row (token gl of the step, quarter kq), K group j -> bytes [gl*256 + (kq*4+j)*16, +16) of the step
+  const size_t lane_off = (size_t)gl * kD + (kq * 4 + j) * 8;
+  int lps[SW], physs[SW];
+#pragma unroll
+  for (int i = 0; i < SW; ++i) {
+    const int sc = min(wslot0 + i, (DENSE ? A.Mmax : A.cap) - 1);
+    lps[i] = DENSE ? sc : clampi(A.page_idx[(size_t)unit * A.cap + sc], 0, A.Mmax - 1);
+  }
+#pragma unroll
+  for (int i = 0; i < SW; ++i) physs[i] = clampi(A.block_table[(size_t)b * A.Mmax + lps[i]], 0, A.n_phys - 1);
+  uint4 a[SW][STEPS];
+#pragma unroll
+  for (int i = 0; i < SW; ++i) {
+    const bf16_t* kpage = k_pool + ((size_t)physs[i] * Hkv + hkv) * PT * kD + lane_off;
+#pragma unroll
+    for (int s = 0; s < STEPS; ++s) a[i][s] = *reinterpret_cast<const uint4*>(kpage + (size_t)s * 4 * kD);
+  }
+  const int n = A.seq_lens[b];
+  const int n_slots = DENSE ? (n + PT - 1) / PT : A.n_sel[unit];
   uint4 bq[NSET];
 #pragma unroll
   for (int s = 0; s < NSET; ++s) {
-    const int g = 4 * s + gl;
-    bq[s] = make_uint4(0, 0, 0, 0);
-    if (g < G) bq[s] = *reinterpret_cast<const uint4*>(q + ((size_t)b * Hq + hq0 + g) * kD + kq * 32 + j * 8);
+    const int g = min(4 * s + gl, G - 1);          // columns past the group repeat its last head (not stored)
+    bq[s] = *reinterpret_cast<const uint4*>(q + ((size_t)b * Hq + hq0 + g) * kD + kq * 32 + j * 8);
   }
-  float wmax[NSET];
-#pragma unroll
-  for (int s = 0; s < NSET; ++s) wmax[s] = -INFINITY;
+  if (wslot0 >= n_slots) return;
 
-  constexpr int kPagesPerWave = kPagesPerScoreBlock / (kScoreThreads / 64);
 #pragma unroll
-  for (int pw = 0; pw < kPagesPerWave; ++pw) {
-    const int slot = slot0 + w * kPagesPerWave + pw;
-    if (slot >= n_slots) break;
-    const int lp = DENSE ? slot : A.page_idx[(size_t)unit * A.cap + slot];
-    const int phys = A.block_table[(size_t)b * A.Mmax + lp];
-    // row (token gl of the step, quarter kq), K group j -> bytes [gl*256 + (kq*4+j)*16, +16) of the step
-    const bf16_t* kpage = k_pool + ((size_t)phys * Hkv + hkv) * PT * kD + gl * kD + (kq * 4 + j) * 8;
-    uint4 a[STEPS];
+  for (int gi = 0; gi < kGroupsPerWave; ++gi) {
+    if (wslot0 + gi * GP >= n_slots) break;
+    float wmax[NSET];
 #pragma unroll
-    for (int s = 0; s < STEPS; ++s) a[s] = *reinterpret_cast<const uint4*>(kpage + (size_t)s * 4 * kD);
-    float zkeep[NSET][KEEP];
+    for (int s = 0; s < NSET; ++s) wmax[s] = -INFINITY;
 #pragma unroll
-    for (int s = 0; s < STEPS; ++s) {
-      const bool valid = lp * PT + 4 * s + j < n;  // result rows 4j..4j+3 belong to token j of the step
+    for (int pg = 0; pg < GP; ++pg) {
+      const int i = gi * GP + pg;
+      const int slot = wslot0 + i;
+      const bool slot_ok = slot < n_slots;             // wave-uniform
+      const int lp = lps[i];
+      float zkeep[NSET][KEEP];
 #pragma unroll
-      for (int cs = 0; cs < NSET; ++cs) {
-        const f32x4_t zero = {0.f, 0.f, 0.f, 0.f};
-        const f32x4_t c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a[s]),
-                                                                  __builtin_bit_cast(bf16x8_t, bq[cs]), zero, 0, 0, 0);
-        float v = kq == 0 ? c[0] : kq == 1 ? c[1] : kq == 2 ? c[2] : c[3];
-        v += dpp_move<0xB1>(v);
-        v += dpp_move<0x4E>(v);
-        const float z = valid ? A.zscale * v : -INFINITY;
-        if ((s & 3) == kq) zkeep[cs][s >> 2] = z;   // lane (j, head, kq) keeps token 4*(4*i + kq) + j
-        wmax[cs] = fmaxf(wmax[cs], z);
+      for (int s = 0; s < STEPS; ++s) {
+        // result rows 4j..4j+3 belong to token j of the step
+        const bool valid = slot_ok && lp * PT + 4 * s + j < n;
+#pragma unroll
+        for (int cs = 0; cs < NSET; ++cs) {
+          const f32x4_t zero = {0.f, 0.f, 0.f, 0.f};
+          const f32x4_t c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a[i][s]),
+                                                                    __builtin_bit_cast(bf16x8_t, bq[cs]), zero, 0, 0, 0);
+          float v = kq == 0 ? c[0] : kq == 1 ? c[1] : kq == 2 ? c[2] : c[3];
+          v += dpp_move<0xB1>(v);
+          v += dpp_move<0x4E>(v);
+          const float z = valid ? A.zscale * v : -INFINITY;
+          if ((s & 3) == kq) zkeep[cs][s >> 2] = z;   // lane (j, head, kq) keeps token 4*(4*i + kq) + j
+          wmax[cs] = fmaxf(wmax[cs], z);
+        }
+      }
+      if (slot_ok) {
+#pragma unroll
+        for (int cs = 0; cs < NSET; ++cs) {
+          const int g = 4 * cs + gl;
+          if (g < G) {
+            const size_t row = DENSE ? (size_t)b * Hq + hq0 + g : (size_t)unit;
+            float* zp = A.zbuf + row * A.zstride + (size_t)slot * PT + j;
+#pragma unroll
+            for (int t = 0; t < KEEP; ++t) zp[4 * (4 * t + kq)] = zkeep[cs][t];
+          }
+        }
       }
     }
 #pragma unroll
     for (int cs = 0; cs < NSET; ++cs) {
+      float mx = wmax[cs];                               // equal over the four kq lanes of a head
+      mx = fmaxf(mx, __shfl_xor(mx, 16));
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
       const int g = 4 * cs + gl;
-      if (g < G) {
+      if (j == 0 && kq == 0 && g < G) {
         const size_t row = DENSE ? (size_t)b * Hq + hq0 + g : (size_t)unit;
-        float* zp = A.zbuf + row * A.zstride + (size_t)slot * PT + j;
-#pragma unroll
-        for (int i = 0; i < KEEP; ++i) zp[4 * (4 * i + kq)] = zkeep[cs][i];
+        A.pmax[row * A.n_chunks_max + (wslot0 / GP + gi)] = mx;
       }
     }
-  }
-#pragma unroll
-  for (int cs = 0; cs < NSET; ++cs) {
-    float mx = wmax[cs];
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    if (j == 0 && kq == 0) wmax_s[w][4 * cs + gl] = mx;
-  }
-  __syncthreads();
-  if (threadIdx.x < G) {
-    const int g = threadIdx.x;
-    float mx = wmax_s[0][g];
-    for (int i = 1; i < kScoreThreads / 64; ++i) mx = fmaxf(mx, wmax_s[i][g]);
-    const size_t row = DENSE ? (size_t)b * Hq + hq0 + g : (size_t)unit;
-    A.pmax[row * A.n_chunks_max + chunk] = mx;
   }
 }
 
@@ -310,7 +327,7 @@ struct SolveArgs {
   const float* zbuf; const float* pmax;
   float* out; float* tau_out; int32_t* supp_out;
   ekv_decode_extras ex;
-  int Hq, Hkv, P, Mmax, cap, n_chunks_max;
+  int Hq, Hkv, P, Mmax, cap, n_chunks_max, n_phys;
   size_t zstride;
   float a, beta; int ibeta;
 };
@@ -319,8 +336,8 @@ struct SolveArgs {
 template <bool DENSE>
 __device__ __forceinline__ uint32_t v_row_of(const SolveArgs& A, int b, int bh, int hkv, int pos) {
   const int slot = pos / A.P, tok = pos - slot * A.P;
-  const int lp = DENSE ? slot : A.page_idx[(size_t)bh * A.cap + slot];
-  const int phys = A.block_table[(size_t)b * A.Mmax + lp];
+  const int lp = DENSE ? slot : clampi(A.page_idx[(size_t)bh * A.cap + slot], 0, A.Mmax - 1);
+  const int phys = clampi(A.block_table[(size_t)b * A.Mmax + lp], 0, A.n_phys - 1);
   return (uint32_t)((phys * A.Hkv + hkv) * A.P + tok);
 }
 template <bool DENSE>
@@ -362,8 +379,8 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
   const int n = A.seq_lens[b];
   const int n_slots = DENSE ? (n + P - 1) / P : A.n_sel[bh];
   const int n_cand = n_slots * P;
-  const int n_chunks = (n_slots + kPagesPerScoreBlock - 1) / kPagesPerScoreBlock;
-  const int chunk_tokens = kPagesPerScoreBlock * P;
+  const int n_chunks = (n_slots + pmax_pages(P) - 1) / pmax_pages(P);
+  const int chunk_tokens = pmax_pages(P) * P;
   const float* zr = A.zbuf + (size_t)bh * A.zstride;
   const float* pm = A.pmax + (size_t)bh * A.n_chunks_max;
   const float beta = A.beta; const int ibeta = A.ibeta;
@@ -608,12 +625,14 @@ void launch_decode(const Dims& dm, bool dense, const void* q, const ekv_cache_vi
                    const int32_t* page_idx, const int32_t* n_sel, float* out, float* tau, int32_t* supp,
                    const ekv_decode_extras& ex, const DecodeWorkspace& ws, hipStream_t st) {
   ScoreArgs sa{q, c.k_pool, c.block_table, c.seq_lens, page_idx, n_sel, ws.z, ws.pmax,
-               dm.Hq, dm.Hkv, dm.P, dm.Mmax, dm.cap, ws.n_chunks_max, ws.zstride, dm.a * dm.scale};
+               dm.Hq, dm.Hkv, dm.P, dm.Mmax, dm.cap, ws.n_chunks_max, c.n_phys_pages, ws.zstride, dm.a * dm.scale};
   SolveArgs so{c.v_pool, c.block_table, c.seq_lens, page_idx, n_sel, ws.z, ws.pmax, out, tau, supp, ex,
-               dm.Hq, dm.Hkv, dm.P, dm.Mmax, dm.cap, ws.n_chunks_max, ws.zstride, dm.a, dm.beta, dm.ibeta};
+               dm.Hq, dm.Hkv, dm.P, dm.Mmax, dm.cap, ws.n_chunks_max, c.n_phys_pages, ws.zstride, dm.a, dm.beta, dm.ibeta};
   dim3 sgrid(dm.B * dm.Hq), sblock(kSolveThreads);
+  const int slots_per_wg = kScoreWaves * kGroupsPerWave * pmax_pages(dm.P);
+  const int score_blocks = ((dense ? dm.Mmax : dm.cap) + slots_per_wg - 1) / slots_per_wg;
   if (dense) {
-    dim3 grid(ws.n_chunks_max, dm.B * dm.Hkv);
+    dim3 grid(score_blocks, dm.B * dm.Hkv);
     switch (dm.G) {
       case 1: launch_scores<1, true>(dm, grid, sa, st); break;
       case 2: launch_scores<2, true>(dm, grid, sa, st); break;
@@ -623,7 +642,7 @@ void launch_decode(const Dims& dm, bool dense, const void* q, const ekv_cache_vi
     if (dm.dtype == EKV_F32) hipLaunchKernelGGL((decode_solve_kernel<float, true>), sgrid, sblock, 0, st, so);
     else hipLaunchKernelGGL((decode_solve_kernel<bf16_t, true>), sgrid, sblock, 0, st, so);
   } else {
-    dim3 grid(ws.n_chunks_max, dm.B * dm.Hq);
+    dim3 grid(score_blocks, dm.B * dm.Hq);
     launch_scores<1, false>(dm, grid, sa, st);
     if (dm.dtype == EKV_F32) hipLaunchKernelGGL((decode_solve_kernel<float, false>), sgrid, sblock, 0, st, so);
     else hipLaunchKernelGGL((decode_solve_kernel<bf16_t, false>), sgrid, sblock, 0, st, so);

@@ -16,11 +16,12 @@ struct Dims {
 };
 
 // decode scratch layout (shared by api.hip and decode.hip)
-constexpr int kPagesPerScoreBlock = 8;   // pages handled by one workgroup of the score pass
+// page slots per entry of pmax (granularity of chunk skipping): 64 tokens when P divides 64
+__host__ __device__ inline int pmax_pages(int P) { return P >= 64 ? 1 : 64 / P; }
 
 struct DecodeWorkspace {
   float* z;        // [B*Hq][zstride] candidate scores z_j (or -inf where masked)
-  float* pmax;     // [B*Hq][n_chunks_max] per-chunk maxima of z
+  float* pmax;     // [B*Hq][n_chunks_max] maxima of z per pmax_pages(P) page slots
   size_t zstride;  // floats per (b,h) row of z
   int n_chunks_max;
 };

@@ -10,6 +10,7 @@ namespace ekv {
 constexpr int kSmThreads = 256;
 constexpr int kSmWaves = kSmThreads / 64;
 constexpr int kSmRec = kD + 2;          // floats per partial record: o[128], m, l
+constexpr int kSmPagesPerBlock = 8;     // page slots per workgroup (one partial record)
 
 template <typename T>
 __global__ __launch_bounds__(kSmThreads) void softmax_partial_kernel(
@@ -23,7 +24,7 @@ __global__ __launch_bounds__(kSmThreads) void softmax_partial_kernel(
   const int b = bh / Hq, hkv = (bh % Hq) / (Hq / Hkv);
   const int n = seq_lens[b];
   const int n_slots = n_sel[bh];
-  const int slot0 = chunk * kPagesPerScoreBlock;
+  const int slot0 = chunk * kSmPagesPerBlock;
   if (slot0 >= n_slots) return;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, r = lane >> 4, c = lane & 15;
   float qv[8];
@@ -31,7 +32,7 @@ __global__ __launch_bounds__(kSmThreads) void softmax_partial_kernel(
   float m_run = -INFINITY, l_run = 0.f, acc[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) acc[i] = 0.f;
-  constexpr int kPagesPerWave = kPagesPerScoreBlock / kSmWaves;
+  constexpr int kPagesPerWave = kSmPagesPerBlock / kSmWaves;
   for (int pw = 0; pw < kPagesPerWave; ++pw) {
     const int slot = slot0 + w * kPagesPerWave + pw;
     if (slot >= n_slots) break;
@@ -92,7 +93,7 @@ __global__ __launch_bounds__(kD) void softmax_merge_kernel(const float* __restri
                                                            float* __restrict__ out, float* __restrict__ lse,
                                                            int n_chunks_max) {
   const int bh = blockIdx.x, t = threadIdx.x;
-  const int n_chunks = (n_sel[bh] + kPagesPerScoreBlock - 1) / kPagesPerScoreBlock;
+  const int n_chunks = (n_sel[bh] + kSmPagesPerBlock - 1) / kSmPagesPerBlock;
   const float* rec0 = part + (size_t)bh * n_chunks_max * kSmRec;
   float M = -INFINITY;
   for (int i = 0; i < n_chunks; ++i) M = fmaxf(M, rec0[(size_t)i * kSmRec + kD]);
@@ -107,7 +108,7 @@ __global__ __launch_bounds__(kD) void softmax_merge_kernel(const float* __restri
 }
 
 size_t softmax_ws_bytes(const Dims& dm) {
-  const int n_chunks_max = (dm.cap + kPagesPerScoreBlock - 1) / kPagesPerScoreBlock;
+  const int n_chunks_max = (dm.cap + kSmPagesPerBlock - 1) / kSmPagesPerBlock;
   size_t b = (size_t)dm.B * dm.Hq * n_chunks_max * kSmRec * sizeof(float);
   return (b + 255) & ~(size_t)255;
 }
@@ -115,7 +116,7 @@ size_t softmax_ws_bytes(const Dims& dm) {
 void launch_decode_sparse_softmax(const Dims& dm, const void* q, const ekv_cache_view& c,
                                   const int32_t* page_idx, const int32_t* n_sel, float* out, float* lse_sel,
                                   void* ws, hipStream_t st) {
-  const int n_chunks_max = (dm.cap + kPagesPerScoreBlock - 1) / kPagesPerScoreBlock;
+  const int n_chunks_max = (dm.cap + kSmPagesPerBlock - 1) / kSmPagesPerBlock;
   dim3 grid(n_chunks_max, dm.B * dm.Hq);
   if (dm.dtype == EKV_F32)
     hipLaunchKernelGGL(softmax_partial_kernel<float>, grid, dim3(kSmThreads), 0, st, (const float*)q,
