@@ -57,15 +57,6 @@ static ekv_status finish(hipStream_t) {
   return EKV_OK;
 }
 
-static void decode_ws_layout(const Dims& dm, bool dense, size_t& zstride, int& n_chunks_max, size_t& bytes) {
-  const int slots = dense ? dm.Mmax : dm.cap;
-  zstride = (size_t)slots * dm.P;
-  n_chunks_max = (slots + pmax_pages(dm.P) - 1) / pmax_pages(dm.P);
-  const size_t rows = (size_t)dm.B * dm.Hq;
-  bytes = rows * zstride * sizeof(float) + rows * (size_t)n_chunks_max * sizeof(float);
-  bytes = (bytes + 255) & ~(size_t)255;
-}
-
 // Phi^{-1}(p) in double by bisection on erfc (monotone; 200 halvings of [-40, 40]).
 static double phi_inv(double log_p) {
   // solve log Phi(x) = log_p ; work with the upper tail 1 - Phi(x) = -expm1(log_p) when p is near 1
@@ -105,12 +96,12 @@ ekv_status ekv_workspace_bytes(const ekv_config* cfg, int32_t op, size_t* bytes)
   const ekv_status s = make_dims(cfg, dm);
   if (s != EKV_OK) return s;
   if (bytes == nullptr) return EKV_ERR_INVALID_ARG;
-  size_t zs; int nc; size_t b = 0;
+  size_t b = 0;
   switch (op) {
     case EKV_OP_SELECT_TOPK: b = select_topk_ws_bytes(dm); break;
     case EKV_OP_SELECT_GAUSS: b = select_gauss_ws_bytes(dm); break;
-    case EKV_OP_DECODE_SPARSE: decode_ws_layout(dm, false, zs, nc, b); break;
-    case EKV_OP_DECODE_FULL: decode_ws_layout(dm, true, zs, nc, b); break;
+    case EKV_OP_DECODE_SPARSE: b = decode_ws_carve(dm, false, nullptr, nullptr); break;
+    case EKV_OP_DECODE_FULL: b = decode_ws_carve(dm, true, nullptr, nullptr); break;
     case EKV_OP_DECODE_SPARSE_SOFTMAX: b = softmax_ws_bytes(dm); break;
     default: return EKV_ERR_INVALID_ARG;
   }
@@ -214,11 +205,9 @@ static ekv_status decode_common(const ekv_config* cfg, bool dense, const void* q
     if (!dense) ex.lse = nullptr;
   }
   DecodeWorkspace ws;
-  size_t need;
-  decode_ws_layout(dm, dense, ws.zstride, ws.n_chunks_max, need);
+  const size_t need = decode_ws_carve(dm, dense, nullptr, nullptr);
   if (workspace == nullptr || !aligned16(workspace) || workspace_bytes < need) return EKV_ERR_WORKSPACE;
-  ws.z = (float*)workspace;
-  ws.pmax = ws.z + (size_t)dm.B * dm.Hq * ws.zstride;
+  decode_ws_carve(dm, dense, workspace, &ws);
   launch_decode(dm, dense, q, *cache, page_idx, n_sel, out, tau, supp, ex, ws, (hipStream_t)stream);
   return finish((hipStream_t)stream);
 }

@@ -60,7 +60,7 @@ __global__ __launch_bounds__(kScoreThreads) void decode_scores_valu_kernel(const
   const int hkv = DENSE ? unit % Hkv : (unit % Hq) / (Hq / Hkv);
   const int hq0 = DENSE ? hkv * G : unit % Hq;            // first (only) query head of this unit
   const int n = A.seq_lens[b];
-  const int n_slots = DENSE ? (n + P - 1) / P : A.n_sel[unit];
+  const int n_slots = clampi(DENSE ? (n + P - 1) / P : A.n_sel[unit], 0, DENSE ? A.Mmax : A.cap);
   const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int gp = pmax_pages(P);
   const int r = lane >> 4, c = lane & 15;
@@ -157,7 +157,7 @@ __global__ __launch_bounds__(kScoreThreads) void decode_scores_mfma_kernel(const
     for (int s = 0; s < STEPS; ++s) a[i][s] = *reinterpret_cast<const uint4*>(kpage + (size_t)s * 4 * kD);
   }
   const int n = A.seq_lens[b];
-  const int n_slots = DENSE ? (n + PT - 1) / PT : A.n_sel[unit];
+  const int n_slots = clampi(DENSE ? (n + PT - 1) / PT : A.n_sel[unit], 0, DENSE ? A.Mmax : A.cap);
   uint4 bq[NSET];
 #pragma unroll
   for (int s = 0; s < NSET; ++s) {
@@ -220,6 +220,183 @@ __global__ __launch_bounds__(kScoreThreads) void decode_scores_mfma_kernel(const
         A.pmax[row * A.n_chunks_max + (wslot0 / GP + gi)] = mx;
       }
     }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// pass 1b (long rows only): multi-workgroup candidate filter
+// ------------------------------------------------------------------------------------------
+// One workgroup of the solve cannot stream a row of a million scores.  Two passes over slices of
+// kFilterSlice positions do it in parallel:
+//   hist    : slice maximum, and a count histogram of the slice's z > max-1 over bins of width 1/64 on the
+//             ABSOLUTE grid floor(64 z) -- histograms of different slices are then mergeable by a shift,
+//             without knowing the row maximum in advance.
+//   compact : every workgroup of a row merges the row's histograms (same integers, same result); an entry
+//             of bin g lies at least (g-i)/64 above grid point i, so counts alone give a lower bound of the
+//             mass at every grid point; the highest grid point whose bound is >= 1 is a certified lower
+//             bound of tau.  The slice's candidates above it are written out in order.
+// The solve then gathers the (few) survivors of all slices into LDS.
+constexpr int kFilterThreads = 1024;
+constexpr int kFilterWaves = kFilterThreads / 64;
+constexpr int kFilterLoads = kFilterSlice / (kFilterThreads * 4);   // float4 loads per thread
+constexpr int kFilterNoGrid = 0x7fffffff;                           // record marker: |z| too large for the grid
+
+struct FilterArgs {
+  const int32_t* seq_lens; const int32_t* n_sel; const float* zbuf;
+  int32_t* fhist; int32_t* fcount; float* frow; float* flist_u; int32_t* flist_pos;
+  int Hq, P, n_slices_max, max_slots;
+  size_t zstride;
+  float beta; int ibeta;
+};
+
+template <bool DENSE>
+__device__ __forceinline__ int filter_n_cand(const FilterArgs& A, int row) {
+  const int slots = DENSE ? (A.seq_lens[row / A.Hq] + A.P - 1) / A.P : A.n_sel[row];
+  return clampi(slots, 0, A.max_slots) * A.P;
+}
+
+// The slice's scores: wavefront w holds positions [t0 + 2048 w, +2048) as (load i, lane, component).
+__device__ __forceinline__ void filter_load(const float* zr, int t0, int n_cand, float4 (&v)[kFilterLoads]) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+#pragma unroll
+  for (int i = 0; i < kFilterLoads; ++i) {
+    const int pos = t0 + (w * kFilterLoads + i) * 256 + lane * 4;
+    v[i] = *reinterpret_cast<const float4*>(zr + min(pos, n_cand - 4));   // n_cand is a multiple of 4
+  }
+#pragma unroll
+  for (int i = 0; i < kFilterLoads; ++i) {
+    const int pos = t0 + (w * kFilterLoads + i) * 256 + lane * 4;
+    if (pos >= n_cand) v[i] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+  }
+}
+
+template <bool DENSE>
+__global__ __launch_bounds__(kFilterThreads) void filter_hist_kernel(const FilterArgs A) {
+  __shared__ float red[kFilterWaves];
+  __shared__ int whist[kFilterWaves][66];
+  const int row = blockIdx.y, slice = blockIdx.x, tid = threadIdx.x, w = tid >> 6;
+  const int n_cand = filter_n_cand<DENSE>(A, row);
+  const int t0 = slice * kFilterSlice;
+  if (t0 >= n_cand) return;
+  float4 v[kFilterLoads];
+  filter_load(A.zbuf + (size_t)row * A.zstride, t0, n_cand, v);
+  for (int i = tid; i < kFilterWaves * 66; i += kFilterThreads) (&whist[0][0])[i] = 0;
+  float m = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < kFilterLoads; ++i) m = fmaxf(m, fmaxf(fmaxf(v[i].x, v[i].y), fmaxf(v[i].z, v[i].w)));
+  const float smax = block_max(m, red);                     // barriers: the zeroed histogram is visible
+  int32_t* rec = A.fhist + ((size_t)row * A.n_slices_max + slice) * kFilterRec;
+  if (tid == 0) rec[1] = __float_as_int(smax);
+  if (!(fabsf(smax) < 100000.0f)) {                         // empty slice (-inf), or off the exact grid
+    if (tid == 0) rec[0] = smax > -INFINITY ? kFilterNoGrid : -kFilterNoGrid;
+    return;
+  }
+  const int top = (int)floorf(smax * 64.0f);
+  const float lowf = (float)(top - 64) * (1.0f / 64.0f);    // exact; every z > smax-1 is >= lowf
+#pragma unroll
+  for (int i = 0; i < kFilterLoads; ++i) {
+    const float zz[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+      if (zz[c] >= lowf) atomicAdd(&whist[w][min(64, (int)floorf(zz[c] * 64.0f) - (top - 64))], 1);
+  }
+  __syncthreads();
+  if (tid < 65) {
+    int c = 0;
+    for (int i = 0; i < kFilterWaves; ++i) c += whist[i][tid];
+    rec[2 + tid] = c;
+  }
+  if (tid == 0) rec[0] = top;
+}
+
+template <bool DENSE>
+__global__ __launch_bounds__(kFilterThreads) void filter_compact_kernel(const FilterArgs A) {
+  __shared__ float red[kFilterWaves];
+  __shared__ int redi[kFilterWaves];
+  __shared__ int mh[66];
+  __shared__ int wtot[kFilterWaves];
+  __shared__ int level_s;
+  const int row = blockIdx.y, slice = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const uint64_t lt = (1ull << lane) - 1ull;
+  const int n_cand = filter_n_cand<DENSE>(A, row);
+  const int t0 = slice * kFilterSlice;
+  if (t0 >= n_cand) return;
+  const float* zr = A.zbuf + (size_t)row * A.zstride;
+  float4 v[kFilterLoads];
+  filter_load(zr, t0, n_cand, v);                           // in flight while the histograms are merged
+  const int n_slices = (n_cand + kFilterSlice - 1) / kFilterSlice;
+  const int32_t* recs = A.fhist + (size_t)row * A.n_slices_max * kFilterRec;
+  // row maximum, top grid cell of the row, and whether every slice is on the grid
+  float zm = -INFINITY; int tp = -kFilterNoGrid;
+  for (int s = tid; s < n_slices; s += kFilterThreads) {
+    tp = max(tp, recs[(size_t)s * kFilterRec]);
+    zm = fmaxf(zm, __int_as_float(recs[(size_t)s * kFilterRec + 1]));
+  }
+  const float zmax = block_max(zm, red);
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) tp = max(tp, __shfl_xor(tp, d));
+  if (lane == 0) redi[w] = tp;
+  if (tid < 66) mh[tid] = 0;
+  __syncthreads();
+  int gtop = redi[0];
+  for (int i = 1; i < kFilterWaves; ++i) gtop = max(gtop, redi[i]);
+  float thr = zmax - 1.0f - 4e-6f * fmaxf(1.f, fabsf(zmax));
+  if (gtop != kFilterNoGrid && gtop != -kFilterNoGrid) {
+    for (int s = w; s < n_slices; s += kFilterWaves) {
+      const int top_s = recs[(size_t)s * kFilterRec];
+      if (top_s == -kFilterNoGrid) continue;                // empty slice
+      const int shift = gtop - top_s;                       // >= 0
+      for (int l = lane; l < 65; l += 64) {
+        const int cnt = recs[(size_t)s * kFilterRec + 2 + l];
+        if (cnt != 0 && l - shift >= 0) atomicAdd(&mh[l - shift], cnt);
+      }
+    }
+    __syncthreads();
+    if (tid < 64) {
+      // lower bound of the mass at grid point tid of [gtop-64, gtop]
+      float lb = 0.f;
+      for (int g = tid + 1; g < 65; ++g)
+        lb += (float)mh[g] * pow_beta(((float)(g - tid) - 0.02f) * (1.0f / 64.0f), A.beta, A.ibeta);
+      const uint64_t okm = __ballot(lb >= 1.0001f);
+      if (tid == 0) level_s = okm ? 63 - __clzll(okm) : 0;
+    }
+    __syncthreads();
+    if (level_s > 0) thr = (float)(gtop - 64 + level_s) * (1.0f / 64.0f);   // > zmax - 1
+  }
+  if (slice == 0 && tid == 0) { A.frow[2 * row] = zmax; A.frow[2 * row + 1] = thr; }
+  // ordered compaction of the slice's entries above thr
+  int c = 0;
+#pragma unroll
+  for (int i = 0; i < kFilterLoads; ++i) c += (v[i].x > thr) + (v[i].y > thr) + (v[i].z > thr) + (v[i].w > thr);
+  c = wave_sum_i(c);
+  if (lane == 0) wtot[w] = c;
+  __syncthreads();
+  int off = 0, tot = 0;
+  for (int i = 0; i < kFilterWaves; ++i) { const int ci = wtot[i]; if (i < w) off += ci; tot += ci; }
+  if (tid == 0) A.fcount[(size_t)row * A.n_slices_max + slice] = tot;
+  if (c == 0) return;
+  float* lu = A.flist_u + ((size_t)row * A.n_slices_max + slice) * kFilterSliceCap;
+  int32_t* lp = A.flist_pos + ((size_t)row * A.n_slices_max + slice) * kFilterSliceCap;
+#pragma unroll
+  for (int i = 0; i < kFilterLoads; ++i) {
+    const float zz[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+    const bool any = zz[0] > thr || zz[1] > thr || zz[2] > thr || zz[3] > thr;
+    if (__ballot(any) == 0) continue;
+    // order within the load: (lane, component)
+    const int mine = (zz[0] > thr) + (zz[1] > thr) + (zz[2] > thr) + (zz[3] > thr);
+    int inc = mine;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) { const int t = __shfl_up(inc, d); if (lane >= d) inc += t; }
+    int o = off + inc - mine;
+    const int pos = t0 + (w * kFilterLoads + i) * 256 + lane * 4;
+#pragma unroll
+    for (int cc = 0; cc < 4; ++cc) {
+      if (zz[cc] > thr) {
+        if (o < kFilterSliceCap) { lu[o] = zz[cc] - zmax; lp[o] = pos + cc; }
+        ++o;
+      }
+    }
+    off += __shfl(inc, 63);
   }
 }
 
@@ -330,6 +507,8 @@ struct SolveArgs {
   int Hq, Hkv, P, Mmax, cap, n_chunks_max, n_phys;
   size_t zstride;
   float a, beta; int ibeta;
+  // results of the filter passes (null for short rows)
+  const int32_t* fcount; const float* frow; const float* flist_u; const int32_t* flist_pos; int n_slices_max;
 };
 
 // V row index (phys*Hkv + hkv)*P + tok of candidate position `pos`.
@@ -377,7 +556,7 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
   const uint64_t lt = (1ull << lane) - 1ull;
   const T* v_pool = (const T*)A.v_pool;
   const int n = A.seq_lens[b];
-  const int n_slots = DENSE ? (n + P - 1) / P : A.n_sel[bh];
+  const int n_slots = clampi(DENSE ? (n + P - 1) / P : A.n_sel[bh], 0, DENSE ? A.Mmax : A.cap);
   const int n_cand = n_slots * P;
   const int n_chunks = (n_slots + pmax_pages(P) - 1) / pmax_pages(P);
   const int chunk_tokens = pmax_pages(P) * P;
@@ -386,9 +565,15 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
   const float beta = A.beta; const int ibeta = A.ibeta;
   float* out = A.out + (size_t)bh * kD;
 
-  float mx = -INFINITY;
-  for (int i = tid; i < n_chunks; i += kSolveThreads) mx = fmaxf(mx, pm[i]);
-  const float zmax = block_max(mx, sh.red1);
+  float zmax, thr_f = 0.f;
+  if (A.fcount != nullptr) {
+    zmax = n_cand > 0 ? A.frow[2 * bh] : -INFINITY;
+    thr_f = n_cand > 0 ? A.frow[2 * bh + 1] : 0.f;
+  } else {
+    float mx = -INFINITY;
+    for (int i = tid; i < n_chunks; i += kSolveThreads) mx = fmaxf(mx, pm[i]);
+    zmax = block_max(mx, sh.red1);
+  }
   if (!(zmax > -INFINITY)) {                // no valid candidate at all
     if (tid < kD) out[tid] = 0.f;
     if (tid == 0) { A.tau_out[bh] = INFINITY; A.supp_out[bh] = 0; }
@@ -401,14 +586,42 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
   // a lower bound of the mass at every slice boundary (an entry of slice j lies at least j-i slices above
   // boundary i), hence a tighter valid threshold: it becomes the starting point of the solve, and, if the
   // candidates did not fit in LDS, the threshold of one more compaction pass.
-  float thr = zmax - 1.0f - 4e-6f * fmaxf(1.f, fabsf(zmax));
+  float thr = A.fcount != nullptr ? thr_f : zmax - 1.0f - 4e-6f * fmaxf(1.f, fabsf(zmax));
   float lo_u = thr - zmax;
   // chunk skipping pays only when there is a lot to skip (dense rows); short candidate lists are read whole,
   // which saves the dependent load of the chunk maxima in every round
   const bool can_skip = (chunk_tokens & 63) == 0 && n_cand > 4 * kRoundTokens;
   int n_list = 0, parity = 0;
   bool in_lds = true;
-  for (int pass = 0; pass < 3; ++pass) {
+  bool prefilled = false;
+  if (A.fcount != nullptr) {
+    // survivors of the filter passes: gather the per-slice lists, in slice order, if they fit
+    const int n_slices = (n_cand + kFilterSlice - 1) / kFilterSlice;
+    const int cs = tid < n_slices ? A.fcount[(size_t)bh * A.n_slices_max + tid] : 0;
+    int inc = cs;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) { const int t = __shfl_up(inc, d); if (lane >= d) inc += t; }
+    if (lane == 63) sh.wcount[0][w] = inc;
+    const int bad = __syncthreads_or(cs > kFilterSliceCap);
+    int base = 0, tot = 0;
+    for (int i = 0; i < kSolveWaves; ++i) { const int ci = sh.wcount[0][i]; if (i < w) base += ci; tot += ci; }
+    if (!bad && tot <= kListCap) {
+      int* start = reinterpret_cast<int*>(sh.list_row);      // free until the solve is done
+      if (tid < n_slices) { start[2 * tid] = base + inc - cs; start[2 * tid + 1] = cs; }
+      __syncthreads();
+      for (int sl = w; sl < n_slices; sl += kSolveWaves) {
+        const int o0 = start[2 * sl], cnt = start[2 * sl + 1];
+        const float* lu = A.flist_u + ((size_t)bh * A.n_slices_max + sl) * kFilterSliceCap;
+        const int32_t* lp = A.flist_pos + ((size_t)bh * A.n_slices_max + sl) * kFilterSliceCap;
+        for (int e = lane; e < cnt; e += 64) { sh.list_u[o0 + e] = lu[e]; sh.list_pos[o0 + e] = lp[e]; }
+      }
+      n_list = tot;
+      prefilled = true;
+      lo_u = fminf(thr - zmax, -1e-7f);
+    }
+    __syncthreads();
+  }
+  for (int pass = 0; pass < 3 && !prefilled; ++pass) {
     const float width = zmax - thr, slice = width * (1.0f / 64.0f), inv_slice = 64.0f / width;
     if (tid < 64) sh.hist[tid] = 0;
     n_list = 0; in_lds = true;
@@ -621,6 +834,38 @@ static void launch_scores(const Dims& dm, dim3 grid, const ScoreArgs& sa, hipStr
     hipLaunchKernelGGL((decode_scores_valu_kernel<float, G, DENSE>), grid, block, 0, st, sa);
 }
 
+size_t decode_ws_carve(const Dims& dm, bool dense, void* base, DecodeWorkspace* ws) {
+  const size_t slots = dense ? dm.Mmax : dm.cap;
+  const size_t rows = (size_t)dm.B * dm.Hq;
+  const size_t zstride = slots * dm.P;
+  const int n_chunks_max = (int)((slots + pmax_pages(dm.P) - 1) / pmax_pages(dm.P));
+  size_t n_slices = (zstride + kFilterSlice - 1) / kFilterSlice;
+  if (zstride < (size_t)kFilterMinTokens || n_slices > (size_t)kFilterMaxSlices) n_slices = 0;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { const size_t o = off; off += (bytes + 255) & ~(size_t)255; return o; };
+  const size_t o_z = take(rows * zstride * sizeof(float));
+  const size_t o_pm = take(rows * n_chunks_max * sizeof(float));
+  size_t o_fh = 0, o_fc = 0, o_fr = 0, o_fu = 0, o_fp = 0;
+  if (n_slices) {
+    o_fh = take(rows * n_slices * kFilterRec * sizeof(int32_t));
+    o_fc = take(rows * n_slices * sizeof(int32_t));
+    o_fr = take(rows * 2 * sizeof(float));
+    o_fu = take(rows * n_slices * kFilterSliceCap * sizeof(float));
+    o_fp = take(rows * n_slices * kFilterSliceCap * sizeof(int32_t));
+  }
+  if (ws != nullptr && base != nullptr) {
+    char* p = (char*)base;
+    ws->z = (float*)(p + o_z); ws->pmax = (float*)(p + o_pm);
+    ws->zstride = zstride; ws->n_chunks_max = n_chunks_max; ws->n_slices_max = (int)n_slices;
+    ws->fhist = n_slices ? (int32_t*)(p + o_fh) : nullptr;
+    ws->fcount = n_slices ? (int32_t*)(p + o_fc) : nullptr;
+    ws->frow = n_slices ? (float*)(p + o_fr) : nullptr;
+    ws->flist_u = n_slices ? (float*)(p + o_fu) : nullptr;
+    ws->flist_pos = n_slices ? (int32_t*)(p + o_fp) : nullptr;
+  }
+  return off;
+}
+
 void launch_decode(const Dims& dm, bool dense, const void* q, const ekv_cache_view& c,
                    const int32_t* page_idx, const int32_t* n_sel, float* out, float* tau, int32_t* supp,
                    const ekv_decode_extras& ex, const DecodeWorkspace& ws, hipStream_t st) {
@@ -628,6 +873,11 @@ void launch_decode(const Dims& dm, bool dense, const void* q, const ekv_cache_vi
                dm.Hq, dm.Hkv, dm.P, dm.Mmax, dm.cap, ws.n_chunks_max, c.n_phys_pages, ws.zstride, dm.a * dm.scale};
   SolveArgs so{c.v_pool, c.block_table, c.seq_lens, page_idx, n_sel, ws.z, ws.pmax, out, tau, supp, ex,
                dm.Hq, dm.Hkv, dm.P, dm.Mmax, dm.cap, ws.n_chunks_max, c.n_phys_pages, ws.zstride, dm.a, dm.beta, dm.ibeta};
+  so.fcount = ws.fcount; so.frow = ws.frow; so.flist_u = ws.flist_u; so.flist_pos = ws.flist_pos;
+  so.n_slices_max = ws.n_slices_max;
+  FilterArgs fa{c.seq_lens, n_sel, ws.z, ws.fhist, ws.fcount, ws.frow, ws.flist_u, ws.flist_pos,
+                dm.Hq, dm.P, ws.n_slices_max, dense ? dm.Mmax : dm.cap, ws.zstride, dm.beta, dm.ibeta};
+  dim3 fgrid(ws.n_slices_max, dm.B * dm.Hq), fblock(kFilterThreads);
   dim3 sgrid(dm.B * dm.Hq), sblock(kSolveThreads);
   const int slots_per_wg = kScoreWaves * kGroupsPerWave * pmax_pages(dm.P);
   const int score_blocks = ((dense ? dm.Mmax : dm.cap) + slots_per_wg - 1) / slots_per_wg;
@@ -639,11 +889,19 @@ void launch_decode(const Dims& dm, bool dense, const void* q, const ekv_cache_vi
       case 4: launch_scores<4, true>(dm, grid, sa, st); break;
       default: launch_scores<8, true>(dm, grid, sa, st); break;
     }
+    if (ws.fcount != nullptr) {
+      hipLaunchKernelGGL((filter_hist_kernel<true>), fgrid, fblock, 0, st, fa);
+      hipLaunchKernelGGL((filter_compact_kernel<true>), fgrid, fblock, 0, st, fa);
+    }
     if (dm.dtype == EKV_F32) hipLaunchKernelGGL((decode_solve_kernel<float, true>), sgrid, sblock, 0, st, so);
     else hipLaunchKernelGGL((decode_solve_kernel<bf16_t, true>), sgrid, sblock, 0, st, so);
   } else {
     dim3 grid(score_blocks, dm.B * dm.Hq);
     launch_scores<1, false>(dm, grid, sa, st);
+    if (ws.fcount != nullptr) {
+      hipLaunchKernelGGL((filter_hist_kernel<false>), fgrid, fblock, 0, st, fa);
+      hipLaunchKernelGGL((filter_compact_kernel<false>), fgrid, fblock, 0, st, fa);
+    }
     if (dm.dtype == EKV_F32) hipLaunchKernelGGL((decode_solve_kernel<float, false>), sgrid, sblock, 0, st, so);
     else hipLaunchKernelGGL((decode_solve_kernel<bf16_t, false>), sgrid, sblock, 0, st, so);
   }

@@ -540,3 +540,65 @@ def test_candidate_list_larger_than_lds_uses_the_streaming_path():
         assert abs(float(tau_f[0, hq]) - ref["tau"]) <= 4e-6 * max(1.0, abs(ref["tau"]))
         assert abs(int(supp_f[0, hq]) - len(ref["support"])) <= 2
         assert rel_err(out_f[0, hq].cpu().numpy(), ref["o"]) <= 2e-5
+
+
+LONG = [synth.C2.scaled(name="C2-long-bf16", context=100000, ragged=7, n_q_heads=4, n_kv_heads=2),
+        synth.C1.scaled(name="C1-long-f32", context=70000, ragged=3, n_q_heads=2, n_kv_heads=2,
+                        scale=1.0 / math.sqrt(128.0)),
+        synth.C5.scaled(name="C5-long-p32-a2", batch=2, context=98304 + 64, ragged=33, n_q_heads=2, n_kv_heads=1,
+                        alpha=2.0),
+        # nearly flat scores: more than 4096 tokens above the certified bound -> the solve cannot take the
+        # filtered lists and falls back to streaming the row from that bound
+        synth.C1.scaled(name="C1-long-flat", context=66000, n_planted=0, scale=0.02 / math.sqrt(128.0),
+                        n_q_heads=2, n_kv_heads=2)]
+
+
+@pytest.mark.parametrize("w", LONG, ids=[w.name for w in LONG])
+def test_decode_long_rows_take_the_filter_passes(w):
+    """Rows of 65536 candidates or more are pre-filtered by the multi-workgroup passes (dense, and sparse
+    with a large selection); results must meet the same bars as the short-row path."""
+    inp = get_inputs(w)
+    M = w.pages_per_seq
+    n = w.context - w.ragged
+    n_pages = -(-n // w.page_size)
+    cap = min(M, -(-66000 // w.page_size))                 # a selection of >= 66000 tokens
+    st = DeviceState(w, inp, cap=cap)
+    dev = st.box.device
+    supp_tok = torch.full((w.batch, w.n_q_heads, 8192), -1, device=dev, dtype=torch.int32)
+    out_f, tau_f, supp_f = torch.zeros_like(st.out), torch.zeros_like(st.tau), torch.zeros_like(st.supp)
+    ekv.ekv_decode_full(st.cfg, st.inp["q"], st.cache(), out_f, tau_f, supp_f, st.workspace(ekv.EKV_OP_DECODE_FULL),
+                        extras=ekv.decode_extras(support_tokens=supp_tok))
+    torch.cuda.synchronize()
+    full_tokens = supp_tok.cpu().numpy().copy()
+    # sparse: a seeded random page list of `cap` pages that always holds the last (partial) page
+    rng = np.random.default_rng(77)
+    lists = {}
+    for b in range(w.batch):
+        for hq in range(w.n_q_heads):
+            pages = np.sort(rng.choice(n_pages - 1, cap - 1, replace=False))
+            pages = np.append(pages, n_pages - 1)
+            lists[(b, hq)] = pages
+            st.page_idx[b, hq, :cap] = torch.from_numpy(pages.astype(np.int32)).to(dev)
+            st.n_sel[b, hq] = cap
+    supp_tok.fill_(-1)
+    ekv.ekv_decode_sparse(st.cfg, st.inp["q"], st.cache(), st.page_idx, st.n_sel, st.out, st.tau, st.supp,
+                          st.workspace(ekv.EKV_OP_DECODE_SPARSE), extras=ekv.decode_extras(support_tokens=supp_tok))
+    torch.cuda.synchronize()
+    sp_tokens = supp_tok.cpu().numpy()
+    flat = "flat" in w.name
+    for (b, hq) in [(0, 0), (w.batch - 1, w.n_q_heads - 1)]:
+        q, K, V = unit_kv(inp, w, b, hq)
+        ref = orc.entmax_attention(q, K, V, w.alpha, w.score_scale)
+        tok = orc.pages_to_tokens(lists[(b, hq)], w.page_size, K.shape[0])
+        ref_s = orc.entmax_attention(q, K, V, w.alpha, w.score_scale, tok)
+        if flat:
+            assert len(ref["support"]) > 4096 and len(ref_s["support"]) > 4096
+            for got_tau, got_supp, got_out, r in ((tau_f, supp_f, out_f, ref), (st.tau, st.supp, st.out, ref_s)):
+                assert abs(float(got_tau[b, hq]) - r["tau"]) <= 4e-6 * max(1.0, abs(r["tau"]))
+                assert abs(int(got_supp[b, hq]) - len(r["support"])) <= 4
+                assert rel_err(got_out[b, hq].cpu().numpy(), r["o"]) <= 2e-5
+        else:
+            check_decode_unit(w, out_f[b, hq].cpu().numpy(), float(tau_f[b, hq]), int(supp_f[b, hq]),
+                              full_tokens[b, hq], ref)
+            check_decode_unit(w, st.out[b, hq].cpu().numpy(), float(st.tau[b, hq]), int(st.supp[b, hq]),
+                              sp_tokens[b, hq], ref_s)
