@@ -226,15 +226,15 @@ __global__ __launch_bounds__(kScoreThreads) void decode_scores_mfma_kernel(const
 // ------------------------------------------------------------------------------------------
 // pass 1b (long rows only): multi-workgroup candidate filter
 // ------------------------------------------------------------------------------------------
-// One workgroup of the solve cannot stream a row of a million scores.  Two passes over slices of
+// One workgroup of the solve cannot stream a row of a million scores.  Passes over slices of
 // kFilterSlice positions do it in parallel:
 //   hist    : slice maximum, and a count histogram of the slice's z > max-1 over bins of width 1/64 on the
 //             ABSOLUTE grid floor(64 z) -- histograms of different slices are then mergeable by a shift,
 //             without knowing the row maximum in advance.
-//   compact : every workgroup of a row merges the row's histograms (same integers, same result); an entry
-//             of bin g lies at least (g-i)/64 above grid point i, so counts alone give a lower bound of the
-//             mass at every grid point; the highest grid point whose bound is >= 1 is a certified lower
-//             bound of tau.  The slice's candidates above it are written out in order.
+//   level   : one workgroup per row merges the row's histograms; an entry of bin g lies at least (g-i)/64
+//             above grid point i, so counts alone give a lower bound of the mass at every grid point; the
+//             highest grid point whose bound is >= 1 is a certified lower bound of tau.
+//   compact : the slice's candidates above that bound are written out in order.
 // The solve then gathers the (few) survivors of all slices into LDS.
 constexpr int kFilterThreads = 1024;
 constexpr int kFilterWaves = kFilterThreads / 64;
@@ -309,26 +309,20 @@ __global__ __launch_bounds__(kFilterThreads) void filter_hist_kernel(const Filte
   if (tid == 0) rec[0] = top;
 }
 
+// One workgroup per row: merge the slice histograms, certify the bound.
+constexpr int kLevelThreads = 1024;
 template <bool DENSE>
-__global__ __launch_bounds__(kFilterThreads) void filter_compact_kernel(const FilterArgs A) {
-  __shared__ float red[kFilterWaves];
-  __shared__ int redi[kFilterWaves];
+__global__ __launch_bounds__(kLevelThreads) void filter_level_kernel(const FilterArgs A) {
+  __shared__ float red[kLevelThreads / 64];
+  __shared__ int redi[kLevelThreads / 64];
   __shared__ int mh[66];
-  __shared__ int wtot[kFilterWaves];
-  __shared__ int level_s;
-  const int row = blockIdx.y, slice = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const uint64_t lt = (1ull << lane) - 1ull;
+  const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int n_cand = filter_n_cand<DENSE>(A, row);
-  const int t0 = slice * kFilterSlice;
-  if (t0 >= n_cand) return;
-  const float* zr = A.zbuf + (size_t)row * A.zstride;
-  float4 v[kFilterLoads];
-  filter_load(zr, t0, n_cand, v);                           // in flight while the histograms are merged
   const int n_slices = (n_cand + kFilterSlice - 1) / kFilterSlice;
   const int32_t* recs = A.fhist + (size_t)row * A.n_slices_max * kFilterRec;
   // row maximum, top grid cell of the row, and whether every slice is on the grid
   float zm = -INFINITY; int tp = -kFilterNoGrid;
-  for (int s = tid; s < n_slices; s += kFilterThreads) {
+  for (int s = tid; s < n_slices; s += kLevelThreads) {
     tp = max(tp, recs[(size_t)s * kFilterRec]);
     zm = fmaxf(zm, __int_as_float(recs[(size_t)s * kFilterRec + 1]));
   }
@@ -339,16 +333,24 @@ __global__ __launch_bounds__(kFilterThreads) void filter_compact_kernel(const Fi
   if (tid < 66) mh[tid] = 0;
   __syncthreads();
   int gtop = redi[0];
-  for (int i = 1; i < kFilterWaves; ++i) gtop = max(gtop, redi[i]);
+  for (int i = 1; i < kLevelThreads / 64; ++i) gtop = max(gtop, redi[i]);
   float thr = zmax - 1.0f - 4e-6f * fmaxf(1.f, fabsf(zmax));
   if (gtop != kFilterNoGrid && gtop != -kFilterNoGrid) {
-    for (int s = w; s < n_slices; s += kFilterWaves) {
-      const int top_s = recs[(size_t)s * kFilterRec];
-      if (top_s == -kFilterNoGrid) continue;                // empty slice
-      const int shift = gtop - top_s;                       // >= 0
-      for (int l = lane; l < 65; l += 64) {
-        const int cnt = recs[(size_t)s * kFilterRec + 2 + l];
-        if (cnt != 0 && l - shift >= 0) atomicAdd(&mh[l - shift], cnt);
+    // (slice, bin) pairs flattened over the threads, loads of a batch issued together
+    const int items = n_slices * 65;
+    for (int e0 = 0; e0 < items; e0 += kLevelThreads * 4) {
+      int tops[4], cnts[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int e = min(e0 + k * kLevelThreads + tid, items - 1), sl = e / 65;
+        tops[k] = recs[(size_t)sl * kFilterRec];
+        cnts[k] = recs[(size_t)sl * kFilterRec + 2 + (e - sl * 65)];
+      }
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int e = e0 + k * kLevelThreads + tid;
+        const int g = e % 65 - (gtop - tops[k]);                // shift >= 0
+        if (e < items && tops[k] != -kFilterNoGrid && cnts[k] != 0 && g >= 0) atomicAdd(&mh[g], cnts[k]);
       }
     }
     __syncthreads();
@@ -358,13 +360,27 @@ __global__ __launch_bounds__(kFilterThreads) void filter_compact_kernel(const Fi
       for (int g = tid + 1; g < 65; ++g)
         lb += (float)mh[g] * pow_beta(((float)(g - tid) - 0.02f) * (1.0f / 64.0f), A.beta, A.ibeta);
       const uint64_t okm = __ballot(lb >= 1.0001f);
-      if (tid == 0) level_s = okm ? 63 - __clzll(okm) : 0;
+      const int level = okm ? 63 - __clzll(okm) : 0;
+      if (level > 0) thr = (float)(gtop - 64 + level) * (1.0f / 64.0f);   // > zmax - 1
+      if (tid == 0) { A.frow[2 * row] = zmax; A.frow[2 * row + 1] = thr; }
     }
-    __syncthreads();
-    if (level_s > 0) thr = (float)(gtop - 64 + level_s) * (1.0f / 64.0f);   // > zmax - 1
+  } else if (tid == 0) {
+    A.frow[2 * row] = zmax; A.frow[2 * row + 1] = thr;
   }
-  if (slice == 0 && tid == 0) { A.frow[2 * row] = zmax; A.frow[2 * row + 1] = thr; }
-  // ordered compaction of the slice's entries above thr
+}
+
+// Ordered compaction of the slice's entries above the certified bound.
+template <bool DENSE>
+__global__ __launch_bounds__(kFilterThreads) __attribute__((amdgpu_waves_per_eu(8, 8))) void filter_compact_kernel(const FilterArgs A) {
+  __shared__ int wtot[kFilterWaves];
+  const int row = blockIdx.y, slice = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const uint64_t lt = (1ull << lane) - 1ull;
+  const int n_cand = filter_n_cand<DENSE>(A, row);
+  const int t0 = slice * kFilterSlice;
+  if (t0 >= n_cand) return;
+  float4 v[kFilterLoads];
+  filter_load(A.zbuf + (size_t)row * A.zstride, t0, n_cand, v);
+  const float zmax = A.frow[2 * row], thr = A.frow[2 * row + 1];
   int c = 0;
 #pragma unroll
   for (int i = 0; i < kFilterLoads; ++i) c += (v[i].x > thr) + (v[i].y > thr) + (v[i].z > thr) + (v[i].w > thr);
@@ -383,11 +399,9 @@ __global__ __launch_bounds__(kFilterThreads) void filter_compact_kernel(const Fi
     const bool any = zz[0] > thr || zz[1] > thr || zz[2] > thr || zz[3] > thr;
     if (__ballot(any) == 0) continue;
     // order within the load: (lane, component)
-    const int mine = (zz[0] > thr) + (zz[1] > thr) + (zz[2] > thr) + (zz[3] > thr);
-    int inc = mine;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) { const int t = __shfl_up(inc, d); if (lane >= d) inc += t; }
-    int o = off + inc - mine;
+    const uint64_t m0 = __ballot(zz[0] > thr), m1 = __ballot(zz[1] > thr), m2 = __ballot(zz[2] > thr),
+                   m3 = __ballot(zz[3] > thr);
+    int o = off + __popcll(m0 & lt) + __popcll(m1 & lt) + __popcll(m2 & lt) + __popcll(m3 & lt);
     const int pos = t0 + (w * kFilterLoads + i) * 256 + lane * 4;
 #pragma unroll
     for (int cc = 0; cc < 4; ++cc) {
@@ -396,7 +410,7 @@ __global__ __launch_bounds__(kFilterThreads) void filter_compact_kernel(const Fi
         ++o;
       }
     }
-    off += __shfl(inc, 63);
+    off += __popcll(m0) + __popcll(m1) + __popcll(m2) + __popcll(m3);
   }
 }
 
@@ -891,6 +905,7 @@ void launch_decode(const Dims& dm, bool dense, const void* q, const ekv_cache_vi
     }
     if (ws.fcount != nullptr) {
       hipLaunchKernelGGL((filter_hist_kernel<true>), fgrid, fblock, 0, st, fa);
+      hipLaunchKernelGGL((filter_level_kernel<true>), dim3(dm.B * dm.Hq), dim3(kLevelThreads), 0, st, fa);
       hipLaunchKernelGGL((filter_compact_kernel<true>), fgrid, fblock, 0, st, fa);
     }
     if (dm.dtype == EKV_F32) hipLaunchKernelGGL((decode_solve_kernel<float, true>), sgrid, sblock, 0, st, so);
@@ -900,6 +915,7 @@ void launch_decode(const Dims& dm, bool dense, const void* q, const ekv_cache_vi
     launch_scores<1, false>(dm, grid, sa, st);
     if (ws.fcount != nullptr) {
       hipLaunchKernelGGL((filter_hist_kernel<false>), fgrid, fblock, 0, st, fa);
+      hipLaunchKernelGGL((filter_level_kernel<false>), dim3(dm.B * dm.Hq), dim3(kLevelThreads), 0, st, fa);
       hipLaunchKernelGGL((filter_compact_kernel<false>), fgrid, fblock, 0, st, fa);
     }
     if (dm.dtype == EKV_F32) hipLaunchKernelGGL((decode_solve_kernel<float, false>), sgrid, sblock, 0, st, so);
