@@ -12,6 +12,7 @@ paper's definitions so that it can be checked against the paper by eye:
   stage 3  top-k page selection     Sec. 4.3 "Top-k page selection"
            Gaussian tau-hat         Sec. 4.3 Eq. 10, App. D (truncated Gaussian moments)
            Gaussian page selection  Sec. 4.3 Eq. 11-12
+           box-threshold selection  App. B.2 (support superset from page bounds)
   stage 4  entmax attention over a candidate token set (all tokens = full cache)
                                     Sec. 2.1 Eq. 1, Sec. 2.2 Eq. 2-3, Sec. 4.1
   metrics  delta, rho, R, softmax dropped mass   Sec. 3 Eq. 4, 7, 8; App. E.1
@@ -24,7 +25,8 @@ steps, with the scalar root taken to float64 convergence by bisection.
 Parity pins (tests/test_oracle_*.py): brute-force subset enumeration, sparsemax
 closed form, softmax limit, normalisation, the tightness example of Prop. 1,
 Prop. 2-4 invariants, P=1 reduction, printed truncated-moment closed forms vs
-quadrature.  Unpinned: which pages a *good* Gaussian selector should pick
+quadrature; box-threshold refinement: a worked example, the P=1 reduction and
+"one refinement from any start reaches the full-cache result".  Unpinned: which pages a *good* Gaussian selector should pick
 (selection quality; the paper states no hyper-parameters) -- "parity unpinned".
 """
 import numpy as np
@@ -126,6 +128,33 @@ def topk_pages(scores, k):
     cut_in = scores[taken[-1]] if k > 0 else np.inf
     cut_out = scores[order[k]] if k < M else -np.inf
     return np.sort(taken), cut_in, cut_out
+
+
+# --------------------------------------------------------------------------------------
+# stage 3c: box-threshold selection (App. B.2, the proposition on page bounds)
+# --------------------------------------------------------------------------------------
+def box_threshold_pages(box, alpha, tau_lo):
+    """Pages p with (alpha-1) * box_p > tau_lo, ascending.
+
+    App. B.2: if tau_lo does not exceed the exact entmax threshold, every page that
+    holds a support token is in this set (the box score bounds every token score of
+    the page from above)."""
+    box = np.asarray(box, dtype=np.float64)
+    return np.nonzero((alpha - 1.0) * box > tau_lo)[0]
+
+
+def refine_selection(box, alpha, tau_lo, pages):
+    """Union of a page list with box_threshold_pages(box, alpha, tau_lo).
+
+    Returns (ascending union, ascending array of the pages that were added).  With
+    tau_lo the threshold of the sparse solve over `pages` (never above the
+    full-cache threshold, since dropping candidates only lowers the mass), an empty
+    `added` certifies that the sparse result is exact, and otherwise the union
+    holds the whole support, so one more sparse solve over it is exact (Prop. 2)."""
+    pages = np.asarray(pages, dtype=np.int64)
+    thr = box_threshold_pages(box, alpha, tau_lo)
+    added = np.setdiff1d(thr, pages)
+    return np.union1d(pages, thr), added
 
 
 # --------------------------------------------------------------------------------------
