@@ -50,7 +50,8 @@ typedef enum {
   EKV_OP_SELECT_GAUSS = 1,
   EKV_OP_DECODE_SPARSE = 2,
   EKV_OP_DECODE_FULL = 3,
-  EKV_OP_DECODE_SPARSE_SOFTMAX = 4
+  EKV_OP_DECODE_SPARSE_SOFTMAX = 4,
+  EKV_OP_SELECT_BOX_THRESHOLD = 5
 } ekv_op;
 
 /* Problem description (host struct).  head_dim must be 128; page_size a multiple of 4 in [4,64];
@@ -141,6 +142,25 @@ ekv_status ekv_select_gauss(const ekv_config* cfg, const float* mu, const float*
                             const int32_t* seq_lens, float q_page, float margin, float* tau_hat,
                             int32_t* page_idx, int32_t* n_sel, int32_t* overflow, void* workspace,
                             size_t workspace_bytes, void* stream);
+
+/* Box-threshold selection and refinement (App. B.2: with a threshold that does not exceed the exact one,
+ * the page bounds of Eq. 9 never miss a page that holds a support token).  Per (b,h):
+ *   page_idx_out = page_idx_in[0..n_sel_in)  UNION  { p < M_b : a * box[b,h,p] > tau_lo[b,h] },  ascending,
+ * n_sel_out its size, n_added the pages of the second set that were not in the first.
+ * Use: tau_lo := tau of ekv_decode_sparse over page_idx_in (a sparse threshold never exceeds the
+ * full-cache one).  n_added == 0 certifies that sparse result as exact; otherwise the output list holds
+ * the whole support and one more ekv_decode_sparse over it is exact (Sec. 3.2, exact recovery).
+ * box f32 [B][Hq][Mmax] from ekv_score_pages; tau_lo f32 [B][Hq] (device; +inf selects nothing, -inf
+ * every page); page_idx_in/n_sel_in may both be NULL (empty list; entries outside [0, M_b) are ignored,
+ * order and duplicates do not matter); page_idx_out int32 [B][Hq][cap] may alias page_idx_in, n_sel_out
+ * may alias n_sel_in; n_added, overflow int32 [B][Hq].  If the union exceeds cap, its first cap pages (by
+ * index) are written and overflow[b,h]=1: the list is then incomplete and certifies nothing.
+ * Workspace: ekv_workspace_bytes(EKV_OP_SELECT_BOX_THRESHOLD). */
+ekv_status ekv_select_box_threshold(const ekv_config* cfg, const float* box, const int32_t* seq_lens,
+                                    const float* tau_lo, const int32_t* page_idx_in,
+                                    const int32_t* n_sel_in, int32_t* page_idx_out, int32_t* n_sel_out,
+                                    int32_t* n_added, int32_t* overflow, void* workspace,
+                                    size_t workspace_bytes, void* stream);
 
 /* Optional side outputs of the decode calls (all device pointers, any may be NULL).
  *   support_tokens int32 [B][Hq][support_cap]: logical token indices j with p_j > 0, in candidate

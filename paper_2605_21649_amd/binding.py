@@ -17,12 +17,13 @@ EKV_OK = 0
 EKV_F32, EKV_BF16 = 0, 1
 EKV_SCORE_BOX, EKV_SCORE_GAUSS, EKV_SCORE_BOTH = 1, 2, 3
 EKV_OP_SELECT_TOPK, EKV_OP_SELECT_GAUSS, EKV_OP_DECODE_SPARSE, EKV_OP_DECODE_FULL, \
-    EKV_OP_DECODE_SPARSE_SOFTMAX = range(5)
+    EKV_OP_DECODE_SPARSE_SOFTMAX, EKV_OP_SELECT_BOX_THRESHOLD = range(6)
 
 # every symbol the header declares
 EXPORTS = ["ekv_stats_build", "ekv_stats_append", "ekv_score_pages", "ekv_select_topk", "ekv_select_gauss",
-           "ekv_decode_sparse", "ekv_decode_full", "ekv_decode_sparse_softmax", "ekv_workspace_bytes",
-           "ekv_status_string", "ekv_last_hip_error", "ekv_version"]
+           "ekv_select_box_threshold", "ekv_decode_sparse", "ekv_decode_full", "ekv_decode_sparse_softmax",
+           "ekv_workspace_bytes", "ekv_status_string", "ekv_last_hip_error", "ekv_version"]
+_STATUS_CALLS = EXPORTS[:10]      # entry points that return ekv_status
 
 
 class ekv_config(ctypes.Structure):
@@ -81,7 +82,9 @@ def load_library():
     lib.ekv_status_string.restype = ctypes.c_char_p
     lib.ekv_last_hip_error.restype = c_int32
     lib.ekv_version.restype = c_int32
-    for name in EXPORTS[:9]:
+    lib.ekv_select_box_threshold.argtypes = [P(ekv_config), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                             c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+    for name in _STATUS_CALLS:
         getattr(lib, name).restype = c_int32
     _lib = lib
     return lib
@@ -159,6 +162,15 @@ def ekv_select_gauss(cfg, mu, sigma, seq_lens, q_page, margin, tau_hat, page_idx
     _check(load_library().ekv_select_gauss(byref(cfg), _ptr(mu), _ptr(sigma), _ptr(seq_lens), q_page, margin,
                                            _ptr(tau_hat), _ptr(page_idx), _ptr(n_sel), _ptr(overflow),
                                            _ptr(workspace), nbytes, _stream(stream)))
+
+
+def ekv_select_box_threshold(cfg, box, seq_lens, tau_lo, page_idx_in, n_sel_in, page_idx_out, n_sel_out, n_added,
+                             overflow, workspace, stream=None):
+    nbytes = workspace.numel() * workspace.element_size()
+    _check(load_library().ekv_select_box_threshold(byref(cfg), _ptr(box), _ptr(seq_lens), _ptr(tau_lo),
+                                                   _ptr(page_idx_in), _ptr(n_sel_in), _ptr(page_idx_out),
+                                                   _ptr(n_sel_out), _ptr(n_added), _ptr(overflow), _ptr(workspace),
+                                                   nbytes, _stream(stream)))
 
 
 def ekv_decode_sparse(cfg, q, cache, page_idx, n_sel, out, tau, supp, workspace, extras=None, stream=None):

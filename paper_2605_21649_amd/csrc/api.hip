@@ -103,6 +103,10 @@ ekv_status ekv_workspace_bytes(const ekv_config* cfg, int32_t op, size_t* bytes)
     case EKV_OP_DECODE_SPARSE: b = decode_ws_carve(dm, false, nullptr, nullptr); break;
     case EKV_OP_DECODE_FULL: b = decode_ws_carve(dm, true, nullptr, nullptr); break;
     case EKV_OP_DECODE_SPARSE_SOFTMAX: b = softmax_ws_bytes(dm); break;
+    case EKV_OP_SELECT_BOX_THRESHOLD:
+      if (!select_box_supported(dm)) return EKV_ERR_UNSUPPORTED;
+      b = select_box_ws_bytes(dm);
+      break;
     default: return EKV_ERR_INVALID_ARG;
   }
   *bytes = b;
@@ -183,6 +187,26 @@ ekv_status ekv_select_gauss(const ekv_config* cfg, const float* mu, const float*
   }
   launch_select_gauss(dm, mu, sigma, seq_lens, zq, margin, tau_hat, page_idx, n_sel, overflow, workspace,
                       (hipStream_t)stream);
+  return finish((hipStream_t)stream);
+}
+
+ekv_status ekv_select_box_threshold(const ekv_config* cfg, const float* box, const int32_t* seq_lens,
+                                    const float* tau_lo, const int32_t* page_idx_in, const int32_t* n_sel_in,
+                                    int32_t* page_idx_out, int32_t* n_sel_out, int32_t* n_added, int32_t* overflow,
+                                    void* workspace, size_t workspace_bytes, void* stream) {
+  Dims dm;
+  const ekv_status s = make_dims(cfg, dm);
+  if (s != EKV_OK) return s;
+  if (!select_box_supported(dm)) return EKV_ERR_UNSUPPORTED;
+  if (!ok_ptr4(box) || !ok_ptr4(seq_lens) || !ok_ptr4(tau_lo) || !ok_ptr4(page_idx_out) || !ok_ptr4(n_sel_out) ||
+      !ok_ptr4(n_added) || !ok_ptr4(overflow))
+    return EKV_ERR_INVALID_ARG;
+  if ((page_idx_in == nullptr) != (n_sel_in == nullptr)) return EKV_ERR_INVALID_ARG;
+  if (page_idx_in != nullptr && (!ok_ptr4(page_idx_in) || !ok_ptr4(n_sel_in))) return EKV_ERR_INVALID_ARG;
+  if (workspace == nullptr || !aligned16(workspace) || workspace_bytes < select_box_ws_bytes(dm))
+    return EKV_ERR_WORKSPACE;
+  launch_select_box_threshold(dm, box, seq_lens, tau_lo, page_idx_in, n_sel_in, page_idx_out, n_sel_out, n_added,
+                              overflow, workspace, (hipStream_t)stream);
   return finish((hipStream_t)stream);
 }
 

@@ -60,7 +60,14 @@ void launch_decode_sparse_softmax(const Dims& dm, const void* q, const ekv_cache
                                   const int32_t* page_idx, const int32_t* n_sel, float* out,
                                   float* lse_sel, void* ws, hipStream_t st);
 
+void launch_select_box_threshold(const Dims& dm, const float* box, const int32_t* seq_lens, const float* tau_lo,
+                                 const int32_t* page_idx_in, const int32_t* n_sel_in, int32_t* page_idx_out,
+                                 int32_t* n_sel_out, int32_t* n_added, int32_t* overflow, void* workspace,
+                                 hipStream_t st);
+
 size_t select_topk_ws_bytes(const Dims& dm);
+size_t select_box_ws_bytes(const Dims& dm);
+bool select_box_supported(const Dims& dm);
 size_t select_gauss_ws_bytes(const Dims& dm);
 bool select_gauss_supported(const Dims& dm);
 size_t softmax_ws_bytes(const Dims& dm);

@@ -602,3 +602,97 @@ def test_decode_long_rows_take_the_filter_passes(w):
                               full_tokens[b, hq], ref)
             check_decode_unit(w, st.out[b, hq].cpu().numpy(), float(st.tau[b, hq]), int(st.supp[b, hq]),
                               sp_tokens[b, hq], ref_s)
+
+
+# ---------------------------------------------------------------------------- box-threshold refinement
+@pytest.mark.parametrize("M,cap,alpha", [(300, 300, 1.5), (40000 - 3, 9000, 1.5), (8192, 700, 2.0),
+                                         (5000, 5000, 1.25)])
+def test_select_box_threshold_on_shared_scores(M, cap, alpha):
+    """Union of a given list with the pages above the threshold, on identical float32 scores: sets,
+    counts and flags must match the oracle (pages within 1e-5 of the threshold may differ)."""
+    P = 16
+    w = synth.C1.scaled(name=f"C1-boxthr-{M}-{alpha}", context=M * P, ragged=5, n_q_heads=6, n_kv_heads=6, alpha=alpha)
+    inp = get_inputs(w)
+    st = DeviceState(w, inp, cap=cap)
+    dev = st.box.device
+    rng = np.random.default_rng(11)
+    scores = rng.normal(size=(1, 6, M)).astype(np.float32)
+    a = alpha - 1.0
+    tau_lo = np.array([[np.quantile(a * scores[0, 0], 0.98), np.quantile(a * scores[0, 1], 0.5), np.inf, -np.inf,
+                        np.quantile(a * scores[0, 4], 0.999), float(a * scores[0, 5].max())]], dtype=np.float32)
+    lists = []
+    for h in range(6):
+        n_in = [0, 17, 40, 3, min(cap, 257), 1][h]
+        lst = rng.choice(M, n_in, replace=False).astype(np.int32)
+        if h == 1:
+            lst = np.concatenate([lst, lst[:5], np.array([M + 3, -1], dtype=np.int32)])   # duplicates, out of range
+        lists.append(lst)
+        st.page_idx[0, h, : len(lst)] = torch.from_numpy(lst).to(dev)
+        st.n_sel[0, h] = len(lst)
+    st.box.copy_(torch.from_numpy(scores))
+    tau_d = torch.from_numpy(tau_lo).to(dev)
+    out_idx = torch.full_like(st.page_idx, -7)
+    out_n, added, ovf = torch.zeros_like(st.n_sel), torch.zeros_like(st.n_sel), torch.zeros_like(st.n_sel)
+    ekv.ekv_select_box_threshold(st.cfg, st.box, st.inp["seq_lens"], tau_d, st.page_idx, st.n_sel, out_idx, out_n,
+                                 added, ovf, st.workspace(ekv.EKV_OP_SELECT_BOX_THRESHOLD))
+    torch.cuda.synchronize()
+    oi, on, ad, ov = out_idx.cpu().numpy(), out_n.cpu().numpy(), added.cpu().numpy(), ovf.cpu().numpy()
+    for h in range(6):
+        given = np.array(sorted(set(int(p) for p in lists[h] if 0 <= p < M)), dtype=np.int64)
+        union, new = orc.refine_selection(scores[0, h].astype(np.float64), alpha, float(tau_lo[0, h]), given)
+        band = 1e-5 * max(1.0, abs(float(tau_lo[0, h]))) if np.isfinite(tau_lo[0, h]) else 0.0
+        near = int(np.sum(np.abs(a * scores[0, h].astype(np.float64) - float(tau_lo[0, h])) <= band)) if band else 0
+        assert abs(int(ad[0, h]) - len(new)) <= near
+        if len(union) > cap + near:
+            assert ov[0, h] == 1 and on[0, h] == cap
+            if near == 0:
+                np.testing.assert_array_equal(oi[0, h, :cap], union[:cap])
+        elif len(union) <= cap - near:
+            assert ov[0, h] == 0
+            got = oi[0, h, : on[0, h]]
+            assert np.all(np.diff(got) > 0)
+            ok, bad = sets_equal_up_to_cut(got, union, a * scores[0, h].astype(np.float64), float(tau_lo[0, h]), band)
+            assert ok, bad
+    # no input list at all: pure threshold selection
+    ekv.ekv_select_box_threshold(st.cfg, st.box, st.inp["seq_lens"], tau_d, None, None, out_idx, out_n, added, ovf,
+                                 st.workspace(ekv.EKV_OP_SELECT_BOX_THRESHOLD))
+    torch.cuda.synchronize()
+    oi, on, ad = out_idx.cpu().numpy(), out_n.cpu().numpy(), added.cpu().numpy()
+    for h in (0, 2, 4, 5):
+        ref = orc.box_threshold_pages(scores[0, h].astype(np.float64), alpha, float(tau_lo[0, h]))
+        if len(ref) <= cap:
+            np.testing.assert_array_equal(oi[0, h, : on[0, h]], ref)
+            assert ad[0, h] == len(ref)
+
+
+@pytest.mark.parametrize("w", [W1S, W2, W5B], ids=["C1-soft", "C2-8k", "C5-small-a2"])
+def test_one_refinement_after_topk_reaches_the_full_cache_result(w):
+    """top-k with a small budget -> sparse decode -> box-threshold refinement with the sparse tau -> sparse
+    decode again: the second result is the full-cache result (oracle), and refining once more adds nothing."""
+    inp = get_inputs(w)
+    st = DeviceState(w, inp)                                   # cap = every page
+    k = max(2, w.pages_per_seq // 64)
+    ekv.ekv_stats_build(st.cfg, st.cache(), st.stats())
+    ekv.ekv_score_pages(st.cfg, st.inp["q"], st.stats(), st.inp["seq_lens"], ekv.EKV_SCORE_BOX, st.box)
+    ekv.ekv_select_topk(st.cfg, st.box, st.inp["seq_lens"], k, st.page_idx, st.n_sel, st.workspace(ekv.EKV_OP_SELECT_TOPK))
+    wsd = st.workspace(ekv.EKV_OP_DECODE_SPARSE)
+    wsb = st.workspace(ekv.EKV_OP_SELECT_BOX_THRESHOLD)
+    ekv.ekv_decode_sparse(st.cfg, st.inp["q"], st.cache(), st.page_idx, st.n_sel, st.out, st.tau, st.supp, wsd)
+    tau_first = st.tau.clone()
+    added, ovf = torch.zeros_like(st.n_sel), torch.zeros_like(st.n_sel)
+    ekv.ekv_select_box_threshold(st.cfg, st.box, st.inp["seq_lens"], st.tau, st.page_idx, st.n_sel, st.page_idx,
+                                 st.n_sel, added, ovf, wsb)                      # in place
+    ekv.ekv_decode_sparse(st.cfg, st.inp["q"], st.cache(), st.page_idx, st.n_sel, st.out, st.tau, st.supp, wsd)
+    added2 = torch.zeros_like(st.n_sel)
+    ekv.ekv_select_box_threshold(st.cfg, st.box, st.inp["seq_lens"], st.tau, st.page_idx, st.n_sel, st.page_idx,
+                                 st.n_sel, added2, ovf, wsb)
+    torch.cuda.synchronize()
+    assert int(ovf.sum()) == 0
+    assert int(added.sum()) > 0                                # the small budget did miss pages
+    assert bool((st.tau >= tau_first - 1e-6).all())            # sparse thresholds only rise towards the full one
+    # the refined threshold is exact, so at most pages whose bound sits on it can still be "added"
+    assert int(added2.sum()) <= 2
+    for (b, hq) in sample_units(w, 4):
+        q, K, V = unit_kv(inp, w, b, hq)
+        ref = orc.entmax_attention(q, K, V, w.alpha, w.score_scale)
+        check_decode_unit(w, st.out[b, hq].cpu().numpy(), float(st.tau[b, hq]), int(st.supp[b, hq]), None, ref)
