@@ -303,6 +303,18 @@ def main():
                 "rho_mean": round(float((kept_supp.float() / supp_f.float()).mean()), 4),
                 "R_mean": round(float(R), 6),
                 "step_us": None}
+        # exactness certificate / refinement: pages whose box bound exceeds the sparse tau (App. B.2)
+        ekv.ekv_select_topk(st0.cfg, st0.box, st0.inp["seq_lens"], k_pages, st0.page_idx, st0.n_sel, st0.workspace(ekv.EKV_OP_SELECT_TOPK))
+        ekv.ekv_decode_sparse(st0.cfg, st0.inp["q"], st0.cache(), st0.page_idx, st0.n_sel, st0.out, st0.tau,
+                              st0.supp, st0.ws_sparse)
+        ref_idx, ref_n = torch.zeros_like(st0.page_idx), torch.zeros_like(st0.n_sel)
+        n_added, ovf = torch.zeros_like(st0.n_sel), torch.zeros_like(st0.n_sel)
+        ws_box = st0.workspace(ekv.EKV_OP_SELECT_BOX_THRESHOLD)
+        extras["box_threshold_refine_us"] = round(time_call(
+            lambda st: ekv.ekv_select_box_threshold(st0.cfg, st0.box, st0.inp["seq_lens"], st0.tau, st0.page_idx,
+                                                    st0.n_sel, ref_idx, ref_n, n_added, ovf, ws_box), reps=10), 2)
+        extras["box_threshold_pages_added_mean"] = float(n_added.float().mean())
+        extras["box_threshold_overflow_heads"] = int(ovf.sum())
         lse_sel = torch.zeros_like(st0.tau)
         ws_sm = copies[0].workspace(ekv.EKV_OP_DECODE_SPARSE_SOFTMAX)
         ekv.ekv_select_topk(st0.cfg, st0.box, st0.inp["seq_lens"], k_pages, st0.page_idx, st0.n_sel, st0.workspace(ekv.EKV_OP_SELECT_TOPK))

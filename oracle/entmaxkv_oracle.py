@@ -131,6 +131,20 @@ def topk_pages(scores, k):
 
 
 # --------------------------------------------------------------------------------------
+# stage 3a': one page list per KV head, shared by the G query heads of its group
+# --------------------------------------------------------------------------------------
+def group_max_scores(box_heads):
+    """Page score of a KV-head group: the maximum over its query heads' box scores.
+
+    box_heads [G, M].  The paper selects "for each attention head" and does not treat
+    grouped-query attention; sharing one list per KV head is this repository's
+    variant.  The maximum keeps the bound of Sec. 4.2 Eq. 9 valid for every head of
+    the group (it is >= each head's own bound), so the exact-recovery and
+    box-threshold statements carry over head by head."""
+    return np.max(np.asarray(box_heads, dtype=np.float64), axis=0)
+
+
+# --------------------------------------------------------------------------------------
 # stage 3c: box-threshold selection (App. B.2, the proposition on page bounds)
 # --------------------------------------------------------------------------------------
 def box_threshold_pages(box, alpha, tau_lo):

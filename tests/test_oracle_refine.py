@@ -96,3 +96,47 @@ def test_one_refinement_from_any_start_is_exact(seed, alpha):
     spg = orc.entmax_attention(q, K, V, alpha, scale, orc.pages_to_tokens(good, P, n))
     _, added_g = orc.refine_selection(box, alpha, spg["tau"], good)
     assert len(added_g) == 0 and abs(spg["tau"] - full["tau"]) <= 1e-12
+
+
+# ---------------------------------------------------------------------------- group-shared selection
+def _group(seed, G=4, n=384, P=16, d=32, scale=0.6):
+    rng = np.random.default_rng(seed)
+    K = rng.standard_normal((n, d))
+    V = rng.standard_normal((n, d))
+    Q = rng.standard_normal((G, d))
+    for g in range(G):
+        idx = rng.choice(n, 4, replace=False)
+        K[idx] = 2.0 * Q[g] / np.linalg.norm(Q[g]) + 0.3 * rng.standard_normal((4, d))
+    kmin, kmax, *_ = orc.page_stats(K, P)
+    box = np.stack([orc.box_scores(Q[g], kmin, kmax, scale) for g in range(G)])
+    return Q, K, V, box
+
+
+def test_group_max_is_a_bound_for_every_head_and_reduces_for_one_head():
+    Q, K, V, box = _group(1)
+    gs = orc.group_max_scores(box)
+    assert gs.shape == (box.shape[1],)
+    for g in range(Q.shape[0]):
+        s = orc.token_scores(Q[g], K, 0.6)
+        page_max = s.reshape(-1, 16).max(axis=1)
+        assert np.all(gs >= box[g]) and np.all(gs >= page_max - 1e-12)
+    # every page's group score is attained by one of the heads
+    assert np.all(np.isin(gs, box))
+    assert np.array_equal(orc.group_max_scores(box[:1]), box[0])
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_group_threshold_selection_recovers_every_head_of_the_group(seed):
+    """Thresholding the group score at the smallest full-cache tau of the group keeps every head's
+    support pages, so each head's sparse result over the shared list equals its full-cache result."""
+    alpha, scale, P = 1.5, 0.6, 16
+    Q, K, V, box = _group(10 + seed)
+    n = K.shape[0]
+    full = [orc.entmax_attention(Q[g], K, V, alpha, scale) for g in range(Q.shape[0])]
+    tau_min = min(f["tau"] for f in full)
+    shared = orc.box_threshold_pages(orc.group_max_scores(box), alpha, tau_min)
+    tok = orc.pages_to_tokens(shared, P, n)
+    for g, f in enumerate(full):
+        assert set((f["support"] // P).tolist()) <= set(shared.tolist())
+        sp = orc.entmax_attention(Q[g], K, V, alpha, scale, tok)
+        assert abs(sp["tau"] - f["tau"]) <= 1e-12 and np.allclose(sp["o"], f["o"], rtol=0, atol=1e-12)
