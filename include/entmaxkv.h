@@ -42,7 +42,12 @@ typedef enum {
 typedef enum { EKV_F32 = 0, EKV_BF16 = 1 } ekv_dtype;
 
 /* Which page scores ekv_score_pages writes. */
-typedef enum { EKV_SCORE_BOX = 1, EKV_SCORE_GAUSS = 2, EKV_SCORE_BOTH = 3 } ekv_score_mode;
+typedef enum {
+  EKV_SCORE_BOX = 1,
+  EKV_SCORE_GAUSS = 2,
+  EKV_SCORE_BOTH = 3,
+  EKV_SCORE_GROUP_MAX = 4 /* with EKV_SCORE_BOX only: one score per KV head, the maximum over its query heads */
+} ekv_score_mode;
 
 /* Operations a workspace can be sized for. */
 typedef enum {
@@ -115,7 +120,13 @@ ekv_status ekv_stats_append(const ekv_config* cfg, const ekv_cache_view* cache,
  *   box[b,h,p]   = scale * sum_i max(q_i kmin_i, q_i kmax_i)          (mode & EKV_SCORE_BOX)
  *   mu[b,h,p]    = scale * q . k_avg                                   (mode & EKV_SCORE_GAUSS)
  *   sigma[b,h,p] = scale * sqrt(sum_i q_i^2 k_var,i)                   (mode & EKV_SCORE_GAUSS)
- * Entries p >= M_b are written as -inf (box, mu) and 0 (sigma). */
+ * Entries p >= M_b are written as -inf (box, mu) and 0 (sigma).
+ * mode == EKV_SCORE_BOX | EKV_SCORE_GROUP_MAX writes instead box f32 [B][Hkv][Mmax], the maximum of the G
+ * query heads' box scores of each KV head: the score of a page list shared by the group (the paper
+ * selects per attention head and does not treat grouped-query attention; the maximum keeps Eq. 9 an
+ * upper bound for every head of the group).  Select on it with a config whose n_q_heads equals
+ * n_kv_heads (ekv_select_topk and ekv_select_box_threshold have batch x n_q_heads rows), then decode with
+ * ekv_decode_sparse_group. */
 ekv_status ekv_score_pages(const ekv_config* cfg, const void* q, const ekv_stats_view* stats,
                            const int32_t* seq_lens, int32_t mode, float* box, float* mu,
                            float* sigma, void* stream);
@@ -187,6 +198,16 @@ ekv_status ekv_decode_sparse(const ekv_config* cfg, const void* q, const ekv_cac
                              const int32_t* page_idx, const int32_t* n_sel, float* out, float* tau,
                              int32_t* supp, const ekv_decode_extras* extras, void* workspace,
                              size_t workspace_bytes, void* stream);
+
+/* a7, page lists shared per KV head: as ekv_decode_sparse, but page_idx int32 [B][Hkv][cap] and n_sel
+ * int32 [B][Hkv] hold one list per KV head and every query head of the group attends over it (its own
+ * tau, support and output).  K of a selected page is read once for the whole group (a [G x d] x [d x P]
+ * tile on the matrix cores), i.e. 1/G of the per-head gather.  Outputs, extras and workspace
+ * (EKV_OP_DECODE_SPARSE) are those of ekv_decode_sparse. */
+ekv_status ekv_decode_sparse_group(const ekv_config* cfg, const void* q, const ekv_cache_view* cache,
+                                   const int32_t* page_idx, const int32_t* n_sel, float* out,
+                                   float* tau, int32_t* supp, const ekv_decode_extras* extras,
+                                   void* workspace, size_t workspace_bytes, void* stream);
 
 /* a8 -- dense full-cache alpha-entmax decode (Sec. 2.1 Eq. 1 with pi = entmax): ekv_decode_sparse
  * with every page p < M_b selected.  K is streamed once per KV head for its G query heads. */

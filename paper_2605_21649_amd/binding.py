@@ -15,15 +15,16 @@ LIB_PATH = os.path.join(_HERE, "libentmaxkv.so")
 
 EKV_OK = 0
 EKV_F32, EKV_BF16 = 0, 1
-EKV_SCORE_BOX, EKV_SCORE_GAUSS, EKV_SCORE_BOTH = 1, 2, 3
+EKV_SCORE_BOX, EKV_SCORE_GAUSS, EKV_SCORE_BOTH, EKV_SCORE_GROUP_MAX = 1, 2, 3, 4
 EKV_OP_SELECT_TOPK, EKV_OP_SELECT_GAUSS, EKV_OP_DECODE_SPARSE, EKV_OP_DECODE_FULL, \
     EKV_OP_DECODE_SPARSE_SOFTMAX, EKV_OP_SELECT_BOX_THRESHOLD = range(6)
 
 # every symbol the header declares
 EXPORTS = ["ekv_stats_build", "ekv_stats_append", "ekv_score_pages", "ekv_select_topk", "ekv_select_gauss",
-           "ekv_select_box_threshold", "ekv_decode_sparse", "ekv_decode_full", "ekv_decode_sparse_softmax",
-           "ekv_workspace_bytes", "ekv_status_string", "ekv_last_hip_error", "ekv_version"]
-_STATUS_CALLS = EXPORTS[:10]      # entry points that return ekv_status
+           "ekv_select_box_threshold", "ekv_decode_sparse", "ekv_decode_sparse_group", "ekv_decode_full",
+           "ekv_decode_sparse_softmax", "ekv_workspace_bytes", "ekv_status_string", "ekv_last_hip_error",
+           "ekv_version"]
+_STATUS_CALLS = EXPORTS[:11]      # entry points that return ekv_status
 
 
 class ekv_config(ctypes.Structure):
@@ -73,6 +74,7 @@ def load_library():
                                      c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
     lib.ekv_decode_sparse.argtypes = [P(ekv_config), c_void_p, P(ekv_cache_view), c_void_p, c_void_p, c_void_p,
                                       c_void_p, c_void_p, P(ekv_decode_extras), c_void_p, c_size_t, c_void_p]
+    lib.ekv_decode_sparse_group.argtypes = lib.ekv_decode_sparse.argtypes
     lib.ekv_decode_full.argtypes = [P(ekv_config), c_void_p, P(ekv_cache_view), c_void_p, c_void_p, c_void_p,
                                     P(ekv_decode_extras), c_void_p, c_size_t, c_void_p]
     lib.ekv_decode_sparse_softmax.argtypes = [P(ekv_config), c_void_p, P(ekv_cache_view), c_void_p, c_void_p,
@@ -179,6 +181,14 @@ def ekv_decode_sparse(cfg, q, cache, page_idx, n_sel, out, tau, supp, workspace,
     _check(load_library().ekv_decode_sparse(byref(cfg), _ptr(q), byref(cache), _ptr(page_idx), _ptr(n_sel),
                                             _ptr(out), _ptr(tau), _ptr(supp), ex, _ptr(workspace), nbytes,
                                             _stream(stream)))
+
+
+def ekv_decode_sparse_group(cfg, q, cache, page_idx, n_sel, out, tau, supp, workspace, extras=None, stream=None):
+    nbytes = workspace.numel() * workspace.element_size()
+    ex = byref(extras) if extras is not None else None
+    _check(load_library().ekv_decode_sparse_group(byref(cfg), _ptr(q), byref(cache), _ptr(page_idx), _ptr(n_sel),
+                                                  _ptr(out), _ptr(tau), _ptr(supp), ex, _ptr(workspace), nbytes,
+                                                  _stream(stream)))
 
 
 def ekv_decode_full(cfg, q, cache, out, tau, supp, workspace, extras=None, stream=None):

@@ -142,7 +142,8 @@ ekv_status ekv_score_pages(const ekv_config* cfg, const void* q, const ekv_stats
   Dims dm;
   const ekv_status s = make_dims(cfg, dm);
   if (s != EKV_OK) return s;
-  if (mode < 1 || mode > 3 || !ok_ptr(q) || stats == nullptr || !ok_ptr4(seq_lens)) return EKV_ERR_INVALID_ARG;
+  const bool ok_mode = (mode >= 1 && mode <= 3) || mode == (EKV_SCORE_BOX | EKV_SCORE_GROUP_MAX);
+  if (!ok_mode || !ok_ptr(q) || stats == nullptr || !ok_ptr4(seq_lens)) return EKV_ERR_INVALID_ARG;
   if ((mode & EKV_SCORE_BOX) && (!ok_ptr(stats->box) || !ok_ptr4(box))) return EKV_ERR_INVALID_ARG;
   if ((mode & EKV_SCORE_GAUSS) && (!ok_ptr(stats->gauss) || !ok_ptr4(mu) || !ok_ptr4(sigma)))
     return EKV_ERR_INVALID_ARG;
@@ -210,7 +211,7 @@ ekv_status ekv_select_box_threshold(const ekv_config* cfg, const float* box, con
   return finish((hipStream_t)stream);
 }
 
-static ekv_status decode_common(const ekv_config* cfg, bool dense, const void* q, const ekv_cache_view* cache,
+static ekv_status decode_common(const ekv_config* cfg, bool dense, bool grouped, const void* q, const ekv_cache_view* cache,
                                 const int32_t* page_idx, const int32_t* n_sel, float* out, float* tau,
                                 int32_t* supp, const ekv_decode_extras* extras, void* workspace,
                                 size_t workspace_bytes, void* stream) {
@@ -232,7 +233,7 @@ static ekv_status decode_common(const ekv_config* cfg, bool dense, const void* q
   const size_t need = decode_ws_carve(dm, dense, nullptr, nullptr);
   if (workspace == nullptr || !aligned16(workspace) || workspace_bytes < need) return EKV_ERR_WORKSPACE;
   decode_ws_carve(dm, dense, workspace, &ws);
-  launch_decode(dm, dense, q, *cache, page_idx, n_sel, out, tau, supp, ex, ws, (hipStream_t)stream);
+  launch_decode(dm, dense, grouped, q, *cache, page_idx, n_sel, out, tau, supp, ex, ws, (hipStream_t)stream);
   return finish((hipStream_t)stream);
 }
 
@@ -240,15 +241,23 @@ ekv_status ekv_decode_sparse(const ekv_config* cfg, const void* q, const ekv_cac
                              const int32_t* page_idx, const int32_t* n_sel, float* out, float* tau, int32_t* supp,
                              const ekv_decode_extras* extras, void* workspace, size_t workspace_bytes,
                              void* stream) {
-  return decode_common(cfg, false, q, cache, page_idx, n_sel, out, tau, supp, extras, workspace, workspace_bytes,
-                       stream);
+  return decode_common(cfg, false, false, q, cache, page_idx, n_sel, out, tau, supp, extras, workspace,
+                       workspace_bytes, stream);
 }
 
 ekv_status ekv_decode_full(const ekv_config* cfg, const void* q, const ekv_cache_view* cache, float* out,
                            float* tau, int32_t* supp, const ekv_decode_extras* extras, void* workspace,
                            size_t workspace_bytes, void* stream) {
-  return decode_common(cfg, true, q, cache, nullptr, nullptr, out, tau, supp, extras, workspace, workspace_bytes,
-                       stream);
+  return decode_common(cfg, true, false, q, cache, nullptr, nullptr, out, tau, supp, extras, workspace,
+                       workspace_bytes, stream);
+}
+
+ekv_status ekv_decode_sparse_group(const ekv_config* cfg, const void* q, const ekv_cache_view* cache,
+                                   const int32_t* page_idx, const int32_t* n_sel, float* out, float* tau,
+                                   int32_t* supp, const ekv_decode_extras* extras, void* workspace,
+                                   size_t workspace_bytes, void* stream) {
+  return decode_common(cfg, false, true, q, cache, page_idx, n_sel, out, tau, supp, extras, workspace,
+                       workspace_bytes, stream);
 }
 
 ekv_status ekv_decode_sparse_softmax(const ekv_config* cfg, const void* q, const ekv_cache_view* cache,

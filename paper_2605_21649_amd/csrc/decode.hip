@@ -29,8 +29,11 @@ typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 // ------------------------------------------------------------------------------------------
 // pass 1: scores
 // ------------------------------------------------------------------------------------------
-// DENSE: unit = (b, KV head); the G query heads of the group are scored from one read of K.
-// sparse: unit = (b, query head) with its own page list (G = 1).
+// Candidate source of a launch: per query head its own page list (unit = (b, query head), G = 1);
+// every page of the sequence; or one page list per KV head shared by its G query heads.  In the last
+// two the unit is (b, KV head) and the G heads are scored from one read of K.
+enum : int { kPerHead = 0, kAllPages = 1, kGroupList = 2 };
+
 struct ScoreArgs {
   const void* q; const void* k_pool;
   const int32_t* block_table; const int32_t* seq_lens; const int32_t* page_idx; const int32_t* n_sel;
@@ -50,15 +53,16 @@ constexpr int kScoreWaves = kScoreThreads / 64;
 __device__ __forceinline__ int clampi(int x, int lo, int hi) { return min(max(x, lo), hi); }
 
 // Generic path (float32 caches, or page sizes that are not 16, 32 or 64): FMAs + DPP row sums.
-template <typename T, int G, bool DENSE>
+template <typename T, int G, int MODE>
 __global__ __launch_bounds__(kScoreThreads) void decode_scores_valu_kernel(const ScoreArgs A) {
+  constexpr bool DENSE = MODE == kAllPages, GROUPED = MODE != kPerHead;
   const T* q = (const T*)A.q;
   const T* k_pool = (const T*)A.k_pool;
   const int P = A.P, Hq = A.Hq, Hkv = A.Hkv;
   const int unit = blockIdx.y;
-  const int b = DENSE ? unit / Hkv : unit / Hq;
-  const int hkv = DENSE ? unit % Hkv : (unit % Hq) / (Hq / Hkv);
-  const int hq0 = DENSE ? hkv * G : unit % Hq;            // first (only) query head of this unit
+  const int b = GROUPED ? unit / Hkv : unit / Hq;
+  const int hkv = GROUPED ? unit % Hkv : (unit % Hq) / (Hq / Hkv);
+  const int hq0 = GROUPED ? hkv * G : unit % Hq;            // first (only) query head of this unit
   const int n = A.seq_lens[b];
   const int n_slots = clampi(DENSE ? (n + P - 1) / P : A.n_sel[unit], 0, DENSE ? A.Mmax : A.cap);
   const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -102,7 +106,7 @@ __global__ __launch_bounds__(kScoreThreads) void decode_scores_valu_kernel(const
         if (c < s1 - s0) {
 #pragma unroll
           for (int g = 0; g < G; ++g) {
-            const size_t row = DENSE ? (size_t)b * Hq + hq0 + g : (size_t)unit;
+            const size_t row = GROUPED ? (size_t)b * Hq + hq0 + g : (size_t)unit;
             A.zbuf[row * A.zstride + (size_t)slot * P + 4 * (s0 + c) + r] = zkeep[g];
           }
         }
@@ -113,15 +117,16 @@ __global__ __launch_bounds__(kScoreThreads) void decode_scores_valu_kernel(const
       float m = wmax[g];                                   // equal over the 16 lanes of a row
       m = fmaxf(m, __shfl_xor(m, 16));
       m = fmaxf(m, __shfl_xor(m, 32));
-      const size_t row = DENSE ? (size_t)b * Hq + hq0 + g : (size_t)unit;
+      const size_t row = GROUPED ? (size_t)b * Hq + hq0 + g : (size_t)unit;
       if (lane == 0) A.pmax[row * A.n_chunks_max + grp] = m;
     }
   }
 }
 
 // bf16 pages with P in {16, 32, 64}: matrix-core path.
-template <int G, bool DENSE, int PT>
+template <int G, int MODE, int PT>
 __global__ __launch_bounds__(kScoreThreads) void decode_scores_mfma_kernel(const ScoreArgs A) {
+  constexpr bool DENSE = MODE == kAllPages, GROUPED = MODE != kPerHead;
   constexpr int NSET = (G + 3) / 4;
   constexpr int STEPS = PT / 4;                   // 16-byte loads per lane and page
   constexpr int KEEP = PT / 16;                   // z values a lane keeps per page and column set
@@ -131,9 +136,9 @@ __global__ __launch_bounds__(kScoreThreads) void decode_scores_mfma_kernel(const
   const bf16_t* k_pool = (const bf16_t*)A.k_pool;
   const int Hq = A.Hq, Hkv = A.Hkv;
   const int unit = blockIdx.y;
-  const int b = DENSE ? unit / Hkv : unit / Hq;
-  const int hkv = DENSE ? unit % Hkv : (unit % Hq) / (Hq / Hkv);
-  const int hq0 = DENSE ? hkv * G : unit % Hq;
+  const int b = GROUPED ? unit / Hkv : unit / Hq;
+  const int hkv = GROUPED ? unit % Hkv : (unit % Hq) / (Hq / Hkv);
+  const int hq0 = GROUPED ? hkv * G : unit % Hq;
   const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wslot0 = (blockIdx.x * kScoreWaves + w) * SW;
   const int m = lane & 15, j = lane >> 4;          // MFMA row/column index, K group
@@ -201,7 +206,7 @@ __global__ __launch_bounds__(kScoreThreads) void decode_scores_mfma_kernel(const
         for (int cs = 0; cs < NSET; ++cs) {
           const int g = 4 * cs + gl;
           if (g < G) {
-            const size_t row = DENSE ? (size_t)b * Hq + hq0 + g : (size_t)unit;
+            const size_t row = GROUPED ? (size_t)b * Hq + hq0 + g : (size_t)unit;
             float* zp = A.zbuf + row * A.zstride + (size_t)slot * PT + j;
 #pragma unroll
             for (int t = 0; t < KEEP; ++t) zp[4 * (4 * t + kq)] = zkeep[cs][t];
@@ -216,7 +221,7 @@ __global__ __launch_bounds__(kScoreThreads) void decode_scores_mfma_kernel(const
       mx = fmaxf(mx, __shfl_xor(mx, 32));
       const int g = 4 * cs + gl;
       if (j == 0 && kq == 0 && g < G) {
-        const size_t row = DENSE ? (size_t)b * Hq + hq0 + g : (size_t)unit;
+        const size_t row = GROUPED ? (size_t)b * Hq + hq0 + g : (size_t)unit;
         A.pmax[row * A.n_chunks_max + (wslot0 / GP + gi)] = mx;
       }
     }
@@ -244,14 +249,15 @@ constexpr int kFilterNoGrid = 0x7fffffff;                           // record ma
 struct FilterArgs {
   const int32_t* seq_lens; const int32_t* n_sel; const float* zbuf;
   int32_t* fhist; int32_t* fcount; float* frow; float* flist_u; int32_t* flist_pos;
-  int Hq, P, n_slices_max, max_slots;
+  int Hq, Hkv, grouped, P, n_slices_max, max_slots;
   size_t zstride;
   float beta; int ibeta;
 };
 
 template <bool DENSE>
 __device__ __forceinline__ int filter_n_cand(const FilterArgs& A, int row) {
-  const int slots = DENSE ? (A.seq_lens[row / A.Hq] + A.P - 1) / A.P : A.n_sel[row];
+  const int lrow = A.grouped ? (row / A.Hq) * A.Hkv + (row % A.Hq) / (A.Hq / A.Hkv) : row;
+  const int slots = DENSE ? (A.seq_lens[row / A.Hq] + A.P - 1) / A.P : A.n_sel[lrow];
   return clampi(slots, 0, A.max_slots) * A.P;
 }
 
@@ -523,6 +529,7 @@ struct SolveArgs {
   float a, beta; int ibeta;
   // results of the filter passes (null for short rows)
   const int32_t* fcount; const float* frow; const float* flist_u; const int32_t* flist_pos; int n_slices_max;
+  int grouped;
 };
 
 // V row index (phys*Hkv + hkv)*P + tok of candidate position `pos`.
@@ -570,7 +577,8 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
   const uint64_t lt = (1ull << lane) - 1ull;
   const T* v_pool = (const T*)A.v_pool;
   const int n = A.seq_lens[b];
-  const int n_slots = clampi(DENSE ? (n + P - 1) / P : A.n_sel[bh], 0, DENSE ? A.Mmax : A.cap);
+  const int lrow = A.grouped ? b * Hkv + hkv : bh;          // row of the page list this head reads
+  const int n_slots = clampi(DENSE ? (n + P - 1) / P : A.n_sel[lrow], 0, DENSE ? A.Mmax : A.cap);
   const int n_cand = n_slots * P;
   const int n_chunks = (n_slots + pmax_pages(P) - 1) / pmax_pages(P);
   const int chunk_tokens = pmax_pages(P) * P;
@@ -712,7 +720,7 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
 #pragma unroll
     for (int k = 0; k < kListCap / kSolveThreads; ++k) {
       const int e = min(tid + k * kSolveThreads, n_list - 1);      // clamped: loads stay unconditional
-      rowreg[k] = v_row_of<DENSE>(A, b, bh, hkv, sh.list_pos[e]);
+      rowreg[k] = v_row_of<DENSE>(A, b, lrow, hkv, sh.list_pos[e]);
     }
     const ListSrc ls{sh.list_u, sh.list_pos, n_list};
     tau_u = solve_tau(ls, lo_u, beta, ibeta, sh, supp);
@@ -761,7 +769,7 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
     if (A.ex.support_tokens != nullptr) {
       int32_t* dst = A.ex.support_tokens + (size_t)bh * A.ex.support_cap;
       for (int e = tid; e < n_sup && e < A.ex.support_cap; e += kSolveThreads)
-        dst[e] = token_of<DENSE>(A, bh, sh.list_pos[e]);
+        dst[e] = token_of<DENSE>(A, lrow, sh.list_pos[e]);
     }
   } else {
     // the candidates do not fit in LDS: stream the score row for every evaluation
@@ -776,7 +784,7 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
       if (x > 0.f) {
         const float p = pow_beta(x, beta, ibeta);
         float vv[8];
-        load8<T>(v_pool + (size_t)v_row_of<DENSE>(A, b, bh, hkv, e) * kD + 8 * c, vv);
+        load8<T>(v_pool + (size_t)v_row_of<DENSE>(A, b, lrow, hkv, e) * kD + 8 * c, vv);
 #pragma unroll
         for (int i = 0; i < 8; ++i) acc[i] = fmaf(p, vv[i], acc[i]);
       }
@@ -796,7 +804,7 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
         for (int k = 0; k < kSolveWaves; ++k) { const int ck = sh.wcount[0][k]; if (k < w) off += ck; tot += ck; }
         if (in) {
           off += __popcll(mk & lt);
-          if (off < A.ex.support_cap) dst[off] = token_of<DENSE>(A, bh, i);
+          if (off < A.ex.support_cap) dst[off] = token_of<DENSE>(A, lrow, i);
         }
         base += tot;
       }
@@ -833,19 +841,19 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
 // ------------------------------------------------------------------------------------------
 // launchers
 // ------------------------------------------------------------------------------------------
-template <int G, bool DENSE>
+template <int G, int MODE>
 static void launch_scores(const Dims& dm, dim3 grid, const ScoreArgs& sa, hipStream_t st) {
   dim3 block(kScoreThreads);
   if (dm.dtype == EKV_BF16 && dm.P == 16)
-    hipLaunchKernelGGL((decode_scores_mfma_kernel<G, DENSE, 16>), grid, block, 0, st, sa);
+    hipLaunchKernelGGL((decode_scores_mfma_kernel<G, MODE, 16>), grid, block, 0, st, sa);
   else if (dm.dtype == EKV_BF16 && dm.P == 32)
-    hipLaunchKernelGGL((decode_scores_mfma_kernel<G, DENSE, 32>), grid, block, 0, st, sa);
+    hipLaunchKernelGGL((decode_scores_mfma_kernel<G, MODE, 32>), grid, block, 0, st, sa);
   else if (dm.dtype == EKV_BF16 && dm.P == 64)
-    hipLaunchKernelGGL((decode_scores_mfma_kernel<G, DENSE, 64>), grid, block, 0, st, sa);
+    hipLaunchKernelGGL((decode_scores_mfma_kernel<G, MODE, 64>), grid, block, 0, st, sa);
   else if (dm.dtype == EKV_BF16)
-    hipLaunchKernelGGL((decode_scores_valu_kernel<bf16_t, G, DENSE>), grid, block, 0, st, sa);
+    hipLaunchKernelGGL((decode_scores_valu_kernel<bf16_t, G, MODE>), grid, block, 0, st, sa);
   else
-    hipLaunchKernelGGL((decode_scores_valu_kernel<float, G, DENSE>), grid, block, 0, st, sa);
+    hipLaunchKernelGGL((decode_scores_valu_kernel<float, G, MODE>), grid, block, 0, st, sa);
 }
 
 size_t decode_ws_carve(const Dims& dm, bool dense, void* base, DecodeWorkspace* ws) {
@@ -880,7 +888,7 @@ size_t decode_ws_carve(const Dims& dm, bool dense, void* base, DecodeWorkspace* 
   return off;
 }
 
-void launch_decode(const Dims& dm, bool dense, const void* q, const ekv_cache_view& c,
+void launch_decode(const Dims& dm, bool dense, bool grouped, const void* q, const ekv_cache_view& c,
                    const int32_t* page_idx, const int32_t* n_sel, float* out, float* tau, int32_t* supp,
                    const ekv_decode_extras& ex, const DecodeWorkspace& ws, hipStream_t st) {
   ScoreArgs sa{q, c.k_pool, c.block_table, c.seq_lens, page_idx, n_sel, ws.z, ws.pmax,
@@ -889,8 +897,9 @@ void launch_decode(const Dims& dm, bool dense, const void* q, const ekv_cache_vi
                dm.Hq, dm.Hkv, dm.P, dm.Mmax, dm.cap, ws.n_chunks_max, c.n_phys_pages, ws.zstride, dm.a, dm.beta, dm.ibeta};
   so.fcount = ws.fcount; so.frow = ws.frow; so.flist_u = ws.flist_u; so.flist_pos = ws.flist_pos;
   so.n_slices_max = ws.n_slices_max;
+  so.grouped = grouped ? 1 : 0;
   FilterArgs fa{c.seq_lens, n_sel, ws.z, ws.fhist, ws.fcount, ws.frow, ws.flist_u, ws.flist_pos,
-                dm.Hq, dm.P, ws.n_slices_max, dense ? dm.Mmax : dm.cap, ws.zstride, dm.beta, dm.ibeta};
+                dm.Hq, dm.Hkv, grouped ? 1 : 0, dm.P, ws.n_slices_max, dense ? dm.Mmax : dm.cap, ws.zstride, dm.beta, dm.ibeta};
   dim3 fgrid(ws.n_slices_max, dm.B * dm.Hq), fblock(kFilterThreads);
   dim3 sgrid(dm.B * dm.Hq), sblock(kSolveThreads);
   const int slots_per_wg = kScoreWaves * kGroupsPerWave * pmax_pages(dm.P);
@@ -898,10 +907,10 @@ void launch_decode(const Dims& dm, bool dense, const void* q, const ekv_cache_vi
   if (dense) {
     dim3 grid(score_blocks, dm.B * dm.Hkv);
     switch (dm.G) {
-      case 1: launch_scores<1, true>(dm, grid, sa, st); break;
-      case 2: launch_scores<2, true>(dm, grid, sa, st); break;
-      case 4: launch_scores<4, true>(dm, grid, sa, st); break;
-      default: launch_scores<8, true>(dm, grid, sa, st); break;
+      case 1: launch_scores<1, kAllPages>(dm, grid, sa, st); break;
+      case 2: launch_scores<2, kAllPages>(dm, grid, sa, st); break;
+      case 4: launch_scores<4, kAllPages>(dm, grid, sa, st); break;
+      default: launch_scores<8, kAllPages>(dm, grid, sa, st); break;
     }
     if (ws.fcount != nullptr) {
       hipLaunchKernelGGL((filter_hist_kernel<true>), fgrid, fblock, 0, st, fa);
@@ -911,8 +920,17 @@ void launch_decode(const Dims& dm, bool dense, const void* q, const ekv_cache_vi
     if (dm.dtype == EKV_F32) hipLaunchKernelGGL((decode_solve_kernel<float, true>), sgrid, sblock, 0, st, so);
     else hipLaunchKernelGGL((decode_solve_kernel<bf16_t, true>), sgrid, sblock, 0, st, so);
   } else {
-    dim3 grid(score_blocks, dm.B * dm.Hq);
-    launch_scores<1, false>(dm, grid, sa, st);
+    if (grouped && dm.G > 1) {
+      dim3 grid(score_blocks, dm.B * dm.Hkv);
+      switch (dm.G) {
+        case 2: launch_scores<2, kGroupList>(dm, grid, sa, st); break;
+        case 4: launch_scores<4, kGroupList>(dm, grid, sa, st); break;
+        default: launch_scores<8, kGroupList>(dm, grid, sa, st); break;
+      }
+    } else {                                    // G == 1: a group list is a per-head list
+      dim3 grid(score_blocks, dm.B * dm.Hq);
+      launch_scores<1, kPerHead>(dm, grid, sa, st);
+    }
     if (ws.fcount != nullptr) {
       hipLaunchKernelGGL((filter_hist_kernel<false>), fgrid, fblock, 0, st, fa);
       hipLaunchKernelGGL((filter_level_kernel<false>), dim3(dm.B * dm.Hq), dim3(kLevelThreads), 0, st, fa);

@@ -53,7 +53,8 @@ void launch_select_topk(const Dims& dm, const float* box, const int32_t* seq_len
 void launch_select_gauss(const Dims& dm, const float* mu, const float* sigma, const int32_t* seq_lens,
                          const float* zq_table, float margin, float* tau_hat, int32_t* page_idx,
                          int32_t* n_sel, int32_t* overflow, void* ws, hipStream_t st);
-void launch_decode(const Dims& dm, bool dense, const void* q, const ekv_cache_view& c,
+// grouped: page_idx/n_sel have one row per (b, KV head), shared by the G query heads of the group
+void launch_decode(const Dims& dm, bool dense, bool grouped, const void* q, const ekv_cache_view& c,
                    const int32_t* page_idx, const int32_t* n_sel, float* out, float* tau, int32_t* supp,
                    const ekv_decode_extras& ex, const DecodeWorkspace& ws, hipStream_t st);
 void launch_decode_sparse_softmax(const Dims& dm, const void* q, const ekv_cache_view& c,

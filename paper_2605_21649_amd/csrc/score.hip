@@ -10,6 +10,8 @@
 // fully coalesced load; only the blocks with matching quarters are meaningful and are summed with
 // two DPP quad steps.  q^2 is split exactly into two bf16 values (a product of two 8-bit significands
 // has 16 bits).  float32 statistics use plain FMAs and DPP row reductions.
+// With EKV_SCORE_GROUP_MAX the box scores of the G heads are reduced to their maximum before they are
+// written (one list of pages per KV head, shared by its query heads).
 #include "ekv_device.h"
 #include "ekv_internal.h"
 
@@ -59,7 +61,8 @@ __global__ __launch_bounds__(256) void score_pages_mfma_kernel(const bf16_t* __r
                                                                const int32_t* __restrict__ seq_lens,
                                                                float* __restrict__ out0,   // box or mu
                                                                float* __restrict__ out1,   // sigma (GAUSS)
-                                                               int Hkv, int P, int Mmax, float scale) {
+                                                               int Hkv, int P, int Mmax, float scale,
+                                                               int group_max) {
   constexpr int NSET = (G + 3) / 4;                 // column sets of 4 heads
   __shared__ float stage[2][G][kScoreTile];
   const int b = blockIdx.z, h = blockIdx.y;
@@ -120,6 +123,17 @@ __global__ __launch_bounds__(256) void score_pages_mfma_kernel(const bf16_t* __r
     }
   }
   __syncthreads();
+  if (group_max) {                                   // one score per page and KV head: the group's maximum
+    for (int pt = threadIdx.x; pt < kScoreTile; pt += 256) {
+      const int p = tile0 + pt;
+      if (p >= Mmax) continue;
+      float v = stage[0][0][pt];
+#pragma unroll
+      for (int g = 1; g < G; ++g) v = fmaxf(v, stage[0][g][pt]);
+      out0[((size_t)b * Hkv + h) * Mmax + p] = p < M ? v : -INFINITY;
+    }
+    return;
+  }
   for (int idx = threadIdx.x; idx < G * kScoreTile; idx += 256) {
     const int g = idx / kScoreTile, pt = idx - g * kScoreTile;
     const int p = tile0 + pt;
@@ -137,7 +151,7 @@ __global__ __launch_bounds__(256) void score_pages_f32_kernel(const float* __res
                                                               const float* __restrict__ stats,
                                                               const int32_t* __restrict__ seq_lens,
                                                               float* __restrict__ out0, float* __restrict__ out1,
-                                                              int Hkv, int P, int Mmax, float scale) {
+                                                              int Hkv, int P, int Mmax, float scale, int group_max) {
   constexpr int kSteps = kScoreTile / 4 / 2;
   __shared__ float stage[2][G][kScoreTile];
   const int b = blockIdx.z, h = blockIdx.y;
@@ -180,6 +194,17 @@ __global__ __launch_bounds__(256) void score_pages_f32_kernel(const float* __res
     }
   }
   __syncthreads();
+  if (group_max) {                                   // one score per page and KV head: the group's maximum
+    for (int pt = threadIdx.x; pt < kScoreTile; pt += 256) {
+      const int p = tile0 + pt;
+      if (p >= Mmax) continue;
+      float v = stage[0][0][pt];
+#pragma unroll
+      for (int g = 1; g < G; ++g) v = fmaxf(v, stage[0][g][pt]);
+      out0[((size_t)b * Hkv + h) * Mmax + p] = p < M ? v : -INFINITY;
+    }
+    return;
+  }
   for (int idx = threadIdx.x; idx < G * kScoreTile; idx += 256) {
     const int g = idx / kScoreTile, pt = idx - g * kScoreTile;
     const int p = tile0 + pt;
@@ -195,20 +220,21 @@ template <int G>
 static void launch_score_G(const Dims& dm, const void* q, const ekv_stats_view& s, const int32_t* seq_lens,
                            int mode, float* box, float* mu, float* sigma, hipStream_t st) {
   dim3 grid((dm.Mmax + kScoreTile - 1) / kScoreTile, dm.Hkv, dm.B), block(256);
+  const int gmax = (mode & EKV_SCORE_GROUP_MAX) ? 1 : 0;
   if (dm.dtype == EKV_BF16) {
     if (mode & EKV_SCORE_BOX)
       hipLaunchKernelGGL((score_pages_mfma_kernel<G, false>), grid, block, 0, st, (const bf16_t*)q,
-                         (const bf16_t*)s.box, seq_lens, box, (float*)nullptr, dm.Hkv, dm.P, dm.Mmax, dm.scale);
+                         (const bf16_t*)s.box, seq_lens, box, (float*)nullptr, dm.Hkv, dm.P, dm.Mmax, dm.scale, gmax);
     if (mode & EKV_SCORE_GAUSS)
       hipLaunchKernelGGL((score_pages_mfma_kernel<G, true>), grid, block, 0, st, (const bf16_t*)q,
-                         (const bf16_t*)s.gauss, seq_lens, mu, sigma, dm.Hkv, dm.P, dm.Mmax, dm.scale);
+                         (const bf16_t*)s.gauss, seq_lens, mu, sigma, dm.Hkv, dm.P, dm.Mmax, dm.scale, 0);
   } else {
     if (mode & EKV_SCORE_BOX)
       hipLaunchKernelGGL((score_pages_f32_kernel<G, false>), grid, block, 0, st, (const float*)q,
-                         (const float*)s.box, seq_lens, box, (float*)nullptr, dm.Hkv, dm.P, dm.Mmax, dm.scale);
+                         (const float*)s.box, seq_lens, box, (float*)nullptr, dm.Hkv, dm.P, dm.Mmax, dm.scale, gmax);
     if (mode & EKV_SCORE_GAUSS)
       hipLaunchKernelGGL((score_pages_f32_kernel<G, true>), grid, block, 0, st, (const float*)q,
-                         (const float*)s.gauss, seq_lens, mu, sigma, dm.Hkv, dm.P, dm.Mmax, dm.scale);
+                         (const float*)s.gauss, seq_lens, mu, sigma, dm.Hkv, dm.P, dm.Mmax, dm.scale, 0);
   }
 }
 

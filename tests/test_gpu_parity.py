@@ -696,3 +696,85 @@ def test_one_refinement_after_topk_reaches_the_full_cache_result(w):
         q, K, V = unit_kv(inp, w, b, hq)
         ref = orc.entmax_attention(q, K, V, w.alpha, w.score_scale)
         check_decode_unit(w, st.out[b, hq].cpu().numpy(), float(st.tau[b, hq]), int(st.supp[b, hq]), None, ref)
+
+
+# ---------------------------------------------------------------------------- page lists shared per KV head
+def group_cfg(st, w, cap):
+    """Selection calls have batch x n_q_heads rows: for one list per KV head they get n_q_heads = n_kv_heads."""
+    return ekv.make_config(w.batch, w.n_kv_heads, w.n_kv_heads, w.head_dim, w.page_size, w.kv_dtype, w.alpha,
+                           w.score_scale, st.Mmax, cap)
+
+
+@pytest.mark.parametrize("w", [W1S, W2, W3, W5], ids=["C1-soft", "C2-8k", "C3-small", "C5-small"])
+def test_group_shared_step(w):
+    """Group-maximum page score -> top-k per KV head -> grouped sparse decode, stage by stage against the
+    oracle: scores on oracle statistics, the selected set up to cut ties, every query head's entmax over
+    the shared list."""
+    inp = get_inputs(w)
+    k = topk_budget(w)
+    st = DeviceState(w, inp, cap=k)
+    dev = st.box.device
+    stats = upload_oracle_stats(st, w, inp)
+    gbox = torch.zeros(w.batch, w.n_kv_heads, st.Mmax, device=dev)
+    ekv.ekv_score_pages(st.cfg, st.inp["q"], st.stats(), st.inp["seq_lens"], ekv.EKV_SCORE_BOX | ekv.EKV_SCORE_GROUP_MAX,
+                        gbox)
+    gcfg = group_cfg(st, w, k)
+    g_idx = torch.zeros(w.batch, w.n_kv_heads, k, device=dev, dtype=torch.int32)
+    g_n = torch.zeros(w.batch, w.n_kv_heads, device=dev, dtype=torch.int32)
+    ws_sel = torch.empty(max(256, ekv.ekv_workspace_bytes(gcfg, ekv.EKV_OP_SELECT_TOPK)), device=dev, dtype=torch.uint8)
+    ekv.ekv_select_topk(gcfg, gbox, st.inp["seq_lens"], k, g_idx, g_n, ws_sel)
+    supp_tok = torch.full((w.batch, w.n_q_heads, 4096), -1, device=dev, dtype=torch.int32)
+    ekv.ekv_decode_sparse_group(st.cfg, st.inp["q"], st.cache(), g_idx, g_n, st.out, st.tau, st.supp,
+                                st.workspace(ekv.EKV_OP_DECODE_SPARSE), extras=ekv.decode_extras(support_tokens=supp_tok))
+    torch.cuda.synchronize()
+    gb, gi, gn, toks = gbox.cpu().numpy(), g_idx.cpu().numpy(), g_n.cpu().numpy(), supp_tok.cpu().numpy()
+    G = w.group
+    for b in range(w.batch):
+        for hkv in range(w.n_kv_heads):
+            kmin, kmax, _, _, cnt = stats[(b, hkv)]
+            M = len(cnt)
+            heads = np.stack([orc.box_scores(to_f64(inp["q"][b, hkv * G + g]), kmin, kmax, w.score_scale)
+                              for g in range(G)])
+            ref_g = orc.group_max_scores(heads)
+            assert np.max(np.abs(gb[b, hkv, :M] - ref_g) / np.maximum(1.0, np.abs(ref_g))) <= 1e-5
+            assert np.all(np.isneginf(gb[b, hkv, M:]))
+            pages, cut_in, cut_out = orc.topk_pages(ref_g, k)
+            ok, bad = sets_equal_up_to_cut(gi[b, hkv, : gn[b, hkv]], pages, ref_g, [cut_in, cut_out],
+                                           1e-5 * max(1.0, abs(cut_in)))
+            assert ok, (b, hkv, bad)
+            if set(gi[b, hkv, : gn[b, hkv]].tolist()) != set(pages.tolist()):
+                continue
+            for g in range(G if (b, hkv) in ((0, 0), (w.batch - 1, w.n_kv_heads - 1)) else 0):
+                hq = hkv * G + g
+                q, K, V = unit_kv(inp, w, b, hq)
+                ref = orc.entmax_attention(q, K, V, w.alpha, w.score_scale, orc.pages_to_tokens(pages, w.page_size, K.shape[0]))
+                check_decode_unit(w, st.out[b, hq].cpu().numpy(), float(st.tau[b, hq]), int(st.supp[b, hq]),
+                                  toks[b, hq], ref)
+
+
+def test_group_decode_equals_per_head_decode_on_the_same_lists():
+    """The same page list given once per KV head, or copied to each of its query heads, must give
+    bit-identical results: only the way K is read differs."""
+    w = W2
+    inp = get_inputs(w)
+    k = 96
+    st = DeviceState(w, inp, cap=k)
+    dev = st.box.device
+    rng = np.random.default_rng(9)
+    n_pages = -(-int(inp["seq_lens"][0]) // w.page_size)
+    g_idx = torch.zeros(w.batch, w.n_kv_heads, k, device=dev, dtype=torch.int32)
+    g_n = torch.zeros(w.batch, w.n_kv_heads, device=dev, dtype=torch.int32)
+    for hkv in range(w.n_kv_heads):
+        cnt = k - (hkv % 3) * 7                                     # ragged list lengths
+        pages = np.sort(rng.choice(n_pages, cnt, replace=False)).astype(np.int32)
+        g_idx[0, hkv, :cnt] = torch.from_numpy(pages).to(dev)
+        g_n[0, hkv] = cnt
+        for g in range(w.group):
+            st.page_idx[0, hkv * w.group + g, :cnt] = torch.from_numpy(pages).to(dev)
+            st.n_sel[0, hkv * w.group + g] = cnt
+    wsd = st.workspace(ekv.EKV_OP_DECODE_SPARSE)
+    ekv.ekv_decode_sparse(st.cfg, st.inp["q"], st.cache(), st.page_idx, st.n_sel, st.out, st.tau, st.supp, wsd)
+    out_g, tau_g, supp_g = torch.zeros_like(st.out), torch.zeros_like(st.tau), torch.zeros_like(st.supp)
+    ekv.ekv_decode_sparse_group(st.cfg, st.inp["q"], st.cache(), g_idx, g_n, out_g, tau_g, supp_g, wsd)
+    torch.cuda.synchronize()
+    assert torch.equal(tau_g, st.tau) and torch.equal(supp_g, st.supp) and torch.equal(out_g, st.out)
