@@ -303,6 +303,33 @@ def main():
                 "rho_mean": round(float((kept_supp.float() / supp_f.float()).mean()), 4),
                 "R_mean": round(float(R), 6),
                 "step_us": None}
+        # one page list per KV head shared by its G query heads (same budget of pages per list)
+        gcfg = ekv.make_config(B, Hkv, Hkv, d, P, w.kv_dtype, w.alpha, w.score_scale, M, cap)
+        gbox = torch.zeros(B, Hkv, M, device=dev)
+        g_idx = torch.zeros(B, Hkv, cap, device=dev, dtype=torch.int32)
+        g_n = torch.zeros(B, Hkv, device=dev, dtype=torch.int32)
+        ws_gsel = torch.empty(max(256, ekv.ekv_workspace_bytes(gcfg, ekv.EKV_OP_SELECT_TOPK)), device=dev,
+                              dtype=torch.uint8)
+
+        def step_group(st, evs=None):
+            if evs: evs[0].record()
+            ekv.ekv_stats_append(st.cfg, st.cache_prev, st.stats(), st.k_new, st.v_new)
+            if evs: evs[1].record()
+            ekv.ekv_score_pages(st.cfg, st.inp["q"], st.stats(), st.inp["seq_lens"],
+                                ekv.EKV_SCORE_BOX | ekv.EKV_SCORE_GROUP_MAX, gbox)
+            if evs: evs[2].record()
+            ekv.ekv_select_topk(gcfg, gbox, st.inp["seq_lens"], k_pages, g_idx, g_n, ws_gsel)
+            if evs: evs[3].record()
+            ekv.ekv_decode_sparse_group(st.cfg, st.inp["q"], st.cache(), g_idx, g_n, st.out, st.tau, st.supp,
+                                        st.ws_sparse)
+            if evs: evs[4].record()
+
+        us_gr, stage_gr, _ = run_timed(step_group, max(10, args.steps // 4), 5)
+        extras["group_shared_step_us"] = round(us_gr, 2)
+        extras["group_shared_stage_us"] = {nm: round(float(v), 2) for nm, v in
+                                           zip(["append", "score_group_max", "select_topk", "decode_sparse_group"],
+                                               stage_gr.mean(axis=0))}
+        extras["speedup_group_shared_vs_dense"] = round(dense_us / us_gr, 2)
         # exactness certificate / refinement: pages whose box bound exceeds the sparse tau (App. B.2)
         ekv.ekv_select_topk(st0.cfg, st0.box, st0.inp["seq_lens"], k_pages, st0.page_idx, st0.n_sel, st0.workspace(ekv.EKV_OP_SELECT_TOPK))
         ekv.ekv_decode_sparse(st0.cfg, st0.inp["q"], st0.cache(), st0.page_idx, st0.n_sel, st0.out, st0.tau,
