@@ -39,6 +39,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="C4")
     ap.add_argument("--budget", type=float, default=0.02, help="top-k budget as a fraction of the pages")
+    ap.add_argument("--variant", default="topk", choices=["topk", "gauss", "group", "dense"],
+                    help="step timed as the headline: top-k (default, the metric's variant), Gaussian selector, "
+                         "group-shared top-k, or the dense full-cache decode alone (for profiling the other rows)")
     ap.add_argument("--copies", type=int, default=4, help="rotating copies of the cache (defeats the LLC)")
     ap.add_argument("--q-page", type=float, default=0.99)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -93,7 +96,10 @@ def main():
     def ev():
         return torch.cuda.Event(enable_timing=True)
 
-    stage_names = ["append", "score_box", "select_topk", "decode_sparse"]
+    stage_names = {"topk": ["append", "score_box", "select_topk", "decode_sparse"],
+                   "gauss": ["append", "score_gauss", "select_gauss", "decode_sparse"],
+                   "group": ["append", "score_group_max", "select_topk", "decode_sparse_group"],
+                   "dense": ["-", "-", "-", "decode_full"]}[args.variant]
 
     def step_topk(st, evs=None):
         if evs: evs[0].record()
@@ -119,6 +125,38 @@ def main():
         if evs: evs[3].record()
         ekv.ekv_decode_sparse(st.cfg, st.inp["q"], st.cache(), st.page_idx, st.n_sel, st.out, st.tau, st.supp,
                               st.ws_sparse)
+        if evs: evs[4].record()
+
+    # one page list per KV head shared by its G query heads (same budget of pages per list)
+    gcfg = ekv.make_config(B, Hkv, Hkv, d, P, w.kv_dtype, w.alpha, w.score_scale, M, cap)
+    gbox = torch.zeros(B, Hkv, M, device=dev)
+    g_idx = torch.zeros(B, Hkv, cap, device=dev, dtype=torch.int32)
+    g_n = torch.zeros(B, Hkv, device=dev, dtype=torch.int32)
+    ws_gsel = torch.empty(max(256, ekv.ekv_workspace_bytes(gcfg, ekv.EKV_OP_SELECT_TOPK)), device=dev,
+                          dtype=torch.uint8)
+
+    def step_group(st, evs=None):
+        if evs: evs[0].record()
+        ekv.ekv_stats_append(st.cfg, st.cache_prev, st.stats(), st.k_new, st.v_new)
+        if evs: evs[1].record()
+        ekv.ekv_score_pages(st.cfg, st.inp["q"], st.stats(), st.inp["seq_lens"],
+                            ekv.EKV_SCORE_BOX | ekv.EKV_SCORE_GROUP_MAX, gbox)
+        if evs: evs[2].record()
+        ekv.ekv_select_topk(gcfg, gbox, st.inp["seq_lens"], k_pages, g_idx, g_n, ws_gsel)
+        if evs: evs[3].record()
+        ekv.ekv_decode_sparse_group(st.cfg, st.inp["q"], st.cache(), g_idx, g_n, st.out, st.tau, st.supp,
+                                    st.ws_sparse)
+        if evs: evs[4].record()
+
+    ws_full_all = None
+
+    def step_dense(st, evs=None):
+        nonlocal ws_full_all
+        if ws_full_all is None:
+            ws_full_all = copies[0].workspace(ekv.EKV_OP_DECODE_FULL)     # one scratch shared by the copies
+        if evs:
+            for e in evs[:4]: e.record()
+        ekv.ekv_decode_full(st.cfg, st.inp["q"], st.cache(), st.out, st.tau, st.supp, ws_full_all)
         if evs: evs[4].record()
 
     def run_timed(step_fn, steps, warmup):
@@ -151,7 +189,10 @@ def main():
         del src, dst
 
     # ---------------------------------------------------------------- headline: top-k step
-    us_wall, stage, whole = run_timed(step_topk, args.steps, args.warmup)
+    step_fn = {"topk": step_topk, "gauss": step_gauss, "group": step_group, "dense": step_dense}[args.variant]
+    us_wall, stage, whole = run_timed(step_fn, args.steps, args.warmup)
+    if args.variant != "topk":       # the byte accounting below is the top-k step's: leave its lists in place
+        step_topk(copies[0]); torch.cuda.synchronize()
     stage_mean = stage.mean(axis=0)
     st0 = copies[0]
     supp_mean = float(st0.supp.float().mean())
@@ -228,7 +269,7 @@ def main():
         "data": "synthetic", "kv_dtype": w.kv_dtype,
         "config": {"workload": f"{w.name}: B{B} {Hq}q/{Hkv}kv d{d} ctx{n} page{P} {w.kv_dtype}, alpha={w.alpha}, "
                                f"top-k {k_pages} pages ({args.budget:.0%}) per query head",
-                   "variant": "entmaxkv-topk", "copies_rotated": args.copies},
+                   "variant": "entmaxkv-" + args.variant, "copies_rotated": args.copies},
         "step_event_us": {"mean": round(float(whole.mean()), 2), "median": round(float(np.median(whole)), 2),
                           "p10": round(float(np.percentile(whole, 10)), 2),
                           "p90": round(float(np.percentile(whole, 90)), 2)},
@@ -303,27 +344,6 @@ def main():
                 "rho_mean": round(float((kept_supp.float() / supp_f.float()).mean()), 4),
                 "R_mean": round(float(R), 6),
                 "step_us": None}
-        # one page list per KV head shared by its G query heads (same budget of pages per list)
-        gcfg = ekv.make_config(B, Hkv, Hkv, d, P, w.kv_dtype, w.alpha, w.score_scale, M, cap)
-        gbox = torch.zeros(B, Hkv, M, device=dev)
-        g_idx = torch.zeros(B, Hkv, cap, device=dev, dtype=torch.int32)
-        g_n = torch.zeros(B, Hkv, device=dev, dtype=torch.int32)
-        ws_gsel = torch.empty(max(256, ekv.ekv_workspace_bytes(gcfg, ekv.EKV_OP_SELECT_TOPK)), device=dev,
-                              dtype=torch.uint8)
-
-        def step_group(st, evs=None):
-            if evs: evs[0].record()
-            ekv.ekv_stats_append(st.cfg, st.cache_prev, st.stats(), st.k_new, st.v_new)
-            if evs: evs[1].record()
-            ekv.ekv_score_pages(st.cfg, st.inp["q"], st.stats(), st.inp["seq_lens"],
-                                ekv.EKV_SCORE_BOX | ekv.EKV_SCORE_GROUP_MAX, gbox)
-            if evs: evs[2].record()
-            ekv.ekv_select_topk(gcfg, gbox, st.inp["seq_lens"], k_pages, g_idx, g_n, ws_gsel)
-            if evs: evs[3].record()
-            ekv.ekv_decode_sparse_group(st.cfg, st.inp["q"], st.cache(), g_idx, g_n, st.out, st.tau, st.supp,
-                                        st.ws_sparse)
-            if evs: evs[4].record()
-
         us_gr, stage_gr, _ = run_timed(step_group, max(10, args.steps // 4), 5)
         extras["group_shared_step_us"] = round(us_gr, 2)
         extras["group_shared_stage_us"] = {nm: round(float(v), 2) for nm, v in

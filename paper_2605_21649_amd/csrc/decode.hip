@@ -375,21 +375,26 @@ __global__ __launch_bounds__(kLevelThreads) void filter_level_kernel(const Filte
   }
 }
 
-// Ordered compaction of the slice's entries above the certified bound.
+// Ordered compaction of the slice's entries above the certified bound.  Survivors are rare (a few hundred
+// per row), so the scores are counted in one sweep and re-read (from cache) only by the wavefronts that
+// have something to write.
 template <bool DENSE>
-__global__ __launch_bounds__(kFilterThreads) __attribute__((amdgpu_waves_per_eu(8, 8))) void filter_compact_kernel(const FilterArgs A) {
+__global__ __launch_bounds__(kFilterThreads) void filter_compact_kernel(const FilterArgs A) {
   __shared__ int wtot[kFilterWaves];
   const int row = blockIdx.y, slice = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const uint64_t lt = (1ull << lane) - 1ull;
   const int n_cand = filter_n_cand<DENSE>(A, row);
   const int t0 = slice * kFilterSlice;
   if (t0 >= n_cand) return;
-  float4 v[kFilterLoads];
-  filter_load(A.zbuf + (size_t)row * A.zstride, t0, n_cand, v);
+  const float* zr = A.zbuf + (size_t)row * A.zstride;
   const float zmax = A.frow[2 * row], thr = A.frow[2 * row + 1];
   int c = 0;
+  {
+    float4 v[kFilterLoads];
+    filter_load(zr, t0, n_cand, v);
 #pragma unroll
-  for (int i = 0; i < kFilterLoads; ++i) c += (v[i].x > thr) + (v[i].y > thr) + (v[i].z > thr) + (v[i].w > thr);
+    for (int i = 0; i < kFilterLoads; ++i) c += (v[i].x > thr) + (v[i].y > thr) + (v[i].z > thr) + (v[i].w > thr);
+  }
   c = wave_sum_i(c);
   if (lane == 0) wtot[w] = c;
   __syncthreads();
@@ -399,16 +404,16 @@ __global__ __launch_bounds__(kFilterThreads) __attribute__((amdgpu_waves_per_eu(
   if (c == 0) return;
   float* lu = A.flist_u + ((size_t)row * A.n_slices_max + slice) * kFilterSliceCap;
   int32_t* lp = A.flist_pos + ((size_t)row * A.n_slices_max + slice) * kFilterSliceCap;
-#pragma unroll
   for (int i = 0; i < kFilterLoads; ++i) {
-    const float zz[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
-    const bool any = zz[0] > thr || zz[1] > thr || zz[2] > thr || zz[3] > thr;
-    if (__ballot(any) == 0) continue;
+    const int pos = t0 + (w * kFilterLoads + i) * 256 + lane * 4;
+    float4 v = *reinterpret_cast<const float4*>(zr + min(pos, n_cand - 4));
+    if (pos >= n_cand) v = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+    const float zz[4] = {v.x, v.y, v.z, v.w};
     // order within the load: (lane, component)
     const uint64_t m0 = __ballot(zz[0] > thr), m1 = __ballot(zz[1] > thr), m2 = __ballot(zz[2] > thr),
                    m3 = __ballot(zz[3] > thr);
+    if ((m0 | m1 | m2 | m3) == 0) continue;
     int o = off + __popcll(m0 & lt) + __popcll(m1 & lt) + __popcll(m2 & lt) + __popcll(m3 & lt);
-    const int pos = t0 + (w * kFilterLoads + i) * 256 + lane * 4;
 #pragma unroll
     for (int cc = 0; cc < 4; ++cc) {
       if (zz[cc] > thr) {
