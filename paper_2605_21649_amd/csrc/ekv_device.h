@@ -41,6 +41,27 @@ template <> __device__ __forceinline__ void load8<bf16_t>(const bf16_t* p, float
   x[6] = __uint_as_float(a.w << 16); x[7] = __uint_as_float(a.w & 0xffff0000u);
 }
 
+// The same 8 channels kept as loaded (16 or 32 bytes), to be widened only where they are consumed:
+// a batch of rows in flight then costs 4 (bf16) or 8 (f32) registers per row, not 8 floats.
+template <typename T> struct Raw8;
+template <> struct Raw8<float> { float4 a, b; };
+template <> struct Raw8<bf16_t> { uint4 a; };
+__device__ __forceinline__ void load_raw8(const float* p, Raw8<float>& r) {
+  r.a = *reinterpret_cast<const float4*>(p);
+  r.b = *reinterpret_cast<const float4*>(p + 4);
+}
+__device__ __forceinline__ void load_raw8(const bf16_t* p, Raw8<bf16_t>& r) { r.a = *reinterpret_cast<const uint4*>(p); }
+__device__ __forceinline__ void widen8(const Raw8<float>& r, float (&x)[8]) {
+  x[0] = r.a.x; x[1] = r.a.y; x[2] = r.a.z; x[3] = r.a.w;
+  x[4] = r.b.x; x[5] = r.b.y; x[6] = r.b.z; x[7] = r.b.w;
+}
+__device__ __forceinline__ void widen8(const Raw8<bf16_t>& r, float (&x)[8]) {
+  x[0] = __uint_as_float(r.a.x << 16); x[1] = __uint_as_float(r.a.x & 0xffff0000u);
+  x[2] = __uint_as_float(r.a.y << 16); x[3] = __uint_as_float(r.a.y & 0xffff0000u);
+  x[4] = __uint_as_float(r.a.z << 16); x[5] = __uint_as_float(r.a.z & 0xffff0000u);
+  x[6] = __uint_as_float(r.a.w << 16); x[7] = __uint_as_float(r.a.w & 0xffff0000u);
+}
+
 template <typename T> __device__ __forceinline__ void store8(T* p, const float (&x)[8]);
 
 template <> __device__ __forceinline__ void store8<float>(float* p, const float (&x)[8]) {

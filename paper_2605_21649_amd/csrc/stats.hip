@@ -1,16 +1,102 @@
 // Page-statistics builder (paper Sec. 4.2): per page k_min, k_max, k_avg and k_var = k_std^2
 // (the variance is what is stored: sigma_p^2 of Sec. 4.3 is linear in it).
-// One 64-lane wavefront per (sequence, KV head, page); a page is a contiguous P x 128 block, read
-// with 16-byte loads (lane = 4 rows x 16 column groups).  HBM-bound stream over K.
+// Sixteen lanes own one page: lane c holds channels 8c..8c+7 and walks the page's rows itself, so no
+// statistic ever crosses lanes; a wavefront covers four pages, each row load being four 256-byte
+// segments.  The kernel is a stream over K (HBM-bound once the per-element work is this small: min,
+// max, subtract, add, fused multiply-add).
 #include "ekv_device.h"
 #include "ekv_internal.h"
 
 namespace ekv {
 
-// Statistics of one page, computed by one wavefront.  `kpage` points at the page's [P][128] block;
-// tokens [0,cnt) are valid.  If ov_row != nullptr, token `ov_slot` takes its values from ov_row[128]
-// instead of the cache (the token being appended).  Sums are taken relative to the first token's
-// value so that m2 - avg^2 does not cancel for channels with a large common offset.
+constexpr int kStatRowBatch = 4;     // row loads in flight per lane in the bulk build
+
+// Summation order shared by both layouts below (so that append-then-query equals rebuild-then-query bit
+// for bit): rows are split by t mod 4 into four partial sums, each taken in ascending row order relative
+// to the first token's value (so that m2 - avg^2 does not cancel for channels with a large common
+// offset), combined as (p0 + p1) + (p2 + p3).  Rows past cnt add exact zeros.
+
+// Bulk layout: the 16 lanes of a DPP row own one page; lane c holds channels 8c..8c+7 and walks the
+// page's rows itself, so no statistic crosses lanes; a wavefront covers four pages, each row load being
+// four 256-byte segments.  `kpage` points at the page's [P][128] block; tokens [0,cnt) are valid.
+template <typename T, int PT>   // PT = compile-time page size, 0 = runtime
+__device__ __forceinline__ void page_stats_rows(const T* __restrict__ kpage, int cnt, int P_rt, bool all_full,
+                                                T* __restrict__ box_out, T* __restrict__ gauss_out) {
+  constexpr int RB = kStatRowBatch;
+  static_assert(RB == 4, "one batch = one row of each partial sum");
+  const int P = PT ? PT : P_rt;
+  const int c = threadIdx.x & 15;
+  float k0[8];
+  load8<T>(kpage + 8 * c, k0);
+  float mn[8], mx[8], s1[4][8], s2[4][8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    mn[i] = INFINITY; mx[i] = -INFINITY;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) { s1[r][i] = 0.f; s2[r][i] = 0.f; }
+  }
+  if (all_full) {                                        // wave-uniform: every page of the wavefront is full
+#pragma unroll 1
+    for (int t0 = 0; t0 < P; t0 += RB) {
+      Raw8<T> raw[RB];
+#pragma unroll
+      for (int j = 0; j < RB; ++j) load_raw8(kpage + (size_t)(t0 + j) * kD + 8 * c, raw[j]);   // P % 4 == 0
+#pragma unroll
+      for (int j = 0; j < RB; ++j) {
+        float x[8];
+        widen8(raw[j], x);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          mn[i] = fminf(mn[i], x[i]);
+          mx[i] = fmaxf(mx[i], x[i]);
+          const float dx = x[i] - k0[i];
+          s1[j][i] += dx;
+          s2[j][i] = fmaf(dx, dx, s2[j][i]);
+        }
+      }
+    }
+  } else {
+#pragma unroll 1
+    for (int t0 = 0; t0 < P; t0 += RB) {
+      Raw8<T> raw[RB];
+#pragma unroll
+      for (int j = 0; j < RB; ++j)                       // rows past cnt re-read row 0: loads stay unconditional
+        load_raw8(kpage + (size_t)(t0 + j < cnt ? t0 + j : 0) * kD + 8 * c, raw[j]);
+#pragma unroll
+      for (int j = 0; j < RB; ++j) {
+        const bool ok = t0 + j < cnt;
+        float x[8];
+        widen8(raw[j], x);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          mn[i] = fminf(mn[i], ok ? x[i] : INFINITY);
+          mx[i] = fmaxf(mx[i], ok ? x[i] : -INFINITY);
+          const float dx = ok ? x[i] - k0[i] : 0.f;
+          s1[j][i] += dx;
+          s2[j][i] = fmaf(dx, dx, s2[j][i]);
+        }
+      }
+    }
+  }
+  const float inv_n = 1.0f / (float)cnt;
+  float avg[8], var[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const float t1 = (s1[0][i] + s1[1][i]) + (s1[2][i] + s1[3][i]);
+    const float t2 = (s2[0][i] + s2[1][i]) + (s2[2][i] + s2[3][i]);
+    const float m1 = t1 * inv_n;
+    var[i] = fmaxf(fmaf(-m1, m1, t2 * inv_n), 0.f);      // m2 - avg^2, clamped at 0
+    avg[i] = k0[i] + m1;
+  }
+  store8<T>(box_out + 8 * c, mn);
+  store8<T>(box_out + kD + 8 * c, mx);
+  store8<T>(gauss_out + 8 * c, avg);
+  store8<T>(gauss_out + kD + 8 * c, var);
+}
+
+// Single-page layout (the append): one wavefront per page, lane = (row mod 4, channel group); the four
+// partial sums live in the four DPP rows and meet in two exchange steps.  If ov_row != nullptr, token
+// `ov_slot` takes its values from ov_row[128] instead of the cache (the token being appended).
 template <typename T, int PT>   // PT = compile-time page size (all row loads issued as one batch), 0 = runtime
 __device__ __forceinline__ void page_stats_wave(const T* __restrict__ kpage, int cnt, int P_rt,
                                                 const T* __restrict__ ov_row, int ov_slot,
@@ -79,17 +165,20 @@ __global__ __launch_bounds__(256) void stats_build_kernel(const T* __restrict__ 
                                                           const int32_t* __restrict__ block_table,
                                                           const int32_t* __restrict__ seq_lens,
                                                           T* __restrict__ box, T* __restrict__ gauss,
-                                                          int Hkv, int P, int Mmax) {
+                                                          int Hkv, int P, int Mmax, int n_phys) {
   const int b = blockIdx.z, h = blockIdx.y;
-  const int p = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int p = blockIdx.x * 16 + (threadIdx.x >> 4);     // 16 pages per workgroup, 4 per wavefront
   const int n = seq_lens[b];
-  const int M = (n + P - 1) / P;
-  if (p >= M) return;
-  const int cnt = min(P, n - p * P);
-  const int phys = block_table[(size_t)b * Mmax + p];
+  const int M = min((n + P - 1) / P, Mmax);
+  const int pc = min(p, M - 1);                           // lanes past the end recompute the last page, unwritten
+  if (M <= 0) return;
+  const int cnt = min(P, n - pc * P);
+  const int phys = min(max(block_table[(size_t)b * Mmax + pc], 0), n_phys - 1);
   const T* kpage = k_pool + ((size_t)phys * Hkv + h) * P * kD;
-  const size_t rec = (((size_t)b * Hkv + h) * Mmax + p) * 2 * kD;
-  page_stats_wave<T, PT>(kpage, cnt, P, nullptr, -1, box + rec, gauss + rec);
+  const size_t rec = (((size_t)b * Hkv + h) * Mmax + pc) * 2 * kD;
+  const bool all_full = __all(cnt == P);
+  if (blockIdx.x * 16 + (int)(threadIdx.x >> 6) * 4 >= M) return;      // whole wavefront past the end
+  if (p < M) page_stats_rows<T, PT>(kpage, cnt, P, all_full, box + rec, gauss + rec);
 }
 
 // One wavefront per (sequence, KV head): write the new token into slot n_b and refresh its page.
@@ -100,12 +189,12 @@ __global__ __launch_bounds__(64) void stats_append_kernel(T* __restrict__ k_pool
                                                           const T* __restrict__ k_new,
                                                           const T* __restrict__ v_new,
                                                           T* __restrict__ box, T* __restrict__ gauss,
-                                                          int Hkv, int P, int Mmax) {
+                                                          int Hkv, int P, int Mmax, int n_phys) {
   const int b = blockIdx.y, h = blockIdx.x;
   const int pos = seq_lens[b];
   const int p = pos / P, slot = pos - p * P;
-  if (p >= Mmax) return;                       // no room: validated against on the host where possible
-  const int phys = block_table[(size_t)b * Mmax + p];
+  if (pos < 0 || p >= Mmax) return;            // no room: validated against on the host where possible
+  const int phys = min(max(block_table[(size_t)b * Mmax + p], 0), n_phys - 1);
   const size_t page_off = ((size_t)phys * Hkv + h) * P * kD;
   const T* knew = k_new + ((size_t)b * Hkv + h) * kD;
   const int lane = threadIdx.x;
@@ -125,16 +214,17 @@ __global__ __launch_bounds__(64) void stats_append_kernel(T* __restrict__ k_pool
 
 template <typename T, int PT>
 static void launch_build_T(const Dims& dm, const ekv_cache_view& c, const ekv_stats_view& s, hipStream_t st) {
-  dim3 grid((dm.Mmax + 3) / 4, dm.Hkv, dm.B), block(256);
+  dim3 grid((dm.Mmax + 15) / 16, dm.Hkv, dm.B), block(256);
   hipLaunchKernelGGL((stats_build_kernel<T, PT>), grid, block, 0, st, (const T*)c.k_pool, c.block_table, c.seq_lens,
-                     (T*)s.box, (T*)s.gauss, dm.Hkv, dm.P, dm.Mmax);
+                     (T*)s.box, (T*)s.gauss, dm.Hkv, dm.P, dm.Mmax, c.n_phys_pages);
 }
 template <typename T, int PT>
 static void launch_append_T(const Dims& dm, const ekv_cache_view& c, const ekv_stats_view& s, const void* k_new,
                             const void* v_new, hipStream_t st) {
   dim3 grid(dm.Hkv, dm.B), block(64);
   hipLaunchKernelGGL((stats_append_kernel<T, PT>), grid, block, 0, st, (T*)c.k_pool, (T*)c.v_pool, c.block_table,
-                     c.seq_lens, (const T*)k_new, (const T*)v_new, (T*)s.box, (T*)s.gauss, dm.Hkv, dm.P, dm.Mmax);
+                     c.seq_lens, (const T*)k_new, (const T*)v_new, (T*)s.box, (T*)s.gauss, dm.Hkv, dm.P, dm.Mmax,
+                     c.n_phys_pages);
 }
 
 void launch_stats_build(const Dims& dm, const ekv_cache_view& c, const ekv_stats_view& s, hipStream_t st) {
