@@ -31,7 +31,8 @@ W2 = synth.C2.scaled(name="C2-8k", context=8192 + 16, ragged=3)
 W3 = synth.C3.scaled(name="C3-small", batch=2, context=4096)
 W5 = synth.C5.scaled(name="C5-small", batch=2, context=8192, alpha=1.25)
 W5B = synth.C5.scaled(name="C5-small-a2", batch=2, context=4096, alpha=2.0, ragged=17)
-ALL = [W1, W1S, W1R, W2, W3, W5, W5B]
+W3A = synth.C3.scaled(name="C3-small-a43", batch=1, context=4096 + 32, ragged=9, alpha=4.0 / 3.0)   # beta = 3
+ALL = [W1, W1S, W1R, W2, W3, W3A, W5, W5B]
 IDS = [w.name for w in ALL]
 
 OUT_TOL = {"f32": 1e-5, "bf16": 2e-3}
@@ -251,7 +252,8 @@ def test_select_gauss_long_context():
 
 
 # ---------------------------------------------------------------------------- a6
-@pytest.mark.parametrize("w", [W1S, W2, W3, W5, W5B], ids=["C1-soft", "C2-8k", "C3-small", "C5-small", "C5-small-a2"])
+@pytest.mark.parametrize("w", [W1S, W2, W3, W3A, W5, W5B],
+                         ids=["C1-soft", "C2-8k", "C3-small", "C3-small-a43", "C5-small", "C5-small-a2"])
 @pytest.mark.parametrize("q_page,margin", [(0.99, 0.0), (0.9, 0.05)])
 def test_select_gauss_on_shared_moments(w, q_page, margin):
     inp = get_inputs(w)
@@ -778,3 +780,63 @@ def test_group_decode_equals_per_head_decode_on_the_same_lists():
     ekv.ekv_decode_sparse_group(st.cfg, st.inp["q"], st.cache(), g_idx, g_n, out_g, tau_g, supp_g, wsd)
     torch.cuda.synchronize()
     assert torch.equal(tau_g, st.tau) and torch.equal(supp_g, st.supp) and torch.equal(out_g, st.out)
+
+
+# ---------------------------------------------------------------------------- multi-step decode loop
+def test_multi_step_decode_loop_with_ragged_batch():
+    """append -> score -> select -> decode for 40 consecutive steps on a batch whose two sequences have
+    different lengths and cross page boundaries at different steps (the lengths are bumped on the device
+    between steps, nothing is synchronised inside the loop); the step's results are checked against the
+    oracle at several steps, and the statistics at the end against a rebuild."""
+    w = synth.C2.scaled(name="C2-loop", batch=2, context=4096, n_q_heads=8, n_kv_heads=2)
+    inp = get_inputs(w)
+    k = 24
+    st = DeviceState(w, inp, cap=k)
+    dev = st.box.device
+    P, T = w.page_size, 40
+    start = torch.tensor([4096 - T - 3, 4096 - T - 14], dtype=torch.int32)       # mid-page, different phases
+    B, Hkv = w.batch, w.n_kv_heads
+    k_log = torch.stack([torch.stack([synth.logical_kv(inp, w, b, h)[0] for h in range(Hkv)]) for b in range(B)])
+    v_log = torch.stack([torch.stack([synth.logical_kv(inp, w, b, h)[1] for h in range(Hkv)]) for b in range(B)])
+    st.inp["seq_lens"].copy_(start)
+    for b in range(B):                                       # wipe the slots that the loop will fill
+        for t in range(int(start[b]), 4096):
+            phys = int(inp["block_table"][b, t // P])
+            st.inp["k_pool"][phys, :, t % P] = -3.0
+            st.inp["v_pool"][phys, :, t % P] = -3.0
+    ekv.ekv_stats_build(st.cfg, st.cache(), st.stats())
+    check_at = {0, 13, 14, 39}
+    snaps = {}
+    ws_t, ws_d = st.workspace(ekv.EKV_OP_SELECT_TOPK), st.workspace(ekv.EKV_OP_DECODE_SPARSE)
+    for step in range(T):
+        pos = (start + step).long()
+        k_new = torch.stack([k_log[b, :, pos[b]] for b in range(B)]).contiguous().to(dev)
+        v_new = torch.stack([v_log[b, :, pos[b]] for b in range(B)]).contiguous().to(dev)
+        ekv.ekv_stats_append(st.cfg, st.cache(), st.stats(), k_new, v_new)
+        st.inp["seq_lens"] += 1
+        ekv.ekv_score_pages(st.cfg, st.inp["q"], st.stats(), st.inp["seq_lens"], ekv.EKV_SCORE_BOX, st.box)
+        ekv.ekv_select_topk(st.cfg, st.box, st.inp["seq_lens"], k, st.page_idx, st.n_sel, ws_t)
+        ekv.ekv_decode_sparse(st.cfg, st.inp["q"], st.cache(), st.page_idx, st.n_sel, st.out, st.tau, st.supp, ws_d)
+        if step in check_at:                                 # device-side copies, read after the loop
+            snaps[step] = (st.page_idx.clone(), st.n_sel.clone(), st.out.clone(), st.tau.clone(), st.supp.clone())
+    torch.cuda.synchronize()
+    for step, (idx, ns, out, tau, supp) in snaps.items():
+        idx, ns = idx.cpu().numpy(), ns.cpu().numpy()
+        for (b, hq) in [(0, 0), (1, 5), (1, 7)]:
+            n_b = int(start[b]) + step + 1
+            q = to_f64(inp["q"][b, hq])
+            K, V = to_f64(k_log[b, hq // w.group, :n_b]), to_f64(v_log[b, hq // w.group, :n_b])
+            ref = orc.decode_step_unit(q, K, V, P, w.alpha, w.score_scale, "topk", w.kv_dtype, k_pages=k)
+            ok, bad = sets_equal_up_to_cut(idx[b, hq, : ns[b, hq]], ref["pages"], ref["box"],
+                                           [ref["cut_in"], ref["cut_out"]], 1e-5 * max(1.0, abs(ref["cut_in"])))
+            assert ok, (step, b, hq, bad)
+            if set(idx[b, hq, : ns[b, hq]].tolist()) == set(ref["pages"].tolist()):
+                assert abs(float(tau[b, hq]) - ref["tau"]) <= 4e-6 * max(1.0, abs(ref["tau"]))
+                assert rel_err(out[b, hq].cpu().numpy(), ref["o"]) <= OUT_TOL[w.kv_dtype]
+    box_a, gauss_a = st.box_stats.clone(), st.gauss_stats.clone()
+    ekv.ekv_stats_build(st.cfg, st.cache(), st.stats())
+    torch.cuda.synchronize()
+    for b in range(B):
+        M = -(-(int(start[b]) + T) // P)
+        assert torch.equal(box_a[b, :, :M].view(torch.uint8), st.box_stats[b, :, :M].view(torch.uint8))
+        assert torch.equal(gauss_a[b, :, :M].view(torch.uint8), st.gauss_stats[b, :, :M].view(torch.uint8))
