@@ -1,18 +1,19 @@
 #!/usr/bin/env python3
 """Decode-step benchmark of the EntmaxKV hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C4] [--budget 0.02]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C4] [--budget 0.02] [--variant topk]
 
 One step = one decode step of the top-k variant over a synthetic paged cache already resident in HBM:
   a2 append the new token + refresh its page statistics -> a3 box page scoring -> a5 top-k selection
   -> a7 sparse alpha-entmax decode (exact tau).
-The same run also times, outside the headline number, the Gaussian-selector step (a4 + a6 + a7), the dense
-full-cache entmax decode (a8), the softmax-over-selection baseline (a9) and the bulk statistics build (a1).
-To keep reads coming from HBM rather than the 256 MB last-level cache, the step rotates over several
-identical copies of the cache and its statistics.
+The same run also times, outside the headline number, the Gaussian-selector step (a4 + a6 + a7), the
+group-shared top-k step, the dense full-cache entmax decode (a8), the softmax-over-selection baseline (a9),
+the box-threshold refinement, the bulk statistics build (a1), and the same steps on the 128K-token batch
+workload (C3).  To keep reads coming from HBM rather than the 256 MB last-level cache, the step rotates
+over several identical copies of the cache and its statistics.
 
-Prints ONE JSON line (see the design doc for the fields): metric/value = median-free mean latency of the K timed
-steps in microseconds; `roofline` for the dominant kernel of the step; `cpu_baseline` = the float64 oracle
+Prints ONE JSON line (see the design doc for the fields): metric/value = mean latency of the K timed steps in
+microseconds; `roofline` for the longest single kernel of the step; `cpu_baseline` = the float64 oracle
 timed on this machine's host cores on a bounded sample of (batch, head) units.
 """
 import argparse
@@ -28,8 +29,13 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 # FETCH_SIZE + WRITE_SIZE of one score_pages launch at C4 (rocprofv3 --pmc, scaled by a plain copy of known
-# size; see profiles/bench_topk_step_C4.md): 256.09 MiB read + 8.00 MiB written
-PMC_TRAFFIC_SCORE_PAGES_C4 = int((256.09 + 8.00) * 1024 * 1024)
+# size; see profiles/bench_topk_step_C4.md): 256.10 MiB read + 8.00 MiB written
+PMC_TRAFFIC_SCORE_PAGES_C4 = int((256.10 + 8.00) * 1024 * 1024)
+
+STAGE_NAMES = {"topk": ["append", "score_box", "select_topk", "decode_sparse"],
+               "gauss": ["append", "score_gauss", "select_gauss", "decode_sparse"],
+               "group": ["append", "score_group_max", "select_topk", "decode_sparse_group"],
+               "dense": ["-", "-", "-", "decode_full"]}
 
 
 def parse():
@@ -44,12 +50,174 @@ def parse():
                          "group-shared top-k, or the dense full-cache decode alone (for profiling the other rows)")
     ap.add_argument("--copies", type=int, default=4, help="rotating copies of the cache (defeats the LLC)")
     ap.add_argument("--q-page", type=float, default=0.99)
+    ap.add_argument("--cap-frac", type=float, default=0.04,
+                    help="capacity of the page lists as a fraction of the pages (room for the adaptive selector)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="time only the headline step")
     ap.add_argument("--cpu-units", type=int, default=16, help="(b,h) units the oracle is timed on")
     ap.add_argument("--pmc-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (calibrates rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     return ap.parse_args()
+
+
+class Runner:
+    """Device state of one workload (several rotating copies) and its step functions.  Every step function
+    takes a copy and, optionally, five HIP events to record between its stages."""
+
+    def __init__(self, w, budget, n_copies, q_page, dev, cap_frac=0.04):
+        import torch
+        from paper_2605_21649_amd import binding as ekv, synth
+        from tests.helpers import DeviceState
+        self.torch, self.ekv, self.w, self.dev, self.q_page = torch, ekv, w, dev, q_page
+        B, Hkv, d, P, n = w.batch, w.n_kv_heads, w.head_dim, w.page_size, w.context
+        M = w.pages_per_seq
+        self.k_pages = max(1, int(math.ceil(budget * M)))
+        self.cap = max(self.k_pages, int(math.ceil(cap_frac * M)))     # room for the adaptive selector
+        self.inp = synth.make_inputs(w, 4000, device=dev)     # seeded, generated on the GPU
+        self.copies = []
+        for c in range(n_copies):
+            ic = self.inp if c == 0 else {k: (v.clone() if k in ("k_pool", "v_pool") else v)
+                                          for k, v in self.inp.items()}
+            st = DeviceState(w, ic, cap=self.cap, device=dev)
+            ekv.ekv_stats_build(st.cfg, st.cache(), st.stats())
+            st.ws_sparse = st.workspace(ekv.EKV_OP_DECODE_SPARSE)
+            st.ws_gauss = st.workspace(ekv.EKV_OP_SELECT_GAUSS)
+            st.ws_topk = st.workspace(ekv.EKV_OP_SELECT_TOPK)
+            # the token appended by the step: the last token of the sequence, re-appended at n-1 every step
+            st.seq_prev = (ic["seq_lens"] - 1).contiguous()
+            st.cache_prev = ekv.cache_view(ic["k_pool"], ic["v_pool"], ic["block_table"], st.seq_prev)
+            rows = ic["block_table"][:, (n - 1) // P].long()
+            st.k_new = ic["k_pool"][rows, :, (n - 1) % P].contiguous()
+            st.v_new = ic["v_pool"][rows, :, (n - 1) % P].contiguous()
+            self.copies.append(st)
+        # one page list per KV head shared by its G query heads (same budget of pages per list)
+        self.gcfg = ekv.make_config(B, Hkv, Hkv, d, P, w.kv_dtype, w.alpha, w.score_scale, M, self.cap)
+        self.gbox = torch.zeros(B, Hkv, M, device=dev)
+        self.g_idx = torch.zeros(B, Hkv, self.cap, device=dev, dtype=torch.int32)
+        self.g_n = torch.zeros(B, Hkv, device=dev, dtype=torch.int32)
+        self.ws_gsel = torch.empty(max(256, ekv.ekv_workspace_bytes(self.gcfg, ekv.EKV_OP_SELECT_TOPK)), device=dev,
+                                   dtype=torch.uint8)
+        self.ws_full = None
+        torch.cuda.synchronize()
+
+    def ev(self):
+        return self.torch.cuda.Event(enable_timing=True)
+
+    # ---- steps ---------------------------------------------------------------------------------
+    def step_topk(self, st, evs=None):
+        ekv = self.ekv
+        if evs: evs[0].record()
+        ekv.ekv_stats_append(st.cfg, st.cache_prev, st.stats(), st.k_new, st.v_new)
+        if evs: evs[1].record()
+        ekv.ekv_score_pages(st.cfg, st.inp["q"], st.stats(), st.inp["seq_lens"], ekv.EKV_SCORE_BOX, st.box)
+        if evs: evs[2].record()
+        ekv.ekv_select_topk(st.cfg, st.box, st.inp["seq_lens"], self.k_pages, st.page_idx, st.n_sel, st.ws_topk)
+        if evs: evs[3].record()
+        ekv.ekv_decode_sparse(st.cfg, st.inp["q"], st.cache(), st.page_idx, st.n_sel, st.out, st.tau, st.supp,
+                              st.ws_sparse)
+        if evs: evs[4].record()
+
+    def step_gauss(self, st, evs=None):
+        ekv = self.ekv
+        if evs: evs[0].record()
+        ekv.ekv_stats_append(st.cfg, st.cache_prev, st.stats(), st.k_new, st.v_new)
+        if evs: evs[1].record()
+        ekv.ekv_score_pages(st.cfg, st.inp["q"], st.stats(), st.inp["seq_lens"], ekv.EKV_SCORE_GAUSS, None, st.mu,
+                            st.sigma)
+        if evs: evs[2].record()
+        ekv.ekv_select_gauss(st.cfg, st.mu, st.sigma, st.inp["seq_lens"], self.q_page, 0.0, st.tau_hat, st.page_idx,
+                             st.n_sel, st.overflow, st.ws_gauss)
+        if evs: evs[3].record()
+        ekv.ekv_decode_sparse(st.cfg, st.inp["q"], st.cache(), st.page_idx, st.n_sel, st.out, st.tau, st.supp,
+                              st.ws_sparse)
+        if evs: evs[4].record()
+
+    def step_group(self, st, evs=None):
+        ekv = self.ekv
+        if evs: evs[0].record()
+        ekv.ekv_stats_append(st.cfg, st.cache_prev, st.stats(), st.k_new, st.v_new)
+        if evs: evs[1].record()
+        ekv.ekv_score_pages(st.cfg, st.inp["q"], st.stats(), st.inp["seq_lens"],
+                            ekv.EKV_SCORE_BOX | ekv.EKV_SCORE_GROUP_MAX, self.gbox)
+        if evs: evs[2].record()
+        ekv.ekv_select_topk(self.gcfg, self.gbox, st.inp["seq_lens"], self.k_pages, self.g_idx, self.g_n, self.ws_gsel)
+        if evs: evs[3].record()
+        ekv.ekv_decode_sparse_group(st.cfg, st.inp["q"], st.cache(), self.g_idx, self.g_n, st.out, st.tau, st.supp,
+                                    st.ws_sparse)
+        if evs: evs[4].record()
+
+    def step_dense(self, st, evs=None):
+        if self.ws_full is None:                              # one scratch shared by the copies
+            self.ws_full = self.copies[0].workspace(self.ekv.EKV_OP_DECODE_FULL)
+        if evs:
+            for e in evs[:4]: e.record()
+        self.ekv.ekv_decode_full(st.cfg, st.inp["q"], st.cache(), st.out, st.tau, st.supp, self.ws_full)
+        if evs: evs[4].record()
+
+    def step(self, variant):
+        return {"topk": self.step_topk, "gauss": self.step_gauss, "group": self.step_group,
+                "dense": self.step_dense}[variant]
+
+    # ---- timing --------------------------------------------------------------------------------
+    def run_timed(self, step_fn, steps, warmup, stages=True):
+        """W untimed steps, then exactly K steps between two synchronisations (wall clock, nothing but the
+        step's own launches in the timed region).  A second pass of K steps records HIP events between the
+        stages on the launch stream for the per-stage breakdown; the markers sit between dependent kernels
+        and cost a little, so that pass is not the headline number."""
+        import numpy as np
+        torch, copies = self.torch, self.copies
+        for i in range(warmup):
+            step_fn(copies[i % len(copies)])
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            step_fn(copies[i % len(copies)])
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        if not stages:
+            return wall / steps * 1e6, None, None
+        all_evs = [[self.ev() for _ in range(5)] for _ in range(steps)]
+        for i in range(steps):
+            step_fn(copies[i % len(copies)], all_evs[i])
+        torch.cuda.synchronize()
+        stage = np.array([[es[j].elapsed_time(es[j + 1]) * 1e3 for j in range(4)] for es in all_evs])   # us
+        whole = np.array([es[0].elapsed_time(es[4]) * 1e3 for es in all_evs])
+        return wall / steps * 1e6, stage, whole
+
+    def back_to_back(self, fn, reps=60, warm=6):
+        """Average launch duration of one entry point: N launches queued back to back on the launch stream
+        between two HIP events (no marker between dependent kernels), rotating over the cache copies."""
+        copies = self.copies
+        for i in range(warm):
+            fn(copies[i % len(copies)])
+        a, b = self.ev(), self.ev()
+        a.record()
+        for i in range(reps):
+            fn(copies[i % len(copies)])
+        b.record()
+        self.torch.cuda.synchronize()
+        return a.elapsed_time(b) * 1e3 / reps
+
+    def time_call(self, fn, reps=20, warm=3):
+        """Median duration of single calls, each bracketed by its own events and a synchronisation."""
+        import numpy as np
+        copies = self.copies
+        for i in range(warm):
+            fn(copies[i % len(copies)])
+        self.torch.cuda.synchronize()
+        ts = []
+        for i in range(reps):
+            a, b = self.ev(), self.ev()
+            a.record(); fn(copies[i % len(copies)]); b.record()
+            self.torch.cuda.synchronize()
+            ts.append(a.elapsed_time(b) * 1e3)
+        return float(np.median(ts))
+
+    def release(self):
+        self.copies = []
+        self.inp = None
+        self.ws_full = None
+        self.torch.cuda.empty_cache()
 
 
 def main():
@@ -62,7 +230,6 @@ def main():
     import numpy as np
     import torch
     from paper_2605_21649_amd import binding as ekv, synth
-    from tests.helpers import DeviceState
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     ekv.load_library()
@@ -72,113 +239,9 @@ def main():
     B, Hq, Hkv, d, P, n = w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.page_size, w.context
     M = w.pages_per_seq
     e = 2 if w.kv_dtype == "bf16" else 4
-    k_pages = max(1, int(math.ceil(args.budget * M)))
-    cap = max(k_pages, int(math.ceil(0.04 * M)))
-
-    # ---------------------------------------------------------------- inputs (seeded, generated on the GPU)
-    inp = synth.make_inputs(w, 4000, device=dev)
-    copies = []
-    for c in range(args.copies):
-        ic = inp if c == 0 else {k: (v.clone() if k in ("k_pool", "v_pool") else v) for k, v in inp.items()}
-        st = DeviceState(w, ic, cap=cap, device=dev)
-        ekv.ekv_stats_build(st.cfg, st.cache(), st.stats())
-        st.ws_sparse = st.workspace(ekv.EKV_OP_DECODE_SPARSE)
-        st.ws_gauss = st.workspace(ekv.EKV_OP_SELECT_GAUSS)
-        # the token appended by the step: the last token of the sequence, re-appended at n-1 every step
-        st.seq_prev = (ic["seq_lens"] - 1).contiguous()
-        st.cache_prev = ekv.cache_view(ic["k_pool"], ic["v_pool"], ic["block_table"], st.seq_prev)
-        rows = ic["block_table"][:, (n - 1) // P].long()
-        st.k_new = ic["k_pool"][rows, :, (n - 1) % P].contiguous()
-        st.v_new = ic["v_pool"][rows, :, (n - 1) % P].contiguous()
-        copies.append(st)
-    torch.cuda.synchronize()
-
-    def ev():
-        return torch.cuda.Event(enable_timing=True)
-
-    stage_names = {"topk": ["append", "score_box", "select_topk", "decode_sparse"],
-                   "gauss": ["append", "score_gauss", "select_gauss", "decode_sparse"],
-                   "group": ["append", "score_group_max", "select_topk", "decode_sparse_group"],
-                   "dense": ["-", "-", "-", "decode_full"]}[args.variant]
-
-    def step_topk(st, evs=None):
-        if evs: evs[0].record()
-        ekv.ekv_stats_append(st.cfg, st.cache_prev, st.stats(), st.k_new, st.v_new)
-        if evs: evs[1].record()
-        ekv.ekv_score_pages(st.cfg, st.inp["q"], st.stats(), st.inp["seq_lens"], ekv.EKV_SCORE_BOX, st.box)
-        if evs: evs[2].record()
-        ekv.ekv_select_topk(st.cfg, st.box, st.inp["seq_lens"], k_pages, st.page_idx, st.n_sel, st.workspace(ekv.EKV_OP_SELECT_TOPK))
-        if evs: evs[3].record()
-        ekv.ekv_decode_sparse(st.cfg, st.inp["q"], st.cache(), st.page_idx, st.n_sel, st.out, st.tau, st.supp,
-                              st.ws_sparse)
-        if evs: evs[4].record()
-
-    def step_gauss(st, evs=None):
-        if evs: evs[0].record()
-        ekv.ekv_stats_append(st.cfg, st.cache_prev, st.stats(), st.k_new, st.v_new)
-        if evs: evs[1].record()
-        ekv.ekv_score_pages(st.cfg, st.inp["q"], st.stats(), st.inp["seq_lens"], ekv.EKV_SCORE_GAUSS, None, st.mu,
-                            st.sigma)
-        if evs: evs[2].record()
-        ekv.ekv_select_gauss(st.cfg, st.mu, st.sigma, st.inp["seq_lens"], args.q_page, 0.0, st.tau_hat, st.page_idx,
-                             st.n_sel, st.overflow, st.ws_gauss)
-        if evs: evs[3].record()
-        ekv.ekv_decode_sparse(st.cfg, st.inp["q"], st.cache(), st.page_idx, st.n_sel, st.out, st.tau, st.supp,
-                              st.ws_sparse)
-        if evs: evs[4].record()
-
-    # one page list per KV head shared by its G query heads (same budget of pages per list)
-    gcfg = ekv.make_config(B, Hkv, Hkv, d, P, w.kv_dtype, w.alpha, w.score_scale, M, cap)
-    gbox = torch.zeros(B, Hkv, M, device=dev)
-    g_idx = torch.zeros(B, Hkv, cap, device=dev, dtype=torch.int32)
-    g_n = torch.zeros(B, Hkv, device=dev, dtype=torch.int32)
-    ws_gsel = torch.empty(max(256, ekv.ekv_workspace_bytes(gcfg, ekv.EKV_OP_SELECT_TOPK)), device=dev,
-                          dtype=torch.uint8)
-
-    def step_group(st, evs=None):
-        if evs: evs[0].record()
-        ekv.ekv_stats_append(st.cfg, st.cache_prev, st.stats(), st.k_new, st.v_new)
-        if evs: evs[1].record()
-        ekv.ekv_score_pages(st.cfg, st.inp["q"], st.stats(), st.inp["seq_lens"],
-                            ekv.EKV_SCORE_BOX | ekv.EKV_SCORE_GROUP_MAX, gbox)
-        if evs: evs[2].record()
-        ekv.ekv_select_topk(gcfg, gbox, st.inp["seq_lens"], k_pages, g_idx, g_n, ws_gsel)
-        if evs: evs[3].record()
-        ekv.ekv_decode_sparse_group(st.cfg, st.inp["q"], st.cache(), g_idx, g_n, st.out, st.tau, st.supp,
-                                    st.ws_sparse)
-        if evs: evs[4].record()
-
-    ws_full_all = None
-
-    def step_dense(st, evs=None):
-        nonlocal ws_full_all
-        if ws_full_all is None:
-            ws_full_all = copies[0].workspace(ekv.EKV_OP_DECODE_FULL)     # one scratch shared by the copies
-        if evs:
-            for e in evs[:4]: e.record()
-        ekv.ekv_decode_full(st.cfg, st.inp["q"], st.cache(), st.out, st.tau, st.supp, ws_full_all)
-        if evs: evs[4].record()
-
-    def run_timed(step_fn, steps, warmup):
-        """W untimed steps, then exactly K steps between two synchronisations (wall clock, nothing but the
-        step's own launches in the timed region).  A second pass of K steps records HIP events between the
-        stages on the launch stream for the per-stage breakdown; the markers sit between dependent kernels
-        and cost a little, so that pass is not the headline number."""
-        for i in range(warmup):
-            step_fn(copies[i % len(copies)])
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for i in range(steps):
-            step_fn(copies[i % len(copies)])
-        torch.cuda.synchronize()
-        wall = time.perf_counter() - t0
-        all_evs = [[ev() for _ in range(5)] for _ in range(steps)]
-        for i in range(steps):
-            step_fn(copies[i % len(copies)], all_evs[i])
-        torch.cuda.synchronize()
-        stage = np.array([[es[j].elapsed_time(es[j + 1]) * 1e3 for j in range(4)] for es in all_evs])   # us
-        whole = np.array([es[0].elapsed_time(es[4]) * 1e3 for es in all_evs])
-        return wall / steps * 1e6, stage, whole
+    R = Runner(w, args.budget, args.copies, args.q_page, dev, args.cap_frac)
+    k_pages, copies = R.k_pages, R.copies
+    stage_names = STAGE_NAMES[args.variant]
 
     if args.pmc_copy:
         # a plain copy of known size: 1 GiB read + 1 GiB written by one elementwise kernel
@@ -189,10 +252,9 @@ def main():
         del src, dst
 
     # ---------------------------------------------------------------- headline: top-k step
-    step_fn = {"topk": step_topk, "gauss": step_gauss, "group": step_group, "dense": step_dense}[args.variant]
-    us_wall, stage, whole = run_timed(step_fn, args.steps, args.warmup)
+    us_wall, stage, whole = R.run_timed(R.step(args.variant), args.steps, args.warmup)
     if args.variant != "topk":       # the byte accounting below is the top-k step's: leave its lists in place
-        step_topk(copies[0]); torch.cuda.synchronize()
+        R.step_topk(copies[0]); torch.cuda.synchronize()
     stage_mean = stage.mean(axis=0)
     st0 = copies[0]
     supp_mean = float(st0.supp.float().mean())
@@ -209,27 +271,14 @@ def main():
     step_bytes = bytes_meta + bytes_scores + bytes_k + bytes_v + bytes_z
     dense_bytes = B * Hkv * n * 2 * d * e
 
-    # Per-entry-point launch durations, measured live: N launches queued back to back on the launch stream
-    # between two HIP events (no marker between dependent kernels), rotating over the cache copies.
-    def back_to_back(fn, reps=60, warm=6):
-        for i in range(warm):
-            fn(copies[i % len(copies)])
-        a, b = ev(), ev()
-        a.record()
-        for i in range(reps):
-            fn(copies[i % len(copies)])
-        b.record()
-        torch.cuda.synchronize()
-        return a.elapsed_time(b) * 1e3 / reps
-
-    ws_topk = {id(st): st.workspace(ekv.EKV_OP_SELECT_TOPK) for st in copies}
-    t_append = back_to_back(lambda st: ekv.ekv_stats_append(st.cfg, st.cache_prev, st.stats(), st.k_new, st.v_new))
-    t_score = back_to_back(lambda st: ekv.ekv_score_pages(st.cfg, st.inp["q"], st.stats(), st.inp["seq_lens"],
-                                                          ekv.EKV_SCORE_BOX, st.box))
-    t_topk = back_to_back(lambda st: ekv.ekv_select_topk(st.cfg, st.box, st.inp["seq_lens"], k_pages, st.page_idx,
-                                                         st.n_sel, ws_topk[id(st)]))
-    t_dec = back_to_back(lambda st: ekv.ekv_decode_sparse(st.cfg, st.inp["q"], st.cache(), st.page_idx, st.n_sel,
-                                                          st.out, st.tau, st.supp, st.ws_sparse))
+    # per-entry-point launch durations, measured live
+    t_append = R.back_to_back(lambda st: ekv.ekv_stats_append(st.cfg, st.cache_prev, st.stats(), st.k_new, st.v_new))
+    t_score = R.back_to_back(lambda st: ekv.ekv_score_pages(st.cfg, st.inp["q"], st.stats(), st.inp["seq_lens"],
+                                                            ekv.EKV_SCORE_BOX, st.box))
+    t_topk = R.back_to_back(lambda st: ekv.ekv_select_topk(st.cfg, st.box, st.inp["seq_lens"], k_pages, st.page_idx,
+                                                           st.n_sel, st.ws_topk))
+    t_dec = R.back_to_back(lambda st: ekv.ekv_decode_sparse(st.cfg, st.inp["q"], st.cache(), st.page_idx, st.n_sel,
+                                                            st.out, st.tau, st.supp, st.ws_sparse))
     kernel_alg_bytes = {
         "stats_append": None,
         "score_pages(box)": bytes_meta + B * Hq * M * 4,                 # metadata read + scores written
@@ -251,14 +300,14 @@ def main():
     roof_bytes = kernel_alg_bytes["score_pages(box)"]
     achieved = roof_bytes / (t_score * 1e-6) / 1e9
     # HBM bytes per launch from the FETCH_SIZE / WRITE_SIZE counter runs (profiles/bench_topk_step_C4.md);
-    # they hold for the workload and budget those runs used
-    pmc_traffic = {("C4", 0.02): PMC_TRAFFIC_SCORE_PAGES_C4}
+    # they hold for the workload those runs used
+    pmc_traffic = {"C4": PMC_TRAFFIC_SCORE_PAGES_C4}
     roofline = {
         "bound": "hbm", "kernel": "score_pages_mfma_kernel<G=%d,box> (ekv_score_pages)" % w.group,
         "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-        "traffic": pmc_traffic.get((args.workload, args.budget)),
+        "traffic": pmc_traffic.get(args.workload),
         "algorithmic_bytes_per_launch": int(roof_bytes), "avg_launch_us": round(t_score, 2),
-        "timing": "HIP events around 60 back-to-back launches on the launch stream, 4 rotating copies",
+        "timing": "HIP events around 60 back-to-back launches on the launch stream, %d rotating copies" % args.copies,
     }
     dom_name = stage_names[int(np.argmax(stage_mean))]
 
@@ -286,18 +335,6 @@ def main():
 
     # ---------------------------------------------------------------- the other rows, same run
     if not args.no_extras:
-        def time_call(fn, reps=20, warm=3):
-            for i in range(warm):
-                fn(copies[i % len(copies)])
-            torch.cuda.synchronize()
-            ts = []
-            for i in range(reps):
-                a, b = ev(), ev()
-                a.record(); fn(copies[i % len(copies)]); b.record()
-                torch.cuda.synchronize()
-                ts.append(a.elapsed_time(b) * 1e3)
-            return float(np.median(ts))
-
         extras = {}
         # context for the roofline fractions: what a plain device copy (torch's elementwise copy kernel,
         # 1 GiB read + 1 GiB written) moves on this GPU
@@ -305,7 +342,7 @@ def main():
         dst = torch.empty_like(src)
         for _ in range(2):
             dst.copy_(src)
-        a, b = ev(), ev()
+        a, b = R.ev(), R.ev()
         a.record()
         for _ in range(5):
             dst.copy_(src)
@@ -313,18 +350,16 @@ def main():
         torch.cuda.synchronize()
         extras["plain_copy_GBps_measured"] = round(2 * src.numel() * 4 / (a.elapsed_time(b) * 1e-3 / 5) / 1e9, 1)
         del src, dst
-        us_g, stage_g, whole_g = run_timed(step_gauss, max(10, args.steps // 4), 5)
+        side = max(10, args.steps // 4)
+        us_g, stage_g, _ = R.run_timed(R.step_gauss, side, 5)
         extras["gauss_step_us"] = round(us_g, 2)
-        extras["gauss_stage_us"] = {nm: round(float(v), 2) for nm, v in
-                                    zip(["append", "score_gauss", "select_gauss", "decode_sparse"], stage_g.mean(axis=0))}
+        extras["gauss_stage_us"] = {nm: round(float(v), 2) for nm, v in zip(STAGE_NAMES["gauss"], stage_g.mean(axis=0))}
         extras["gauss_selected_pages_mean"] = float(copies[0].n_sel.float().mean())
         extras["gauss_overflow"] = int(copies[0].overflow.sum())
-        for st in copies:
-            st.ws_full = None
         ws_full = copies[0].workspace(ekv.EKV_OP_DECODE_FULL)       # one scratch shared by the copies
         out_f, tau_f, supp_f = torch.zeros_like(st0.out), torch.zeros_like(st0.tau), torch.zeros_like(st0.supp)
-        dense_us = time_call(lambda st: ekv.ekv_decode_full(st.cfg, st.inp["q"], st.cache(), out_f, tau_f, supp_f,
-                                                            ws_full), reps=10)
+        dense_us = R.time_call(lambda st: ekv.ekv_decode_full(st.cfg, st.inp["q"], st.cache(), out_f, tau_f, supp_f,
+                                                              ws_full), reps=10)
         extras["dense_full_us"] = round(dense_us, 2)
         extras["dense_full_GBps"] = round((dense_bytes / 2 + B * Hq * n * 8) / (dense_us * 1e-6) / 1e9, 1)
         extras["speedup_vs_dense"] = round(dense_us / us_wall, 2)
@@ -333,43 +368,41 @@ def main():
         kept_mass = torch.zeros_like(st0.tau); kept_supp = torch.zeros_like(st0.supp)
         for frac in (0.01, 0.02, 0.04):
             kp = max(1, int(math.ceil(frac * M)))
-            ekv.ekv_select_topk(st0.cfg, st0.box, st0.inp["seq_lens"], kp, st0.page_idx, st0.n_sel, st0.workspace(ekv.EKV_OP_SELECT_TOPK))
+            ekv.ekv_select_topk(st0.cfg, st0.box, st0.inp["seq_lens"], kp, st0.page_idx, st0.n_sel, st0.ws_topk)
             ekv.ekv_decode_sparse(st0.cfg, st0.inp["q"], st0.cache(), st0.page_idx, st0.n_sel, st0.out, st0.tau,
                                   st0.supp, st0.ws_sparse,
                                   extras=ekv.decode_extras(tau_ref=tau_f, kept_mass_ref=kept_mass, kept_supp_ref=kept_supp))
             torch.cuda.synchronize()
-            R = ((st0.out - out_f).norm(dim=-1) / out_f.norm(dim=-1)).mean()
+            Rerr = ((st0.out - out_f).norm(dim=-1) / out_f.norm(dim=-1)).mean()
             extras[f"topk_{frac:.0%}"] = {
                 "delta_mean": round(float((1 - kept_mass).mean()), 6),
                 "rho_mean": round(float((kept_supp.float() / supp_f.float()).mean()), 4),
-                "R_mean": round(float(R), 6),
-                "step_us": None}
-        us_gr, stage_gr, _ = run_timed(step_group, max(10, args.steps // 4), 5)
+                "R_mean": round(float(Rerr), 6)}
+        us_gr, stage_gr, _ = R.run_timed(R.step_group, side, 5)
         extras["group_shared_step_us"] = round(us_gr, 2)
         extras["group_shared_stage_us"] = {nm: round(float(v), 2) for nm, v in
-                                           zip(["append", "score_group_max", "select_topk", "decode_sparse_group"],
-                                               stage_gr.mean(axis=0))}
+                                           zip(STAGE_NAMES["group"], stage_gr.mean(axis=0))}
         extras["speedup_group_shared_vs_dense"] = round(dense_us / us_gr, 2)
         # exactness certificate / refinement: pages whose box bound exceeds the sparse tau (App. B.2)
-        ekv.ekv_select_topk(st0.cfg, st0.box, st0.inp["seq_lens"], k_pages, st0.page_idx, st0.n_sel, st0.workspace(ekv.EKV_OP_SELECT_TOPK))
+        ekv.ekv_select_topk(st0.cfg, st0.box, st0.inp["seq_lens"], k_pages, st0.page_idx, st0.n_sel, st0.ws_topk)
         ekv.ekv_decode_sparse(st0.cfg, st0.inp["q"], st0.cache(), st0.page_idx, st0.n_sel, st0.out, st0.tau,
                               st0.supp, st0.ws_sparse)
         ref_idx, ref_n = torch.zeros_like(st0.page_idx), torch.zeros_like(st0.n_sel)
         n_added, ovf = torch.zeros_like(st0.n_sel), torch.zeros_like(st0.n_sel)
         ws_box = st0.workspace(ekv.EKV_OP_SELECT_BOX_THRESHOLD)
-        extras["box_threshold_refine_us"] = round(time_call(
+        extras["box_threshold_refine_us"] = round(R.time_call(
             lambda st: ekv.ekv_select_box_threshold(st0.cfg, st0.box, st0.inp["seq_lens"], st0.tau, st0.page_idx,
                                                     st0.n_sel, ref_idx, ref_n, n_added, ovf, ws_box), reps=10), 2)
         extras["box_threshold_pages_added_mean"] = float(n_added.float().mean())
         extras["box_threshold_overflow_heads"] = int(ovf.sum())
         lse_sel = torch.zeros_like(st0.tau)
         ws_sm = copies[0].workspace(ekv.EKV_OP_DECODE_SPARSE_SOFTMAX)
-        ekv.ekv_select_topk(st0.cfg, st0.box, st0.inp["seq_lens"], k_pages, st0.page_idx, st0.n_sel, st0.workspace(ekv.EKV_OP_SELECT_TOPK))
-        extras["softmax_sparse_us"] = round(time_call(
+        ekv.ekv_select_topk(st0.cfg, st0.box, st0.inp["seq_lens"], k_pages, st0.page_idx, st0.n_sel, st0.ws_topk)
+        extras["softmax_sparse_us"] = round(R.time_call(
             lambda st: ekv.ekv_decode_sparse_softmax(st0.cfg, st0.inp["q"], st.cache(), st0.page_idx, st0.n_sel,
                                                      st0.out, lse_sel, ws_sm), reps=10), 2)
-        extras["stats_build_us"] = round(time_call(lambda st: ekv.ekv_stats_build(st.cfg, st.cache(), st.stats()),
-                                                   reps=8), 2)
+        extras["stats_build_us"] = round(R.time_call(lambda st: ekv.ekv_stats_build(st.cfg, st.cache(), st.stats()),
+                                                     reps=8), 2)
         extras["stats_build_GBps"] = round((dense_bytes / 2 + 2 * bytes_meta) / (extras["stats_build_us"] * 1e-6) / 1e9, 1)
         result["other_rows"] = extras
 
@@ -379,6 +412,7 @@ def main():
         from tests.helpers import to_f64
         from threadpoolctl import threadpool_limits
         threadpool_limits(1)                                   # one thread, so that `cores` is exact
+        inp = R.inp
         all_units = [(b, h) for b in range(B) for h in range(Hq)]
         units = all_units[: max(1, min(args.cpu_units, len(all_units)))]
         t_cpu = 0.0
@@ -407,6 +441,40 @@ def main():
             "sample": f"float64 numpy oracle, whole top-k step (stats+score+select+sparse entmax) of {len(units)} of "
                       f"{B * Hq} (b,head) units, single thread, {t_cpu:.1f} s measured; value = per-unit time x {B * Hq} units",
         }
+
+    # ---------------------------------------------------------------- the 128K-token batch workload, same steps
+    if not args.no_extras and args.workload == "C4":
+        R.release()
+        del R, copies, st0
+        w3 = synth.WORKLOADS["C3"]
+        R3 = Runner(w3, args.budget, args.copies, args.q_page, dev, args.cap_frac)
+        side = max(10, args.steps // 4)
+        row = {"workload": f"{w3.name}: B{w3.batch} {w3.n_q_heads}q/{w3.n_kv_heads}kv ctx{w3.context} page{w3.page_size} "
+                           f"{w3.kv_dtype}, top-k {R3.k_pages} pages ({args.budget:.0%})"}
+        us3, stage3, _ = R3.run_timed(R3.step_topk, side, 5)
+        row["topk_step_us"] = round(us3, 2)
+        row["topk_stage_us"] = {nm: round(float(v), 2) for nm, v in zip(STAGE_NAMES["topk"], stage3.mean(axis=0))}
+        us3r, _, _ = R3.run_timed(R3.step_group, side, 5, stages=False)
+        row["group_shared_step_us"] = round(us3r, 2)
+        us3d, _, _ = R3.run_timed(R3.step_dense, max(5, side // 2), 3, stages=False)
+        row["dense_full_us"] = round(us3d, 2)
+        d3 = w3.batch * w3.n_kv_heads * w3.context * 2 * w3.head_dim * 2
+        row["dense_full_GBps"] = round((d3 / 2 + w3.batch * w3.n_q_heads * w3.context * 8) / (us3d * 1e-6) / 1e9, 1)
+        row["speedup_topk_vs_dense"] = round(us3d / us3, 2)
+        R3.release()
+        del R3
+        # at 128K the adaptive selector keeps 5-16 % of the pages of this data: its lists get that room
+        # (the list capacity also sizes the decode's launch grid, so the top-k rows above keep the small one)
+        R3g = Runner(w3, args.budget, args.copies, args.q_page, dev, cap_frac=0.25)
+        us3g, stage3g, _ = R3g.run_timed(R3g.step_gauss, side, 5)
+        row["gauss_step_us"] = round(us3g, 2)
+        row["gauss_stage_us"] = {nm: round(float(v), 2) for nm, v in zip(STAGE_NAMES["gauss"], stage3g.mean(axis=0))}
+        row["gauss_selected_pages_mean"] = float(R3g.copies[0].n_sel.float().mean())
+        row["gauss_overflow_heads"] = int(R3g.copies[0].overflow.sum())
+        row["speedup_gauss_vs_dense"] = round(us3d / us3g, 2)
+        result["other_rows"]["C3-128k"] = row
+        R3g.release()
+
     print(json.dumps(result))
 
 

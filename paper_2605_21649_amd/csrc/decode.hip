@@ -45,8 +45,8 @@ struct ScoreArgs {
 
 // A wavefront covers kGroupsPerWave groups of pmax_pages(P) consecutive page slots (64 tokens when P
 // divides 64) and writes each group's maximum straight to pmax (no LDS, no barrier); a workgroup is four
-// such wavefronts.  Page indices are resolved first (wave-uniform loads, clamped into range so that
-// nothing depends on n_sel), then all K loads of the wavefront are issued before any is consumed.
+// such wavefronts.  Page indices are resolved first (wave-uniform loads issued together with the list
+// length, clamped into range), then all K loads of the wavefront are issued before any is consumed.
 constexpr int kGroupsPerWave = 1;
 constexpr int kScoreWaves = kScoreThreads / 64;
 
@@ -152,6 +152,11 @@ __global__ __launch_bounds__(kScoreThreads) void decode_scores_mfma_kernel(const
     const int sc = min(wslot0 + i, (DENSE ? A.Mmax : A.cap) - 1);
     lps[i] = DENSE ? sc : clampi(A.page_idx[(size_t)unit * A.cap + sc], 0, A.Mmax - 1);
   }
+  // the lengths arrive with the page indices (independent loads): a wavefront past the end of its list
+  // leaves before it touches the block table or K
+  const int n = A.seq_lens[b];
+  const int n_slots = clampi(DENSE ? (n + PT - 1) / PT : A.n_sel[unit], 0, DENSE ? A.Mmax : A.cap);
+  if (wslot0 >= n_slots) return;
 #pragma unroll
   for (int i = 0; i < SW; ++i) physs[i] = clampi(A.block_table[(size_t)b * A.Mmax + lps[i]], 0, A.n_phys - 1);
   uint4 a[SW][STEPS];
@@ -161,15 +166,12 @@ __global__ __launch_bounds__(kScoreThreads) void decode_scores_mfma_kernel(const
 #pragma unroll
     for (int s = 0; s < STEPS; ++s) a[i][s] = *reinterpret_cast<const uint4*>(kpage + (size_t)s * 4 * kD);
   }
-  const int n = A.seq_lens[b];
-  const int n_slots = clampi(DENSE ? (n + PT - 1) / PT : A.n_sel[unit], 0, DENSE ? A.Mmax : A.cap);
   uint4 bq[NSET];
 #pragma unroll
   for (int s = 0; s < NSET; ++s) {
     const int g = min(4 * s + gl, G - 1);          // columns past the group repeat its last head (not stored)
     bq[s] = *reinterpret_cast<const uint4*>(q + ((size_t)b * Hq + hq0 + g) * kD + kq * 32 + j * 8);
   }
-  if (wslot0 >= n_slots) return;
 
 #pragma unroll
   for (int gi = 0; gi < kGroupsPerWave; ++gi) {

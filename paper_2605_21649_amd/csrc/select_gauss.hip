@@ -248,9 +248,11 @@ __global__ __launch_bounds__(kGaussEvalThreads) void gauss_eval_kernel(const flo
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int p = pb + j * kGaussEvalThreads;
-      float fp, dp;
-      page_mass<NB>(fmaf(a, mv[j], -st.tau), a * sv[j], p == M - 1 ? cnt_last : (float)P, fp, dp);
-      if (p < p1) { f += fp; d += dp; }
+      if (p < p1) {                                                    // no loads inside: divergence is harmless
+        float fp, dp;
+        page_mass<NB>(fmaf(a, mv[j], -st.tau), a * sv[j], p == M - 1 ? cnt_last : (float)P, fp, dp);
+        f += fp; d += dp;
+      }
     }
   }
   f = wave_sum(f); d = wave_sum(d);
