@@ -243,6 +243,24 @@ __global__ __launch_bounds__(kScoreThreads) void decode_scores_mfma_kernel(const
 //             highest grid point whose bound is >= 1 is a certified lower bound of tau.
 //   compact : the slice's candidates above that bound are written out in order.
 // The solve then gathers the (few) survivors of all slices into LDS.
+// Counts per 1/64-wide bin above a base point give a lower bound of the mass at every grid point i: an
+// entry of bin g lies at least (g - i) bins above it.  Returns the highest i in [0, 64) whose bound
+// sum_{g > i} cnt[g] * ((g - i - 0.02) * step)^beta reaches 1 (with a margin), or 0.  Called by all 1024
+// threads of a workgroup: 16 lanes per grid point, a DPP row sum, one barrier; `flags` is LDS [64].
+template <int NB>
+__device__ __forceinline__ int certified_level(const int* cnt, float step, float beta, int ibeta, int* flags) {
+  const int i = threadIdx.x >> 4, l = threadIdx.x & 15;
+  float lb = 0.f;
+#pragma unroll
+  for (int g = l; g < NB; g += 16)
+    if (g > i) lb += (float)cnt[g] * pow_beta(((float)(g - i) - 0.02f) * step, beta, ibeta);
+  lb = row16_sum(lb);
+  if (l == 0) flags[i] = lb >= 1.0001f ? 1 : 0;
+  __syncthreads();
+  const uint64_t okm = __ballot(flags[threadIdx.x & 63] != 0);
+  return okm ? 63 - __clzll(okm) : 0;
+}
+
 constexpr int kFilterThreads = 1024;
 constexpr int kFilterWaves = kFilterThreads / 64;
 constexpr int kFilterLoads = kFilterSlice / (kFilterThreads * 4);   // float4 loads per thread
@@ -324,6 +342,7 @@ __global__ __launch_bounds__(kLevelThreads) void filter_level_kernel(const Filte
   __shared__ float red[kLevelThreads / 64];
   __shared__ int redi[kLevelThreads / 64];
   __shared__ int mh[66];
+  __shared__ int flags[64];
   const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int n_cand = filter_n_cand<DENSE>(A, row);
   const int n_slices = (n_cand + kFilterSlice - 1) / kFilterSlice;
@@ -362,16 +381,9 @@ __global__ __launch_bounds__(kLevelThreads) void filter_level_kernel(const Filte
       }
     }
     __syncthreads();
-    if (tid < 64) {
-      // lower bound of the mass at grid point tid of [gtop-64, gtop]
-      float lb = 0.f;
-      for (int g = tid + 1; g < 65; ++g)
-        lb += (float)mh[g] * pow_beta(((float)(g - tid) - 0.02f) * (1.0f / 64.0f), A.beta, A.ibeta);
-      const uint64_t okm = __ballot(lb >= 1.0001f);
-      const int level = okm ? 63 - __clzll(okm) : 0;
-      if (level > 0) thr = (float)(gtop - 64 + level) * (1.0f / 64.0f);   // > zmax - 1
-      if (tid == 0) { A.frow[2 * row] = zmax; A.frow[2 * row + 1] = thr; }
-    }
+    const int level = certified_level<65>(mh, 1.0f / 64.0f, A.beta, A.ibeta, flags);   // grid [gtop-64, gtop]
+    if (level > 0) thr = (float)(gtop - 64 + level) * (1.0f / 64.0f);   // > zmax - 1
+    if (tid == 0) { A.frow[2 * row] = zmax; A.frow[2 * row + 1] = thr; }
   } else if (tid == 0) {
     A.frow[2 * row] = zmax; A.frow[2 * row + 1] = thr;
   }
@@ -439,7 +451,7 @@ struct SolveShared {
   int wcount[2][kSolveWaves];
   float red1[kSolveWaves];
   int hist[64];                   // candidates per 1/64 slice of [thr, zmax] (threshold tightening)
-  int level;
+  int flags[64];
 };
 
 // Candidate source: the compacted LDS list, or (when it does not fit) the score row itself.
@@ -703,15 +715,7 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
     }
     __syncthreads();
     // highest slice boundary whose counted lower bound of the mass is still >= 1
-    if (tid < 64) {
-      float lb = 0.f;
-      for (int jj = tid + 1; jj < 64; ++jj)
-        lb += (float)sh.hist[jj] * pow_beta(((float)(jj - tid) - 0.02f) * slice, beta, ibeta);
-      const uint64_t okm = __ballot(lb >= 1.0001f);
-      if (tid == 0) sh.level = okm ? 63 - __clzll(okm) : 0;
-    }
-    __syncthreads();
-    const int level = sh.level;
+    const int level = certified_level<64>(sh.hist, slice, beta, ibeta, sh.flags);
     const float thr2 = thr + (float)level * slice;
     if (in_lds) { lo_u = fminf(thr2 - zmax, -1e-7f); break; }
     if (level == 0) break;                       // no tighter threshold from counts: stream the row

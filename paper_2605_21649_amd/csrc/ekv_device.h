@@ -96,29 +96,38 @@ __device__ __forceinline__ float row16_sum(float v) {
   return v;
 }
 
+// Wavefront reductions: DPP butterflies inside each 16-lane row, then the two cross-row DPP broadcasts
+// (lane 15 of a row into the next row, lane 31 into the upper half), which leave the result in lane 63;
+// it is returned to every lane through a scalar register.  No LDS traffic, fixed order.
+template <int CTRL, int ROW_MASK> __device__ __forceinline__ float dpp_rows(float old, float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(old), __float_as_int(v), CTRL, ROW_MASK, 0xf, false));
+}
+template <int CTRL, int ROW_MASK> __device__ __forceinline__ int dpp_rows_i(int old, int v) {
+  return __builtin_amdgcn_update_dpp(old, v, CTRL, ROW_MASK, 0xf, false);
+}
 __device__ __forceinline__ float wave_sum(float v) {
   v = row16_sum(v);
-  v += __shfl_xor(v, 16);
-  v += __shfl_xor(v, 32);
-  return v;
+  v += dpp_rows<0x142, 0xa>(0.f, v);     // row_bcast15 into rows 1 and 3
+  v += dpp_rows<0x143, 0xc>(0.f, v);     // row_bcast31 into rows 2 and 3
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 __device__ __forceinline__ float wave_max(float v) {
   v = fmaxf(v, dpp_move<0xB1>(v));
   v = fmaxf(v, dpp_move<0x4E>(v));
   v = fmaxf(v, dpp_move<0x141>(v));
   v = fmaxf(v, dpp_move<0x140>(v));
-  v = fmaxf(v, __shfl_xor(v, 16));
-  v = fmaxf(v, __shfl_xor(v, 32));
-  return v;
+  v = fmaxf(v, dpp_rows<0x142, 0xa>(v, v));
+  v = fmaxf(v, dpp_rows<0x143, 0xc>(v, v));
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 __device__ __forceinline__ int wave_sum_i(int v) {
   v += dpp_move_i<0xB1>(v);
   v += dpp_move_i<0x4E>(v);
   v += dpp_move_i<0x141>(v);
   v += dpp_move_i<0x140>(v);
-  v += __shfl_xor(v, 16);
-  v += __shfl_xor(v, 32);
-  return v;
+  v += dpp_rows_i<0x142, 0xa>(0, v);
+  v += dpp_rows_i<0x143, 0xc>(0, v);
+  return __builtin_amdgcn_readlane(v, 63);
 }
 
 // Block-wide reductions through a small LDS array (one slot per wavefront); all threads get the
