@@ -91,3 +91,34 @@ def test_binding_raises_without_fallback(monkeypatch):
     monkeypatch.setattr(ekv, "LIB_PATH", "/nonexistent/libentmaxkv.so")
     with pytest.raises(ekv.EkvError):
         ekv.load_library()
+
+
+def test_new_entry_points_validate_their_arguments():
+    lib = ekv.load_library()
+    cfg = good_cfg()
+    # box-threshold selection: missing outputs, list given without its length, workspace too small
+    assert lib.ekv_select_box_threshold(ctypes.byref(cfg), 0x1000, 0x2000, 0x3000, None, None, None, 0x5000, 0x6000,
+                                        0x7000, 0x8000, 1 << 30, None) == 1
+    assert lib.ekv_select_box_threshold(ctypes.byref(cfg), 0x1000, 0x2000, 0x3000, 0x4000, None, 0x4000, 0x5000,
+                                        0x6000, 0x7000, 0x8000, 1 << 30, None) == 1
+    assert lib.ekv_select_box_threshold(ctypes.byref(cfg), 0x1000, 0x2000, 0x3000, None, None, 0x4000, 0x5000,
+                                        0x6000, 0x7000, 0x8000, 16, None) == 3
+    assert ekv.ekv_workspace_bytes(cfg, ekv.EKV_OP_SELECT_BOX_THRESHOLD) >= 32 * 16 * 4096 * 4
+    # group maximum only combines with the box score
+    stats = ekv.ekv_stats_view(0x5000, 0x6000)
+    bad_mode = ekv.EKV_SCORE_GAUSS | ekv.EKV_SCORE_GROUP_MAX
+    assert lib.ekv_score_pages(ctypes.byref(cfg), 0x1000, ctypes.byref(stats), 0x4000, bad_mode, 0x7000, 0x8000,
+                               0x9000, None) == 1
+    # grouped decode: same checks as the per-head decode
+    cache = ekv.ekv_cache_view(0x1000, 0x2000, 0x3000, 0x4000, 4)
+    assert lib.ekv_decode_sparse_group(ctypes.byref(cfg), 0x1000, ctypes.byref(cache), None, 0x9000, 0x5000, 0x6000,
+                                       0x7000, None, 0xA000, 1 << 40, None) == 1
+    assert lib.ekv_decode_sparse_group(ctypes.byref(cfg), 0x1000, ctypes.byref(cache), 0x8000, 0x9000, 0x5000,
+                                       0x6000, 0x7000, None, 0xA000, 1024, None) == 3
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
