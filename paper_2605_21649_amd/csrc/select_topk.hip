@@ -192,12 +192,12 @@ __global__ __launch_bounds__(kSelThreads) void topk_find_kernel(const float* __r
   uint32_t a0 = 0, a1 = 0;
   {
     const uint32_t* ab = ws.above + (size_t)bh * S * kBins + 2 * tid;
-    for (int s0 = 0; s0 < S; s0 += 8) {
-      uint2 v[8];
+    for (int s0 = 0; s0 < S; s0 += 16) {
+      uint2 v[16];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) v[i] = *reinterpret_cast<const uint2*>(ab + (size_t)min(s0 + i, S - 1) * kBins);
+      for (int i = 0; i < 16; ++i) v[i] = *reinterpret_cast<const uint2*>(ab + (size_t)min(s0 + i, S - 1) * kBins);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) if (s0 + i < S) { a0 += v[i].x; a1 += v[i].y; }
+      for (int i = 0; i < 16; ++i) if (s0 + i < S) { a0 += v[i].x; a1 += v[i].y; }
     }
   }
   tot_above[2 * tid] = a0; tot_above[2 * tid + 1] = a1;
@@ -240,14 +240,24 @@ __global__ __launch_bounds__(kSelThreads) void topk_find_kernel(const float* __r
   }
   __syncthreads();
   // exact rank of every member: larger key first, lower page first among equal keys
-  if (tid < m) {
-    const uint32_t kk = mem_key[tid]; const int pp = mem_page[tid];
+  // (16 lanes share a member and split the others among them; 64 members per sweep of the workgroup)
+  for (int i0 = 0; i0 < m; i0 += kSelThreads / 16) {
+    const int i = min(i0 + (tid >> 4), m - 1), l = tid & 15;
+    const uint32_t kk = mem_key[i]; const int pp = mem_page[i];
     int rank = 0;
-    for (int jj = 0; jj < m; ++jj) {
-      const uint32_t kj = mem_key[jj];
-      rank += (kj > kk) || (kj == kk && mem_page[jj] < pp);
+    for (int j0 = 0; j0 < m; j0 += 64) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int jj = j0 + u * 16 + l, jc = min(jj, m - 1);
+        const uint32_t kj = mem_key[jc]; const int pj = mem_page[jc];
+        rank += jj < m && ((kj > kk) || (kj == kk && pj < pp));
+      }
     }
-    if (rank == k_rem - 1) s_keyt = kk;                // the k-th largest key overall
+    rank += dpp_move_i<0xB1>(rank);
+    rank += dpp_move_i<0x4E>(rank);
+    rank += dpp_move_i<0x141>(rank);
+    rank += dpp_move_i<0x140>(rank);
+    if (l == 0 && i0 + (tid >> 4) < m && rank == k_rem - 1) s_keyt = kk;   // the k-th largest key overall
   }
   __syncthreads();
   const uint32_t key_t = s_keyt;
