@@ -98,7 +98,8 @@ __device__ __forceinline__ float row16_sum(float v) {
 
 // Wavefront reductions: DPP butterflies inside each 16-lane row, then the two cross-row DPP broadcasts
 // (lane 15 of a row into the next row, lane 31 into the upper half), which leave the result in lane 63;
-// it is returned to every lane through a scalar register.  No LDS traffic, fixed order.
+// it is returned to every lane through a scalar register.  No LDS traffic, fixed order.  All 64 lanes of
+// the wavefront must be active at the call (every call site is wavefront-uniform).
 template <int CTRL, int ROW_MASK> __device__ __forceinline__ float dpp_rows(float old, float v) {
   return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(old), __float_as_int(v), CTRL, ROW_MASK, 0xf, false));
 }
