@@ -383,6 +383,37 @@ def main():
         extras["group_shared_stage_us"] = {nm: round(float(v), 2) for nm, v in
                                            zip(STAGE_NAMES["group"], stage_gr.mean(axis=0))}
         extras["speedup_group_shared_vs_dense"] = round(dense_us / us_gr, 2)
+        # 64 consecutive decode steps: the sequence grows by one token per step (the length is bumped on the
+        # device between steps, page boundaries are crossed every P steps), nothing is synchronised in between
+        T = 64
+        seq = st0.inp["seq_lens"]                              # shared by the copies
+        seq_full = seq.clone()
+        pos = [n - T + t for t in range(T)]
+        rows_t = [st0.inp["block_table"][:, p_ // P].long() for p_ in pos]
+        k_news = [st0.inp["k_pool"][rows_t[t], :, pos[t] % P].contiguous() for t in range(T)]
+        v_news = [st0.inp["v_pool"][rows_t[t], :, pos[t] % P].contiguous() for t in range(T)]
+
+        def run_loop():
+            seq.fill_(n - T)
+            for t in range(T):
+                st = copies[t % len(copies)]
+                ekv.ekv_stats_append(st.cfg, st.cache(), st.stats(), k_news[t], v_news[t])
+                seq.add_(1)
+                ekv.ekv_score_pages(st.cfg, st.inp["q"], st.stats(), seq, ekv.EKV_SCORE_BOX, st.box)
+                ekv.ekv_select_topk(st.cfg, st.box, seq, k_pages, st.page_idx, st.n_sel, st.ws_topk)
+                ekv.ekv_decode_sparse(st.cfg, st.inp["q"], st.cache(), st.page_idx, st.n_sel, st.out, st.tau,
+                                      st.supp, st.ws_sparse)
+        run_loop()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run_loop()
+        torch.cuda.synchronize()
+        extras["decode_loop_us_per_step"] = round((time.perf_counter() - t0) / T * 1e6, 2)
+        extras["decode_loop_steps"] = T
+        seq.copy_(seq_full)
+        for st in copies:                                      # last pages back to their full statistics
+            ekv.ekv_stats_build(st.cfg, st.cache(), st.stats())
+        torch.cuda.synchronize()
         # exactness certificate / refinement: pages whose box bound exceeds the sparse tau (App. B.2)
         ekv.ekv_select_topk(st0.cfg, st0.box, st0.inp["seq_lens"], k_pages, st0.page_idx, st0.n_sel, st0.ws_topk)
         ekv.ekv_decode_sparse(st0.cfg, st0.inp["q"], st0.cache(), st0.page_idx, st0.n_sel, st0.out, st0.tau,
