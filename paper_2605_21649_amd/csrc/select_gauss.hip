@@ -224,7 +224,13 @@ __global__ __launch_bounds__(kGaussEvalThreads) void gauss_eval_kernel(const flo
     const float mean = s1 / s0;
     const float var = fmaxf(s2 / s0 - mean * mean, 0.f);
     st.lo = mx - 1.0f; st.hi = INFINITY; st.done = 0;
-    st.tau = pooled_guess<NB>(s0, mean, sqrtf(var), st.lo);
+    // the scalar start iteration runs on one wavefront only (the others would just repeat it)
+    float tau0 = 0.f;
+    if (tid < 64) tau0 = pooled_guess<NB>(s0, mean, sqrtf(var), st.lo);
+    __syncthreads();
+    if (tid == 0) bc[0] = tau0;
+    __syncthreads();
+    st.tau = bc[0];
   } else {
     float F, D;
     sum_eval_partials(ws, k - 1, bh, BH, bc, F, D);
