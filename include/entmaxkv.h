@@ -15,7 +15,7 @@
  *  - variable-length results are (indices, count) pairs on the device with fixed capacity.
  *  - the same inputs give bit-identical outputs from run to run (fixed reduction orders, no
  *    floating-point atomics).
- *  - outputs must not alias inputs.
+ *  - outputs must not alias inputs, unless an entry point says otherwise.
  *
  * Shapes use: B batch, Hq query heads, Hkv KV heads, G=Hq/Hkv, d head_dim (=128), P page_size,
  * Mmax = max_pages_per_seq, cap = max_sel_pages, n_b = seq_lens[b], M_b = ceil(n_b/P),
@@ -72,13 +72,14 @@ typedef struct {
   float alpha;               /* entmax alpha (paper Eq. 2)                                         */
   float scale;               /* score multiplier; the paper's 1/sqrt(d) (Eq. 1)                    */
   int32_t max_pages_per_seq; /* Mmax: row length of block_table and of the per-page score arrays   */
-  int32_t max_sel_pages;     /* cap: row length of page_idx                                        */
+  int32_t max_sel_pages;     /* cap: row length of page_idx; also sizes the decode calls' launch   */
+                             /* grid, so keep it near what the selectors return                    */
 } ekv_config;
 
 /* Paged KV cache (paper Sec. 4.2: block layout of PagedAttention).  Physical page `phys` of KV head h
  * is the contiguous block pool[((phys*Hkv + h)*P + t)*d + i], t < P, i < d, element type kv_dtype.
  * block_table[b*Mmax + p] = physical page of logical page p of sequence b (0 <= phys < n_phys_pages;
- * entries with p >= M_b are never read).  seq_lens[b] = n_b >= 1. */
+ * entries with p >= M_b may hold anything: what is read from them is clamped into range and masked).  seq_lens[b] = n_b >= 1. */
 typedef struct {
   void* k_pool;
   void* v_pool;
