@@ -233,20 +233,21 @@ __global__ __launch_bounds__(kScoreThreads) void decode_scores_mfma_kernel(const
 // ------------------------------------------------------------------------------------------
 // pass 1b (long rows only): multi-workgroup candidate filter
 // ------------------------------------------------------------------------------------------
-// One workgroup of the solve cannot stream a row of a million scores.  Passes over slices of
-// kFilterSlice positions do it in parallel:
-//   hist    : slice maximum, and a count histogram of the slice's z > max-1 over bins of width 1/64 on the
-//             ABSOLUTE grid floor(64 z) -- histograms of different slices are then mergeable by a shift,
-//             without knowing the row maximum in advance.
-//   level   : one workgroup per row merges the row's histograms; an entry of bin g lies at least (g-i)/64
-//             above grid point i, so counts alone give a lower bound of the mass at every grid point; the
-//             highest grid point whose bound is >= 1 is a certified lower bound of tau.
-//   compact : the slice's candidates above that bound are written out in order.
-// The solve then gathers the (few) survivors of all slices into LDS.
-// Counts per 1/64-wide bin above a base point give a lower bound of the mass at every grid point i: an
-// entry of bin g lies at least (g - i) bins above it.  Returns the highest i in [0, 64) whose bound
-// sum_{g > i} cnt[g] * ((g - i - 0.02) * step)^beta reaches 1 (with a margin), or 0.  Called by all 1024
-// threads of a workgroup: 16 lanes per grid point, a DPP row sum, one barrier; `flags` is LDS [64].
+// One workgroup of the solve cannot stream a row of a million scores, and it does not have to: the
+// maxima of the 64-token groups written by pass 1 already bound tau from below.
+//   level   (one workgroup per row): row maximum from the group maxima, then a 64-bin count histogram of
+//           the group maxima above zmax-1.  Every counted group holds at least one score (its maximum)
+//           in that bin, and an entry of bin g lies at least (g-i) bins above grid point i, so the counts
+//           give a lower bound of the mass at every grid point; the highest grid point whose bound is >= 1
+//           is a certified lower bound of tau.  Reads 4 bytes per 64 tokens.
+//   compact (slices of kFilterSliceChunks groups x rows): only groups whose maximum exceeds that bound are
+//           read (a few hundred per row); their scores above the bound are written out in order.
+// The solve then gathers the survivors of all slices into LDS.
+
+// Counts per bin above a base point give a lower bound of the mass at every grid point i.  Returns the
+// highest i in [0, 64) whose bound sum_{g > i} cnt[g] * ((g - i - 0.02) * step)^beta reaches 1 (with a
+// margin), or 0.  Called by all 1024 threads of a workgroup: 16 lanes per grid point, a DPP row sum, one
+// barrier; `flags` is LDS [64].
 template <int NB>
 __device__ __forceinline__ int certified_level(const int* cnt, float step, float beta, int ibeta, int* flags) {
   const int i = threadIdx.x >> 4, l = threadIdx.x & 15;
@@ -263,153 +264,102 @@ __device__ __forceinline__ int certified_level(const int* cnt, float step, float
 
 constexpr int kFilterThreads = 1024;
 constexpr int kFilterWaves = kFilterThreads / 64;
-constexpr int kFilterLoads = kFilterSlice / (kFilterThreads * 4);   // float4 loads per thread
-constexpr int kFilterNoGrid = 0x7fffffff;                           // record marker: |z| too large for the grid
+constexpr int kFilterWaveChunks = kFilterSliceChunks / kFilterWaves;   // groups per wavefront: 32
+static_assert(kFilterWaveChunks <= 64, "one ballot covers a wavefront's groups");
 
 struct FilterArgs {
-  const int32_t* seq_lens; const int32_t* n_sel; const float* zbuf;
-  int32_t* fhist; int32_t* fcount; float* frow; float* flist_u; int32_t* flist_pos;
-  int Hq, Hkv, grouped, P, n_slices_max, max_slots;
+  const int32_t* seq_lens; const int32_t* n_sel; const float* zbuf; const float* pmax;
+  int32_t* fcount; float* frow; float* flist_u; int32_t* flist_pos;
+  int Hq, Hkv, grouped, P, n_slices_max, max_slots, n_chunks_max;
   size_t zstride;
   float beta; int ibeta;
 };
 
 template <bool DENSE>
-__device__ __forceinline__ int filter_n_cand(const FilterArgs& A, int row) {
+__device__ __forceinline__ int filter_n_slots(const FilterArgs& A, int row) {
   const int lrow = A.grouped ? (row / A.Hq) * A.Hkv + (row % A.Hq) / (A.Hq / A.Hkv) : row;
   const int slots = DENSE ? (A.seq_lens[row / A.Hq] + A.P - 1) / A.P : A.n_sel[lrow];
-  return clampi(slots, 0, A.max_slots) * A.P;
-}
-
-// The slice's scores: wavefront w holds positions [t0 + 2048 w, +2048) as (load i, lane, component).
-__device__ __forceinline__ void filter_load(const float* zr, int t0, int n_cand, float4 (&v)[kFilterLoads]) {
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-#pragma unroll
-  for (int i = 0; i < kFilterLoads; ++i) {
-    const int pos = t0 + (w * kFilterLoads + i) * 256 + lane * 4;
-    v[i] = *reinterpret_cast<const float4*>(zr + min(pos, n_cand - 4));   // n_cand is a multiple of 4
-  }
-#pragma unroll
-  for (int i = 0; i < kFilterLoads; ++i) {
-    const int pos = t0 + (w * kFilterLoads + i) * 256 + lane * 4;
-    if (pos >= n_cand) v[i] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
-  }
+  return clampi(slots, 0, A.max_slots);
 }
 
 template <bool DENSE>
-__global__ __launch_bounds__(kFilterThreads) void filter_hist_kernel(const FilterArgs A) {
+__global__ __launch_bounds__(kFilterThreads) void filter_level_kernel(const FilterArgs A) {
   __shared__ float red[kFilterWaves];
-  __shared__ int whist[kFilterWaves][66];
-  const int row = blockIdx.y, slice = blockIdx.x, tid = threadIdx.x, w = tid >> 6;
-  const int n_cand = filter_n_cand<DENSE>(A, row);
-  const int t0 = slice * kFilterSlice;
-  if (t0 >= n_cand) return;
-  float4 v[kFilterLoads];
-  filter_load(A.zbuf + (size_t)row * A.zstride, t0, n_cand, v);
-  for (int i = tid; i < kFilterWaves * 66; i += kFilterThreads) (&whist[0][0])[i] = 0;
-  float m = -INFINITY;
+  __shared__ int hist[64];
+  __shared__ int flags[64];
+  const int row = blockIdx.x, tid = threadIdx.x;
+  const int gp = pmax_pages(A.P);
+  const int n_chunks = (filter_n_slots<DENSE>(A, row) + gp - 1) / gp;
+  const float* pm = A.pmax + (size_t)row * A.n_chunks_max;
+  float mx = -INFINITY;
+  for (int i0 = 0; i0 < n_chunks; i0 += kFilterThreads * 16) {
+    float v[16];
 #pragma unroll
-  for (int i = 0; i < kFilterLoads; ++i) m = fmaxf(m, fmaxf(fmaxf(v[i].x, v[i].y), fmaxf(v[i].z, v[i].w)));
-  const float smax = block_max(m, red);                     // barriers: the zeroed histogram is visible
-  int32_t* rec = A.fhist + ((size_t)row * A.n_slices_max + slice) * kFilterRec;
-  if (tid == 0) rec[1] = __float_as_int(smax);
-  if (!(fabsf(smax) < 100000.0f)) {                         // empty slice (-inf), or off the exact grid
-    if (tid == 0) rec[0] = smax > -INFINITY ? kFilterNoGrid : -kFilterNoGrid;
+    for (int k = 0; k < 16; ++k) v[k] = pm[min(i0 + k * kFilterThreads + tid, n_chunks - 1)];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) mx = fmaxf(mx, v[k]);        // clamped repeats do not change a maximum
+  }
+  if (tid < 64) hist[tid] = 0;
+  const float zmax = block_max(mx, red);
+  if (!(zmax > -INFINITY)) {                                  // empty row, or nothing but masked tokens
+    if (tid == 0) { A.frow[2 * row] = -INFINITY; A.frow[2 * row + 1] = 0.f; }
     return;
   }
-  const int top = (int)floorf(smax * 64.0f);
-  const float lowf = (float)(top - 64) * (1.0f / 64.0f);    // exact; every z > smax-1 is >= lowf
+  const float thr0 = zmax - 1.0f - 4e-6f * fmaxf(1.f, fabsf(zmax));
+  const float width = zmax - thr0, step = width * (1.0f / 64.0f), inv_step = 64.0f / width;
+  for (int i0 = 0; i0 < n_chunks; i0 += kFilterThreads * 16) {
+    float v[16];
 #pragma unroll
-  for (int i = 0; i < kFilterLoads; ++i) {
-    const float zz[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+    for (int k = 0; k < 16; ++k) v[k] = pm[min(i0 + k * kFilterThreads + tid, n_chunks - 1)];
 #pragma unroll
-    for (int c = 0; c < 4; ++c)
-      if (zz[c] >= lowf) atomicAdd(&whist[w][min(64, (int)floorf(zz[c] * 64.0f) - (top - 64))], 1);
+    for (int k = 0; k < 16; ++k)
+      if (i0 + k * kFilterThreads + tid < n_chunks && v[k] > thr0)
+        atomicAdd(&hist[min(63, (int)((v[k] - thr0) * inv_step))], 1);
   }
   __syncthreads();
-  if (tid < 65) {
-    int c = 0;
-    for (int i = 0; i < kFilterWaves; ++i) c += whist[i][tid];
-    rec[2 + tid] = c;
-  }
-  if (tid == 0) rec[0] = top;
+  const int level = certified_level<64>(hist, step, A.beta, A.ibeta, flags);
+  if (tid == 0) { A.frow[2 * row] = zmax; A.frow[2 * row + 1] = thr0 + (float)level * step; }
 }
 
-// One workgroup per row: merge the slice histograms, certify the bound.
-constexpr int kLevelThreads = 1024;
-template <bool DENSE>
-__global__ __launch_bounds__(kLevelThreads) void filter_level_kernel(const FilterArgs A) {
-  __shared__ float red[kLevelThreads / 64];
-  __shared__ int redi[kLevelThreads / 64];
-  __shared__ int mh[66];
-  __shared__ int flags[64];
-  const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int n_cand = filter_n_cand<DENSE>(A, row);
-  const int n_slices = (n_cand + kFilterSlice - 1) / kFilterSlice;
-  const int32_t* recs = A.fhist + (size_t)row * A.n_slices_max * kFilterRec;
-  // row maximum, top grid cell of the row, and whether every slice is on the grid
-  float zm = -INFINITY; int tp = -kFilterNoGrid;
-  for (int s = tid; s < n_slices; s += kLevelThreads) {
-    tp = max(tp, recs[(size_t)s * kFilterRec]);
-    zm = fmaxf(zm, __int_as_float(recs[(size_t)s * kFilterRec + 1]));
-  }
-  const float zmax = block_max(zm, red);
+// Scores of up to four groups of a wavefront at once (lane = token of the group), -inf where masked.
+__device__ __forceinline__ void filter_group_scores(const float* zr, const int (&chunk)[4], int n_valid, int ct,
+                                                    int n_cand, float (&z)[4]) {
+  const int lane = threadIdx.x & 63;
 #pragma unroll
-  for (int d = 1; d < 64; d <<= 1) tp = max(tp, __shfl_xor(tp, d));
-  if (lane == 0) redi[w] = tp;
-  if (tid < 66) mh[tid] = 0;
-  __syncthreads();
-  int gtop = redi[0];
-  for (int i = 1; i < kLevelThreads / 64; ++i) gtop = max(gtop, redi[i]);
-  float thr = zmax - 1.0f - 4e-6f * fmaxf(1.f, fabsf(zmax));
-  if (gtop != kFilterNoGrid && gtop != -kFilterNoGrid) {
-    // (slice, bin) pairs flattened over the threads, loads of a batch issued together
-    const int items = n_slices * 65;
-    for (int e0 = 0; e0 < items; e0 += kLevelThreads * 4) {
-      int tops[4], cnts[4];
+  for (int k = 0; k < 4; ++k) z[k] = zr[min(chunk[min(k, n_valid - 1)] * ct + min(lane, ct - 1), n_cand - 1)];
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const int e = min(e0 + k * kLevelThreads + tid, items - 1), sl = e / 65;
-        tops[k] = recs[(size_t)sl * kFilterRec];
-        cnts[k] = recs[(size_t)sl * kFilterRec + 2 + (e - sl * 65)];
-      }
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const int e = e0 + k * kLevelThreads + tid;
-        const int g = e % 65 - (gtop - tops[k]);                // shift >= 0
-        if (e < items && tops[k] != -kFilterNoGrid && cnts[k] != 0 && g >= 0) atomicAdd(&mh[g], cnts[k]);
-      }
-    }
-    __syncthreads();
-    const int level = certified_level<65>(mh, 1.0f / 64.0f, A.beta, A.ibeta, flags);   // grid [gtop-64, gtop]
-    if (level > 0) thr = (float)(gtop - 64 + level) * (1.0f / 64.0f);   // > zmax - 1
-    if (tid == 0) { A.frow[2 * row] = zmax; A.frow[2 * row + 1] = thr; }
-  } else if (tid == 0) {
-    A.frow[2 * row] = zmax; A.frow[2 * row + 1] = thr;
-  }
+  for (int k = 0; k < 4; ++k)
+    if (k >= n_valid || lane >= ct || chunk[k] * ct + lane >= n_cand) z[k] = -INFINITY;
 }
 
-// Ordered compaction of the slice's entries above the certified bound.  Survivors are rare (a few hundred
-// per row), so the scores are counted in one sweep and re-read (from cache) only by the wavefronts that
-// have something to write.
 template <bool DENSE>
 __global__ __launch_bounds__(kFilterThreads) void filter_compact_kernel(const FilterArgs A) {
   __shared__ int wtot[kFilterWaves];
   const int row = blockIdx.y, slice = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const uint64_t lt = (1ull << lane) - 1ull;
-  const int n_cand = filter_n_cand<DENSE>(A, row);
-  const int t0 = slice * kFilterSlice;
-  if (t0 >= n_cand) return;
-  const float* zr = A.zbuf + (size_t)row * A.zstride;
+  const int gp = pmax_pages(A.P), ct = gp * A.P;              // tokens per group (<= 64)
+  const int n_slots = filter_n_slots<DENSE>(A, row);
+  const int n_cand = n_slots * A.P, n_chunks = (n_slots + gp - 1) / gp;
+  const int c0 = slice * kFilterSliceChunks;
+  if (c0 >= n_chunks) return;
   const float zmax = A.frow[2 * row], thr = A.frow[2 * row + 1];
+  const float* zr = A.zbuf + (size_t)row * A.zstride;
+  const float* pm = A.pmax + (size_t)row * A.n_chunks_max;
+  // groups of this wavefront whose maximum can hold a survivor
+  const int cw = c0 + w * kFilterWaveChunks;
+  const float pmv = pm[min(cw + min(lane, kFilterWaveChunks - 1), n_chunks - 1)];
+  const uint64_t pass = __ballot(lane < kFilterWaveChunks && cw + lane < n_chunks && pmv > thr);
   int c = 0;
-  {
-    float4 v[kFilterLoads];
-    filter_load(zr, t0, n_cand, v);
+  for (uint64_t m = pass; m != 0;) {
+    int chunk[4], nv = 0;
 #pragma unroll
-    for (int i = 0; i < kFilterLoads; ++i) c += (v[i].x > thr) + (v[i].y > thr) + (v[i].z > thr) + (v[i].w > thr);
+    for (int k = 0; k < 4; ++k)
+      if (m != 0) { chunk[k] = cw + __builtin_ctzll(m); m &= m - 1; ++nv; } else chunk[k] = cw;
+    float z[4];
+    filter_group_scores(zr, chunk, nv, ct, n_cand, z);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) c += __popcll(__ballot(z[k] > thr));
   }
-  c = wave_sum_i(c);
   if (lane == 0) wtot[w] = c;
   __syncthreads();
   int off = 0, tot = 0;
@@ -418,24 +368,21 @@ __global__ __launch_bounds__(kFilterThreads) void filter_compact_kernel(const Fi
   if (c == 0) return;
   float* lu = A.flist_u + ((size_t)row * A.n_slices_max + slice) * kFilterSliceCap;
   int32_t* lp = A.flist_pos + ((size_t)row * A.n_slices_max + slice) * kFilterSliceCap;
-  for (int i = 0; i < kFilterLoads; ++i) {
-    const int pos = t0 + (w * kFilterLoads + i) * 256 + lane * 4;
-    float4 v = *reinterpret_cast<const float4*>(zr + min(pos, n_cand - 4));
-    if (pos >= n_cand) v = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
-    const float zz[4] = {v.x, v.y, v.z, v.w};
-    // order within the load: (lane, component)
-    const uint64_t m0 = __ballot(zz[0] > thr), m1 = __ballot(zz[1] > thr), m2 = __ballot(zz[2] > thr),
-                   m3 = __ballot(zz[3] > thr);
-    if ((m0 | m1 | m2 | m3) == 0) continue;
-    int o = off + __popcll(m0 & lt) + __popcll(m1 & lt) + __popcll(m2 & lt) + __popcll(m3 & lt);
+  for (uint64_t m = pass; m != 0;) {                          // second sweep (from cache): ordered write
+    int chunk[4], nv = 0;
 #pragma unroll
-    for (int cc = 0; cc < 4; ++cc) {
-      if (zz[cc] > thr) {
-        if (o < kFilterSliceCap) { lu[o] = zz[cc] - zmax; lp[o] = pos + cc; }
-        ++o;
-      }
+    for (int k = 0; k < 4; ++k)
+      if (m != 0) { chunk[k] = cw + __builtin_ctzll(m); m &= m - 1; ++nv; } else chunk[k] = cw;
+    float z[4];
+    filter_group_scores(zr, chunk, nv, ct, n_cand, z);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const bool in = z[k] > thr;
+      const uint64_t mk = __ballot(in);
+      const int o = off + __popcll(mk & lt);
+      if (in && o < kFilterSliceCap) { lu[o] = z[k] - zmax; lp[o] = chunk[k] * ct + lane; }
+      off += __popcll(mk);
     }
-    off += __popcll(m0) + __popcll(m1) + __popcll(m2) + __popcll(m3);
   }
 }
 
@@ -637,7 +584,7 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
   bool prefilled = false;
   if (A.fcount != nullptr) {
     // survivors of the filter passes: gather the per-slice lists, in slice order, if they fit
-    const int n_slices = (n_cand + kFilterSlice - 1) / kFilterSlice;
+    const int n_slices = (n_chunks + kFilterSliceChunks - 1) / kFilterSliceChunks;
     const int cs = tid < n_slices ? A.fcount[(size_t)bh * A.n_slices_max + tid] : 0;
     int inc = cs;
 #pragma unroll
@@ -872,15 +819,14 @@ size_t decode_ws_carve(const Dims& dm, bool dense, void* base, DecodeWorkspace* 
   const size_t rows = (size_t)dm.B * dm.Hq;
   const size_t zstride = slots * dm.P;
   const int n_chunks_max = (int)((slots + pmax_pages(dm.P) - 1) / pmax_pages(dm.P));
-  size_t n_slices = (zstride + kFilterSlice - 1) / kFilterSlice;
+  size_t n_slices = ((size_t)n_chunks_max + kFilterSliceChunks - 1) / kFilterSliceChunks;
   if (zstride < (size_t)kFilterMinTokens || n_slices > (size_t)kFilterMaxSlices) n_slices = 0;
   size_t off = 0;
   auto take = [&](size_t bytes) { const size_t o = off; off += (bytes + 255) & ~(size_t)255; return o; };
   const size_t o_z = take(rows * zstride * sizeof(float));
   const size_t o_pm = take(rows * n_chunks_max * sizeof(float));
-  size_t o_fh = 0, o_fc = 0, o_fr = 0, o_fu = 0, o_fp = 0;
+  size_t o_fc = 0, o_fr = 0, o_fu = 0, o_fp = 0;
   if (n_slices) {
-    o_fh = take(rows * n_slices * kFilterRec * sizeof(int32_t));
     o_fc = take(rows * n_slices * sizeof(int32_t));
     o_fr = take(rows * 2 * sizeof(float));
     o_fu = take(rows * n_slices * kFilterSliceCap * sizeof(float));
@@ -890,7 +836,6 @@ size_t decode_ws_carve(const Dims& dm, bool dense, void* base, DecodeWorkspace* 
     char* p = (char*)base;
     ws->z = (float*)(p + o_z); ws->pmax = (float*)(p + o_pm);
     ws->zstride = zstride; ws->n_chunks_max = n_chunks_max; ws->n_slices_max = (int)n_slices;
-    ws->fhist = n_slices ? (int32_t*)(p + o_fh) : nullptr;
     ws->fcount = n_slices ? (int32_t*)(p + o_fc) : nullptr;
     ws->frow = n_slices ? (float*)(p + o_fr) : nullptr;
     ws->flist_u = n_slices ? (float*)(p + o_fu) : nullptr;
@@ -909,8 +854,9 @@ void launch_decode(const Dims& dm, bool dense, bool grouped, const void* q, cons
   so.fcount = ws.fcount; so.frow = ws.frow; so.flist_u = ws.flist_u; so.flist_pos = ws.flist_pos;
   so.n_slices_max = ws.n_slices_max;
   so.grouped = grouped ? 1 : 0;
-  FilterArgs fa{c.seq_lens, n_sel, ws.z, ws.fhist, ws.fcount, ws.frow, ws.flist_u, ws.flist_pos,
-                dm.Hq, dm.Hkv, grouped ? 1 : 0, dm.P, ws.n_slices_max, dense ? dm.Mmax : dm.cap, ws.zstride, dm.beta, dm.ibeta};
+  FilterArgs fa{c.seq_lens, n_sel, ws.z, ws.pmax, ws.fcount, ws.frow, ws.flist_u, ws.flist_pos,
+                dm.Hq, dm.Hkv, grouped ? 1 : 0, dm.P, ws.n_slices_max, dense ? dm.Mmax : dm.cap, ws.n_chunks_max,
+                ws.zstride, dm.beta, dm.ibeta};
   dim3 fgrid(ws.n_slices_max, dm.B * dm.Hq), fblock(kFilterThreads);
   dim3 sgrid(dm.B * dm.Hq), sblock(kSolveThreads);
   const int slots_per_wg = kScoreWaves * kGroupsPerWave * pmax_pages(dm.P);
@@ -924,8 +870,7 @@ void launch_decode(const Dims& dm, bool dense, bool grouped, const void* q, cons
       default: launch_scores<8, kAllPages>(dm, grid, sa, st); break;
     }
     if (ws.fcount != nullptr) {
-      hipLaunchKernelGGL((filter_hist_kernel<true>), fgrid, fblock, 0, st, fa);
-      hipLaunchKernelGGL((filter_level_kernel<true>), dim3(dm.B * dm.Hq), dim3(kLevelThreads), 0, st, fa);
+      hipLaunchKernelGGL((filter_level_kernel<true>), dim3(dm.B * dm.Hq), fblock, 0, st, fa);
       hipLaunchKernelGGL((filter_compact_kernel<true>), fgrid, fblock, 0, st, fa);
     }
     if (dm.dtype == EKV_F32) hipLaunchKernelGGL((decode_solve_kernel<float, true>), sgrid, sblock, 0, st, so);
@@ -943,8 +888,7 @@ void launch_decode(const Dims& dm, bool dense, bool grouped, const void* q, cons
       launch_scores<1, kPerHead>(dm, grid, sa, st);
     }
     if (ws.fcount != nullptr) {
-      hipLaunchKernelGGL((filter_hist_kernel<false>), fgrid, fblock, 0, st, fa);
-      hipLaunchKernelGGL((filter_level_kernel<false>), dim3(dm.B * dm.Hq), dim3(kLevelThreads), 0, st, fa);
+      hipLaunchKernelGGL((filter_level_kernel<false>), dim3(dm.B * dm.Hq), fblock, 0, st, fa);
       hipLaunchKernelGGL((filter_compact_kernel<false>), fgrid, fblock, 0, st, fa);
     }
     if (dm.dtype == EKV_F32) hipLaunchKernelGGL((decode_solve_kernel<float, false>), sgrid, sblock, 0, st, so);

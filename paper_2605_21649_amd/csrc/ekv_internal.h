@@ -19,12 +19,11 @@ struct Dims {
 // page slots per entry of pmax (granularity of chunk skipping): 64 tokens when P divides 64
 __host__ __device__ inline int pmax_pages(int P) { return P >= 64 ? 1 : 64 / P; }
 
-// Long rows are pre-filtered by two multi-workgroup passes before the single-workgroup solve.
-constexpr int kFilterSlice = 32768;       // candidate positions per workgroup of the filter passes
+// Long rows are pre-filtered by multi-workgroup passes before the single-workgroup solve.
+constexpr int kFilterSliceChunks = 512;   // pmax entries (groups of <= 64 tokens) per workgroup of the filter
 constexpr int kFilterMinTokens = 65536;   // rows that can be at least this long take the filter passes
 constexpr int kFilterMaxSlices = 1024;    // ... unless they would need more slices than this
 constexpr int kFilterSliceCap = 4096;     // candidates kept per slice (the solve holds this many in LDS)
-constexpr int kFilterRec = 68;            // ints per slice record: top bin, max (float bits), 65 counts, pad
 
 struct DecodeWorkspace {
   float* z;        // [B*Hq][zstride] candidate scores z_j (or -inf where masked)
@@ -33,7 +32,6 @@ struct DecodeWorkspace {
   int n_chunks_max;
   // filter passes; all null / 0 when the rows are short
   int n_slices_max;
-  int32_t* fhist;      // [B*Hq][n_slices_max][kFilterRec]
   int32_t* fcount;     // [B*Hq][n_slices_max] candidates above the certified bound, per slice
   float* frow;         // [B*Hq][2]: zmax, certified lower bound of tau
   float* flist_u;      // [B*Hq][n_slices_max][kFilterSliceCap] z - zmax of those candidates, in order
