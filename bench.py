@@ -374,7 +374,13 @@ def main():
                                   extras=ekv.decode_extras(tau_ref=tau_f, kept_mass_ref=kept_mass, kept_supp_ref=kept_supp))
             torch.cuda.synchronize()
             Rerr = ((st0.out - out_f).norm(dim=-1) / out_f.norm(dim=-1)).mean()
+            R.k_pages = kp                                         # whole step at this budget
+            us_b, _, _ = R.run_timed(R.step_topk, side, 5, stages=False)
+            R.k_pages = k_pages
+            sel_b = B * Hq * kp * P
             extras[f"topk_{frac:.0%}"] = {
+                "pages_per_head": kp, "step_us": round(us_b, 2),
+                "effective_kv_GBps": round((bytes_meta + bytes_scores + sel_b * (d * e + 8)) / (us_b * 1e-6) / 1e9, 1),
                 "delta_mean": round(float((1 - kept_mass).mean()), 6),
                 "rho_mean": round(float((kept_supp.float() / supp_f.float()).mean()), 4),
                 "R_mean": round(float(Rerr), 6)}
