@@ -4,8 +4,8 @@
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C4] [--budget 0.02] [--variant topk]
 
 One step = one decode step of the top-k variant over a synthetic paged cache already resident in HBM:
-  a2 append the new token + refresh its page statistics -> a3 box page scoring -> a5 top-k selection
-  -> a7 sparse alpha-entmax decode (exact tau).
+  a2 append the new token + refresh its page statistics and a3 box page scoring (one launch:
+  ekv_append_score_pages) -> a5 top-k selection -> a7 sparse alpha-entmax decode (exact tau).
 The same run also times, outside the headline number, the Gaussian-selector step (a4 + a6 + a7), the
 group-shared top-k step, the dense full-cache entmax decode (a8), the softmax-over-selection baseline (a9),
 the box-threshold refinement, the bulk statistics build (a1), and the same steps on the 128K-token batch
@@ -32,9 +32,10 @@ HBM_PEAK_GBS = 8000.0
 # size; see profiles/bench_topk_step_C4.md): 256.10 MiB read + 8.00 MiB written
 PMC_TRAFFIC_SCORE_PAGES_C4 = int((256.10 + 8.00) * 1024 * 1024)
 
-STAGE_NAMES = {"topk": ["append", "score_box", "select_topk", "decode_sparse"],
-               "gauss": ["append", "score_gauss", "select_gauss", "decode_sparse"],
-               "group": ["append", "score_group_max", "select_topk", "decode_sparse_group"],
+# the append runs inside the scoring launch (ekv_append_score_pages) unless --two-launch-append is given
+STAGE_NAMES = {"topk": ["append_own_launch", "append+score_box", "select_topk", "decode_sparse"],
+               "gauss": ["append_own_launch", "append+score_gauss", "select_gauss", "decode_sparse"],
+               "group": ["append_own_launch", "append+score_group_max", "select_topk", "decode_sparse_group"],
                "dense": ["-", "-", "-", "decode_full"]}
 
 
@@ -52,6 +53,8 @@ def parse():
     ap.add_argument("--q-page", type=float, default=0.99)
     ap.add_argument("--cap-frac", type=float, default=0.04,
                     help="capacity of the page lists as a fraction of the pages (room for the adaptive selector)")
+    ap.add_argument("--two-launch-append", action="store_true",
+                    help="append with its own launch (ekv_stats_append) instead of inside the scoring launch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="time only the headline step")
     ap.add_argument("--cpu-units", type=int, default=16, help="(b,h) units the oracle is timed on")
@@ -64,11 +67,12 @@ class Runner:
     """Device state of one workload (several rotating copies) and its step functions.  Every step function
     takes a copy and, optionally, five HIP events to record between its stages."""
 
-    def __init__(self, w, budget, n_copies, q_page, dev, cap_frac=0.04):
+    def __init__(self, w, budget, n_copies, q_page, dev, cap_frac=0.04, fused_append=True):
         import torch
         from paper_2605_21649_amd import binding as ekv, synth
         from tests.helpers import DeviceState
         self.torch, self.ekv, self.w, self.dev, self.q_page = torch, ekv, w, dev, q_page
+        self.fused_append = fused_append
         B, Hkv, d, P, n = w.batch, w.n_kv_heads, w.head_dim, w.page_size, w.context
         M = w.pages_per_seq
         self.k_pages = max(1, int(math.ceil(budget * M)))
@@ -104,13 +108,24 @@ class Runner:
         return self.torch.cuda.Event(enable_timing=True)
 
     # ---- steps ---------------------------------------------------------------------------------
-    def step_topk(self, st, evs=None):
+    def append_and_score(self, st, evs, mode, box=None, mu=None, sigma=None):
+        """a2 + a3/a4: the new token is appended at n-1 (st.cache_prev holds the lengths before it) and the
+        pages are scored over n tokens -- in one launch, or as the two separate calls."""
         ekv = self.ekv
         if evs: evs[0].record()
-        ekv.ekv_stats_append(st.cfg, st.cache_prev, st.stats(), st.k_new, st.v_new)
-        if evs: evs[1].record()
-        ekv.ekv_score_pages(st.cfg, st.inp["q"], st.stats(), st.inp["seq_lens"], ekv.EKV_SCORE_BOX, st.box)
+        if self.fused_append:
+            if evs: evs[1].record()
+            ekv.ekv_append_score_pages(st.cfg, st.cache_prev, st.stats(), st.k_new, st.v_new, st.inp["q"], mode,
+                                       box, mu, sigma)
+        else:
+            ekv.ekv_stats_append(st.cfg, st.cache_prev, st.stats(), st.k_new, st.v_new)
+            if evs: evs[1].record()
+            ekv.ekv_score_pages(st.cfg, st.inp["q"], st.stats(), st.inp["seq_lens"], mode, box, mu, sigma)
         if evs: evs[2].record()
+
+    def step_topk(self, st, evs=None):
+        ekv = self.ekv
+        self.append_and_score(st, evs, ekv.EKV_SCORE_BOX, box=st.box)
         ekv.ekv_select_topk(st.cfg, st.box, st.inp["seq_lens"], self.k_pages, st.page_idx, st.n_sel, st.ws_topk)
         if evs: evs[3].record()
         ekv.ekv_decode_sparse(st.cfg, st.inp["q"], st.cache(), st.page_idx, st.n_sel, st.out, st.tau, st.supp,
@@ -119,12 +134,7 @@ class Runner:
 
     def step_gauss(self, st, evs=None):
         ekv = self.ekv
-        if evs: evs[0].record()
-        ekv.ekv_stats_append(st.cfg, st.cache_prev, st.stats(), st.k_new, st.v_new)
-        if evs: evs[1].record()
-        ekv.ekv_score_pages(st.cfg, st.inp["q"], st.stats(), st.inp["seq_lens"], ekv.EKV_SCORE_GAUSS, None, st.mu,
-                            st.sigma)
-        if evs: evs[2].record()
+        self.append_and_score(st, evs, ekv.EKV_SCORE_GAUSS, mu=st.mu, sigma=st.sigma)
         ekv.ekv_select_gauss(st.cfg, st.mu, st.sigma, st.inp["seq_lens"], self.q_page, 0.0, st.tau_hat, st.page_idx,
                              st.n_sel, st.overflow, st.ws_gauss)
         if evs: evs[3].record()
@@ -134,12 +144,7 @@ class Runner:
 
     def step_group(self, st, evs=None):
         ekv = self.ekv
-        if evs: evs[0].record()
-        ekv.ekv_stats_append(st.cfg, st.cache_prev, st.stats(), st.k_new, st.v_new)
-        if evs: evs[1].record()
-        ekv.ekv_score_pages(st.cfg, st.inp["q"], st.stats(), st.inp["seq_lens"],
-                            ekv.EKV_SCORE_BOX | ekv.EKV_SCORE_GROUP_MAX, self.gbox)
-        if evs: evs[2].record()
+        self.append_and_score(st, evs, ekv.EKV_SCORE_BOX | ekv.EKV_SCORE_GROUP_MAX, box=self.gbox)
         ekv.ekv_select_topk(self.gcfg, self.gbox, st.inp["seq_lens"], self.k_pages, self.g_idx, self.g_n, self.ws_gsel)
         if evs: evs[3].record()
         ekv.ekv_decode_sparse_group(st.cfg, st.inp["q"], st.cache(), self.g_idx, self.g_n, st.out, st.tau, st.supp,
@@ -239,7 +244,7 @@ def main():
     B, Hq, Hkv, d, P, n = w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.page_size, w.context
     M = w.pages_per_seq
     e = 2 if w.kv_dtype == "bf16" else 4
-    R = Runner(w, args.budget, args.copies, args.q_page, dev, args.cap_frac)
+    R = Runner(w, args.budget, args.copies, args.q_page, dev, args.cap_frac, fused_append=not args.two_launch_append)
     k_pages, copies = R.k_pages, R.copies
     stage_names = STAGE_NAMES[args.variant]
 
@@ -275,6 +280,8 @@ def main():
     t_append = R.back_to_back(lambda st: ekv.ekv_stats_append(st.cfg, st.cache_prev, st.stats(), st.k_new, st.v_new))
     t_score = R.back_to_back(lambda st: ekv.ekv_score_pages(st.cfg, st.inp["q"], st.stats(), st.inp["seq_lens"],
                                                             ekv.EKV_SCORE_BOX, st.box))
+    t_fused = R.back_to_back(lambda st: ekv.ekv_append_score_pages(st.cfg, st.cache_prev, st.stats(), st.k_new, st.v_new,
+                                                                   st.inp["q"], ekv.EKV_SCORE_BOX, st.box))
     t_topk = R.back_to_back(lambda st: ekv.ekv_select_topk(st.cfg, st.box, st.inp["seq_lens"], k_pages, st.page_idx,
                                                            st.n_sel, st.ws_topk))
     t_dec = R.back_to_back(lambda st: ekv.ekv_decode_sparse(st.cfg, st.inp["q"], st.cache(), st.page_idx, st.n_sel,
@@ -282,10 +289,12 @@ def main():
     kernel_alg_bytes = {
         "stats_append": None,
         "score_pages(box)": bytes_meta + B * Hq * M * 4,                 # metadata read + scores written
+        "append_score_pages(box)": bytes_meta + B * Hq * M * 4,
         "select_topk": B * Hq * M * 4,                                   # scores read (once, algorithmically)
         "decode_sparse": bytes_k + bytes_v + bytes_z,
     }
-    kernel_us = {"stats_append": t_append, "score_pages(box)": t_score, "select_topk": t_topk, "decode_sparse": t_dec}
+    kernel_us = {"stats_append": t_append, "score_pages(box)": t_score, "append_score_pages(box)": t_fused,
+                 "select_topk": t_topk, "decode_sparse": t_dec}
     kernels = {}
     for nm, us in kernel_us.items():
         nb = kernel_alg_bytes[nm]
@@ -318,7 +327,8 @@ def main():
         "data": "synthetic", "kv_dtype": w.kv_dtype,
         "config": {"workload": f"{w.name}: B{B} {Hq}q/{Hkv}kv d{d} ctx{n} page{P} {w.kv_dtype}, alpha={w.alpha}, "
                                f"top-k {k_pages} pages ({args.budget:.0%}) per query head",
-                   "variant": "entmaxkv-" + args.variant, "copies_rotated": args.copies},
+                   "variant": "entmaxkv-" + args.variant, "copies_rotated": args.copies,
+                   "append": "own launch" if args.two_launch_append else "inside the scoring launch"},
         "step_event_us": {"mean": round(float(whole.mean()), 2), "median": round(float(np.median(whole)), 2),
                           "p10": round(float(np.percentile(whole, 10)), 2),
                           "p90": round(float(np.percentile(whole, 90)), 2)},
@@ -351,6 +361,11 @@ def main():
         extras["plain_copy_GBps_measured"] = round(2 * src.numel() * 4 / (a.elapsed_time(b) * 1e-3 / 5) / 1e9, 1)
         del src, dst
         side = max(10, args.steps // 4)
+        if R.fused_append:                                     # the same step with the append as its own launch
+            R.fused_append = False
+            us_2l, _, _ = R.run_timed(R.step_topk, side, 5, stages=False)
+            R.fused_append = True
+            extras["topk_step_two_launch_append_us"] = round(us_2l, 2)
         us_g, stage_g, _ = R.run_timed(R.step_gauss, side, 5)
         extras["gauss_step_us"] = round(us_g, 2)
         extras["gauss_stage_us"] = {nm: round(float(v), 2) for nm, v in zip(STAGE_NAMES["gauss"], stage_g.mean(axis=0))}
@@ -403,9 +418,14 @@ def main():
             seq.fill_(n - T)
             for t in range(T):
                 st = copies[t % len(copies)]
-                ekv.ekv_stats_append(st.cfg, st.cache(), st.stats(), k_news[t], v_news[t])
-                seq.add_(1)
-                ekv.ekv_score_pages(st.cfg, st.inp["q"], st.stats(), seq, ekv.EKV_SCORE_BOX, st.box)
+                if R.fused_append:
+                    ekv.ekv_append_score_pages(st.cfg, st.cache(), st.stats(), k_news[t], v_news[t], st.inp["q"],
+                                               ekv.EKV_SCORE_BOX, st.box)
+                    seq.add_(1)
+                else:
+                    ekv.ekv_stats_append(st.cfg, st.cache(), st.stats(), k_news[t], v_news[t])
+                    seq.add_(1)
+                    ekv.ekv_score_pages(st.cfg, st.inp["q"], st.stats(), seq, ekv.EKV_SCORE_BOX, st.box)
                 ekv.ekv_select_topk(st.cfg, st.box, seq, k_pages, st.page_idx, st.n_sel, st.ws_topk)
                 ekv.ekv_decode_sparse(st.cfg, st.inp["q"], st.cache(), st.page_idx, st.n_sel, st.out, st.tau,
                                       st.supp, st.ws_sparse)
@@ -484,7 +504,7 @@ def main():
         R.release()
         del R, copies, st0
         w3 = synth.WORKLOADS["C3"]
-        R3 = Runner(w3, args.budget, args.copies, args.q_page, dev, args.cap_frac)
+        R3 = Runner(w3, args.budget, args.copies, args.q_page, dev, args.cap_frac, fused_append=not args.two_launch_append)
         side = max(10, args.steps // 4)
         row = {"workload": f"{w3.name}: B{w3.batch} {w3.n_q_heads}q/{w3.n_kv_heads}kv ctx{w3.context} page{w3.page_size} "
                            f"{w3.kv_dtype}, top-k {R3.k_pages} pages ({args.budget:.0%})"}
@@ -502,7 +522,8 @@ def main():
         del R3
         # at 128K the adaptive selector keeps 5-16 % of the pages of this data: its lists get that room
         # (the list capacity also sizes the decode's launch grid, so the top-k rows above keep the small one)
-        R3g = Runner(w3, args.budget, args.copies, args.q_page, dev, cap_frac=0.25)
+        R3g = Runner(w3, args.budget, args.copies, args.q_page, dev, cap_frac=0.25,
+                     fused_append=not args.two_launch_append)
         us3g, stage3g, _ = R3g.run_timed(R3g.step_gauss, side, 5)
         row["gauss_step_us"] = round(us3g, 2)
         row["gauss_stage_us"] = {nm: round(float(v), 2) for nm, v in zip(STAGE_NAMES["gauss"], stage3g.mean(axis=0))}

@@ -132,6 +132,18 @@ ekv_status ekv_score_pages(const ekv_config* cfg, const void* q, const ekv_stats
                            const int32_t* seq_lens, int32_t mode, float* box, float* mu,
                            float* sigma, void* stream);
 
+/* a2 + a3/a4 in one launch: ekv_stats_append followed by ekv_score_pages over the lengths n_b + 1, bit for bit,
+ * without the separate small launch of the append on the critical path of a decode step: the workgroup of
+ * the scoring kernel whose tile holds the new token's page appends it first (cache slot written, that page's
+ * statistics recomputed), every other workgroup starts scoring at once.  cache->seq_lens holds the lengths
+ * BEFORE the append (slot n_b is written) and is not modified; the scores cover n_b + 1 tokens, so add 1 to
+ * every entry before the selection and decode calls.  Arguments as in the two calls it replaces; both
+ * statistics arrays must be given whatever `mode` scores. */
+ekv_status ekv_append_score_pages(const ekv_config* cfg, const ekv_cache_view* cache,
+                                  const ekv_stats_view* stats, const void* k_new, const void* v_new,
+                                  const void* q, int32_t mode, float* box, float* mu, float* sigma,
+                                  void* stream);
+
 /* a5 -- fixed-budget top-k page selection (Sec. 4.3).  For each (b,h): the min(k_pages, M_b) pages
  * of largest box score among p < M_b; equal scores are resolved towards the lower page index.
  * page_idx int32 [B][Hq][cap] receives the logical page indices in ASCENDING order, n_sel int32

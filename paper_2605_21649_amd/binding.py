@@ -20,11 +20,12 @@ EKV_OP_SELECT_TOPK, EKV_OP_SELECT_GAUSS, EKV_OP_DECODE_SPARSE, EKV_OP_DECODE_FUL
     EKV_OP_DECODE_SPARSE_SOFTMAX, EKV_OP_SELECT_BOX_THRESHOLD = range(6)
 
 # every symbol the header declares
-EXPORTS = ["ekv_stats_build", "ekv_stats_append", "ekv_score_pages", "ekv_select_topk", "ekv_select_gauss",
+EXPORTS = ["ekv_stats_build", "ekv_stats_append", "ekv_score_pages", "ekv_append_score_pages", "ekv_select_topk",
+           "ekv_select_gauss",
            "ekv_select_box_threshold", "ekv_decode_sparse", "ekv_decode_sparse_group", "ekv_decode_full",
            "ekv_decode_sparse_softmax", "ekv_workspace_bytes", "ekv_status_string", "ekv_last_hip_error",
            "ekv_version"]
-_STATUS_CALLS = EXPORTS[:11]      # entry points that return ekv_status
+_STATUS_CALLS = EXPORTS[:12]      # entry points that return ekv_status
 
 
 class ekv_config(ctypes.Structure):
@@ -68,6 +69,8 @@ def load_library():
                                      c_void_p]
     lib.ekv_score_pages.argtypes = [P(ekv_config), c_void_p, P(ekv_stats_view), c_void_p, c_int32, c_void_p,
                                     c_void_p, c_void_p, c_void_p]
+    lib.ekv_append_score_pages.argtypes = [P(ekv_config), P(ekv_cache_view), P(ekv_stats_view), c_void_p, c_void_p,
+                                           c_void_p, c_int32, c_void_p, c_void_p, c_void_p, c_void_p]
     lib.ekv_select_topk.argtypes = [P(ekv_config), c_void_p, c_void_p, c_int32, c_void_p, c_void_p, c_void_p,
                                     c_size_t, c_void_p]
     lib.ekv_select_gauss.argtypes = [P(ekv_config), c_void_p, c_void_p, c_void_p, c_float, c_float, c_void_p,
@@ -150,6 +153,11 @@ def ekv_stats_append(cfg, cache, stats, k_new, v_new=None, stream=None):
 def ekv_score_pages(cfg, q, stats, seq_lens, mode, box=None, mu=None, sigma=None, stream=None):
     _check(load_library().ekv_score_pages(byref(cfg), _ptr(q), byref(stats), _ptr(seq_lens), mode, _ptr(box),
                                           _ptr(mu), _ptr(sigma), _stream(stream)))
+
+
+def ekv_append_score_pages(cfg, cache, stats, k_new, v_new, q, mode, box=None, mu=None, sigma=None, stream=None):
+    _check(load_library().ekv_append_score_pages(byref(cfg), byref(cache), byref(stats), _ptr(k_new), _ptr(v_new),
+                                                 _ptr(q), mode, _ptr(box), _ptr(mu), _ptr(sigma), _stream(stream)))
 
 
 def ekv_select_topk(cfg, box, seq_lens, k_pages, page_idx, n_sel, workspace, stream=None):

@@ -151,6 +151,23 @@ ekv_status ekv_score_pages(const ekv_config* cfg, const void* q, const ekv_stats
   return finish((hipStream_t)stream);
 }
 
+ekv_status ekv_append_score_pages(const ekv_config* cfg, const ekv_cache_view* cache, const ekv_stats_view* stats,
+                                  const void* k_new, const void* v_new, const void* q, int32_t mode, float* box,
+                                  float* mu, float* sigma, void* stream) {
+  Dims dm;
+  ekv_status s = make_dims(cfg, dm);
+  if (s != EKV_OK) return s;
+  if ((s = check_cache(cache, false)) != EKV_OK) return s;
+  if (v_new != nullptr && !ok_ptr(cache->v_pool)) return EKV_ERR_INVALID_ARG;
+  const bool ok_mode = (mode >= 1 && mode <= 3) || mode == (EKV_SCORE_BOX | EKV_SCORE_GROUP_MAX);
+  if (!ok_mode || !ok_ptr(q) || !ok_ptr(k_new) || (v_new != nullptr && !ok_ptr(v_new))) return EKV_ERR_INVALID_ARG;
+  if (stats == nullptr || !ok_ptr(stats->box) || !ok_ptr(stats->gauss)) return EKV_ERR_INVALID_ARG;
+  if ((mode & EKV_SCORE_BOX) && !ok_ptr4(box)) return EKV_ERR_INVALID_ARG;
+  if ((mode & EKV_SCORE_GAUSS) && (!ok_ptr4(mu) || !ok_ptr4(sigma))) return EKV_ERR_INVALID_ARG;
+  launch_score_pages(dm, q, *stats, cache->seq_lens, mode, box, mu, sigma, (hipStream_t)stream, cache, k_new, v_new);
+  return finish((hipStream_t)stream);
+}
+
 ekv_status ekv_select_topk(const ekv_config* cfg, const float* box, const int32_t* seq_lens, int32_t k_pages,
                            int32_t* page_idx, int32_t* n_sel, void* workspace, size_t workspace_bytes,
                            void* stream) {

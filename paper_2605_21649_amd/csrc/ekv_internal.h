@@ -44,8 +44,11 @@ size_t decode_ws_carve(const Dims& dm, bool dense, void* base, DecodeWorkspace* 
 void launch_stats_build(const Dims& dm, const ekv_cache_view& c, const ekv_stats_view& s, hipStream_t st);
 void launch_stats_append(const Dims& dm, const ekv_cache_view& c, const ekv_stats_view& s,
                          const void* k_new, const void* v_new, hipStream_t st);
+// append_to != nullptr: fused append of (k_new, v_new) at slot seq_lens[b] before scoring with seq_lens[b] + 1
 void launch_score_pages(const Dims& dm, const void* q, const ekv_stats_view& s, const int32_t* seq_lens,
-                        int mode, float* box, float* mu, float* sigma, hipStream_t st);
+                        int mode, float* box, float* mu, float* sigma, hipStream_t st,
+                        const ekv_cache_view* append_to = nullptr, const void* k_new = nullptr,
+                        const void* v_new = nullptr);
 void launch_select_topk(const Dims& dm, const float* box, const int32_t* seq_lens, int k_pages,
                         int32_t* page_idx, int32_t* n_sel, void* ws, hipStream_t st);
 void launch_select_gauss(const Dims& dm, const float* mu, const float* sigma, const int32_t* seq_lens,

@@ -14,10 +14,47 @@
 // written (one list of pages per KV head, shared by its query heads).
 #include "ekv_device.h"
 #include "ekv_internal.h"
+#include "ekv_stats.h"
 
 namespace ekv {
 
 constexpr int kScoreTile = 64;    // pages per workgroup: 4 wavefronts x 16 pages
+
+// Fused append: the workgroup whose tile holds the page of the new token first appends it (one wavefront:
+// cache slot written, page statistics recomputed), then every workgroup scores with the length n_b + 1.
+// mode 0: plain scoring; 1: append, then score; 2: score with n_b + 1 only (a second launch of the call).
+struct ScoreAppend {
+  void* k_pool; void* v_pool; const int32_t* block_table; const void* k_new; const void* v_new;
+  void* box_stats; void* gauss_stats;
+  int n_phys, mode;
+};
+
+// Returns the sequence length the kernel scores with.
+template <typename T>
+__device__ __forceinline__ int fused_append(const ScoreAppend& ap, int n, int b, int h, int tile0, int Hkv, int P,
+                                            int Mmax) {
+  if (ap.mode == 0) return n;
+  const int p_new = n / P;
+  if (n < 0 || p_new >= Mmax) return n;             // no room: nothing is appended
+  if (ap.mode == 1 && p_new >= tile0 && p_new < tile0 + kScoreTile) {       // workgroup-uniform
+    if (threadIdx.x < 64) {
+      if (P == 16)                                    // same instantiations as the append kernel
+        append_token_wave<T, 16>((T*)ap.k_pool, (T*)ap.v_pool, ap.block_table, n, (const T*)ap.k_new,
+                                 (const T*)ap.v_new, (T*)ap.box_stats, (T*)ap.gauss_stats, b, h, Hkv, P, Mmax, ap.n_phys);
+      else if (P == 32)
+        append_token_wave<T, 32>((T*)ap.k_pool, (T*)ap.v_pool, ap.block_table, n, (const T*)ap.k_new,
+                                 (const T*)ap.v_new, (T*)ap.box_stats, (T*)ap.gauss_stats, b, h, Hkv, P, Mmax, ap.n_phys);
+      else
+        append_token_wave<T, 0>((T*)ap.k_pool, (T*)ap.v_pool, ap.block_table, n, (const T*)ap.k_new,
+                                (const T*)ap.v_new, (T*)ap.box_stats, (T*)ap.gauss_stats, b, h, Hkv, P, Mmax, ap.n_phys);
+    }
+    // the statistics rows written above are read below by the other wavefronts of this workgroup only (same
+    // compute unit): a workgroup-scope fence is enough; a device-scope one would write back the whole L2
+    __threadfence_block();
+    __syncthreads();
+  }
+  return n + 1;
+}
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
@@ -62,17 +99,29 @@ __global__ __launch_bounds__(256) void score_pages_mfma_kernel(const bf16_t* __r
                                                                float* __restrict__ out0,   // box or mu
                                                                float* __restrict__ out1,   // sigma (GAUSS)
                                                                int Hkv, int P, int Mmax, float scale,
-                                                               int group_max) {
+                                                               int group_max, const ScoreAppend ap) {
   constexpr int NSET = (G + 3) / 4;                 // column sets of 4 heads
   __shared__ float stage[2][G][kScoreTile];
   const int b = blockIdx.z, h = blockIdx.y;
-  const int tile0 = blockIdx.x * kScoreTile;
+  // with a fused append the tiles are taken from the end, so that the workgroup that appends (the last
+  // page's) is dispatched first and its extra latency hides behind the stream of the others
+  const int tile0 = (ap.mode == 1 ? gridDim.x - 1 - blockIdx.x : blockIdx.x) * kScoreTile;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int m = lane & 15, j = lane >> 4;           // MFMA row / column index, K group
   const int pg = m >> 2, kq = m & 3;                // as a row: page of the group, channel quarter
-  const int n = seq_lens[b];
+  const int n = fused_append<bf16_t>(ap, seq_lens[b], b, h, tile0, Hkv, P, Mmax);
   const int M = (n + P - 1) / P;
   const int Hq = Hkv * G;
+  if (tile0 >= M) {                                  // tile past the end of the sequence: no statistics are read
+    for (int idx = threadIdx.x; idx < (group_max ? 1 : G) * kScoreTile; idx += 256) {
+      const int g = idx / kScoreTile, p = tile0 + idx - g * kScoreTile;
+      if (p >= Mmax) continue;
+      const size_t o = group_max ? ((size_t)b * Hkv + h) * Mmax + p : ((size_t)b * Hq + h * G + g) * Mmax + p;
+      out0[o] = -INFINITY;
+      if (GAUSS) out1[o] = 0.f;
+    }
+    return;
+  }
 
   // B operands: column (g = m>>2, quarter kq) holds q[g][kq*32 + j*8 .. +8] (zero for g >= G)
   uint4 b0[NSET], b1[NSET], b2[NSET];
@@ -151,16 +200,27 @@ __global__ __launch_bounds__(256) void score_pages_f32_kernel(const float* __res
                                                               const float* __restrict__ stats,
                                                               const int32_t* __restrict__ seq_lens,
                                                               float* __restrict__ out0, float* __restrict__ out1,
-                                                              int Hkv, int P, int Mmax, float scale, int group_max) {
+                                                              int Hkv, int P, int Mmax, float scale, int group_max,
+                                                              const ScoreAppend ap) {
   constexpr int kSteps = kScoreTile / 4 / 2;
   __shared__ float stage[2][G][kScoreTile];
   const int b = blockIdx.z, h = blockIdx.y;
-  const int tile0 = blockIdx.x * kScoreTile;
+  const int tile0 = (ap.mode == 1 ? gridDim.x - 1 - blockIdx.x : blockIdx.x) * kScoreTile;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int half = lane >> 5, which = (lane >> 4) & 1, c = lane & 15;
-  const int n = seq_lens[b];
+  const int n = fused_append<float>(ap, seq_lens[b], b, h, tile0, Hkv, P, Mmax);
   const int M = (n + P - 1) / P;
   const int Hq = Hkv * G;
+  if (tile0 >= M) {                                  // tile past the end of the sequence: no statistics are read
+    for (int idx = threadIdx.x; idx < (group_max ? 1 : G) * kScoreTile; idx += 256) {
+      const int g = idx / kScoreTile, p = tile0 + idx - g * kScoreTile;
+      if (p >= Mmax) continue;
+      const size_t o = group_max ? ((size_t)b * Hkv + h) * Mmax + p : ((size_t)b * Hq + h * G + g) * Mmax + p;
+      out0[o] = -INFINITY;
+      if (GAUSS) out1[o] = 0.f;
+    }
+    return;
+  }
   float coef[G][8];
 #pragma unroll
   for (int g = 0; g < G; ++g) {
@@ -218,33 +278,41 @@ __global__ __launch_bounds__(256) void score_pages_f32_kernel(const float* __res
 
 template <int G>
 static void launch_score_G(const Dims& dm, const void* q, const ekv_stats_view& s, const int32_t* seq_lens,
-                           int mode, float* box, float* mu, float* sigma, hipStream_t st) {
+                           int mode, float* box, float* mu, float* sigma, hipStream_t st, const ScoreAppend& ap0) {
   dim3 grid((dm.Mmax + kScoreTile - 1) / kScoreTile, dm.Hkv, dm.B), block(256);
   const int gmax = (mode & EKV_SCORE_GROUP_MAX) ? 1 : 0;
+  // with both score kinds requested the first launch appends, the second only scores with the new length
+  ScoreAppend ap_box = ap0, ap_gauss = ap0;
+  if (ap0.mode == 1 && (mode & EKV_SCORE_BOX)) ap_gauss.mode = 2;
   if (dm.dtype == EKV_BF16) {
     if (mode & EKV_SCORE_BOX)
       hipLaunchKernelGGL((score_pages_mfma_kernel<G, false>), grid, block, 0, st, (const bf16_t*)q,
-                         (const bf16_t*)s.box, seq_lens, box, (float*)nullptr, dm.Hkv, dm.P, dm.Mmax, dm.scale, gmax);
+                         (const bf16_t*)s.box, seq_lens, box, (float*)nullptr, dm.Hkv, dm.P, dm.Mmax, dm.scale, gmax, ap_box);
     if (mode & EKV_SCORE_GAUSS)
       hipLaunchKernelGGL((score_pages_mfma_kernel<G, true>), grid, block, 0, st, (const bf16_t*)q,
-                         (const bf16_t*)s.gauss, seq_lens, mu, sigma, dm.Hkv, dm.P, dm.Mmax, dm.scale, 0);
+                         (const bf16_t*)s.gauss, seq_lens, mu, sigma, dm.Hkv, dm.P, dm.Mmax, dm.scale, 0, ap_gauss);
   } else {
     if (mode & EKV_SCORE_BOX)
       hipLaunchKernelGGL((score_pages_f32_kernel<G, false>), grid, block, 0, st, (const float*)q,
-                         (const float*)s.box, seq_lens, box, (float*)nullptr, dm.Hkv, dm.P, dm.Mmax, dm.scale, gmax);
+                         (const float*)s.box, seq_lens, box, (float*)nullptr, dm.Hkv, dm.P, dm.Mmax, dm.scale, gmax, ap_box);
     if (mode & EKV_SCORE_GAUSS)
       hipLaunchKernelGGL((score_pages_f32_kernel<G, true>), grid, block, 0, st, (const float*)q,
-                         (const float*)s.gauss, seq_lens, mu, sigma, dm.Hkv, dm.P, dm.Mmax, dm.scale, 0);
+                         (const float*)s.gauss, seq_lens, mu, sigma, dm.Hkv, dm.P, dm.Mmax, dm.scale, 0, ap_gauss);
   }
 }
 
 void launch_score_pages(const Dims& dm, const void* q, const ekv_stats_view& s, const int32_t* seq_lens,
-                        int mode, float* box, float* mu, float* sigma, hipStream_t st) {
+                        int mode, float* box, float* mu, float* sigma, hipStream_t st, const ekv_cache_view* append_to,
+                        const void* k_new, const void* v_new) {
+  ScoreAppend ap{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0, 0};
+  if (append_to != nullptr)
+    ap = ScoreAppend{append_to->k_pool, append_to->v_pool, append_to->block_table, k_new, v_new, s.box, s.gauss,
+                     append_to->n_phys_pages, 1};
   switch (dm.G) {
-    case 1: launch_score_G<1>(dm, q, s, seq_lens, mode, box, mu, sigma, st); break;
-    case 2: launch_score_G<2>(dm, q, s, seq_lens, mode, box, mu, sigma, st); break;
-    case 4: launch_score_G<4>(dm, q, s, seq_lens, mode, box, mu, sigma, st); break;
-    default: launch_score_G<8>(dm, q, s, seq_lens, mode, box, mu, sigma, st); break;
+    case 1: launch_score_G<1>(dm, q, s, seq_lens, mode, box, mu, sigma, st, ap); break;
+    case 2: launch_score_G<2>(dm, q, s, seq_lens, mode, box, mu, sigma, st, ap); break;
+    case 4: launch_score_G<4>(dm, q, s, seq_lens, mode, box, mu, sigma, st, ap); break;
+    default: launch_score_G<8>(dm, q, s, seq_lens, mode, box, mu, sigma, st, ap); break;
   }
 }
 

@@ -136,7 +136,8 @@ def upload_oracle_stats(st, w, inp):
     return stats
 
 
-@pytest.mark.parametrize("w", ALL, ids=IDS)
+@pytest.mark.parametrize("w", ALL + [synth.C2.scaled(name="C2-short", context=8192, ragged=8192 - 1000)],
+                         ids=IDS + ["C2-short"])
 def test_score_pages(w):
     inp = get_inputs(w)
     st = DeviceState(w, inp)
@@ -896,3 +897,60 @@ def test_shape_matrix_whole_step_and_dense(w):
             check_decode_unit(w, st.out[b, hq].cpu().numpy(), float(st.tau[b, hq]), int(st.supp[b, hq]), None, sp)
         full = orc.entmax_attention(q, K, V, w.alpha, w.score_scale)
         check_decode_unit(w, out_f[b, hq].cpu().numpy(), float(tau_f[b, hq]), int(supp_f[b, hq]), None, full)
+
+
+# ---------------------------------------------------------------------------- fused append + score
+WSHORT = synth.C2.scaled(name="C2-short", context=8192, ragged=8192 - 1000)      # most score tiles lie past the end
+
+
+@pytest.mark.parametrize("w", [W1R, W2, W5, WP8, WSHORT], ids=["C1-ragged", "C2-8k", "C5-small", "C2-p8-g2", "C2-short"])
+@pytest.mark.parametrize("mode", ["box", "gauss", "both", "group"])
+def test_fused_append_score_equals_the_two_calls(w, mode):
+    """ekv_append_score_pages == ekv_stats_append then ekv_score_pages with the lengths + 1, bit for bit
+    (cache, statistics, scores), over steps that fill a page, cross into a new one and continue."""
+    inp = get_inputs(w)
+    P, B, Hkv = w.page_size, w.batch, w.n_kv_heads
+    n_final = int(inp["seq_lens"][0])
+    steps = P + 2
+    n0 = n_final - steps
+    k_log = torch.stack([torch.stack([synth.logical_kv(inp, w, b, h)[0] for h in range(Hkv)]) for b in range(B)])
+    v_log = torch.stack([torch.stack([synth.logical_kv(inp, w, b, h)[1] for h in range(Hkv)]) for b in range(B)])
+    flags = {"box": ekv.EKV_SCORE_BOX, "gauss": ekv.EKV_SCORE_GAUSS, "both": ekv.EKV_SCORE_BOTH,
+             "group": ekv.EKV_SCORE_BOX | ekv.EKV_SCORE_GROUP_MAX}[mode]
+    results = []
+    for fused in (False, True):
+        st = DeviceState(w, inp)
+        dev = st.box.device
+        box = torch.zeros(B, Hkv if mode == "group" else w.n_q_heads, st.Mmax, device=dev)
+        st.inp["seq_lens"].fill_(n0)
+        for b in range(B):                                   # wipe the slots that will be appended
+            for t in range(n0, n_final):
+                phys = int(inp["block_table"][b, t // P])
+                st.inp["k_pool"][phys, :, t % P] = 5.0
+                st.inp["v_pool"][phys, :, t % P] = 5.0
+        ekv.ekv_stats_build(st.cfg, st.cache(), st.stats())
+        snaps = []
+        for t in range(n0, n_final):
+            k_new = k_log[:, :, t].contiguous().to(dev); v_new = v_log[:, :, t].contiguous().to(dev)
+            args = dict(box=box if mode != "gauss" else None, mu=st.mu if mode in ("gauss", "both") else None,
+                        sigma=st.sigma if mode in ("gauss", "both") else None)
+            if fused:
+                ekv.ekv_append_score_pages(st.cfg, st.cache(), st.stats(), k_new, v_new, st.inp["q"], flags, **args)
+                st.inp["seq_lens"] += 1
+            else:
+                ekv.ekv_stats_append(st.cfg, st.cache(), st.stats(), k_new, v_new)
+                st.inp["seq_lens"] += 1
+                ekv.ekv_score_pages(st.cfg, st.inp["q"], st.stats(), st.inp["seq_lens"], flags, **args)
+            snaps.append((box.clone(), st.mu.clone(), st.sigma.clone()))
+        torch.cuda.synchronize()
+        results.append((st.inp["k_pool"].cpu(), st.inp["v_pool"].cpu(), st.box_stats.cpu(), st.gauss_stats.cpu(), snaps))
+    a, b_ = results
+    M = -(-n_final // P)
+    assert torch.equal(a[0], b_[0]) and torch.equal(a[1], b_[1])
+    assert torch.equal(a[0], inp["k_pool"]) and torch.equal(a[1], inp["v_pool"])
+    assert torch.equal(a[2][:, :, :M].view(torch.uint8), b_[2][:, :, :M].view(torch.uint8))
+    assert torch.equal(a[3][:, :, :M].view(torch.uint8), b_[3][:, :, :M].view(torch.uint8))
+    for (ba, ma, sa), (bb, mb, sb) in zip(a[4], b_[4]):
+        assert torch.equal(ba.view(torch.int32), bb.view(torch.int32))
+        assert torch.equal(ma.view(torch.int32), mb.view(torch.int32))
+        assert torch.equal(sa.view(torch.int32), sb.view(torch.int32))
