@@ -12,56 +12,84 @@ constexpr int kSmWaves = kSmThreads / 64;
 constexpr int kSmRec = kD + 2;          // floats per partial record: o[128], m, l
 constexpr int kSmPagesPerBlock = 8;     // page slots per workgroup (one partial record)
 
-template <typename T>
+// One wavefront handles kSmPagesPerBlock / kSmWaves pages; the K and V rows of a page are fetched as one
+// batch of unconditional loads (lane = (token mod 4, channel group)), the running maximum is updated once
+// per page.  Page and block-table indices are clamped into range; tokens past the sequence end are masked.
+template <typename T, int PT>   // PT = compile-time page size (16 or 32), 0 = runtime
 __global__ __launch_bounds__(kSmThreads) void softmax_partial_kernel(
     const T* __restrict__ q, const T* __restrict__ k_pool, const T* __restrict__ v_pool,
     const int32_t* __restrict__ block_table, const int32_t* __restrict__ seq_lens,
     const int32_t* __restrict__ page_idx, const int32_t* __restrict__ n_sel, float* __restrict__ part, int Hq,
-    int Hkv, int P, int Mmax, int cap, int n_chunks_max, float scale) {
+    int Hkv, int P_rt, int Mmax, int cap, int n_chunks_max, int n_phys, float scale) {
   __shared__ float s_o[kSmWaves][kD];
   __shared__ float s_m[kSmWaves], s_l[kSmWaves];
+  constexpr int kPagesPerWave = kSmPagesPerBlock / kSmWaves;
+  constexpr int SMAX = PT ? PT / 4 : 16;            // row steps per page (page size <= 64)
+  const int P = PT ? PT : P_rt;
   const int bh = blockIdx.y, chunk = blockIdx.x;
   const int b = bh / Hq, hkv = (bh % Hq) / (Hq / Hkv);
-  const int n = seq_lens[b];
-  const int n_slots = n_sel[bh];
+  const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int r = lane >> 4, c = lane & 15;
   const int slot0 = chunk * kSmPagesPerBlock;
-  if (slot0 >= n_slots) return;
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, r = lane >> 4, c = lane & 15;
+  const int wslot0 = slot0 + w * kPagesPerWave;
+  int lps[kPagesPerWave], physs[kPagesPerWave];
+#pragma unroll
+  for (int i = 0; i < kPagesPerWave; ++i)
+    lps[i] = min(max(page_idx[(size_t)bh * cap + min(wslot0 + i, cap - 1)], 0), Mmax - 1);
+  const int n = seq_lens[b];
+  const int n_slots = min(max(n_sel[bh], 0), cap);
+  if (slot0 >= n_slots) return;                      // workgroup-uniform
+#pragma unroll
+  for (int i = 0; i < kPagesPerWave; ++i) physs[i] = min(max(block_table[(size_t)b * Mmax + lps[i]], 0), n_phys - 1);
   float qv[8];
   load8<T>(q + (size_t)bh * kD + 8 * c, qv);
   float m_run = -INFINITY, l_run = 0.f, acc[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) acc[i] = 0.f;
-  constexpr int kPagesPerWave = kSmPagesPerBlock / kSmWaves;
+#pragma unroll
   for (int pw = 0; pw < kPagesPerWave; ++pw) {
-    const int slot = slot0 + w * kPagesPerWave + pw;
-    if (slot >= n_slots) break;
-    const int lp = page_idx[(size_t)bh * cap + slot];
-    const int phys = block_table[(size_t)b * Mmax + lp];
-    const size_t page_off = ((size_t)phys * Hkv + hkv) * P * kD + 8 * c;
-    for (int s = 0; s < P / 4; ++s) {
-      const int tok = 4 * s + r;
+    const bool slot_ok = wslot0 + pw < n_slots;      // wave-uniform
+    const size_t page_off = ((size_t)physs[pw] * Hkv + hkv) * P * kD + 8 * c;
+    const int steps = P / 4;
+    Raw8<T> kr[SMAX], vr[SMAX];
+#pragma unroll
+    for (int s = 0; s < SMAX; ++s) {
+      const int tok = 4 * min(s, steps - 1) + r;
+      load_raw8(k_pool + page_off + (size_t)tok * kD, kr[s]);
+      load_raw8(v_pool + page_off + (size_t)tok * kD, vr[s]);
+    }
+    float sc[SMAX];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int s = 0; s < SMAX; ++s) {
       float x[8];
-      load8<T>(k_pool + page_off + (size_t)tok * kD, x);
+      widen8(kr[s], x);
       float d = 0.f;
 #pragma unroll
       for (int i = 0; i < 8; ++i) d = fmaf(qv[i], x[i], d);
       d = row16_sum(d);
-      const bool valid = lp * P + tok < n;
-      const float sc = valid ? scale * d : -INFINITY;
-      float mx = fmaxf(sc, __shfl_xor(sc, 16));
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(m_run, mx);
-      if (m_new > -INFINITY) {
-        const float resc = __expf(m_run - m_new);          // exp(-inf) = 0 on the first valid step
-        const float p = valid ? __expf(sc - m_new) : 0.f;
-        l_run = l_run * resc + p;
-        float v[8];
-        load8<T>(v_pool + page_off + (size_t)tok * kD, v);
+      const bool valid = slot_ok && s < steps && lps[pw] * P + 4 * s + r < n;
+      sc[s] = valid ? scale * d : -INFINITY;
+      mx = fmaxf(mx, sc[s]);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(m_run, mx);
+    if (m_new > -INFINITY) {                          // wave-uniform; no loads inside
+      const float resc = __expf(m_run - m_new);      // exp(-inf) = 0 on the first valid page
+      l_run *= resc;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) acc[i] = fmaf(p, v[i], acc[i] * resc);
-        m_run = m_new;
+      for (int i = 0; i < 8; ++i) acc[i] *= resc;
+#pragma unroll
+      for (int s = 0; s < SMAX; ++s) {
+        const float p = __expf(sc[s] - m_new);       // 0 for masked tokens
+        l_run += p;
+        float v[8];
+        widen8(vr[s], v);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = fmaf(p, v[i], acc[i]);
       }
+      m_run = m_new;
     }
   }
   // rows of the wavefront share m_run; add their partial sums
@@ -88,23 +116,45 @@ __global__ __launch_bounds__(kSmThreads) void softmax_partial_kernel(
   }
 }
 
-__global__ __launch_bounds__(kD) void softmax_merge_kernel(const float* __restrict__ part,
-                                                           const int32_t* __restrict__ n_sel,
-                                                           float* __restrict__ out, float* __restrict__ lse,
-                                                           int n_chunks_max) {
-  const int bh = blockIdx.x, t = threadIdx.x;
-  const int n_chunks = (n_sel[bh] + kSmPagesPerBlock - 1) / kSmPagesPerBlock;
+// Merge of the per-chunk partials of one (b,h): 8 groups of 128 threads take the chunks round robin
+// (independent loads), then the groups are combined through LDS in index order.
+constexpr int kMergeGroups = 8;
+__global__ __launch_bounds__(kMergeGroups * kD) void softmax_merge_kernel(const float* __restrict__ part,
+                                                                          const int32_t* __restrict__ n_sel,
+                                                                          float* __restrict__ out,
+                                                                          float* __restrict__ lse,
+                                                                          int n_chunks_max, int cap) {
+  __shared__ float red[kMergeGroups * kD / 64];
+  __shared__ float g_o[kMergeGroups][kD], g_l[kMergeGroups];
+  const int bh = blockIdx.x, tid = threadIdx.x, t = tid & (kD - 1), grp = tid >> 7;
+  const int n_chunks = (min(max(n_sel[bh], 0), cap) + kSmPagesPerBlock - 1) / kSmPagesPerBlock;
   const float* rec0 = part + (size_t)bh * n_chunks_max * kSmRec;
-  float M = -INFINITY;
-  for (int i = 0; i < n_chunks; ++i) M = fmaxf(M, rec0[(size_t)i * kSmRec + kD]);
+  float mx = -INFINITY;
+  for (int i = tid; i < n_chunks; i += kMergeGroups * kD) mx = fmaxf(mx, rec0[(size_t)i * kSmRec + kD]);
+  const float M = block_max(mx, red);
   float L = 0.f, o = 0.f;
-  for (int i = 0; i < n_chunks; ++i) {
-    const float* rec = rec0 + (size_t)i * kSmRec;
-    const float f = rec[kD] > -INFINITY ? __expf(rec[kD] - M) : 0.f;
-    L += rec[kD + 1] * f; o += rec[t] * f;
+  for (int i0 = grp; i0 < n_chunks; i0 += 4 * kMergeGroups) {
+    float rm[4], rl[4], ro[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const float* rec = rec0 + (size_t)min(i0 + u * kMergeGroups, n_chunks - 1) * kSmRec;
+      rm[u] = rec[kD]; rl[u] = rec[kD + 1]; ro[u] = rec[t];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const float f = (i0 + u * kMergeGroups < n_chunks && rm[u] > -INFINITY) ? __expf(rm[u] - M) : 0.f;
+      L += rl[u] * f; o += ro[u] * f;
+    }
   }
-  out[(size_t)bh * kD + t] = L > 0.f ? o / L : 0.f;
-  if (t == 0) lse[bh] = L > 0.f ? M + __logf(L) : -INFINITY;
+  g_o[grp][t] = o;
+  if (t == 0) g_l[grp] = L;
+  __syncthreads();
+  if (tid < kD) {
+    float Ls = 0.f, os = 0.f;
+    for (int g = 0; g < kMergeGroups; ++g) { Ls += g_l[g]; os += g_o[g][tid]; }
+    out[(size_t)bh * kD + tid] = Ls > 0.f ? os / Ls : 0.f;
+    if (tid == 0) lse[bh] = Ls > 0.f ? M + __logf(Ls) : -INFINITY;
+  }
 }
 
 size_t softmax_ws_bytes(const Dims& dm) {
@@ -113,21 +163,28 @@ size_t softmax_ws_bytes(const Dims& dm) {
   return (b + 255) & ~(size_t)255;
 }
 
+template <typename T>
+static void launch_softmax_T(const Dims& dm, const void* q, const ekv_cache_view& c, const int32_t* page_idx,
+                             const int32_t* n_sel, float* ws, int n_chunks_max, hipStream_t st) {
+  dim3 grid(n_chunks_max, dm.B * dm.Hq), block(kSmThreads);
+#define EKV_SM(PT)                                                                                                  \
+  hipLaunchKernelGGL((softmax_partial_kernel<T, PT>), grid, block, 0, st, (const T*)q, (const T*)c.k_pool,          \
+                     (const T*)c.v_pool, c.block_table, c.seq_lens, page_idx, n_sel, ws, dm.Hq, dm.Hkv, dm.P,       \
+                     dm.Mmax, dm.cap, n_chunks_max, c.n_phys_pages, dm.scale)
+  if (dm.P == 16) EKV_SM(16);
+  else if (dm.P == 32) EKV_SM(32);
+  else EKV_SM(0);
+#undef EKV_SM
+}
+
 void launch_decode_sparse_softmax(const Dims& dm, const void* q, const ekv_cache_view& c,
                                   const int32_t* page_idx, const int32_t* n_sel, float* out, float* lse_sel,
                                   void* ws, hipStream_t st) {
   const int n_chunks_max = (dm.cap + kSmPagesPerBlock - 1) / kSmPagesPerBlock;
-  dim3 grid(n_chunks_max, dm.B * dm.Hq);
-  if (dm.dtype == EKV_F32)
-    hipLaunchKernelGGL(softmax_partial_kernel<float>, grid, dim3(kSmThreads), 0, st, (const float*)q,
-                       (const float*)c.k_pool, (const float*)c.v_pool, c.block_table, c.seq_lens, page_idx, n_sel,
-                       (float*)ws, dm.Hq, dm.Hkv, dm.P, dm.Mmax, dm.cap, n_chunks_max, dm.scale);
-  else
-    hipLaunchKernelGGL(softmax_partial_kernel<bf16_t>, grid, dim3(kSmThreads), 0, st, (const bf16_t*)q,
-                       (const bf16_t*)c.k_pool, (const bf16_t*)c.v_pool, c.block_table, c.seq_lens, page_idx,
-                       n_sel, (float*)ws, dm.Hq, dm.Hkv, dm.P, dm.Mmax, dm.cap, n_chunks_max, dm.scale);
-  hipLaunchKernelGGL(softmax_merge_kernel, dim3(dm.B * dm.Hq), dim3(kD), 0, st, (const float*)ws, n_sel, out,
-                     lse_sel, n_chunks_max);
+  if (dm.dtype == EKV_F32) launch_softmax_T<float>(dm, q, c, page_idx, n_sel, (float*)ws, n_chunks_max, st);
+  else launch_softmax_T<bf16_t>(dm, q, c, page_idx, n_sel, (float*)ws, n_chunks_max, st);
+  hipLaunchKernelGGL(softmax_merge_kernel, dim3(dm.B * dm.Hq), dim3(kMergeGroups * kD), 0, st, (const float*)ws, n_sel,
+                     out, lse_sel, n_chunks_max, dm.cap);
 }
 
 }  // namespace ekv

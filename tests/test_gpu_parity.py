@@ -422,7 +422,11 @@ def test_sparse_equals_full_when_support_is_covered():
 
 
 # ---------------------------------------------------------------------------- a9
-@pytest.mark.parametrize("w", [W1S, W5], ids=["C1-soft", "C5-small"])
+@pytest.mark.parametrize("w", [W1S, W5, synth.C2.scaled(name="C2-p64-g8", context=4096 + 64, ragged=21, page_size=64,
+                                                        n_q_heads=16, n_kv_heads=2),
+                               synth.C2.scaled(name="C2-p8-g2", context=2048 + 8, ragged=3, page_size=8, n_q_heads=4,
+                                               n_kv_heads=2)],
+                         ids=["C1-soft", "C5-small", "C2-p64-g8", "C2-p8-g2"])
 def test_decode_sparse_softmax(w):
     inp = get_inputs(w)
     k = topk_budget(w)
