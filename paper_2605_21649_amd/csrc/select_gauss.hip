@@ -206,6 +206,18 @@ __global__ __launch_bounds__(kGaussEvalThreads) void gauss_eval_kernel(const flo
   __shared__ float red[kGaussEvalThreads / 64][2];
   __shared__ float bc[4];
   const int bh = blockIdx.y, s = blockIdx.x, b = bh / Hq, tid = threadIdx.x;
+  // The slice of pages is fixed by Mmax alone, so its first batch of (mu, sigma) is in flight before the
+  // sequence length, the iteration state or the previous partials have arrived (rows have Mmax entries).
+  const int per = (Mmax + ws.S - 1) / ws.S;
+  const int p0 = s * per;
+  const float* mu_r = mu + (size_t)bh * Mmax;
+  const float* sg_r = sigma + (size_t)bh * Mmax;
+  float mv0[4], sv0[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int p = min(p0 + tid + j * kGaussEvalThreads, Mmax - 1);
+    mv0[j] = mu_r[p]; sv0[j] = sg_r[p];
+  }
   const int n = seq_lens[b];
   const int M = (n + P - 1) / P;
   const float cnt_last = (float)(n - (M - 1) * P);
@@ -239,18 +251,9 @@ __global__ __launch_bounds__(kGaussEvalThreads) void gauss_eval_kernel(const flo
   if (s == 0 && tid == 0) ws.state[(size_t)(k & 1) * BH + bh] = st;
   if (st.done) return;
 
-  const int per = (M + ws.S - 1) / ws.S;
-  const int p0 = s * per, p1 = min(p0 + per, M);
-  const float* mu_r = mu + (size_t)bh * Mmax;
-  const float* sg_r = sigma + (size_t)bh * Mmax;
+  const int p1 = min(p0 + per, M);
   float f = 0.f, d = 0.f;
-  for (int pb = p0 + tid; pb < p1; pb += 4 * kGaussEvalThreads) {     // 4 pages per lane and batch
-    float mv[4], sv[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int p = min(pb + j * kGaussEvalThreads, M - 1);           // clamped: loads stay unconditional
-      mv[j] = mu_r[p]; sv[j] = sg_r[p];
-    }
+  auto batch = [&](const float (&mv)[4], const float (&sv)[4], int pb) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int p = pb + j * kGaussEvalThreads;
@@ -260,6 +263,16 @@ __global__ __launch_bounds__(kGaussEvalThreads) void gauss_eval_kernel(const flo
         f += fp; d += dp;
       }
     }
+  };
+  batch(mv0, sv0, p0 + tid);                                           // the prefetched first batch
+  for (int pb = p0 + tid + 4 * kGaussEvalThreads; pb < p1; pb += 4 * kGaussEvalThreads) {
+    float mv[4], sv[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int p = min(pb + j * kGaussEvalThreads, M - 1);           // clamped: loads stay unconditional
+      mv[j] = mu_r[p]; sv[j] = sg_r[p];
+    }
+    batch(mv, sv, pb);
   }
   f = wave_sum(f); d = wave_sum(d);
   if ((tid & 63) == 0) { red[tid >> 6][0] = f; red[tid >> 6][1] = d; }
