@@ -62,6 +62,7 @@ constexpr int kTkSlice = kTkThreads * kTkItems;               // pages per slice
 constexpr int kTkSample = 1024;                               // pages the key range is estimated from
 constexpr int kTkMembers = 1024;                              // ranking list of the find kernel
 constexpr int kTkMaxSlices = 64;
+constexpr int kTkPrefix = 512;                                // best pages of a slice kept sorted by bin
 
 struct TopkHead {             // per (b,h) state passed between the launches
   uint32_t lo;                // bin(key) = key <= lo ? 0 : min(kBins-1, (key - lo) >> shift)
@@ -76,6 +77,8 @@ struct TopkWs {
   uint32_t* above;            // [BH][S][kBins]   pages of the slice in bins above this one
   int32_t* slice_off;         // [BH][S]          output offset of the slice
   int32_t* slice_eq;          // [BH][S]          pages with key == key_t in earlier slices
+  uint32_t* prefix_key;       // [BH][S][kTkPrefix]  the slice's pages of the highest bins, grouped by bin
+  int32_t* prefix_page;       //                     (descending; arbitrary order inside a bin)
   int S;
 };
 
@@ -102,6 +105,8 @@ __global__ __launch_bounds__(kTkThreads) void topk_hist_kernel(const float* __re
                                                                const int32_t* __restrict__ seq_lens, TopkWs ws,
                                                                int Hq, int P, int Mmax) {
   __shared__ uint32_t hist[kBins];
+  __shared__ uint32_t pre_key[kTkPrefix];
+  __shared__ int32_t pre_page[kTkPrefix];
   __shared__ uint32_t red[2][kTkWaves];
   __shared__ int wsum[kTkWaves];
   const int bh = blockIdx.y, slice = blockIdx.x, b = bh / Hq, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -166,6 +171,26 @@ __global__ __launch_bounds__(kTkThreads) void topk_hist_kernel(const float* __re
   uint32_t* out = ws.above + ((size_t)bh * ws.S + slice) * kBins + tid * BPT;
 #pragma unroll
   for (int i = 0; i < BPT; ++i) out[i] = ab[i];
+  // The kTkPrefix best pages of the slice, grouped by bin in descending bin order: a page of bin g goes to
+  // position above[g] + (arrival number inside the bin).  The find kernel then reads the members of the
+  // bin of the k-th key from these lists instead of scanning every score again.
+  __syncthreads();                                   // all reads of the counts are done
+#pragma unroll
+  for (int i = 0; i < BPT; ++i) hist[tid * BPT + i] = ab[i];
+  __syncthreads();
+  const int page0 = slice * kTkSlice + w * (kTkSlice / kTkWaves) + lane;
+#pragma unroll
+  for (int i = 0; i < kTkItems; ++i) {
+    if (vmask & (1u << i)) {
+      const uint32_t pos = atomicAdd(&hist[topk_bin(key[i], lo_w, shift)], 1u);
+      if (pos < (uint32_t)kTkPrefix) { pre_key[pos] = key[i]; pre_page[pos] = page0 + i * 64; }
+    }
+  }
+  __syncthreads();
+  const int n_valid = min(kTkSlice, M - slice * kTkSlice);
+  uint32_t* pk = ws.prefix_key + ((size_t)bh * ws.S + slice) * kTkPrefix;
+  int32_t* pp = ws.prefix_page + ((size_t)bh * ws.S + slice) * kTkPrefix;
+  for (int t = tid; t < min(kTkPrefix, n_valid); t += kTkThreads) { pk[t] = pre_key[t]; pp[t] = pre_page[t]; }
 }
 
 __global__ __launch_bounds__(kSelThreads) void topk_find_kernel(const float* __restrict__ box,
@@ -221,8 +246,41 @@ __global__ __launch_bounds__(kSelThreads) void topk_find_kernel(const float* __r
     topk_single<0>(box, seq_lens, k_pages, page_idx, n_sel, Hq, P, Mmax, cap, sh);
     return;
   }
-  // gather the members of bin b1: one scan of the scores in batches of 32 clamped loads per lane
-  const int per_wave = ((M + kSelWaves - 1) / kSelWaves + 63) & ~63;
+  // Members of bin b1.  In slice s they sit at positions [above_s[b1], above_s[b1 - 1]) of its prefix list
+  // (above_s[-1] := pages of the slice); if every slice's range ends inside its list, they are copied
+  // from there.  Otherwise (very large budgets) the scores are scanned.
+  __shared__ int s_lo[kTkMaxSlices], s_cnt_s[kTkMaxSlices], s_start[kTkMaxSlices + 1];
+  __shared__ int s_short;
+  if (tid == 0) s_short = 0;
+  __syncthreads();
+  if (tid < S) {
+    const uint32_t* ab = ws.above + ((size_t)bh * S + tid) * kBins;
+    const int lo_s = (int)ab[b1];
+    const int valid_s = max(0, min(kTkSlice, M - tid * kTkSlice));
+    const int hi_s = b1 == 0 ? valid_s : (int)ab[b1 - 1];
+    s_lo[tid] = lo_s; s_cnt_s[tid] = hi_s - lo_s;
+    if (hi_s > kTkPrefix && hi_s > lo_s) atomicOr(&s_short, 1);
+  }
+  __syncthreads();
+  const bool from_lists = s_short == 0;
+  if (from_lists) {
+    if (tid == 0) {
+      int run = 0;
+      for (int i = 0; i < S; ++i) { s_start[i] = run; run += s_cnt_s[i]; }
+      s_start[S] = run;
+      s_m = run;
+    }
+    __syncthreads();
+    for (int sl = tid >> 6; sl < S; sl += kSelWaves) {
+      const uint32_t* pk = ws.prefix_key + ((size_t)bh * S + sl) * kTkPrefix + s_lo[sl];
+      const int32_t* pp = ws.prefix_page + ((size_t)bh * S + sl) * kTkPrefix + s_lo[sl];
+      for (int e = tid & 63; e < s_cnt_s[sl]; e += 64) {
+        const int slot = s_start[sl] + e;
+        if (slot < kTkMembers) { mem_key[slot] = pk[e]; mem_page[slot] = pp[e]; }
+      }
+    }
+  }
+  const int per_wave = from_lists ? 0 : ((M + kSelWaves - 1) / kSelWaves + 63) & ~63;
   const int wbase = (tid >> 6) * per_wave + (tid & 63);
   for (int i0 = 0; i0 < per_wave; i0 += 32 * 64) {
     float raw[32];
@@ -347,7 +405,8 @@ static bool topk_sliced(const Dims& dm) { return dm.Mmax > 16 * kSelThreads && t
 size_t select_topk_ws_bytes(const Dims& dm) {
   if (!topk_sliced(dm)) return 256;
   const size_t BH = (size_t)dm.B * dm.Hq, S = topk_slices(dm);
-  size_t b = BH * sizeof(TopkHead) + BH * S * kBins * sizeof(uint32_t) + 2 * BH * S * sizeof(int32_t);
+  size_t b = BH * sizeof(TopkHead) + BH * S * kBins * sizeof(uint32_t) + 2 * BH * S * sizeof(int32_t) +
+             2 * BH * S * kTkPrefix * sizeof(int32_t);
   return (b + 255) & ~(size_t)255;
 }
 
@@ -371,6 +430,8 @@ void launch_select_topk(const Dims& dm, const float* box, const int32_t* seq_len
   ws.above = (uint32_t*)(ws.head + BH);
   ws.slice_off = (int32_t*)(ws.above + BH * ws.S * kBins);
   ws.slice_eq = ws.slice_off + BH * ws.S;
+  ws.prefix_key = (uint32_t*)(ws.slice_eq + BH * ws.S);
+  ws.prefix_page = (int32_t*)(ws.prefix_key + BH * ws.S * kTkPrefix);
   dim3 sgrid(ws.S, dm.B * dm.Hq), sblock(kTkThreads);
   hipLaunchKernelGGL(topk_hist_kernel, sgrid, sblock, 0, st, box, seq_lens, ws, dm.Hq, dm.P, dm.Mmax);
   hipLaunchKernelGGL(topk_find_kernel, grid, block, 0, st, box, seq_lens, k_pages, ws, page_idx, n_sel, dm.Hq, dm.P,
