@@ -554,12 +554,13 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
   float* out = A.out + (size_t)bh * kD;
 
   float zmax, thr_f = 0.f;
+  float mypm = -INFINITY;                   // this thread's group maximum (rows of at most 1024 groups)
   if (A.fcount != nullptr) {
     zmax = n_cand > 0 ? A.frow[2 * bh] : -INFINITY;
     thr_f = n_cand > 0 ? A.frow[2 * bh + 1] : 0.f;
   } else {
     float mx = -INFINITY;
-    for (int i = tid; i < n_chunks; i += kSolveThreads) mx = fmaxf(mx, pm[i]);
+    for (int i = tid; i < n_chunks; i += kSolveThreads) { mypm = pm[i]; mx = fmaxf(mx, mypm); }
     zmax = block_max(mx, sh.red1);
   }
   if (!(zmax > -INFINITY)) {                // no valid candidate at all
@@ -575,6 +576,23 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
   // boundary i), hence a tighter valid threshold: it becomes the starting point of the solve, and, if the
   // candidates did not fit in LDS, the threshold of one more compaction pass.
   float thr = A.fcount != nullptr ? thr_f : zmax - 1.0f - 4e-6f * fmaxf(1.f, fabsf(zmax));
+  // Short rows: the first round of scores is requested now, and while it is in flight the group maxima
+  // (one per thread) give a first certified bound of tau -- every group counted in a bin holds at least
+  // its maximum there -- so that far fewer candidates go through the compaction and the solve.
+  const bool pre = A.fcount == nullptr && n_chunks <= kSolveThreads;
+  float v0[kRoundLoads];
+  if (pre) {
+    const int seg0 = w * 64 * kRoundLoads;
+#pragma unroll
+    for (int i = 0; i < kRoundLoads; ++i) v0[i] = zr[min(seg0 + i * 64 + lane, n_cand - 1)];
+    const float step = (zmax - thr) * (1.0f / 64.0f), inv_step = 64.0f / (zmax - thr);
+    if (tid < 64) sh.hist[tid] = 0;
+    __syncthreads();
+    if (mypm > thr) atomicAdd(&sh.hist[min(63, (int)((mypm - thr) * inv_step))], 1);
+    __syncthreads();
+    thr += (float)certified_level<64>(sh.hist, step, beta, ibeta, sh.flags) * step;
+    __syncthreads();                                   // hist and flags are reused by the passes below
+  }
   float lo_u = thr - zmax;
   // chunk skipping pays only when there is a lot to skip (dense rows); short candidate lists are read whole,
   // which saves the dependent load of the chunk maxima in every round
@@ -623,12 +641,17 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
 #pragma unroll
       for (int i = 0; i < kRoundLoads; ++i) pmv[i] = can_skip ? pm[min(seg + i * 64, n_cand - 1) / chunk_tokens] : INFINITY;
       float v[kRoundLoads];
+      if (pre && pass == 0 && round0 == 0) {          // block-uniform: the scores requested above
 #pragma unroll
-      for (int i = 0; i < kRoundLoads; ++i) {
-        const int pos0 = seg + i * 64;
-        const float pmu = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(pmv[i])));
-        v[i] = -INFINITY;
-        if (pos0 < n_cand && (!can_skip || pmu > thr)) v[i] = zr[min(pos0 + lane, n_cand - 1)];
+        for (int i = 0; i < kRoundLoads; ++i) v[i] = v0[i];
+      } else {
+#pragma unroll
+        for (int i = 0; i < kRoundLoads; ++i) {
+          const int pos0 = seg + i * 64;
+          const float pmu = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(pmv[i])));
+          v[i] = -INFINITY;
+          if (pos0 < n_cand && (!can_skip || pmu > thr)) v[i] = zr[min(pos0 + lane, n_cand - 1)];
+        }
       }
 #pragma unroll
       for (int i = 0; i < kRoundLoads; ++i) v[i] = seg + i * 64 + lane < n_cand ? v[i] : -INFINITY;
