@@ -440,18 +440,17 @@ __device__ __forceinline__ void eval_mass(const Src& src, float tau, float beta,
 // the exact root for the current support when beta is 1 or 2 (closed forms), Newton otherwise; from a
 // right point a Newton step (F is convex, so it lands left of the root).  For beta in {1,2} the root is
 // accepted as exact once a closed-form step leaves the support count unchanged.
-template <typename Src>
-__device__ __forceinline__ float solve_tau(const Src& src, float lo_init, float beta, int ibeta, SolveShared& sh,
-                                           int& supp) {
+// `eval(tau, F, D, cnt)` evaluates the mass, its negated derivative and the support count at tau.
+template <typename Eval>
+__device__ __forceinline__ float solve_tau_core(Eval&& eval, float lo_init, int ibeta, int& supp) {
   float lo = lo_init, hi = 0.f;
   float tau = lo;
   int pending_cnt = -1;
-  int parity = 0, cnt = 0;
+  int cnt = 0;
   bool reeval = false;
   for (int it = 0; it < 64; ++it) {
     float F, D;
-    eval_mass(src, tau, beta, ibeta, sh, parity, F, D, cnt);
-    parity ^= 1;
+    eval(tau, F, D, cnt);
     if (pending_cnt >= 0 && cnt == pending_cnt) break;       // exact step kept the support: done
     if (fabsf(F - 1.0f) <= 4e-7f) break;                     // float32 resolution of F: tau is the root
     pending_cnt = -1;
@@ -478,10 +477,49 @@ __device__ __forceinline__ float solve_tau(const Src& src, float lo_init, float 
   }
   if (reeval) {                                              // tau moved after the last evaluation
     float F, D;
-    eval_mass(src, tau, beta, ibeta, sh, parity, F, D, cnt);
+    eval(tau, F, D, cnt);
   }
   supp = cnt;
   return tau;
+}
+
+// The whole workgroup iterates (one barrier per evaluation).
+template <typename Src>
+__device__ __forceinline__ float solve_tau(const Src& src, float lo_init, float beta, int ibeta, SolveShared& sh,
+                                           int& supp) {
+  int parity = 0;
+  return solve_tau_core([&](float tau, float& F, float& D, int& cnt) {
+    eval_mass(src, tau, beta, ibeta, sh, parity, F, D, cnt);
+    parity ^= 1;
+  }, lo_init, ibeta, supp);
+}
+
+// Short candidate lists (at most kWaveList entries, the usual case once the certified bound has been
+// applied): one wavefront holds them in registers and iterates without any barrier; the result is handed
+// to the other wavefronts through LDS.  Called by the whole workgroup.
+constexpr int kWaveList = 256;
+__device__ __forceinline__ float solve_tau_wave(const float* list_u, int n, float lo_init, float beta, int ibeta,
+                                                SolveShared& sh, int& supp) {
+  if (threadIdx.x < 64) {
+    const int lane = threadIdx.x;
+    float u[kWaveList / 64];
+#pragma unroll
+    for (int k = 0; k < kWaveList / 64; ++k) u[k] = lane + 64 * k < n ? list_u[lane + 64 * k] : -INFINITY;
+    int sp = 0;
+    const float tau = solve_tau_core([&](float t, float& F, float& D, int& cnt) {
+      float f = 0.f, d = 0.f; int c = 0;
+#pragma unroll
+      for (int k = 0; k < kWaveList / 64; ++k) {
+        const float x = u[k] - t;
+        if (x > 0.f) { f += pow_beta(x, beta, ibeta); d += pow_beta_m1(x, beta, ibeta); ++c; }
+      }
+      F = wave_sum(f); D = beta * wave_sum(d); cnt = wave_sum_i(c);
+    }, lo_init, ibeta, sp);
+    if (lane == 0) { sh.red1[0] = tau; sh.wcount[0][0] = sp; }
+  }
+  __syncthreads();
+  supp = sh.wcount[0][0];
+  return sh.red1[0];
 }
 
 struct SolveArgs {
@@ -576,22 +614,18 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
   // boundary i), hence a tighter valid threshold: it becomes the starting point of the solve, and, if the
   // candidates did not fit in LDS, the threshold of one more compaction pass.
   float thr = A.fcount != nullptr ? thr_f : zmax - 1.0f - 4e-6f * fmaxf(1.f, fabsf(zmax));
-  // Short rows: the first round of scores is requested now, and while it is in flight the group maxima
-  // (one per thread) give a first certified bound of tau -- every group counted in a bin holds at least
-  // its maximum there -- so that far fewer candidates go through the compaction and the solve.
+  // Short rows: the group maxima (one per thread) give a first certified bound of tau -- every group
+  // counted in a bin holds at least its maximum there -- and only the groups whose maximum exceeds it are
+  // read at all: their scores are fetched through an ordered list of group numbers, so that a row of any
+  // length up to 1024 groups normally takes one round of loads.
   const bool pre = A.fcount == nullptr && n_chunks <= kSolveThreads;
-  float v0[kRoundLoads];
   if (pre) {
-    const int seg0 = w * 64 * kRoundLoads;
-#pragma unroll
-    for (int i = 0; i < kRoundLoads; ++i) v0[i] = zr[min(seg0 + i * 64 + lane, n_cand - 1)];
     const float step = (zmax - thr) * (1.0f / 64.0f), inv_step = 64.0f / (zmax - thr);
     if (tid < 64) sh.hist[tid] = 0;
     __syncthreads();
     if (mypm > thr) atomicAdd(&sh.hist[min(63, (int)((mypm - thr) * inv_step))], 1);
     __syncthreads();
     thr += (float)certified_level<64>(sh.hist, step, beta, ibeta, sh.flags) * step;
-    __syncthreads();                                   // hist and flags are reused by the passes below
   }
   float lo_u = thr - zmax;
   // chunk skipping pays only when there is a lot to skip (dense rows); short candidate lists are read whole,
@@ -627,7 +661,64 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
     }
     __syncthreads();
   }
-  for (int pass = 0; pass < 3 && !prefilled; ++pass) {
+  if (pre) {
+    int* glist = reinterpret_cast<int*>(sh.list_row);        // free until the solve is done
+    const bool gp = mypm > thr;
+    const uint64_t gmk = __ballot(gp);
+    if (lane == 0) sh.wcount[parity][w] = __popcll(gmk);
+    __syncthreads();
+    int goff = 0, n_pass = 0;
+    for (int i = 0; i < kSolveWaves; ++i) { const int ci = sh.wcount[parity][i]; if (i < w) goff += ci; n_pass += ci; }
+    parity ^= 1;
+    if (gp) glist[goff + __popcll(gmk & lt)] = tid;
+    n_pass = __builtin_amdgcn_readfirstlane(n_pass);
+    __syncthreads();
+    // wavefront w of a round owns `per` consecutive list entries: (round, w, load, lane) is candidate order
+    for (int j0 = 0; j0 < n_pass; j0 += kSolveWaves * kRoundLoads) {
+      const int rem = min(n_pass - j0, kSolveWaves * kRoundLoads);
+      const int per = (rem + kSolveWaves - 1) / kSolveWaves;
+      const int jw = j0 + w * per, jend = j0 + rem;
+      float v[kRoundLoads]; int vpos[kRoundLoads];
+#pragma unroll
+      for (int i = 0; i < kRoundLoads; ++i) {
+        v[i] = -INFINITY; vpos[i] = 0;
+        if (i < per) {                                   // wave-uniform
+          const int g = glist[min(jw + i, n_pass - 1)];
+          vpos[i] = g * chunk_tokens + lane;
+          v[i] = zr[min(vpos[i], n_cand - 1)];
+        }
+      }
+      int c = 0;
+#pragma unroll
+      for (int i = 0; i < kRoundLoads; ++i) {
+        const bool ok = i < per && jw + i < jend && lane < chunk_tokens && vpos[i] < n_cand;
+        v[i] = ok ? v[i] : -INFINITY;
+        c += __popcll(__ballot(v[i] > thr));
+      }
+      if (lane == 0) sh.wcount[parity][w] = c;
+      __syncthreads();
+      int off = n_list, tot = 0;
+      for (int i = 0; i < kSolveWaves; ++i) { const int ci = sh.wcount[parity][i]; if (i < w) off += ci; tot += ci; }
+      n_list += tot;
+      parity ^= 1;
+      if (n_list > kListCap) in_lds = false;
+      if (in_lds) {
+#pragma unroll
+        for (int i = 0; i < kRoundLoads; ++i) {
+          const bool in = v[i] > thr;
+          const uint64_t mk = __ballot(in);
+          if (in) {
+            const int o = off + __popcll(mk & lt);
+            sh.list_u[o] = v[i] - zmax;
+            sh.list_pos[o] = vpos[i];
+          }
+          off += __popcll(mk);
+        }
+      }
+    }
+    if (in_lds) lo_u = fminf(thr - zmax, -1e-7f);
+  }
+  for (int pass = 0; pass < 3 && !prefilled && !pre; ++pass) {
     const float width = zmax - thr, slice = width * (1.0f / 64.0f), inv_slice = 64.0f / width;
     if (tid < 64) sh.hist[tid] = 0;
     n_list = 0; in_lds = true;
@@ -641,17 +732,12 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
 #pragma unroll
       for (int i = 0; i < kRoundLoads; ++i) pmv[i] = can_skip ? pm[min(seg + i * 64, n_cand - 1) / chunk_tokens] : INFINITY;
       float v[kRoundLoads];
-      if (pre && pass == 0 && round0 == 0) {          // block-uniform: the scores requested above
 #pragma unroll
-        for (int i = 0; i < kRoundLoads; ++i) v[i] = v0[i];
-      } else {
-#pragma unroll
-        for (int i = 0; i < kRoundLoads; ++i) {
-          const int pos0 = seg + i * 64;
-          const float pmu = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(pmv[i])));
-          v[i] = -INFINITY;
-          if (pos0 < n_cand && (!can_skip || pmu > thr)) v[i] = zr[min(pos0 + lane, n_cand - 1)];
-        }
+      for (int i = 0; i < kRoundLoads; ++i) {
+        const int pos0 = seg + i * 64;
+        const float pmu = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(pmv[i])));
+        v[i] = -INFINITY;
+        if (pos0 < n_cand && (!can_skip || pmu > thr)) v[i] = zr[min(pos0 + lane, n_cand - 1)];
       }
 #pragma unroll
       for (int i = 0; i < kRoundLoads; ++i) v[i] = seg + i * 64 + lane < n_cand ? v[i] : -INFINITY;
@@ -704,7 +790,8 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
       rowreg[k] = v_row_of<DENSE>(A, b, lrow, hkv, sh.list_pos[e]);
     }
     const ListSrc ls{sh.list_u, sh.list_pos, n_list};
-    tau_u = solve_tau(ls, lo_u, beta, ibeta, sh, supp);
+    if (n_list <= kWaveList) tau_u = solve_tau_wave(sh.list_u, n_list, lo_u, beta, ibeta, sh, supp);
+    else tau_u = solve_tau(ls, lo_u, beta, ibeta, sh, supp);
 #pragma unroll
     for (int k = 0; k < kListCap / kSolveThreads; ++k) {
       const int e = tid + k * kSolveThreads;
