@@ -1,0 +1,49 @@
+"""Device buffers of one workload: everything the entry points read and write, plus the ekv_config.
+
+Plumbing for the tests and the benchmark (torch allocates, the library computes); no part of the method."""
+import torch
+
+from . import binding as ekv
+from . import synth
+
+
+class DeviceState:
+    """All device buffers of one workload plus its ekv_config."""
+
+    def __init__(self, w, inp, cap=None, device="cuda"):
+        self.w = w
+        dev = torch.device(device)
+        self.inp = {k: v.to(dev) for k, v in inp.items()}
+        B, Hq, Hkv, d, P = w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.page_size
+        self.Mmax = w.pages_per_seq
+        self.cap = cap if cap is not None else self.Mmax
+        self.cfg = ekv.make_config(B, Hq, Hkv, d, P, w.kv_dtype, w.alpha, w.score_scale, self.Mmax, self.cap)
+        dt = synth.torch_dtype(w.kv_dtype)
+        self.box_stats = torch.zeros(B, Hkv, self.Mmax, 2, d, device=dev, dtype=dt)
+        self.gauss_stats = torch.zeros(B, Hkv, self.Mmax, 2, d, device=dev, dtype=dt)
+        f32 = dict(device=dev, dtype=torch.float32)
+        i32 = dict(device=dev, dtype=torch.int32)
+        self.box = torch.zeros(B, Hq, self.Mmax, **f32)
+        self.mu = torch.zeros(B, Hq, self.Mmax, **f32)
+        self.sigma = torch.zeros(B, Hq, self.Mmax, **f32)
+        self.page_idx = torch.zeros(B, Hq, self.cap, **i32)
+        self.n_sel = torch.zeros(B, Hq, **i32)
+        self.overflow = torch.zeros(B, Hq, **i32)
+        self.tau_hat = torch.zeros(B, Hq, **f32)
+        self.out = torch.zeros(B, Hq, d, **f32)
+        self.tau = torch.zeros(B, Hq, **f32)
+        self.supp = torch.zeros(B, Hq, **i32)
+        self.ws = {}
+
+    def cache(self):
+        i = self.inp
+        return ekv.cache_view(i["k_pool"], i["v_pool"], i["block_table"], i["seq_lens"])
+
+    def stats(self):
+        return ekv.stats_view(self.box_stats, self.gauss_stats)
+
+    def workspace(self, op):
+        if op not in self.ws:
+            n = ekv.ekv_workspace_bytes(self.cfg, op)
+            self.ws[op] = torch.empty(max(n, 256), device=self.box.device, dtype=torch.uint8)
+        return self.ws[op]

@@ -1,0 +1,265 @@
+"""GPU parity at the benchmark's full sizes: the million-token workload (C4: 1 sequence, 32 query / 8 KV
+heads, 65 536 pages of 16 tokens, bf16) and the 128K-token batch of 4 (C3), generated on the GPU with the
+benchmark's seed and run in the
+launch configuration `bench.py` times (statistics built once; append inside the scoring launch; top-k of
+2 % of the pages with a list capacity of 4 %, or the Gaussian-aware selector, or one list per KV head;
+sparse decode; dense decode).
+
+The float64 oracle cannot run every head of this size in seconds, so it runs SAMPLED heads one by one,
+each over its whole KV head (all 1 048 576 or 131 072 tokens): the statistics of every page of the head, the score of
+every page, the selection, the sparse attention and the dense attention.  Oracle inputs are copied from
+the generated cache BEFORE any library call touches it; the appended token is the test's own tensor.
+Acceptance rules are those of tests/test_gpu_parity.py."""
+import math
+import numpy as np
+import pytest
+import torch
+
+from oracle import entmaxkv_oracle as orc
+from paper_2605_21649_amd import binding as ekv
+from paper_2605_21649_amd import synth
+from tests.helpers import DeviceState, storage_ulp, sets_equal_up_to_cut, rel_err, to_f64
+
+pytestmark = pytest.mark.gpu
+
+SEED = 4000                     # the benchmark's
+BUDGET, CAP_FRAC = 0.02, 0.04   # the benchmark's
+# sampled (sequence, query head) units
+UNITS = {"C4": [(0, 1), (0, 10), (0, 20), (0, 31)], "C3": [(0, 3), (1, 12), (2, 21), (3, 30)]}
+
+
+@pytest.fixture(scope="module", params=["C4", "C3"])
+def fs(request):
+    global W, HEADS
+    W = synth.WORKLOADS[request.param]
+    HEADS = UNITS[request.param]
+    dev = torch.device("cuda")
+    inp = synth.make_inputs(W, SEED, device=dev)
+    n, P, d = W.context, W.page_size, W.head_dim
+    M = W.pages_per_seq
+    k_pages = int(math.ceil(BUDGET * M)); cap = int(math.ceil(CAP_FRAC * M))
+    g = torch.Generator().manual_seed(77)
+    k_new = (torch.randn(W.batch, W.n_kv_heads, d, generator=g) + 0.5).to(torch.bfloat16)
+    v_new = torch.randn(W.batch, W.n_kv_heads, d, generator=g).to(torch.bfloat16)
+    # oracle inputs, taken before the library runs: logical K, V of the sampled KV heads with the new
+    # token in the last slot
+    cpu = {}
+    for (b, hq) in HEADS:
+        h = hq // W.group
+        k, v = synth.logical_kv(inp, W, b, h)
+        k, v = k.cpu(), v.cpu()
+        k[n - 1] = k_new[b, h]; v[n - 1] = v_new[b, h]
+        cpu[(b, hq)] = (to_f64(inp["q"][b, hq]), to_f64(k), to_f64(v))
+    st = DeviceState(W, inp, cap=cap, device=dev)
+    return dict(inp=inp, st=st, cpu=cpu, k_pages=k_pages, cap=cap, k_new=k_new.to(dev), v_new=v_new.to(dev))
+
+
+def test_full_size_statistics_of_every_page_of_the_sampled_heads(fs):
+    st, inp = fs["st"], fs["inp"]
+    n, P = W.context, W.page_size
+    ekv.ekv_stats_build(st.cfg, st.cache(), st.stats())            # over the n generated tokens
+    seq_prev = (inp["seq_lens"] - 1).contiguous()
+    cache_prev = ekv.cache_view(inp["k_pool"], inp["v_pool"], inp["block_table"], seq_prev)
+    ekv.ekv_stats_append(st.cfg, cache_prev, st.stats(), fs["k_new"], fs["v_new"])   # token n-1 replaced
+    torch.cuda.synchronize()
+    for (b, hq) in HEADS:
+        h = hq // W.group
+        _, K, _ = fs["cpu"][(b, hq)]
+        kmin, kmax, kavg, kstd, cnt = orc.page_stats(K, P)
+        box = to_f64(st.box_stats[b, h]); gauss = to_f64(st.gauss_stats[b, h])
+        np.testing.assert_array_equal(box[:, 0], kmin)
+        np.testing.assert_array_equal(box[:, 1], kmax)
+        kvar = kstd ** 2
+        assert np.all(np.abs(gauss[:, 0] - kavg) <= storage_ulp(kavg, "bf16"))
+        assert np.all(np.abs(gauss[:, 1] - kvar) <= storage_ulp(kvar, "bf16"))
+
+
+def test_full_size_topk_step_as_timed(fs):
+    """append + box scoring in one launch, top-k 2 %, sparse decode: every stage of the sampled heads
+    against the oracle's whole step."""
+    st, inp = fs["st"], fs["inp"]
+    k, P = fs["k_pages"], W.page_size
+    # statistics over the cache as it stands, then the step exactly as the benchmark runs it
+    ekv.ekv_stats_build(st.cfg, st.cache(), st.stats())
+    seq_prev = (inp["seq_lens"] - 1).contiguous()
+    cache_prev = ekv.cache_view(inp["k_pool"], inp["v_pool"], inp["block_table"], seq_prev)
+    ekv.ekv_append_score_pages(st.cfg, cache_prev, st.stats(), fs["k_new"], fs["v_new"], inp["q"],
+                               ekv.EKV_SCORE_BOX, st.box, None, None)
+    ekv.ekv_select_topk(st.cfg, st.box, inp["seq_lens"], k, st.page_idx, st.n_sel,
+                        st.workspace(ekv.EKV_OP_SELECT_TOPK))
+    toks = torch.full((W.batch, W.n_q_heads, 4096), -1, dtype=torch.int32, device=st.box.device)
+    ex = ekv.decode_extras(support_tokens=toks)
+    ekv.ekv_decode_sparse(st.cfg, inp["q"], st.cache(), st.page_idx, st.n_sel, st.out, st.tau, st.supp,
+                          st.workspace(ekv.EKV_OP_DECODE_SPARSE), extras=ex)
+    torch.cuda.synchronize()
+    idx, ns = st.page_idx.cpu().numpy(), st.n_sel.cpu().numpy()
+    assert np.all(ns == k)
+    for (b, hq) in HEADS:
+        q, K, V = fs["cpu"][(b, hq)]
+        ref = orc.decode_step_unit(q, K, V, P, W.alpha, W.score_scale, "topk", W.kv_dtype, k_pages=k)
+        got_box = st.box[b, hq].cpu().numpy()
+        assert np.max(np.abs(got_box - ref["box"]) / np.maximum(1.0, np.abs(ref["box"]))) <= 1e-5
+        band = 1e-5 * max(1.0, abs(ref["cut_in"]))
+        ok, bad = sets_equal_up_to_cut(idx[b, hq, :k], ref["pages"], ref["box"], [ref["cut_in"], ref["cut_out"]], band)
+        assert ok, (hq, bad)
+        assert np.all(np.diff(idx[b, hq, :k]) > 0)
+        if set(idx[b, hq, :k].tolist()) == set(ref["pages"].tolist()):
+            assert abs(float(st.tau[b, hq]) - ref["tau"]) <= 4e-6 * max(1.0, abs(ref["tau"]))
+            n_sup = int(st.supp[b, hq])
+            got_tokens = toks[b, hq, :n_sup].cpu().numpy()
+            z = (W.alpha - 1.0) * orc.token_scores(q, K[ref["support"]], W.score_scale)
+            diff = set(got_tokens.tolist()).symmetric_difference(ref["support"].tolist())
+            # a token may fall on either side only if its z is within float32 resolution of tau
+            if diff:
+                zd = (W.alpha - 1.0) * orc.token_scores(q, K[sorted(diff)], W.score_scale)
+                assert np.all(np.abs(zd - ref["tau"]) <= 2e-6 * max(1.0, abs(ref["tau"]))), (hq, sorted(diff))
+            assert z.min() > ref["tau"]
+            assert rel_err(st.out[b, hq].cpu().numpy(), ref["o"]) <= 2e-3
+
+
+def test_full_size_dense_decode(fs):
+    """Full-cache entmax over 1 048 576 tokens (scores, filter passes, solve) against the sorted exact
+    solution of the oracle for the sampled heads."""
+    st, inp = fs["st"], fs["inp"]
+    seq_prev = (inp["seq_lens"] - 1).contiguous()
+    cache_prev = ekv.cache_view(inp["k_pool"], inp["v_pool"], inp["block_table"], seq_prev)
+    ekv.ekv_stats_append(st.cfg, cache_prev, st.stats(), fs["k_new"], fs["v_new"])   # the token the oracle has
+    toks = torch.full((W.batch, W.n_q_heads, 4096), -1, dtype=torch.int32, device=st.box.device)
+    lse = torch.zeros(W.batch, W.n_q_heads, device=st.box.device)
+    ex = ekv.decode_extras(support_tokens=toks, lse=lse)
+    ekv.ekv_decode_full(st.cfg, inp["q"], st.cache(), st.out, st.tau, st.supp, st.workspace(ekv.EKV_OP_DECODE_FULL),
+                        extras=ex)
+    torch.cuda.synchronize()
+    for (b, hq) in HEADS:
+        q, K, V = fs["cpu"][(b, hq)]
+        ref = orc.entmax_attention(q, K, V, W.alpha, W.score_scale)
+        o, tau, support, s = ref["o"], ref["tau"], ref["support"], ref["s"]
+        assert abs(float(st.tau[b, hq]) - tau) <= 4e-6 * max(1.0, abs(tau)), (float(st.tau[b, hq]), tau)
+        n_sup = int(st.supp[b, hq])
+        got_tokens = toks[b, hq, :n_sup].cpu().numpy()
+        z = (W.alpha - 1.0) * s
+        boundary = set(np.nonzero(np.abs(z - tau) <= 2e-6 * max(1.0, abs(tau)))[0].tolist())
+        diff = set(got_tokens.tolist()).symmetric_difference(support.tolist())
+        assert diff.issubset(boundary), (hq, sorted(diff))
+        assert rel_err(st.out[b, hq].cpu().numpy(), o) <= 2e-3
+        ref_lse = float(np.log(np.sum(np.exp(s - s.max()))) + s.max())
+        assert abs(float(lse[b, hq]) - ref_lse) <= 1e-4 * max(1.0, abs(ref_lse))
+
+
+def _check_decode(b, hq, st, toks, q, K, ref):
+    tau = ref["tau"]
+    assert abs(float(st.tau[b, hq]) - tau) <= 4e-6 * max(1.0, abs(tau)), (hq, float(st.tau[b, hq]), tau)
+    got_tokens = toks[b, hq, : int(st.supp[b, hq])].cpu().numpy()
+    diff = sorted(set(got_tokens.tolist()).symmetric_difference(ref["support"].tolist()))
+    if diff:
+        zd = (W.alpha - 1.0) * orc.token_scores(q, K[diff], W.score_scale)
+        assert np.all(np.abs(zd - tau) <= 2e-6 * max(1.0, abs(tau))), (hq, diff)
+    assert np.all(np.diff(got_tokens) > 0)
+    assert rel_err(st.out[b, hq].cpu().numpy(), ref["o"]) <= 2e-3
+
+
+def test_full_size_gauss_step(fs):
+    """Gaussian-aware step at full size.  Stage by stage, each on inputs both sides share: moments on the
+    oracle's stored statistics; tau-hat and the selection on the oracle's float32 moments; the sparse
+    decode on the list the library selected (when it is the oracle's list)."""
+    st, inp = fs["st"], fs["inp"]
+    dev, P = st.box.device, W.page_size
+    seq_prev = (inp["seq_lens"] - 1).contiguous()
+    cache_prev = ekv.cache_view(inp["k_pool"], inp["v_pool"], inp["block_table"], seq_prev)
+    ekv.ekv_stats_build(st.cfg, st.cache(), st.stats())
+    # a4 on the library's own statistics first (one launch with the append, as timed) ...
+    ekv.ekv_append_score_pages(st.cfg, cache_prev, st.stats(), fs["k_new"], fs["v_new"], inp["q"],
+                               ekv.EKV_SCORE_GAUSS, None, st.mu, st.sigma)
+    torch.cuda.synchronize()
+    own_mu = {(b, hq): st.mu[b, hq].cpu().numpy() for (b, hq) in HEADS}
+    # ... then on the oracle's statistics, where the comparison is sharp
+    moments = {}
+    for (b, hq) in HEADS:
+        h = hq // W.group
+        q, K, V = fs["cpu"][(b, hq)]
+        kmin, kmax, kavg, kstd, cnt = orc.page_stats(K, P)
+        kavg, kstd = orc.stored_gauss_stats(kavg, kstd, "bf16")
+        kvar = orc.round_to_storage(kstd ** 2, "bf16")
+        st.gauss_stats[b, h, :, 0] = torch.from_numpy(kavg).to(torch.bfloat16).to(dev)
+        st.gauss_stats[b, h, :, 1] = torch.from_numpy(kvar).to(torch.bfloat16).to(dev)
+        moments[(b, hq)] = orc.gauss_moments(q, kavg, kstd, W.score_scale) + (cnt,)
+    ekv.ekv_score_pages(st.cfg, inp["q"], st.stats(), inp["seq_lens"], ekv.EKV_SCORE_GAUSS, None, st.mu, st.sigma)
+    torch.cuda.synchronize()
+    for (b, hq) in HEADS:
+        mu, sg, cnt = moments[(b, hq)]
+        for got, ref in ((st.mu[b, hq].cpu().numpy(), mu), (st.sigma[b, hq].cpu().numpy(), sg)):
+            assert np.max(np.abs(got - ref) / np.maximum(1.0, np.abs(ref))) <= 1e-5
+        # the library's own statistics differ from the oracle's by at most one storage ulp per element
+        bound = W.score_scale * np.sum(np.abs(fs["cpu"][(b, hq)][0])) * 2.0 ** -8 * 16.0
+        assert np.max(np.abs(own_mu[(b, hq)] - mu)) <= bound
+        st.mu[b, hq] = torch.from_numpy(mu.astype(np.float32)).to(dev)
+        st.sigma[b, hq] = torch.from_numpy(sg.astype(np.float32)).to(dev)
+    # list capacity as the benchmark sets it for this selector: 4 % at 1M, 25 % at 128K (where it keeps
+    # 5-16 % of the pages of this data)
+    cap = fs["cap"] if W.batch == 1 else int(math.ceil(0.25 * W.pages_per_seq))
+    cfg = ekv.make_config(W.batch, W.n_q_heads, W.n_kv_heads, W.head_dim, P, W.kv_dtype, W.alpha, W.score_scale,
+                          W.pages_per_seq, cap)
+    page_idx = torch.zeros(W.batch, W.n_q_heads, cap, dtype=torch.int32, device=dev)
+    ws = lambda op: torch.empty(max(256, ekv.ekv_workspace_bytes(cfg, op)), dtype=torch.uint8, device=dev)
+    ekv.ekv_select_gauss(cfg, st.mu, st.sigma, inp["seq_lens"], 0.99, 0.0, st.tau_hat, page_idx, st.n_sel,
+                         st.overflow, ws(ekv.EKV_OP_SELECT_GAUSS))
+    toks = torch.full((W.batch, W.n_q_heads, 4096), -1, dtype=torch.int32, device=dev)
+    ekv.ekv_decode_sparse(cfg, inp["q"], st.cache(), page_idx, st.n_sel, st.out, st.tau, st.supp,
+                          ws(ekv.EKV_OP_DECODE_SPARSE), extras=ekv.decode_extras(support_tokens=toks))
+    torch.cuda.synchronize()
+    assert not st.overflow.cpu().numpy().any()
+    idx, ns = page_idx.cpu().numpy(), st.n_sel.cpu().numpy()
+    for (b, hq) in HEADS:
+        q, K, V = fs["cpu"][(b, hq)]
+        mu, sg, cnt = moments[(b, hq)]
+        m32, s32 = mu.astype(np.float32).astype(np.float64), sg.astype(np.float32).astype(np.float64)
+        pages, tau_hat, ovf, g = orc.gauss_select(m32, s32, cnt, W.alpha, 0.99, 0.0, cap=cap)
+        assert not ovf
+        assert abs(float(st.tau_hat[b, hq]) - tau_hat) <= 4e-6 * max(1.0, abs(tau_hat))
+        got = idx[b, hq, : ns[b, hq]]
+        ok, bad = sets_equal_up_to_cut(got, pages, g, tau_hat, 1e-5 * max(1.0, abs(tau_hat)))
+        assert ok, (hq, bad[:5], len(pages), len(got))
+        assert np.all(np.diff(got) > 0)
+        if set(got.tolist()) == set(pages.tolist()):
+            ref = orc.entmax_attention(q, K, V, W.alpha, W.score_scale, orc.pages_to_tokens(pages, P, K.shape[0]))
+            _check_decode(b, hq, st, toks, q, K, ref)
+
+
+def test_full_size_group_shared_step(fs):
+    """One page list per KV head (group-maximum score, top-k 2 %), grouped sparse decode, as timed."""
+    st, inp = fs["st"], fs["inp"]
+    dev, P, k, cap, G = st.box.device, W.page_size, fs["k_pages"], fs["cap"], W.group
+    M = W.pages_per_seq
+    seq_prev = (inp["seq_lens"] - 1).contiguous()
+    cache_prev = ekv.cache_view(inp["k_pool"], inp["v_pool"], inp["block_table"], seq_prev)
+    ekv.ekv_stats_build(st.cfg, st.cache(), st.stats())
+    gbox = torch.zeros(W.batch, W.n_kv_heads, M, device=dev)
+    ekv.ekv_append_score_pages(st.cfg, cache_prev, st.stats(), fs["k_new"], fs["v_new"], inp["q"],
+                               ekv.EKV_SCORE_BOX | ekv.EKV_SCORE_GROUP_MAX, gbox, None, None)
+    gcfg = ekv.make_config(W.batch, W.n_kv_heads, W.n_kv_heads, W.head_dim, P, W.kv_dtype, W.alpha, W.score_scale, M, cap)
+    g_idx = torch.zeros(W.batch, W.n_kv_heads, cap, device=dev, dtype=torch.int32)
+    g_n = torch.zeros(W.batch, W.n_kv_heads, device=dev, dtype=torch.int32)
+    ws_sel = torch.empty(max(256, ekv.ekv_workspace_bytes(gcfg, ekv.EKV_OP_SELECT_TOPK)), device=dev, dtype=torch.uint8)
+    ekv.ekv_select_topk(gcfg, gbox, inp["seq_lens"], k, g_idx, g_n, ws_sel)
+    toks = torch.full((W.batch, W.n_q_heads, 4096), -1, dtype=torch.int32, device=dev)
+    ekv.ekv_decode_sparse_group(st.cfg, inp["q"], st.cache(), g_idx, g_n, st.out, st.tau, st.supp,
+                                st.workspace(ekv.EKV_OP_DECODE_SPARSE), extras=ekv.decode_extras(support_tokens=toks))
+    torch.cuda.synchronize()
+    gb, gi, gn = gbox.cpu().numpy(), g_idx.cpu().numpy(), g_n.cpu().numpy()
+    for (b, hq0) in HEADS:
+        h = hq0 // G
+        _, K, V = fs["cpu"][(b, hq0)]
+        kmin, kmax, *_ = orc.page_stats(K, P)
+        qs = [to_f64(inp["q"][b, h * G + g]) for g in range(G)]
+        ref_g = orc.group_max_scores(np.stack([orc.box_scores(q, kmin, kmax, W.score_scale) for q in qs]))
+        assert np.max(np.abs(gb[b, h] - ref_g) / np.maximum(1.0, np.abs(ref_g))) <= 1e-5
+        pages, cut_in, cut_out = orc.topk_pages(ref_g, k)
+        got = gi[b, h, : gn[b, h]]
+        ok, bad = sets_equal_up_to_cut(got, pages, ref_g, [cut_in, cut_out], 1e-5 * max(1.0, abs(cut_in)))
+        assert ok, (h, bad)
+        if set(got.tolist()) != set(pages.tolist()):
+            continue
+        tokens = orc.pages_to_tokens(pages, P, K.shape[0])
+        for g in range(G):
+            ref = orc.entmax_attention(qs[g], K, V, W.alpha, W.score_scale, tokens)
+            _check_decode(b, h * G + g, st, toks, qs[g], K, ref)
