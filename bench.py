@@ -436,6 +436,20 @@ def main():
         torch.cuda.synchronize()
         extras["decode_loop_us_per_step"] = round((time.perf_counter() - t0) / T * 1e6, 2)
         extras["decode_loop_steps"] = T
+        # the same loop recorded once as a HIP graph (the library only launches kernels) and replayed
+        graph = torch.cuda.CUDAGraph()
+        cap_stream = torch.cuda.Stream()
+        cap_stream.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.graph(graph, stream=cap_stream):
+            run_loop()
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(3):
+            graph.replay()
+        torch.cuda.synchronize()
+        extras["decode_loop_graph_replay_us_per_step"] = round((time.perf_counter() - t0) / (3 * T) * 1e6, 2)
+        del graph
         seq.copy_(seq_full)
         for st in copies:                                      # last pages back to their full statistics
             ekv.ekv_stats_build(st.cfg, st.cache(), st.stats())
