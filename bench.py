@@ -142,6 +142,20 @@ class Runner:
                               st.ws_sparse)
         if evs: evs[4].record()
 
+    def step_gauss_seeded(self, st, evs=None):
+        """The Gaussian step with tau-hat handed to the decode as the solver's starting point."""
+        ekv = self.ekv
+        if not hasattr(st, "ex_seed"):
+            st.evals = self.torch.zeros_like(st.supp)
+            st.ex_seed = ekv.decode_extras(tau_seed=st.tau_hat, solve_evals=st.evals)
+        self.append_and_score(st, evs, ekv.EKV_SCORE_GAUSS, mu=st.mu, sigma=st.sigma)
+        ekv.ekv_select_gauss(st.cfg, st.mu, st.sigma, st.inp["seq_lens"], self.q_page, 0.0, st.tau_hat, st.page_idx,
+                             st.n_sel, st.overflow, st.ws_gauss)
+        if evs: evs[3].record()
+        ekv.ekv_decode_sparse(st.cfg, st.inp["q"], st.cache(), st.page_idx, st.n_sel, st.out, st.tau, st.supp,
+                              st.ws_sparse, extras=st.ex_seed)
+        if evs: evs[4].record()
+
     def step_group(self, st, evs=None):
         ekv = self.ekv
         self.append_and_score(st, evs, ekv.EKV_SCORE_BOX | ekv.EKV_SCORE_GROUP_MAX, box=self.gbox)
@@ -370,6 +384,15 @@ def main():
         extras["gauss_step_us"] = round(us_g, 2)
         extras["gauss_stage_us"] = {nm: round(float(v), 2) for nm, v in zip(STAGE_NAMES["gauss"], stage_g.mean(axis=0))}
         extras["gauss_selected_pages_mean"] = float(copies[0].n_sel.float().mean())
+        # warm start: tau-hat as the solver's first iterate (Sec. 4.3); evaluations of the mass per solve
+        st0_ = copies[0]
+        ev_plain = torch.zeros_like(st0_.supp)
+        ekv.ekv_decode_sparse(st0_.cfg, st0_.inp["q"], st0_.cache(), st0_.page_idx, st0_.n_sel, st0_.out, st0_.tau,
+                              st0_.supp, st0_.ws_sparse, extras=ekv.decode_extras(solve_evals=ev_plain))
+        us_gs, _, _ = R.run_timed(R.step_gauss_seeded, side, 5, stages=False)
+        extras["gauss_step_tau_hat_seeded_us"] = round(us_gs, 2)
+        extras["gauss_solve_evals_mean"] = {"unseeded": round(float(ev_plain.float().mean()), 2),
+                                            "tau_hat_seeded": round(float(st0_.evals.float().mean()), 2)}
         extras["gauss_overflow"] = int(copies[0].overflow.sum())
         ws_full = copies[0].workspace(ekv.EKV_OP_DECODE_FULL)       # one scratch shared by the copies
         out_f, tau_f, supp_f = torch.zeros_like(st0.out), torch.zeros_like(st0.tau), torch.zeros_like(st0.supp)

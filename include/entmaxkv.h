@@ -192,7 +192,16 @@ ekv_status ekv_select_box_threshold(const ekv_config* cfg, const float* box, con
  *   tau_ref f32 [B][Hq] (input): a reference threshold (normally the full-cache tau); when given,
  *       kept_mass_ref[b,h] = sum_{j in candidates} (z_j - tau_ref)_+^beta   (1 - dropped mass, Eq. 4)
  *       kept_supp_ref[b,h] = #{j in candidates : z_j > tau_ref}             (numerator of Eq. 7)
- *   lse f32 [B][Hq] (ekv_decode_full only): log sum_j exp(scale q.k_j) over the whole cache. */
+ *   lse f32 [B][Hq] (ekv_decode_full only): log sum_j exp(scale q.k_j) over the whole cache.
+ *   tau_seed f32 [B][Hq] (input): a guess of tau for a warm start -- the Gaussian-aware estimate
+ *       tau-hat of the same query (Sec. 4.3 uses it as the solver's starting point), or the threshold
+ *       of an earlier solve.  It only chooses where the exact solve starts: the first evaluation is taken
+ *       at the seed when it lies inside the certified bracket, and, on rows of at most 65 536 candidates,
+ *       a seed that the group maxima certify as a lower bound of tau also serves as the candidate
+ *       threshold.  Any value (wrong, infinite, NaN) is safe; tau, supp and out do not depend on it
+ *       beyond float32 rounding of the last iterate.
+ *   solve_evals int32 [B][Hq]: number of evaluations of the mass sum_j (z_j - tau)_+^beta the solve
+ *       took (a measure of what a seed saves). */
 typedef struct {
   int32_t* support_tokens;
   int32_t support_cap;
@@ -200,6 +209,8 @@ typedef struct {
   float* kept_mass_ref;
   int32_t* kept_supp_ref;
   float* lse;
+  const float* tau_seed;
+  int32_t* solve_evals;
 } ekv_decode_extras;
 
 /* a7 -- sparse alpha-entmax attention over the selected pages (Sec. 4.1, Sec. 4.4).

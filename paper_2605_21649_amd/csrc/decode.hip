@@ -441,16 +441,21 @@ __device__ __forceinline__ void eval_mass(const Src& src, float tau, float beta,
 // right point a Newton step (F is convex, so it lands left of the root).  For beta in {1,2} the root is
 // accepted as exact once a closed-form step leaves the support count unchanged.
 // `eval(tau, F, D, cnt)` evaluates the mass, its negated derivative and the support count at tau.
+// `seed`: where to take the first evaluation if it lies inside the bracket (NaN: none); `evals` counts
+// the evaluations.
 template <typename Eval>
-__device__ __forceinline__ float solve_tau_core(Eval&& eval, float lo_init, int ibeta, int& supp) {
+__device__ __forceinline__ float solve_tau_core(Eval&& eval, float lo_init, float seed, int ibeta, int& supp,
+                                                int& evals) {
   float lo = lo_init, hi = 0.f;
-  float tau = lo;
+  float tau = (seed > lo && seed < hi) ? seed : lo;
   int pending_cnt = -1;
   int cnt = 0;
   bool reeval = false;
+  evals = 0;
   for (int it = 0; it < 64; ++it) {
     float F, D;
     eval(tau, F, D, cnt);
+    ++evals;
     if (pending_cnt >= 0 && cnt == pending_cnt) break;       // exact step kept the support: done
     if (fabsf(F - 1.0f) <= 4e-7f) break;                     // float32 resolution of F: tau is the root
     pending_cnt = -1;
@@ -478,6 +483,7 @@ __device__ __forceinline__ float solve_tau_core(Eval&& eval, float lo_init, int 
   if (reeval) {                                              // tau moved after the last evaluation
     float F, D;
     eval(tau, F, D, cnt);
+    ++evals;
   }
   supp = cnt;
   return tau;
@@ -485,27 +491,27 @@ __device__ __forceinline__ float solve_tau_core(Eval&& eval, float lo_init, int 
 
 // The whole workgroup iterates (one barrier per evaluation).
 template <typename Src>
-__device__ __forceinline__ float solve_tau(const Src& src, float lo_init, float beta, int ibeta, SolveShared& sh,
-                                           int& supp) {
+__device__ __forceinline__ float solve_tau(const Src& src, float lo_init, float seed, float beta, int ibeta,
+                                           SolveShared& sh, int& supp, int& evals) {
   int parity = 0;
   return solve_tau_core([&](float tau, float& F, float& D, int& cnt) {
     eval_mass(src, tau, beta, ibeta, sh, parity, F, D, cnt);
     parity ^= 1;
-  }, lo_init, ibeta, supp);
+  }, lo_init, seed, ibeta, supp, evals);
 }
 
 // Short candidate lists (at most kWaveList entries, the usual case once the certified bound has been
 // applied): one wavefront holds them in registers and iterates without any barrier; the result is handed
 // to the other wavefronts through LDS.  Called by the whole workgroup.
 constexpr int kWaveList = 256;
-__device__ __forceinline__ float solve_tau_wave(const float* list_u, int n, float lo_init, float beta, int ibeta,
-                                                SolveShared& sh, int& supp) {
+__device__ __forceinline__ float solve_tau_wave(const float* list_u, int n, float lo_init, float seed, float beta,
+                                                int ibeta, SolveShared& sh, int& supp, int& evals) {
   if (threadIdx.x < 64) {
     const int lane = threadIdx.x;
     float u[kWaveList / 64];
 #pragma unroll
     for (int k = 0; k < kWaveList / 64; ++k) u[k] = lane + 64 * k < n ? list_u[lane + 64 * k] : -INFINITY;
-    int sp = 0;
+    int sp = 0, ev = 0;
     const float tau = solve_tau_core([&](float t, float& F, float& D, int& cnt) {
       float f = 0.f, d = 0.f; int c = 0;
 #pragma unroll
@@ -514,11 +520,12 @@ __device__ __forceinline__ float solve_tau_wave(const float* list_u, int n, floa
         if (x > 0.f) { f += pow_beta(x, beta, ibeta); d += pow_beta_m1(x, beta, ibeta); ++c; }
       }
       F = wave_sum(f); D = beta * wave_sum(d); cnt = wave_sum_i(c);
-    }, lo_init, ibeta, sp);
-    if (lane == 0) { sh.red1[0] = tau; sh.wcount[0][0] = sp; }
+    }, lo_init, seed, ibeta, sp, ev);
+    if (lane == 0) { sh.red1[0] = tau; sh.wcount[0][0] = sp; sh.wcount[0][1] = ev; }
   }
   __syncthreads();
   supp = sh.wcount[0][0];
+  evals = sh.wcount[0][1];
   return sh.red1[0];
 }
 
@@ -591,6 +598,8 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
   const float beta = A.beta; const int ibeta = A.ibeta;
   float* out = A.out + (size_t)bh * kD;
 
+  // warm start (optional): requested with the first loads, used once zmax is known
+  const float seed_z = A.ex.tau_seed != nullptr ? A.ex.tau_seed[bh] : NAN;
   float zmax, thr_f = 0.f;
   float mypm = -INFINITY;                   // this thread's group maximum (rows of at most 1024 groups)
   if (A.fcount != nullptr) {
@@ -603,7 +612,10 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
   }
   if (!(zmax > -INFINITY)) {                // no valid candidate at all
     if (tid < kD) out[tid] = 0.f;
-    if (tid == 0) { A.tau_out[bh] = INFINITY; A.supp_out[bh] = 0; }
+    if (tid == 0) {
+      A.tau_out[bh] = INFINITY; A.supp_out[bh] = 0;
+      if (A.ex.solve_evals != nullptr) A.ex.solve_evals[bh] = 0;
+    }
     return;
   }
   // Only z > zmax - 1 can be in the support.  That set is compacted IN ORDER into LDS in rounds of
@@ -626,7 +638,17 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
     if (mypm > thr) atomicAdd(&sh.hist[min(63, (int)((mypm - thr) * inv_step))], 1);
     __syncthreads();
     thr += (float)certified_level<64>(sh.hist, step, beta, ibeta, sh.flags) * step;
+    if (A.ex.tau_seed != nullptr) {
+      // A seed above that bound becomes the candidate threshold if the group maxima alone already put a
+      // mass of 1 above it (then the full mass there is >= 1, i.e. the seed is a lower bound of tau).
+      const bool try_seed = seed_z > thr && seed_z < zmax;            // false for NaN
+      float f = (try_seed && mypm > seed_z) ? pow_beta(mypm - seed_z, beta, ibeta) : 0.f;
+      f = block_sum(f, sh.red1);
+      if (try_seed && f >= 1.0001f) thr = seed_z;
+    }
   }
+  const float seed_u = seed_z - zmax;
+  int evals = 0;
   float lo_u = thr - zmax;
   // chunk skipping pays only when there is a lot to skip (dense rows); short candidate lists are read whole,
   // which saves the dependent load of the chunk maxima in every round
@@ -790,8 +812,8 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
       rowreg[k] = v_row_of<DENSE>(A, b, lrow, hkv, sh.list_pos[e]);
     }
     const ListSrc ls{sh.list_u, sh.list_pos, n_list};
-    if (n_list <= kWaveList) tau_u = solve_tau_wave(sh.list_u, n_list, lo_u, beta, ibeta, sh, supp);
-    else tau_u = solve_tau(ls, lo_u, beta, ibeta, sh, supp);
+    if (n_list <= kWaveList) tau_u = solve_tau_wave(sh.list_u, n_list, lo_u, seed_u, beta, ibeta, sh, supp, evals);
+    else tau_u = solve_tau(ls, lo_u, seed_u, beta, ibeta, sh, supp, evals);
 #pragma unroll
     for (int k = 0; k < kListCap / kSolveThreads; ++k) {
       const int e = tid + k * kSolveThreads;
@@ -842,7 +864,7 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
   } else {
     // the candidates do not fit in LDS: stream the score row for every evaluation
     const RowSrc rsrc{zr, n_cand, zmax};
-    tau_u = solve_tau(rsrc, lo_u, beta, ibeta, sh, supp);
+    tau_u = solve_tau(rsrc, lo_u, seed_u, beta, ibeta, sh, supp, evals);
     const int rs = tid >> 4, c = tid & 15;
     float acc[8];
 #pragma unroll
@@ -879,7 +901,10 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
     }
   }
   const float tau = tau_u + zmax;
-  if (tid == 0) { A.tau_out[bh] = tau; A.supp_out[bh] = supp; }
+  if (tid == 0) {
+    A.tau_out[bh] = tau; A.supp_out[bh] = supp;
+    if (A.ex.solve_evals != nullptr) A.ex.solve_evals[bh] = evals;
+  }
 
   // ---- optional side outputs over ALL candidates ----------------------------------------
   if (A.ex.tau_ref != nullptr && (A.ex.kept_mass_ref != nullptr || A.ex.kept_supp_ref != nullptr)) {

@@ -421,6 +421,76 @@ def test_sparse_equals_full_when_support_is_covered():
     assert rel_err(st.out.cpu().numpy().ravel(), out_f.cpu().numpy().ravel().astype(np.float64)) <= 2e-6
 
 
+def seeded(base, kind, rng):
+    """Seeds for the warm start, from the oracle's tau (float64 array [B, Hq])."""
+    if kind == "exact": return base
+    if kind == "slightly-low": return base - 1e-3
+    if kind == "slightly-high": return base + 1e-3
+    if kind == "far-low": return base - 0.7
+    if kind == "far-high": return base + 0.7
+    if kind == "garbage":
+        vals = np.array([np.nan, np.inf, -np.inf, 1e30, -1e30, 0.0])
+        return vals[rng.integers(0, len(vals), size=base.shape)]
+    raise ValueError(kind)
+
+
+@pytest.mark.parametrize("w", [W1S, W2, W3A, W5, W5B], ids=["C1-soft", "C2-8k", "C3-small-a43", "C5-small", "C5-small-a2"])
+def test_warm_started_solve_gives_the_same_result(w):
+    """tau_seed only moves the starting point: whatever the seed (the exact tau, near it on either side,
+    far off, NaN/inf), threshold, support and output are those of the unseeded solve and of the oracle; a
+    good seed takes fewer evaluations of the mass.  Sparse decode on top-k lists and dense decode."""
+    inp = get_inputs(w)
+    k = topk_budget(w)
+    st = DeviceState(w, inp, cap=k)
+    dev = st.box.device
+    run_step(st, w, "topk", k=k)
+    torch.cuda.synchronize()
+    idx, ns = st.page_idx.cpu().numpy(), st.n_sel.cpu().numpy()
+    B, Hq = w.batch, w.n_q_heads
+    units = [(b, h) for b in range(B) for h in range(Hq)]
+    ref_s = np.zeros((B, Hq)); ref_d = np.zeros((B, Hq))
+    refs = {}
+    for (b, hq) in units:
+        q, K, V = unit_kv(inp, w, b, hq)
+        tok = orc.pages_to_tokens(idx[b, hq, : ns[b, hq]], w.page_size, K.shape[0])
+        rs = orc.entmax_attention(q, K, V, w.alpha, w.score_scale, tok)
+        rd = orc.entmax_attention(q, K, V, w.alpha, w.score_scale)
+        ref_s[b, hq], ref_d[b, hq] = rs["tau"], rd["tau"]
+        refs[(b, hq)] = (rs, rd)
+    evals = torch.zeros(B, Hq, dtype=torch.int32, device=dev)
+    ws_s, ws_d = st.workspace(ekv.EKV_OP_DECODE_SPARSE), st.workspace(ekv.EKV_OP_DECODE_FULL)
+    rng = np.random.default_rng(3)
+
+    def run(dense, seed):
+        t = None if seed is None else torch.from_numpy(seed.astype(np.float32)).to(dev)
+        ex = ekv.decode_extras(tau_seed=t, solve_evals=evals)
+        if dense:
+            ekv.ekv_decode_full(st.cfg, st.inp["q"], st.cache(), st.out, st.tau, st.supp, ws_d, extras=ex)
+        else:
+            ekv.ekv_decode_sparse(st.cfg, st.inp["q"], st.cache(), st.page_idx, st.n_sel, st.out, st.tau, st.supp,
+                                  ws_s, extras=ex)
+        torch.cuda.synchronize()
+        return st.tau.cpu().numpy().copy(), st.supp.cpu().numpy().copy(), st.out.cpu().numpy().copy(), \
+            evals.cpu().numpy().copy()
+
+    for dense, base in ((False, ref_s), (True, ref_d)):
+        tau0, supp0, out0, ev0 = run(dense, None)
+        assert ev0.min() >= 1
+        for kind in ("exact", "slightly-low", "slightly-high", "far-low", "far-high", "garbage"):
+            tau1, supp1, out1, ev1 = run(dense, seeded(base, kind, rng))
+            assert np.all(np.abs(tau1 - base) <= 4e-6 * np.maximum(1.0, np.abs(base))), kind
+            for (b, hq) in units:
+                ref = refs[(b, hq)][1 if dense else 0]
+                z = (w.alpha - 1.0) * ref["s"]
+                n_boundary = int(np.sum(np.abs(z - ref["tau"]) <= 2e-6 * max(1.0, abs(ref["tau"]))))
+                assert abs(int(supp1[b, hq]) - len(ref["support"])) <= n_boundary, (kind, b, hq)
+                if n_boundary == 0:
+                    assert supp1[b, hq] == supp0[b, hq]
+                assert rel_err(out1[b, hq], ref["o"]) <= OUT_TOL[w.kv_dtype], (kind, b, hq)
+            if kind == "exact":
+                assert ev1.mean() <= ev0.mean() and ev1.max() <= 3, (ev0.mean(), ev1.mean(), ev1.max())
+
+
 # ---------------------------------------------------------------------------- a9
 @pytest.mark.parametrize("w", [W1S, W5, synth.C2.scaled(name="C2-p64-g8", context=4096 + 64, ragged=21, page_size=64,
                                                         n_q_heads=16, n_kv_heads=2),
