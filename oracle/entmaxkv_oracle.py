@@ -8,6 +8,7 @@ paper's definitions so that it can be checked against the paper by eye:
 
   stage 1  page statistics          Sec. 4.2 (page min/max; k_avg, m_2, k_std)
   stage 2  box page score           Sec. 4.2 Eq. 9, App. B.1
+           8-bit page bounds        extension of Eq. 9 (bounds rounded outward to OCP E4M3)
            Gaussian page moments    Sec. 4.3 (mu_p, sigma_p^2)
   stage 3  top-k page selection     Sec. 4.3 "Top-k page selection"
            Gaussian tau-hat         Sec. 4.3 Eq. 10, App. D (truncated Gaussian moments)
@@ -26,7 +27,9 @@ Parity pins (tests/test_oracle_*.py): brute-force subset enumeration, sparsemax
 closed form, softmax limit, normalisation, the tightness example of Prop. 1,
 Prop. 2-4 invariants, P=1 reduction, printed truncated-moment closed forms vs
 quadrature; box-threshold refinement: a worked example, the P=1 reduction and
-"one refinement from any start reaches the full-cache result".  Unpinned: which pages a *good* Gaussian selector should pick
+"one refinement from any start reaches the full-cache result"; 8-bit bounds: the value
+table against a library decoder, directed rounding by brute force over the table, a worked
+example, and "8-bit score >= cache-dtype score >= largest token score".  Unpinned: which pages a *good* Gaussian selector should pick
 (selection quality; the paper states no hyper-parameters) -- "parity unpinned".
 """
 import numpy as np
@@ -110,6 +113,60 @@ def gauss_moments(q, kavg, kstd, scale):
     mu = scale * (kavg @ q)
     var = scale * scale * ((kstd * kstd) @ (q * q))
     return mu, np.sqrt(var)
+
+
+# --------------------------------------------------------------------------------------
+# stage 1'/2': 8-bit page bounds (an extension: the paper keeps its metadata in the cache dtype)
+# --------------------------------------------------------------------------------------
+# Eq. 9 stays an upper bound of scale*q.k over the page as long as the stored k_min is not above the
+# true minimum and the stored k_max not below the true maximum (App. B.1's argument uses nothing
+# else).  The bounds can therefore be kept in any coarser number format if k_min is rounded DOWN and
+# k_max UP to that format.  Format here: the 8-bit float E4M3 of the OCP 8-bit floating point
+# specification (1 sign, 4 exponent bits with bias 7, 3 mantissa bits; subnormals; no infinities;
+# the all-ones exponent-and-mantissa code is NaN; largest finite value 448).
+def e4m3_grid():
+    """Every finite E4M3 value, ascending (253 distinct values, -448 .. 448), from the format's
+    definition: code (e, m) is (m/8) * 2^-6 for e = 0, else (1 + m/8) * 2^(e-7); (15, 7) is NaN."""
+    pos = []
+    for e in range(16):
+        for m in range(8):
+            if e == 15 and m == 7:
+                continue
+            pos.append((m / 8.0) * 2.0 ** -6 if e == 0 else (1.0 + m / 8.0) * 2.0 ** (e - 7))
+    pos = np.array(pos, dtype=np.float64)
+    return np.concatenate([-pos[:0:-1], pos])
+
+
+def round_e4m3(x, direction):
+    """Directed rounding to E4M3: 'down' = the largest finite format value <= x, 'up' = the smallest
+    >= x.  NaN where no such value exists (x > 448 rounding up, x < -448 rounding down) or x is NaN."""
+    grid = e4m3_grid()
+    x = np.asarray(x, dtype=np.float64)
+    out = np.full(x.shape, np.nan)
+    ok = ~np.isnan(x)
+    if direction == "down":
+        i = np.searchsorted(grid, x[ok], side="right") - 1          # last grid value <= x
+        vals = np.where(i >= 0, grid[np.maximum(i, 0)], np.nan)
+    elif direction == "up":
+        i = np.searchsorted(grid, x[ok], side="left")               # first grid value >= x
+        vals = np.where(i < len(grid), grid[np.minimum(i, len(grid) - 1)], np.nan)
+    else:
+        raise ValueError(direction)
+    out[ok] = vals
+    return out
+
+
+def box8_stats(kmin, kmax):
+    """8-bit page bounds: (k_min rounded down, k_max rounded up), as float64 (NaN = not representable)."""
+    return round_e4m3(kmin, "down"), round_e4m3(kmax, "up")
+
+
+def box8_scores(q, lo8, hi8, scale):
+    """Eq. 9 on the 8-bit bounds.  A page with a bound that the format cannot hold (NaN) gets +inf:
+    it is always selected, which keeps the score an upper bound."""
+    bad = np.isnan(lo8).any(axis=1) | np.isnan(hi8).any(axis=1)
+    s = box_scores(q, np.nan_to_num(lo8), np.nan_to_num(hi8), scale)
+    return np.where(bad, np.inf, s)
 
 
 # --------------------------------------------------------------------------------------
