@@ -36,7 +36,9 @@ PMC_TRAFFIC_SCORE_PAGES_C4 = int((256.17 + 8.01) * 1024 * 1024)
 STAGE_NAMES = {"topk": ["append_own_launch", "append+score_box", "select_topk", "decode_sparse"],
                "gauss": ["append_own_launch", "append+score_gauss", "select_gauss", "decode_sparse"],
                "group": ["append_own_launch", "append+score_group_max", "select_topk", "decode_sparse_group"],
-               "dense": ["-", "-", "-", "decode_full"]}
+               "dense": ["-", "-", "-", "decode_full"],
+               "topk8": ["append_own_launch", "append+score_box8", "select_topk", "decode_sparse"],
+               "group8": ["append_own_launch", "append+score_box8_group_max", "select_topk", "decode_sparse_group"]}
 
 
 def parse():
@@ -46,7 +48,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="C4")
     ap.add_argument("--budget", type=float, default=0.02, help="top-k budget as a fraction of the pages")
-    ap.add_argument("--variant", default="topk", choices=["topk", "gauss", "group", "dense"],
+    ap.add_argument("--variant", default="topk", choices=["topk", "gauss", "group", "dense", "topk8", "group8"],
                     help="step timed as the headline: top-k (default, the metric's variant), Gaussian selector, "
                          "group-shared top-k, or the dense full-cache decode alone (for profiling the other rows)")
     ap.add_argument("--copies", type=int, default=4, help="rotating copies of the cache (defeats the LLC)")
@@ -156,6 +158,25 @@ class Runner:
                               st.ws_sparse, extras=st.ex_seed)
         if evs: evs[4].record()
 
+    def step_topk8(self, st, evs=None):
+        """Top-k step selecting on the 8-bit page bounds (half the metadata bytes)."""
+        ekv = self.ekv
+        self.append_and_score(st, evs, ekv.EKV_SCORE_BOX8, box=st.box)
+        ekv.ekv_select_topk(st.cfg, st.box, st.inp["seq_lens"], self.k_pages, st.page_idx, st.n_sel, st.ws_topk)
+        if evs: evs[3].record()
+        ekv.ekv_decode_sparse(st.cfg, st.inp["q"], st.cache(), st.page_idx, st.n_sel, st.out, st.tau, st.supp,
+                              st.ws_sparse)
+        if evs: evs[4].record()
+
+    def step_group8(self, st, evs=None):
+        ekv = self.ekv
+        self.append_and_score(st, evs, ekv.EKV_SCORE_BOX8 | ekv.EKV_SCORE_GROUP_MAX, box=self.gbox)
+        ekv.ekv_select_topk(self.gcfg, self.gbox, st.inp["seq_lens"], self.k_pages, self.g_idx, self.g_n, self.ws_gsel)
+        if evs: evs[3].record()
+        ekv.ekv_decode_sparse_group(st.cfg, st.inp["q"], st.cache(), self.g_idx, self.g_n, st.out, st.tau, st.supp,
+                                    st.ws_sparse)
+        if evs: evs[4].record()
+
     def step_group(self, st, evs=None):
         ekv = self.ekv
         self.append_and_score(st, evs, ekv.EKV_SCORE_BOX | ekv.EKV_SCORE_GROUP_MAX, box=self.gbox)
@@ -175,7 +196,7 @@ class Runner:
 
     def step(self, variant):
         return {"topk": self.step_topk, "gauss": self.step_gauss, "group": self.step_group,
-                "dense": self.step_dense}[variant]
+                "dense": self.step_dense, "topk8": self.step_topk8, "group8": self.step_group8}[variant]
 
     # ---- timing --------------------------------------------------------------------------------
     def run_timed(self, step_fn, steps, warmup, stages=True):
@@ -261,6 +282,11 @@ def main():
     R = Runner(w, args.budget, args.copies, args.q_page, dev, args.cap_frac, fused_append=not args.two_launch_append)
     k_pages, copies = R.k_pages, R.copies
     stage_names = STAGE_NAMES[args.variant]
+    if args.variant in ("topk8", "group8"):      # the 8-bit bounds exist only where a step reads them
+        for st in copies:
+            st.enable_box8()
+            ekv.ekv_stats_build(st.cfg, st.cache(), st.stats())
+        torch.cuda.synchronize()
 
     if args.pmc_copy:
         # a plain copy of known size: 1 GiB read + 1 GiB written by one elementwise kernel
@@ -498,6 +524,33 @@ def main():
         extras["stats_build_us"] = round(R.time_call(lambda st: ekv.ekv_stats_build(st.cfg, st.cache(), st.stats()),
                                                      reps=8), 2)
         extras["stats_build_GBps"] = round((dense_bytes / 2 + 2 * bytes_meta) / (extras["stats_build_us"] * 1e-6) / 1e9, 1)
+        # 8-bit page bounds (an extension; the rows above keep the paper's cache-dtype metadata): allocated and
+        # built only now, so that nothing above pays for them
+        for st in copies:
+            st.enable_box8()
+            ekv.ekv_stats_build(st.cfg, st.cache(), st.stats())
+        torch.cuda.synchronize()
+        us_8, stage_8, _ = R.run_timed(R.step_topk8, side, 5)
+        us_g8, _, _ = R.run_timed(R.step_group8, side, 5, stages=False)
+        score8_us = R.time_call(lambda st: ekv.ekv_score_pages(st.cfg, st.inp["q"], st.stats(), st.inp["seq_lens"],
+                                                               ekv.EKV_SCORE_BOX8, st.box), reps=20)
+        bytes8 = B * Hkv * M * 256 + B * Hq * M * 4
+        ekv.ekv_score_pages(st0.cfg, st0.inp["q"], st0.stats(), st0.inp["seq_lens"], ekv.EKV_SCORE_BOX8, st0.box)
+        ekv.ekv_select_topk(st0.cfg, st0.box, st0.inp["seq_lens"], k_pages, st0.page_idx, st0.n_sel, st0.ws_topk)
+        ekv.ekv_decode_sparse(st0.cfg, st0.inp["q"], st0.cache(), st0.page_idx, st0.n_sel, st0.out, st0.tau,
+                              st0.supp, st0.ws_sparse,
+                              extras=ekv.decode_extras(tau_ref=tau_f, kept_mass_ref=kept_mass, kept_supp_ref=kept_supp))
+        torch.cuda.synchronize()
+        extras["box8"] = {
+            "topk_step_us": round(us_8, 2),
+            "topk_stage_us": {nm: round(float(v), 2) for nm, v in zip(STAGE_NAMES["topk"], stage_8.mean(axis=0))},
+            "group_shared_step_us": round(us_g8, 2),
+            "score_pages_us": round(score8_us, 2), "score_pages_algorithmic_bytes": bytes8,
+            "score_pages_GBps": round(bytes8 / (score8_us * 1e-6) / 1e9, 1),
+            "speedup_vs_dense": round(dense_us / us_8, 2),
+            "delta_mean": round(float((1.0 - kept_mass).mean()), 6),
+            "rho_mean": round(float((kept_supp.float() / supp_f.float()).mean()), 4),
+            "R_mean": round(float(((st0.out - out_f).norm(dim=-1) / out_f.norm(dim=-1)).mean()), 6)}
         result["other_rows"] = extras
 
     # ---------------------------------------------------------------- CPU baseline: the oracle, as it stands

@@ -46,7 +46,9 @@ typedef enum {
   EKV_SCORE_BOX = 1,
   EKV_SCORE_GAUSS = 2,
   EKV_SCORE_BOTH = 3,
-  EKV_SCORE_GROUP_MAX = 4 /* with EKV_SCORE_BOX only: one score per KV head, the maximum over its query heads */
+  EKV_SCORE_GROUP_MAX = 4, /* with EKV_SCORE_BOX or EKV_SCORE_BOX8 only: one score per KV head, the maximum over
+                              its query heads */
+  EKV_SCORE_BOX8 = 8       /* the box score computed from the 8-bit bounds stats->box8 (alone or with GROUP_MAX) */
 } ekv_score_mode;
 
 /* Operations a workspace can be sized for. */
@@ -94,10 +96,20 @@ typedef struct {
  * both in kv_dtype.  (The variance rather than k_std is stored because sigma_p^2 of Sec. 4.3 is linear
  * in it, which lets the scoring kernel run as one bf16 matrix contraction; k_std = sqrt(k_var).)
  * Rows of pages p >= M_b are not defined.  Either pointer may be NULL in calls that do not need it
- * (scoring with a mode that does not read it). */
+ * (scoring with a mode that does not read it).
+ * box8 (optional, may be NULL everywhere): the same bounds in 8 bits per value, half the bytes to stream
+ * when scoring -- an extension; the paper keeps its metadata in the cache dtype.  uint8 [B][Hkv][Mmax][16][2][8]:
+ * unit u of a page holds k_min of channels 8u..8u+7, then k_max of the same channels, as OCP E4M3 codes
+ * (1 sign, 4 exponent bits with bias 7, 3 mantissa bits; 0x7f/0xff = NaN; largest finite value 448), with
+ * k_min rounded DOWN and k_max rounded UP to the format, so that Eq. 9 computed from them is still an upper
+ * bound of every token score of the page (only looser).  A bound the format cannot hold (k_max > 448,
+ * k_min < -448, NaN) is stored as NaN and gives the page the score +inf: it is always selected.
+ * kv_dtype must be EKV_BF16.  When box8 is not NULL, ekv_stats_build, ekv_stats_append and
+ * ekv_append_score_pages keep it up to date together with box and gauss. */
 typedef struct {
   void* box;
   void* gauss;
+  void* box8;
 } ekv_stats_view;
 
 /* a1 -- bulk statistics build (Sec. 4.2).  For every sequence b, KV head and logical page p < M_b,
@@ -122,6 +134,8 @@ ekv_status ekv_stats_append(const ekv_config* cfg, const ekv_cache_view* cache,
  *   mu[b,h,p]    = scale * q . k_avg                                   (mode & EKV_SCORE_GAUSS)
  *   sigma[b,h,p] = scale * sqrt(sum_i q_i^2 k_var,i)                   (mode & EKV_SCORE_GAUSS)
  * Entries p >= M_b are written as -inf (box, mu) and 0 (sigma).
+ * mode == EKV_SCORE_BOX8 computes box from stats->box8 instead (bf16 only; not combined with BOX or GAUSS
+ * in one call); pages with a NaN bound score +inf.
  * mode == EKV_SCORE_BOX | EKV_SCORE_GROUP_MAX writes instead box f32 [B][Hkv][Mmax], the maximum of the G
  * query heads' box scores of each KV head: the score of a page list shared by the group (the paper
  * selects per attention head and does not treat grouped-query attention; the maximum keeps Eq. 9 an

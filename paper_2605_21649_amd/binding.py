@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libentmaxkv.so")
 
 EKV_OK = 0
 EKV_F32, EKV_BF16 = 0, 1
-EKV_SCORE_BOX, EKV_SCORE_GAUSS, EKV_SCORE_BOTH, EKV_SCORE_GROUP_MAX = 1, 2, 3, 4
+EKV_SCORE_BOX, EKV_SCORE_GAUSS, EKV_SCORE_BOTH, EKV_SCORE_GROUP_MAX, EKV_SCORE_BOX8 = 1, 2, 3, 4, 8
 EKV_OP_SELECT_TOPK, EKV_OP_SELECT_GAUSS, EKV_OP_DECODE_SPARSE, EKV_OP_DECODE_FULL, \
     EKV_OP_DECODE_SPARSE_SOFTMAX, EKV_OP_SELECT_BOX_THRESHOLD = range(6)
 
@@ -40,7 +40,7 @@ class ekv_cache_view(ctypes.Structure):
 
 
 class ekv_stats_view(ctypes.Structure):
-    _fields_ = [("box", c_void_p), ("gauss", c_void_p)]
+    _fields_ = [("box", c_void_p), ("gauss", c_void_p), ("box8", c_void_p)]
 
 
 class ekv_decode_extras(ctypes.Structure):
@@ -126,8 +126,8 @@ def cache_view(k_pool, v_pool, block_table, seq_lens):
     return ekv_cache_view(_ptr(k_pool), _ptr(v_pool), _ptr(block_table), _ptr(seq_lens), k_pool.shape[0])
 
 
-def stats_view(box, gauss):
-    return ekv_stats_view(_ptr(box), _ptr(gauss))
+def stats_view(box, gauss, box8=None):
+    return ekv_stats_view(_ptr(box), _ptr(gauss), _ptr(box8))
 
 
 def decode_extras(support_tokens=None, tau_ref=None, kept_mass_ref=None, kept_supp_ref=None, lse=None,

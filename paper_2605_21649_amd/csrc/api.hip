@@ -74,9 +74,22 @@ static double phi_inv(double log_p) {
 
 using namespace ekv;
 
+// box (Eq. 9 on cache-dtype bounds), gauss, both, box8 (Eq. 9 on the 8-bit bounds); box or box8 may be reduced to
+// the group maximum
+static bool score_mode_ok(int32_t mode) {
+  return (mode >= 1 && mode <= 3) || mode == (EKV_SCORE_BOX | EKV_SCORE_GROUP_MAX) || mode == EKV_SCORE_BOX8 ||
+         mode == (EKV_SCORE_BOX8 | EKV_SCORE_GROUP_MAX);
+}
+// the optional 8-bit bounds: 16-byte units, bf16 caches only
+static ekv_status check_box8(const Dims& dm, const ekv_stats_view* stats, bool required) {
+  if (stats->box8 == nullptr) return required ? EKV_ERR_INVALID_ARG : EKV_OK;
+  if (!aligned16(stats->box8)) return EKV_ERR_INVALID_ARG;
+  return dm.dtype == EKV_BF16 ? EKV_OK : EKV_ERR_UNSUPPORTED;
+}
+
 extern "C" {
 
-int32_t ekv_version(void) { return 100; }
+int32_t ekv_version(void) { return 101; }
 
 int32_t ekv_last_hip_error(void) { return g_last_hip_error; }
 
@@ -120,6 +133,7 @@ ekv_status ekv_stats_build(const ekv_config* cfg, const ekv_cache_view* cache, c
   if (s != EKV_OK) return s;
   if ((s = check_cache(cache, false)) != EKV_OK) return s;
   if (stats == nullptr || !ok_ptr(stats->box) || !ok_ptr(stats->gauss)) return EKV_ERR_INVALID_ARG;
+  if ((s = check_box8(dm, stats, false)) != EKV_OK) return s;
   launch_stats_build(dm, *cache, *stats, (hipStream_t)stream);
   return finish((hipStream_t)stream);
 }
@@ -132,6 +146,7 @@ ekv_status ekv_stats_append(const ekv_config* cfg, const ekv_cache_view* cache, 
   if ((s = check_cache(cache, v_new != nullptr)) != EKV_OK) return s;
   if (stats == nullptr || !ok_ptr(stats->box) || !ok_ptr(stats->gauss)) return EKV_ERR_INVALID_ARG;
   if (!ok_ptr(k_new) || (v_new != nullptr && !aligned16(v_new))) return EKV_ERR_INVALID_ARG;
+  if ((s = check_box8(dm, stats, false)) != EKV_OK) return s;
   launch_stats_append(dm, *cache, *stats, k_new, v_new, (hipStream_t)stream);
   return finish((hipStream_t)stream);
 }
@@ -140,11 +155,14 @@ ekv_status ekv_score_pages(const ekv_config* cfg, const void* q, const ekv_stats
                            const int32_t* seq_lens, int32_t mode, float* box, float* mu, float* sigma,
                            void* stream) {
   Dims dm;
-  const ekv_status s = make_dims(cfg, dm);
+  ekv_status s = make_dims(cfg, dm);
   if (s != EKV_OK) return s;
-  const bool ok_mode = (mode >= 1 && mode <= 3) || mode == (EKV_SCORE_BOX | EKV_SCORE_GROUP_MAX);
-  if (!ok_mode || !ok_ptr(q) || stats == nullptr || !ok_ptr4(seq_lens)) return EKV_ERR_INVALID_ARG;
+  if (!score_mode_ok(mode) || !ok_ptr(q) || stats == nullptr || !ok_ptr4(seq_lens)) return EKV_ERR_INVALID_ARG;
   if ((mode & EKV_SCORE_BOX) && (!ok_ptr(stats->box) || !ok_ptr4(box))) return EKV_ERR_INVALID_ARG;
+  if (mode & EKV_SCORE_BOX8) {
+    if (!ok_ptr4(box)) return EKV_ERR_INVALID_ARG;
+    if ((s = check_box8(dm, stats, true)) != EKV_OK) return s;
+  }
   if ((mode & EKV_SCORE_GAUSS) && (!ok_ptr(stats->gauss) || !ok_ptr4(mu) || !ok_ptr4(sigma)))
     return EKV_ERR_INVALID_ARG;
   launch_score_pages(dm, q, *stats, seq_lens, mode, box, mu, sigma, (hipStream_t)stream);
@@ -159,10 +177,11 @@ ekv_status ekv_append_score_pages(const ekv_config* cfg, const ekv_cache_view* c
   if (s != EKV_OK) return s;
   if ((s = check_cache(cache, false)) != EKV_OK) return s;
   if (v_new != nullptr && !ok_ptr(cache->v_pool)) return EKV_ERR_INVALID_ARG;
-  const bool ok_mode = (mode >= 1 && mode <= 3) || mode == (EKV_SCORE_BOX | EKV_SCORE_GROUP_MAX);
-  if (!ok_mode || !ok_ptr(q) || !ok_ptr(k_new) || (v_new != nullptr && !ok_ptr(v_new))) return EKV_ERR_INVALID_ARG;
+  if (!score_mode_ok(mode) || !ok_ptr(q) || !ok_ptr(k_new) || (v_new != nullptr && !ok_ptr(v_new)))
+    return EKV_ERR_INVALID_ARG;
   if (stats == nullptr || !ok_ptr(stats->box) || !ok_ptr(stats->gauss)) return EKV_ERR_INVALID_ARG;
-  if ((mode & EKV_SCORE_BOX) && !ok_ptr4(box)) return EKV_ERR_INVALID_ARG;
+  if ((s = check_box8(dm, stats, (mode & EKV_SCORE_BOX8) != 0)) != EKV_OK) return s;
+  if ((mode & (EKV_SCORE_BOX | EKV_SCORE_BOX8)) && !ok_ptr4(box)) return EKV_ERR_INVALID_ARG;
   if ((mode & EKV_SCORE_GAUSS) && (!ok_ptr4(mu) || !ok_ptr4(sigma))) return EKV_ERR_INVALID_ARG;
   launch_score_pages(dm, q, *stats, cache->seq_lens, mode, box, mu, sigma, (hipStream_t)stream, cache, k_new, v_new);
   return finish((hipStream_t)stream);

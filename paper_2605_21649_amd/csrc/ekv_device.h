@@ -78,6 +78,41 @@ template <> __device__ __forceinline__ void store8<bf16_t>(bf16_t* p, const floa
   *reinterpret_cast<uint4*>(p) = a;
 }
 
+// ---- 8-bit bounds: OCP E4M3 (bias 7, 3 mantissa bits, subnormals, max 448, 0x7f = NaN) -----------
+// Directed rounding of a float: UP gives the code of the smallest format value >= x, otherwise of the
+// largest <= x; the NaN code when no finite format value qualifies (or x is NaN).
+template <bool UP> __device__ __forceinline__ uint32_t f32_to_e4m3_directed(float x) {
+  const uint32_t bits = __float_as_uint(x);
+  const uint32_t sign = bits >> 31, abits = bits & 0x7fffffffu;
+  const float a = __uint_as_float(abits);
+  const bool away = UP ? sign == 0u : sign != 0u;        // the magnitude is rounded up
+  if (!(a <= 448.0f)) return (a != a || away) ? 0x7fu : ((sign << 7) | 0x7eu);
+  uint32_t mag;
+  if (a < 0.015625f) {                                   // below 2^-6: multiples of 2^-9 (codes 0..8)
+    const float s = a * 512.0f, f = floorf(s);
+    mag = (uint32_t)f + ((away && s != f) ? 1u : 0u);
+  } else {
+    uint32_t t = abits & ~0xfffffu;                      // three mantissa bits kept
+    if (away && t != abits) t += 0x100000u;              // next format value; a carry moves to the next binade
+    mag = (t >> 20) - (120u << 3);                       // exponent field = float exponent - 127 + 7
+  }
+  return (sign << 7) | mag;
+}
+
+// One 16-byte unit of the 8-bit bounds: k_min of 8 channels (rounded down), then k_max (rounded up).
+__device__ __forceinline__ void store_box8_unit(uint8_t* p, const float (&mn)[8], const float (&mx)[8]) {
+  uint4 u;
+  u.x = f32_to_e4m3_directed<false>(mn[0]) | (f32_to_e4m3_directed<false>(mn[1]) << 8) |
+        (f32_to_e4m3_directed<false>(mn[2]) << 16) | (f32_to_e4m3_directed<false>(mn[3]) << 24);
+  u.y = f32_to_e4m3_directed<false>(mn[4]) | (f32_to_e4m3_directed<false>(mn[5]) << 8) |
+        (f32_to_e4m3_directed<false>(mn[6]) << 16) | (f32_to_e4m3_directed<false>(mn[7]) << 24);
+  u.z = f32_to_e4m3_directed<true>(mx[0]) | (f32_to_e4m3_directed<true>(mx[1]) << 8) |
+        (f32_to_e4m3_directed<true>(mx[2]) << 16) | (f32_to_e4m3_directed<true>(mx[3]) << 24);
+  u.w = f32_to_e4m3_directed<true>(mx[4]) | (f32_to_e4m3_directed<true>(mx[5]) << 8) |
+        (f32_to_e4m3_directed<true>(mx[6]) << 16) | (f32_to_e4m3_directed<true>(mx[7]) << 24);
+  *reinterpret_cast<uint4*>(p) = u;
+}
+
 // ---- DPP cross-lane moves (no LDS traffic) -------------------------------------------------
 template <int CTRL> __device__ __forceinline__ float dpp_move(float v) {
   return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));

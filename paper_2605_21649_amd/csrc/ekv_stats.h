@@ -11,7 +11,8 @@ namespace ekv {
 template <typename T, int PT>   // PT = compile-time page size (all row loads issued as one batch), 0 = runtime
 __device__ __forceinline__ void page_stats_wave(const T* __restrict__ kpage, int cnt, int P_rt,
                                                 const T* __restrict__ ov_row, int ov_slot,
-                                                T* __restrict__ box_out, T* __restrict__ gauss_out) {
+                                                T* __restrict__ box_out, T* __restrict__ gauss_out,
+                                                uint8_t* __restrict__ box8_out) {
   const int P = PT ? PT : P_rt;
   const int lane = threadIdx.x & 63;
   const int r = lane >> 4, c = lane & 15;
@@ -68,6 +69,7 @@ __device__ __forceinline__ void page_stats_wave(const T* __restrict__ kpage, int
     store8<T>(box_out + kD + 8 * c, mx);
     store8<T>(gauss_out + 8 * c, avg);
     store8<T>(gauss_out + kD + 8 * c, sd);
+    if (box8_out != nullptr) store_box8_unit(box8_out + 16 * c, mn, mx);
   }
 }
 
@@ -78,7 +80,8 @@ template <typename T, int PT>
 __device__ __forceinline__ void append_token_wave(T* __restrict__ k_pool, T* __restrict__ v_pool,
                                                   const int32_t* __restrict__ block_table, int pos,
                                                   const T* __restrict__ k_new, const T* __restrict__ v_new,
-                                                  T* __restrict__ box, T* __restrict__ gauss, int b, int h, int Hkv,
+                                                  T* __restrict__ box, T* __restrict__ gauss,
+                                                  uint8_t* __restrict__ box8, int b, int h, int Hkv,
                                                   int P, int Mmax, int n_phys) {
   const int p = pos / P, slot = pos - p * P;
   if (pos < 0 || p >= Mmax) return;            // no room: validated against on the host where possible
@@ -97,7 +100,8 @@ __device__ __forceinline__ void append_token_wave(T* __restrict__ k_pool, T* __r
     store8<T>(v_pool + page_off + (size_t)slot * kD + 8 * c, x);
   }
   const size_t rec = (((size_t)b * Hkv + h) * Mmax + p) * 2 * kD;
-  page_stats_wave<T, PT>(k_pool + page_off, slot + 1, P, knew, slot, box + rec, gauss + rec);
+  page_stats_wave<T, PT>(k_pool + page_off, slot + 1, P, knew, slot, box + rec, gauss + rec,
+                         box8 != nullptr ? box8 + rec : nullptr);       // 256 bytes per page in either array
 }
 
 }  // namespace ekv

@@ -25,28 +25,33 @@ constexpr int kScoreTile = 64;    // pages per workgroup: 4 wavefronts x 16 page
 // mode 0: plain scoring; 1: append, then score; 2: score with n_b + 1 only (a second launch of the call).
 struct ScoreAppend {
   void* k_pool; void* v_pool; const int32_t* block_table; const void* k_new; const void* v_new;
-  void* box_stats; void* gauss_stats;
+  void* box_stats; void* gauss_stats; void* box8_stats;
   int n_phys, mode;
 };
 
 // Returns the sequence length the kernel scores with.
-template <typename T>
-__device__ __forceinline__ int fused_append(const ScoreAppend& ap, int n, int b, int h, int tile0, int Hkv, int P,
-                                            int Mmax) {
+// APPEND = false instantiations carry no append code at all (modes 0 and 2): their register count, and with it
+// the occupancy of the stream, is that of the scoring loop alone.
+template <typename T, bool APPEND>
+__device__ __forceinline__ int fused_append(const ScoreAppend& ap, int n, int b, int h, int tile0, int tile,
+                                            int Hkv, int P, int Mmax) {
   if (ap.mode == 0) return n;
   const int p_new = n / P;
   if (n < 0 || p_new >= Mmax) return n;             // no room: nothing is appended
-  if (ap.mode == 1 && p_new >= tile0 && p_new < tile0 + kScoreTile) {       // workgroup-uniform
+  if (APPEND && ap.mode == 1 && p_new >= tile0 && p_new < tile0 + tile) {    // workgroup-uniform
     if (threadIdx.x < 64) {
       if (P == 16)                                    // same instantiations as the append kernel
         append_token_wave<T, 16>((T*)ap.k_pool, (T*)ap.v_pool, ap.block_table, n, (const T*)ap.k_new,
-                                 (const T*)ap.v_new, (T*)ap.box_stats, (T*)ap.gauss_stats, b, h, Hkv, P, Mmax, ap.n_phys);
+                                 (const T*)ap.v_new, (T*)ap.box_stats, (T*)ap.gauss_stats, (uint8_t*)ap.box8_stats,
+                                 b, h, Hkv, P, Mmax, ap.n_phys);
       else if (P == 32)
         append_token_wave<T, 32>((T*)ap.k_pool, (T*)ap.v_pool, ap.block_table, n, (const T*)ap.k_new,
-                                 (const T*)ap.v_new, (T*)ap.box_stats, (T*)ap.gauss_stats, b, h, Hkv, P, Mmax, ap.n_phys);
+                                 (const T*)ap.v_new, (T*)ap.box_stats, (T*)ap.gauss_stats, (uint8_t*)ap.box8_stats,
+                                 b, h, Hkv, P, Mmax, ap.n_phys);
       else
         append_token_wave<T, 0>((T*)ap.k_pool, (T*)ap.v_pool, ap.block_table, n, (const T*)ap.k_new,
-                                (const T*)ap.v_new, (T*)ap.box_stats, (T*)ap.gauss_stats, b, h, Hkv, P, Mmax, ap.n_phys);
+                                (const T*)ap.v_new, (T*)ap.box_stats, (T*)ap.gauss_stats, (uint8_t*)ap.box8_stats,
+                                b, h, Hkv, P, Mmax, ap.n_phys);
     }
     // the statistics rows written above are read below by the other wavefronts of this workgroup only (same
     // compute unit): a workgroup-scope fence is enough; a device-scope one would write back the whole L2
@@ -92,29 +97,47 @@ __device__ __forceinline__ float diag_quad_sum(const f32x4_t& c, int kq) {
   return v;
 }
 
-template <int G, bool GAUSS>
+// Eight E4M3 codes (two dwords) -> eight bf16 values (exact: every E4M3 value is a bf16 value).
+__device__ __forceinline__ uint4 e4m3x8_to_bf16x8(uint32_t lo, uint32_t hi) {
+  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+  uint4 r;
+  r.x = __builtin_bit_cast(uint32_t, (bf16x2_t)__builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(lo, 1.0f, false));
+  r.y = __builtin_bit_cast(uint32_t, (bf16x2_t)__builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(lo, 1.0f, true));
+  r.z = __builtin_bit_cast(uint32_t, (bf16x2_t)__builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, 1.0f, false));
+  r.w = __builtin_bit_cast(uint32_t, (bf16x2_t)__builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, 1.0f, true));
+  return r;
+}
+
+enum : int { kKindBox = 0, kKindGauss = 1, kKindBox8 = 2 };
+// pages per workgroup: 4 wavefronts x 16 pages of 512-byte records, or x 32 pages of 256-byte 8-bit records
+// (the same bytes per wavefront; 64 pages per wavefront was measured and is no faster)
+__host__ __device__ constexpr int score_tile(int kind) { return kind == kKindBox8 ? 2 * kScoreTile : kScoreTile; }
+
+template <int G, int KIND, bool APPEND>
 __global__ __launch_bounds__(256) void score_pages_mfma_kernel(const bf16_t* __restrict__ q,
-                                                               const bf16_t* __restrict__ stats,
+                                                               const void* __restrict__ stats_any,
                                                                const int32_t* __restrict__ seq_lens,
                                                                float* __restrict__ out0,   // box or mu
                                                                float* __restrict__ out1,   // sigma (GAUSS)
                                                                int Hkv, int P, int Mmax, float scale,
                                                                int group_max, const ScoreAppend ap) {
+  constexpr bool GAUSS = KIND == kKindGauss, BOX8 = KIND == kKindBox8;
+  constexpr int TILE = score_tile(KIND), NT = TILE / 16;   // NT groups of 4 pages per wavefront
   constexpr int NSET = (G + 3) / 4;                 // column sets of 4 heads
-  __shared__ float stage[2][G][kScoreTile];
+  __shared__ float stage[2][G][TILE];
   const int b = blockIdx.z, h = blockIdx.y;
   // with a fused append the tiles are taken from the end, so that the workgroup that appends (the last
   // page's) is dispatched first and its extra latency hides behind the stream of the others
-  const int tile0 = (ap.mode == 1 ? gridDim.x - 1 - blockIdx.x : blockIdx.x) * kScoreTile;
+  const int tile0 = (ap.mode == 1 ? gridDim.x - 1 - blockIdx.x : blockIdx.x) * TILE;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int m = lane & 15, j = lane >> 4;           // MFMA row / column index, K group
   const int pg = m >> 2, kq = m & 3;                // as a row: page of the group, channel quarter
-  const int n = fused_append<bf16_t>(ap, seq_lens[b], b, h, tile0, Hkv, P, Mmax);
+  const int n = fused_append<bf16_t, APPEND>(ap, seq_lens[b], b, h, tile0, TILE, Hkv, P, Mmax);
   const int M = (n + P - 1) / P;
   const int Hq = Hkv * G;
   if (tile0 >= M) {                                  // tile past the end of the sequence: no statistics are read
-    for (int idx = threadIdx.x; idx < (group_max ? 1 : G) * kScoreTile; idx += 256) {
-      const int g = idx / kScoreTile, p = tile0 + idx - g * kScoreTile;
+    for (int idx = threadIdx.x; idx < (group_max ? 1 : G) * TILE; idx += 256) {
+      const int g = idx / TILE, p = tile0 + idx - g * TILE;
       if (p >= Mmax) continue;
       const size_t o = group_max ? ((size_t)b * Hkv + h) * Mmax + p : ((size_t)b * Hq + h * G + g) * Mmax + p;
       out0[o] = -INFINITY;
@@ -141,39 +164,56 @@ __global__ __launch_bounds__(256) void score_pages_mfma_kernel(const bf16_t* __r
     }
   }
 
-  const int pw0 = tile0 + w * 16;                    // first page of this wavefront
-  const bf16_t* base = stats + (((size_t)b * Hkv + h) * Mmax) * 2 * kD + (kq * 4 + j) * 8;
-  uint4 a[4][2];
+  const int pw0 = tile0 + w * (TILE / 4);            // first page of this wavefront
+  uint4 a[BOX8 ? 1 : NT][2];
+  uint4 raw[BOX8 ? NT : 1];
+  if constexpr (BOX8) {
+    // one 16-byte unit per lane and page: k_min and k_max codes of the lane's 8 channels
+    const uint8_t* base8 = (const uint8_t*)stats_any + (((size_t)b * Hkv + h) * Mmax) * 256 + (kq * 4 + j) * 16;
 #pragma unroll
-  for (int t = 0; t < 4; ++t) {
-    const int p = min(pw0 + 4 * t + pg, M - 1);     // clamped: pages past the end are masked on output
+    for (int t = 0; t < NT; ++t) {
+      const int p = min(pw0 + 4 * t + pg, M - 1);   // clamped: pages past the end are masked on output
+      raw[t] = *reinterpret_cast<const uint4*>(base8 + (size_t)p * 256);
+    }
+  } else {
+    const bf16_t* base = (const bf16_t*)stats_any + (((size_t)b * Hkv + h) * Mmax) * 2 * kD + (kq * 4 + j) * 8;
 #pragma unroll
-    for (int s = 0; s < 2; ++s) a[t][s] = *reinterpret_cast<const uint4*>(base + ((size_t)p * 2 + s) * kD);
+    for (int t = 0; t < NT; ++t) {
+      const int p = min(pw0 + 4 * t + pg, M - 1);   // clamped: pages past the end are masked on output
+#pragma unroll
+      for (int s = 0; s < 2; ++s) a[t][s] = *reinterpret_cast<const uint4*>(base + ((size_t)p * 2 + s) * kD);
+    }
   }
 #pragma unroll
-  for (int t = 0; t < 4; ++t) {
-    const int pt = w * 16 + 4 * t + j;               // result row group j = page of the group
+  for (int t = 0; t < NT; ++t) {
+    const int pt = w * (TILE / 4) + 4 * t + j;       // result row group j = page of the group
+    const int ta = BOX8 ? 0 : t;
+    if constexpr (BOX8) {                            // codes -> bf16 just before use (exact)
+      a[0][0] = e4m3x8_to_bf16x8(raw[t].x, raw[t].y);
+      a[0][1] = e4m3x8_to_bf16x8(raw[t].z, raw[t].w);
+    }
 #pragma unroll
     for (int s = 0; s < NSET; ++s) {
       const int g = 4 * s + (m >> 2);
       const f32x4_t zero = {0.f, 0.f, 0.f, 0.f};
       if (GAUSS) {
-        const f32x4_t c0 = mfma_bf16(a[t][0], b0[s], zero);
-        f32x4_t c1 = mfma_bf16(a[t][1], b1[s], zero);
-        c1 = mfma_bf16(a[t][1], b2[s], c1);
+        const f32x4_t c0 = mfma_bf16(a[ta][0], b0[s], zero);
+        f32x4_t c1 = mfma_bf16(a[ta][1], b1[s], zero);
+        c1 = mfma_bf16(a[ta][1], b2[s], c1);
         const float mu = diag_quad_sum(c0, kq), var = diag_quad_sum(c1, kq);
         if (kq == 0 && g < G) { stage[0][g][pt] = scale * mu; stage[1][g][pt] = scale * sqrtf(fmaxf(var, 0.f)); }
       } else {
-        f32x4_t c0 = mfma_bf16(a[t][0], b0[s], zero);
-        c0 = mfma_bf16(a[t][1], b1[s], c0);
+        f32x4_t c0 = mfma_bf16(a[ta][0], b0[s], zero);
+        c0 = mfma_bf16(a[ta][1], b1[s], c0);
         const float v = diag_quad_sum(c0, kq);
-        if (kq == 0 && g < G) stage[0][g][pt] = scale * v;
+        // a bound the 8-bit format could not hold is NaN: such a page scores +inf (always selected)
+        if (kq == 0 && g < G) stage[0][g][pt] = (BOX8 && v != v) ? INFINITY : scale * v;
       }
     }
   }
   __syncthreads();
   if (group_max) {                                   // one score per page and KV head: the group's maximum
-    for (int pt = threadIdx.x; pt < kScoreTile; pt += 256) {
+    for (int pt = threadIdx.x; pt < TILE; pt += 256) {
       const int p = tile0 + pt;
       if (p >= Mmax) continue;
       float v = stage[0][0][pt];
@@ -183,8 +223,8 @@ __global__ __launch_bounds__(256) void score_pages_mfma_kernel(const bf16_t* __r
     }
     return;
   }
-  for (int idx = threadIdx.x; idx < G * kScoreTile; idx += 256) {
-    const int g = idx / kScoreTile, pt = idx - g * kScoreTile;
+  for (int idx = threadIdx.x; idx < G * TILE; idx += 256) {
+    const int g = idx / TILE, pt = idx - g * TILE;
     const int p = tile0 + pt;
     if (p >= Mmax) continue;
     const size_t o = ((size_t)b * Hq + h * G + g) * Mmax + p;
@@ -195,7 +235,7 @@ __global__ __launch_bounds__(256) void score_pages_mfma_kernel(const bf16_t* __r
 }
 
 // float32 statistics: one wavefront step = two page records, 32 lanes x 8 channels each.
-template <int G, bool GAUSS>
+template <int G, bool GAUSS, bool APPEND>
 __global__ __launch_bounds__(256) void score_pages_f32_kernel(const float* __restrict__ q,
                                                               const float* __restrict__ stats,
                                                               const int32_t* __restrict__ seq_lens,
@@ -208,7 +248,7 @@ __global__ __launch_bounds__(256) void score_pages_f32_kernel(const float* __res
   const int tile0 = (ap.mode == 1 ? gridDim.x - 1 - blockIdx.x : blockIdx.x) * kScoreTile;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int half = lane >> 5, which = (lane >> 4) & 1, c = lane & 15;
-  const int n = fused_append<float>(ap, seq_lens[b], b, h, tile0, Hkv, P, Mmax);
+  const int n = fused_append<float, APPEND>(ap, seq_lens[b], b, h, tile0, kScoreTile, Hkv, P, Mmax);
   const int M = (n + P - 1) / P;
   const int Hq = Hkv * G;
   if (tile0 >= M) {                                  // tile past the end of the sequence: no statistics are read
@@ -276,8 +316,8 @@ __global__ __launch_bounds__(256) void score_pages_f32_kernel(const float* __res
   }
 }
 
-template <int G>
-static void launch_score_G(const Dims& dm, const void* q, const ekv_stats_view& s, const int32_t* seq_lens,
+template <int G, bool APPEND>
+static void launch_score_GA(const Dims& dm, const void* q, const ekv_stats_view& s, const int32_t* seq_lens,
                            int mode, float* box, float* mu, float* sigma, hipStream_t st, const ScoreAppend& ap0) {
   dim3 grid((dm.Mmax + kScoreTile - 1) / kScoreTile, dm.Hkv, dm.B), block(256);
   const int gmax = (mode & EKV_SCORE_GROUP_MAX) ? 1 : 0;
@@ -285,29 +325,41 @@ static void launch_score_G(const Dims& dm, const void* q, const ekv_stats_view& 
   ScoreAppend ap_box = ap0, ap_gauss = ap0;
   if (ap0.mode == 1 && (mode & EKV_SCORE_BOX)) ap_gauss.mode = 2;
   if (dm.dtype == EKV_BF16) {
+    if (mode & EKV_SCORE_BOX8) {
+      dim3 grid8((dm.Mmax + score_tile(kKindBox8) - 1) / score_tile(kKindBox8), dm.Hkv, dm.B);
+      hipLaunchKernelGGL((score_pages_mfma_kernel<G, kKindBox8, APPEND>), grid8, block, 0, st, (const bf16_t*)q,
+                         (const void*)s.box8, seq_lens, box, (float*)nullptr, dm.Hkv, dm.P, dm.Mmax, dm.scale, gmax, ap_box);
+    }
     if (mode & EKV_SCORE_BOX)
-      hipLaunchKernelGGL((score_pages_mfma_kernel<G, false>), grid, block, 0, st, (const bf16_t*)q,
-                         (const bf16_t*)s.box, seq_lens, box, (float*)nullptr, dm.Hkv, dm.P, dm.Mmax, dm.scale, gmax, ap_box);
+      hipLaunchKernelGGL((score_pages_mfma_kernel<G, kKindBox, APPEND>), grid, block, 0, st, (const bf16_t*)q,
+                         (const void*)s.box, seq_lens, box, (float*)nullptr, dm.Hkv, dm.P, dm.Mmax, dm.scale, gmax, ap_box);
     if (mode & EKV_SCORE_GAUSS)
-      hipLaunchKernelGGL((score_pages_mfma_kernel<G, true>), grid, block, 0, st, (const bf16_t*)q,
-                         (const bf16_t*)s.gauss, seq_lens, mu, sigma, dm.Hkv, dm.P, dm.Mmax, dm.scale, 0, ap_gauss);
+      hipLaunchKernelGGL((score_pages_mfma_kernel<G, kKindGauss, APPEND>), grid, block, 0, st, (const bf16_t*)q,
+                         (const void*)s.gauss, seq_lens, mu, sigma, dm.Hkv, dm.P, dm.Mmax, dm.scale, 0, ap_gauss);
   } else {
     if (mode & EKV_SCORE_BOX)
-      hipLaunchKernelGGL((score_pages_f32_kernel<G, false>), grid, block, 0, st, (const float*)q,
+      hipLaunchKernelGGL((score_pages_f32_kernel<G, false, APPEND>), grid, block, 0, st, (const float*)q,
                          (const float*)s.box, seq_lens, box, (float*)nullptr, dm.Hkv, dm.P, dm.Mmax, dm.scale, gmax, ap_box);
     if (mode & EKV_SCORE_GAUSS)
-      hipLaunchKernelGGL((score_pages_f32_kernel<G, true>), grid, block, 0, st, (const float*)q,
+      hipLaunchKernelGGL((score_pages_f32_kernel<G, true, APPEND>), grid, block, 0, st, (const float*)q,
                          (const float*)s.gauss, seq_lens, mu, sigma, dm.Hkv, dm.P, dm.Mmax, dm.scale, 0, ap_gauss);
   }
+}
+
+template <int G>
+static void launch_score_G(const Dims& dm, const void* q, const ekv_stats_view& s, const int32_t* seq_lens,
+                           int mode, float* box, float* mu, float* sigma, hipStream_t st, const ScoreAppend& ap) {
+  if (ap.mode == 1) launch_score_GA<G, true>(dm, q, s, seq_lens, mode, box, mu, sigma, st, ap);
+  else launch_score_GA<G, false>(dm, q, s, seq_lens, mode, box, mu, sigma, st, ap);
 }
 
 void launch_score_pages(const Dims& dm, const void* q, const ekv_stats_view& s, const int32_t* seq_lens,
                         int mode, float* box, float* mu, float* sigma, hipStream_t st, const ekv_cache_view* append_to,
                         const void* k_new, const void* v_new) {
-  ScoreAppend ap{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0, 0};
+  ScoreAppend ap{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0, 0};
   if (append_to != nullptr)
     ap = ScoreAppend{append_to->k_pool, append_to->v_pool, append_to->block_table, k_new, v_new, s.box, s.gauss,
-                     append_to->n_phys_pages, 1};
+                     s.box8, append_to->n_phys_pages, 1};
   switch (dm.G) {
     case 1: launch_score_G<1>(dm, q, s, seq_lens, mode, box, mu, sigma, st, ap); break;
     case 2: launch_score_G<2>(dm, q, s, seq_lens, mode, box, mu, sigma, st, ap); break;

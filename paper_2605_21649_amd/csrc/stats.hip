@@ -22,7 +22,8 @@ constexpr int kStatRowBatch = 4;     // row loads in flight per lane in the bulk
 // four 256-byte segments.  `kpage` points at the page's [P][128] block; tokens [0,cnt) are valid.
 template <typename T, int PT>   // PT = compile-time page size, 0 = runtime
 __device__ __forceinline__ void page_stats_rows(const T* __restrict__ kpage, int cnt, int P_rt, bool all_full,
-                                                T* __restrict__ box_out, T* __restrict__ gauss_out) {
+                                                T* __restrict__ box_out, T* __restrict__ gauss_out,
+                                                uint8_t* __restrict__ box8_out) {
   constexpr int RB = kStatRowBatch;
   static_assert(RB == 4, "one batch = one row of each partial sum");
   const int P = PT ? PT : P_rt;
@@ -93,6 +94,7 @@ __device__ __forceinline__ void page_stats_rows(const T* __restrict__ kpage, int
   store8<T>(box_out + kD + 8 * c, mx);
   store8<T>(gauss_out + 8 * c, avg);
   store8<T>(gauss_out + kD + 8 * c, var);
+  if (box8_out != nullptr) store_box8_unit(box8_out + 16 * c, mn, mx);
 }
 
 template <typename T, int PT>
@@ -100,6 +102,7 @@ __global__ __launch_bounds__(256) void stats_build_kernel(const T* __restrict__ 
                                                           const int32_t* __restrict__ block_table,
                                                           const int32_t* __restrict__ seq_lens,
                                                           T* __restrict__ box, T* __restrict__ gauss,
+                                                          uint8_t* __restrict__ box8,
                                                           int Hkv, int P, int Mmax, int n_phys) {
   const int b = blockIdx.z, h = blockIdx.y;
   const int p = blockIdx.x * 16 + (threadIdx.x >> 4);     // 16 pages per workgroup, 4 per wavefront
@@ -113,7 +116,8 @@ __global__ __launch_bounds__(256) void stats_build_kernel(const T* __restrict__ 
   const size_t rec = (((size_t)b * Hkv + h) * Mmax + pc) * 2 * kD;
   const bool all_full = __all(cnt == P);
   if (blockIdx.x * 16 + (int)(threadIdx.x >> 6) * 4 >= M) return;      // whole wavefront past the end
-  if (p < M) page_stats_rows<T, PT>(kpage, cnt, P, all_full, box + rec, gauss + rec);
+  if (p < M) page_stats_rows<T, PT>(kpage, cnt, P, all_full, box + rec, gauss + rec,
+                                    box8 != nullptr ? box8 + rec : nullptr);   // 256 bytes per page there
 }
 
 // One wavefront per (sequence, KV head): write the new token into slot n_b and refresh its page.
@@ -124,24 +128,25 @@ __global__ __launch_bounds__(64) void stats_append_kernel(T* __restrict__ k_pool
                                                           const T* __restrict__ k_new,
                                                           const T* __restrict__ v_new,
                                                           T* __restrict__ box, T* __restrict__ gauss,
+                                                          uint8_t* __restrict__ box8,
                                                           int Hkv, int P, int Mmax, int n_phys) {
-  append_token_wave<T, PT>(k_pool, v_pool, block_table, seq_lens[blockIdx.y], k_new, v_new, box, gauss, blockIdx.y,
-                           blockIdx.x, Hkv, P, Mmax, n_phys);
+  append_token_wave<T, PT>(k_pool, v_pool, block_table, seq_lens[blockIdx.y], k_new, v_new, box, gauss, box8,
+                           blockIdx.y, blockIdx.x, Hkv, P, Mmax, n_phys);
 }
 
 template <typename T, int PT>
 static void launch_build_T(const Dims& dm, const ekv_cache_view& c, const ekv_stats_view& s, hipStream_t st) {
   dim3 grid((dm.Mmax + 15) / 16, dm.Hkv, dm.B), block(256);
   hipLaunchKernelGGL((stats_build_kernel<T, PT>), grid, block, 0, st, (const T*)c.k_pool, c.block_table, c.seq_lens,
-                     (T*)s.box, (T*)s.gauss, dm.Hkv, dm.P, dm.Mmax, c.n_phys_pages);
+                     (T*)s.box, (T*)s.gauss, (uint8_t*)s.box8, dm.Hkv, dm.P, dm.Mmax, c.n_phys_pages);
 }
 template <typename T, int PT>
 static void launch_append_T(const Dims& dm, const ekv_cache_view& c, const ekv_stats_view& s, const void* k_new,
                             const void* v_new, hipStream_t st) {
   dim3 grid(dm.Hkv, dm.B), block(64);
   hipLaunchKernelGGL((stats_append_kernel<T, PT>), grid, block, 0, st, (T*)c.k_pool, (T*)c.v_pool, c.block_table,
-                     c.seq_lens, (const T*)k_new, (const T*)v_new, (T*)s.box, (T*)s.gauss, dm.Hkv, dm.P, dm.Mmax,
-                     c.n_phys_pages);
+                     c.seq_lens, (const T*)k_new, (const T*)v_new, (T*)s.box, (T*)s.gauss, (uint8_t*)s.box8, dm.Hkv,
+                     dm.P, dm.Mmax, c.n_phys_pages);
 }
 
 void launch_stats_build(const Dims& dm, const ekv_cache_view& c, const ekv_stats_view& s, hipStream_t st) {

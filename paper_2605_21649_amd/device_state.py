@@ -40,7 +40,14 @@ class DeviceState:
         return ekv.cache_view(i["k_pool"], i["v_pool"], i["block_table"], i["seq_lens"])
 
     def stats(self):
-        return ekv.stats_view(self.box_stats, self.gauss_stats)
+        return ekv.stats_view(self.box_stats, self.gauss_stats, getattr(self, "box8_stats", None))
+
+    def enable_box8(self):
+        """Allocate the optional 8-bit bounds; from then on build/append keep them up to date."""
+        w = self.w
+        self.box8_stats = torch.zeros(w.batch, w.n_kv_heads, self.Mmax, 16, 2, 8, device=self.box.device,
+                                      dtype=torch.uint8)
+        return self.box8_stats
 
     def workspace(self, op):
         if op not in self.ws:

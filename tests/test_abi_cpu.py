@@ -117,6 +117,34 @@ def test_new_entry_points_validate_their_arguments():
                                        0x6000, 0x7000, None, 0xA000, 1024, None) == 3
 
 
+def test_eight_bit_bounds_are_validated_before_any_launch():
+    lib = ekv.load_library()
+    cfg = good_cfg()
+    mode8 = ekv.EKV_SCORE_BOX8
+    # the mode needs the buffer; it does not combine with the cache-dtype box score or the Gaussian moments
+    no8 = ekv.ekv_stats_view(0x5000, 0x6000, None)
+    assert lib.ekv_score_pages(ctypes.byref(cfg), 0x1000, ctypes.byref(no8), 0x4000, mode8, 0x7000, None, None,
+                               None) == 1
+    with8 = ekv.ekv_stats_view(0x5000, 0x6000, 0x9000)
+    for bad in (mode8 | ekv.EKV_SCORE_BOX, mode8 | ekv.EKV_SCORE_GAUSS, 16):
+        assert lib.ekv_score_pages(ctypes.byref(cfg), 0x1000, ctypes.byref(with8), 0x4000, bad, 0x7000, 0x8000,
+                                   0xA000, None) == 1
+    assert lib.ekv_score_pages(ctypes.byref(cfg), 0x1000, ctypes.byref(with8), 0x4000, mode8, None, None, None,
+                               None) == 1                               # no output
+    # 16-byte units
+    odd = ekv.ekv_stats_view(0x5000, 0x6000, 0x9004)
+    cache = ekv.ekv_cache_view(0x1000, 0x2000, 0x3000, 0x4000, 4)
+    assert lib.ekv_stats_build(ctypes.byref(cfg), ctypes.byref(cache), ctypes.byref(odd), None) == 1
+    assert lib.ekv_stats_append(ctypes.byref(cfg), ctypes.byref(cache), ctypes.byref(odd), 0x7000, None, None) == 1
+    # bf16 caches only
+    cfg32 = good_cfg(kv_dtype=ekv.EKV_F32)
+    assert lib.ekv_stats_build(ctypes.byref(cfg32), ctypes.byref(cache), ctypes.byref(with8), None) == 2
+    assert lib.ekv_score_pages(ctypes.byref(cfg32), 0x1000, ctypes.byref(with8), 0x4000, mode8, 0x7000, None, None,
+                               None) == 2
+    assert lib.ekv_append_score_pages(ctypes.byref(cfg32), ctypes.byref(cache), ctypes.byref(with8), 0x7000, None,
+                                      0x1000, mode8, 0x8000, None, None, None) == 2
+
+
 def test_bench_refuses_more_than_one_gpu():
     import subprocess
     import sys

@@ -263,3 +263,40 @@ def test_full_size_group_shared_step(fs):
         for g in range(G):
             ref = orc.entmax_attention(qs[g], K, V, W.alpha, W.score_scale, tokens)
             _check_decode(b, h * G + g, st, toks, qs[g], K, ref)
+
+
+def test_full_size_box8_topk_step(fs):
+    """The top-k step selecting on the 8-bit page bounds, as timed (append inside the scoring launch)."""
+    st, inp = fs["st"], fs["inp"]
+    k, P = fs["k_pages"], W.page_size
+    st.enable_box8()
+    ekv.ekv_stats_build(st.cfg, st.cache(), st.stats())
+    seq_prev = (inp["seq_lens"] - 1).contiguous()
+    cache_prev = ekv.cache_view(inp["k_pool"], inp["v_pool"], inp["block_table"], seq_prev)
+    ekv.ekv_append_score_pages(st.cfg, cache_prev, st.stats(), fs["k_new"], fs["v_new"], inp["q"],
+                               ekv.EKV_SCORE_BOX8, st.box, None, None)
+    ekv.ekv_select_topk(st.cfg, st.box, inp["seq_lens"], k, st.page_idx, st.n_sel,
+                        st.workspace(ekv.EKV_OP_SELECT_TOPK))
+    toks = torch.full((W.batch, W.n_q_heads, 4096), -1, dtype=torch.int32, device=st.box.device)
+    ekv.ekv_decode_sparse(st.cfg, inp["q"], st.cache(), st.page_idx, st.n_sel, st.out, st.tau, st.supp,
+                          st.workspace(ekv.EKV_OP_DECODE_SPARSE), extras=ekv.decode_extras(support_tokens=toks))
+    torch.cuda.synchronize()
+    idx, ns = st.page_idx.cpu().numpy(), st.n_sel.cpu().numpy()
+    codes = st.box8_stats.cpu().view(torch.float8_e4m3fn).to(torch.float32).numpy().astype(np.float64)
+    for (b, hq) in HEADS:
+        h = hq // W.group
+        q, K, V = fs["cpu"][(b, hq)]
+        kmin, kmax, *_ = orc.page_stats(K, P)
+        lo8, hi8 = orc.box8_stats(kmin, kmax)
+        assert np.array_equal(codes[b, h, :, :, 0, :].reshape(-1, 128), lo8)
+        assert np.array_equal(codes[b, h, :, :, 1, :].reshape(-1, 128), hi8)
+        s8 = orc.box8_scores(q, lo8, hi8, W.score_scale)
+        got = st.box[b, hq].cpu().numpy()
+        assert np.max(np.abs(got - s8) / np.maximum(1.0, np.abs(s8))) <= 1e-5
+        pages, cut_in, cut_out = orc.topk_pages(s8, k)
+        ok, bad = sets_equal_up_to_cut(idx[b, hq, : ns[b, hq]], pages, s8, [cut_in, cut_out], 1e-5 * max(1.0, abs(cut_in)))
+        assert ok, (b, hq, bad)
+        if set(idx[b, hq, : ns[b, hq]].tolist()) == set(pages.tolist()):
+            ref = orc.entmax_attention(q, K, V, W.alpha, W.score_scale, orc.pages_to_tokens(pages, P, K.shape[0]))
+            _check_decode(b, hq, st, toks, q, K, ref)
+    del st.box8_stats                                  # the other tests of this module run without it
