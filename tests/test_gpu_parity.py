@@ -932,6 +932,11 @@ SHAPES = [
     synth.C1.scaled(name="C1-f32-p4-b3", batch=3, context=1024, ragged=1, page_size=4, n_q_heads=2, n_kv_heads=1,
                     scale=0.5 / math.sqrt(128.0)),
     synth.C5.scaled(name="C5-p32-g2-b2", batch=2, context=4096, ragged=31, n_q_heads=4, n_kv_heads=2, alpha=1.25),
+    # page sizes that do not divide 64: a group of the decode's score pass is 5 pages of 12 (60 tokens), 2 of 24
+    synth.C2.scaled(name="C2-p12-g2", context=12 * 260, ragged=7, page_size=12, n_q_heads=4, n_kv_heads=2),
+    synth.C2.scaled(name="C2-p24-g4", context=24 * 150, ragged=23, page_size=24, n_q_heads=8, n_kv_heads=2),
+    synth.C1.scaled(name="C1-f32-p20", context=20 * 120, ragged=19, page_size=20, n_q_heads=2, n_kv_heads=2,
+                    scale=0.5 / math.sqrt(128.0)),
 ]
 
 
