@@ -399,6 +399,16 @@ def main():
         b.record()
         torch.cuda.synchronize()
         extras["plain_copy_GBps_measured"] = round(2 * src.numel() * 4 / (a.elapsed_time(b) * 1e-3 / 5) / 1e9, 1)
+        # ... and what a plain read-only kernel reaches (torch's reduction over the same 1 GiB)
+        for _ in range(2):
+            src.sum()
+        a, b = R.ev(), R.ev()
+        a.record()
+        for _ in range(5):
+            src.sum()
+        b.record()
+        torch.cuda.synchronize()
+        extras["plain_read_torch_sum_GBps_measured"] = round(src.numel() * 4 / (a.elapsed_time(b) * 1e-3 / 5) / 1e9, 1)
         del src, dst
         side = max(10, args.steps // 4)
         if R.fused_append:                                     # the same step with the append as its own launch
