@@ -33,15 +33,21 @@ __device__ __forceinline__ void page_stats_wave(const T* __restrict__ kpage, int
     }
   };
   if constexpr (PT != 0) {
-    float x[PT / 4][8];
+    // the whole page in flight at once, kept in storage format until it is consumed (registers: this
+    // function also runs inside the scoring kernels, whose occupancy its register count would set)
+    Raw8<T> raw[PT / 4];
 #pragma unroll
     for (int s = 0; s < PT / 4; ++s) {
       const int row = 4 * s + r;
       const int rc = row < cnt ? row : 0;
-      load8<T>((ov_row != nullptr && rc == ov_slot ? ov_row : kpage + (size_t)rc * kD) + 8 * c, x[s]);
+      load_raw8((ov_row != nullptr && rc == ov_slot ? ov_row : kpage + (size_t)rc * kD) + 8 * c, raw[s]);
     }
 #pragma unroll
-    for (int s = 0; s < PT / 4; ++s) accumulate(x[s], 4 * s + r < cnt);
+    for (int s = 0; s < PT / 4; ++s) {
+      float x[8];
+      widen8(raw[s], x);
+      accumulate(x, 4 * s + r < cnt);
+    }
   } else {
     for (int t0 = 0; t0 < P; t0 += kRowsPerWave) {
       const int row = t0 + r;
