@@ -25,13 +25,16 @@ pytestmark = pytest.mark.gpu
 SEED = 4000                     # the benchmark's
 BUDGET, CAP_FRAC = 0.02, 0.04   # the benchmark's
 # sampled (sequence, query head) units
-UNITS = {"C4": [(0, 1), (0, 10), (0, 20), (0, 31)], "C3": [(0, 3), (1, 12), (2, 21), (3, 30)]}
+UNITS = {"C4": [(0, 1), (0, 10), (0, 20), (0, 31)], "C3": [(0, 3), (1, 12), (2, 21), (3, 30)], "4M": [(0, 0), (0, 1)]}
+# beyond the benchmark: one KV head of 4 194 304 tokens (262 144 pages) shared by two query heads -- 64 slices
+# in the top-k, 128 in the dense decode's filter, row offsets past 2^24
+BIG = synth.C4.scaled(name="C4-4M-1kv", context=4 * 1048576, n_q_heads=2, n_kv_heads=1)
 
 
-@pytest.fixture(scope="module", params=["C4", "C3"])
+@pytest.fixture(scope="module", params=["C4", "C3", "4M"])
 def fs(request):
     global W, HEADS
-    W = synth.WORKLOADS[request.param]
+    W = BIG if request.param == "4M" else synth.WORKLOADS[request.param]
     HEADS = UNITS[request.param]
     dev = torch.device("cuda")
     inp = synth.make_inputs(W, SEED, device=dev)
