@@ -29,8 +29,8 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 # FETCH_SIZE + WRITE_SIZE of one score_pages launch at C4 (rocprofv3 --pmc, scaled by a plain copy of known
-# size; see profiles/bench_topk_step_C4.md): 256.17 MiB read + 8.01 MiB written
-PMC_TRAFFIC_SCORE_PAGES_C4 = int((256.17 + 8.01) * 1024 * 1024)
+# size; see profiles/bench_topk_step_C4.md, the instantiation without the append): 256.09 MiB read + 8.00 MiB written
+PMC_TRAFFIC_SCORE_PAGES_C4 = int((256.09 + 8.00) * 1024 * 1024)
 
 # the append runs inside the scoring launch (ekv_append_score_pages) unless --two-launch-append is given
 STAGE_NAMES = {"topk": ["append_own_launch", "append+score_box", "select_topk", "decode_sparse"],
