@@ -440,6 +440,17 @@ def main():
         extras["speedup_gauss_vs_dense"] = round(dense_us / us_g, 2)
         # dropped mass / support recall of the top-k selection against the dense threshold (GPU side outputs)
         kept_mass = torch.zeros_like(st0.tau); kept_supp = torch.zeros_like(st0.supp)
+        # ... first of the Gaussian-aware selection (adaptive number of pages per head)
+        R.step_gauss(st0)
+        ekv.ekv_decode_sparse(st0.cfg, st0.inp["q"], st0.cache(), st0.page_idx, st0.n_sel, st0.out, st0.tau,
+                              st0.supp, st0.ws_sparse,
+                              extras=ekv.decode_extras(tau_ref=tau_f, kept_mass_ref=kept_mass, kept_supp_ref=kept_supp))
+        torch.cuda.synchronize()
+        extras["gauss_quality"] = {
+            "pages_per_head_mean": float(st0.n_sel.float().mean()), "pages_per_head_max": int(st0.n_sel.max()),
+            "delta_mean": round(float((1.0 - kept_mass).mean()), 6),
+            "rho_mean": round(float((kept_supp.float() / supp_f.float()).mean()), 4),
+            "R_mean": round(float(((st0.out - out_f).norm(dim=-1) / out_f.norm(dim=-1)).mean()), 6)}
         for frac in (0.01, 0.02, 0.04):
             kp = max(1, int(math.ceil(frac * M)))
             ekv.ekv_select_topk(st0.cfg, st0.box, st0.inp["seq_lens"], kp, st0.page_idx, st0.n_sel, st0.ws_topk)
