@@ -469,6 +469,18 @@ def main():
                 "delta_mean": round(float((1 - kept_mass).mean()), 6),
                 "rho_mean": round(float((kept_supp.float() / supp_f.float()).mean()), 4),
                 "R_mean": round(float(Rerr), 6)}
+        # throughput with two independent steps in flight (two sequences or layers: rotating copies here) on two
+        # streams: the latency-bound selection and solve of one run under the HBM-bound streams of the other
+        sA, sB = torch.cuda.Stream(), torch.cuda.Stream()
+        def two_in_flight(nsteps):
+            for i in range(nsteps // 2):
+                with torch.cuda.stream(sA): R.step_topk(copies[(2 * i) % len(copies)])
+                with torch.cuda.stream(sB): R.step_topk(copies[(2 * i + 1) % len(copies)])
+        torch.cuda.synchronize()
+        two_in_flight(20); torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        two_in_flight(2 * side); torch.cuda.synchronize()
+        extras["topk_two_independent_steps_in_flight_us_per_step"] = round((time.perf_counter() - t0) / (2 * side) * 1e6, 2)
         us_gr, stage_gr, _ = R.run_timed(R.step_group, side, 5)
         extras["group_shared_step_us"] = round(us_gr, 2)
         extras["group_shared_stage_us"] = {nm: round(float(v), 2) for nm, v in

@@ -76,10 +76,16 @@ typedef struct {
   int32_t max_pages_per_seq; /* Mmax: row length of block_table and of the per-page score arrays   */
   int32_t max_sel_pages;     /* cap: row length of page_idx; also sizes the decode calls' launch   */
                              /* grid, so keep it near what the selectors return                    */
+  int32_t pool_kv_heads;     /* KV heads per physical page of the pools; 0 means n_kv_heads.  A     */
+                             /* config may cover only heads [h0, h0 + n_kv_heads) of a cache with   */
+                             /* more heads (to run independent head groups on separate streams):    */
+                             /* set this to the cache's head count, pass k_pool / v_pool advanced   */
+                             /* by h0*P*d elements, and every [B][H..] array restricted to those     */
+                             /* heads (contiguous slices when batch == 1)                           */
 } ekv_config;
 
 /* Paged KV cache (paper Sec. 4.2: block layout of PagedAttention).  Physical page `phys` of KV head h
- * is the contiguous block pool[((phys*Hkv + h)*P + t)*d + i], t < P, i < d, element type kv_dtype.
+ * is the contiguous block pool[((phys*pool_kv_heads + h)*P + t)*d + i], t < P, i < d, element type kv_dtype.
  * block_table[b*Mmax + p] = physical page of logical page p of sequence b (0 <= phys < n_phys_pages;
  * entries with p >= M_b may hold anything: what is read from them is clamped into range and masked).  seq_lens[b] = n_b >= 1. */
 typedef struct {

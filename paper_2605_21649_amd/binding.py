@@ -31,7 +31,7 @@ _STATUS_CALLS = EXPORTS[:12]      # entry points that return ekv_status
 class ekv_config(ctypes.Structure):
     _fields_ = [("batch", c_int32), ("n_q_heads", c_int32), ("n_kv_heads", c_int32), ("head_dim", c_int32),
                 ("page_size", c_int32), ("kv_dtype", c_int32), ("alpha", c_float), ("scale", c_float),
-                ("max_pages_per_seq", c_int32), ("max_sel_pages", c_int32)]
+                ("max_pages_per_seq", c_int32), ("max_sel_pages", c_int32), ("pool_kv_heads", c_int32)]
 
 
 class ekv_cache_view(ctypes.Structure):
@@ -116,14 +116,23 @@ def _stream(stream):
 
 
 def make_config(batch, n_q_heads, n_kv_heads, head_dim, page_size, kv_dtype, alpha, scale, max_pages_per_seq,
-                max_sel_pages):
+                max_sel_pages, pool_kv_heads=0):
     dt = {"f32": EKV_F32, "bf16": EKV_BF16}.get(kv_dtype, kv_dtype)
     return ekv_config(batch, n_q_heads, n_kv_heads, head_dim, page_size, dt, alpha, scale, max_pages_per_seq,
-                      max_sel_pages)
+                      max_sel_pages, pool_kv_heads)
 
 
 def cache_view(k_pool, v_pool, block_table, seq_lens):
     return ekv_cache_view(_ptr(k_pool), _ptr(v_pool), _ptr(block_table), _ptr(seq_lens), k_pool.shape[0])
+
+
+def cache_view_heads(k_pool, v_pool, block_table, seq_lens, first_kv_head):
+    """Cache view of the KV heads from `first_kv_head` on (pools [n_phys][Hkv][P][d]): the pool pointers are
+    advanced to that head; use it with a config whose pool_kv_heads is the cache's head count."""
+    off = first_kv_head * k_pool.shape[2] * k_pool.shape[3] * k_pool.element_size()
+    assert k_pool.is_contiguous() and v_pool.is_contiguous()
+    return ekv_cache_view(k_pool.data_ptr() + off, v_pool.data_ptr() + off, _ptr(block_table), _ptr(seq_lens),
+                          k_pool.shape[0])
 
 
 def stats_view(box, gauss, box8=None):

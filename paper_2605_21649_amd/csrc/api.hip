@@ -27,8 +27,10 @@ static ekv_status make_dims(const ekv_config* cfg, Dims& dm) {
   if (G != 1 && G != 2 && G != 4 && G != 8) return EKV_ERR_UNSUPPORTED;
   if ((int64_t)cfg->max_pages_per_seq * cfg->page_size > (int64_t)1 << 30) return EKV_ERR_UNSUPPORTED;
   if (cfg->max_sel_pages > cfg->max_pages_per_seq) return EKV_ERR_INVALID_ARG;
+  if (cfg->pool_kv_heads < 0 || (cfg->pool_kv_heads > 0 && cfg->pool_kv_heads < cfg->n_kv_heads)) return EKV_ERR_INVALID_ARG;
   dm.B = cfg->batch; dm.Hq = cfg->n_q_heads; dm.Hkv = cfg->n_kv_heads; dm.G = G; dm.P = cfg->page_size;
   dm.Mmax = cfg->max_pages_per_seq; dm.cap = cfg->max_sel_pages; dm.dtype = cfg->kv_dtype;
+  dm.HkvPool = cfg->pool_kv_heads > 0 ? cfg->pool_kv_heads : cfg->n_kv_heads;
   dm.alpha = cfg->alpha; dm.scale = cfg->scale;
   dm.a = cfg->alpha - 1.0f;
   dm.beta = 1.0f / dm.a;
@@ -45,9 +47,9 @@ static ekv_status check_cache(const ekv_cache_view* c, bool need_v) {
   return EKV_OK;
 }
 
-// V rows are addressed by a 32-bit row index (phys*Hkv + hkv)*P + tok inside the decode kernels.
+// V rows are addressed by a 32-bit row index (phys*HkvPool + hkv)*P + tok inside the decode kernels.
 static ekv_status check_pool_rows(const ekv_cache_view* c, const Dims& dm) {
-  if ((int64_t)c->n_phys_pages * dm.Hkv * dm.P > (int64_t)0x7fffffff) return EKV_ERR_UNSUPPORTED;
+  if ((int64_t)c->n_phys_pages * dm.HkvPool * dm.P > (int64_t)0x7fffffff) return EKV_ERR_UNSUPPORTED;
   return EKV_OK;
 }
 
@@ -89,7 +91,7 @@ static ekv_status check_box8(const Dims& dm, const ekv_stats_view* stats, bool r
 
 extern "C" {
 
-int32_t ekv_version(void) { return 101; }
+int32_t ekv_version(void) { return 102; }
 
 int32_t ekv_last_hip_error(void) { return g_last_hip_error; }
 

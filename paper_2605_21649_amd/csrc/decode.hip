@@ -41,6 +41,7 @@ struct ScoreArgs {
   int Hq, Hkv, P, Mmax, cap, n_chunks_max, n_phys;
   size_t zstride;
   float zscale;
+  int HkvPool;
 };
 
 // A wavefront covers kGroupsPerWave groups of pmax_pages(P) consecutive page slots (64 tokens when P
@@ -82,7 +83,7 @@ __global__ __launch_bounds__(kScoreThreads) void decode_scores_valu_kernel(const
       if (slot >= n_slots) break;
       const int lp = clampi(DENSE ? slot : A.page_idx[(size_t)unit * A.cap + slot], 0, A.Mmax - 1);
       const int phys = clampi(A.block_table[(size_t)b * A.Mmax + lp], 0, A.n_phys - 1);
-      const T* kpage = k_pool + ((size_t)phys * Hkv + hkv) * P * kD + 8 * c;
+      const T* kpage = k_pool + ((size_t)phys * A.HkvPool + hkv) * P * kD + 8 * c;
       for (int s0 = 0; s0 < P / 4; s0 += 16) {          // 16 steps (64 tokens) per sweep of the c lanes
         float zkeep[G];
 #pragma unroll
@@ -162,7 +163,7 @@ __global__ __launch_bounds__(kScoreThreads) void decode_scores_mfma_kernel(const
   uint4 a[SW][STEPS];
 #pragma unroll
   for (int i = 0; i < SW; ++i) {
-    const bf16_t* kpage = k_pool + ((size_t)physs[i] * Hkv + hkv) * PT * kD + lane_off;
+    const bf16_t* kpage = k_pool + ((size_t)physs[i] * A.HkvPool + hkv) * PT * kD + lane_off;
 #pragma unroll
     for (int s = 0; s < STEPS; ++s) a[i][s] = *reinterpret_cast<const uint4*>(kpage + (size_t)s * 4 * kD);
   }
@@ -541,6 +542,7 @@ struct SolveArgs {
   // results of the filter passes (null for short rows)
   const int32_t* fcount; const float* frow; const float* flist_u; const int32_t* flist_pos; int n_slices_max;
   int grouped;
+  int HkvPool;
 };
 
 // V row index (phys*Hkv + hkv)*P + tok of candidate position `pos`.
@@ -549,7 +551,7 @@ __device__ __forceinline__ uint32_t v_row_of(const SolveArgs& A, int b, int bh, 
   const int slot = pos / A.P, tok = pos - slot * A.P;
   const int lp = DENSE ? slot : clampi(A.page_idx[(size_t)bh * A.cap + slot], 0, A.Mmax - 1);
   const int phys = clampi(A.block_table[(size_t)b * A.Mmax + lp], 0, A.n_phys - 1);
-  return (uint32_t)((phys * A.Hkv + hkv) * A.P + tok);
+  return (uint32_t)((phys * A.HkvPool + hkv) * A.P + tok);
 }
 template <bool DENSE>
 __device__ __forceinline__ int token_of(const SolveArgs& A, int bh, int pos) {
@@ -983,12 +985,14 @@ void launch_decode(const Dims& dm, bool dense, bool grouped, const void* q, cons
                    const int32_t* page_idx, const int32_t* n_sel, float* out, float* tau, int32_t* supp,
                    const ekv_decode_extras& ex, const DecodeWorkspace& ws, hipStream_t st) {
   ScoreArgs sa{q, c.k_pool, c.block_table, c.seq_lens, page_idx, n_sel, ws.z, ws.pmax,
-               dm.Hq, dm.Hkv, dm.P, dm.Mmax, dm.cap, ws.n_chunks_max, c.n_phys_pages, ws.zstride, dm.a * dm.scale};
+               dm.Hq, dm.Hkv, dm.P, dm.Mmax, dm.cap, ws.n_chunks_max, c.n_phys_pages, ws.zstride, dm.a * dm.scale,
+               dm.HkvPool};
   SolveArgs so{c.v_pool, c.block_table, c.seq_lens, page_idx, n_sel, ws.z, ws.pmax, out, tau, supp, ex,
                dm.Hq, dm.Hkv, dm.P, dm.Mmax, dm.cap, ws.n_chunks_max, c.n_phys_pages, ws.zstride, dm.a, dm.beta, dm.ibeta};
   so.fcount = ws.fcount; so.frow = ws.frow; so.flist_u = ws.flist_u; so.flist_pos = ws.flist_pos;
   so.n_slices_max = ws.n_slices_max;
   so.grouped = grouped ? 1 : 0;
+  so.HkvPool = dm.HkvPool;
   FilterArgs fa{c.seq_lens, n_sel, ws.z, ws.pmax, ws.fcount, ws.frow, ws.flist_u, ws.flist_pos,
                 dm.Hq, dm.Hkv, grouped ? 1 : 0, dm.P, ws.n_slices_max, dense ? dm.Mmax : dm.cap, ws.n_chunks_max,
                 ws.zstride, dm.beta, dm.ibeta};

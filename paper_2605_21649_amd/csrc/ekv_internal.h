@@ -8,6 +8,7 @@ namespace ekv {
 
 struct Dims {
   int B, Hq, Hkv, G, P, Mmax, cap;
+  int HkvPool;        // KV heads per physical page of the pools (>= Hkv; the stride when a config covers a subset)
   int dtype;          // ekv_dtype
   float alpha, scale;
   float a;            // alpha - 1

@@ -88,11 +88,11 @@ __device__ __forceinline__ void append_token_wave(T* __restrict__ k_pool, T* __r
                                                   const T* __restrict__ k_new, const T* __restrict__ v_new,
                                                   T* __restrict__ box, T* __restrict__ gauss,
                                                   uint8_t* __restrict__ box8, int b, int h, int Hkv,
-                                                  int P, int Mmax, int n_phys) {
+                                                  int HkvPool, int P, int Mmax, int n_phys) {
   const int p = pos / P, slot = pos - p * P;
   if (pos < 0 || p >= Mmax) return;            // no room: validated against on the host where possible
   const int phys = min(max(block_table[(size_t)b * Mmax + p], 0), n_phys - 1);
-  const size_t page_off = ((size_t)phys * Hkv + h) * P * kD;
+  const size_t page_off = ((size_t)phys * HkvPool + h) * P * kD;
   const T* knew = k_new + ((size_t)b * Hkv + h) * kD;
   const int lane = threadIdx.x & 63;
   if (lane < 16) {

@@ -28,7 +28,7 @@ constexpr int kScoreTile = 32;
 struct ScoreAppend {
   void* k_pool; void* v_pool; const int32_t* block_table; const void* k_new; const void* v_new;
   void* box_stats; void* gauss_stats; void* box8_stats;
-  int n_phys, mode;
+  int n_phys, mode, hkv_pool;
 };
 
 // Returns the sequence length the kernel scores with.
@@ -48,11 +48,11 @@ __device__ __forceinline__ int fused_append(const ScoreAppend& ap, int n, int b,
       if (P == 16)
         append_token_wave<T, 16>((T*)ap.k_pool, (T*)ap.v_pool, ap.block_table, n, (const T*)ap.k_new,
                                  (const T*)ap.v_new, (T*)ap.box_stats, (T*)ap.gauss_stats, (uint8_t*)ap.box8_stats,
-                                 b, h, Hkv, P, Mmax, ap.n_phys);
+                                 b, h, Hkv, ap.hkv_pool, P, Mmax, ap.n_phys);
       else
         append_token_wave<T, 0>((T*)ap.k_pool, (T*)ap.v_pool, ap.block_table, n, (const T*)ap.k_new,
                                 (const T*)ap.v_new, (T*)ap.box_stats, (T*)ap.gauss_stats, (uint8_t*)ap.box8_stats,
-                                b, h, Hkv, P, Mmax, ap.n_phys);
+                                b, h, Hkv, ap.hkv_pool, P, Mmax, ap.n_phys);
     }
     // the statistics rows written above are read below by the other wavefronts of this workgroup only (same
     // compute unit): a workgroup-scope fence is enough; a device-scope one would write back the whole L2
@@ -361,10 +361,10 @@ static void launch_score_G(const Dims& dm, const void* q, const ekv_stats_view& 
 void launch_score_pages(const Dims& dm, const void* q, const ekv_stats_view& s, const int32_t* seq_lens,
                         int mode, float* box, float* mu, float* sigma, hipStream_t st, const ekv_cache_view* append_to,
                         const void* k_new, const void* v_new) {
-  ScoreAppend ap{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0, 0};
+  ScoreAppend ap{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0, 0, dm.HkvPool};
   if (append_to != nullptr)
     ap = ScoreAppend{append_to->k_pool, append_to->v_pool, append_to->block_table, k_new, v_new, s.box, s.gauss,
-                     s.box8, append_to->n_phys_pages, 1};
+                     s.box8, append_to->n_phys_pages, 1, dm.HkvPool};
   switch (dm.G) {
     case 1: launch_score_G<1>(dm, q, s, seq_lens, mode, box, mu, sigma, st, ap); break;
     case 2: launch_score_G<2>(dm, q, s, seq_lens, mode, box, mu, sigma, st, ap); break;

@@ -20,7 +20,7 @@ __global__ __launch_bounds__(kSmThreads) void softmax_partial_kernel(
     const T* __restrict__ q, const T* __restrict__ k_pool, const T* __restrict__ v_pool,
     const int32_t* __restrict__ block_table, const int32_t* __restrict__ seq_lens,
     const int32_t* __restrict__ page_idx, const int32_t* __restrict__ n_sel, float* __restrict__ part, int Hq,
-    int Hkv, int P_rt, int Mmax, int cap, int n_chunks_max, int n_phys, float scale) {
+    int Hkv, int HkvPool, int P_rt, int Mmax, int cap, int n_chunks_max, int n_phys, float scale) {
   __shared__ float s_o[kSmWaves][kD];
   __shared__ float s_m[kSmWaves], s_l[kSmWaves];
   constexpr int kPagesPerWave = kSmPagesPerBlock / kSmWaves;
@@ -49,7 +49,7 @@ __global__ __launch_bounds__(kSmThreads) void softmax_partial_kernel(
 #pragma unroll
   for (int pw = 0; pw < kPagesPerWave; ++pw) {
     const bool slot_ok = wslot0 + pw < n_slots;      // wave-uniform
-    const size_t page_off = ((size_t)physs[pw] * Hkv + hkv) * P * kD + 8 * c;
+    const size_t page_off = ((size_t)physs[pw] * HkvPool + hkv) * P * kD + 8 * c;
     const int steps = P / 4;
     Raw8<T> kr[SMAX], vr[SMAX];
 #pragma unroll
@@ -169,7 +169,7 @@ static void launch_softmax_T(const Dims& dm, const void* q, const ekv_cache_view
   dim3 grid(n_chunks_max, dm.B * dm.Hq), block(kSmThreads);
 #define EKV_SM(PT)                                                                                                  \
   hipLaunchKernelGGL((softmax_partial_kernel<T, PT>), grid, block, 0, st, (const T*)q, (const T*)c.k_pool,          \
-                     (const T*)c.v_pool, c.block_table, c.seq_lens, page_idx, n_sel, ws, dm.Hq, dm.Hkv, dm.P,       \
+                     (const T*)c.v_pool, c.block_table, c.seq_lens, page_idx, n_sel, ws, dm.Hq, dm.Hkv, dm.HkvPool, dm.P,       \
                      dm.Mmax, dm.cap, n_chunks_max, c.n_phys_pages, dm.scale)
   if (dm.P == 16) EKV_SM(16);
   else if (dm.P == 32) EKV_SM(32);

@@ -103,7 +103,7 @@ __global__ __launch_bounds__(256) void stats_build_kernel(const T* __restrict__ 
                                                           const int32_t* __restrict__ seq_lens,
                                                           T* __restrict__ box, T* __restrict__ gauss,
                                                           uint8_t* __restrict__ box8,
-                                                          int Hkv, int P, int Mmax, int n_phys) {
+                                                          int Hkv, int HkvPool, int P, int Mmax, int n_phys) {
   const int b = blockIdx.z, h = blockIdx.y;
   const int p = blockIdx.x * 16 + (threadIdx.x >> 4);     // 16 pages per workgroup, 4 per wavefront
   const int n = seq_lens[b];
@@ -112,7 +112,7 @@ __global__ __launch_bounds__(256) void stats_build_kernel(const T* __restrict__ 
   if (M <= 0) return;
   const int cnt = min(P, n - pc * P);
   const int phys = min(max(block_table[(size_t)b * Mmax + pc], 0), n_phys - 1);
-  const T* kpage = k_pool + ((size_t)phys * Hkv + h) * P * kD;
+  const T* kpage = k_pool + ((size_t)phys * HkvPool + h) * P * kD;
   const size_t rec = (((size_t)b * Hkv + h) * Mmax + pc) * 2 * kD;
   const bool all_full = __all(cnt == P);
   if (blockIdx.x * 16 + (int)(threadIdx.x >> 6) * 4 >= M) return;      // whole wavefront past the end
@@ -129,16 +129,16 @@ __global__ __launch_bounds__(64) void stats_append_kernel(T* __restrict__ k_pool
                                                           const T* __restrict__ v_new,
                                                           T* __restrict__ box, T* __restrict__ gauss,
                                                           uint8_t* __restrict__ box8,
-                                                          int Hkv, int P, int Mmax, int n_phys) {
+                                                          int Hkv, int HkvPool, int P, int Mmax, int n_phys) {
   append_token_wave<T, PT>(k_pool, v_pool, block_table, seq_lens[blockIdx.y], k_new, v_new, box, gauss, box8,
-                           blockIdx.y, blockIdx.x, Hkv, P, Mmax, n_phys);
+                           blockIdx.y, blockIdx.x, Hkv, HkvPool, P, Mmax, n_phys);
 }
 
 template <typename T, int PT>
 static void launch_build_T(const Dims& dm, const ekv_cache_view& c, const ekv_stats_view& s, hipStream_t st) {
   dim3 grid((dm.Mmax + 15) / 16, dm.Hkv, dm.B), block(256);
   hipLaunchKernelGGL((stats_build_kernel<T, PT>), grid, block, 0, st, (const T*)c.k_pool, c.block_table, c.seq_lens,
-                     (T*)s.box, (T*)s.gauss, (uint8_t*)s.box8, dm.Hkv, dm.P, dm.Mmax, c.n_phys_pages);
+                     (T*)s.box, (T*)s.gauss, (uint8_t*)s.box8, dm.Hkv, dm.HkvPool, dm.P, dm.Mmax, c.n_phys_pages);
 }
 template <typename T, int PT>
 static void launch_append_T(const Dims& dm, const ekv_cache_view& c, const ekv_stats_view& s, const void* k_new,
@@ -146,7 +146,7 @@ static void launch_append_T(const Dims& dm, const ekv_cache_view& c, const ekv_s
   dim3 grid(dm.Hkv, dm.B), block(64);
   hipLaunchKernelGGL((stats_append_kernel<T, PT>), grid, block, 0, st, (T*)c.k_pool, (T*)c.v_pool, c.block_table,
                      c.seq_lens, (const T*)k_new, (const T*)v_new, (T*)s.box, (T*)s.gauss, (uint8_t*)s.box8, dm.Hkv,
-                     dm.P, dm.Mmax, c.n_phys_pages);
+                     dm.HkvPool, dm.P, dm.Mmax, c.n_phys_pages);
 }
 
 void launch_stats_build(const Dims& dm, const ekv_cache_view& c, const ekv_stats_view& s, hipStream_t st) {

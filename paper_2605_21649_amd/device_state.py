@@ -54,3 +54,44 @@ class DeviceState:
             n = ekv.ekv_workspace_bytes(self.cfg, op)
             self.ws[op] = torch.empty(max(n, 256), device=self.box.device, dtype=torch.uint8)
         return self.ws[op]
+
+
+class HeadSlice:
+    """The KV heads [h0, h1) of a batch-1 DeviceState (and their query heads) as a problem of its own: a config
+    with the pools' head stride, pool pointers advanced to h0, and contiguous slices of every per-head array.
+    Independent slices can run on separate streams."""
+
+    def __init__(self, st, h0, h1):
+        w = st.w
+        assert w.batch == 1, "per-head arrays of a head range are contiguous only for batch 1"
+        G = w.group
+        self.st, self.h0, self.h1 = st, h0, h1
+        q0, q1 = h0 * G, h1 * G
+        self.cfg = ekv.make_config(1, q1 - q0, h1 - h0, w.head_dim, w.page_size, w.kv_dtype, w.alpha, w.score_scale,
+                                   st.Mmax, st.cap, pool_kv_heads=w.n_kv_heads)
+        i = st.inp
+        self.q = i["q"][:, q0:q1]
+        self.seq_lens = i["seq_lens"]
+        self.box_stats, self.gauss_stats = st.box_stats[:, h0:h1], st.gauss_stats[:, h0:h1]
+        self.box8_stats = st.box8_stats[:, h0:h1] if hasattr(st, "box8_stats") else None
+        for name in ("box", "mu", "sigma", "page_idx", "n_sel", "overflow", "tau_hat", "out", "tau", "supp"):
+            setattr(self, name, getattr(st, name)[:, q0:q1])
+        self.ws = {}
+
+    def cache(self, seq_lens=None):
+        i = self.st.inp
+        return ekv.cache_view_heads(i["k_pool"], i["v_pool"], i["block_table"],
+                                    self.seq_lens if seq_lens is None else seq_lens, self.h0)
+
+    def stats(self):
+        return ekv.stats_view(self.box_stats, self.gauss_stats, self.box8_stats)
+
+    def new_token(self, k_new, v_new):
+        """[1][Hkv][d] tokens of all heads -> this slice's."""
+        return k_new[:, self.h0:self.h1], v_new[:, self.h0:self.h1]
+
+    def workspace(self, op):
+        if op not in self.ws:
+            n = ekv.ekv_workspace_bytes(self.cfg, op)
+            self.ws[op] = torch.empty(max(n, 256), device=self.box.device, dtype=torch.uint8)
+        return self.ws[op]
