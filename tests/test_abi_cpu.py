@@ -50,6 +50,7 @@ def test_workspace_sizes():
     (dict(head_dim=64), 2), (dict(page_size=10), 2), (dict(n_q_heads=24, n_kv_heads=8), 2),
     (dict(n_q_heads=30), 1), (dict(alpha=1.0), 1), (dict(scale=0.0), 1), (dict(batch=0), 1),
     (dict(kv_dtype=7), 2), (dict(max_sel_pages=70000), 1),
+    (dict(pool_kv_heads=4), 1), (dict(pool_kv_heads=-1), 1),          # fewer pool heads than the config covers
 ])
 def test_bad_config_is_rejected(kw, code):
     lib = ekv.load_library()
