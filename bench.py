@@ -12,7 +12,7 @@ the box-threshold refinement, the bulk statistics build (a1), and the same steps
 workload (C3).  To keep reads coming from HBM rather than the 256 MB last-level cache, the step rotates
 over several identical copies of the cache and its statistics.
 
-Prints ONE JSON line (see the design doc for the fields): metric/value = mean latency of the K timed steps in
+Prints ONE JSON line: metric/value = mean latency of the K timed steps in
 microseconds; `roofline` for the longest single kernel of the step; `cpu_baseline` = the float64 oracle
 timed on this machine's host cores on a bounded sample of (batch, head) units.
 """
@@ -264,7 +264,7 @@ def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
-              "(how the path would shard is described in DESIGN.md).", file=sys.stderr)
+              "(every (sequence, KV head) unit is independent, so more GPUs would take disjoint units).", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
@@ -305,7 +305,7 @@ def main():
     supp_mean = float(st0.supp.float().mean())
     n_sel_mean = float(st0.n_sel.float().mean())
 
-    # algorithmic bytes of the step (DESIGN.md "Measurement"): box metadata + selected K pages +
+    # algorithmic bytes of the step: box metadata + selected K pages +
     # support V rows + score scratch (written then read once)
     sel_tokens = n_sel_mean * P
     bytes_meta = B * Hkv * M * 2 * d * e

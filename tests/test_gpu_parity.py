@@ -1,6 +1,7 @@
 """GPU parity: every C-ABI entry point against the float64 oracle on the same seeded inputs.
 
-Acceptance rules (written out here; derivations in the design doc):
+Acceptance rules (float32 accumulation of 256 exact products bounds the score error by a few ulp of
+sum |q k| * scale; everything downstream inherits that resolution):
   * page statistics: min/max bit-exact; mean and variance within 1 ulp of the storage dtype (bf16) or
     2e-6 relative to the page's value range (f32);
   * page scores: |gpu - oracle| <= 1e-5 * max(1, |score|);
