@@ -863,6 +863,46 @@ def test_group_decode_equals_per_head_decode_on_the_same_lists():
     assert torch.equal(tau_g, st.tau) and torch.equal(supp_g, st.supp) and torch.equal(out_g, st.out)
 
 
+def test_results_do_not_depend_on_where_pages_live():
+    """The same logical cache in three physical arrangements -- a random permutation of exactly the mapped
+    pages (the generator's), the identity, and a larger pool with unused pages of garbage between the
+    mapped ones -- gives bit-identical statistics, scores, selections and outputs (and the first of them is
+    checked against the oracle by the other tests)."""
+    w = W2
+    inp = get_inputs(w)
+    k = topk_budget(w)
+    dev = torch.device("cuda")
+    P, M = w.page_size, w.pages_per_seq
+    n_phys = inp["k_pool"].shape[0]
+    results = []
+    g = torch.Generator().manual_seed(3)
+    for arrangement in ("generated", "identity", "sparse-pool"):
+        i2 = dict(inp)
+        if arrangement != "generated":
+            bt = inp["block_table"].long()                                   # [B, M] -> old physical page
+            if arrangement == "identity":
+                new_of_logical = torch.arange(w.batch * M).view(w.batch, M)
+                pool_pages = w.batch * M
+            else:
+                pool_pages = 3 * n_phys + 5
+                new_of_logical = torch.randperm(pool_pages, generator=g)[: w.batch * M].view(w.batch, M)
+            k2 = torch.full((pool_pages,) + tuple(inp["k_pool"].shape[1:]), 1e4).to(inp["k_pool"].dtype)
+            v2 = torch.full_like(k2, -1e4)
+            k2[new_of_logical.reshape(-1)] = inp["k_pool"][bt.reshape(-1)]
+            v2[new_of_logical.reshape(-1)] = inp["v_pool"][bt.reshape(-1)]
+            i2.update(k_pool=k2, v_pool=v2, block_table=new_of_logical.to(torch.int32).contiguous())
+        st = DeviceState(w, i2, cap=k, device=dev)
+        run_step(st, w, "topk", k=k)
+        out_f, tau_f, supp_f = torch.zeros_like(st.out), torch.zeros_like(st.tau), torch.zeros_like(st.supp)
+        ekv.ekv_decode_full(st.cfg, st.inp["q"], st.cache(), out_f, tau_f, supp_f, st.workspace(ekv.EKV_OP_DECODE_FULL))
+        torch.cuda.synchronize()
+        results.append([t.clone() for t in (st.box_stats, st.gauss_stats, st.box, st.page_idx, st.n_sel, st.out, st.tau,
+                                            st.supp, out_f, tau_f, supp_f)])
+    for other in results[1:]:
+        for a, b_ in zip(results[0], other):
+            assert torch.equal(a.view(torch.uint8), b_.view(torch.uint8))
+
+
 # ---------------------------------------------------------------------------- multi-step decode loop
 def test_multi_step_decode_loop_with_ragged_batch():
     """append -> score -> select -> decode for 40 consecutive steps on a batch whose two sequences have
