@@ -28,9 +28,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# FETCH_SIZE + WRITE_SIZE of one score_pages launch at C4 (rocprofv3 --pmc, scaled by a plain copy of known
-# size; see profiles/bench_topk_step_C4.md, the instantiation without the append): 256.09 MiB read + 8.00 MiB written
-PMC_TRAFFIC_SCORE_PAGES_C4 = int((256.09 + 8.00) * 1024 * 1024)
+# FETCH_SIZE + WRITE_SIZE of one page-scoring launch at C4 (rocprofv3 --pmc, scaled by a plain copy of known
+# size; see profiles/bench_topk_step_C4.md): the instantiation with the append inside (the one the step runs)
+# 256.21 MiB read + 8.02 MiB written, the one without 256.09 + 8.00
+PMC_TRAFFIC_SCORE_PAGES_C4 = {True: int((256.21 + 8.02) * 1024 * 1024), False: int((256.09 + 8.00) * 1024 * 1024)}
 
 # the append runs inside the scoring launch (ekv_append_score_pages) unless --two-launch-append is given
 STAGE_NAMES = {"topk": ["append_own_launch", "append+score_box", "select_topk", "decode_sparse"],
@@ -344,18 +345,24 @@ def main():
     kernels["decode_sparse"]["kernels"] = 2     # score pass (HBM-bound gather) + single-workgroup solve
 
     # The roofline entry is for the longest single kernel of the step: the page-scoring stream
-    # (score_pages_mfma_kernel).  select_topk and decode_sparse are several shorter kernels each; the
-    # committed kernel trace under profiles/ lists them one by one.
-    roof_bytes = kernel_alg_bytes["score_pages(box)"]
-    achieved = roof_bytes / (t_score * 1e-6) / 1e9
+    # (score_pages_mfma_kernel; the instantiation with the append inside when the step uses the fused call).
+    # select_topk and decode_sparse are several shorter kernels each; the committed kernel trace under
+    # profiles/ lists them one by one.
+    roof_key = "append_score_pages(box)" if R.fused_append else "score_pages(box)"
+    roof_us = t_fused if R.fused_append else t_score
+    roof_bytes = kernel_alg_bytes[roof_key]
+    achieved = roof_bytes / (roof_us * 1e-6) / 1e9
     # HBM bytes per launch from the FETCH_SIZE / WRITE_SIZE counter runs (profiles/bench_topk_step_C4.md);
     # they hold for the workload those runs used
-    pmc_traffic = {"C4": PMC_TRAFFIC_SCORE_PAGES_C4}
+    pmc_traffic = {"C4": PMC_TRAFFIC_SCORE_PAGES_C4[bool(R.fused_append)]}
     roofline = {
-        "bound": "hbm", "kernel": "score_pages_mfma_kernel<G=%d,box> (ekv_score_pages)" % w.group,
+        "bound": "hbm",
+        "kernel": "score_pages_mfma_kernel<%d, 0, %s> (%s)" % (w.group, "true" if R.fused_append else "false",
+                                                              "ekv_append_score_pages" if R.fused_append
+                                                              else "ekv_score_pages"),
         "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
         "traffic": pmc_traffic.get(args.workload),
-        "algorithmic_bytes_per_launch": int(roof_bytes), "avg_launch_us": round(t_score, 2),
+        "algorithmic_bytes_per_launch": int(roof_bytes), "avg_launch_us": round(roof_us, 2),
         "timing": "HIP events around 60 back-to-back launches on the launch stream, %d rotating copies" % args.copies,
     }
     dom_name = stage_names[int(np.argmax(stage_mean))]
