@@ -22,44 +22,79 @@ namespace ekv {
 // 47.7 with 64 pages, 52 with 128 -- small workgroups at high occupancy keep more of the stream in flight.
 constexpr int kScoreTile = 32;
 
-// Fused append: the workgroup whose tile holds the page of the new token first appends it (one wavefront:
-// cache slot written, page statistics recomputed), then every workgroup scores with the length n_b + 1.
+// Fused append: the workgroup that scores the tile holding the page of the new token first appends it (one
+// wavefront: cache slot written, page statistics recomputed); every workgroup scores with the length n_b + 1.
 // mode 0: plain scoring; 1: append, then score; 2: score with n_b + 1 only (a second launch of the call).
 struct ScoreAppend {
   void* k_pool; void* v_pool; const int32_t* block_table; const void* k_new; const void* v_new;
   void* box_stats; void* gauss_stats; void* box8_stats;
   int n_phys, mode, hkv_pool;
+  int units, n_tiles;     // (sequence, KV head) units and tiles per unit of this launch
 };
 
-// Returns the sequence length the kernel scores with.
+// What a workgroup does.  The grid is one-dimensional (folded over x and y): workgroup j scores tile
+// j % n_tiles of unit j / n_tiles -- tile index fastest, so that consecutive workgroups read consecutive
+// parts of one unit's statistics stream.  A launch that appends puts one extra workgroup per unit IN FRONT
+// of all of those: it appends the unit's token and scores the tile of that page, and the regular workgroup of
+// that tile leaves at once.  The appending workgroups are then the first ones dispatched and their extra
+// latency hides behind the stream (as part of the regular order, the last unit's started near the end of
+// the launch and lengthened it by 2 us).
+struct TileWork { int b, h, tile0, n; bool run; };
+
 // APPEND = false instantiations carry no append code at all (modes 0 and 2): their register count, and with it
 // the occupancy of the stream, is that of the scoring loop alone.
 template <typename T, bool APPEND>
-__device__ __forceinline__ int fused_append(const ScoreAppend& ap, int n, int b, int h, int tile0, int tile,
-                                            int Hkv, int P, int Mmax) {
-  if (ap.mode == 0) return n;
-  const int p_new = n / P;
-  if (n < 0 || p_new >= Mmax) return n;             // no room: nothing is appended
-  if (APPEND && ap.mode == 1 && p_new >= tile0 && p_new < tile0 + tile) {    // workgroup-uniform
-    if (threadIdx.x < 64) {
-      // 16-token pages fetch the whole page as one batch (as the append kernel does); other sizes take the
-      // row-by-row instantiation, same summation order, because the register count of this path sets the
-      // occupancy of every streaming workgroup of the launch
-      if (P == 16)
-        append_token_wave<T, 16>((T*)ap.k_pool, (T*)ap.v_pool, ap.block_table, n, (const T*)ap.k_new,
-                                 (const T*)ap.v_new, (T*)ap.box_stats, (T*)ap.gauss_stats, (uint8_t*)ap.box8_stats,
-                                 b, h, Hkv, ap.hkv_pool, P, Mmax, ap.n_phys);
-      else
-        append_token_wave<T, 0>((T*)ap.k_pool, (T*)ap.v_pool, ap.block_table, n, (const T*)ap.k_new,
-                                (const T*)ap.v_new, (T*)ap.box_stats, (T*)ap.gauss_stats, (uint8_t*)ap.box8_stats,
-                                b, h, Hkv, ap.hkv_pool, P, Mmax, ap.n_phys);
-    }
-    // the statistics rows written above are read below by the other wavefronts of this workgroup only (same
-    // compute unit): a workgroup-scope fence is enough; a device-scope one would write back the whole L2
-    __threadfence_block();
-    __syncthreads();
+__device__ __forceinline__ TileWork score_work(const ScoreAppend& ap, const int32_t* __restrict__ seq_lens, int Hkv,
+                                               int P, int Mmax, int tile) {
+  TileWork tw{0, 0, 0, 0, false};
+  const bool appending = APPEND && ap.mode == 1;
+  const long long gid = (long long)blockIdx.y * gridDim.x + blockIdx.x;
+  const long long total = (long long)ap.units * ap.n_tiles + (appending ? ap.units : 0);
+  if (gid >= total) return tw;
+  const bool front = appending && gid < ap.units;
+  int unit, tix;
+  if (front) { unit = (int)gid; tix = 0; }
+  else if (total <= 0x7fffffffLL) {                 // the usual case: 32-bit division
+    const int j = (int)(appending ? gid - ap.units : gid);
+    unit = j / ap.n_tiles; tix = j - unit * ap.n_tiles;
+  } else {
+    const long long j = appending ? gid - ap.units : gid;
+    unit = (int)(j / ap.n_tiles); tix = (int)(j - (long long)unit * ap.n_tiles);
   }
-  return n + 1;
+  tw.b = unit / Hkv; tw.h = unit - tw.b * Hkv;
+  const int n = seq_lens[tw.b];
+  const int p_new = n / P;
+  const bool has_new = ap.mode != 0 && n >= 0 && p_new < Mmax;      // false: no room, nothing is appended
+  tw.n = has_new ? n + 1 : n;
+  if (appending) {
+    const int t_new = p_new / tile;
+    if (front) {
+      if (!has_new) return tw;
+      tix = t_new;
+      if (threadIdx.x < 64) {
+        // 16-token pages fetch the whole page as one batch (as the append kernel does); other sizes take the
+        // row-by-row instantiation, same summation order, because the register count of this path sets the
+        // occupancy of every streaming workgroup of the launch
+        if (P == 16)
+          append_token_wave<T, 16>((T*)ap.k_pool, (T*)ap.v_pool, ap.block_table, n, (const T*)ap.k_new,
+                                   (const T*)ap.v_new, (T*)ap.box_stats, (T*)ap.gauss_stats, (uint8_t*)ap.box8_stats,
+                                   tw.b, tw.h, Hkv, ap.hkv_pool, P, Mmax, ap.n_phys);
+        else
+          append_token_wave<T, 0>((T*)ap.k_pool, (T*)ap.v_pool, ap.block_table, n, (const T*)ap.k_new,
+                                  (const T*)ap.v_new, (T*)ap.box_stats, (T*)ap.gauss_stats, (uint8_t*)ap.box8_stats,
+                                  tw.b, tw.h, Hkv, ap.hkv_pool, P, Mmax, ap.n_phys);
+      }
+      // the statistics rows written above are read below by the other wavefronts of this workgroup only (same
+      // compute unit): a workgroup-scope fence is enough; a device-scope one would write back the whole L2
+      __threadfence_block();
+      __syncthreads();
+    } else if (has_new && tix == t_new) {
+      return tw;                                       // scored by the appending workgroup
+    }
+  }
+  tw.tile0 = tix * tile;
+  tw.run = true;
+  return tw;
 }
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
@@ -130,14 +165,13 @@ void score_pages_mfma_kernel(const bf16_t* __restrict__ q,
   constexpr int TILE = score_tile(KIND), NT = TILE / 16;   // NT groups of 4 pages per wavefront
   constexpr int NSET = (G + 3) / 4;                 // column sets of 4 heads
   __shared__ float stage[2][G][TILE];
-  const int b = blockIdx.z, h = blockIdx.y;
-  // with a fused append the tiles are taken from the end, so that the workgroup that appends (the last
-  // page's) is dispatched first and its extra latency hides behind the stream of the others
-  const int tile0 = (ap.mode == 1 ? gridDim.x - 1 - blockIdx.x : blockIdx.x) * TILE;
+  const TileWork tw = score_work<bf16_t, APPEND>(ap, seq_lens, Hkv, P, Mmax, TILE);
+  if (!tw.run) return;                               // workgroup-uniform
+  const int b = tw.b, h = tw.h, tile0 = tw.tile0;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int m = lane & 15, j = lane >> 4;           // MFMA row / column index, K group
   const int pg = m >> 2, kq = m & 3;                // as a row: page of the group, channel quarter
-  const int n = fused_append<bf16_t, APPEND>(ap, seq_lens[b], b, h, tile0, TILE, Hkv, P, Mmax);
+  const int n = tw.n;
   const int M = (n + P - 1) / P;
   const int Hq = Hkv * G;
   if (tile0 >= M) {                                  // tile past the end of the sequence: no statistics are read
@@ -249,11 +283,12 @@ __global__ __launch_bounds__(256) void score_pages_f32_kernel(const float* __res
                                                               const ScoreAppend ap) {
   constexpr int kSteps = kScoreTile / 4 / 2;
   __shared__ float stage[2][G][kScoreTile];
-  const int b = blockIdx.z, h = blockIdx.y;
-  const int tile0 = (ap.mode == 1 ? gridDim.x - 1 - blockIdx.x : blockIdx.x) * kScoreTile;
+  const TileWork tw = score_work<float, APPEND>(ap, seq_lens, Hkv, P, Mmax, kScoreTile);
+  if (!tw.run) return;                               // workgroup-uniform
+  const int b = tw.b, h = tw.h, tile0 = tw.tile0;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int half = lane >> 5, which = (lane >> 4) & 1, c = lane & 15;
-  const int n = fused_append<float, APPEND>(ap, seq_lens[b], b, h, tile0, kScoreTile, Hkv, P, Mmax);
+  const int n = tw.n;
   const int M = (n + P - 1) / P;
   const int Hq = Hkv * G;
   if (tile0 >= M) {                                  // tile past the end of the sequence: no statistics are read
@@ -321,32 +356,44 @@ __global__ __launch_bounds__(256) void score_pages_f32_kernel(const float* __res
   }
 }
 
+// One-dimensional grid over (unit, tile) plus the appending workgroups, folded over x and y.
+static dim3 score_grid(const Dims& dm, int tile, bool appending, ScoreAppend* ap) {
+  ap->units = dm.Hkv * dm.B;
+  ap->n_tiles = (dm.Mmax + tile - 1) / tile;
+  const long long total = (long long)ap->units * ap->n_tiles + (appending ? ap->units : 0);
+  const long long gx = total < (1 << 20) ? total : (1 << 20);
+  return dim3((unsigned)gx, (unsigned)((total + gx - 1) / gx));
+}
+
 template <int G, bool APPEND>
 static void launch_score_GA(const Dims& dm, const void* q, const ekv_stats_view& s, const int32_t* seq_lens,
                            int mode, float* box, float* mu, float* sigma, hipStream_t st, const ScoreAppend& ap0) {
-  dim3 grid((dm.Mmax + kScoreTile - 1) / kScoreTile, dm.Hkv, dm.B), block(256);
+  dim3 block(256);
   const int gmax = (mode & EKV_SCORE_GROUP_MAX) ? 1 : 0;
   // with both score kinds requested the first launch appends, the second only scores with the new length
   ScoreAppend ap_box = ap0, ap_gauss = ap0;
   if (ap0.mode == 1 && (mode & EKV_SCORE_BOX)) ap_gauss.mode = 2;
+  const dim3 grid = score_grid(dm, kScoreTile, APPEND && ap_box.mode == 1, &ap_box);       // 512-byte records
+  const dim3 grid_g = score_grid(dm, kScoreTile, APPEND && ap_gauss.mode == 1, &ap_gauss);
   if (dm.dtype == EKV_BF16) {
     if (mode & EKV_SCORE_BOX8) {
-      dim3 grid8((dm.Mmax + score_tile(kKindBox8) - 1) / score_tile(kKindBox8), dm.Hkv, dm.B);
+      ScoreAppend ap8 = ap_box;
+      const dim3 grid8 = score_grid(dm, score_tile(kKindBox8), APPEND && ap8.mode == 1, &ap8);
       hipLaunchKernelGGL((score_pages_mfma_kernel<G, kKindBox8, APPEND>), grid8, block, 0, st, (const bf16_t*)q,
-                         (const void*)s.box8, seq_lens, box, (float*)nullptr, dm.Hkv, dm.P, dm.Mmax, dm.scale, gmax, ap_box);
+                         (const void*)s.box8, seq_lens, box, (float*)nullptr, dm.Hkv, dm.P, dm.Mmax, dm.scale, gmax, ap8);
     }
     if (mode & EKV_SCORE_BOX)
       hipLaunchKernelGGL((score_pages_mfma_kernel<G, kKindBox, APPEND>), grid, block, 0, st, (const bf16_t*)q,
                          (const void*)s.box, seq_lens, box, (float*)nullptr, dm.Hkv, dm.P, dm.Mmax, dm.scale, gmax, ap_box);
     if (mode & EKV_SCORE_GAUSS)
-      hipLaunchKernelGGL((score_pages_mfma_kernel<G, kKindGauss, APPEND>), grid, block, 0, st, (const bf16_t*)q,
+      hipLaunchKernelGGL((score_pages_mfma_kernel<G, kKindGauss, APPEND>), grid_g, block, 0, st, (const bf16_t*)q,
                          (const void*)s.gauss, seq_lens, mu, sigma, dm.Hkv, dm.P, dm.Mmax, dm.scale, 0, ap_gauss);
   } else {
     if (mode & EKV_SCORE_BOX)
       hipLaunchKernelGGL((score_pages_f32_kernel<G, false, APPEND>), grid, block, 0, st, (const float*)q,
                          (const float*)s.box, seq_lens, box, (float*)nullptr, dm.Hkv, dm.P, dm.Mmax, dm.scale, gmax, ap_box);
     if (mode & EKV_SCORE_GAUSS)
-      hipLaunchKernelGGL((score_pages_f32_kernel<G, true, APPEND>), grid, block, 0, st, (const float*)q,
+      hipLaunchKernelGGL((score_pages_f32_kernel<G, true, APPEND>), grid_g, block, 0, st, (const float*)q,
                          (const float*)s.gauss, seq_lens, mu, sigma, dm.Hkv, dm.P, dm.Mmax, dm.scale, 0, ap_gauss);
   }
 }
@@ -361,10 +408,10 @@ static void launch_score_G(const Dims& dm, const void* q, const ekv_stats_view& 
 void launch_score_pages(const Dims& dm, const void* q, const ekv_stats_view& s, const int32_t* seq_lens,
                         int mode, float* box, float* mu, float* sigma, hipStream_t st, const ekv_cache_view* append_to,
                         const void* k_new, const void* v_new) {
-  ScoreAppend ap{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0, 0, dm.HkvPool};
+  ScoreAppend ap{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0, 0, dm.HkvPool, 0, 0};
   if (append_to != nullptr)
     ap = ScoreAppend{append_to->k_pool, append_to->v_pool, append_to->block_table, k_new, v_new, s.box, s.gauss,
-                     s.box8, append_to->n_phys_pages, 1, dm.HkvPool};
+                     s.box8, append_to->n_phys_pages, 1, dm.HkvPool, 0, 0};
   switch (dm.G) {
     case 1: launch_score_G<1>(dm, q, s, seq_lens, mode, box, mu, sigma, st, ap); break;
     case 2: launch_score_G<2>(dm, q, s, seq_lens, mode, box, mu, sigma, st, ap); break;
