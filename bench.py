@@ -30,8 +30,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 # FETCH_SIZE + WRITE_SIZE of one page-scoring launch at C4 (rocprofv3 --pmc, scaled by a plain copy of known
 # size; see profiles/bench_topk_step_C4.md): the instantiation with the append inside (the one the step runs)
-# 256.21 MiB read + 8.02 MiB written, the one without 256.09 + 8.00
-PMC_TRAFFIC_SCORE_PAGES_C4 = {True: int((256.21 + 8.02) * 1024 * 1024), False: int((256.09 + 8.00) * 1024 * 1024)}
+# 256.32 MiB read + 8.02 MiB written, the one without 256.12 + 8.00
+PMC_TRAFFIC_SCORE_PAGES_C4 = {True: int((256.32 + 8.02) * 1024 * 1024), False: int((256.12 + 8.00) * 1024 * 1024)}
 
 # the append runs inside the scoring launch (ekv_append_score_pages) unless --two-launch-append is given
 STAGE_NAMES = {"topk": ["append_own_launch", "append+score_box", "select_topk", "decode_sparse"],
