@@ -271,6 +271,7 @@ def main():
     import numpy as np
     import torch
     from paper_2605_21649_amd import binding as ekv, synth
+    from paper_2605_21649_amd.device_state import DeviceState
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     ekv.load_library()
@@ -564,6 +565,31 @@ def main():
         extras["stats_build_us"] = round(R.time_call(lambda st: ekv.ekv_stats_build(st.cfg, st.cache(), st.stats()),
                                                      reps=8), 2)
         extras["stats_build_GBps"] = round((dense_bytes / 2 + 2 * bytes_meta) / (extras["stats_build_us"] * 1e-6) / 1e9, 1)
+        # Gaussian-aware selector on plain random inputs (q, K, V ~ N(0,1), batch 8, page 16, 4K-64K tokens: the
+        # setting of the paper's selector-quality table, App. E): coverage, dropped mass, recall, output error
+        tab = {}
+        for n_t in (4096, 8192, 16384, 32768, 65536):
+            wt = synth.Workload("randn", 8, 8, 8, 128, n_t, 16, "bf16")
+            it = synth.make_inputs(wt, 9000 + n_t, device=dev)
+            stt = DeviceState(wt, it, cap=wt.pages_per_seq, device=dev)
+            ekv.ekv_stats_build(stt.cfg, stt.cache(), stt.stats())
+            ekv.ekv_score_pages(stt.cfg, it["q"], stt.stats(), it["seq_lens"], ekv.EKV_SCORE_GAUSS, None, stt.mu, stt.sigma)
+            ekv.ekv_select_gauss(stt.cfg, stt.mu, stt.sigma, it["seq_lens"], args.q_page, 0.0, stt.tau_hat, stt.page_idx,
+                                 stt.n_sel, stt.overflow, stt.workspace(ekv.EKV_OP_SELECT_GAUSS))
+            o_f, t_f, s_f = torch.zeros_like(stt.out), torch.zeros_like(stt.tau), torch.zeros_like(stt.supp)
+            ekv.ekv_decode_full(stt.cfg, it["q"], stt.cache(), o_f, t_f, s_f, stt.workspace(ekv.EKV_OP_DECODE_FULL))
+            km_t, ks_t = torch.zeros_like(stt.tau), torch.zeros_like(stt.supp)
+            ekv.ekv_decode_sparse(stt.cfg, it["q"], stt.cache(), stt.page_idx, stt.n_sel, stt.out, stt.tau, stt.supp,
+                                  stt.workspace(ekv.EKV_OP_DECODE_SPARSE),
+                                  extras=ekv.decode_extras(tau_ref=t_f, kept_mass_ref=km_t, kept_supp_ref=ks_t))
+            torch.cuda.synchronize()
+            tab[str(n_t)] = {"coverage": round(float(stt.n_sel.float().mean()) / wt.pages_per_seq, 4),
+                             "delta_mean": round(float((1.0 - km_t).mean()), 5),
+                             "rho_mean": round(float((ks_t.float() / s_f.float()).mean()), 4),
+                             "R_mean": round(float(((stt.out - o_f).norm(dim=-1) / o_f.norm(dim=-1)).mean()), 5),
+                             "tau_hat_minus_tau_mean": round(float((stt.tau_hat - t_f).mean()), 4)}
+            del stt, it
+        extras["randn_gauss_selector_by_context"] = {"q_page": args.q_page, "margin": 0.0, "rows": tab}
         # 8-bit page bounds (an extension; the rows above keep the paper's cache-dtype metadata): allocated and
         # built only now, so that nothing above pays for them
         for st in copies:

@@ -1074,3 +1074,36 @@ def test_fused_append_score_equals_the_two_calls(w, mode):
         assert torch.equal(ba.view(torch.int32), bb.view(torch.int32))
         assert torch.equal(ma.view(torch.int32), mb.view(torch.int32))
         assert torch.equal(sa.view(torch.int32), sb.view(torch.int32))
+
+
+# ---------------------------------------------------------------------------- trend of the paper's selector table
+def test_gauss_selector_on_plain_random_inputs_follows_the_papers_trend():
+    """q, K, V ~ N(0,1), batch 8, page 16 (the setting of the paper's selector-quality table, App. E): the
+    estimated threshold is close to the exact full-cache one, the fraction of pages kept falls as the
+    context grows, and at 4K/8K tokens almost nothing of the mass is dropped.  (The table's own numbers
+    depend on hyper-parameters the paper does not state; only the trend is checked.)"""
+    dev = torch.device("cuda")
+    cov, delta, gap = [], [], []
+    for n in (4096, 8192, 16384, 32768):
+        w = synth.Workload("randn", 8, 8, 8, 128, n, 16, "bf16")
+        inp = synth.make_inputs(w, 9000 + n, device=dev)
+        st = DeviceState(w, inp, cap=w.pages_per_seq, device=dev)
+        ekv.ekv_stats_build(st.cfg, st.cache(), st.stats())
+        ekv.ekv_score_pages(st.cfg, inp["q"], st.stats(), inp["seq_lens"], ekv.EKV_SCORE_GAUSS, None, st.mu, st.sigma)
+        ekv.ekv_select_gauss(st.cfg, st.mu, st.sigma, inp["seq_lens"], 0.99, 0.0, st.tau_hat, st.page_idx, st.n_sel,
+                             st.overflow, st.workspace(ekv.EKV_OP_SELECT_GAUSS))
+        out_f, tau_f, supp_f = torch.zeros_like(st.out), torch.zeros_like(st.tau), torch.zeros_like(st.supp)
+        ekv.ekv_decode_full(st.cfg, inp["q"], st.cache(), out_f, tau_f, supp_f, st.workspace(ekv.EKV_OP_DECODE_FULL))
+        km = torch.zeros_like(st.tau)
+        ekv.ekv_decode_sparse(st.cfg, inp["q"], st.cache(), st.page_idx, st.n_sel, st.out, st.tau, st.supp,
+                              st.workspace(ekv.EKV_OP_DECODE_SPARSE),
+                              extras=ekv.decode_extras(tau_ref=tau_f, kept_mass_ref=km))
+        torch.cuda.synchronize()
+        cov.append(float(st.n_sel.float().mean()) / w.pages_per_seq)
+        delta.append(float((1.0 - km).mean()))
+        gap.append(float((st.tau_hat - tau_f).abs().mean()))
+        assert float((st.tau - tau_f).max()) <= 1e-6          # a sparse threshold never exceeds the full one
+    assert all(a > b for a, b in zip(cov, cov[1:])), cov
+    assert delta[0] <= 0.01 and delta[1] <= 0.02, delta
+    assert all(a <= b + 1e-3 for a, b in zip(delta, delta[1:])), delta
+    assert max(gap) <= 0.1, gap
