@@ -583,6 +583,24 @@ def main():
                                   stt.workspace(ekv.EKV_OP_DECODE_SPARSE),
                                   extras=ekv.decode_extras(tau_ref=t_f, kept_mass_ref=km_t, kept_supp_ref=ks_t))
             torch.cuda.synchronize()
+            if n_t == 16384:
+                # the top-k selector on the same inputs at several coverages (the approximation-quality figure's setting)
+                tk = {}
+                ekv.ekv_score_pages(stt.cfg, it["q"], stt.stats(), it["seq_lens"], ekv.EKV_SCORE_BOX, stt.box)
+                idx_t, ns_t = torch.zeros_like(stt.page_idx), torch.zeros_like(stt.n_sel)
+                out_t, tau_t, supp_t = torch.zeros_like(stt.out), torch.zeros_like(stt.tau), torch.zeros_like(stt.supp)
+                km2, ks2 = torch.zeros_like(stt.tau), torch.zeros_like(stt.supp)
+                for cov_t in (0.0625, 0.125, 0.25, 0.5):
+                    kp_t = int(cov_t * wt.pages_per_seq)
+                    ekv.ekv_select_topk(stt.cfg, stt.box, it["seq_lens"], kp_t, idx_t, ns_t, stt.workspace(ekv.EKV_OP_SELECT_TOPK))
+                    ekv.ekv_decode_sparse(stt.cfg, it["q"], stt.cache(), idx_t, ns_t, out_t, tau_t, supp_t,
+                                          stt.workspace(ekv.EKV_OP_DECODE_SPARSE),
+                                          extras=ekv.decode_extras(tau_ref=t_f, kept_mass_ref=km2, kept_supp_ref=ks2))
+                    torch.cuda.synchronize()
+                    tk[str(cov_t)] = {"delta_mean": round(float((1.0 - km2).mean()), 5),
+                                      "rho_mean": round(float((ks2.float() / s_f.float()).mean()), 4),
+                                      "R_mean": round(float(((out_t - o_f).norm(dim=-1) / o_f.norm(dim=-1)).mean()), 5)}
+                extras["randn_topk_by_coverage_16k"] = tk
             tab[str(n_t)] = {"coverage": round(float(stt.n_sel.float().mean()) / wt.pages_per_seq, 4),
                              "delta_mean": round(float((1.0 - km_t).mean()), 5),
                              "rho_mean": round(float((ks_t.float() / s_f.float()).mean()), 4),
