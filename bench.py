@@ -706,6 +706,34 @@ def main():
         row["speedup_gauss_vs_dense"] = round(us3d / us3g, 2)
         result["other_rows"]["C3-128k"] = row
         R3g.release()
+        del R3g
+        # latency against context length (one sequence of the headline's shape), the form of the paper's decode-only
+        # efficiency figure: dense entmax decode, top-k (2 %) and Gaussian-aware steps, softmax over the top-k lists
+        sweep = {}
+        for ctx in (32768, 131072, 524288):
+            wn = synth.WORKLOADS["C4"].scaled(name=f"C4-shape-{ctx}", context=ctx)
+            Rn = Runner(wn, args.budget, args.copies, args.q_page, dev, cap_frac=max(args.cap_frac, 0.75 if ctx <= 32768 else 0.25 if ctx <= 131072 else 0.08),
+                        fused_append=not args.two_launch_append)
+            u_t, _, _ = Rn.run_timed(Rn.step_topk, side, 5, stages=False)
+            u_g, _, _ = Rn.run_timed(Rn.step_gauss, side, 5, stages=False)
+            ovf_g = int(Rn.copies[0].overflow.sum())
+            u_d, _, _ = Rn.run_timed(Rn.step_dense, max(5, side // 2), 3, stages=False)
+            stn = Rn.copies[0]
+            Rn.step_topk(stn)
+            ws_smn = stn.workspace(ekv.EKV_OP_DECODE_SPARSE_SOFTMAX)
+            lse_n = torch.zeros_like(stn.tau)
+            u_s = Rn.time_call(lambda st_: ekv.ekv_decode_sparse_softmax(stn.cfg, stn.inp["q"], st_.cache(), stn.page_idx,
+                                                                         stn.n_sel, stn.out, lse_n, ws_smn), reps=10)
+            sweep[str(ctx)] = {"dense_full_us": round(u_d, 2), "topk_step_us": round(u_t, 2), "gauss_step_us": round(u_g, 2),
+                               "gauss_overflow_heads": ovf_g, "softmax_over_topk_lists_us": round(u_s, 2),
+                               "speedup_topk_vs_dense": round(u_d / u_t, 2)}
+            Rn.release()
+            del Rn, stn
+        sweep["1048576"] = {"dense_full_us": result["other_rows"]["dense_full_us"], "topk_step_us": result["value"],
+                            "gauss_step_us": result["other_rows"]["gauss_step_us"],
+                            "softmax_over_topk_lists_us": result["other_rows"]["softmax_sparse_us"],
+                            "speedup_topk_vs_dense": result["other_rows"]["speedup_vs_dense"]}
+        result["other_rows"]["latency_by_context_B1"] = sweep
 
     print(json.dumps(result))
 
