@@ -505,6 +505,19 @@ __device__ __forceinline__ float solve_tau(const Src& src, float lo_init, float 
 // applied): one wavefront holds them in registers and iterates without any barrier; the result is handed
 // to the other wavefronts through LDS.  Called by the whole workgroup.
 constexpr int kWaveList = 256;
+// entries of one wavefront in registers (u[k] of lane l is list entry l + 64 k, -inf past the end)
+__device__ __forceinline__ float solve_tau_regs(const float (&u)[kWaveList / 64], float lo_init, float seed, float beta,
+                                                int ibeta, int& supp, int& evals) {
+  return solve_tau_core([&](float t, float& F, float& D, int& cnt) {
+    float f = 0.f, d = 0.f; int c = 0;
+#pragma unroll
+    for (int k = 0; k < kWaveList / 64; ++k) {
+      const float x = u[k] - t;
+      if (x > 0.f) { f += pow_beta(x, beta, ibeta); d += pow_beta_m1(x, beta, ibeta); ++c; }
+    }
+    F = wave_sum(f); D = beta * wave_sum(d); cnt = wave_sum_i(c);
+  }, lo_init, seed, ibeta, supp, evals);
+}
 __device__ __forceinline__ float solve_tau_wave(const float* list_u, int n, float lo_init, float seed, float beta,
                                                 int ibeta, SolveShared& sh, int& supp, int& evals) {
   if (threadIdx.x < 64) {
@@ -513,15 +526,7 @@ __device__ __forceinline__ float solve_tau_wave(const float* list_u, int n, floa
 #pragma unroll
     for (int k = 0; k < kWaveList / 64; ++k) u[k] = lane + 64 * k < n ? list_u[lane + 64 * k] : -INFINITY;
     int sp = 0, ev = 0;
-    const float tau = solve_tau_core([&](float t, float& F, float& D, int& cnt) {
-      float f = 0.f, d = 0.f; int c = 0;
-#pragma unroll
-      for (int k = 0; k < kWaveList / 64; ++k) {
-        const float x = u[k] - t;
-        if (x > 0.f) { f += pow_beta(x, beta, ibeta); d += pow_beta_m1(x, beta, ibeta); ++c; }
-      }
-      F = wave_sum(f); D = beta * wave_sum(d); cnt = wave_sum_i(c);
-    }, lo_init, seed, ibeta, sp, ev);
+    const float tau = solve_tau_regs(u, lo_init, seed, beta, ibeta, sp, ev);
     if (lane == 0) { sh.red1[0] = tau; sh.wcount[0][0] = sp; sh.wcount[0][1] = ev; }
   }
   __syncthreads();
@@ -803,6 +808,84 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
     lo_u = thr - zmax;
   }
   __syncthreads();
+
+  // Short lists and no side output over all candidates (the usual call): ONE wavefront finishes the row --
+  // V rows resolved while it solves in registers, support compacted with ballots, values gathered by its four
+  // 16-lane rows -- and the other fifteen leave; nothing below this point needs a barrier then.
+  const bool block_extras = (A.ex.tau_ref != nullptr && (A.ex.kept_mass_ref != nullptr || A.ex.kept_supp_ref != nullptr)) ||
+                            (DENSE && A.ex.lse != nullptr);
+  if (in_lds && n_list <= kWaveList && !block_extras) {
+    if (w != 0) return;
+    constexpr int KW = kWaveList / 64;
+    float u[KW]; int pos[KW]; uint32_t row[KW];
+#pragma unroll
+    for (int k = 0; k < KW; ++k) {
+      const int e = lane + 64 * k;
+      u[k] = e < n_list ? sh.list_u[e] : -INFINITY;
+      pos[k] = e < n_list ? sh.list_pos[e] : 0;
+    }
+#pragma unroll
+    for (int k = 0; k < KW; ++k) row[k] = v_row_of<DENSE>(A, b, lrow, hkv, pos[k]);     // clamped, unconditional
+    int supp_w = 0;
+    const float tau_w = solve_tau_regs(u, lo_u, seed_u, beta, ibeta, supp_w, evals);
+    // ordered compaction of the support: (p, row, position) of entry e = lane + 64 k, k-major = candidate order
+    int n_sup = 0;
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int k = 0; k < KW; ++k) {
+      const float x = u[k] - tau_w;
+      const bool in = x > 0.f;
+      const uint64_t mk = __ballot(in);
+      if (in) {
+        const int o = n_sup + __popcll(mk & lt);
+        sh.list_u[o] = pow_beta(x, beta, ibeta);
+        sh.list_row[o] = row[k];
+        sh.list_pos[o] = pos[k];
+      }
+      n_sup += __popcll(mk);
+    }
+    __builtin_amdgcn_wave_barrier();
+    // weighted value sum: 4 row slots x 16 lanes, batches of 8 independent 16-byte loads per lane
+    const int rs = lane >> 4, c = lane & 15;
+    float acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+    for (int e0 = 0; e0 < n_sup; e0 += 32) {
+      Raw8<T> vr[8]; float pw[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int e = e0 + 4 * j + rs;
+        const int ec = min(e, n_sup - 1);                              // clamped: loads stay unconditional
+        pw[j] = e < n_sup ? sh.list_u[ec] : 0.f;
+        load_raw8(v_pool + (size_t)sh.list_row[ec] * kD + 8 * c, vr[j]);
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        float vv[8];
+        widen8(vr[j], vv);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = fmaf(pw[j], vv[i], acc[i]);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      acc[i] += __shfl_xor(acc[i], 16);
+      acc[i] += __shfl_xor(acc[i], 32);
+    }
+    if (lane < 16) {
+      *reinterpret_cast<float4*>(out + 8 * c) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+      *reinterpret_cast<float4*>(out + 8 * c + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
+    }
+    if (A.ex.support_tokens != nullptr) {
+      int32_t* dst = A.ex.support_tokens + (size_t)bh * A.ex.support_cap;
+      for (int e = lane; e < n_sup && e < A.ex.support_cap; e += 64) dst[e] = token_of<DENSE>(A, lrow, sh.list_pos[e]);
+    }
+    if (lane == 0) {
+      A.tau_out[bh] = tau_w + zmax; A.supp_out[bh] = supp_w;
+      if (A.ex.solve_evals != nullptr) A.ex.solve_evals[bh] = evals;
+    }
+    return;
+  }
 
   float tau_u; int supp;
   if (in_lds) {
