@@ -128,10 +128,16 @@ __device__ __forceinline__ void radix_select_kth(KeySet<ITEMS, KeyFn>& ks, int k
     __syncthreads();
     for (int i = tid; i < kBins; i += kSelThreads) sh.hist[i] = 0;
     __syncthreads();
+    // Slots past M hold the rebased key 0.  They are counted (as copies of the smallest key) but not sent
+    // through the histogram one by one: thousands of atomics on one LDS address serialise.
 #pragma unroll
     for (int i = 0; i < (ITEMS ? ITEMS : ks.items); ++i) {
       const uint32_t v = ks.key(i);
-      if (first || (v >> up) == prefix) atomicAdd(&sh.hist[(v >> shift) & dmask], 1u);
+      if (ks.page(i) < ks.M && (first || (v >> up) == prefix)) atomicAdd(&sh.hist[(v >> shift) & dmask], 1u);
+    }
+    if (tid == 0 && (first || prefix == 0u)) {
+      const int n_pad = kSelThreads * (ITEMS ? ITEMS : ks.items) - ks.M;
+      if (n_pad > 0) atomicAdd(&sh.hist[0], (uint32_t)n_pad);
     }
     __syncthreads();
     // thread t owns digits (kBins-1-2t) and (kBins-2-2t): scan from the top digit downwards

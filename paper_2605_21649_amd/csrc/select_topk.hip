@@ -417,7 +417,9 @@ void launch_select_topk(const Dims& dm, const float* box, const int32_t* seq_len
   hipLaunchKernelGGL(select_topk_kernel<ITEMS>, grid, block, 0, st, box, seq_lens, k_pages, page_idx, n_sel, dm.Hq, \
                      dm.P, dm.Mmax, dm.cap)
   if (!topk_sliced(dm)) {
-    if (dm.Mmax <= 4 * kSelThreads) EKV_TOPK(4);
+    if (dm.Mmax <= 2 * kSelThreads) EKV_TOPK(2);
+    else if (dm.Mmax <= 4 * kSelThreads) EKV_TOPK(4);
+    else if (dm.Mmax <= 8 * kSelThreads) EKV_TOPK(8);
     else if (dm.Mmax <= 16 * kSelThreads) EKV_TOPK(16);
     else EKV_TOPK(0);
     return;
