@@ -105,14 +105,11 @@ __device__ __forceinline__ void radix_select_kth(KeySet<ITEMS, KeyFn>& ks, int k
     lo = min(lo, (uint32_t)__shfl_xor((int)lo, d));
     hi = max(hi, (uint32_t)__shfl_xor((int)hi, d));
   }
+  // both extremes in one exchange (the histogram array is free here: it is zeroed at the start of every pass)
   __syncthreads();
-  if ((tid & 63) == 0) sh.red_u[tid >> 6] = lo;
+  if ((tid & 63) == 0) { sh.red_u[tid >> 6] = lo; sh.hist[tid >> 6] = hi; }
   __syncthreads();
-  for (int i = 0; i < kSelWaves; ++i) lo = min(lo, sh.red_u[i]);
-  __syncthreads();
-  if ((tid & 63) == 0) sh.red_u[tid >> 6] = hi;
-  __syncthreads();
-  for (int i = 0; i < kSelWaves; ++i) hi = max(hi, sh.red_u[i]);
+  for (int i = 0; i < kSelWaves; ++i) { lo = min(lo, sh.red_u[i]); hi = max(hi, sh.hist[i]); }
   const uint32_t range = hi - lo;
   ks.rebase(lo);
   int shift = range ? 32 - __clz(range) : 0;     // significant bits of the rebased keys
