@@ -303,3 +303,37 @@ def test_full_size_box8_topk_step(fs):
             ref = orc.entmax_attention(q, K, V, W.alpha, W.score_scale, orc.pages_to_tokens(pages, P, K.shape[0]))
             _check_decode(b, hq, st, toks, q, K, ref)
     del st.box8_stats                                  # the other tests of this module run without it
+
+
+def test_scoring_grid_folded_over_two_dimensions():
+    """More than 2^20 workgroups in one scoring launch (64 units x 16 385 tiles of 32 pages): the linear
+    workgroup index is folded over two grid dimensions.  Statistics are synthetic (17 GB of random bounds, no
+    cache behind them); sampled pages of sampled units are checked against the oracle's Eq. 9, the tail past
+    the sequence length against -inf."""
+    dev = torch.device("cuda")
+    B, H, P = 8, 8, 16
+    Mmax = 524288 + 32
+    cfg = ekv.make_config(B, H, H, 128, P, "bf16", 1.5, 0.1, Mmax, 16)
+    g = torch.Generator(device=dev).manual_seed(123)
+    box_stats = torch.empty(B, H, Mmax, 2, 128, device=dev, dtype=torch.bfloat16)
+    for b in range(B):
+        c = torch.randn(H, Mmax, 1, 128, device=dev, generator=g)
+        hw = torch.rand(H, Mmax, 1, 128, device=dev, generator=g)
+        box_stats[b] = torch.cat([c - hw, c + hw], dim=2).to(torch.bfloat16)
+        del c, hw
+    q = torch.randn(B, H, 128, device=dev, generator=g).to(torch.bfloat16)
+    lens = torch.tensor([Mmax * P - 5 - 1000 * P * b for b in range(B)], dtype=torch.int32, device=dev)
+    out = torch.full((B, H, Mmax), float("nan"), device=dev)
+    ekv.ekv_score_pages(cfg, q, ekv.stats_view(box_stats, None), lens, ekv.EKV_SCORE_BOX, out)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(0)
+    for (b, h) in [(0, 0), (3, 5), (7, 7), (7, 0)]:
+        M = -(-int(lens[b]) // P)
+        pages = np.unique(np.concatenate([rng.integers(0, M, 400), [0, 31, 32, M - 1, M - 33]]))
+        st = to_f64(box_stats[b, h, torch.from_numpy(pages).to(dev)])
+        ref = orc.box_scores(to_f64(q[b, h]), st[:, 0], st[:, 1], 0.1)
+        got = out[b, h, torch.from_numpy(pages).to(dev)].cpu().numpy()
+        assert np.max(np.abs(got - ref) / np.maximum(1.0, np.abs(ref))) <= 1e-5, (b, h)
+        assert bool(torch.isneginf(out[b, h, M:]).all())
+    # every entry was written (none of the NaN fill is left)
+    assert not bool(torch.isnan(out).any())
