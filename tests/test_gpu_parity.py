@@ -186,7 +186,8 @@ def test_select_topk_on_shared_scores(w):
             np.testing.assert_array_equal(idx[b, hq, : ns[b, hq]], ref)
 
 
-@pytest.mark.parametrize("M,k", [(40000 - 3, 1311), (65536, 2622), (20000, 20000), (17000, 1)])
+@pytest.mark.parametrize("M,k", [(40000 - 3, 1311), (65536, 2622), (20000, 20000), (17000, 1),
+                                 (270000, 5400)])       # beyond 64 slices: one workgroup per head reads the keys from memory
 def test_select_topk_long_context(M, k):
     """More than 16384 pages: the selection is split over slices of 4096 pages and several launches.
     Synthetic float32 scores (no cache needed); heads with massive ties take the redo path."""
