@@ -34,7 +34,8 @@ extern "C" {
 typedef enum {
   EKV_OK = 0,
   EKV_ERR_INVALID_ARG = 1, /* null/misaligned pointer, non-positive size, inconsistent config      */
-  EKV_ERR_UNSUPPORTED = 2, /* head_dim / page_size / dtype / alpha this build has no kernel for    */
+  EKV_ERR_UNSUPPORTED = 2, /* head_dim / page_size / dtype / alpha this build has no kernel for,   */
+                           /* or a size beyond a kernel's range (stated with each entry point)      */
   EKV_ERR_WORKSPACE = 3,   /* workspace pointer NULL or smaller than ekv_workspace_bytes reports   */
   EKV_ERR_HIP = 4          /* a HIP runtime call failed; ekv_last_hip_error() returns its code     */
 } ekv_status;
@@ -181,6 +182,7 @@ ekv_status ekv_select_topk(const ekv_config* cfg, const float* box, const int32_
  * An empty result is replaced by the single best page; more than cap pages keeps the cap pages of
  * largest estimate (lower index first on ties) and sets overflow[b,h]=1 (else 0).
  * tau_hat f32 [B][Hq]; page_idx/n_sel as in ekv_select_topk; overflow int32 [B][Hq].
+ * Range: alpha with integer 1/(alpha-1) in 1..4 and max_pages_per_seq <= 4 194 304, else EKV_ERR_UNSUPPORTED.
  * 0 < q_page < 1, margin >= 0.  beta must be 1, 2, 3 or 4. */
 ekv_status ekv_select_gauss(const ekv_config* cfg, const float* mu, const float* sigma,
                             const int32_t* seq_lens, float q_page, float margin, float* tau_hat,
@@ -199,7 +201,8 @@ ekv_status ekv_select_gauss(const ekv_config* cfg, const float* mu, const float*
  * order and duplicates do not matter); page_idx_out int32 [B][Hq][cap] may alias page_idx_in, n_sel_out
  * may alias n_sel_in; n_added, overflow int32 [B][Hq].  If the union exceeds cap, its first cap pages (by
  * index) are written and overflow[b,h]=1: the list is then incomplete and certifies nothing.
- * Workspace: ekv_workspace_bytes(EKV_OP_SELECT_BOX_THRESHOLD). */
+ * Workspace: ekv_workspace_bytes(EKV_OP_SELECT_BOX_THRESHOLD).  Range: max_pages_per_seq <= 4 194 304 (else
+ * EKV_ERR_UNSUPPORTED, also from ekv_workspace_bytes). */
 ekv_status ekv_select_box_threshold(const ekv_config* cfg, const float* box, const int32_t* seq_lens,
                                     const float* tau_lo, const int32_t* page_idx_in,
                                     const int32_t* n_sel_in, int32_t* page_idx_out, int32_t* n_sel_out,
