@@ -74,7 +74,7 @@ struct TopkHead {             // per (b,h) state passed between the launches
 };
 struct TopkWs {
   TopkHead* head;             // [BH]
-  uint32_t* above;            // [BH][S][kBins]   pages of the slice in bins above this one
+  uint16_t* above;            // [BH][S][kBins]   pages of the slice in bins above this one (<= 4096)
   int32_t* slice_off;         // [BH][S]          output offset of the slice
   int32_t* slice_eq;          // [BH][S]          pages with key == key_t in earlier slices
   uint32_t* prefix_key;       // [BH][S][kTkPrefix]  the slice's pages of the highest bins, grouped by bin
@@ -114,7 +114,7 @@ __global__ __launch_bounds__(kTkThreads) void topk_hist_kernel(const float* __re
   const int M = (n + P - 1) / P;
   const float* s = box + (size_t)bh * Mmax;
   if (slice * kTkSlice >= M) {            // empty slice: all counts are zero
-    for (int i = tid; i < kBins; i += kTkThreads) ws.above[((size_t)bh * ws.S + slice) * kBins + i] = 0;
+    for (int i = tid; i < kBins; i += kTkThreads) ws.above[((size_t)bh * ws.S + slice) * kBins + i] = (uint16_t)0;
     return;
   }
   // key range of the first kTkSample pages, widened by half its width on both sides
@@ -168,9 +168,10 @@ __global__ __launch_bounds__(kTkThreads) void topk_hist_kernel(const float* __re
   uint32_t ab[BPT];
 #pragma unroll
   for (int i = BPT - 1; i >= 0; --i) { ab[i] = run; run += c[i]; }
-  uint32_t* out = ws.above + ((size_t)bh * ws.S + slice) * kBins + tid * BPT;
-#pragma unroll
-  for (int i = 0; i < BPT; ++i) out[i] = ab[i];
+  static_assert(BPT == 8, "one 16-byte store of eight 16-bit counts per thread");
+  uint16_t* out = ws.above + ((size_t)bh * ws.S + slice) * kBins + tid * BPT;
+  *reinterpret_cast<uint4*>(out) = make_uint4(ab[0] | (ab[1] << 16), ab[2] | (ab[3] << 16), ab[4] | (ab[5] << 16),
+                                              ab[6] | (ab[7] << 16));
   // The kTkPrefix best pages of the slice, grouped by bin in descending bin order: a page of bin g goes to
   // position above[g] + (arrival number inside the bin).  The find kernel then reads the members of the
   // bin of the k-th key from these lists instead of scanning every score again.
@@ -216,13 +217,13 @@ __global__ __launch_bounds__(kSelThreads) void topk_find_kernel(const float* __r
   // counts above each bin, summed over the slices (thread t owns bins 2t and 2t+1)
   uint32_t a0 = 0, a1 = 0;
   {
-    const uint32_t* ab = ws.above + (size_t)bh * S * kBins + 2 * tid;
+    const uint16_t* ab = ws.above + (size_t)bh * S * kBins + 2 * tid;
     for (int s0 = 0; s0 < S; s0 += 16) {
-      uint2 v[16];
+      uint32_t v[16];                                       // two 16-bit counts per load
 #pragma unroll
-      for (int i = 0; i < 16; ++i) v[i] = *reinterpret_cast<const uint2*>(ab + (size_t)min(s0 + i, S - 1) * kBins);
+      for (int i = 0; i < 16; ++i) v[i] = *reinterpret_cast<const uint32_t*>(ab + (size_t)min(s0 + i, S - 1) * kBins);
 #pragma unroll
-      for (int i = 0; i < 16; ++i) if (s0 + i < S) { a0 += v[i].x; a1 += v[i].y; }
+      for (int i = 0; i < 16; ++i) if (s0 + i < S) { a0 += v[i] & 0xffffu; a1 += v[i] >> 16; }
     }
   }
   tot_above[2 * tid] = a0; tot_above[2 * tid + 1] = a1;
@@ -254,7 +255,7 @@ __global__ __launch_bounds__(kSelThreads) void topk_find_kernel(const float* __r
   if (tid == 0) s_short = 0;
   __syncthreads();
   if (tid < S) {
-    const uint32_t* ab = ws.above + ((size_t)bh * S + tid) * kBins;
+    const uint16_t* ab = ws.above + ((size_t)bh * S + tid) * kBins;
     const int lo_s = (int)ab[b1];
     const int valid_s = max(0, min(kTkSlice, M - tid * kTkSlice));
     const int hi_s = b1 == 0 ? valid_s : (int)ab[b1 - 1];
@@ -405,7 +406,7 @@ static bool topk_sliced(const Dims& dm) { return dm.Mmax > 16 * kSelThreads && t
 size_t select_topk_ws_bytes(const Dims& dm) {
   if (!topk_sliced(dm)) return 256;
   const size_t BH = (size_t)dm.B * dm.Hq, S = topk_slices(dm);
-  size_t b = BH * sizeof(TopkHead) + BH * S * kBins * sizeof(uint32_t) + 2 * BH * S * sizeof(int32_t) +
+  size_t b = BH * sizeof(TopkHead) + BH * S * kBins * sizeof(uint16_t) + 2 * BH * S * sizeof(int32_t) +
              2 * BH * S * kTkPrefix * sizeof(int32_t);
   return (b + 255) & ~(size_t)255;
 }
@@ -429,7 +430,7 @@ void launch_select_topk(const Dims& dm, const float* box, const int32_t* seq_len
   TopkWs ws;
   ws.S = topk_slices(dm);
   ws.head = (TopkHead*)workspace;
-  ws.above = (uint32_t*)(ws.head + BH);
+  ws.above = (uint16_t*)(ws.head + BH);
   ws.slice_off = (int32_t*)(ws.above + BH * ws.S * kBins);
   ws.slice_eq = ws.slice_off + BH * ws.S;
   ws.prefix_key = (uint32_t*)(ws.slice_eq + BH * ws.S);
