@@ -734,6 +734,46 @@ def main():
                             "softmax_over_topk_lists_us": result["other_rows"]["softmax_sparse_us"],
                             "speedup_topk_vs_dense": result["other_rows"]["speedup_vs_dense"]}
         result["other_rows"]["latency_by_context_B1"] = sweep
+        # the alpha and baseline sweep workload (batch 8, 256K tokens per sequence, pages of 32): top-k at a matched
+        # budget of 4096 tokens per head under alpha = 1.25 / 1.5 / 2 against the dense decode of the same alpha, and
+        # softmax over the same lists (its dropped mass next to entmax's)
+        w5 = synth.WORKLOADS["C5"]
+        k5 = 4096 // w5.page_size
+        row5 = {"workload": f"{w5.name}: B{w5.batch} {w5.n_q_heads}q/{w5.n_kv_heads}kv ctx{w5.context} page{w5.page_size} "
+                            f"{w5.kv_dtype}, top-k {k5} pages (4096 tokens) per query head", "by_alpha": {}}
+        for al in (1.25, 1.5, 2.0):
+            R5 = Runner(w5.scaled(alpha=al), k5 / w5.pages_per_seq, 2, args.q_page, dev, cap_frac=k5 / w5.pages_per_seq,
+                        fused_append=not args.two_launch_append)
+            assert R5.k_pages == k5
+            u5, stage5, _ = R5.run_timed(R5.step_topk, side, 5)
+            u5d, _, _ = R5.run_timed(R5.step_dense, max(5, side // 2), 3, stages=False)
+            s5 = R5.copies[0]
+            o5, t5, n5, lse5 = (torch.zeros_like(s5.out), torch.zeros_like(s5.tau), torch.zeros_like(s5.supp),
+                                torch.zeros_like(s5.tau))
+            ekv.ekv_decode_full(s5.cfg, s5.inp["q"], s5.cache(), o5, t5, n5, R5.ws_full, extras=ekv.decode_extras(lse=lse5))
+            km5, ks5 = torch.zeros_like(s5.tau), torch.zeros_like(s5.supp)
+            R5.step_topk(s5)
+            ekv.ekv_decode_sparse(s5.cfg, s5.inp["q"], s5.cache(), s5.page_idx, s5.n_sel, s5.out, s5.tau, s5.supp,
+                                  s5.ws_sparse, extras=ekv.decode_extras(tau_ref=t5, kept_mass_ref=km5, kept_supp_ref=ks5))
+            torch.cuda.synchronize()
+            row5["by_alpha"][str(al)] = {
+                "topk_step_us": round(u5, 2),
+                "topk_stage_us": {nm: round(float(v), 2) for nm, v in zip(STAGE_NAMES["topk"], stage5.mean(axis=0))},
+                "dense_full_us": round(u5d, 2), "speedup_topk_vs_dense": round(u5d / u5, 2),
+                "support_full_mean": float(n5.float().mean()),
+                "delta_mean": round(float((1.0 - km5).mean()), 6),
+                "rho_mean": round(float((ks5.float() / n5.float()).mean()), 4),
+                "R_mean": round(float(((s5.out - o5).norm(dim=-1) / o5.norm(dim=-1)).mean()), 6)}
+            if al == 2.0:                                          # softmax does not depend on alpha: once
+                lse_s5, o_s5 = torch.zeros_like(s5.tau), torch.zeros_like(s5.out)
+                ws_s5 = s5.workspace(ekv.EKV_OP_DECODE_SPARSE_SOFTMAX)
+                row5["softmax_over_topk_lists_us"] = round(R5.time_call(
+                    lambda st_: ekv.ekv_decode_sparse_softmax(s5.cfg, s5.inp["q"], st_.cache(), s5.page_idx, s5.n_sel,
+                                                              o_s5, lse_s5, ws_s5), reps=10), 2)
+                row5["softmax_delta_mean"] = round(float((1.0 - torch.exp(lse_s5 - lse5)).mean()), 6)
+            R5.release()
+            del R5, s5
+        result["other_rows"]["C5-256k"] = row5
 
     print(json.dumps(result))
 
