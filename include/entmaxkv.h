@@ -88,7 +88,10 @@ typedef struct {
 /* Paged KV cache (paper Sec. 4.2: block layout of PagedAttention).  Physical page `phys` of KV head h
  * is the contiguous block pool[((phys*pool_kv_heads + h)*P + t)*d + i], t < P, i < d, element type kv_dtype.
  * block_table[b*Mmax + p] = physical page of logical page p of sequence b (0 <= phys < n_phys_pages;
- * entries with p >= M_b may hold anything: what is read from them is clamped into range and masked).  seq_lens[b] = n_b >= 1. */
+ * entries with p >= M_b may hold anything: what is read from them is clamped into range and masked).
+ * seq_lens[b] = n_b >= 0.  A sequence with n_b = 0 (an idle slot of a serving batch) is legal in every call:
+ * its score rows are all -inf (sigma 0), the selectors return no page (tau_hat 0), the decodes write a zero
+ * output, tau = +inf, an empty support, and a log-sum-exp of -inf; an append makes it a sequence of one token. */
 typedef struct {
   void* k_pool;
   void* v_pool;

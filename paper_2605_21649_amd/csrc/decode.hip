@@ -622,6 +622,9 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
     if (tid == 0) {
       A.tau_out[bh] = INFINITY; A.supp_out[bh] = 0;
       if (A.ex.solve_evals != nullptr) A.ex.solve_evals[bh] = 0;
+      if (A.ex.tau_ref != nullptr && A.ex.kept_mass_ref != nullptr) A.ex.kept_mass_ref[bh] = 0.f;
+      if (A.ex.tau_ref != nullptr && A.ex.kept_supp_ref != nullptr) A.ex.kept_supp_ref[bh] = 0;
+      if (DENSE && A.ex.lse != nullptr) A.ex.lse[bh] = -INFINITY;
     }
     return;
   }

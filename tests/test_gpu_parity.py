@@ -1108,3 +1108,97 @@ def test_gauss_selector_on_plain_random_inputs_follows_the_papers_trend():
     assert delta[0] <= 0.01 and delta[1] <= 0.02, delta
     assert all(a <= b + 1e-3 for a, b in zip(delta, delta[1:])), delta
     assert max(gap) <= 0.1, gap
+
+
+# ---------------------------------------------------------------------------- an idle batch slot
+@pytest.mark.parametrize("kv_dtype,context,lens", [("bf16", 2048, [2048 - 5, 0, 37]), ("f32", 2048, [2048 - 5, 0, 37]),
+                                                  ("bf16", 70000, [70000 - 3, 0])],
+                         ids=["bf16", "f32", "bf16-long-rows"])
+def test_batch_slot_with_zero_tokens(kv_dtype, context, lens):
+    """A sequence of length 0 (an idle slot of a serving batch) next to live ones: every entry point runs,
+    the idle slot gets the documented empty results (no page, zero output, tau = +inf, empty support,
+    log-sum-exp = -inf, tau-hat = 0), and the live sequences match the oracle as if the slot were not there.
+    Then a first token is appended to the idle slot and the step serves it.  The long case takes the dense
+    decode through its multi-workgroup filter passes."""
+    w = synth.C2.scaled(name="C2-idle-slot", batch=len(lens), context=context, n_q_heads=4, n_kv_heads=2,
+                        kv_dtype=kv_dtype)
+    inp = {key: v.clone() for key, v in synth.make_inputs(w, 2000 + 31, device="cpu").items()}
+    inp["seq_lens"] = torch.tensor(lens, dtype=torch.int32)
+    live = [b for b, n_b in enumerate(lens) if n_b > 0]
+    k = 8
+    st = DeviceState(w, inp, cap=16)
+    dev = st.box.device
+    P = w.page_size
+
+    def run(selector):
+        run_step(st, w, selector, k=k, q_page=0.9, margin=0.02)
+        full = dict(out=torch.zeros_like(st.out), tau=torch.zeros_like(st.tau), supp=torch.zeros_like(st.supp),
+                    lse=torch.zeros_like(st.tau))
+        ekv.ekv_decode_full(st.cfg, st.inp["q"], st.cache(), full["out"], full["tau"], full["supp"],
+                            st.workspace(ekv.EKV_OP_DECODE_FULL), extras=ekv.decode_extras(lse=full["lse"]))
+        sm_out, sm_lse = torch.full_like(st.out, 7.0), torch.full_like(st.tau, 7.0)
+        ekv.ekv_decode_sparse_softmax(st.cfg, st.inp["q"], st.cache(), st.page_idx, st.n_sel, sm_out, sm_lse,
+                                      st.workspace(ekv.EKV_OP_DECODE_SPARSE_SOFTMAX))
+        ref_idx, ref_n = torch.zeros_like(st.page_idx), torch.full_like(st.n_sel, 7)
+        added, ovf = torch.full_like(st.n_sel, 7), torch.full_like(st.n_sel, 7)
+        ekv.ekv_select_box_threshold(st.cfg, st.box, st.inp["seq_lens"], st.tau, st.page_idx, st.n_sel, ref_idx, ref_n,
+                                     added, ovf, st.workspace(ekv.EKV_OP_SELECT_BOX_THRESHOLD))
+        km, kn = torch.full_like(st.tau, 7.0), torch.full_like(st.supp, 7)
+        ekv.ekv_decode_sparse(st.cfg, st.inp["q"], st.cache(), st.page_idx, st.n_sel, st.out, st.tau, st.supp,
+                              st.workspace(ekv.EKV_OP_DECODE_SPARSE),
+                              extras=ekv.decode_extras(tau_ref=full["tau"], kept_mass_ref=km, kept_supp_ref=kn))
+        torch.cuda.synchronize()
+        assert torch.all(km[1] == 0) and torch.all(kn[1] == 0)
+        assert torch.all((km[live] >= 0) & (km[live] <= 1.0 + 1e-5)) and torch.all((kn[live] >= 0) & (kn[live] <= full["supp"][live]))
+        return full, sm_out, sm_lse, ref_n, added
+
+    for selector in ("topk", "gauss"):
+        st.out.fill_(7.0); st.tau.fill_(7.0); st.supp.fill_(7); st.n_sel.fill_(7); st.tau_hat.fill_(7.0)
+        if selector == "topk":
+            st.box.fill_(7.0)
+        full, sm_out, sm_lse, ref_n, added = run(selector)
+        # the idle slot
+        assert torch.all(st.n_sel[1] == 0) and torch.all(st.supp[1] == 0) and torch.all(full["supp"][1] == 0)
+        assert torch.all(st.out[1] == 0) and torch.all(full["out"][1] == 0) and torch.all(sm_out[1] == 0)
+        assert torch.all(torch.isposinf(st.tau[1])) and torch.all(torch.isposinf(full["tau"][1]))
+        assert torch.all(torch.isneginf(full["lse"][1])) and torch.all(torch.isneginf(sm_lse[1]))
+        assert torch.all(ref_n[1] == 0) and torch.all(added[1] == 0)
+        if selector == "topk":
+            assert torch.all(torch.isneginf(st.box[1]))
+        else:
+            assert torch.all(st.tau_hat[1] == 0) and torch.all(torch.isneginf(st.mu[1])) and torch.all(st.sigma[1] == 0)
+        # the live sequences
+        for b in live:
+            for hq in (0, 3):
+                q, K, V = unit_kv(inp, w, b, hq)
+                if selector == "topk":
+                    ref = orc.decode_step_unit(q, K, V, P, w.alpha, w.score_scale, "topk", w.kv_dtype, k_pages=k)
+                else:
+                    ref = orc.decode_step_unit(q, K, V, P, w.alpha, w.score_scale, "gauss", w.kv_dtype, q_page=0.9,
+                                               margin=0.02, cap=16)
+                    if ref["overflow"]:
+                        continue
+                got = st.page_idx[b, hq, : int(st.n_sel[b, hq])].cpu().numpy()
+                if set(got.tolist()) == set(ref["pages"].tolist()):
+                    ref["s"] = orc.token_scores(q, K[ref["tokens"]], w.score_scale)
+                    check_decode_unit(w, st.out[b, hq].cpu().numpy(), float(st.tau[b, hq]), int(st.supp[b, hq]), None, ref)
+                dense = orc.entmax_attention(q, K, V, w.alpha, w.score_scale)
+                check_decode_unit(w, full["out"][b, hq].cpu().numpy(), float(full["tau"][b, hq]),
+                                  int(full["supp"][b, hq]), None, dense)
+
+    # the idle slot receives its first token
+    g = torch.Generator().manual_seed(5)
+    k_new = torch.randn(w.batch, w.n_kv_heads, w.head_dim, generator=g).to(st.inp["k_pool"].dtype).to(dev)
+    v_new = torch.randn(w.batch, w.n_kv_heads, w.head_dim, generator=g).to(st.inp["k_pool"].dtype).to(dev)
+    ekv.ekv_append_score_pages(st.cfg, st.cache(), st.stats(), k_new, v_new, st.inp["q"], ekv.EKV_SCORE_BOX, st.box,
+                               None, None)
+    st.inp["seq_lens"] += 1
+    ekv.ekv_select_topk(st.cfg, st.box, st.inp["seq_lens"], k, st.page_idx, st.n_sel, st.workspace(ekv.EKV_OP_SELECT_TOPK))
+    ekv.ekv_decode_sparse(st.cfg, st.inp["q"], st.cache(), st.page_idx, st.n_sel, st.out, st.tau, st.supp,
+                          st.workspace(ekv.EKV_OP_DECODE_SPARSE))
+    torch.cuda.synchronize()
+    assert torch.all(st.n_sel[1] == 1) and torch.all(st.page_idx[1, :, 0] == 0) and torch.all(st.supp[1] == 1)
+    # one token: p = (1), the output is its value row
+    for hq in range(w.n_q_heads):
+        np.testing.assert_allclose(st.out[1, hq].cpu().numpy(), v_new[1, hq // w.group].float().cpu().numpy(),
+                                   rtol=1e-6, atol=0)
