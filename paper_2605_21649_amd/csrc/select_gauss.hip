@@ -29,10 +29,12 @@ constexpr float kInvSqrt2 = 0.70710678118654752f;
 constexpr float kInvSqrt2Pi = 0.39894228040143268f;
 constexpr int kGaussEvalThreads = 256;
 constexpr int kGaussMaxSplits = 64;
-// Evaluation launches per call.  From the pooled start the iteration has converged after three evaluations on
-// the benchmark workloads; a launch that finds its head converged still costs 4.6 us (2048 workgroups read the
-// state and leave), about what the rare continuation inside the gather kernel costs, so there are no spare ones.
-constexpr int kGaussIters = 3;
+// Evaluation launches per call.  The pooled start is within ~1e-2 of the root on the benchmark workloads, the
+// first Newton step brings that to ~1e-5 and the second to ~1e-10, which advance_state recognises from the two
+// step sizes without a third evaluation.  A launch that finds its head converged still costs 4.6 us (2048
+// workgroups read the state and leave), about what the rare continuation inside the gather kernel costs, so
+// there are no spare ones.
+constexpr int kGaussIters = 2;
 constexpr int kGsThreads = 256;           // selection slices: 256 threads x 16 pages
 constexpr int kGsItems = 16;
 constexpr int kGsSlice = kGsThreads * kGsItems;
@@ -54,7 +56,7 @@ __device__ __forceinline__ float horner_tail(float s) {
 template <int NB>
 __device__ __forceinline__ void trunc_h(float t, float& h_nb, float& h_nbm1) {
   if (t < -kTailXHi) { h_nb = 0.f; h_nbm1 = 0.f; return; }      // below float32 resolution of the sum
-  const float phi = expf(-0.5f * t * t) * kInvSqrt2Pi;
+  const float phi = __expf(-0.5f * t * t) * kInvSqrt2Pi;
   if (t >= -kTailXLo) {
     const float Phi = 0.5f * erfcf(-t * kInvSqrt2);
     float h[5];
@@ -64,7 +66,7 @@ __device__ __forceinline__ void trunc_h(float t, float& h_nb, float& h_nbm1) {
     for (int n = 2; n <= NB; ++n) h[n] = fmaf(t, h[n - 1], (float)(n - 1) * h[n - 2]);
     h_nb = h[NB]; h_nbm1 = h[NB - 1];
   } else {
-    const float inv = 1.0f / -t, u = inv * inv;
+    const float inv = __builtin_amdgcn_rcpf(-t), u = inv * inv;
     float p_nb, p_m1;
     if (-t < kTailXSplit) {
       const float s = (u - kTailMid[0]) * kTailInvHalf[0];
@@ -86,7 +88,7 @@ template <int NB>
 __device__ __forceinline__ void page_mass(float muY, float sY, float cnt, float& f, float& d) {
   if (sY > 1e-30f) {
     float hb, hbm1;
-    trunc_h<NB>(muY / sY, hb, hbm1);
+    trunc_h<NB>(muY * __builtin_amdgcn_rcpf(sY), hb, hbm1);
     float sp = 1.f;                        // sY^(NB-1)
 #pragma unroll
     for (int i = 0; i < NB - 1; ++i) sp *= sY;
@@ -103,7 +105,8 @@ __device__ __forceinline__ void page_mass(float muY, float sY, float cnt, float&
 }
 
 // Iteration state of one (b,h): the point the next evaluation is taken at, and its bracket.
-struct GaussState { float tau, lo, hi; int done; };
+// `step` is the Newton step that led to tau (0: none yet, or the point came from a fallback).
+struct GaussState { float tau, lo, hi; int done; float step; };
 
 // workspace: state[2][BH], init partials [BH][S][4], eval partials [2][BH][S][2],
 //            per selection slice: count [BH][NS] and page list [BH][NS][kGsSlice]
@@ -144,7 +147,9 @@ __global__ __launch_bounds__(kGaussEvalThreads) void gauss_init_kernel(const flo
 
 // Scalar solve of n * sd^NB * h_NB((m - tau)/sd) = 1 (the pooled single-Gaussian model): a starting point
 // for the real iteration, so a loose tolerance is enough.  Starts from the leading-order tail estimate
-// t0 = -sqrt(2 ln(n sd^NB)) and iterates Newton on the logarithm.
+// t0 = -sqrt(2 ln(n sd^NB)) and iterates Newton on the logarithm; two consecutive steps s1, s2 of a quadratically
+// converging iteration leave an error of about |s2|^3 / s1^2, which ends the loop without a confirming
+// evaluation (every workgroup of the first evaluation launch waits for this serial chain).
 template <int NB>
 __device__ float pooled_guess(float n, float m, float sd, float lo) {
   if (!(sd > 1e-20f)) return lo;
@@ -153,33 +158,46 @@ __device__ float pooled_guess(float n, float m, float sd, float lo) {
   for (int i = 0; i < NB; ++i) sp *= sd;
   float tau = sp > 1.f ? m + sd * sqrtf(2.f * __logf(sp)) : lo;
   tau = fmaxf(tau, lo);
+  float prev = 0.f;
   for (int it = 0; it < 8; ++it) {
     float f, d;
     page_mass<NB>(m - tau, sd, n, f, d);
     d *= (float)NB;
     if (!(f > 0.f && d > 0.f)) break;
     const float next = fmaxf(tau + f * __logf(f) / d, lo);
-    const bool close = fabsf(next - tau) <= 1e-3f * sd;
+    const float step = fabsf(next - tau);
+    const bool close = step <= 1e-3f * sd ||
+                       (prev != 0.f && step <= 0.25f * prev && step * step * step <= 2e-3f * sd * prev * prev);
     tau = next;
+    prev = step;
     if (close) break;
   }
   return tau;
 }
 
 // Advance the iteration state with the result (F, D = -dF/dtau) of the evaluation at st.tau.
+// Stopping: F = 1 to float32 resolution; or a step below the resolution of tau; or two consecutive Newton steps
+// s1, s2 in the quadratic regime (|s2| <= |s1|/20): the error shrinks as e' = K e^2 with K = |s2|/s1^2, so after
+// the second step it is about |s2|^3/s1^2 -- accepted when that is below 1e-7 (relative to max(1, |tau|)),
+// without evaluating F at the new point.
 __device__ __forceinline__ GaussState advance_state(GaussState st, float F, float D) {
   if (st.done) return st;
   if (fabsf(F - 1.0f) <= 2e-6f) { st.done = 1; return st; }         // float32 resolution of F: tau is the root
   if (F >= 1.0f) st.lo = st.tau; else st.hi = st.tau;
   float next = st.tau;
-  bool ok = false;
+  bool ok = false, newton_log = false;
   if (F > 0.f && D > 0.f) {
     next = st.tau + F * __logf(F) / D;                              // Newton on log F
     ok = next > st.lo && next < st.hi;
+    newton_log = ok;
     if (!ok) { next = st.tau + (F - 1.0f) / D; ok = next > st.lo && next < st.hi; }   // Newton on F
   }
   if (!ok) next = st.hi < INFINITY ? 0.5f * (st.lo + st.hi) : st.lo + 1.0f;
-  if (fabsf(next - st.tau) <= 3e-7f * fmaxf(1.f, fabsf(next))) st.done = 1;
+  const float step = next - st.tau, scale = fmaxf(1.f, fabsf(next));
+  if (fabsf(step) <= 3e-7f * scale) st.done = 1;
+  if (newton_log && st.step != 0.f && fabsf(step) <= 0.05f * fabsf(st.step) &&
+      fabsf(step) * step * step <= 1e-7f * scale * st.step * st.step) st.done = 1;
+  st.step = newton_log ? step : 0.f;
   st.tau = next;
   return st;
 }
@@ -238,7 +256,7 @@ __global__ __launch_bounds__(kGaussEvalThreads) void gauss_eval_kernel(const flo
     mx = bc[0]; s0 = bc[1]; s1 = bc[2]; s2 = bc[3];
     const float mean = s1 / s0;
     const float var = fmaxf(s2 / s0 - mean * mean, 0.f);
-    st.lo = mx - 1.0f; st.hi = INFINITY; st.done = 0;
+    st.lo = mx - 1.0f; st.hi = INFINITY; st.done = 0; st.step = 0.f;
     // the scalar start iteration runs on one wavefront only (the others would just repeat it)
     float tau0 = 0.f;
     if (tid < 64) tau0 = pooled_guess<NB>(s0, mean, sqrtf(var), st.lo);
@@ -427,8 +445,12 @@ __global__ __launch_bounds__(kSelThreads) __attribute__((amdgpu_waves_per_eu(4, 
 
 static int gauss_splits(const Dims& dm) {
   const int BH = dm.B * dm.Hq;
-  int S = (4096 + BH - 1) / BH;
+  // about four pages per thread (one batch of loads): fewer, longer slices lose to the per-workgroup cost of
+  // reading the state and reducing the partial sums (4 us on the 128K-token batch of 4), shorter ones gain nothing
+  int S = (dm.Mmax + 4 * kGaussEvalThreads - 1) / (4 * kGaussEvalThreads);
   const int max_by_pages = (dm.Mmax + kGaussEvalThreads - 1) / kGaussEvalThreads;   // >= 256 pages per slice
+  const int fill = (256 + BH - 1) / BH;                  // short rows: still a workgroup per compute unit
+  if (S < fill) S = fill;
   if (S > max_by_pages) S = max_by_pages;
   if (S > kGaussMaxSplits) S = kGaussMaxSplits;
   if (S < 1) S = 1;
