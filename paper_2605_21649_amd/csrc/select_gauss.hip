@@ -8,10 +8,12 @@
 // One evaluation of F costs an exp and two short polynomials per page, so the pages of a head are split
 // over many workgroups.  The root iteration is a fixed sequence of launches without host involvement:
 // launch k first advances the iteration state from the partial sums of launch k-1 (every workgroup
-// repeats the same few scalar operations), then evaluates its slice at the new tau; once converged the
-// remaining launches return at once.  The selection rule is then applied per slice of 4096 pages in
-// parallel and the per-slice lists are concatenated in order; a head that has not converged by then is
-// finished by the concatenating workgroup iterating alone (rare).
+// repeats the same few scalar operations), then evaluates its slice at the new tau.  The last evaluation
+// launch also applies the selection rule SPECULATIVELY, at a threshold slightly below the one its own point
+// implies: every wavefront writes the passing pages of its range, in order, with their estimates.  The final
+// kernel takes the last state update, keeps the candidates above the final threshold and concatenates them
+// in order; if the final threshold fell below the speculative one, or the iteration has not converged, its
+// workgroup finishes the head alone over all pages (rare).
 //
 // Root finding: F is positive, decreasing and convex.  The start is the root of the same equation for a
 // single Gaussian with the pooled mean and variance of all pages; the iteration is Newton on log F
@@ -35,10 +37,7 @@ constexpr int kGaussMaxSplits = 64;
 // workgroups read the state and leave), about what the rare continuation inside the gather kernel costs, so
 // there are no spare ones.
 constexpr int kGaussIters = 2;
-constexpr int kGsThreads = 256;           // selection slices: 256 threads x 16 pages
-constexpr int kGsItems = 16;
-constexpr int kGsSlice = kGsThreads * kGsItems;
-constexpr int kGsMaxSlices = 1024;
+constexpr int kGaussWaves = kGaussEvalThreads / 64;
 
 template <int IV, int N>
 __device__ __forceinline__ float horner_tail(float s) {
@@ -109,11 +108,20 @@ __device__ __forceinline__ void page_mass(float muY, float sY, float cnt, float&
 struct GaussState { float tau, lo, hi; int done; float step; };
 
 // workspace: state[2][BH], init partials [BH][S][4], eval partials [2][BH][S][2],
-//            per selection slice: count [BH][NS] and page list [BH][NS][kGsSlice]
+//            per wavefront of the last evaluation launch: count [BH][S*4] and candidate lists
+//            (page, estimate) [BH][S*4][pw]
 struct GaussWs {
-  GaussState* state; float* init_part; float* eval_part; int32_t* sel_cnt; int32_t* sel_list;
-  int S, NS;
+  GaussState* state; float* init_part; float* eval_part; int32_t* sel_cnt; int32_t* sel_page; float* sel_key;
+  int S, per, pw;    // slices per head, pages per slice, pages per wavefront of a slice
 };
+
+struct ZqTable { float z[65]; };   // z[c] = PhiInv(q_page^(1/c)), c = 1..64
+
+// The speculative selection threshold of an evaluation at tau: candidates are complete whenever the final
+// threshold tau_hat - margin is not below it.
+__device__ __forceinline__ float spec_threshold(float tau, float margin) {
+  return tau - margin - 4e-3f * fmaxf(1.f, fabsf(tau));
+}
 
 // Launch 0 of a call: slice partials of max a*mu and of the pooled first and second moments.
 __global__ __launch_bounds__(kGaussEvalThreads) void gauss_init_kernel(const float* __restrict__ mu,
@@ -222,21 +230,22 @@ template <int NB>
 __global__ __launch_bounds__(kGaussEvalThreads) void gauss_eval_kernel(const float* __restrict__ mu,
                                                                        const float* __restrict__ sigma,
                                                                        const int32_t* __restrict__ seq_lens,
-                                                                       GaussWs ws, int k, float a, int Hq, int P,
-                                                                       int Mmax, int BH) {
-  __shared__ float red[kGaussEvalThreads / 64][2];
+                                                                       GaussWs ws, int k, ZqTable zq, float margin,
+                                                                       float a, int Hq, int P, int Mmax, int BH) {
+  __shared__ float red[kGaussWaves][2];
   __shared__ float bc[4];
-  const int bh = blockIdx.y, s = blockIdx.x, b = bh / Hq, tid = threadIdx.x;
-  // The slice of pages is fixed by Mmax alone, so its first batch of (mu, sigma) is in flight before the
-  // sequence length, the iteration state or the previous partials have arrived (rows have Mmax entries).
-  const int per = (Mmax + ws.S - 1) / ws.S;
-  const int p0 = s * per;
+  const int bh = blockIdx.y, s = blockIdx.x, b = bh / Hq, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const uint64_t lt = (1ull << lane) - 1ull;
+  // Wavefront w of slice s owns the pages [wbase, wbase + pw) (cut at the end of the slice and of the sequence):
+  // fixed by Mmax alone, so its first batch of (mu, sigma) is in flight before the sequence length, the
+  // iteration state or the previous partials have arrived (rows have Mmax entries).
+  const int wbase = s * ws.per + w * ws.pw;
   const float* mu_r = mu + (size_t)bh * Mmax;
   const float* sg_r = sigma + (size_t)bh * Mmax;
   float mv0[4], sv0[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    const int p = min(p0 + tid + j * kGaussEvalThreads, Mmax - 1);
+    const int p = min(wbase + j * 64 + lane, Mmax - 1);
     mv0[j] = mu_r[p]; sv0[j] = sg_r[p];
   }
   const int n = seq_lens[b];
@@ -270,139 +279,121 @@ __global__ __launch_bounds__(kGaussEvalThreads) void gauss_eval_kernel(const flo
     st = advance_state(ws.state[(size_t)((k - 1) & 1) * BH + bh], F, (float)NB * D);
   }
   if (s == 0 && tid == 0) ws.state[(size_t)(k & 1) * BH + bh] = st;
-  if (st.done) return;
+  const bool last = k == kGaussIters - 1;                 // this launch also writes the candidates
+  if (st.done && !last) return;
 
-  const int p1 = min(p0 + per, M);
+  const int wend = min(min(wbase + ws.pw, (s + 1) * ws.per), M);
+  const float thr_spec = spec_threshold(st.tau, margin);
+  const float z_full = zq.z[P], z_last = zq.z[min(max(n - (M - 1) * P, 0), 64)];
+  const size_t sub = ((size_t)bh * ws.S + s) * kGaussWaves + w;
+  int32_t* lpage = ws.sel_page + sub * ws.pw;
+  float* lkey = ws.sel_key + sub * ws.pw;
+  int n_c = 0;
   float f = 0.f, d = 0.f;
   auto batch = [&](const float (&mv)[4], const float (&sv)[4], int pb) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const int p = pb + j * kGaussEvalThreads;
-      if (p < p1) {                                                    // no loads inside: divergence is harmless
+      const int p = pb + j * 64;
+      const bool ok = p < wend;
+      if (ok) {                                                        // no loads inside: divergence is harmless
         float fp, dp;
         page_mass<NB>(fmaf(a, mv[j], -st.tau), a * sv[j], p == M - 1 ? cnt_last : (float)P, fp, dp);
         f += fp; d += dp;
       }
+      if (last) {                                                      // wave-uniform
+        const float key = a * fmaf(sv[j], p == M - 1 ? z_last : z_full, mv[j]);
+        const bool in = ok && key > thr_spec;
+        const uint64_t mk = __ballot(in);
+        if (in) { const int o = n_c + __popcll(mk & lt); lpage[o] = p; lkey[o] = key; }
+        n_c += __popcll(mk);
+      }
     }
   };
-  batch(mv0, sv0, p0 + tid);                                           // the prefetched first batch
-  for (int pb = p0 + tid + 4 * kGaussEvalThreads; pb < p1; pb += 4 * kGaussEvalThreads) {
+  batch(mv0, sv0, wbase + lane);                                       // the prefetched first batch
+  for (int pb = wbase + 256 + lane; pb - lane < wend; pb += 256) {
     float mv[4], sv[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const int p = min(pb + j * kGaussEvalThreads, M - 1);           // clamped: loads stay unconditional
+      const int p = min(pb + j * 64, Mmax - 1);                        // clamped: loads stay unconditional
       mv[j] = mu_r[p]; sv[j] = sg_r[p];
     }
     batch(mv, sv, pb);
   }
+  if (last && lane == 0) ws.sel_cnt[sub] = n_c;
   f = wave_sum(f); d = wave_sum(d);
-  if ((tid & 63) == 0) { red[tid >> 6][0] = f; red[tid >> 6][1] = d; }
+  if (lane == 0) { red[w][0] = f; red[w][1] = d; }
   __syncthreads();
   if (tid == 0) {
-    for (int i = 1; i < kGaussEvalThreads / 64; ++i) { f += red[i][0]; d += red[i][1]; }
+    for (int i = 1; i < kGaussWaves; ++i) { f += red[i][0]; d += red[i][1]; }
     float* o = ws.eval_part + (((size_t)(k & 1) * BH + bh) * ws.S + s) * 2;
     o[0] = f; o[1] = d;
   }
 }
 
-struct ZqTable { float z[65]; };   // z[c] = PhiInv(q_page^(1/c)), c = 1..64
-
-// Selection rule on one slice of 4096 pages: passing pages in ascending order + their count.  Every
-// workgroup first takes the last state update itself (a few scalar operations); the slice-0 workgroup
-// publishes it.  If the iteration has not converged the head is left to the gather kernel (count -1).
-__global__ __launch_bounds__(kGsThreads) void gauss_mark_kernel(const float* __restrict__ mu,
-                                                                const float* __restrict__ sigma,
-                                                                const int32_t* __restrict__ seq_lens, GaussWs ws,
-                                                                ZqTable zq, float margin, float a, int nb,
-                                                                float* __restrict__ tau_hat, int Hq, int P, int Mmax,
-                                                                int BH) {
-  __shared__ int wcnt[kGsThreads / 64];
-  __shared__ float bc[4];
-  const int bh = blockIdx.y, slice = blockIdx.x, b = bh / Hq, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int n = seq_lens[b];
-  const int M = (n + P - 1) / P;
-  int32_t* cnt_out = ws.sel_cnt + (size_t)bh * ws.NS + slice;
-  if (M <= 0) { if (tid == 0) *cnt_out = 0; return; }
-  float F, D;
-  sum_eval_partials(ws, kGaussIters - 1, bh, BH, bc, F, D);
-  const GaussState st = advance_state(ws.state[(size_t)((kGaussIters - 1) & 1) * BH + bh], F, (float)nb * D);
-  if (slice == 0 && tid == 0) {
-    ws.state[(size_t)(kGaussIters & 1) * BH + bh] = st;
-    if (st.done) tau_hat[bh] = st.tau;
-  }
-  if (!st.done) { if (tid == 0) *cnt_out = -1; return; }
-  if (slice * kGsSlice >= M) { if (tid == 0) *cnt_out = 0; return; }
-  const float thr = st.tau - margin;
-  const float z_full = zq.z[P], z_last = zq.z[n - (M - 1) * P];
-  const float* mu_r = mu + (size_t)bh * Mmax;
-  const float* sg_r = sigma + (size_t)bh * Mmax;
-  const int page0 = slice * kGsSlice + w * (kGsSlice / (kGsThreads / 64)) + lane;
-  float mv[kGsItems], sv[kGsItems];
-#pragma unroll
-  for (int i = 0; i < kGsItems; ++i) { const int p = min(page0 + i * 64, M - 1); mv[i] = mu_r[p]; sv[i] = sg_r[p]; }
-  uint32_t pass = 0;
-  int c = 0;
-#pragma unroll
-  for (int i = 0; i < kGsItems; ++i) {
-    const int p = page0 + i * 64;
-    const bool in = p < M && a * fmaf(sv[i], p == M - 1 ? z_last : z_full, mv[i]) > thr;
-    pass |= (uint32_t)in << i;
-    c += in;
-  }
-  c = wave_sum_i(c);
-  if (lane == 0) wcnt[w] = c;
-  __syncthreads();
-  int o_run = 0, tot = 0;
-  for (int i = 0; i < kGsThreads / 64; ++i) { if (i < w) o_run += wcnt[i]; tot += wcnt[i]; }
-  int32_t* list = ws.sel_list + ((size_t)bh * ws.NS + slice) * kGsSlice;
-  const uint64_t lt = (1ull << lane) - 1ull;
-#pragma unroll
-  for (int i = 0; i < kGsItems; ++i) {
-    const bool in = (pass >> i) & 1u;
-    const uint64_t mk = __ballot(in);
-    if (in) list[o_run + __popcll(mk & lt)] = page0 + i * 64;
-    o_run += __popcll(mk);
-  }
-  if (tid == 0) *cnt_out = tot;
-}
-
-// Concatenates the slice lists in order.  Rare cases are handled here by one workgroup per head over all
-// pages: an iteration that has not converged is continued to convergence; nothing passed -> the single
-// best page; more than cap pages -> the cap best estimates (lower index on ties), flagged.
+// Takes the last state update, keeps the candidates above the final threshold and writes them in page order.
+// Rare cases are handled here by one workgroup per head over all pages: an iteration that has not converged is
+// continued to convergence (then, or when the final threshold is below the speculative one, the pages are
+// re-examined); nothing passed -> the single best page; more than cap pages -> the cap best estimates (lower
+// index on ties), flagged.
 template <int NB, int ITEMS>
 __global__ __launch_bounds__(kSelThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void gauss_gather_kernel(
     const float* __restrict__ mu, const float* __restrict__ sigma, const int32_t* __restrict__ seq_lens,
     GaussWs ws, ZqTable zq, float margin, float a, float* __restrict__ tau_hat, int32_t* __restrict__ page_idx,
     int32_t* __restrict__ n_sel, int32_t* __restrict__ overflow, int Hq, int P, int Mmax, int cap, int BH) {
   __shared__ SelectShared sh;
-  __shared__ int s_off[kGsMaxSlices + 1];
+  __shared__ int s_off[kGaussMaxSplits * kGaussWaves + 1];
+  __shared__ int wtot[kSelWaves];
   __shared__ float red_f[kSelWaves];
-  const int bh = blockIdx.x, b = bh / Hq, tid = threadIdx.x;
+  __shared__ float bc[4];
+  const int bh = blockIdx.x, b = bh / Hq, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const uint64_t lt = (1ull << lane) - 1ull;
   const int n = seq_lens[b];
   const int M = (n + P - 1) / P;
   int32_t* out = page_idx + (size_t)bh * cap;
   if (M <= 0) { if (tid == 0) { n_sel[bh] = 0; overflow[bh] = 0; tau_hat[bh] = 0.f; } return; }
-  const int NS = ws.NS;
-  GaussState st = ws.state[(size_t)(kGaussIters & 1) * BH + bh];
+  const GaussState st1 = ws.state[(size_t)((kGaussIters - 1) & 1) * BH + bh];
+  float F, D;
+  sum_eval_partials(ws, kGaussIters - 1, bh, BH, bc, F, D);
+  GaussState st = advance_state(st1, F, (float)NB * D);
   int count = -1;
-  if (st.done) {
-    for (int i = tid; i < NS; i += kSelThreads) s_off[i] = ws.sel_cnt[(size_t)bh * NS + i];
+  if (st.done && st.tau - margin >= spec_threshold(st1.tau, margin)) {
+    const float thr = st.tau - margin;
+    const int NSS = ws.S * kGaussWaves;                      // candidate lists of this head (<= 256)
+    const int c = tid < NSS ? ws.sel_cnt[(size_t)bh * NSS + tid] : 0;
+    int inc = c;
+#pragma unroll
+    for (int dd = 1; dd < 64; dd <<= 1) { const int t = __shfl_up(inc, dd); if (lane >= dd) inc += t; }
+    if (lane == 63) wtot[w] = inc;
     __syncthreads();
-    if (tid == 0) {
-      int run = 0;
-      for (int i = 0; i < NS; ++i) { const int c = s_off[i]; s_off[i] = run; run += c; }
-      s_off[NS] = run;
-    }
+    int base = 0, n_c = 0;
+    for (int i = 0; i < kSelWaves; ++i) { const int ci = wtot[i]; if (i < w) base += ci; n_c += ci; }
+    if (tid < NSS) s_off[tid] = base + inc - c;
+    if (tid == 0) s_off[NSS] = n_c;
     __syncthreads();
-    count = s_off[NS];
-    if (count >= 1 && count <= cap) {
-      // output position j belongs to the slice sl with s_off[sl] <= j < s_off[sl+1]
-      for (int j = tid; j < count; j += kSelThreads) {
-        int lo = 0, hi = NS;                               // invariant: s_off[lo] <= j < s_off[hi]
-        while (hi - lo > 1) { const int mid = (lo + hi) >> 1; if (s_off[mid] <= j) lo = mid; else hi = mid; }
-        out[j] = ws.sel_list[((size_t)bh * NS + lo) * kGsSlice + (j - s_off[lo])];
+    int n_out = 0;
+    for (int e0 = 0; e0 < n_c; e0 += kSelThreads) {
+      const int e = e0 + tid;
+      int page = 0; bool in = false;
+      if (e < n_c) {
+        int lo = 0, hi = NSS;                                // invariant: s_off[lo] <= e < s_off[hi]
+        while (hi - lo > 1) { const int mid = (lo + hi) >> 1; if (s_off[mid] <= e) lo = mid; else hi = mid; }
+        const size_t at = ((size_t)bh * NSS + lo) * ws.pw + (e - s_off[lo]);
+        page = ws.sel_page[at];
+        in = ws.sel_key[at] > thr;
       }
-      if (tid == 0) { n_sel[bh] = count; overflow[bh] = 0; }
+      const uint64_t mk = __ballot(in);
+      if (lane == 0) wtot[w] = __popcll(mk);
+      __syncthreads();
+      int off = n_out, tot = 0;
+      for (int i = 0; i < kSelWaves; ++i) { const int ci = wtot[i]; if (i < w) off += ci; tot += ci; }
+      const int o = off + __popcll(mk & lt);
+      if (in && o < cap) out[o] = page;
+      n_out += tot;
+      __syncthreads();
+    }
+    count = n_out;
+    if (count >= 1 && count <= cap) {
+      if (tid == 0) { tau_hat[bh] = st.tau; n_sel[bh] = count; overflow[bh] = 0; }
       return;
     }
   }
@@ -424,7 +415,7 @@ __global__ __launch_bounds__(kSelThreads) __attribute__((amdgpu_waves_per_eu(4, 
   const float z_full = zq.z[P], z_last = zq.z[n - (M - 1) * P];
   auto keyfn = [=](int p) { return float_to_key(a * fmaf(sg_r[p], p == M - 1 ? z_last : z_full, mu_r[p])); };
   KeySet<ITEMS, decltype(keyfn)> ks(keyfn, M);
-  if (count < 0) {                                         // the slices were not marked: count here
+  if (count < 0) {                                         // the candidates were not usable: count here
     const uint32_t kthr = float_to_key(st.tau - margin);
     int c = 0;
 #pragma unroll
@@ -456,16 +447,17 @@ static int gauss_splits(const Dims& dm) {
   if (S < 1) S = 1;
   return S;
 }
-static int gauss_sel_slices(const Dims& dm) { return (dm.Mmax + kGsSlice - 1) / kGsSlice; }
+static int gauss_per(const Dims& dm, int S) { return (dm.Mmax + S - 1) / S; }
+static int gauss_pw(const Dims& dm, int S) { return (gauss_per(dm, S) + kGaussWaves - 1) / kGaussWaves; }
 
 size_t select_gauss_ws_bytes(const Dims& dm) {
-  const size_t BH = (size_t)dm.B * dm.Hq, S = gauss_splits(dm), NS = gauss_sel_slices(dm);
+  const size_t BH = (size_t)dm.B * dm.Hq, S = gauss_splits(dm), pw = gauss_pw(dm, (int)S);
   size_t b = 2 * BH * sizeof(GaussState) + BH * S * 4 * sizeof(float) + 2 * BH * S * 2 * sizeof(float) +
-             BH * NS * sizeof(int32_t) + BH * NS * kGsSlice * sizeof(int32_t);
+             BH * S * kGaussWaves * sizeof(int32_t) + BH * S * kGaussWaves * pw * (sizeof(int32_t) + sizeof(float));
   return (b + 255) & ~(size_t)255;
 }
 
-bool select_gauss_supported(const Dims& dm) { return gauss_sel_slices(dm) <= kGsMaxSlices; }
+bool select_gauss_supported(const Dims& dm) { return dm.Mmax <= 4194304; }
 
 template <int NB>
 static void launch_gauss_NB(const Dims& dm, const float* mu, const float* sigma, const int32_t* seq_lens,
@@ -475,11 +467,9 @@ static void launch_gauss_NB(const Dims& dm, const float* mu, const float* sigma,
   dim3 egrid(ws.S, BH), eblock(kGaussEvalThreads);
   hipLaunchKernelGGL(gauss_init_kernel, egrid, eblock, 0, st, mu, sigma, seq_lens, ws, dm.a, dm.Hq, dm.P, dm.Mmax);
   for (int k = 0; k < kGaussIters; ++k)
-    hipLaunchKernelGGL(gauss_eval_kernel<NB>, egrid, eblock, 0, st, mu, sigma, seq_lens, ws, k, dm.a, dm.Hq, dm.P,
-                       dm.Mmax, BH);
+    hipLaunchKernelGGL(gauss_eval_kernel<NB>, egrid, eblock, 0, st, mu, sigma, seq_lens, ws, k, zq, margin, dm.a,
+                       dm.Hq, dm.P, dm.Mmax, BH);
   dim3 hgrid(BH), hblock(kSelThreads);
-  hipLaunchKernelGGL(gauss_mark_kernel, dim3(ws.NS, BH), dim3(kGsThreads), 0, st, mu, sigma, seq_lens, ws, zq, margin,
-                     dm.a, NB, tau_hat, dm.Hq, dm.P, dm.Mmax, BH);
 #define EKV_GGATHER(ITEMS)                                                                                          \
   hipLaunchKernelGGL((gauss_gather_kernel<NB, ITEMS>), hgrid, hblock, 0, st, mu, sigma, seq_lens, ws, zq, margin, dm.a, \
                      tau_hat, page_idx, n_sel, overflow, dm.Hq, dm.P, dm.Mmax, dm.cap, BH)
@@ -497,12 +487,14 @@ void launch_select_gauss(const Dims& dm, const float* mu, const float* sigma, co
   const size_t BH = (size_t)dm.B * dm.Hq;
   GaussWs ws;
   ws.S = gauss_splits(dm);
-  ws.NS = gauss_sel_slices(dm);
+  ws.per = gauss_per(dm, ws.S);
+  ws.pw = gauss_pw(dm, ws.S);
   ws.state = (GaussState*)workspace;
   ws.init_part = (float*)(ws.state + 2 * BH);
   ws.eval_part = ws.init_part + BH * ws.S * 4;
   ws.sel_cnt = (int32_t*)(ws.eval_part + 2 * BH * ws.S * 2);
-  ws.sel_list = ws.sel_cnt + BH * ws.NS;
+  ws.sel_page = ws.sel_cnt + BH * ws.S * kGaussWaves;
+  ws.sel_key = (float*)(ws.sel_page + BH * ws.S * kGaussWaves * ws.pw);
   switch (dm.ibeta) {
     case 1: launch_gauss_NB<1>(dm, mu, sigma, seq_lens, zq, margin, tau_hat, page_idx, n_sel, overflow, ws, st); break;
     case 2: launch_gauss_NB<2>(dm, mu, sigma, seq_lens, zq, margin, tau_hat, page_idx, n_sel, overflow, ws, st); break;
