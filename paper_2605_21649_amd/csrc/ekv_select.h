@@ -14,6 +14,7 @@ constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / 64;
 constexpr int kDigitBits = 11;
 constexpr int kBins = 1 << kDigitBits;
+constexpr int kRankMax = 256;             // elements ranked directly once the radix passes have narrowed to so few
 
 struct SelectShared {
   uint32_t hist[kBins];
@@ -116,12 +117,14 @@ __device__ __forceinline__ void radix_select_kth(KeySet<ITEMS, KeyFn>& ks, int k
 
   uint32_t prefix = 0;       // high bits of the answer fixed so far: (v >> shift) == prefix
   int k_rem = k;             // rank of the answer among the elements sharing that prefix
+  const int n_pad = kSelThreads * (ITEMS ? ITEMS : ks.items) - ks.M;
   while (shift > 0) {
     const int dbits = min(kDigitBits, shift);
     shift -= dbits;
     const uint32_t dmask = (1u << dbits) - 1u;
     const int up = shift + dbits;                  // bits above the current digit: (v >> up) must equal prefix
     const bool first = up >= 32;                   // first pass of a full 32-bit range: every key matches
+    const bool pad_counted = first || prefix == 0u;
     __syncthreads();
     for (int i = tid; i < kBins; i += kSelThreads) sh.hist[i] = 0;
     __syncthreads();
@@ -132,10 +135,7 @@ __device__ __forceinline__ void radix_select_kth(KeySet<ITEMS, KeyFn>& ks, int k
       const uint32_t v = ks.key(i);
       if (ks.page(i) < ks.M && (first || (v >> up) == prefix)) atomicAdd(&sh.hist[(v >> shift) & dmask], 1u);
     }
-    if (tid == 0 && (first || prefix == 0u)) {
-      const int n_pad = kSelThreads * (ITEMS ? ITEMS : ks.items) - ks.M;
-      if (n_pad > 0) atomicAdd(&sh.hist[0], (uint32_t)n_pad);
-    }
+    if (tid == 0 && pad_counted && n_pad > 0) atomicAdd(&sh.hist[0], (uint32_t)n_pad);
     __syncthreads();
     // thread t owns digits (kBins-1-2t) and (kBins-2-2t): scan from the top digit downwards
     const int d_hi = kBins - 1 - 2 * tid, d_lo = d_hi - 1;
@@ -145,8 +145,34 @@ __device__ __forceinline__ void radix_select_kth(KeySet<ITEMS, KeyFn>& ks, int k
     if (above < k_rem && k_rem <= above + c_hi) { sh.digit = d_hi; sh.above = above; }
     else if (above + c_hi < k_rem && k_rem <= above + c_hi + c_lo) { sh.digit = d_lo; sh.above = above + c_hi; }
     __syncthreads();
-    prefix = (prefix << dbits) | sh.digit;
+    const uint32_t digit = sh.digit;
+    prefix = (prefix << dbits) | digit;
     k_rem -= (int)sh.above;
+    if (shift == 0) break;
+    // Few real elements share the prefix (the usual case after the first pass): rank them against each other
+    // directly instead of taking more passes.  Padding slots are the last of the smallest keys and never
+    // decide the answer for k <= M, so they stay out.
+    const int members = (int)sh.hist[digit] - (digit == 0u && pad_counted && n_pad > 0 ? n_pad : 0);
+    if (members <= kRankMax) {                     // workgroup-uniform
+      __syncthreads();                             // every thread has read the count
+      if (tid == 0) sh.scan_buf[kSelWaves] = 0;
+      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < (ITEMS ? ITEMS : ks.items); ++i) {
+        const uint32_t v = ks.key(i);
+        if (ks.page(i) < ks.M && (v >> shift) == prefix) sh.hist[atomicAdd(&sh.scan_buf[kSelWaves], 1)] = v;
+      }
+      __syncthreads();
+      if (tid < members) {
+        const uint32_t v = sh.hist[tid];
+        int g = 0, e = 0;
+        for (int j = 0; j < members; ++j) { const uint32_t u = sh.hist[j]; g += u > v; e += u == v; }
+        if (g < k_rem && k_rem <= g + e) { sh.digit = v; sh.above = (uint32_t)g; }    // equal keys write the same
+      }
+      __syncthreads();
+      vT_out = sh.digit; k_eq_out = k_rem - (int)sh.above;
+      return;
+    }
   }
   vT_out = prefix; k_eq_out = k_rem;
 }
