@@ -604,6 +604,17 @@ def test_tiny_sequences_and_all_pages_selected():
             assert int(st.n_sel[0, hq]) == w.pages_per_seq
             assert int(st.supp[0, hq]) == len(ref["support"])
             assert rel_err(st.out[0, hq].cpu().numpy(), ref["o"]) <= 1e-5
+        # the Gaussian-aware selector on the same few pages (one page per wavefront of its single slice)
+        run_step(st, w, "gauss", q_page=0.99, margin=0.0)
+        for hq in (0, 5):
+            q, K, V = unit_kv(inp, w, 0, hq)
+            ref = orc.decode_step_unit(q, K, V, w.page_size, w.alpha, w.score_scale, "gauss", w.kv_dtype, q_page=0.99,
+                                       margin=0.0, cap=w.pages_per_seq)
+            assert abs(float(st.tau_hat[0, hq]) - ref["tau_hat"]) <= 4e-6 * max(1.0, abs(ref["tau_hat"]))
+            got = st.page_idx[0, hq, : int(st.n_sel[0, hq])].cpu().numpy()
+            band = 1e-5 * max(1.0, abs(ref["tau_hat"]))
+            ok, bad = sets_equal_up_to_cut(got, ref["pages"], ref["g"], ref["tau_hat"], band)
+            assert ok, (n, hq, bad)
 
 
 def test_candidate_list_larger_than_lds_uses_the_streaming_path():
