@@ -608,6 +608,24 @@ def main():
                              "tau_hat_minus_tau_mean": round(float((stt.tau_hat - t_f).mean()), 4)}
             del stt, it
         extras["randn_gauss_selector_by_context"] = {"q_page": args.q_page, "margin": 0.0, "rows": tab}
+        # the Gaussian-aware selector alone on page moments that are NOT homogeneous (what attention sinks or a few
+        # relevant pages produce): a few pages far above the bulk are caught by the start of the root iteration
+        # (hottest page of every wavefront), so the fixed launches still converge; a bimodal population is not, and
+        # its heads are finished by one workgroup each
+        gsel = {}
+        gm = torch.Generator().manual_seed(17)
+        base_mu = torch.randn(B, Hq, M, generator=gm)
+        one_sg = torch.ones(B, Hq, M)
+        hot64 = base_mu.clone(); hot64[:, :, torch.randperm(M, generator=gm)[:64]] += 8.0
+        hot4 = base_mu.clone(); hot4[:, :, torch.randperm(M, generator=gm)[:4]] += 6.0
+        bimodal = torch.cat([torch.randn(B, Hq, M // 2, generator=gm), 3 + 0.5 * torch.randn(B, Hq, M - M // 2, generator=gm)], dim=-1)
+        for name, mu_t in (("homogeneous", base_mu), ("4_pages_plus_6_sigma", hot4), ("64_pages_plus_8_sigma", hot64),
+                           ("bimodal", bimodal)):
+            mu_d, sg_d = mu_t.to(dev).contiguous(), one_sg.to(dev)
+            gsel[name] = round(R.time_call(lambda st: ekv.ekv_select_gauss(st0.cfg, mu_d, sg_d, st0.inp["seq_lens"], args.q_page,
+                                                                           0.0, st0.tau_hat, st0.page_idx, st0.n_sel,
+                                                                           st0.overflow, st0.ws_gauss), reps=10), 2)
+        extras["select_gauss_us_by_page_moment_shape"] = gsel
         # 8-bit page bounds (an extension; the rows above keep the paper's cache-dtype metadata): allocated and
         # built only now, so that nothing above pays for them
         for st in copies:

@@ -79,6 +79,15 @@ struct KeySet {
     const uint32_t k = page(i) < M ? k0 : 0u;
     return max(k, base) - base;
   }
+  // ITEMS == 0: the keys of slots i0 .. i0+7, all eight loads issued before any is used (a loop that calls
+  // key(i) once per iteration waits for memory in every iteration)
+  __device__ __forceinline__ void key_batch(int i0, uint32_t (&k)[8]) const {
+    uint32_t k0[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) k0[j] = fn(min(page(i0 + j), M - 1));
+#pragma unroll
+    for (int j = 0; j < 8; ++j) k[j] = max(page(i0 + j) < M ? k0[j] : 0u, base) - base;
+  }
   __device__ __forceinline__ void rebase(uint32_t kmin) {
     base = kmin;
     if (ITEMS) {
@@ -185,11 +194,21 @@ __device__ __forceinline__ void compact_ordered(const KeySet<ITEMS, KeyFn>& ks, 
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const uint64_t lt = (1ull << lane) - 1ull;
   int n_gt = 0, n_eq = 0;
+  if constexpr (ITEMS == 0) {
+    for (int i0 = 0; i0 < ks.items; i0 += 8) {
+      uint32_t kb[8];
+      ks.key_batch(i0, kb);
 #pragma unroll
-  for (int i = 0; i < (ITEMS ? ITEMS : ks.items); ++i) {
-    const uint32_t v = ks.key(i);       // per-lane counts (no ballots here: they would all be kept
-    n_gt += v > vT;                     // alive for the second loop and exhaust the scalar registers)
-    n_eq += v == vT;
+      for (int j = 0; j < 8; ++j)
+        if (i0 + j < ks.items) { n_gt += kb[j] > vT; n_eq += kb[j] == vT; }
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < (ITEMS ? ITEMS : ks.items); ++i) {
+      const uint32_t v = ks.key(i);       // per-lane counts (no ballots here: they would all be kept
+      n_gt += v > vT;                     // alive for the second loop and exhaust the scalar registers)
+      n_eq += v == vT;
+    }
   }
   n_gt = wave_sum_i(n_gt);
   n_eq = wave_sum_i(n_eq);
@@ -200,9 +219,7 @@ __device__ __forceinline__ void compact_ordered(const KeySet<ITEMS, KeyFn>& ks, 
   for (int i = 0; i < w; ++i) { gt_before += sh.wave_gt[i]; eq_before += sh.wave_eq[i]; }
   int eq_run = eq_before;
   int o_run = gt_before + min(eq_before, k_eq);
-#pragma unroll
-  for (int i = 0; i < (ITEMS ? ITEMS : ks.items); ++i) {
-    const uint32_t v = ks.key(i);
+  auto emit = [&](int i, uint32_t v) {
     const bool eq = v == vT;
     const uint64_t m_eq = __ballot(eq);
     const bool take = v > vT || (eq && eq_run + __popcll(m_eq & lt) < k_eq);
@@ -210,8 +227,22 @@ __device__ __forceinline__ void compact_ordered(const KeySet<ITEMS, KeyFn>& ks, 
     if (take) out[o_run + __popcll(m_take & lt)] = ks.page(i);
     eq_run += __popcll(m_eq);
     o_run += __popcll(m_take);
-    __builtin_amdgcn_sched_barrier(0);    // keep the iterations in order: hoisting every compare first
-  }                                       // needs two scalar register pairs per key
+  };
+  if constexpr (ITEMS == 0) {
+    for (int i0 = 0; i0 < ks.items; i0 += 8) {
+      uint32_t kb[8];
+      ks.key_batch(i0, kb);
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (i0 + j < ks.items) emit(i0 + j, kb[j]);       // wave-uniform condition
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < (ITEMS ? ITEMS : ks.items); ++i) {
+      emit(i, ks.key(i));
+      __builtin_amdgcn_sched_barrier(0);    // keep the iterations in order: hoisting every compare first
+    }                                       // needs two scalar register pairs per key
+  }
 }
 
 }  // namespace ekv

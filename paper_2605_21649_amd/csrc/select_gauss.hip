@@ -16,10 +16,11 @@
 // workgroup finishes the head alone over all pages (rare).
 //
 // Root finding: F is positive, decreasing and convex.  The start is the root of the same equation for a
-// single Gaussian with the pooled mean and variance of all pages; the iteration is Newton on log F
-// kept inside a bracket [lo, hi] with F(lo) >= 1 > F(hi) (a step that leaves it falls back to Newton on
-// F, then to bisection).  The left end a*mu_max - 1 is valid because cnt*E[(Y)_+^beta] >=
-// cnt*(E Y)_+^beta >= 1 there (Jensen).
+// single Gaussian with the pooled mean and variance of all pages, raised to the root of the mixture of the
+// hottest page of every wavefront of the first pass when that is higher (a few pages far above the bulk);
+// the iteration is Halley's on log F kept inside a bracket [lo, hi] with F(lo) >= 1 > F(hi) (a step that
+// leaves it falls back to Newton on log F, on F, then to bisection).  The left end a*mu_max - 1 is valid
+// because cnt*E[(Y)_+^beta] >= cnt*(E Y)_+^beta >= 1 there (Jensen).
 #include "ekv_select.h"
 #include "ekv_internal.h"
 
@@ -53,8 +54,9 @@ __device__ __forceinline__ float horner_tail(float s) {
 // t <  -2.5: those forms cancel catastrophically in float32; there h_n(t) = phi(t) * |t|^-(n+1) * P_n(1/t^2)
 //            with fitted degree-8 polynomials (relative error 2e-7, see gen_trunc_tail_coeffs.py).
 template <int NB>
-__device__ __forceinline__ void trunc_h(float t, float& h_nb, float& h_nbm1) {
-  if (t < -kTailXHi) { h_nb = 0.f; h_nbm1 = 0.f; return; }      // below float32 resolution of the sum
+__device__ __forceinline__ void trunc_h(float t, float& h_nb, float& h_nbm1, float& h_nbm2) {
+  // h_nbm2 = h_{NB-2} (for the second derivative of F); for NB = 1 it is the density phi(t) = dPhi/dt
+  if (t < -kTailXHi) { h_nb = 0.f; h_nbm1 = 0.f; h_nbm2 = 0.f; return; }   // below float32 resolution of the sum
   const float phi = __expf(-0.5f * t * t) * kInvSqrt2Pi;
   if (t >= -kTailXLo) {
     const float Phi = 0.5f * erfcf(-t * kInvSqrt2);
@@ -63,55 +65,72 @@ __device__ __forceinline__ void trunc_h(float t, float& h_nb, float& h_nbm1) {
     h[1] = fmaf(t, Phi, phi);
 #pragma unroll
     for (int n = 2; n <= NB; ++n) h[n] = fmaf(t, h[n - 1], (float)(n - 1) * h[n - 2]);
-    h_nb = h[NB]; h_nbm1 = h[NB - 1];
+    h_nb = h[NB]; h_nbm1 = h[NB - 1]; h_nbm2 = NB >= 2 ? h[NB >= 2 ? NB - 2 : 0] : phi;
   } else {
     const float inv = __builtin_amdgcn_rcpf(-t), u = inv * inv;
-    float p_nb, p_m1;
+    float p_nb, p_m1, p_m2 = 1.f;
     if (-t < kTailXSplit) {
       const float s = (u - kTailMid[0]) * kTailInvHalf[0];
       p_nb = horner_tail<0, NB>(s); p_m1 = horner_tail<0, NB - 1>(s);
+      if (NB >= 2) p_m2 = horner_tail<0, (NB >= 2 ? NB - 2 : 0)>(s);
     } else {
       const float s = (u - kTailMid[1]) * kTailInvHalf[1];
       p_nb = horner_tail<1, NB>(s); p_m1 = horner_tail<1, NB - 1>(s);
+      if (NB >= 2) p_m2 = horner_tail<1, (NB >= 2 ? NB - 2 : 0)>(s);
     }
-    float ip = phi;                        // phi * x^-NB
+    float ipm = phi;                       // phi * x^-(NB-1)
 #pragma unroll
-    for (int i = 0; i < NB; ++i) ip *= inv;
+    for (int i = 0; i < NB - 1; ++i) ipm *= inv;
+    const float ip = ipm * inv;            // phi * x^-NB
+    h_nbm2 = NB >= 2 ? ipm * p_m2 : phi;
     h_nbm1 = ip * p_m1;
     h_nb = ip * inv * p_nb;
   }
 }
 
 // cnt * M_NB and cnt * M_{NB-1} of Y ~ N(muY, sY^2)
+// Also d2 with F'' = NB * sum d2:  (NB-1) * cnt * M_{NB-2} for NB >= 2, cnt * density of Y at 0 for NB = 1.
 template <int NB>
-__device__ __forceinline__ void page_mass(float muY, float sY, float cnt, float& f, float& d) {
+__device__ __forceinline__ void page_mass(float muY, float sY, float cnt, float& f, float& d, float& d2) {
   if (sY > 1e-30f) {
-    float hb, hbm1;
-    trunc_h<NB>(muY * __builtin_amdgcn_rcpf(sY), hb, hbm1);
-    float sp = 1.f;                        // sY^(NB-1)
+    float hb, hbm1, hbm2;
+    const float rs = __builtin_amdgcn_rcpf(sY);
+    trunc_h<NB>(muY * rs, hb, hbm1, hbm2);
+    float sp2 = 1.f;                       // sY^(NB-2) (NB >= 2)
 #pragma unroll
-    for (int i = 0; i < NB - 1; ++i) sp *= sY;
+    for (int i = 0; i < NB - 2; ++i) sp2 *= sY;
+    const float sp = NB >= 2 ? sp2 * sY : 1.f;     // sY^(NB-1)
     f = cnt * sp * sY * hb;
     d = cnt * sp * hbm1;
+    d2 = NB >= 2 ? (float)(NB - 1) * cnt * sp2 * hbm2 : cnt * hbm2 * rs;
   } else {
     const float m = fmaxf(muY, 0.f);
-    float mp = 1.f;
+    float mp2 = 1.f;                       // m^(NB-2) (NB >= 3)
 #pragma unroll
-    for (int i = 0; i < NB - 1; ++i) mp *= m;
+    for (int i = 0; i < NB - 2; ++i) mp2 *= m;
+    const float mp = NB >= 2 ? mp2 * m : 1.f;
     f = cnt * mp * m;
     d = (NB == 1) ? (muY > 0.f ? cnt : 0.f) : cnt * mp;
+    d2 = NB >= 3 ? (float)(NB - 1) * cnt * mp2 : (NB == 2 && muY > 0.f ? cnt : 0.f);
   }
+}
+template <int NB>
+__device__ __forceinline__ void page_mass(float muY, float sY, float cnt, float& f, float& d) {
+  float d2;
+  page_mass<NB>(muY, sY, cnt, f, d, d2);
 }
 
 // Iteration state of one (b,h): the point the next evaluation is taken at, and its bracket.
 // `step` is the Newton step that led to tau (0: none yet, or the point came from a fallback).
 struct GaussState { float tau, lo, hi; int done; float step; };
 
-// workspace: state[2][BH], init partials [BH][S][4], eval partials [2][BH][S][2],
+// workspace: state[2][BH], init partials [BH][S][4], eval partials [2][BH][S][3],
+//            hottest page (a mu, a sigma, count) of every wavefront of the init launch [BH][S*4][3],
 //            per wavefront of the last evaluation launch: count [BH][S*4] and candidate lists
 //            (page, estimate) [BH][S*4][pw]
 struct GaussWs {
-  GaussState* state; float* init_part; float* eval_part; int32_t* sel_cnt; int32_t* sel_page; float* sel_key;
+  GaussState* state; float* init_part; float* eval_part; float* hot_part; int32_t* sel_cnt; int32_t* sel_page;
+  float* sel_key;
   int S, per, pw;    // slices per head, pages per slice, pages per wavefront of a slice
 };
 
@@ -136,10 +155,24 @@ __global__ __launch_bounds__(kGaussEvalThreads) void gauss_init_kernel(const flo
   const int per = (M + ws.S - 1) / ws.S;
   const int p0 = s * per, p1 = min(p0 + per, M);
   float mx = -INFINITY, s0 = 0.f, s1 = 0.f, s2 = 0.f;
+  float hk = -INFINITY, hm = 0.f, hs = 1.f, hc = 0.f;      // this thread's hottest page: a(mu + 2 sigma) largest
   for (int p = p0 + tid; p < p1; p += kGaussEvalThreads) {
     const float m = a * mu[(size_t)bh * Mmax + p], sd = a * sigma[(size_t)bh * Mmax + p];
     const float c = p == M - 1 ? cnt_last : (float)P;
     mx = fmaxf(mx, m); s0 += c; s1 = fmaf(c, m, s1); s2 = fmaf(c, fmaf(m, m, sd * sd), s2);
+    const float key = fmaf(2.f, sd, m);
+    if (key > hk) { hk = key; hm = m; hs = sd; hc = c; }
+  }
+  {
+    // the wavefront's hottest page (lowest lane on ties): one component of the start's mixture
+    const float kmax = wave_max(hk);
+    const uint64_t who = __ballot(hc > 0.f && hk == kmax);
+    const int src = who ? __builtin_ctzll(who) : 0;
+    const float wm = __shfl(hm, src), wsd = __shfl(hs, src), wc = who ? __shfl(hc, src) : 0.f;
+    if ((tid & 63) == 0) {
+      float* o = ws.hot_part + (((size_t)bh * ws.S + s) * kGaussWaves + (tid >> 6)) * 3;
+      o[0] = wm; o[1] = wsd; o[2] = wc;
+    }
   }
   mx = wave_max(mx); s0 = wave_sum(s0); s1 = wave_sum(s1); s2 = wave_sum(s2);
   if ((tid & 63) == 0) { red[tid >> 6][0] = mx; red[tid >> 6][1] = s0; red[tid >> 6][2] = s1; red[tid >> 6][3] = s2; }
@@ -183,47 +216,101 @@ __device__ float pooled_guess(float n, float m, float sd, float lo) {
   return tau;
 }
 
+// The pooled model misses a few pages far above the bulk (their mass decides tau when they exist).  The hottest
+// page of every wavefront of the init launch (at most 256 pages, four per lane here) gives F_hot <= F, so the
+// root of F_hot = 1 is a lower bound of tau_hat: if F_hot(tau) > 1 at the pooled start, the start is moved to
+// that root (Newton on log F_hot inside a bracket, secant on log F_hot when a step leaves it; to 2e-3 in
+// log F_hot).  One wavefront; on homogeneous pages the first evaluation gives F_hot <= 1 and nothing changes.
+struct HotPages { float m[4], s[4], c[4]; };
+
+__device__ __forceinline__ HotPages load_hot_pages(const float* __restrict__ hot, int n_hot) {
+  HotPages h;
+  const int lane = threadIdx.x & 63;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int i = lane + 64 * j;
+    const bool ok = i < n_hot;
+    const float* o = hot + (size_t)(ok ? i : 0) * 3;
+    h.m[j] = o[0]; h.s[j] = o[1]; h.c[j] = ok ? o[2] : 0.f;
+  }
+  return h;
+}
+
+template <int NB>
+__device__ float raise_to_hot_pages(float tau, const HotPages& h) {
+  float lo = -INFINITY, hi = INFINITY, glo = 0.f, ghi = 0.f;
+  for (int it = 0; it < 10; ++it) {
+    float f = 0.f, d = 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (h.c[j] > 0.f) {
+        float fp, dp;
+        page_mass<NB>(h.m[j] - tau, h.s[j], h.c[j], fp, dp);
+        f += fp; d += dp;
+      }
+    }
+    f = wave_sum(f); d = (float)NB * wave_sum(d);          // wave-uniform from here on
+    if (it == 0 && !(f > 1.0f)) break;                     // the pooled start is not below the hot pages' root
+    if (!(f > 0.f && d > 0.f)) { if (lo > -INFINITY) tau = lo; break; }
+    const float g = __logf(f);
+    if (fabsf(g) <= 2e-3f) break;
+    if (g > 0.f) { lo = tau; glo = g; } else { hi = tau; ghi = g; }
+    float next = tau + f * g / d;
+    if (!(next > lo && next < hi)) next = lo + (hi - lo) * glo / (glo - ghi);
+    tau = next;
+  }
+  return tau;
+}
+
 // Advance the iteration state with the result (F, D = -dF/dtau) of the evaluation at st.tau.
-// Stopping: F = 1 to float32 resolution; or a step below the resolution of tau; or two consecutive Newton steps
-// s1, s2 in the quadratic regime (|s2| <= |s1|/20): the error shrinks as e' = K e^2 with K = |s2|/s1^2, so after
-// the second step it is about |s2|^3/s1^2 -- accepted when that is below 1e-7 (relative to max(1, |tau|)),
-// without evaluating F at the new point.
-__device__ __forceinline__ GaussState advance_state(GaussState st, float F, float D) {
+// The update is Halley's on log F (the paper names Newton or Halley; the third moment it needs comes with the
+// other two), Newton's on log F where Halley's denominator is not positive.
+// Stopping: F = 1 to float32 resolution; or a step below the resolution of tau; or two consecutive such steps
+// s1, s2 with |s2| <= |s1|/20: an iteration of order >= 2 shrinks the error at least as e' = K e^2 with
+// K = |s2|/s1^2, so after the second step it is at most about |s2|^3/s1^2 -- accepted when that is below 1e-7
+// (relative to max(1, |tau|)), without evaluating F at the new point.
+__device__ __forceinline__ GaussState advance_state(GaussState st, float F, float D, float D2) {
   if (st.done) return st;
   if (fabsf(F - 1.0f) <= 2e-6f) { st.done = 1; return st; }         // float32 resolution of F: tau is the root
   if (F >= 1.0f) st.lo = st.tau; else st.hi = st.tau;
   float next = st.tau;
-  bool ok = false, newton_log = false;
+  bool ok = false, smooth = false;
   if (F > 0.f && D > 0.f) {
-    next = st.tau + F * __logf(F) / D;                              // Newton on log F
-    ok = next > st.lo && next < st.hi;
-    newton_log = ok;
+    // g = log F:  g' = -D/F,  g'' = D2/F - (D/F)^2.  Halley: -2 g g' / (2 g'^2 - g g''); Newton: -g / g'
+    const float g = __logf(F), g1 = -D / F, g2 = D2 / F - g1 * g1;
+    const float den = 2.f * g1 * g1 - g * g2;
+    if (den > 0.f) {
+      next = st.tau - 2.f * g * g1 / den;
+      ok = next > st.lo && next < st.hi;
+    }
+    if (!ok) { next = st.tau - g / g1; ok = next > st.lo && next < st.hi; }           // Newton on log F
+    smooth = ok;
     if (!ok) { next = st.tau + (F - 1.0f) / D; ok = next > st.lo && next < st.hi; }   // Newton on F
   }
   if (!ok) next = st.hi < INFINITY ? 0.5f * (st.lo + st.hi) : st.lo + 1.0f;
   const float step = next - st.tau, scale = fmaxf(1.f, fabsf(next));
   if (fabsf(step) <= 3e-7f * scale) st.done = 1;
-  if (newton_log && st.step != 0.f && fabsf(step) <= 0.05f * fabsf(st.step) &&
+  if (smooth && st.step != 0.f && fabsf(step) <= 0.05f * fabsf(st.step) &&
       fabsf(step) * step * step <= 1e-7f * scale * st.step * st.step) st.done = 1;
-  st.step = newton_log ? step : 0.f;
+  st.step = smooth ? step : 0.f;
   st.tau = next;
   return st;
 }
 
 // Sum of the S slice partials (F, D) of evaluation launch k, fixed order, broadcast to the block.
 __device__ __forceinline__ void sum_eval_partials(const GaussWs& ws, int k, int bh, int BH, float* bc, float& F,
-                                                  float& D) {
+                                                  float& D, float& D2) {
   const int tid = threadIdx.x;
-  float f = 0.f, d = 0.f;
+  float f = 0.f, d = 0.f, d2 = 0.f;
   if (tid < ws.S) {
-    const float* o = ws.eval_part + (((size_t)(k & 1) * BH + bh) * ws.S + tid) * 2;
-    f = o[0]; d = o[1];
+    const float* o = ws.eval_part + (((size_t)(k & 1) * BH + bh) * ws.S + tid) * 3;
+    f = o[0]; d = o[1]; d2 = o[2];
   }
-  if (tid < 64) { f = wave_sum(f); d = wave_sum(d); }
+  if (tid < 64) { f = wave_sum(f); d = wave_sum(d); d2 = wave_sum(d2); }
   __syncthreads();
-  if (tid == 0) { bc[0] = f; bc[1] = d; }
+  if (tid == 0) { bc[0] = f; bc[1] = d; bc[2] = d2; }
   __syncthreads();
-  F = bc[0]; D = bc[1];
+  F = bc[0]; D = bc[1]; D2 = bc[2];
 }
 
 template <int NB>
@@ -232,7 +319,7 @@ __global__ __launch_bounds__(kGaussEvalThreads) void gauss_eval_kernel(const flo
                                                                        const int32_t* __restrict__ seq_lens,
                                                                        GaussWs ws, int k, ZqTable zq, float margin,
                                                                        float a, int Hq, int P, int Mmax, int BH) {
-  __shared__ float red[kGaussWaves][2];
+  __shared__ float red[kGaussWaves][3];
   __shared__ float bc[4];
   const int bh = blockIdx.y, s = blockIdx.x, b = bh / Hq, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const uint64_t lt = (1ull << lane) - 1ull;
@@ -254,6 +341,8 @@ __global__ __launch_bounds__(kGaussEvalThreads) void gauss_eval_kernel(const flo
   GaussState st;
   if (k == 0) {
     // start: left end from max a*mu, first point from the pooled single-Gaussian model
+    HotPages hot;
+    if (tid < 64) hot = load_hot_pages(ws.hot_part + (size_t)bh * ws.S * kGaussWaves * 3, ws.S * kGaussWaves);
     float mx = -INFINITY, s0 = 0.f, s1 = 0.f, s2 = 0.f;
     if (tid < ws.S) {
       const float* o = ws.init_part + ((size_t)bh * ws.S + tid) * 4;
@@ -268,15 +357,18 @@ __global__ __launch_bounds__(kGaussEvalThreads) void gauss_eval_kernel(const flo
     st.lo = mx - 1.0f; st.hi = INFINITY; st.done = 0; st.step = 0.f;
     // the scalar start iteration runs on one wavefront only (the others would just repeat it)
     float tau0 = 0.f;
-    if (tid < 64) tau0 = pooled_guess<NB>(s0, mean, sqrtf(var), st.lo);
+    if (tid < 64) {
+      tau0 = pooled_guess<NB>(s0, mean, sqrtf(var), st.lo);
+      tau0 = raise_to_hot_pages<NB>(tau0, hot);
+    }
     __syncthreads();
     if (tid == 0) bc[0] = tau0;
     __syncthreads();
     st.tau = bc[0];
   } else {
-    float F, D;
-    sum_eval_partials(ws, k - 1, bh, BH, bc, F, D);
-    st = advance_state(ws.state[(size_t)((k - 1) & 1) * BH + bh], F, (float)NB * D);
+    float F, D, D2;
+    sum_eval_partials(ws, k - 1, bh, BH, bc, F, D, D2);
+    st = advance_state(ws.state[(size_t)((k - 1) & 1) * BH + bh], F, (float)NB * D, (float)NB * D2);
   }
   if (s == 0 && tid == 0) ws.state[(size_t)(k & 1) * BH + bh] = st;
   const bool last = k == kGaussIters - 1;                 // this launch also writes the candidates
@@ -289,16 +381,16 @@ __global__ __launch_bounds__(kGaussEvalThreads) void gauss_eval_kernel(const flo
   int32_t* lpage = ws.sel_page + sub * ws.pw;
   float* lkey = ws.sel_key + sub * ws.pw;
   int n_c = 0;
-  float f = 0.f, d = 0.f;
+  float f = 0.f, d = 0.f, d2 = 0.f;
   auto batch = [&](const float (&mv)[4], const float (&sv)[4], int pb) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int p = pb + j * 64;
       const bool ok = p < wend;
       if (ok) {                                                        // no loads inside: divergence is harmless
-        float fp, dp;
-        page_mass<NB>(fmaf(a, mv[j], -st.tau), a * sv[j], p == M - 1 ? cnt_last : (float)P, fp, dp);
-        f += fp; d += dp;
+        float fp, dp, dp2;
+        page_mass<NB>(fmaf(a, mv[j], -st.tau), a * sv[j], p == M - 1 ? cnt_last : (float)P, fp, dp, dp2);
+        f += fp; d += dp; d2 += dp2;
       }
       if (last) {                                                      // wave-uniform
         const float key = a * fmaf(sv[j], p == M - 1 ? z_last : z_full, mv[j]);
@@ -320,21 +412,21 @@ __global__ __launch_bounds__(kGaussEvalThreads) void gauss_eval_kernel(const flo
     batch(mv, sv, pb);
   }
   if (last && lane == 0) ws.sel_cnt[sub] = n_c;
-  f = wave_sum(f); d = wave_sum(d);
-  if (lane == 0) { red[w][0] = f; red[w][1] = d; }
+  f = wave_sum(f); d = wave_sum(d); d2 = wave_sum(d2);
+  if (lane == 0) { red[w][0] = f; red[w][1] = d; red[w][2] = d2; }
   __syncthreads();
   if (tid == 0) {
-    for (int i = 1; i < kGaussWaves; ++i) { f += red[i][0]; d += red[i][1]; }
-    float* o = ws.eval_part + (((size_t)(k & 1) * BH + bh) * ws.S + s) * 2;
-    o[0] = f; o[1] = d;
+    for (int i = 1; i < kGaussWaves; ++i) { f += red[i][0]; d += red[i][1]; d2 += red[i][2]; }
+    float* o = ws.eval_part + (((size_t)(k & 1) * BH + bh) * ws.S + s) * 3;
+    o[0] = f; o[1] = d; o[2] = d2;
   }
 }
 
 // Takes the last state update, keeps the candidates above the final threshold and writes them in page order.
-// Rare cases are handled here by one workgroup per head over all pages: an iteration that has not converged is
-// continued to convergence (then, or when the final threshold is below the speculative one, the pages are
-// re-examined); nothing passed -> the single best page; more than cap pages -> the cap best estimates (lower
-// index on ties), flagged.
+// Rare cases are handled here by one workgroup per head: an iteration that has not converged is continued to
+// convergence over all pages; if the final threshold is below the speculative one the pages are re-examined;
+// nothing passed -> the single best page; more than cap pages -> the cap best estimates (lower index on
+// ties), flagged.
 template <int NB, int ITEMS>
 __global__ __launch_bounds__(kSelThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void gauss_gather_kernel(
     const float* __restrict__ mu, const float* __restrict__ sigma, const int32_t* __restrict__ seq_lens,
@@ -352,11 +444,38 @@ __global__ __launch_bounds__(kSelThreads) __attribute__((amdgpu_waves_per_eu(4, 
   int32_t* out = page_idx + (size_t)bh * cap;
   if (M <= 0) { if (tid == 0) { n_sel[bh] = 0; overflow[bh] = 0; tau_hat[bh] = 0.f; } return; }
   const GaussState st1 = ws.state[(size_t)((kGaussIters - 1) & 1) * BH + bh];
-  float F, D;
-  sum_eval_partials(ws, kGaussIters - 1, bh, BH, bc, F, D);
-  GaussState st = advance_state(st1, F, (float)NB * D);
+  float F, D, D2;
+  sum_eval_partials(ws, kGaussIters - 1, bh, BH, bc, F, D, D2);
+  GaussState st = advance_state(st1, F, (float)NB * D, (float)NB * D2);
   int count = -1;
-  if (st.done && st.tau - margin >= spec_threshold(st1.tau, margin)) {
+  const float cnt_last = (float)(n - (M - 1) * P);
+  const float* mu_r = mu + (size_t)bh * Mmax;
+  const float* sg_r = sigma + (size_t)bh * Mmax;
+  for (int it = 0; it < 64 && !st.done; ++it) {            // finish the root iteration alone
+    float f = 0.f, d = 0.f, d2 = 0.f;
+    for (int p0 = tid; p0 < M; p0 += 4 * kSelThreads) {      // four pages per batch of loads
+      float mv[4], sv[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int p = min(p0 + j * kSelThreads, M - 1);
+        mv[j] = mu_r[p]; sv[j] = sg_r[p];
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int p = p0 + j * kSelThreads;
+        if (p < M) {
+          float fp, dp, dp2;
+          page_mass<NB>(fmaf(a, mv[j], -st.tau), a * sv[j], p == M - 1 ? cnt_last : (float)P, fp, dp, dp2);
+          f += fp; d += dp; d2 += dp2;
+        }
+      }
+    }
+    const float Fs = block_sum(f, red_f);
+    const float Ds = block_sum(d, red_f);
+    const float D2s = block_sum(d2, red_f);
+    st = advance_state(st, Fs, (float)NB * Ds, (float)NB * D2s);
+  }
+  if (st.tau - margin >= spec_threshold(st1.tau, margin)) {   // the candidates are complete
     const float thr = st.tau - margin;
     const int NSS = ws.S * kGaussWaves;                      // candidate lists of this head (<= 256)
     const int c = tid < NSS ? ws.sel_cnt[(size_t)bh * NSS + tid] : 0;
@@ -397,20 +516,6 @@ __global__ __launch_bounds__(kSelThreads) __attribute__((amdgpu_waves_per_eu(4, 
       return;
     }
   }
-  const float cnt_last = (float)(n - (M - 1) * P);
-  const float* mu_r = mu + (size_t)bh * Mmax;
-  const float* sg_r = sigma + (size_t)bh * Mmax;
-  for (int it = 0; it < 64 && !st.done; ++it) {            // finish the root iteration alone
-    float f = 0.f, d = 0.f;
-    for (int p = tid; p < M; p += kSelThreads) {
-      float fp, dp;
-      page_mass<NB>(fmaf(a, mu_r[p], -st.tau), a * sg_r[p], p == M - 1 ? cnt_last : (float)P, fp, dp);
-      f += fp; d += dp;
-    }
-    const float Fs = block_sum(f, red_f);
-    const float Ds = block_sum(d, red_f);
-    st = advance_state(st, Fs, (float)NB * Ds);
-  }
   if (tid == 0) tau_hat[bh] = st.tau;
   const float z_full = zq.z[P], z_last = zq.z[n - (M - 1) * P];
   auto keyfn = [=](int p) { return float_to_key(a * fmaf(sg_r[p], p == M - 1 ? z_last : z_full, mu_r[p])); };
@@ -418,8 +523,17 @@ __global__ __launch_bounds__(kSelThreads) __attribute__((amdgpu_waves_per_eu(4, 
   if (count < 0) {                                         // the candidates were not usable: count here
     const uint32_t kthr = float_to_key(st.tau - margin);
     int c = 0;
+    if constexpr (ITEMS == 0) {
+      for (int i0 = 0; i0 < ks.items; i0 += 8) {
+        uint32_t kb[8];
+        ks.key_batch(i0, kb);
 #pragma unroll
-    for (int i = 0; i < (ITEMS ? ITEMS : ks.items); ++i) c += ks.key(i) > kthr;
+        for (int j = 0; j < 8; ++j) c += i0 + j < ks.items && kb[j] > kthr;
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < (ITEMS ? ITEMS : ks.items); ++i) c += ks.key(i) > kthr;
+    }
     count = block_sum_i(c, sh.scan_buf);
     if (count >= 1 && count <= cap) {
       compact_ordered(ks, kthr, 0, sh, out);
@@ -452,8 +566,8 @@ static int gauss_pw(const Dims& dm, int S) { return (gauss_per(dm, S) + kGaussWa
 
 size_t select_gauss_ws_bytes(const Dims& dm) {
   const size_t BH = (size_t)dm.B * dm.Hq, S = gauss_splits(dm), pw = gauss_pw(dm, (int)S);
-  size_t b = 2 * BH * sizeof(GaussState) + BH * S * 4 * sizeof(float) + 2 * BH * S * 2 * sizeof(float) +
-             BH * S * kGaussWaves * sizeof(int32_t) + BH * S * kGaussWaves * pw * (sizeof(int32_t) + sizeof(float));
+  size_t b = 2 * BH * sizeof(GaussState) + BH * S * 4 * sizeof(float) + 2 * BH * S * 3 * sizeof(float) +
+             BH * S * kGaussWaves * 3 * sizeof(float) + BH * S * kGaussWaves * sizeof(int32_t) + BH * S * kGaussWaves * pw * (sizeof(int32_t) + sizeof(float));
   return (b + 255) & ~(size_t)255;
 }
 
@@ -492,7 +606,8 @@ void launch_select_gauss(const Dims& dm, const float* mu, const float* sigma, co
   ws.state = (GaussState*)workspace;
   ws.init_part = (float*)(ws.state + 2 * BH);
   ws.eval_part = ws.init_part + BH * ws.S * 4;
-  ws.sel_cnt = (int32_t*)(ws.eval_part + 2 * BH * ws.S * 2);
+  ws.hot_part = ws.eval_part + 2 * BH * ws.S * 3;
+  ws.sel_cnt = (int32_t*)(ws.hot_part + BH * ws.S * kGaussWaves * 3);
   ws.sel_page = ws.sel_cnt + BH * ws.S * kGaussWaves;
   ws.sel_key = (float*)(ws.sel_page + BH * ws.S * kGaussWaves * ws.pw);
   switch (dm.ibeta) {
