@@ -107,9 +107,19 @@ __device__ __forceinline__ void radix_select_kth(KeySet<ITEMS, KeyFn>& ks, int k
                                                  uint32_t& vT_out, int& k_eq_out) {
   const int tid = threadIdx.x;
   uint32_t lo = 0xffffffffu, hi = 0u;
+  if constexpr (ITEMS == 0) {
+    for (int i0 = 0; i0 < ks.items; i0 += 8) {
+      uint32_t kb[8];
+      ks.key_batch(i0, kb);
 #pragma unroll
-  for (int i = 0; i < (ITEMS ? ITEMS : ks.items); ++i) {
-    if (ks.valid(i)) { const uint32_t key = ks.key(i); lo = min(lo, key); hi = max(hi, key); }
+      for (int j = 0; j < 8; ++j)
+        if (ks.page(i0 + j) < ks.M) { lo = min(lo, kb[j]); hi = max(hi, kb[j]); }
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < (ITEMS ? ITEMS : ks.items); ++i) {
+      if (ks.valid(i)) { const uint32_t key = ks.key(i); lo = min(lo, key); hi = max(hi, key); }
+    }
   }
   for (int d = 32; d >= 1; d >>= 1) {
     lo = min(lo, (uint32_t)__shfl_xor((int)lo, d));
@@ -139,10 +149,20 @@ __device__ __forceinline__ void radix_select_kth(KeySet<ITEMS, KeyFn>& ks, int k
     __syncthreads();
     // Slots past M hold the rebased key 0.  They are counted (as copies of the smallest key) but not sent
     // through the histogram one by one: thousands of atomics on one LDS address serialise.
+    if constexpr (ITEMS == 0) {
+      for (int i0 = 0; i0 < ks.items; i0 += 8) {
+        uint32_t kb[8];
+        ks.key_batch(i0, kb);
 #pragma unroll
-    for (int i = 0; i < (ITEMS ? ITEMS : ks.items); ++i) {
-      const uint32_t v = ks.key(i);
-      if (ks.page(i) < ks.M && (first || (v >> up) == prefix)) atomicAdd(&sh.hist[(v >> shift) & dmask], 1u);
+        for (int j = 0; j < 8; ++j)
+          if (ks.page(i0 + j) < ks.M && (first || (kb[j] >> up) == prefix)) atomicAdd(&sh.hist[(kb[j] >> shift) & dmask], 1u);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < (ITEMS ? ITEMS : ks.items); ++i) {
+        const uint32_t v = ks.key(i);
+        if (ks.page(i) < ks.M && (first || (v >> up) == prefix)) atomicAdd(&sh.hist[(v >> shift) & dmask], 1u);
+      }
     }
     if (tid == 0 && pad_counted && n_pad > 0) atomicAdd(&sh.hist[0], (uint32_t)n_pad);
     __syncthreads();
@@ -166,10 +186,20 @@ __device__ __forceinline__ void radix_select_kth(KeySet<ITEMS, KeyFn>& ks, int k
       __syncthreads();                             // every thread has read the count
       if (tid == 0) sh.scan_buf[kSelWaves] = 0;
       __syncthreads();
+      if constexpr (ITEMS == 0) {
+        for (int i0 = 0; i0 < ks.items; i0 += 8) {
+          uint32_t kb[8];
+          ks.key_batch(i0, kb);
 #pragma unroll
-      for (int i = 0; i < (ITEMS ? ITEMS : ks.items); ++i) {
-        const uint32_t v = ks.key(i);
-        if (ks.page(i) < ks.M && (v >> shift) == prefix) sh.hist[atomicAdd(&sh.scan_buf[kSelWaves], 1)] = v;
+          for (int j = 0; j < 8; ++j)
+            if (ks.page(i0 + j) < ks.M && (kb[j] >> shift) == prefix) sh.hist[atomicAdd(&sh.scan_buf[kSelWaves], 1)] = kb[j];
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < (ITEMS ? ITEMS : ks.items); ++i) {
+          const uint32_t v = ks.key(i);
+          if (ks.page(i) < ks.M && (v >> shift) == prefix) sh.hist[atomicAdd(&sh.scan_buf[kSelWaves], 1)] = v;
+        }
       }
       __syncthreads();
       if (tid < members) {

@@ -59,7 +59,7 @@ constexpr int kTkThreads = 256;
 constexpr int kTkWaves = kTkThreads / 64;
 constexpr int kTkItems = 16;                                  // keys per lane
 constexpr int kTkSlice = kTkThreads * kTkItems;               // pages per slice: 4096
-constexpr int kTkSample = 1024;                               // pages the key range is estimated from
+constexpr int kTkSample = 1024;                               // pages the key range is estimated from (16 runs of 64)
 constexpr int kTkMembers = 1024;                              // ranking list of the find kernel
 constexpr int kTkMaxSlices = 64;
 constexpr int kTkPrefix = 512;                                // best pages of a slice kept sorted by bin
@@ -117,12 +117,18 @@ __global__ __launch_bounds__(kTkThreads) void topk_hist_kernel(const float* __re
     for (int i = tid; i < kBins; i += kTkThreads) ws.above[((size_t)bh * ws.S + slice) * kBins + i] = (uint16_t)0;
     return;
   }
-  // key range of the first kTkSample pages, widened by half its width on both sides
+  // key range of kTkSample pages -- 16 runs of 64 consecutive pages spread evenly over the sequence, so that a
+  // trend along the sequence (recent pages scoring higher, a block of high pages at the start) is inside the
+  // range -- widened by half its width on both sides
   uint32_t lo = 0xffffffffu, hi = 0u;
   {
+    const int run_stride = max(64, (M / (kTkSample / 64)) & ~63);
     float sv[kTkSample / kTkThreads];
 #pragma unroll
-    for (int i = 0; i < kTkSample / kTkThreads; ++i) sv[i] = s[min(tid + i * kTkThreads, M - 1)];
+    for (int i = 0; i < kTkSample / kTkThreads; ++i) {
+      const int j = tid + i * kTkThreads;
+      sv[i] = s[min((j >> 6) * run_stride + (j & 63), M - 1)];
+    }
 #pragma unroll
     for (int i = 0; i < kTkSample / kTkThreads; ++i) {
       const uint32_t kk = float_to_key(sv[i]);

@@ -202,6 +202,8 @@ def test_select_topk_long_context(M, k):
     scores[0, 3, :1024] = 1.0; scores[0, 3, 1024:] += 40.0         # range estimate from the first pages is off
     scores[0, 4] = np.abs(scores[0, 4]) * 1e-3 * rng.choice([-1.0, 1.0], size=Mmax)   # both signs
     scores[0, 5, ::2] = scores[0, 5, 1::2]                         # every value twice
+    scores[0, 6] += np.linspace(0.0, 18.0, Mmax, dtype=np.float32)  # trend along the sequence: the top pages crowd the last slices
+    scores[0, 7, rng.choice(M, 40, replace=False)] += 60.0         # a few pages far above the sampled range
     box = torch.from_numpy(scores).to(dev)
     seq_lens = torch.full((B,), M * P - 5, dtype=torch.int32, device=dev)
     page_idx = torch.full((B, Hq, k), -1, dtype=torch.int32, device=dev)
