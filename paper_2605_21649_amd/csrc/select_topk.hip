@@ -254,50 +254,45 @@ __global__ __launch_bounds__(kSelThreads) void topk_find_kernel(const float* __r
     return;
   }
   // Members of bin b1.  In slice s they sit at positions [above_s[b1], above_s[b1 - 1]) of its prefix list
-  // (above_s[-1] := pages of the slice); if every slice's range ends inside its list, they are copied
-  // from there.  Otherwise (very large budgets) the scores are scanned.
-  __shared__ int s_lo[kTkMaxSlices], s_cnt_s[kTkMaxSlices], s_start[kTkMaxSlices + 1];
-  __shared__ int s_short;
-  if (tid == 0) s_short = 0;
-  __syncthreads();
+  // (above_s[-1] := pages of the slice): copied from there when the range ends inside the list.  A slice
+  // whose range does not (more than kTkPrefix of its pages at or above the bin: the top pages crowd into a
+  // few slices, or the budget is very large) has its 4096 scores scanned instead.
+  __shared__ int s_lo[kTkMaxSlices], s_cnt_s[kTkMaxSlices], s_start[kTkMaxSlices + 1], s_scan[kTkMaxSlices];
   if (tid < S) {
     const uint16_t* ab = ws.above + ((size_t)bh * S + tid) * kBins;
     const int lo_s = (int)ab[b1];
     const int valid_s = max(0, min(kTkSlice, M - tid * kTkSlice));
     const int hi_s = b1 == 0 ? valid_s : (int)ab[b1 - 1];
-    s_lo[tid] = lo_s; s_cnt_s[tid] = hi_s - lo_s;
-    if (hi_s > kTkPrefix && hi_s > lo_s) atomicOr(&s_short, 1);
+    const bool scan = hi_s > kTkPrefix && hi_s > lo_s;
+    s_lo[tid] = lo_s; s_cnt_s[tid] = scan ? 0 : hi_s - lo_s; s_scan[tid] = scan ? 1 : 0;
   }
   __syncthreads();
-  const bool from_lists = s_short == 0;
-  if (from_lists) {
-    if (tid == 0) {
-      int run = 0;
-      for (int i = 0; i < S; ++i) { s_start[i] = run; run += s_cnt_s[i]; }
-      s_start[S] = run;
-      s_m = run;
-    }
-    __syncthreads();
-    for (int sl = tid >> 6; sl < S; sl += kSelWaves) {
-      const uint32_t* pk = ws.prefix_key + ((size_t)bh * S + sl) * kTkPrefix + s_lo[sl];
-      const int32_t* pp = ws.prefix_page + ((size_t)bh * S + sl) * kTkPrefix + s_lo[sl];
-      for (int e = tid & 63; e < s_cnt_s[sl]; e += 64) {
-        const int slot = s_start[sl] + e;
-        if (slot < kTkMembers) { mem_key[slot] = pk[e]; mem_page[slot] = pp[e]; }
-      }
+  if (tid == 0) {
+    int run = 0;
+    for (int i = 0; i < S; ++i) { s_start[i] = run; run += s_cnt_s[i]; }
+    s_start[S] = run;
+    s_m = run;                                         // the scanned slices append behind the copied ones
+  }
+  __syncthreads();
+  for (int sl = tid >> 6; sl < S; sl += kSelWaves) {
+    const uint32_t* pk = ws.prefix_key + ((size_t)bh * S + sl) * kTkPrefix + s_lo[sl];
+    const int32_t* pp = ws.prefix_page + ((size_t)bh * S + sl) * kTkPrefix + s_lo[sl];
+    for (int e = tid & 63; e < s_cnt_s[sl]; e += 64) {
+      const int slot = s_start[sl] + e;
+      if (slot < kTkMembers) { mem_key[slot] = pk[e]; mem_page[slot] = pp[e]; }
     }
   }
-  const int per_wave = from_lists ? 0 : ((M + kSelWaves - 1) / kSelWaves + 63) & ~63;
-  const int wbase = (tid >> 6) * per_wave + (tid & 63);
-  for (int i0 = 0; i0 < per_wave; i0 += 32 * 64) {
-    float raw[32];
+  for (int sl = 0; sl < S; ++sl) {
+    if (!s_scan[sl]) continue;                         // workgroup-uniform
+    constexpr int PER = kTkSlice / kSelThreads;        // 4 scores per thread
+    float raw[PER];
 #pragma unroll
-    for (int i = 0; i < 32; ++i) raw[i] = s[min(wbase + i0 + i * 64, M - 1)];
+    for (int i = 0; i < PER; ++i) raw[i] = s[min(sl * kTkSlice + tid + i * kSelThreads, M - 1)];
 #pragma unroll
-    for (int i = 0; i < 32; ++i) {
-      const int p = wbase + i0 + i * 64;
+    for (int i = 0; i < PER; ++i) {
+      const int p = sl * kTkSlice + tid + i * kSelThreads;
       const uint32_t kk = float_to_key(raw[i]);
-      if (i0 + i * 64 < per_wave && p < M && topk_bin(kk, hd.lo, hd.shift) == b1) {
+      if (p < M && topk_bin(kk, hd.lo, hd.shift) == b1) {
         const int slot = atomicAdd(&s_m, 1);           // arrival order is irrelevant: ranks below are exact
         if (slot < kTkMembers) { mem_key[slot] = kk; mem_page[slot] = p; }
       }
