@@ -420,9 +420,15 @@ template <typename Src>
 __device__ __forceinline__ void eval_mass(const Src& src, float tau, float beta, int ibeta, SolveShared& sh,
                                           int parity, float& F, float& D, int& cnt) {
   float f = 0.f, d = 0.f; int c = 0;
-  for (int i = threadIdx.x; i < src.n; i += kSolveThreads) {
-    const float x = src.get_u(i) - tau;
-    if (x > 0.f) { f += pow_beta(x, beta, ibeta); d += pow_beta_m1(x, beta, ibeta); ++c; }
+  for (int i0 = threadIdx.x; i0 < src.n; i0 += 8 * kSolveThreads) {     // eight loads in flight per thread
+    float u[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) u[j] = src.get_u(min(i0 + j * kSolveThreads, src.n - 1));
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float x = i0 + j * kSolveThreads < src.n ? u[j] - tau : -1.f;
+      if (x > 0.f) { f += pow_beta(x, beta, ibeta); d += pow_beta_m1(x, beta, ibeta); ++c; }
+    }
   }
   f = wave_sum(f); d = wave_sum(d); c = wave_sum_i(c);
   const int w = threadIdx.x >> 6;
@@ -957,12 +963,41 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
     float acc[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[i] = 0.f;
-    for (int e = rs; e < n_cand; e += kSolveThreads / 16) {
-      const float x = zr[e] - zmax - tau_u;
-      if (x > 0.f) {
-        const float p = pow_beta(x, beta, ibeta);
+    // Rounds of 4096 candidates (wavefront w owns 256 consecutive ones): the support tokens of a round are
+    // compacted into LDS (weight, V row) -- at most 4096, so they always fit -- and gathered by the 64 row slots
+    // with independent loads.  (A loop over all candidates with one score load per iteration and row slot waited
+    // for memory n_cand / 64 times: 2 ms for a row of 262 144.)
+    for (int base = 0; base < n_cand; base += 4 * kSolveThreads) {
+      float xs[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) xs[i] = zr[min(base + w * 256 + i * 64 + lane, n_cand - 1)];
+      int cw = 0;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        xs[i] = base + w * 256 + i * 64 + lane < n_cand ? xs[i] - zmax - tau_u : -1.f;
+        cw += __popcll(__ballot(xs[i] > 0.f));
+      }
+      if (lane == 0) sh.wcount[parity][w] = cw;
+      __syncthreads();                                   // also: the previous round's gather is done
+      int off = 0, tot = 0;
+      for (int i = 0; i < kSolveWaves; ++i) { const int ci = sh.wcount[parity][i]; if (i < w) off += ci; tot += ci; }
+      parity ^= 1;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const bool in = xs[i] > 0.f;
+        const uint64_t mk = __ballot(in);
+        if (in) {
+          const int o = off + __popcll(mk & lt);
+          sh.list_u[o] = pow_beta(xs[i], beta, ibeta);
+          sh.list_row[o] = v_row_of<DENSE>(A, b, lrow, hkv, base + w * 256 + i * 64 + lane);
+        }
+        off += __popcll(mk);
+      }
+      __syncthreads();
+      for (int e = rs; e < tot; e += kSolveThreads / 16) {
+        const float p = sh.list_u[e];
         float vv[8];
-        load8<T>(v_pool + (size_t)v_row_of<DENSE>(A, b, lrow, hkv, e) * kD + 8 * c, vv);
+        load8<T>(v_pool + (size_t)sh.list_row[e] * kD + 8 * c, vv);
 #pragma unroll
         for (int i = 0; i < 8; ++i) acc[i] = fmaf(p, vv[i], acc[i]);
       }
