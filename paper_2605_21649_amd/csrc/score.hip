@@ -409,9 +409,19 @@ void launch_score_pages(const Dims& dm, const void* q, const ekv_stats_view& s, 
                         int mode, float* box, float* mu, float* sigma, hipStream_t st, const ekv_cache_view* append_to,
                         const void* k_new, const void* v_new) {
   ScoreAppend ap{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0, 0, dm.HkvPool, 0, 0};
-  if (append_to != nullptr)
+  if (append_to != nullptr) {
     ap = ScoreAppend{append_to->k_pool, append_to->v_pool, append_to->block_table, k_new, v_new, s.box, s.gauss,
                      s.box8, append_to->n_phys_pages, 1, dm.HkvPool, 0, 0};
+    if (dm.P > 32) {
+      // Inside the scoring launch a page other than 16 tokens is read row by row (a batch of loads per lane
+      // would raise the register count of the kernel, which sets the occupancy of the whole stream): 16
+      // dependent loads for 64 tokens, and the launch is as long as that chain (23 us instead of 14 at 8192
+      // pages).  Such pages take the append kernel first (one batch of loads there); the scoring launch then
+      // only counts the new token (mode 2).  Up to 32 tokens the chain is short enough to stay inside.
+      launch_stats_append(dm, *append_to, s, k_new, v_new, st);
+      ap.mode = 2;
+    }
+  }
   switch (dm.G) {
     case 1: launch_score_G<1>(dm, q, s, seq_lens, mode, box, mu, sigma, st, ap); break;
     case 2: launch_score_G<2>(dm, q, s, seq_lens, mode, box, mu, sigma, st, ap); break;

@@ -161,6 +161,7 @@ void launch_stats_append(const Dims& dm, const ekv_cache_view& c, const ekv_stat
   const bool f32 = dm.dtype == EKV_F32;
   if (dm.P == 16) { if (f32) launch_append_T<float, 16>(dm, c, s, k_new, v_new, st); else launch_append_T<bf16_t, 16>(dm, c, s, k_new, v_new, st); }
   else if (dm.P == 32) { if (f32) launch_append_T<float, 32>(dm, c, s, k_new, v_new, st); else launch_append_T<bf16_t, 32>(dm, c, s, k_new, v_new, st); }
+  else if (dm.P == 64) { if (f32) launch_append_T<float, 64>(dm, c, s, k_new, v_new, st); else launch_append_T<bf16_t, 64>(dm, c, s, k_new, v_new, st); }
   else { if (f32) launch_append_T<float, 0>(dm, c, s, k_new, v_new, st); else launch_append_T<bf16_t, 0>(dm, c, s, k_new, v_new, st); }
 }
 
