@@ -156,10 +156,12 @@ ekv_status ekv_score_pages(const ekv_config* cfg, const void* q, const ekv_stats
                            const int32_t* seq_lens, int32_t mode, float* box, float* mu,
                            float* sigma, void* stream);
 
-/* a2 + a3/a4 in one launch: ekv_stats_append followed by ekv_score_pages over the lengths n_b + 1, bit for bit,
- * without the separate small launch of the append on the critical path of a decode step: the workgroup of
- * the scoring kernel whose tile holds the new token's page appends it first (cache slot written, that page's
- * statistics recomputed), every other workgroup starts scoring at once.  cache->seq_lens holds the lengths
+/* a2 + a3/a4 in one call: ekv_stats_append followed by ekv_score_pages over the lengths n_b + 1, bit for bit.
+ * For pages of up to 32 tokens it is one launch, without the separate small launch of the append on the
+ * critical path of a decode step: a workgroup of the scoring kernel appends the token first (cache slot
+ * written, that page's statistics recomputed) and scores the tile of that page, every other workgroup starts
+ * scoring at once.  Larger pages take the two launches (the append is too long a chain of loads to hide inside
+ * the scoring kernel).  cache->seq_lens holds the lengths
  * BEFORE the append (slot n_b is written) and is not modified; the scores cover n_b + 1 tokens, so add 1 to
  * every entry before the selection and decode calls.  Arguments as in the two calls it replaces; both
  * statistics arrays must be given whatever `mode` scores. */
