@@ -221,7 +221,7 @@ def test_select_topk_long_context(M, k):
 
 def test_select_gauss_long_context():
     """Gaussian selector with 65536 pages per head (keys held in registers, 64 per lane)."""
-    P, B, Hq, M = 16, 1, 4, 65536
+    P, B, Hq, M = 16, 1, 6, 65536
     cap = 3000
     cfg = ekv.make_config(B, Hq, Hq, 128, P, "bf16", 1.5, 0.1, M, cap)
     dev = torch.device("cuda")
@@ -232,6 +232,8 @@ def test_select_gauss_long_context():
     mu[0, 2, : M // 2] -= 12.0                                      # bimodal: the pooled start is far off
     sg[0, 2, : M // 2] *= 0.05
     mu[0, 3, rng.choice(M, 3, replace=False)] += 9.0; sg[0, 3] *= 0.02   # three pages carry all the mass
+    sg[0, 4] = (np.abs(rng.normal(size=M)) * 0.6 + 0.05).astype(np.float32)   # page deviations from 0.05 to ~2
+    mu[0, 5] = (1.0 + 0.25 * rng.standard_t(3, size=M)).astype(np.float32)   # heavy-tailed page means
     seq_lens = torch.full((B,), M * P - 7, dtype=torch.int32, device=dev)
     t = lambda a: torch.from_numpy(a).to(dev)
     tau_hat = torch.zeros(B, Hq, device=dev); page_idx = torch.zeros(B, Hq, cap, dtype=torch.int32, device=dev)
