@@ -202,7 +202,8 @@ __device__ __forceinline__ int block_sum_i(int v, int* buf) {
 
 // Order-preserving map float -> uint32 (larger float <=> larger key); -inf maps near 0.
 __device__ __forceinline__ uint32_t float_to_key(float f) {
-  const uint32_t u = __float_as_uint(f);
+  const uint32_t u0 = __float_as_uint(f);
+  const uint32_t u = u0 == 0x80000000u ? 0u : u0;        // -0.0 and +0.0 are one value (a tie), not two
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 

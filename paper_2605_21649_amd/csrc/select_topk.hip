@@ -53,6 +53,65 @@ __global__ __launch_bounds__(kSelThreads) __attribute__((amdgpu_waves_per_eu(4, 
 }
 
 // ------------------------------------------------------------------------------------------
+// short rows: one wavefront per (b,h)
+// ------------------------------------------------------------------------------------------
+// Rows of at most 64*KPL pages: the keys of a row sit in the registers of ONE wavefront (lane l holds pages
+// i*64 + l), the k-th largest key is found bit by bit from the top (the largest v with #{key >= v} >= k; a
+// ballot and a population count per register and bit), and ballots give the ordered output.  No LDS, no
+// barrier, four rows per 256-thread workgroup: with hundreds or thousands of short rows (many sequences of a
+// few thousand tokens) the 1024-thread workgroup per row of the kernel above fills the GPU several times over.
+template <int KPL>
+__global__ __launch_bounds__(256) void select_topk_wave_kernel(const float* __restrict__ box,
+                                                               const int32_t* __restrict__ seq_lens, int k_pages,
+                                                               int32_t* __restrict__ page_idx,
+                                                               int32_t* __restrict__ n_sel, int Hq, int P, int Mmax,
+                                                               int cap, int BH) {
+  const int lane = threadIdx.x & 63;
+  const int bh = blockIdx.x * 4 + (int)(threadIdx.x >> 6);
+  if (bh >= BH) return;                                   // wave-uniform
+  const int n = seq_lens[bh / Hq];
+  const int M = min((n + P - 1) / P, Mmax);
+  const int k = min(min(k_pages, M), cap);
+  if (k <= 0) { if (lane == 0) n_sel[bh] = 0; return; }
+  const float* s = box + (size_t)bh * Mmax;
+  const uint64_t lt = (1ull << lane) - 1ull;
+  float raw[KPL];
+#pragma unroll
+  for (int i = 0; i < KPL; ++i) raw[i] = s[min(i * 64 + lane, M - 1)];
+  uint32_t key[KPL];                                      // slots past M: 0, below every real key
+#pragma unroll
+  for (int i = 0; i < KPL; ++i) key[i] = i * 64 + lane < M ? float_to_key(raw[i]) : 0u;
+  uint32_t kth = 0u;
+  bool exact = false;                                     // exactly k keys are >= kth: the set is decided
+  for (int bit = 31; bit >= 0 && !exact; --bit) {
+    const uint32_t cand = kth | (1u << bit);
+    int cnt = 0;
+#pragma unroll
+    for (int i = 0; i < KPL; ++i) cnt += __popcll(__ballot(key[i] >= cand));
+    if (cnt >= k) { kth = cand; exact = cnt == k; }       // wave-uniform
+  }
+  if (exact) kth -= 1u;                                   // the k keys above kth - 1 (kth >= 1 here)
+  int n_gt = 0;
+#pragma unroll
+  for (int i = 0; i < KPL; ++i) n_gt += __popcll(__ballot(key[i] > kth));
+  const int k_eq = k - n_gt;                              // pages equal to the k-th key that are taken: lowest indices
+  int32_t* out = page_idx + (size_t)bh * cap;
+  int o_run = 0, eq_run = 0;
+#pragma unroll
+  for (int i = 0; i < KPL; ++i) {
+    const bool valid = i * 64 + lane < M;
+    const bool eq = valid && key[i] == kth;
+    const uint64_t m_eq = __ballot(eq);
+    const bool take = (valid && key[i] > kth) || (eq && eq_run + __popcll(m_eq & lt) < k_eq);
+    const uint64_t m_take = __ballot(take);
+    if (take) out[o_run + __popcll(m_take & lt)] = i * 64 + lane;
+    eq_run += __popcll(m_eq);
+    o_run += __popcll(m_take);
+  }
+  if (lane == 0) n_sel[bh] = k;
+}
+
+// ------------------------------------------------------------------------------------------
 // sliced kernels
 // ------------------------------------------------------------------------------------------
 constexpr int kTkThreads = 256;
@@ -418,6 +477,17 @@ void launch_select_topk(const Dims& dm, const float* box, const int32_t* seq_len
 #define EKV_TOPK(ITEMS)                                                                                        \
   hipLaunchKernelGGL(select_topk_kernel<ITEMS>, grid, block, 0, st, box, seq_lens, k_pages, page_idx, n_sel, dm.Hq, \
                      dm.P, dm.Mmax, dm.cap)
+  const int n_rows = dm.B * dm.Hq;
+#define EKV_TOPK_WAVE(KPL)                                                                                          \
+  hipLaunchKernelGGL(select_topk_wave_kernel<KPL>, dim3((n_rows + 3) / 4), dim3(256), 0, st, box, seq_lens, k_pages, \
+                     page_idx, n_sel, dm.Hq, dm.P, dm.Mmax, dm.cap, n_rows)
+  if (n_rows > 512) {              // up to 512 rows the workgroup kernel below takes one round and is as fast
+    if (dm.Mmax <= 256) { EKV_TOPK_WAVE(4); return; }
+    if (dm.Mmax <= 512) { EKV_TOPK_WAVE(8); return; }
+    if (dm.Mmax <= 1024) { EKV_TOPK_WAVE(16); return; }
+    if (dm.Mmax <= 2048) { EKV_TOPK_WAVE(32); return; }
+  }
+#undef EKV_TOPK_WAVE
   if (!topk_sliced(dm)) {
     if (dm.Mmax <= 2 * kSelThreads) EKV_TOPK(2);
     else if (dm.Mmax <= 4 * kSelThreads) EKV_TOPK(4);

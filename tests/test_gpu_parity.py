@@ -1217,3 +1217,36 @@ def test_batch_slot_with_zero_tokens(kv_dtype, context, lens):
     for hq in range(w.n_q_heads):
         np.testing.assert_allclose(st.out[1, hq].cpu().numpy(), v_new[1, hq // w.group].float().cpu().numpy(),
                                    rtol=1e-6, atol=0)
+
+
+@pytest.mark.parametrize("Mmax,k", [(100, 7), (700, 14), (1024, 1024), (2048, 41)])
+def test_select_topk_many_short_rows(Mmax, k):
+    """More than 512 short rows take the one-wavefront-per-row kernel: ragged lengths (0 and 1 token
+    included), ties, constant rows, both signs, k larger than a row."""
+    P, B, Hq = 16, 20, 32
+    cfg = ekv.make_config(B, Hq, Hq, 128, P, "bf16", 1.5, 0.1, Mmax, k)
+    dev = torch.device("cuda")
+    rng = np.random.default_rng(Mmax + k)
+    scores = (rng.normal(size=(B, Hq, Mmax)) * 3.0 + 1.0).astype(np.float32)
+    scores[:, 1] = 2.5                                             # all equal: the lowest indices win
+    scores[:, 2] = np.round(scores[:, 2])                          # heavy ties
+    scores[:, 3, ::2] = scores[:, 3, 1::2]                         # every value twice
+    lens = rng.integers(1, Mmax * P + 1, size=B).astype(np.int32)
+    lens[0], lens[1], lens[2], lens[3] = Mmax * P, 0, 1, Mmax * P - 5
+    box = torch.from_numpy(scores).to(dev)
+    seq_lens = torch.from_numpy(lens).to(dev)
+    page_idx = torch.full((B, Hq, k), -1, dtype=torch.int32, device=dev)
+    n_sel = torch.full((B, Hq), -1, dtype=torch.int32, device=dev)
+    ws = torch.empty(max(256, ekv.ekv_workspace_bytes(cfg, ekv.EKV_OP_SELECT_TOPK)), dtype=torch.uint8, device=dev)
+    ekv.ekv_select_topk(cfg, box, seq_lens, k, page_idx, n_sel, ws)
+    torch.cuda.synchronize()
+    idx, ns = page_idx.cpu().numpy(), n_sel.cpu().numpy()
+    for b in range(B):
+        M = -(-int(lens[b]) // P)
+        for hq in (0, 1, 2, 3, 17, 31):
+            if M == 0:
+                assert ns[b, hq] == 0
+                continue
+            ref, _, _ = orc.topk_pages(scores[b, hq, :M].astype(np.float64), k)
+            assert ns[b, hq] == len(ref)
+            np.testing.assert_array_equal(idx[b, hq, : ns[b, hq]], ref)
