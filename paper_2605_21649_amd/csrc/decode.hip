@@ -1055,6 +1055,194 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
 }
 
 // ------------------------------------------------------------------------------------------
+// pass 2 for short candidate rows: one wavefront per (b, h)
+// ------------------------------------------------------------------------------------------
+// Rows of at most 64*KZ candidate tokens (page lists of a few dozen pages): all scores of a row sit in the
+// registers of ONE wavefront (lane l holds candidates i*64 + l), the threshold is solved there, and the support
+// is gathered through a small LDS list in candidate order, flushed whenever it could overflow -- any support
+// size, no barrier.  Four rows per 256-thread workgroup: with hundreds or thousands of rows (many sequences
+// of a few thousand tokens) the 1024-thread workgroup per row of the kernel above fills the GPU several times
+// over.  Sparse and group-shared lists only.
+constexpr int kWaveRowList = 256;        // LDS list entries per wavefront
+constexpr int kWaveRowsMin = 512;        // up to 512 rows the workgroup kernel takes one round and is as fast
+
+template <typename T, int KZ>
+__global__ __launch_bounds__(256) void decode_solve_wave_kernel(const SolveArgs A, int BH) {
+  __shared__ float l_p[4][kWaveRowList];
+  __shared__ uint32_t l_row[4][kWaveRowList];
+  __shared__ int32_t l_pos[4][kWaveRowList];
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int bh = blockIdx.x * 4 + wv;
+  if (bh >= BH) return;                                      // wave-uniform
+  const uint64_t lt = (1ull << lane) - 1ull;
+  const int Hq = A.Hq, Hkv = A.Hkv, P = A.P;
+  const int b = bh / Hq, hq = bh % Hq, hkv = hq / (Hq / Hkv);
+  const int lrow = A.grouped ? b * Hkv + hkv : bh;
+  const T* v_pool = (const T*)A.v_pool;
+  const float beta = A.beta; const int ibeta = A.ibeta;
+  float* out = A.out + (size_t)bh * kD;
+  const float* zr = A.zbuf + (size_t)bh * A.zstride;
+  const int n_cand = min(clampi(A.n_sel[lrow], 0, A.cap) * P, 64 * KZ);
+  const float seed_z = A.ex.tau_seed != nullptr ? A.ex.tau_seed[bh] : NAN;
+  float u[KZ];
+#pragma unroll
+  for (int i = 0; i < KZ; ++i) u[i] = zr[min(i * 64 + lane, max(n_cand - 1, 0))];
+  float zmax = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < KZ; ++i) { u[i] = i * 64 + lane < n_cand ? u[i] : -INFINITY; zmax = fmaxf(zmax, u[i]); }
+  zmax = wave_max(zmax);
+  const bool want_kept = A.ex.tau_ref != nullptr && (A.ex.kept_mass_ref != nullptr || A.ex.kept_supp_ref != nullptr);
+  if (!(zmax > -INFINITY)) {                                 // no valid candidate at all
+    if (lane < 16) {
+      *reinterpret_cast<float4*>(out + 8 * lane) = make_float4(0.f, 0.f, 0.f, 0.f);
+      *reinterpret_cast<float4*>(out + 8 * lane + 4) = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    if (lane == 0) {
+      A.tau_out[bh] = INFINITY; A.supp_out[bh] = 0;
+      if (A.ex.solve_evals != nullptr) A.ex.solve_evals[bh] = 0;
+      if (want_kept && A.ex.kept_mass_ref != nullptr) A.ex.kept_mass_ref[bh] = 0.f;
+      if (want_kept && A.ex.kept_supp_ref != nullptr) A.ex.kept_supp_ref[bh] = 0;
+    }
+    return;
+  }
+  if (want_kept) {                                           // mass and count above a given threshold, all candidates
+    const float tr = A.ex.tau_ref[bh];
+    float f = 0.f; int c = 0;
+#pragma unroll
+    for (int i = 0; i < KZ; ++i) {
+      const float x = u[i] - tr;
+      if (x > 0.f) { f += pow_beta(x, beta, ibeta); ++c; }
+    }
+    f = wave_sum(f); c = wave_sum_i(c);
+    if (lane == 0) {
+      if (A.ex.kept_mass_ref != nullptr) A.ex.kept_mass_ref[bh] = f;
+      if (A.ex.kept_supp_ref != nullptr) A.ex.kept_supp_ref[bh] = c;
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < KZ; ++i) u[i] -= zmax;
+  const float lo_u = -1.0f - 4e-6f * fmaxf(1.f, fabsf(zmax));
+  int supp = 0, evals = 0;
+  float tau_u;
+  // Only candidates above zmax - 1 can be in the support: usually a few dozen.  They are compacted (in order)
+  // into the LDS list and the threshold is solved over four registers per lane; if there are more than the list
+  // holds, it is solved over all KZ registers.
+  int n_c = 0;
+#pragma unroll
+  for (int i = 0; i < KZ; ++i) {
+    const bool in = u[i] > lo_u;
+    const uint64_t mk = __ballot(in);
+    const int r = n_c + __popcll(mk & lt);
+    if (in && r < kWaveRowList) { l_p[wv][r] = u[i]; l_pos[wv][r] = i * 64 + lane; }
+    n_c += __popcll(mk);
+  }
+  const bool short_list = n_c <= kWaveRowList;               // wave-uniform
+  float uu[kWaveRowList / 64]; int pp[kWaveRowList / 64];
+  if (short_list) {
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int k = 0; k < kWaveRowList / 64; ++k) {
+      const int e = lane + 64 * k;
+      uu[k] = e < n_c ? l_p[wv][e] : -INFINITY;
+      pp[k] = e < n_c ? l_pos[wv][e] : 0;
+    }
+    __builtin_amdgcn_wave_barrier();
+    tau_u = solve_tau_regs(uu, lo_u, seed_z - zmax, beta, ibeta, supp, evals);
+  } else {
+    tau_u = solve_tau_core([&](float t, float& F, float& D, int& cnt) {
+      float f = 0.f, d = 0.f; int c = 0;
+#pragma unroll
+      for (int i = 0; i < KZ; ++i) {
+        const float x = u[i] - t;
+        if (x > 0.f) { f += pow_beta(x, beta, ibeta); d += pow_beta_m1(x, beta, ibeta); ++c; }
+      }
+      F = wave_sum(f); D = beta * wave_sum(d); cnt = wave_sum_i(c);
+    }, lo_u, seed_z - zmax, ibeta, supp, evals);
+  }
+
+  // weighted value sum: the support in candidate order through the LDS list; 4 row slots x 16 lanes gather it
+  const int rs = lane >> 4, c = lane & 15;
+  float acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+  int32_t* tok_dst = A.ex.support_tokens != nullptr ? A.ex.support_tokens + (size_t)bh * A.ex.support_cap : nullptr;
+  // the support in candidate order, kWaveRowList tokens per pass (normally one pass): entry of rank r goes to
+  // slot r - w0 of the list (the unrolled loop over the registers has no gather inside, so the code stays small)
+  for (int w0 = 0; w0 < supp; w0 += kWaveRowList) {
+    int run = 0;
+    if (short_list) {                                        // one pass: the support is a subset of the list
+#pragma unroll
+      for (int k = 0; k < kWaveRowList / 64; ++k) {
+        const float x = uu[k] - tau_u;
+        const bool in = x > 0.f;
+        const uint64_t mk = __ballot(in);
+        const int r = run + __popcll(mk & lt);
+        if (in) { l_p[wv][r] = pow_beta(x, beta, ibeta); l_pos[wv][r] = pp[k]; }
+        run += __popcll(mk);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < KZ; ++i) {
+        const float x = u[i] - tau_u;
+        const bool in = x > 0.f;
+        const uint64_t mk = __ballot(in);
+        const int r = run + __popcll(mk & lt) - w0;
+        if (in && r >= 0 && r < kWaveRowList) { l_p[wv][r] = pow_beta(x, beta, ibeta); l_pos[wv][r] = i * 64 + lane; }
+        run += __popcll(mk);
+      }
+    }
+    const int n_list = min(supp - w0, kWaveRowList);
+    __builtin_amdgcn_wave_barrier();
+    {
+      // V rows of the listed tokens: page list -> block table, all lookups of the pass in flight together
+      uint32_t rw[kWaveRowList / 64];
+#pragma unroll
+      for (int j = 0; j < kWaveRowList / 64; ++j)
+        rw[j] = v_row_of<false>(A, b, lrow, hkv, l_pos[wv][min(lane + 64 * j, n_list - 1)]);
+#pragma unroll
+      for (int j = 0; j < kWaveRowList / 64; ++j)
+        if (lane + 64 * j < n_list) l_row[wv][lane + 64 * j] = rw[j];
+    }
+    __builtin_amdgcn_wave_barrier();
+    for (int e0 = 0; e0 < n_list; e0 += 32) {
+      Raw8<T> vr[8]; float pw[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int e = e0 + 4 * j + rs;
+        const int ec = min(e, n_list - 1);                   // clamped: loads stay unconditional
+        pw[j] = e < n_list ? l_p[wv][ec] : 0.f;
+        load_raw8(v_pool + (size_t)l_row[wv][ec] * kD + 8 * c, vr[j]);
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        float vv[8];
+        widen8(vr[j], vv);
+#pragma unroll
+        for (int q = 0; q < 8; ++q) acc[q] = fmaf(pw[j], vv[q], acc[q]);
+      }
+    }
+    if (tok_dst != nullptr) {
+      for (int e = lane; e < n_list && w0 + e < A.ex.support_cap; e += 64)
+        tok_dst[w0 + e] = token_of<false>(A, lrow, l_pos[wv][e]);
+    }
+    __builtin_amdgcn_wave_barrier();
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    acc[i] += __shfl_xor(acc[i], 16);
+    acc[i] += __shfl_xor(acc[i], 32);
+  }
+  if (lane < 16) {
+    *reinterpret_cast<float4*>(out + 8 * c) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+    *reinterpret_cast<float4*>(out + 8 * c + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
+  }
+  if (lane == 0) {
+    A.tau_out[bh] = tau_u + zmax; A.supp_out[bh] = supp;
+    if (A.ex.solve_evals != nullptr) A.ex.solve_evals[bh] = evals;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
 // launchers
 // ------------------------------------------------------------------------------------------
 template <int G, int MODE>
@@ -1150,6 +1338,20 @@ void launch_decode(const Dims& dm, bool dense, bool grouped, const void* q, cons
     if (ws.fcount != nullptr) {
       hipLaunchKernelGGL((filter_level_kernel<false>), dim3(dm.B * dm.Hq), fblock, 0, st, fa);
       hipLaunchKernelGGL((filter_compact_kernel<false>), fgrid, fblock, 0, st, fa);
+    }
+    const int rows = dm.B * dm.Hq;
+    const long long max_cand = (long long)dm.cap * dm.P;
+    if (ws.fcount == nullptr && max_cand <= 2048 && rows > kWaveRowsMin) {
+      // many short rows: one wavefront per row
+      dim3 wgrid((rows + 3) / 4), wblock(256);
+      if (dm.dtype == EKV_F32) {
+        if (max_cand <= 1024) hipLaunchKernelGGL((decode_solve_wave_kernel<float, 16>), wgrid, wblock, 0, st, so, rows);
+        else hipLaunchKernelGGL((decode_solve_wave_kernel<float, 32>), wgrid, wblock, 0, st, so, rows);
+      } else {
+        if (max_cand <= 1024) hipLaunchKernelGGL((decode_solve_wave_kernel<bf16_t, 16>), wgrid, wblock, 0, st, so, rows);
+        else hipLaunchKernelGGL((decode_solve_wave_kernel<bf16_t, 32>), wgrid, wblock, 0, st, so, rows);
+      }
+      return;
     }
     if (dm.dtype == EKV_F32) hipLaunchKernelGGL((decode_solve_kernel<float, false>), sgrid, sblock, 0, st, so);
     else hipLaunchKernelGGL((decode_solve_kernel<bf16_t, false>), sgrid, sblock, 0, st, so);

@@ -1250,3 +1250,65 @@ def test_select_topk_many_short_rows(Mmax, k):
             ref, _, _ = orc.topk_pages(scores[b, hq, :M].astype(np.float64), k)
             assert ns[b, hq] == len(ref)
             np.testing.assert_array_equal(idx[b, hq, : ns[b, hq]], ref)
+
+
+@pytest.mark.parametrize("kv_dtype,ctx,k,scale", [("bf16", 2048, 8, 1.0), ("bf16", 4096, 100, 1.0), ("f32", 1024, 20, 1.0),
+                                                  ("bf16", 2048, 40, 0.02)],
+                         ids=["bf16-8-pages", "bf16-100-pages", "f32-20-pages", "bf16-flat-scores"])
+def test_many_short_rows_step(kv_dtype, ctx, k, scale):
+    """More than 512 (sequence, head) rows with short page lists take the one-wavefront-per-row selection and
+    solve kernels: whole top-k step and the group-shared decode against the oracle on sampled rows, ragged
+    lengths; the flat-score case has more candidates near the maximum than the kernel's list holds."""
+    w = synth.C2.scaled(name="C2-many-rows", batch=24, context=ctx, n_q_heads=32, n_kv_heads=8, kv_dtype=kv_dtype,
+                        n_planted=8, scale=scale / math.sqrt(128.0))
+    inp = {key: v.clone() for key, v in synth.make_inputs(w, 2000 + 77, device="cpu").items()}
+    rng = np.random.default_rng(3)
+    lens = rng.integers(1, ctx + 1, size=w.batch).astype(np.int32)
+    lens[0], lens[1] = ctx, 5
+    inp["seq_lens"] = torch.from_numpy(lens)
+    st = DeviceState(w, inp, cap=k)
+    dev = st.box.device
+    toks = torch.full((w.batch, w.n_q_heads, 2048), -1, dtype=torch.int32, device=dev)
+    ekv.ekv_stats_build(st.cfg, st.cache(), st.stats())
+    ekv.ekv_score_pages(st.cfg, st.inp["q"], st.stats(), st.inp["seq_lens"], ekv.EKV_SCORE_BOX, st.box)
+    ekv.ekv_select_topk(st.cfg, st.box, st.inp["seq_lens"], k, st.page_idx, st.n_sel, st.workspace(ekv.EKV_OP_SELECT_TOPK))
+    full = dict(out=torch.zeros_like(st.out), tau=torch.zeros_like(st.tau), supp=torch.zeros_like(st.supp))
+    ekv.ekv_decode_full(st.cfg, st.inp["q"], st.cache(), full["out"], full["tau"], full["supp"],
+                        st.workspace(ekv.EKV_OP_DECODE_FULL))
+    km, kn = torch.zeros_like(st.tau), torch.zeros_like(st.supp)
+    ekv.ekv_decode_sparse(st.cfg, st.inp["q"], st.cache(), st.page_idx, st.n_sel, st.out, st.tau, st.supp,
+                          st.workspace(ekv.EKV_OP_DECODE_SPARSE),
+                          extras=ekv.decode_extras(support_tokens=toks, tau_ref=full["tau"], kept_mass_ref=km,
+                                                   kept_supp_ref=kn))
+    torch.cuda.synchronize()
+    P = w.page_size
+    for (b, hq) in [(0, 0), (0, 31), (1, 5), (7, 12), (13, 20), (23, 9)]:
+        q, K, V = unit_kv(inp, w, b, hq)
+        ref = orc.decode_step_unit(q, K, V, P, w.alpha, w.score_scale, "topk", w.kv_dtype, k_pages=k)
+        got = st.page_idx[b, hq, : int(st.n_sel[b, hq])].cpu().numpy()
+        band = 1e-5 * max(1.0, abs(ref["cut_in"]))
+        ok, bad = sets_equal_up_to_cut(got, ref["pages"], ref["box"], [ref["cut_in"], ref["cut_out"]], band)
+        assert ok, (b, hq, bad)
+        if set(got.tolist()) == set(ref["pages"].tolist()):
+            ref["s"] = orc.token_scores(q, K[ref["tokens"]], w.score_scale)
+            check_decode_unit(w, st.out[b, hq].cpu().numpy(), float(st.tau[b, hq]), int(st.supp[b, hq]),
+                              toks[b, hq].cpu().numpy(), ref)
+            dense = orc.entmax_attention(q, K, V, w.alpha, w.score_scale)
+            assert abs((1.0 - float(km[b, hq])) - orc.dropped_mass(dense["p"], ref["tokens"])) <= 1e-4
+    # one list per KV head through the same kernel
+    gcfg = group_cfg(st, w, k)
+    gbox = torch.zeros(w.batch, w.n_kv_heads, st.Mmax, device=dev)
+    g_idx = torch.zeros(w.batch, w.n_kv_heads, k, dtype=torch.int32, device=dev)
+    g_n = torch.zeros(w.batch, w.n_kv_heads, dtype=torch.int32, device=dev)
+    ekv.ekv_score_pages(st.cfg, st.inp["q"], st.stats(), st.inp["seq_lens"], ekv.EKV_SCORE_BOX | ekv.EKV_SCORE_GROUP_MAX, gbox)
+    ekv.ekv_select_topk(gcfg, gbox, st.inp["seq_lens"], k, g_idx, g_n,
+                        torch.empty(max(256, ekv.ekv_workspace_bytes(gcfg, ekv.EKV_OP_SELECT_TOPK)), device=dev, dtype=torch.uint8))
+    ekv.ekv_decode_sparse_group(st.cfg, st.inp["q"], st.cache(), g_idx, g_n, st.out, st.tau, st.supp,
+                                st.workspace(ekv.EKV_OP_DECODE_SPARSE))
+    torch.cuda.synchronize()
+    for (b, hq) in [(0, 3), (7, 12), (23, 30)]:
+        q, K, V = unit_kv(inp, w, b, hq)
+        pages = g_idx[b, hq // w.group, : int(g_n[b, hq // w.group])].cpu().numpy()
+        tok = orc.pages_to_tokens(pages, P, K.shape[0])
+        ref = orc.entmax_attention(q, K, V, w.alpha, w.score_scale, tok)
+        check_decode_unit(w, st.out[b, hq].cpu().numpy(), float(st.tau[b, hq]), int(st.supp[b, hq]), None, ref)
