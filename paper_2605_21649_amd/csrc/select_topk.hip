@@ -316,14 +316,21 @@ __global__ __launch_bounds__(kSelThreads) void topk_find_kernel(const float* __r
   // (above_s[-1] := pages of the slice): copied from there when the range ends inside the list.  A slice
   // whose range does not (more than kTkPrefix of its pages at or above the bin: the top pages crowd into a
   // few slices, or the budget is very large) has its 4096 scores scanned instead.
-  __shared__ int s_lo[kTkMaxSlices], s_cnt_s[kTkMaxSlices], s_start[kTkMaxSlices + 1], s_scan[kTkMaxSlices];
-  if (tid < S) {
-    const uint16_t* ab = ws.above + ((size_t)bh * S + tid) * kBins;
-    const int lo_s = (int)ab[b1];
-    const int valid_s = max(0, min(kTkSlice, M - tid * kTkSlice));
-    const int hi_s = b1 == 0 ? valid_s : (int)ab[b1 - 1];
-    const bool scan = hi_s > kTkPrefix && hi_s > lo_s;
-    s_lo[tid] = lo_s; s_cnt_s[tid] = scan ? 0 : hi_s - lo_s; s_scan[tid] = scan ? 1 : 0;
+  __shared__ int s_lo[kTkMaxSlices], s_cnt_s[kTkMaxSlices], s_start[kTkMaxSlices + 1];
+  __shared__ unsigned long long s_scan_mask;             // slices to scan (kTkMaxSlices <= 64: the first wavefront's ballot)
+  static_assert(kTkMaxSlices <= 64, "one ballot covers the slices");
+  if (tid < 64) {
+    bool scan = false;
+    if (tid < S) {
+      const uint16_t* ab = ws.above + ((size_t)bh * S + tid) * kBins;
+      const int lo_s = (int)ab[b1];
+      const int valid_s = max(0, min(kTkSlice, M - tid * kTkSlice));
+      const int hi_s = b1 == 0 ? valid_s : (int)ab[b1 - 1];
+      scan = hi_s > kTkPrefix && hi_s > lo_s;
+      s_lo[tid] = lo_s; s_cnt_s[tid] = scan ? 0 : hi_s - lo_s;
+    }
+    const unsigned long long mask = __ballot(scan);
+    if (tid == 0) s_scan_mask = mask;
   }
   __syncthreads();
   if (tid == 0) {
@@ -341,8 +348,8 @@ __global__ __launch_bounds__(kSelThreads) void topk_find_kernel(const float* __r
       if (slot < kTkMembers) { mem_key[slot] = pk[e]; mem_page[slot] = pp[e]; }
     }
   }
-  for (int sl = 0; sl < S; ++sl) {
-    if (!s_scan[sl]) continue;                         // workgroup-uniform
+  for (unsigned long long todo = s_scan_mask; todo != 0; todo &= todo - 1) {     // workgroup-uniform, usually empty
+    const int sl = __builtin_ctzll(todo);
     constexpr int PER = kTkSlice / kSelThreads;        // 4 scores per thread
     float raw[PER];
 #pragma unroll
