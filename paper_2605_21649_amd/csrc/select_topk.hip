@@ -331,13 +331,14 @@ __global__ __launch_bounds__(kSelThreads) void topk_find_kernel(const float* __r
     }
     const unsigned long long mask = __ballot(scan);
     if (tid == 0) s_scan_mask = mask;
-  }
-  __syncthreads();
-  if (tid == 0) {
-    int run = 0;
-    for (int i = 0; i < S; ++i) { s_start[i] = run; run += s_cnt_s[i]; }
-    s_start[S] = run;
-    s_m = run;                                         // the scanned slices append behind the copied ones
+    // exclusive prefix of the copied counts (one lane per slice: a serial loop over LDS costs a latency per slice)
+    const int cs = tid < S ? s_cnt_s[tid] : 0;
+    int inc = cs;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) { const int t = __shfl_up(inc, d); if (tid >= d) inc += t; }
+    if (tid < S) s_start[tid] = inc - cs;
+    const int run = __shfl(inc, 63);
+    if (tid == 0) { s_start[S] = run; s_m = run; }       // the scanned slices append behind the copied ones
   }
   __syncthreads();
   for (int sl = tid >> 6; sl < S; sl += kSelWaves) {
@@ -395,27 +396,27 @@ __global__ __launch_bounds__(kSelThreads) void topk_find_kernel(const float* __r
   }
   __syncthreads();
   // per-slice output offsets: the global loads are done in parallel, the short serial prefix runs on LDS
-  __shared__ int s_above[kTkMaxSlices], s_off[kTkMaxSlices], s_eqb[kTkMaxSlices];
-  if (tid < S) s_above[tid] = (int)ws.above[((size_t)bh * S + tid) * kBins + b1];
-  __syncthreads();
-  if (tid == 0) {
-    int gt_members = 0;
-    for (int i = 0; i < S; ++i) gt_members += s_gt[i];
-    const int k_eq = k_rem - gt_members;               // pages equal to key_t that are taken
-    int off = 0, eq_before = 0;
-    for (int i = 0; i < S; ++i) {
-      s_off[i] = off; s_eqb[i] = eq_before;
-      const int take_eq = max(0, min(s_eq[i], k_eq - eq_before));
-      off += s_above[i] + s_gt[i] + take_eq;
-      eq_before += s_eq[i];
+  if (tid < 64) {                                      // one lane per slice, wave scans instead of serial loops
+    const int ab_s = tid < S ? (int)ws.above[((size_t)bh * S + tid) * kBins + b1] : 0;
+    const int gt_s = tid < S ? s_gt[tid] : 0, eq_s = tid < S ? s_eq[tid] : 0;
+    int gt_inc = gt_s, eq_inc = eq_s;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const int tg = __shfl_up(gt_inc, d), te = __shfl_up(eq_inc, d);
+      if (tid >= d) { gt_inc += tg; eq_inc += te; }
     }
-    ws.head[bh].key_t = key_t; ws.head[bh].k_eq = k_eq;
-    n_sel[bh] = k;
-  }
-  __syncthreads();
-  if (tid < S) {
-    ws.slice_off[(size_t)bh * S + tid] = s_off[tid];
-    ws.slice_eq[(size_t)bh * S + tid] = s_eqb[tid];
+    const int k_eq = k_rem - __shfl(gt_inc, 63);       // pages equal to key_t that are taken
+    const int eq_before = eq_inc - eq_s;
+    const int take_eq = max(0, min(eq_s, k_eq - eq_before));
+    int off_inc = ab_s + gt_s + take_eq;
+    const int mine = off_inc;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) { const int t = __shfl_up(off_inc, d); if (tid >= d) off_inc += t; }
+    if (tid < S) {
+      ws.slice_off[(size_t)bh * S + tid] = off_inc - mine;
+      ws.slice_eq[(size_t)bh * S + tid] = eq_before;
+    }
+    if (tid == 0) { ws.head[bh].key_t = key_t; ws.head[bh].k_eq = k_eq; n_sel[bh] = k; }
   }
 }
 
