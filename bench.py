@@ -626,6 +626,21 @@ def main():
                                                                            0.0, st0.tau_hat, st0.page_idx, st0.n_sel,
                                                                            st0.overflow, st0.ws_gauss), reps=10), 2)
         extras["select_gauss_us_by_page_moment_shape"] = gsel
+        # the top-k selector alone on score rows that are not stationary along the sequence (synthetic rows at the
+        # headline's shape): the key range of the slice histograms is sampled from runs spread over the sequence, and
+        # a slice crowded with top pages is scanned alone
+        tsel = {}
+        ramp = torch.linspace(0, 1, M, device=dev)
+        base_s = torch.randn(B, Hq, M, generator=gm).to(dev) * 3 + 17
+        shapes_t = {"stationary": base_s, "trend_plus_6_sigma_along_the_sequence": base_s + 18 * ramp,
+                    "last_5_percent_plus_10_sigma": base_s + 30 * (ramp > 0.95),
+                    "first_1024_pages_plus_10_sigma": base_s + 30 * (ramp < 1024 / M),
+                    "16_distinct_values": torch.round(base_s).clamp(10, 25)}
+        for name, box_t in shapes_t.items():
+            box_t = box_t.contiguous()
+            tsel[name] = round(R.back_to_back(lambda st: ekv.ekv_select_topk(st0.cfg, box_t, st0.inp["seq_lens"], k_pages,
+                                                                             st0.page_idx, st0.n_sel, st0.ws_topk), reps=20), 2)
+        extras["select_topk_us_by_score_shape"] = tsel
         # 8-bit page bounds (an extension; the rows above keep the paper's cache-dtype metadata): allocated and
         # built only now, so that nothing above pays for them
         for st in copies:
@@ -792,6 +807,19 @@ def main():
             R5.release()
             del R5, s5
         result["other_rows"]["C5-256k"] = row5
+        # many short sequences (64 x 8K tokens: 2048 (sequence, head) rows of 11 selected pages): the rows take the
+        # one-wavefront-per-row selection and solve kernels
+        wm = synth.Workload("B64-8k", 64, 32, 8, 128, 8192, 16, "bf16", n_planted=16, n_outlier_channels=4)
+        Rm = Runner(wm, args.budget, 2, args.q_page, dev, args.cap_frac, fused_append=not args.two_launch_append)
+        um, stage_m, _ = Rm.run_timed(Rm.step_topk, side, 5)
+        umd, _, _ = Rm.run_timed(Rm.step_dense, max(5, side // 2), 3, stages=False)
+        result["other_rows"]["B64-8k"] = {
+            "workload": f"{wm.batch} sequences x {wm.context} tokens, 32q/8kv, top-k {Rm.k_pages} pages",
+            "topk_step_us": round(um, 2),
+            "topk_stage_us": {nm: round(float(v), 2) for nm, v in zip(STAGE_NAMES["topk"], stage_m.mean(axis=0))},
+            "dense_full_us": round(umd, 2), "speedup_topk_vs_dense": round(umd / um, 2)}
+        Rm.release()
+        del Rm
 
     print(json.dumps(result))
 
