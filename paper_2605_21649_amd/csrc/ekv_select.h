@@ -80,7 +80,8 @@ struct KeySet {
     return max(k, base) - base;
   }
   // ITEMS == 0: the keys of slots i0 .. i0+7, all eight loads issued before any is used (a loop that calls
-  // key(i) once per iteration waits for memory in every iteration)
+  // key(i) once per iteration waits for memory in every iteration).  Slots i >= items belong to the NEXT
+  // wavefront's pages: the caller must skip them (i0 + j < items), not only pages >= M.
   __device__ __forceinline__ void key_batch(int i0, uint32_t (&k)[8]) const {
     uint32_t k0[8];
 #pragma unroll
@@ -113,7 +114,7 @@ __device__ __forceinline__ void radix_select_kth(KeySet<ITEMS, KeyFn>& ks, int k
       ks.key_batch(i0, kb);
 #pragma unroll
       for (int j = 0; j < 8; ++j)
-        if (ks.page(i0 + j) < ks.M) { lo = min(lo, kb[j]); hi = max(hi, kb[j]); }
+        if (i0 + j < ks.items && ks.page(i0 + j) < ks.M) { lo = min(lo, kb[j]); hi = max(hi, kb[j]); }
     }
   } else {
 #pragma unroll
@@ -155,7 +156,8 @@ __device__ __forceinline__ void radix_select_kth(KeySet<ITEMS, KeyFn>& ks, int k
         ks.key_batch(i0, kb);
 #pragma unroll
         for (int j = 0; j < 8; ++j)
-          if (ks.page(i0 + j) < ks.M && (first || (kb[j] >> up) == prefix)) atomicAdd(&sh.hist[(kb[j] >> shift) & dmask], 1u);
+          if (i0 + j < ks.items && ks.page(i0 + j) < ks.M && (first || (kb[j] >> up) == prefix))
+            atomicAdd(&sh.hist[(kb[j] >> shift) & dmask], 1u);
       }
     } else {
 #pragma unroll
@@ -192,7 +194,8 @@ __device__ __forceinline__ void radix_select_kth(KeySet<ITEMS, KeyFn>& ks, int k
           ks.key_batch(i0, kb);
 #pragma unroll
           for (int j = 0; j < 8; ++j)
-            if (ks.page(i0 + j) < ks.M && (kb[j] >> shift) == prefix) sh.hist[atomicAdd(&sh.scan_buf[kSelWaves], 1)] = kb[j];
+            if (i0 + j < ks.items && ks.page(i0 + j) < ks.M && (kb[j] >> shift) == prefix)
+              sh.hist[atomicAdd(&sh.scan_buf[kSelWaves], 1)] = kb[j];
         }
       } else {
 #pragma unroll

@@ -515,6 +515,26 @@ __global__ __launch_bounds__(kSelThreads) __attribute__((amdgpu_waves_per_eu(4, 
       if (tid == 0) { tau_hat[bh] = st.tau; n_sel[bh] = count; overflow[bh] = 0; }
       return;
     }
+    if (count > cap) {
+      // More pages pass than the list holds: the cap best estimates are among the candidates (every passing page
+      // is one), so they are selected there -- candidate j of the concatenated lists plays the page -- instead of
+      // over all pages of the head; the selected candidate numbers are then replaced by their pages.
+      auto cand_at = [&](int j) {
+        int lo = 0, hi = NSS;                                // invariant: s_off[lo] <= j < s_off[hi]
+        while (hi - lo > 1) { const int mid = (lo + hi) >> 1; if (s_off[mid] <= j) lo = mid; else hi = mid; }
+        return ((size_t)bh * NSS + lo) * ws.pw + (j - s_off[lo]);
+      };
+      auto ckey = [&](int j) { return float_to_key(ws.sel_key[cand_at(j)]); };
+      KeySet<0, decltype(ckey)> cs(ckey, n_c);
+      uint32_t vT; int k_eq;
+      __syncthreads();
+      radix_select_kth(cs, cap, sh, vT, k_eq);
+      compact_ordered(cs, vT, k_eq, sh, out);
+      __syncthreads();
+      for (int e = tid; e < cap; e += kSelThreads) out[e] = ws.sel_page[cand_at(out[e])];
+      if (tid == 0) { tau_hat[bh] = st.tau; n_sel[bh] = cap; overflow[bh] = 1; }
+      return;
+    }
   }
   if (tid == 0) tau_hat[bh] = st.tau;
   const float z_full = zq.z[P], z_last = zq.z[n - (M - 1) * P];

@@ -253,8 +253,11 @@ def test_select_gauss_long_context():
                 cut = th - margin
                 ok, bad = sets_equal_up_to_cut(got, pages, g, cut, 1e-5 * max(1.0, abs(cut)))
                 assert ok, (hq, bad[:5], len(pages), len(got))
-            else:
+            else:                                              # the cap best estimates, up to ties at the cut
                 assert len(got) == cap
+                cut = float(np.min(g[pages]))
+                ok, bad = sets_equal_up_to_cut(got, pages, g, cut, 1e-5 * max(1.0, abs(cut)))
+                assert ok, (hq, bad[:5])
             assert np.all(np.diff(got) > 0)
 
 
@@ -1312,3 +1315,31 @@ def test_many_short_rows_step(kv_dtype, ctx, k, scale):
         tok = orc.pages_to_tokens(pages, P, K.shape[0])
         ref = orc.entmax_attention(q, K, V, w.alpha, w.score_scale, tok)
         check_decode_unit(w, st.out[b, hq].cpu().numpy(), float(st.tau[b, hq]), int(st.supp[b, hq]), None, ref)
+
+
+@pytest.mark.parametrize("M,k,levels", [(21003, 400, 16), (299999, 777, 0), (299999, 5000, 64)])
+def test_select_topk_memory_backed_rows_of_odd_length(M, k, levels):
+    """The one-workgroup selection that reads its keys from memory (rows beyond the sliced kernels' range,
+    and rows whose k-th key has thousands of exact ties) with a page count that leaves the last batch of
+    key slots of a lane partly in the next wavefront's range."""
+    P, B, Hq = 16, 1, 3
+    Mmax = -(-M // 64) * 64
+    cfg = ekv.make_config(B, Hq, Hq, 128, P, "bf16", 1.5, 0.1, Mmax, k)
+    dev = torch.device("cuda")
+    rng = np.random.default_rng(M + k)
+    scores = (rng.normal(size=(B, Hq, Mmax)) * 3.0 + 17.0).astype(np.float32)
+    if levels:
+        scores[0, 1] = np.round(np.clip(scores[0, 1], 10, 10 + levels - 1))      # `levels` distinct values
+        scores[0, 2] = 3.25                                                       # one value
+    box = torch.from_numpy(scores).to(dev)
+    seq_lens = torch.full((B,), M * P - 2, dtype=torch.int32, device=dev)
+    page_idx = torch.full((B, Hq, k), -1, dtype=torch.int32, device=dev)
+    n_sel = torch.zeros(B, Hq, dtype=torch.int32, device=dev)
+    ws = torch.empty(max(256, ekv.ekv_workspace_bytes(cfg, ekv.EKV_OP_SELECT_TOPK)), dtype=torch.uint8, device=dev)
+    ekv.ekv_select_topk(cfg, box, seq_lens, k, page_idx, n_sel, ws)
+    torch.cuda.synchronize()
+    idx, ns = page_idx.cpu().numpy(), n_sel.cpu().numpy()
+    for hq in range(Hq):
+        ref, _, _ = orc.topk_pages(scores[0, hq, :M].astype(np.float64), k)
+        assert ns[0, hq] == len(ref)
+        np.testing.assert_array_equal(idx[0, hq, : ns[0, hq]], ref)
