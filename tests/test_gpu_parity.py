@@ -1298,6 +1298,18 @@ def test_many_short_rows_step(kv_dtype, ctx, k, scale):
                               toks[b, hq].cpu().numpy(), ref)
             dense = orc.entmax_attention(q, K, V, w.alpha, w.score_scale)
             assert abs((1.0 - float(km[b, hq])) - orc.dropped_mass(dense["p"], ref["tokens"])) <= 1e-4
+    # a warm start (the exact thresholds as seeds) changes nothing but the number of evaluations
+    out2, tau2, supp2 = torch.zeros_like(st.out), torch.zeros_like(st.tau), torch.zeros_like(st.supp)
+    evals = torch.full_like(st.supp, -1)
+    ekv.ekv_decode_sparse(st.cfg, st.inp["q"], st.cache(), st.page_idx, st.n_sel, out2, tau2, supp2,
+                          st.workspace(ekv.EKV_OP_DECODE_SPARSE),
+                          extras=ekv.decode_extras(tau_seed=st.tau, solve_evals=evals))
+    torch.cuda.synchronize()
+    assert torch.equal(supp2, st.supp)
+    assert torch.allclose(tau2, st.tau, rtol=0, atol=4e-6)
+    # (a threshold that moves within its tolerance moves the weights of a flat row by far more, relatively)
+    assert float(((out2 - st.out).norm(dim=-1) / st.out.norm(dim=-1).clamp_min(1e-30)).max()) <= 2e-3
+    assert int(evals.min()) >= 0 and int(evals.max()) <= 8
     # one list per KV head through the same kernel
     gcfg = group_cfg(st, w, k)
     gbox = torch.zeros(w.batch, w.n_kv_heads, st.Mmax, device=dev)
