@@ -171,7 +171,7 @@ ekv_status ekv_append_score_pages(const ekv_config* cfg, const ekv_cache_view* c
                                   void* stream);
 
 /* a5 -- fixed-budget top-k page selection (Sec. 4.3).  For each (b,h): the min(k_pages, M_b) pages
- * of largest box score among p < M_b; equal scores are resolved towards the lower page index.
+ * of largest box score among p < M_b; equal scores (-0 and +0 are equal) are resolved towards the lower page index.
  * page_idx int32 [B][Hq][cap] receives the logical page indices in ASCENDING order, n_sel int32
  * [B][Hq] their number.  Requires 1 <= k_pages <= cap and a workspace of
  * ekv_workspace_bytes(EKV_OP_SELECT_TOPK) bytes (long contexts are split over several workgroups per
