@@ -1255,15 +1255,17 @@ def test_select_topk_many_short_rows(Mmax, k):
             np.testing.assert_array_equal(idx[b, hq, : ns[b, hq]], ref)
 
 
-@pytest.mark.parametrize("kv_dtype,ctx,k,scale", [("bf16", 2048, 8, 1.0), ("bf16", 4096, 100, 1.0), ("f32", 1024, 20, 1.0),
-                                                  ("bf16", 2048, 40, 0.02)],
-                         ids=["bf16-8-pages", "bf16-100-pages", "f32-20-pages", "bf16-flat-scores"])
-def test_many_short_rows_step(kv_dtype, ctx, k, scale):
+@pytest.mark.parametrize("kv_dtype,ctx,k,scale,alpha", [("bf16", 2048, 8, 1.0, 1.5), ("bf16", 4096, 100, 1.0, 1.5),
+                                                        ("f32", 1024, 20, 1.0, 1.5), ("bf16", 2048, 40, 0.02, 1.5),
+                                                        ("bf16", 2048, 16, 1.0, 1.25), ("bf16", 2048, 16, 1.0, 2.0)],
+                         ids=["bf16-8-pages", "bf16-100-pages", "f32-20-pages", "bf16-flat-scores", "alpha-1.25",
+                              "alpha-2"])
+def test_many_short_rows_step(kv_dtype, ctx, k, scale, alpha):
     """More than 512 (sequence, head) rows with short page lists take the one-wavefront-per-row selection and
     solve kernels: whole top-k step and the group-shared decode against the oracle on sampled rows, ragged
     lengths; the flat-score case has more candidates near the maximum than the kernel's list holds."""
     w = synth.C2.scaled(name="C2-many-rows", batch=24, context=ctx, n_q_heads=32, n_kv_heads=8, kv_dtype=kv_dtype,
-                        n_planted=8, scale=scale / math.sqrt(128.0))
+                        n_planted=8, scale=scale / math.sqrt(128.0), alpha=alpha)
     inp = {key: v.clone() for key, v in synth.make_inputs(w, 2000 + 77, device="cpu").items()}
     rng = np.random.default_rng(3)
     lens = rng.integers(1, ctx + 1, size=w.batch).astype(np.int32)
