@@ -1357,3 +1357,40 @@ def test_select_topk_memory_backed_rows_of_odd_length(M, k, levels):
         ref, _, _ = orc.topk_pages(scores[0, hq, :M].astype(np.float64), k)
         assert ns[0, hq] == len(ref)
         np.testing.assert_array_equal(idx[0, hq, : ns[0, hq]], ref)
+
+
+def test_select_gauss_many_short_rows():
+    """768 (sequence, head) rows of at most 200 pages, ragged lengths (0 and 1 token included): one slice per row,
+    one page per wavefront lane at most; tau-hat and the page sets against the oracle on sampled rows."""
+    P, B, Hq, Mmax = 16, 24, 32, 200
+    cfg = ekv.make_config(B, Hq, Hq, 128, P, "bf16", 1.5, 0.1, Mmax, Mmax)
+    dev = torch.device("cuda")
+    rng = np.random.default_rng(5)
+    mu = (rng.normal(size=(B, Hq, Mmax)) * 0.6 + 1.0).astype(np.float32)
+    sg = (np.abs(rng.normal(size=(B, Hq, Mmax))) * 0.3 + 0.2).astype(np.float32)
+    mu[:, 3, 7] += 6.0                                             # one hot page per row of head 3
+    lens = rng.integers(1, Mmax * P + 1, size=B).astype(np.int32)
+    lens[0], lens[1], lens[2] = Mmax * P, 0, 1
+    seq_lens = torch.from_numpy(lens).to(dev)
+    t = lambda a: torch.from_numpy(a).to(dev)
+    tau_hat = torch.zeros(B, Hq, device=dev); page_idx = torch.zeros(B, Hq, Mmax, dtype=torch.int32, device=dev)
+    n_sel = torch.full((B, Hq), -1, dtype=torch.int32, device=dev); ovf = torch.zeros_like(n_sel)
+    ws = torch.empty(ekv.ekv_workspace_bytes(cfg, ekv.EKV_OP_SELECT_GAUSS), dtype=torch.uint8, device=dev)
+    ekv.ekv_select_gauss(cfg, t(mu), t(sg), seq_lens, 0.9, 0.02, tau_hat, page_idx, n_sel, ovf, ws)
+    torch.cuda.synchronize()
+    assert int(ovf.sum()) == 0
+    for b in range(B):
+        n = int(lens[b]); M = -(-n // P)
+        for hq in (0, 3, 17, 31):
+            if M == 0:
+                assert int(n_sel[b, hq]) == 0
+                continue
+            cnt = np.full(M, P); cnt[-1] = n - (M - 1) * P
+            pages, th, o, g = orc.gauss_select(mu[b, hq, :M].astype(np.float64), sg[b, hq, :M].astype(np.float64), cnt, 1.5,
+                                               0.9, 0.02, cap=Mmax)
+            assert abs(float(tau_hat[b, hq]) - th) <= 4e-6 * max(1.0, abs(th)), (b, hq, float(tau_hat[b, hq]), th)
+            got = page_idx[b, hq, : int(n_sel[b, hq])].cpu().numpy()
+            cut = th - 0.02
+            ok, bad = sets_equal_up_to_cut(got, pages, g, cut, 1e-5 * max(1.0, abs(cut)))
+            assert ok, (b, hq, bad[:5], len(pages), len(got))
+            assert np.all(np.diff(got) > 0)
