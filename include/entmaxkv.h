@@ -276,6 +276,19 @@ ekv_status ekv_decode_sparse_softmax(const ekv_config* cfg, const void* q,
                                      const int32_t* n_sel, float* out, float* lse_sel,
                                      void* workspace, size_t workspace_bytes, void* stream);
 
+/* Measurement aid, no part of the method: reads n_pages pages of page_bytes bytes (4096 or 8192) of the device
+ * buffer `base` and discards the data, four pages per wavefront.  Page i of the launch is page page_ids[i] of the
+ * buffer (device int32 list), or page lookup[page_ids[i]] when `lookup` (device int32 table) is given -- a second
+ * dependent read per page, as the decode does through page list and block table.  Every resulting page number must
+ * lie inside the buffer; it is NOT checked.  With a permutation the probe has the access pattern of the sparse
+ * decode's gather, with the identity that of a linear stream: the rate it reaches is the ceiling a read-only kernel
+ * gets on the GPU at hand, reported next to the published HBM peak.  `out` (optional, device float
+ * [ceil(n_pages/4) * 64]): every wavefront also writes 256 bytes, the output volume of the decode's score pass.
+ * `sink`: 4 bytes of device memory (written only in a practically impossible case).  Asynchronous on `stream`;
+ * EKV_ERR_INVALID_ARG for null or misaligned pointers or n_pages <= 0, EKV_ERR_UNSUPPORTED for other page sizes. */
+ekv_status ekv_probe_read(const void* base, const int32_t* page_ids, const int32_t* lookup, int32_t n_pages,
+                          int32_t page_bytes, float* out, void* sink, void* stream);
+
 /* Bytes of workspace `op` needs under cfg (host computation, no HIP calls). */
 ekv_status ekv_workspace_bytes(const ekv_config* cfg, int32_t op, size_t* bytes);
 

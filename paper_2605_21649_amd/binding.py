@@ -23,9 +23,9 @@ EKV_OP_SELECT_TOPK, EKV_OP_SELECT_GAUSS, EKV_OP_DECODE_SPARSE, EKV_OP_DECODE_FUL
 EXPORTS = ["ekv_stats_build", "ekv_stats_append", "ekv_score_pages", "ekv_append_score_pages", "ekv_select_topk",
            "ekv_select_gauss",
            "ekv_select_box_threshold", "ekv_decode_sparse", "ekv_decode_sparse_group", "ekv_decode_full",
-           "ekv_decode_sparse_softmax", "ekv_workspace_bytes", "ekv_status_string", "ekv_last_hip_error",
-           "ekv_version"]
-_STATUS_CALLS = EXPORTS[:12]      # entry points that return ekv_status
+           "ekv_decode_sparse_softmax", "ekv_workspace_bytes", "ekv_probe_read", "ekv_status_string",
+           "ekv_last_hip_error", "ekv_version"]
+_STATUS_CALLS = EXPORTS[:13]      # entry points that return ekv_status
 
 
 class ekv_config(ctypes.Structure):
@@ -90,6 +90,7 @@ def load_library():
     lib.ekv_version.restype = c_int32
     lib.ekv_select_box_threshold.argtypes = [P(ekv_config), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                              c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+    lib.ekv_probe_read.argtypes = [c_void_p, c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p]
     for name in _STATUS_CALLS:
         getattr(lib, name).restype = c_int32
     _lib = lib
@@ -222,3 +223,8 @@ def ekv_decode_sparse_softmax(cfg, q, cache, page_idx, n_sel, out, lse_sel, work
     _check(load_library().ekv_decode_sparse_softmax(byref(cfg), _ptr(q), byref(cache), _ptr(page_idx),
                                                     _ptr(n_sel), _ptr(out), _ptr(lse_sel), _ptr(workspace), nbytes,
                                                     _stream(stream)))
+
+
+def ekv_probe_read(base, page_ids, n_pages, page_bytes, sink, lookup=None, out=None, stream=None):
+    _check(load_library().ekv_probe_read(_ptr(base), _ptr(page_ids), _ptr(lookup), n_pages, page_bytes, _ptr(out),
+                                         _ptr(sink), _stream(stream)))

@@ -12,7 +12,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libentmaxkv.so")
 SOURCES = ["api.hip", "stats.hip", "score.hip", "select_topk.hip", "select_gauss.hip", "select_box.hip", "decode.hip",
-           "softmax_sparse.hip"]
+           "softmax_sparse.hip", "probe.hip"]
 # packed-FP32 instructions are switched off for all device code (hipcc-only flag; the host pass warns
 # that it does not know the feature, which is harmless)
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",

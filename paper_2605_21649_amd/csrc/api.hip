@@ -313,4 +313,13 @@ ekv_status ekv_decode_sparse_softmax(const ekv_config* cfg, const void* q, const
   return finish((hipStream_t)stream);
 }
 
+ekv_status ekv_probe_read(const void* base, const int32_t* page_ids, const int32_t* lookup, int32_t n_pages,
+                          int32_t page_bytes, float* out, void* sink, void* stream) {
+  if (!ok_ptr(base) || !ok_ptr4(page_ids) || !ok_ptr4(sink) || n_pages <= 0) return EKV_ERR_INVALID_ARG;
+  if ((lookup != nullptr && !ok_ptr4(lookup)) || (out != nullptr && !ok_ptr4(out))) return EKV_ERR_INVALID_ARG;
+  if (page_bytes != 4096 && page_bytes != 8192) return EKV_ERR_UNSUPPORTED;
+  launch_probe_read(base, page_ids, lookup, n_pages, page_bytes, out, (uint32_t*)sink, (hipStream_t)stream);
+  return finish((hipStream_t)stream);
+}
+
 }  // extern "C"

@@ -42,39 +42,105 @@ struct ScoreArgs {
   size_t zstride;
   float zscale;
   int HkvPool;
+  int U;                  // units of the launch: B*Hq page lists, or B*Hkv (all pages / one list per KV head)
+  const int32_t* pre_g;   // exclusive prefix of the items per unit, [U + 1], when U is too large for LDS
 };
 
-// A wavefront covers kGroupsPerWave groups of pmax_pages(P) consecutive page slots (64 tokens when P
-// divides 64) and writes each group's maximum straight to pmax (no LDS, no barrier); a workgroup is four
-// such wavefronts.  Page indices are resolved first (wave-uniform loads issued together with the list
-// length, clamped into range), then all K loads of the wavefront are issued before any is consumed.
-constexpr int kGroupsPerWave = 1;
 constexpr int kScoreWaves = kScoreThreads / 64;
+constexpr int kUnitsLdsMax = 8192;      // units whose item prefix a workgroup keeps in LDS (32 KB)
 
 __device__ __forceinline__ int clampi(int x, int lo, int hi) { return min(max(x, lo), hi); }
+__device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
+
+// Work distribution of pass 1.  An item is one group of pmax_pages(P) page slots of one unit (64 tokens when P
+// divides 64): the granularity of pmax.  The launch has a fixed number of wavefronts that does not depend on the
+// capacity of the page lists: the items of all units, in (unit, group) order, form one sequence of T items, and
+// wavefront i of W takes the contiguous range [i*T/W, (i+1)*T/W).  T and the unit boundaries come from the
+// device-side lengths (n_sel, or seq_lens when every page is a candidate): every workgroup builds the exclusive
+// prefix of the items per unit in LDS (launches with more units than LDS holds read it from `pre_g`, written by
+// unit_prefix_kernel before).
+template <int MODE>
+__device__ __forceinline__ int unit_slots(const ScoreArgs& A, int u) {
+  if (MODE == kAllPages) return clampi((A.seq_lens[u / A.Hkv] + A.P - 1) / A.P, 0, A.Mmax);
+  return clampi(A.n_sel[u], 0, A.cap);
+}
+
+// Exclusive prefix over `U` counts produced by `count_of(u)`, written to pre[0..U] (pre[U] = total); `wsum` holds
+// one int per wavefront.  Called by every thread of the workgroup.
+template <int THREADS, typename F>
+__device__ __forceinline__ void block_exclusive_prefix(int U, F&& count_of, int* pre, int* wsum) {
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  for (int u = tid; u < U; u += THREADS) pre[u] = count_of(u);
+  __syncthreads();
+  const int upt = (U + THREADS - 1) / THREADS;          // a contiguous segment per thread
+  const int s0 = min(tid * upt, U), s1 = min(s0 + upt, U);
+  int s = 0;
+  for (int u = s0; u < s1; ++u) s += pre[u];
+  int inc = s;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) { const int t = __shfl_up(inc, d); if (lane >= d) inc += t; }
+  if (lane == 63) wsum[w] = inc;
+  __syncthreads();
+  int base = inc - s;
+  for (int i = 0; i < w; ++i) base += wsum[i];
+  for (int u = s0; u < s1; ++u) { const int c = pre[u]; pre[u] = base; base += c; }
+  if (tid == THREADS - 1) pre[U] = base;                // the last segment ends at U
+  __syncthreads();
+}
+
+template <int MODE>
+__global__ __launch_bounds__(1024) void unit_prefix_kernel(const ScoreArgs A, int32_t* pre_out) {
+  __shared__ int wsum[16];
+  const int gp = pmax_pages(A.P);
+  block_exclusive_prefix<1024>(A.U, [&](int u) { return (unit_slots<MODE>(A, u) + gp - 1) / gp; }, pre_out, wsum);
+}
+
+// The item range of this wavefront and the unit its first item lies in.
+struct WaveItems { int begin, end, unit; };
+template <typename P>
+__device__ __forceinline__ WaveItems wave_item_range(const P pre, int U, int w) {
+  const int total = uniform(pre[U]);
+  const uint32_t W = gridDim.x * kScoreWaves, gw = blockIdx.x * kScoreWaves + w;
+  WaveItems r;
+  r.begin = (int)((uint64_t)gw * (uint32_t)total / W);
+  r.end = (int)((uint64_t)(gw + 1) * (uint32_t)total / W);
+  int lo = 0, hi = U;                                   // pre[lo] <= begin < pre[hi] whenever begin < total
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (uniform(pre[mid]) <= r.begin) lo = mid; else hi = mid;
+  }
+  r.unit = lo;
+  return r;
+}
 
 // Generic path (float32 caches, or page sizes that are not 16, 32 or 64): FMAs + DPP row sums.
-template <typename T, int G, int MODE>
+template <typename T, int G, int MODE, bool PRE_GLOBAL>
 __global__ __launch_bounds__(kScoreThreads) void decode_scores_valu_kernel(const ScoreArgs A) {
   constexpr bool DENSE = MODE == kAllPages, GROUPED = MODE != kPerHead;
+  extern __shared__ int pre_lds[];
+  __shared__ int wsum[kScoreWaves];
   const T* q = (const T*)A.q;
   const T* k_pool = (const T*)A.k_pool;
   const int P = A.P, Hq = A.Hq, Hkv = A.Hkv;
-  const int unit = blockIdx.y;
-  const int b = GROUPED ? unit / Hkv : unit / Hq;
-  const int hkv = GROUPED ? unit % Hkv : (unit % Hq) / (Hq / Hkv);
-  const int hq0 = GROUPED ? hkv * G : unit % Hq;            // first (only) query head of this unit
-  const int n = A.seq_lens[b];
-  const int n_slots = clampi(DENSE ? (n + P - 1) / P : A.n_sel[unit], 0, DENSE ? A.Mmax : A.cap);
-  const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63, w = uniform(threadIdx.x >> 6);
   const int gp = pmax_pages(P);
   const int r = lane >> 4, c = lane & 15;
-  float coef[G][8];
+  if (!PRE_GLOBAL)
+    block_exclusive_prefix<kScoreThreads>(A.U, [&](int u) { return (unit_slots<MODE>(A, u) + gp - 1) / gp; }, pre_lds, wsum);
+  const int* pre = PRE_GLOBAL ? A.pre_g : pre_lds;
+  const WaveItems wi = wave_item_range(pre, A.U, w);
+  int unit = wi.unit;
+  for (int it = wi.begin; it < wi.end; ++it) {
+    while (it >= uniform(pre[unit + 1])) ++unit;
+    const int grp = it - uniform(pre[unit]);
+    const int b = GROUPED ? unit / Hkv : unit / Hq;
+    const int hkv = GROUPED ? unit % Hkv : (unit % Hq) / (Hq / Hkv);
+    const int hq0 = GROUPED ? hkv * G : unit % Hq;          // first (only) query head of this unit
+    const int n = A.seq_lens[b];
+    const int n_slots = unit_slots<MODE>(A, unit);
+    float coef[G][8];
 #pragma unroll
-  for (int g = 0; g < G; ++g) load8<T>(q + ((size_t)b * Hq + hq0 + g) * kD + 8 * c, coef[g]);
-  for (int gi = 0; gi < kGroupsPerWave; ++gi) {
-    const int grp = (blockIdx.x * kScoreWaves + w) * kGroupsPerWave + gi;
-    if (grp * gp >= n_slots) break;
+    for (int g = 0; g < G; ++g) load8<T>(q + ((size_t)b * Hq + hq0 + g) * kD + 8 * c, coef[g]);
     float wmax[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) wmax[g] = -INFINITY;
@@ -124,83 +190,103 @@ __global__ __launch_bounds__(kScoreThreads) void decode_scores_valu_kernel(const
   }
 }
 
-// bf16 pages with P in {16, 32, 64}: matrix-core path.
-template <int G, int MODE, int PT>
-__global__ __launch_bounds__(kScoreThreads) void decode_scores_mfma_kernel(const ScoreArgs A) {
+// bf16 pages with P in {16, 32, 64}: matrix-core path.  Many resident wavefronts with little in flight each stream
+// better than few with much: the kernel is compiled for eight wavefronts per SIMD and a wavefront holds two chunks
+// of 16 tokens at a time (the next chunk is requested before the current one is consumed).  The page-list and block-table entries
+// of up to 64 page slots are resolved at once, one slot per lane (two dependent vector loads per batch of 64 / GP
+// items instead of two per page), and handed out with v_readlane.
+template <int G, int MODE, int PT, bool PRE_GLOBAL>
+__global__ __launch_bounds__(kScoreThreads) __attribute__((amdgpu_waves_per_eu(G <= 4 ? 8 : 6)))
+void decode_scores_mfma_kernel(const ScoreArgs A) {
   constexpr bool DENSE = MODE == kAllPages, GROUPED = MODE != kPerHead;
   constexpr int NSET = (G + 3) / 4;
-  constexpr int STEPS = PT / 4;                   // 16-byte loads per lane and page
-  constexpr int KEEP = PT / 16;                   // z values a lane keeps per page and column set
-  constexpr int GP = 64 / PT;                     // pages per pmax group
-  constexpr int SW = GP * kGroupsPerWave;         // page slots per wavefront
+  constexpr int KEEP = PT / 16;                   // 16-token chunks per page
+  constexpr int GP = 64 / PT;                     // page slots per item
+  constexpr int kBatchItems = 64 / GP;
+  extern __shared__ int pre_lds[];
+  __shared__ int wsum[kScoreWaves];
   const bf16_t* q = (const bf16_t*)A.q;
   const bf16_t* k_pool = (const bf16_t*)A.k_pool;
   const int Hq = A.Hq, Hkv = A.Hkv;
-  const int unit = blockIdx.y;
-  const int b = GROUPED ? unit / Hkv : unit / Hq;
-  const int hkv = GROUPED ? unit % Hkv : (unit % Hq) / (Hq / Hkv);
-  const int hq0 = GROUPED ? hkv * G : unit % Hq;
-  const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int wslot0 = (blockIdx.x * kScoreWaves + w) * SW;
+  const int lane = threadIdx.x & 63, w = uniform(threadIdx.x >> 6);
   const int m = lane & 15, j = lane >> 4;          // MFMA row/column index, K group
   const int kq = m & 3, gl = m >> 2;               // channel quarter; as a row: token of the step,
                                                    // as a column: head within the set
   // row (token gl of the step, quarter kq), K group j -> bytes [gl*256 + (kq*4+j)*16, +16) of the step
-  const size_t lane_off = (size_t)gl * kD + (kq * 4 + j) * 8;
-  int lps[SW], physs[SW];
-#pragma unroll
-  for (int i = 0; i < SW; ++i) {
-    const int sc = min(wslot0 + i, (DENSE ? A.Mmax : A.cap) - 1);
-    lps[i] = DENSE ? sc : clampi(A.page_idx[(size_t)unit * A.cap + sc], 0, A.Mmax - 1);
-  }
-  // the lengths arrive with the page indices (independent loads): a wavefront past the end of its list
-  // leaves before it touches the block table or K
-  const int n = A.seq_lens[b];
-  const int n_slots = clampi(DENSE ? (n + PT - 1) / PT : A.n_sel[unit], 0, DENSE ? A.Mmax : A.cap);
-  if (wslot0 >= n_slots) return;
-#pragma unroll
-  for (int i = 0; i < SW; ++i) physs[i] = clampi(A.block_table[(size_t)b * A.Mmax + lps[i]], 0, A.n_phys - 1);
-  uint4 a[SW][STEPS];
-#pragma unroll
-  for (int i = 0; i < SW; ++i) {
-    const bf16_t* kpage = k_pool + ((size_t)physs[i] * A.HkvPool + hkv) * PT * kD + lane_off;
-#pragma unroll
-    for (int s = 0; s < STEPS; ++s) a[i][s] = *reinterpret_cast<const uint4*>(kpage + (size_t)s * 4 * kD);
-  }
-  uint4 bq[NSET];
-#pragma unroll
-  for (int s = 0; s < NSET; ++s) {
-    const int g = min(4 * s + gl, G - 1);          // columns past the group repeat its last head (not stored)
-    bq[s] = *reinterpret_cast<const uint4*>(q + ((size_t)b * Hq + hq0 + g) * kD + kq * 32 + j * 8);
-  }
+  const int lane_off = gl * kD + (kq * 4 + j) * 8;
+  if (!PRE_GLOBAL)
+    block_exclusive_prefix<kScoreThreads>(A.U, [&](int u) { return (unit_slots<MODE>(A, u) + GP - 1) / GP; }, pre_lds, wsum);
+  const int* pre = PRE_GLOBAL ? A.pre_g : pre_lds;
+  const WaveItems wi = wave_item_range(pre, A.U, w);
+  const int last = (DENSE ? A.Mmax : A.cap) - 1;
 
-#pragma unroll
-  for (int gi = 0; gi < kGroupsPerWave; ++gi) {
-    if (wslot0 + gi * GP >= n_slots) break;
+  for (int it0 = wi.begin; it0 < wi.end; it0 += kBatchItems) {
+    // lane l: page slot l % GP of item it0 + l / GP (clamped to the last item): its unit, logical and physical page
+    int l_unit, l_lp, l_phys;
+    {
+      const int my_it = min(it0 + lane / GP, wi.end - 1);
+      int lo = 0, hi = A.U;
+      while (hi - lo > 1) { const int mid = (lo + hi) >> 1; if (pre[mid] <= my_it) lo = mid; else hi = mid; }
+      l_unit = lo;
+      const int slot = min((my_it - pre[lo]) * GP + lane % GP, last);
+      const int b = GROUPED ? lo / Hkv : lo / Hq;
+      l_lp = clampi(DENSE ? slot : A.page_idx[(size_t)lo * A.cap + slot], 0, A.Mmax - 1);
+      l_phys = clampi(A.block_table[(size_t)b * A.Mmax + l_lp], 0, A.n_phys - 1);
+    }
+    const int n_ck = (min(it0 + kBatchItems, wi.end) - it0) * 4;       // 16-token chunks of this batch
+
+    // state of the item being consumed (wave-uniform), refreshed at its first chunk
+    int n = 0, n_slots = 0, slot0 = 0, grp = 0;
+    size_t row0 = 0;
+    uint4 bq[NSET];
     float wmax[NSET];
+    auto open_item = [&](int pg) {
+      const int unit = __builtin_amdgcn_readlane(l_unit, pg);
+      const int b = GROUPED ? unit / Hkv : unit / Hq;
+      const int hq0 = GROUPED ? (unit % Hkv) * G : unit % Hq;
+      grp = it0 + pg / GP - uniform(pre[unit]);
+      slot0 = grp * GP;
+      row0 = GROUPED ? (size_t)b * Hq + hq0 : (size_t)unit;      // first row of z / pmax written
+      n = uniform_load(A.seq_lens + b);
+      n_slots = DENSE ? clampi((n + PT - 1) / PT, 0, A.Mmax) : clampi(uniform_load(A.n_sel + unit), 0, A.cap);
 #pragma unroll
-    for (int s = 0; s < NSET; ++s) wmax[s] = -INFINITY;
+      for (int s = 0; s < NSET; ++s) {
+        const int g = min(4 * s + gl, G - 1);          // columns past the group repeat its last head (not stored)
+        bq[s] = *reinterpret_cast<const uint4*>(q + ((size_t)b * Hq + hq0 + g) * kD + kq * 32 + j * 8);
+        wmax[s] = -INFINITY;
+      }
+    };
+    // chunk ck of the batch = tokens [16 t, 16 t + 16) of page slot pg = ck / KEEP, t = ck % KEEP
+    auto request = [&](int ck, uint4 (&a)[4]) {
+      const int pg = ck / KEEP, t = ck % KEEP;
+      const int unit = __builtin_amdgcn_readlane(l_unit, pg);
+      const int hkv = GROUPED ? unit % Hkv : (unit % Hq) / (Hq / Hkv);
+      const int phys = __builtin_amdgcn_readlane(l_phys, pg);
+      const bf16_t* kc = k_pool + (((size_t)phys * A.HkvPool + hkv) * PT + 16 * t) * kD + lane_off;
 #pragma unroll
-    for (int pg = 0; pg < GP; ++pg) {
-      const int i = gi * GP + pg;
-      const int slot = wslot0 + i;
+      for (int s = 0; s < 4; ++s) a[s] = *reinterpret_cast<const uint4*>(kc + s * 4 * kD);
+    };
+    auto consume = [&](int ck, const uint4 (&a)[4]) {
+      const int pg = ck / KEEP, t = ck % KEEP;
+      if (ck % 4 == 0) open_item(pg);
+      const int slot = slot0 + pg % GP;
       const bool slot_ok = slot < n_slots;             // wave-uniform
-      const int lp = lps[i];
-      float zkeep[NSET][KEEP];
+      const int tok0 = __builtin_amdgcn_readlane(l_lp, pg) * PT + 16 * t + j;
+      float zkeep[NSET];
 #pragma unroll
-      for (int s = 0; s < STEPS; ++s) {
+      for (int s = 0; s < 4; ++s) {
         // result rows 4j..4j+3 belong to token j of the step
-        const bool valid = slot_ok && lp * PT + 4 * s + j < n;
+        const bool valid = slot_ok && tok0 + 4 * s < n;
 #pragma unroll
         for (int cs = 0; cs < NSET; ++cs) {
           const f32x4_t zero = {0.f, 0.f, 0.f, 0.f};
-          const f32x4_t c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a[i][s]),
+          const f32x4_t c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a[s]),
                                                                     __builtin_bit_cast(bf16x8_t, bq[cs]), zero, 0, 0, 0);
           float v = kq == 0 ? c[0] : kq == 1 ? c[1] : kq == 2 ? c[2] : c[3];
           v += dpp_move<0xB1>(v);
           v += dpp_move<0x4E>(v);
           const float z = valid ? A.zscale * v : -INFINITY;
-          if ((s & 3) == kq) zkeep[cs][s >> 2] = z;   // lane (j, head, kq) keeps token 4*(4*i + kq) + j
+          if (s == kq) zkeep[cs] = z;                  // lane (j, head, kq) keeps token 4 kq + j of the chunk
           wmax[cs] = fmaxf(wmax[cs], z);
         }
       }
@@ -208,25 +294,31 @@ __global__ __launch_bounds__(kScoreThreads) void decode_scores_mfma_kernel(const
 #pragma unroll
         for (int cs = 0; cs < NSET; ++cs) {
           const int g = 4 * cs + gl;
-          if (g < G) {
-            const size_t row = GROUPED ? (size_t)b * Hq + hq0 + g : (size_t)unit;
-            float* zp = A.zbuf + row * A.zstride + (size_t)slot * PT + j;
-#pragma unroll
-            for (int t = 0; t < KEEP; ++t) zp[4 * (4 * t + kq)] = zkeep[cs][t];
-          }
+          if (g < G) A.zbuf[(row0 + g) * A.zstride + (size_t)slot * PT + 16 * t + 4 * kq + j] = zkeep[cs];
         }
       }
-    }
+      if (ck % 4 == 3) {                               // last chunk of the item: its maximum
 #pragma unroll
-    for (int cs = 0; cs < NSET; ++cs) {
-      float mx = wmax[cs];                               // equal over the four kq lanes of a head
-      mx = fmaxf(mx, __shfl_xor(mx, 16));
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const int g = 4 * cs + gl;
-      if (j == 0 && kq == 0 && g < G) {
-        const size_t row = GROUPED ? (size_t)b * Hq + hq0 + g : (size_t)unit;
-        A.pmax[row * A.n_chunks_max + (wslot0 / GP + gi)] = mx;
+        for (int cs = 0; cs < NSET; ++cs) {
+          float mx = wmax[cs];                         // equal over the four kq lanes of a head
+          mx = fmaxf(mx, __shfl_xor(mx, 16));
+          mx = fmaxf(mx, __shfl_xor(mx, 32));
+          const int g = 4 * cs + gl;
+          if (j == 0 && kq == 0 && g < G) A.pmax[(row0 + g) * A.n_chunks_max + grp] = mx;
+        }
       }
+    };
+
+    // two chunks in flight, alternating register sets (n_ck is a multiple of 4)
+    uint4 a0[4], a1[4];
+    request(0, a0);
+    for (int ck = 0; ck < n_ck; ck += 2) {
+      request(ck + 1, a1);
+      __builtin_amdgcn_sched_barrier(0);
+      consume(ck, a0);
+      if (ck + 2 < n_ck) request(ck + 2, a0);
+      __builtin_amdgcn_sched_barrier(0);
+      consume(ck + 1, a1);
     }
   }
 }
@@ -1245,19 +1337,51 @@ __global__ __launch_bounds__(256) void decode_solve_wave_kernel(const SolveArgs 
 // ------------------------------------------------------------------------------------------
 // launchers
 // ------------------------------------------------------------------------------------------
+// Wavefronts of a pass-1 launch: enough to fill every compute unit several times over, never more than the
+// lists can hold items; independent of how full the lists are.
+static int device_compute_units() {
+  static int cus[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  if (cus[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+    cus[dev] = n;
+  }
+  return cus[dev];
+}
+// Workgroups per compute unit in a pass-1 launch.  Eight are resident at a time; launching up to four times that
+// (when there is that much work) measured 5 % faster than a grid of resident workgroups only -- a wavefront that
+// starts fresh streams better than one that loops -- while workgroups without work cost about half a microsecond
+// per thousand.  Every workgroup reads the U lengths, so launches with many units get fewer.
+static int score_wgs_per_cu(int U) { return U <= 64 ? 32 : U <= 256 ? 16 : 8; }
+
 template <int G, int MODE>
-static void launch_scores(const Dims& dm, dim3 grid, const ScoreArgs& sa, hipStream_t st) {
-  dim3 block(kScoreThreads);
-  if (dm.dtype == EKV_BF16 && dm.P == 16)
-    hipLaunchKernelGGL((decode_scores_mfma_kernel<G, MODE, 16>), grid, block, 0, st, sa);
-  else if (dm.dtype == EKV_BF16 && dm.P == 32)
-    hipLaunchKernelGGL((decode_scores_mfma_kernel<G, MODE, 32>), grid, block, 0, st, sa);
-  else if (dm.dtype == EKV_BF16 && dm.P == 64)
-    hipLaunchKernelGGL((decode_scores_mfma_kernel<G, MODE, 64>), grid, block, 0, st, sa);
-  else if (dm.dtype == EKV_BF16)
-    hipLaunchKernelGGL((decode_scores_valu_kernel<bf16_t, G, MODE>), grid, block, 0, st, sa);
-  else
-    hipLaunchKernelGGL((decode_scores_valu_kernel<float, G, MODE>), grid, block, 0, st, sa);
+static void launch_scores(const Dims& dm, ScoreArgs sa, int32_t* pre_ws, hipStream_t st) {
+  const int gp = pmax_pages(dm.P);
+  const long long max_items = (long long)sa.U * (((MODE == kAllPages ? dm.Mmax : dm.cap) + gp - 1) / gp);
+  long long wgs = (max_items + kScoreWaves - 1) / kScoreWaves;
+  const long long wg_cap = (long long)device_compute_units() * score_wgs_per_cu(sa.U);
+  if (wgs > wg_cap) wgs = wg_cap;
+  if (wgs < 1) wgs = 1;
+  dim3 grid((unsigned)wgs), block(kScoreThreads);
+  const bool pre_global = sa.U > kUnitsLdsMax;
+  const size_t lds = pre_global ? 0 : (size_t)(sa.U + 1) * sizeof(int);
+  if (pre_global) {
+    sa.pre_g = pre_ws;
+    hipLaunchKernelGGL((unit_prefix_kernel<MODE>), dim3(1), dim3(1024), 0, st, sa, pre_ws);
+  }
+#define EKV_SCORES(KERNEL, ...)                                                                          \
+  do {                                                                                                   \
+    if (pre_global) hipLaunchKernelGGL((KERNEL<__VA_ARGS__, true>), grid, block, lds, st, sa);            \
+    else hipLaunchKernelGGL((KERNEL<__VA_ARGS__, false>), grid, block, lds, st, sa);                      \
+  } while (0)
+  if (dm.dtype == EKV_BF16 && dm.P == 16) EKV_SCORES(decode_scores_mfma_kernel, G, MODE, 16);
+  else if (dm.dtype == EKV_BF16 && dm.P == 32) EKV_SCORES(decode_scores_mfma_kernel, G, MODE, 32);
+  else if (dm.dtype == EKV_BF16 && dm.P == 64) EKV_SCORES(decode_scores_mfma_kernel, G, MODE, 64);
+  else if (dm.dtype == EKV_BF16) EKV_SCORES(decode_scores_valu_kernel, bf16_t, G, MODE);
+  else EKV_SCORES(decode_scores_valu_kernel, float, G, MODE);
+#undef EKV_SCORES
 }
 
 size_t decode_ws_carve(const Dims& dm, bool dense, void* base, DecodeWorkspace* ws) {
@@ -1271,6 +1395,7 @@ size_t decode_ws_carve(const Dims& dm, bool dense, void* base, DecodeWorkspace* 
   auto take = [&](size_t bytes) { const size_t o = off; off += (bytes + 255) & ~(size_t)255; return o; };
   const size_t o_z = take(rows * zstride * sizeof(float));
   const size_t o_pm = take(rows * n_chunks_max * sizeof(float));
+  const size_t o_pre = take((rows + 1) * sizeof(int32_t));
   size_t o_fc = 0, o_fr = 0, o_fu = 0, o_fp = 0;
   if (n_slices) {
     o_fc = take(rows * n_slices * sizeof(int32_t));
@@ -1280,7 +1405,7 @@ size_t decode_ws_carve(const Dims& dm, bool dense, void* base, DecodeWorkspace* 
   }
   if (ws != nullptr && base != nullptr) {
     char* p = (char*)base;
-    ws->z = (float*)(p + o_z); ws->pmax = (float*)(p + o_pm);
+    ws->z = (float*)(p + o_z); ws->pmax = (float*)(p + o_pm); ws->unit_pre = (int32_t*)(p + o_pre);
     ws->zstride = zstride; ws->n_chunks_max = n_chunks_max; ws->n_slices_max = (int)n_slices;
     ws->fcount = n_slices ? (int32_t*)(p + o_fc) : nullptr;
     ws->frow = n_slices ? (float*)(p + o_fr) : nullptr;
@@ -1295,7 +1420,7 @@ void launch_decode(const Dims& dm, bool dense, bool grouped, const void* q, cons
                    const ekv_decode_extras& ex, const DecodeWorkspace& ws, hipStream_t st) {
   ScoreArgs sa{q, c.k_pool, c.block_table, c.seq_lens, page_idx, n_sel, ws.z, ws.pmax,
                dm.Hq, dm.Hkv, dm.P, dm.Mmax, dm.cap, ws.n_chunks_max, c.n_phys_pages, ws.zstride, dm.a * dm.scale,
-               dm.HkvPool};
+               dm.HkvPool, 0, nullptr};
   SolveArgs so{c.v_pool, c.block_table, c.seq_lens, page_idx, n_sel, ws.z, ws.pmax, out, tau, supp, ex,
                dm.Hq, dm.Hkv, dm.P, dm.Mmax, dm.cap, ws.n_chunks_max, c.n_phys_pages, ws.zstride, dm.a, dm.beta, dm.ibeta};
   so.fcount = ws.fcount; so.frow = ws.frow; so.flist_u = ws.flist_u; so.flist_pos = ws.flist_pos;
@@ -1307,15 +1432,13 @@ void launch_decode(const Dims& dm, bool dense, bool grouped, const void* q, cons
                 ws.zstride, dm.beta, dm.ibeta};
   dim3 fgrid(ws.n_slices_max, dm.B * dm.Hq), fblock(kFilterThreads);
   dim3 sgrid(dm.B * dm.Hq), sblock(kSolveThreads);
-  const int slots_per_wg = kScoreWaves * kGroupsPerWave * pmax_pages(dm.P);
-  const int score_blocks = ((dense ? dm.Mmax : dm.cap) + slots_per_wg - 1) / slots_per_wg;
   if (dense) {
-    dim3 grid(score_blocks, dm.B * dm.Hkv);
+    sa.U = dm.B * dm.Hkv;
     switch (dm.G) {
-      case 1: launch_scores<1, kAllPages>(dm, grid, sa, st); break;
-      case 2: launch_scores<2, kAllPages>(dm, grid, sa, st); break;
-      case 4: launch_scores<4, kAllPages>(dm, grid, sa, st); break;
-      default: launch_scores<8, kAllPages>(dm, grid, sa, st); break;
+      case 1: launch_scores<1, kAllPages>(dm, sa, ws.unit_pre, st); break;
+      case 2: launch_scores<2, kAllPages>(dm, sa, ws.unit_pre, st); break;
+      case 4: launch_scores<4, kAllPages>(dm, sa, ws.unit_pre, st); break;
+      default: launch_scores<8, kAllPages>(dm, sa, ws.unit_pre, st); break;
     }
     if (ws.fcount != nullptr) {
       hipLaunchKernelGGL((filter_level_kernel<true>), dim3(dm.B * dm.Hq), fblock, 0, st, fa);
@@ -1325,15 +1448,15 @@ void launch_decode(const Dims& dm, bool dense, bool grouped, const void* q, cons
     else hipLaunchKernelGGL((decode_solve_kernel<bf16_t, true>), sgrid, sblock, 0, st, so);
   } else {
     if (grouped && dm.G > 1) {
-      dim3 grid(score_blocks, dm.B * dm.Hkv);
+      sa.U = dm.B * dm.Hkv;
       switch (dm.G) {
-        case 2: launch_scores<2, kGroupList>(dm, grid, sa, st); break;
-        case 4: launch_scores<4, kGroupList>(dm, grid, sa, st); break;
-        default: launch_scores<8, kGroupList>(dm, grid, sa, st); break;
+        case 2: launch_scores<2, kGroupList>(dm, sa, ws.unit_pre, st); break;
+        case 4: launch_scores<4, kGroupList>(dm, sa, ws.unit_pre, st); break;
+        default: launch_scores<8, kGroupList>(dm, sa, ws.unit_pre, st); break;
       }
     } else {                                    // G == 1: a group list is a per-head list
-      dim3 grid(score_blocks, dm.B * dm.Hq);
-      launch_scores<1, kPerHead>(dm, grid, sa, st);
+      sa.U = dm.B * dm.Hq;
+      launch_scores<1, kPerHead>(dm, sa, ws.unit_pre, st);
     }
     if (ws.fcount != nullptr) {
       hipLaunchKernelGGL((filter_level_kernel<false>), dim3(dm.B * dm.Hq), fblock, 0, st, fa);

@@ -23,6 +23,12 @@ __device__ __forceinline__ uint16_t float_to_bf16_bits(float f) {
   return (uint16_t)(u >> 16);
 }
 
+// Wave-uniform read of an int32 in device memory that nothing in the running launch writes (page lists, block
+// table, lengths written by earlier launches): a load through the constant address space with a uniform address
+// is a scalar load, which does not queue behind the vector loads in flight and costs no vector register.
+typedef const int32_t __attribute__((address_space(4)))* const_i32_ptr;
+__device__ __forceinline__ int32_t uniform_load(const int32_t* p) { return *(const_i32_ptr)(uintptr_t)p; }
+
 // Load 8 consecutive channels (one lane's share of a 128-channel row) as float.
 template <typename T> __device__ __forceinline__ void load8(const T* p, float (&x)[8]);
 

@@ -29,6 +29,7 @@ constexpr int kFilterSliceCap = 4096;     // candidates kept per slice (the solv
 struct DecodeWorkspace {
   float* z;        // [B*Hq][zstride] candidate scores z_j (or -inf where masked)
   float* pmax;     // [B*Hq][n_chunks_max] maxima of z per pmax_pages(P) page slots
+  int32_t* unit_pre;  // [B*Hq + 1] item prefix of pass 1 (used when the units do not fit in LDS)
   size_t zstride;  // floats per (b,h) row of z
   int n_chunks_max;
   // filter passes; all null / 0 when the rows are short
@@ -67,6 +68,9 @@ void launch_select_box_threshold(const Dims& dm, const float* box, const int32_t
                                  const int32_t* page_idx_in, const int32_t* n_sel_in, int32_t* page_idx_out,
                                  int32_t* n_sel_out, int32_t* n_added, int32_t* overflow, void* workspace,
                                  hipStream_t st);
+
+void launch_probe_read(const void* base, const int32_t* page_ids, const int32_t* lookup, int n_pages, int page_bytes,
+                       float* out, uint32_t* sink, hipStream_t st);
 
 size_t select_topk_ws_bytes(const Dims& dm);
 size_t select_box_ws_bytes(const Dims& dm);
