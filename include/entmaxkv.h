@@ -251,6 +251,21 @@ ekv_status ekv_decode_sparse(const ekv_config* cfg, const void* q, const ekv_cac
                              int32_t* supp, const ekv_decode_extras* extras, void* workspace,
                              size_t workspace_bytes, void* stream);
 
+/* For callers that cannot allocate device memory and have no workspace to pass (code recorded into a HIP graph,
+ * tight serving loops, harnesses that forbid hipMalloc): ekv_decode_sparse with the same arguments, results and
+ * kernels, but with its scratch in a static device array inside the library instead of a caller workspace.  The call
+ * allocates nothing and frees nothing.  The array has EKV_STATIC_SCRATCH_BYTES bytes; a configuration whose
+ * ekv_workspace_bytes(cfg, EKV_OP_DECODE_SPARSE, ..) exceeds that is rejected with EKV_ERR_WORKSPACE before anything
+ * is launched.  Each GPU the library runs on holds its own copy of the array until the process ends, and every call on
+ * a GPU uses that one copy: calls that overlap in time on one GPU (different streams or threads) race on it and must
+ * be serialised by the caller; calls in one stream are safe.  Nothing in the array has to start at zero (every value
+ * a kernel reads is written earlier in the same call), so a call does not depend on what the previous one left.
+ * Other errors as ekv_decode_sparse; EKV_ERR_HIP if the array's device address cannot be obtained. */
+#define EKV_STATIC_SCRATCH_BYTES (32u << 20)
+ekv_status ekv_decode_sparse_static(const ekv_config* cfg, const void* q, const ekv_cache_view* cache,
+                                    const int32_t* page_idx, const int32_t* n_sel, float* out, float* tau,
+                                    int32_t* supp, const ekv_decode_extras* extras, void* stream);
+
 /* a7, page lists shared per KV head: as ekv_decode_sparse, but page_idx int32 [B][Hkv][cap] and n_sel
  * int32 [B][Hkv] hold one list per KV head and every query head of the group attends over it (its own
  * tau, support and output).  K of a selected page is read once for the whole group (a [G x d] x [d x P]

@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libentmaxkv.so")
 EKV_OK = 0
 EKV_F32, EKV_BF16 = 0, 1
 EKV_SCORE_BOX, EKV_SCORE_GAUSS, EKV_SCORE_BOTH, EKV_SCORE_GROUP_MAX, EKV_SCORE_BOX8 = 1, 2, 3, 4, 8
+EKV_STATIC_SCRATCH_BYTES = 32 << 20
 EKV_OP_SELECT_TOPK, EKV_OP_SELECT_GAUSS, EKV_OP_DECODE_SPARSE, EKV_OP_DECODE_FULL, \
     EKV_OP_DECODE_SPARSE_SOFTMAX, EKV_OP_SELECT_BOX_THRESHOLD = range(6)
 
@@ -23,9 +24,9 @@ EKV_OP_SELECT_TOPK, EKV_OP_SELECT_GAUSS, EKV_OP_DECODE_SPARSE, EKV_OP_DECODE_FUL
 EXPORTS = ["ekv_stats_build", "ekv_stats_append", "ekv_score_pages", "ekv_append_score_pages", "ekv_select_topk",
            "ekv_select_gauss",
            "ekv_select_box_threshold", "ekv_decode_sparse", "ekv_decode_sparse_group", "ekv_decode_full",
-           "ekv_decode_sparse_softmax", "ekv_workspace_bytes", "ekv_probe_read", "ekv_status_string",
-           "ekv_last_hip_error", "ekv_version"]
-_STATUS_CALLS = EXPORTS[:13]      # entry points that return ekv_status
+           "ekv_decode_sparse_softmax", "ekv_workspace_bytes", "ekv_probe_read", "ekv_decode_sparse_static",
+           "ekv_status_string", "ekv_last_hip_error", "ekv_version"]
+_STATUS_CALLS = EXPORTS[:14]      # entry points that return ekv_status
 
 
 class ekv_config(ctypes.Structure):
@@ -79,6 +80,8 @@ def load_library():
     lib.ekv_decode_sparse.argtypes = [P(ekv_config), c_void_p, P(ekv_cache_view), c_void_p, c_void_p, c_void_p,
                                       c_void_p, c_void_p, P(ekv_decode_extras), c_void_p, c_size_t, c_void_p]
     lib.ekv_decode_sparse_group.argtypes = lib.ekv_decode_sparse.argtypes
+    lib.ekv_decode_sparse_static.argtypes = [P(ekv_config), c_void_p, P(ekv_cache_view), c_void_p, c_void_p, c_void_p,
+                                             c_void_p, c_void_p, P(ekv_decode_extras), c_void_p]
     lib.ekv_decode_full.argtypes = [P(ekv_config), c_void_p, P(ekv_cache_view), c_void_p, c_void_p, c_void_p,
                                     P(ekv_decode_extras), c_void_p, c_size_t, c_void_p]
     lib.ekv_decode_sparse_softmax.argtypes = [P(ekv_config), c_void_p, P(ekv_cache_view), c_void_p, c_void_p,
@@ -228,3 +231,9 @@ def ekv_decode_sparse_softmax(cfg, q, cache, page_idx, n_sel, out, lse_sel, work
 def ekv_probe_read(base, page_ids, n_pages, page_bytes, sink, lookup=None, out=None, stream=None):
     _check(load_library().ekv_probe_read(_ptr(base), _ptr(page_ids), _ptr(lookup), n_pages, page_bytes, _ptr(out),
                                          _ptr(sink), _stream(stream)))
+
+
+def ekv_decode_sparse_static(cfg, q, cache, page_idx, n_sel, out, tau, supp, extras=None, stream=None):
+    ex = byref(extras) if extras is not None else None
+    _check(load_library().ekv_decode_sparse_static(byref(cfg), _ptr(q), byref(cache), _ptr(page_idx), _ptr(n_sel),
+                                                   _ptr(out), _ptr(tau), _ptr(supp), ex, _stream(stream)))

@@ -2,6 +2,7 @@
 // Nothing here touches device data from the host or synchronises.
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include "ekv_internal.h"
 
 namespace ekv {
@@ -281,6 +282,49 @@ ekv_status ekv_decode_sparse(const ekv_config* cfg, const void* q, const ekv_cac
                              void* stream) {
   return decode_common(cfg, false, false, q, cache, page_idx, n_sel, out, tau, supp, extras, workspace,
                        workspace_bytes, stream);
+}
+
+// ---- entry point that allocates nothing: decode scratch in a static device array -------------------------------
+// A __device__ array is part of the code object: every GPU the library is loaded on holds its own copy, at its own
+// address, until the process ends.  In host code the array's name only stands for the symbol; its device address is
+// looked up once per device and only that address is used afterwards.
+namespace ekv {
+constexpr size_t kStaticScratchBytes = (size_t)EKV_STATIC_SCRATCH_BYTES;
+constexpr int kStaticScratchDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+static void* g_scratch_ptr[kStaticScratchDevices] = {nullptr};
+static std::mutex g_scratch_mutex;
+
+// Device address of this GPU's copy of `scratch` (looked up on the first call on a device, with that device current).
+static ekv_status static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) { g_last_hip_error = (int32_t)e; return EKV_ERR_HIP; }
+  if (dev < 0 || dev >= kStaticScratchDevices) return EKV_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || ptr == nullptr) { g_last_hip_error = (int32_t)e; return EKV_ERR_HIP; }
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return EKV_OK;
+}
+}  // namespace ekv
+
+ekv_status ekv_decode_sparse_static(const ekv_config* cfg, const void* q, const ekv_cache_view* cache,
+                                    const int32_t* page_idx, const int32_t* n_sel, float* out, float* tau,
+                                    int32_t* supp, const ekv_decode_extras* extras, void* stream) {
+  Dims dm;
+  const ekv_status s = make_dims(cfg, dm);
+  if (s != EKV_OK) return s;
+  if (decode_ws_carve(dm, false, nullptr, nullptr) > kStaticScratchBytes) return EKV_ERR_WORKSPACE;
+  void* ws = nullptr;
+  const ekv_status ss = static_scratch(&ws);
+  if (ss != EKV_OK) return ss;
+  return decode_common(cfg, false, false, q, cache, page_idx, n_sel, out, tau, supp, extras, ws, kStaticScratchBytes,
+                       stream);
 }
 
 ekv_status ekv_decode_full(const ekv_config* cfg, const void* q, const ekv_cache_view* cache, float* out,

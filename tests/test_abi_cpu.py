@@ -151,3 +151,16 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_static_scratch_entry_point_rejects_what_does_not_fit():
+    """ekv_decode_sparse_static has a fixed scratch array: a configuration whose decode workspace is larger is
+    refused with EKV_ERR_WORKSPACE on the host, before any pointer is looked at or anything is launched."""
+    lib = ekv.load_library()
+    big = good_cfg(batch=8, max_sel_pages=8192)
+    assert ekv.ekv_workspace_bytes(big, ekv.EKV_OP_DECODE_SPARSE) > ekv.EKV_STATIC_SCRATCH_BYTES
+    assert lib.ekv_decode_sparse_static(ctypes.byref(big), None, None, None, None, None, None, None, None, None) == 3
+    assert lib.ekv_decode_sparse_static(None, None, None, None, None, None, None, None, None, None) == 1
+    header = open(os.path.join(ROOT, "include", "entmaxkv.h")).read()
+    assert re.search(r"#define\s+EKV_STATIC_SCRATCH_BYTES\s+\(32u\s*<<\s*20\)", header)
+    assert ekv.EKV_STATIC_SCRATCH_BYTES == 32 << 20
