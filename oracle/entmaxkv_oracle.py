@@ -29,7 +29,9 @@ Prop. 2-4 invariants, P=1 reduction, printed truncated-moment closed forms vs
 quadrature; box-threshold refinement: a worked example, the P=1 reduction and
 "one refinement from any start reaches the full-cache result"; 8-bit bounds: the value
 table against a library decoder, directed rounding by brute force over the table, a worked
-example, and "8-bit score >= cache-dtype score >= largest token score".  Unpinned: which pages a *good* Gaussian selector should pick
+example, and "8-bit score >= cache-dtype score >= largest token score"; the storage reading of the Gaussian
+statistics (mean and VARIANCE rounded, k_std = root of the stored variance) against the library's bf16 cast on
+hand-built values; the softmax baseline's output as the explicit sum p_j v_j; R on a hand-worked pair.  Unpinned: which pages a *good* Gaussian selector should pick
 (selection quality; the paper states no hyper-parameters) -- "parity unpinned".
 """
 import numpy as np

@@ -106,18 +106,9 @@ def test_full_size_topk_step_as_timed(fs):
         ok, bad = sets_equal_up_to_cut(idx[b, hq, :k], ref["pages"], ref["box"], [ref["cut_in"], ref["cut_out"]], band)
         assert ok, (hq, bad)
         assert np.all(np.diff(idx[b, hq, :k]) > 0)
-        if set(idx[b, hq, :k].tolist()) == set(ref["pages"].tolist()):
-            assert abs(float(st.tau[b, hq]) - ref["tau"]) <= 4e-6 * max(1.0, abs(ref["tau"]))
-            n_sup = int(st.supp[b, hq])
-            got_tokens = toks[b, hq, :n_sup].cpu().numpy()
-            z = (W.alpha - 1.0) * orc.token_scores(q, K[ref["support"]], W.score_scale)
-            diff = set(got_tokens.tolist()).symmetric_difference(ref["support"].tolist())
-            # a token may fall on either side only if its z is within float32 resolution of tau
-            if diff:
-                zd = (W.alpha - 1.0) * orc.token_scores(q, K[sorted(diff)], W.score_scale)
-                assert np.all(np.abs(zd - ref["tau"]) <= 2e-6 * max(1.0, abs(ref["tau"]))), (hq, sorted(diff))
-            assert z.min() > ref["tau"]
-            assert rel_err(st.out[b, hq].cpu().numpy(), ref["o"]) <= 2e-3
+        # the decode of the list the GPU chose, whether or not it equals the oracle's (pages inside the tie band)
+        own = orc.entmax_attention(q, K, V, W.alpha, W.score_scale, orc.pages_to_tokens(idx[b, hq, :k], P, K.shape[0]))
+        _check_decode(b, hq, st, toks, q, K, own)
 
 
 def test_full_size_dense_decode(fs):
@@ -223,9 +214,8 @@ def test_full_size_gauss_step(fs):
         ok, bad = sets_equal_up_to_cut(got, pages, g, tau_hat, 1e-5 * max(1.0, abs(tau_hat)))
         assert ok, (hq, bad[:5], len(pages), len(got))
         assert np.all(np.diff(got) > 0)
-        if set(got.tolist()) == set(pages.tolist()):
-            ref = orc.entmax_attention(q, K, V, W.alpha, W.score_scale, orc.pages_to_tokens(pages, P, K.shape[0]))
-            _check_decode(b, hq, st, toks, q, K, ref)
+        ref = orc.entmax_attention(q, K, V, W.alpha, W.score_scale, orc.pages_to_tokens(got, P, K.shape[0]))
+        _check_decode(b, hq, st, toks, q, K, ref)
 
 
 def test_full_size_group_shared_step(fs):
@@ -260,9 +250,7 @@ def test_full_size_group_shared_step(fs):
         got = gi[b, h, : gn[b, h]]
         ok, bad = sets_equal_up_to_cut(got, pages, ref_g, [cut_in, cut_out], 1e-5 * max(1.0, abs(cut_in)))
         assert ok, (h, bad)
-        if set(got.tolist()) != set(pages.tolist()):
-            continue
-        tokens = orc.pages_to_tokens(pages, P, K.shape[0])
+        tokens = orc.pages_to_tokens(got, P, K.shape[0])      # the GPU's own list for this KV head
         for g in range(G):
             ref = orc.entmax_attention(qs[g], K, V, W.alpha, W.score_scale, tokens)
             _check_decode(b, h * G + g, st, toks, qs[g], K, ref)
@@ -299,9 +287,9 @@ def test_full_size_box8_topk_step(fs):
         pages, cut_in, cut_out = orc.topk_pages(s8, k)
         ok, bad = sets_equal_up_to_cut(idx[b, hq, : ns[b, hq]], pages, s8, [cut_in, cut_out], 1e-5 * max(1.0, abs(cut_in)))
         assert ok, (b, hq, bad)
-        if set(idx[b, hq, : ns[b, hq]].tolist()) == set(pages.tolist()):
-            ref = orc.entmax_attention(q, K, V, W.alpha, W.score_scale, orc.pages_to_tokens(pages, P, K.shape[0]))
-            _check_decode(b, hq, st, toks, q, K, ref)
+        ref = orc.entmax_attention(q, K, V, W.alpha, W.score_scale,
+                                   orc.pages_to_tokens(idx[b, hq, : ns[b, hq]], P, K.shape[0]))
+        _check_decode(b, hq, st, toks, q, K, ref)
     del st.box8_stats                                  # the other tests of this module run without it
 
 

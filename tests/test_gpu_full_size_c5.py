@@ -14,7 +14,8 @@ import torch
 from oracle import entmaxkv_oracle as orc
 from paper_2605_21649_amd import binding as ekv
 from paper_2605_21649_amd import synth
-from tests.helpers import DeviceState, sets_equal_up_to_cut, rel_err, to_f64
+from tests.helpers import (DeviceState, sets_equal_up_to_cut, rel_err, to_f64, check_decode_unit,
+                           check_decode_of_gpu_list)
 
 pytestmark = pytest.mark.gpu
 
@@ -79,24 +80,27 @@ def test_full_size_topk_and_dense_under_each_alpha(c5, alpha):
         band = 1e-5 * max(1.0, abs(ref["cut_in"]))
         ok, bad = sets_equal_up_to_cut(idx[b, hq], ref["pages"], ref["box"], [ref["cut_in"], ref["cut_out"]], band)
         assert ok, (hq, bad)
+        wa = W.scaled(alpha=alpha)
         dense = orc.entmax_attention(q, K, V, alpha, W.score_scale)
-        assert abs(float(full["tau"][b, hq]) - dense["tau"]) <= 4e-6 * max(1.0, abs(dense["tau"]))
-        assert rel_err(full["out"][b, hq].cpu().numpy(), dense["o"]) <= 2e-3
-        assert abs(int(full["supp"][b, hq]) - len(dense["support"])) <= 1      # a token may sit on tau in float32
+        # tau, output, and the support count exact up to tokens whose z lies within float32 resolution of tau
+        check_decode_unit(wa, full["out"][b, hq].cpu().numpy(), float(full["tau"][b, hq]), int(full["supp"][b, hq]),
+                          None, dense)
         lse_ref = float(np.log(np.sum(np.exp(dense["s"] - dense["s"].max()))) + dense["s"].max())
         assert abs(float(full["lse"][b, hq]) - lse_ref) <= 1e-4 * max(1.0, abs(lse_ref))
         if alpha == 2.0:
             assert abs(float(full["tau"][b, hq]) - sparsemax_tau(a * dense["s"])) <= 4e-6
-        if set(idx[b, hq].tolist()) == set(ref["pages"].tolist()):
-            assert abs(float(st.tau[b, hq]) - ref["tau"]) <= 4e-6 * max(1.0, abs(ref["tau"]))
-            assert rel_err(st.out[b, hq].cpu().numpy(), ref["o"]) <= 2e-3
-            assert abs(int(st.supp[b, hq]) - len(ref["support"])) <= 1
-            # dropped mass and support recall of the selection under the dense threshold (Eq. 4, Eq. 7)
-            delta = orc.dropped_mass(dense["p"], ref["tokens"])
-            assert abs((1.0 - float(kept[b, hq])) - delta) <= 1e-4
-            rho = orc.support_retention(dense["support"], ref["tokens"])
-            assert abs(int(kept_n[b, hq]) - rho * len(dense["support"])) <= 1
-            assert float(st.tau[b, hq]) <= float(full["tau"][b, hq]) + 1e-6    # a sparse solve never overshoots
+        # the sparse decode of the list the GPU chose (equal to the oracle's or not: pages inside the tie band)
+        own = check_decode_of_gpu_list(wa, q, K, V, idx[b, hq], st.out[b, hq].cpu().numpy(), st.tau[b, hq],
+                                       st.supp[b, hq])
+        # dropped mass and support recall of that selection under the dense threshold (Eq. 4, Eq. 7); a dense
+        # support token on the float32 boundary of tau may or may not be counted
+        delta = orc.dropped_mass(dense["p"], own["tokens"])
+        assert abs((1.0 - float(kept[b, hq])) - delta) <= 1e-4
+        rho = orc.support_retention(dense["support"], own["tokens"])
+        zb = a * dense["s"]
+        n_bound = int(np.sum(np.abs(zb - dense["tau"]) <= 2e-6 * max(1.0, abs(dense["tau"]))))
+        assert abs(int(kept_n[b, hq]) - rho * len(dense["support"])) <= n_bound + 0.5
+        assert float(st.tau[b, hq]) <= float(full["tau"][b, hq]) + 1e-6    # a sparse solve never overshoots
 
 
 def test_full_size_softmax_over_the_topk_lists(c5):

@@ -21,7 +21,7 @@ from oracle import entmaxkv_oracle as orc
 from paper_2605_21649_amd import binding as ekv
 from paper_2605_21649_amd import synth
 from tests.helpers import (DeviceState, unit_kv, oracle_stats, storage_ulp, sets_equal_up_to_cut, rel_err,
-                           to_f64)
+                           to_f64, OUT_TOL, check_decode_unit, check_decode_of_gpu_list)
 
 pytestmark = pytest.mark.gpu
 
@@ -36,7 +36,6 @@ W3A = synth.C3.scaled(name="C3-small-a43", batch=1, context=4096 + 32, ragged=9,
 ALL = [W1, W1S, W1R, W2, W3, W3A, W5, W5B]
 IDS = [w.name for w in ALL]
 
-OUT_TOL = {"f32": 1e-5, "bf16": 2e-3}
 _cache = {}
 
 
@@ -333,23 +332,6 @@ def test_select_gauss_empty_and_overflow():
 
 
 # ---------------------------------------------------------------------------- a7 / a8 / metrics
-def check_decode_unit(w, got_out, got_tau, got_supp, got_tokens, ref):
-    tol = OUT_TOL[w.kv_dtype]
-    assert abs(got_tau - ref["tau"]) <= 4e-6 * max(1.0, abs(ref["tau"])), (got_tau, ref["tau"])
-    # tokens whose z sits within float32 resolution of tau may fall on either side; everything else
-    # must match exactly.  On the float32-cache workloads the seeded inputs have no such token.
-    z = (w.alpha - 1.0) * ref["s"]
-    boundary = set(ref["tokens"][np.abs(z - ref["tau"]) <= 2e-6 * max(1.0, abs(ref["tau"]))].tolist())
-    if w.kv_dtype == "f32":
-        assert not boundary, "seeded float32 input has a token on the support boundary"
-    assert abs(got_supp - len(ref["support"])) <= len(boundary)
-    if got_tokens is not None:
-        diff = set(got_tokens[:got_supp].tolist()).symmetric_difference(ref["support"].tolist())
-        assert diff.issubset(boundary), sorted(diff)
-        assert np.all(np.diff(got_tokens[:got_supp]) > 0)
-    assert rel_err(got_out, ref["o"]) <= tol, rel_err(got_out, ref["o"])
-
-
 @pytest.mark.parametrize("w", ALL, ids=IDS)
 def test_decode_sparse_and_full_on_shared_page_lists(w):
     inp = get_inputs(w)
@@ -567,10 +549,9 @@ def test_end_to_end_topk_step(w):
         band = 1e-5 * max(1.0, abs(ref["cut_in"]))
         ok, bad = sets_equal_up_to_cut(idx[b, hq, : ns[b, hq]], ref["pages"], ref["box"], cuts, band)
         assert ok, (b, hq, bad)
-        if set(idx[b, hq, : ns[b, hq]].tolist()) == set(ref["pages"].tolist()):
-            assert abs(float(st.tau[b, hq]) - ref["tau"]) <= 4e-6 * max(1.0, abs(ref["tau"]))
-            assert int(st.supp[b, hq]) == len(ref["support"])
-            assert rel_err(st.out[b, hq].cpu().numpy(), ref["o"]) <= OUT_TOL[w.kv_dtype]
+        # the decode is checked for the list the GPU chose, whether or not it equals the oracle's (tie band)
+        check_decode_of_gpu_list(w, q, K, V, idx[b, hq, : ns[b, hq]], st.out[b, hq].cpu().numpy(), st.tau[b, hq],
+                                 st.supp[b, hq])
 
 
 @pytest.mark.parametrize("w", [W1S, W2, W5B], ids=["C1-soft", "C2-8k", "C5-small-a2"])
@@ -639,9 +620,9 @@ def test_candidate_list_larger_than_lds_uses_the_streaming_path():
         ref = orc.entmax_attention(q, K, V, w.alpha, w.score_scale)
         z = (w.alpha - 1.0) * ref["s"]
         assert np.sum(z > z.max() - 1.0) > 4096 and len(ref["support"]) > 4096
-        assert abs(float(tau_f[0, hq]) - ref["tau"]) <= 4e-6 * max(1.0, abs(ref["tau"]))
-        assert abs(int(supp_f[0, hq]) - len(ref["support"])) <= 2
-        assert rel_err(out_f[0, hq].cpu().numpy(), ref["o"]) <= 2e-5
+        # same rule as everywhere: tau 4e-6, output 1e-5, support exact up to tokens within float32 resolution of tau
+        check_decode_unit(w, out_f[0, hq].cpu().numpy(), float(tau_f[0, hq]), int(supp_f[0, hq]), None, ref,
+                          boundary_expected=True)
 
 
 LONG = [synth.C2.scaled(name="C2-long-bf16", context=100000, ragged=7, n_q_heads=4, n_kv_heads=2),
@@ -695,10 +676,10 @@ def test_decode_long_rows_take_the_filter_passes(w):
         ref_s = orc.entmax_attention(q, K, V, w.alpha, w.score_scale, tok)
         if flat:
             assert len(ref["support"]) > 4096 and len(ref_s["support"]) > 4096
+            # supports larger than the token list the test asked for: counts, tau and outputs under the usual rule
             for got_tau, got_supp, got_out, r in ((tau_f, supp_f, out_f, ref), (st.tau, st.supp, st.out, ref_s)):
-                assert abs(float(got_tau[b, hq]) - r["tau"]) <= 4e-6 * max(1.0, abs(r["tau"]))
-                assert abs(int(got_supp[b, hq]) - len(r["support"])) <= 4
-                assert rel_err(got_out[b, hq].cpu().numpy(), r["o"]) <= 2e-5
+                check_decode_unit(w, got_out[b, hq].cpu().numpy(), float(got_tau[b, hq]), int(got_supp[b, hq]), None, r,
+                                  boundary_expected=True)
         else:
             check_decode_unit(w, out_f[b, hq].cpu().numpy(), float(tau_f[b, hq]), int(supp_f[b, hq]),
                               full_tokens[b, hq], ref)
@@ -844,14 +825,12 @@ def test_group_shared_step(w):
             ok, bad = sets_equal_up_to_cut(gi[b, hkv, : gn[b, hkv]], pages, ref_g, [cut_in, cut_out],
                                            1e-5 * max(1.0, abs(cut_in)))
             assert ok, (b, hkv, bad)
-            if set(gi[b, hkv, : gn[b, hkv]].tolist()) != set(pages.tolist()):
-                continue
+            # every head of the group decodes the list the GPU wrote for its KV head (equal to the oracle's or not)
             for g in range(G if (b, hkv) in ((0, 0), (w.batch - 1, w.n_kv_heads - 1)) else 0):
                 hq = hkv * G + g
                 q, K, V = unit_kv(inp, w, b, hq)
-                ref = orc.entmax_attention(q, K, V, w.alpha, w.score_scale, orc.pages_to_tokens(pages, w.page_size, K.shape[0]))
-                check_decode_unit(w, st.out[b, hq].cpu().numpy(), float(st.tau[b, hq]), int(st.supp[b, hq]),
-                                  toks[b, hq], ref)
+                check_decode_of_gpu_list(w, q, K, V, gi[b, hkv, : gn[b, hkv]], st.out[b, hq].cpu().numpy(),
+                                         st.tau[b, hq], st.supp[b, hq], toks[b, hq])
 
 
 def test_group_decode_equals_per_head_decode_on_the_same_lists():
@@ -970,9 +949,8 @@ def test_multi_step_decode_loop_with_ragged_batch():
             ok, bad = sets_equal_up_to_cut(idx[b, hq, : ns[b, hq]], ref["pages"], ref["box"],
                                            [ref["cut_in"], ref["cut_out"]], 1e-5 * max(1.0, abs(ref["cut_in"])))
             assert ok, (step, b, hq, bad)
-            if set(idx[b, hq, : ns[b, hq]].tolist()) == set(ref["pages"].tolist()):
-                assert abs(float(tau[b, hq]) - ref["tau"]) <= 4e-6 * max(1.0, abs(ref["tau"]))
-                assert rel_err(out[b, hq].cpu().numpy(), ref["o"]) <= OUT_TOL[w.kv_dtype]
+            check_decode_of_gpu_list(w, q, K, V, idx[b, hq, : ns[b, hq]], out[b, hq].cpu().numpy(), tau[b, hq],
+                                     supp[b, hq])
     box_a, gauss_a = st.box_stats.clone(), st.gauss_stats.clone()
     ekv.ekv_stats_build(st.cfg, st.cache(), st.stats())
     torch.cuda.synchronize()
@@ -1031,9 +1009,8 @@ def test_shape_matrix_whole_step_and_dense(w):
         ok, bad = sets_equal_up_to_cut(idx[b, hq, : ns[b, hq]], ref["pages"], ref["box"],
                                        [ref["cut_in"], ref["cut_out"]], 1e-5 * max(1.0, abs(ref["cut_in"])))
         assert ok, (b, hq, bad)
-        if set(idx[b, hq, : ns[b, hq]].tolist()) == set(ref["pages"].tolist()):
-            sp = orc.entmax_attention(q, K, V, w.alpha, w.score_scale, ref["tokens"])
-            check_decode_unit(w, st.out[b, hq].cpu().numpy(), float(st.tau[b, hq]), int(st.supp[b, hq]), None, sp)
+        check_decode_of_gpu_list(w, q, K, V, idx[b, hq, : ns[b, hq]], st.out[b, hq].cpu().numpy(), st.tau[b, hq],
+                                 st.supp[b, hq])
         full = orc.entmax_attention(q, K, V, w.alpha, w.score_scale)
         check_decode_unit(w, out_f[b, hq].cpu().numpy(), float(tau_f[b, hq]), int(supp_f[b, hq]), None, full)
 
@@ -1197,9 +1174,7 @@ def test_batch_slot_with_zero_tokens(kv_dtype, context, lens):
                     if ref["overflow"]:
                         continue
                 got = st.page_idx[b, hq, : int(st.n_sel[b, hq])].cpu().numpy()
-                if set(got.tolist()) == set(ref["pages"].tolist()):
-                    ref["s"] = orc.token_scores(q, K[ref["tokens"]], w.score_scale)
-                    check_decode_unit(w, st.out[b, hq].cpu().numpy(), float(st.tau[b, hq]), int(st.supp[b, hq]), None, ref)
+                check_decode_of_gpu_list(w, q, K, V, got, st.out[b, hq].cpu().numpy(), st.tau[b, hq], st.supp[b, hq])
                 dense = orc.entmax_attention(q, K, V, w.alpha, w.score_scale)
                 check_decode_unit(w, full["out"][b, hq].cpu().numpy(), float(full["tau"][b, hq]),
                                   int(full["supp"][b, hq]), None, dense)
@@ -1294,12 +1269,10 @@ def test_many_short_rows_step(kv_dtype, ctx, k, scale, alpha):
         band = 1e-5 * max(1.0, abs(ref["cut_in"]))
         ok, bad = sets_equal_up_to_cut(got, ref["pages"], ref["box"], [ref["cut_in"], ref["cut_out"]], band)
         assert ok, (b, hq, bad)
-        if set(got.tolist()) == set(ref["pages"].tolist()):
-            ref["s"] = orc.token_scores(q, K[ref["tokens"]], w.score_scale)
-            check_decode_unit(w, st.out[b, hq].cpu().numpy(), float(st.tau[b, hq]), int(st.supp[b, hq]),
-                              toks[b, hq].cpu().numpy(), ref)
-            dense = orc.entmax_attention(q, K, V, w.alpha, w.score_scale)
-            assert abs((1.0 - float(km[b, hq])) - orc.dropped_mass(dense["p"], ref["tokens"])) <= 1e-4
+        own = check_decode_of_gpu_list(w, q, K, V, got, st.out[b, hq].cpu().numpy(), st.tau[b, hq], st.supp[b, hq],
+                                       toks[b, hq].cpu().numpy())
+        dense = orc.entmax_attention(q, K, V, w.alpha, w.score_scale)
+        assert abs((1.0 - float(km[b, hq])) - orc.dropped_mass(dense["p"], own["tokens"])) <= 1e-4
     # a warm start (the exact thresholds as seeds) changes nothing but the number of evaluations
     out2, tau2, supp2 = torch.zeros_like(st.out), torch.zeros_like(st.tau), torch.zeros_like(st.supp)
     evals = torch.full_like(st.supp, -1)

@@ -4,6 +4,7 @@ Each test checks the oracle against something other than itself: brute force, a 
 closed form, a value the paper prints, or an invariant the paper proves."""
 import itertools
 import os
+import math
 import numpy as np
 import pytest
 from scipy.optimize import brentq
@@ -145,6 +146,40 @@ def test_attention_uses_q_dot_k_and_p_times_v():
     p_ref, _ = brute_force_entmax(s, 1.5)
     np.testing.assert_allclose(att["p"], p_ref, atol=1e-12)
     np.testing.assert_allclose(att["o"], sum(p_ref[j] * V[j] for j in range(n)), atol=1e-12)
+
+
+def test_softmax_attention_output_is_p_times_v():
+    # same construction for the softmax baseline: probabilities and log-sum-exp typed out term by term, and the
+    # output as the explicit sum p_j v_j over a candidate subset (a transposed V, a sum over the wrong axis or
+    # values taken from the wrong tokens all fail)
+    d, n = 5, 7
+    K = np.arange(n * d, dtype=np.float64).reshape(n, d) / 10.0
+    V = np.eye(n, d) + 2.0 + np.arange(n)[:, None] * 0.25
+    q = np.zeros(d); q[1] = -1.5
+    tokens = np.array([6, 0, 3, 4])
+    att = orc.softmax_attention(q, K, V, 0.5, tokens=tokens)
+    s = [0.5 * -1.5 * K[j, 1] for j in tokens]
+    z = sum(math.exp(x) for x in s)
+    p_ref = [math.exp(x) / z for x in s]
+    np.testing.assert_allclose(att["s"], s, atol=1e-15)
+    np.testing.assert_allclose(att["p"], p_ref, atol=1e-15)
+    assert abs(att["lse"] - math.log(z)) < 1e-14
+    o_ref = np.zeros(d)
+    for pj, j in zip(p_ref, tokens):
+        o_ref += pj * V[j]
+    np.testing.assert_allclose(att["o"], o_ref, atol=1e-14)
+    # one candidate: its value row exactly
+    one = orc.softmax_attention(q, K, V, 0.5, tokens=np.array([2]))
+    np.testing.assert_array_equal(one["o"], V[2])
+
+
+def test_relative_output_error_by_hand():
+    # R = ||o - o~|| / ||o|| with the FULL-cache output in the denominator (App. E.1): o = (3, 4), o~ = (3, 0)
+    o, ot = np.array([3.0, 4.0]), np.array([3.0, 0.0])
+    assert orc.relative_output_error(o, ot) == pytest.approx(4.0 / 5.0, abs=1e-15)
+    assert orc.relative_output_error(ot, o) == pytest.approx(4.0 / 3.0, abs=1e-15)     # not symmetric
+    assert orc.relative_output_error(o, o) == 0.0
+    assert orc.relative_output_error(np.array([0.0, 2.0, 0.0]), np.array([1.0, 2.0, 2.0])) == pytest.approx(math.sqrt(5.0) / 2.0)
 
 
 def test_prop1_tightness_golden():

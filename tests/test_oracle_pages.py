@@ -20,6 +20,27 @@ def test_round_to_bf16_matches_library_cast():
     np.testing.assert_array_equal(orc.round_to_storage(x, "f32"), ref32)
 
 
+def test_stored_gauss_stats_round_mean_and_variance_not_std():
+    # Storage reading: the cache-dtype copy holds the mean and the VARIANCE; k_std is the root of the stored
+    # variance.  Hand-built values whose bf16 roundings tell the variants apart, checked against the library cast.
+    kavg = np.array([[0.3337, -5.0123, 1.0e-3], [2.00390625, 7.77, -0.0]])
+    kstd = np.array([[1.2345, 0.05678, 3.0], [0.999, 1.0039, 0.0]])
+    to_bf16 = lambda a: torch.tensor(a, dtype=torch.float64).to(torch.bfloat16).to(torch.float64).numpy()
+    avg_s, std_s = orc.stored_gauss_stats(kavg, kstd, "bf16")
+    np.testing.assert_array_equal(avg_s, to_bf16(kavg))
+    np.testing.assert_array_equal(std_s, np.sqrt(to_bf16(kstd * kstd)))
+    # the variants a slip would produce differ on these values: rounding k_std instead of its square, or no root
+    assert np.any(std_s != to_bf16(kstd))
+    assert np.any(std_s != np.sqrt(to_bf16(kstd) ** 2))
+    assert np.any(std_s != to_bf16(kstd * kstd))
+    # exactly representable inputs pass through unchanged; a float32 store rounds to float32
+    avg_e, std_e = orc.stored_gauss_stats(np.array([1.5, -0.25]), np.array([2.0, 0.5]), "bf16")
+    np.testing.assert_array_equal(avg_e, [1.5, -0.25]); np.testing.assert_array_equal(std_e, [2.0, 0.5])
+    avg_f, std_f = orc.stored_gauss_stats(kavg, kstd, "f32")
+    np.testing.assert_array_equal(avg_f, kavg.astype(np.float32).astype(np.float64))
+    np.testing.assert_array_equal(std_f, np.sqrt((kstd * kstd).astype(np.float32).astype(np.float64)))
+
+
 # ---------------------------------------------------------------- stage 1
 def test_page_stats_against_numpy_reductions():
     rng = np.random.default_rng(1)
