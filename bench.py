@@ -73,7 +73,7 @@ class Runner:
     def __init__(self, w, budget, n_copies, q_page, dev, cap_frac=0.04, fused_append=True):
         import torch
         from paper_2605_21649_amd import binding as ekv, synth
-        from paper_2605_21649_amd.device_state import DeviceState
+        from tests.device_state import DeviceState
         self.torch, self.ekv, self.w, self.dev, self.q_page = torch, ekv, w, dev, q_page
         self.fused_append = fused_append
         B, Hkv, d, P, n = w.batch, w.n_kv_heads, w.head_dim, w.page_size, w.context
@@ -271,7 +271,7 @@ def main():
     import numpy as np
     import torch
     from paper_2605_21649_amd import binding as ekv, synth
-    from paper_2605_21649_amd.device_state import DeviceState
+    from tests.device_state import DeviceState
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     ekv.load_library()

@@ -3,8 +3,8 @@
 Plumbing for the tests and the benchmark (torch allocates, the library computes); no part of the method."""
 import torch
 
-from . import binding as ekv
-from . import synth
+from paper_2605_21649_amd import binding as ekv
+from paper_2605_21649_amd import synth
 
 
 class DeviceState:

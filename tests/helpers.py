@@ -9,7 +9,7 @@ import torch
 from oracle import entmaxkv_oracle as orc
 from paper_2605_21649_amd import binding as ekv
 from paper_2605_21649_amd import synth
-from paper_2605_21649_amd.device_state import DeviceState  # noqa: F401  (re-exported for the tests)
+from tests.device_state import DeviceState  # noqa: F401  (re-exported for the tests)
 
 
 def to_f64(t):

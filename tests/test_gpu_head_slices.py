@@ -8,7 +8,7 @@ import torch
 
 from paper_2605_21649_amd import binding as ekv
 from paper_2605_21649_amd import synth
-from paper_2605_21649_amd.device_state import DeviceState, HeadSlice
+from tests.device_state import DeviceState, HeadSlice
 
 pytestmark = pytest.mark.gpu
 
