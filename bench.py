@@ -28,10 +28,14 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# FETCH_SIZE + WRITE_SIZE of one page-scoring launch at C4 (rocprofv3 --pmc, scaled by a plain copy of known
-# size; see profiles/bench_topk_step_C4.md): the instantiation with the append inside (the one the step runs)
-# 256.32 MiB read + 8.02 MiB written, the one without 256.12 + 8.00
+# HBM bytes per launch from the committed counter runs (rocprofv3 --pmc FETCH_SIZE, then WRITE_SIZE, each scaled by
+# the same counter's reading for a plain copy of known size): NOT measured in this run, copied from
+# profiles/bench_topk_step_C4.md, and valid for the C4 workload at the default budget only.
+#   page scoring with the append inside (the launch the step runs): 256.32 MiB read + 8.02 MiB written;
+#   without the append: 256.12 + 8.00;  score pass of the sparse decode: PMC_TRAFFIC_DECODE_SCORES_C4
+PMC_TRAFFIC_SOURCE = "profiles/bench_topk_step_C4.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a plain copy)"
 PMC_TRAFFIC_SCORE_PAGES_C4 = {True: int((256.32 + 8.02) * 1024 * 1024), False: int((256.12 + 8.00) * 1024 * 1024)}
+PMC_TRAFFIC_DECODE_SCORES_C4 = int((165.39 + 2.79) * 1024 * 1024)
 
 # the append runs inside the scoring launch (ekv_append_score_pages) unless --two-launch-append is given
 STAGE_NAMES = {"topk": ["append_own_launch", "append+score_box", "select_topk", "decode_sparse"],
@@ -60,7 +64,7 @@ def parse():
                     help="append with its own launch (ekv_stats_append) instead of inside the scoring launch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="time only the headline step")
-    ap.add_argument("--cpu-units", type=int, default=16, help="(b,h) units the oracle is timed on")
+    ap.add_argument("--cpu-units", type=int, default=64, help="most (b,h) units the oracle is timed on (C4 has 32)")
     ap.add_argument("--pmc-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (calibrates rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     return ap.parse_args()
@@ -109,6 +113,12 @@ class Runner:
 
     def ev(self):
         return self.torch.cuda.Event(enable_timing=True)
+
+    def full_ws(self):
+        """Scratch of the dense decode, one buffer shared by the copies."""
+        if self.ws_full is None:
+            self.ws_full = self.copies[0].workspace(self.ekv.EKV_OP_DECODE_FULL)
+        return self.ws_full
 
     # ---- steps ---------------------------------------------------------------------------------
     def append_and_score(self, st, evs, mode, box=None, mu=None, sigma=None):
@@ -261,6 +271,116 @@ class Runner:
         self.torch.cuda.empty_cache()
 
 
+# ---- CPU baseline: the float64 oracle's whole top-k step, one thread and all cores ----------------------------
+def _bf16_bits_to_f64(bits):
+    import numpy as np
+    return (bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def _cpu_worker(task):
+    """One process of the all-core leg: loads the K and V of its KV heads (raw cache values written by the parent),
+    waits until every process is ready, then times the oracle on its units.  No GPU, no torch."""
+    import numpy as np
+    from threadpoolctl import threadpool_limits
+    from oracle import entmaxkv_oracle as orc
+    threadpool_limits(1)
+    units, wdict, k_pages, tmpdir, ready, go, done = task
+    cache, t_units = {}, 0.0
+    for (b, hq) in units:
+        key = (b, hq // wdict["group"])
+        if key not in cache:
+            raw = np.load(os.path.join(tmpdir, "kv_%d_%d.npy" % key))
+            conv = _bf16_bits_to_f64 if wdict["kv_dtype"] == "bf16" else (lambda x: x.astype(np.float64))
+            cache[key] = (conv(raw[0]), conv(raw[1]))
+    qs = np.load(os.path.join(tmpdir, "q.npy"))
+    ready.release()
+    go.wait()
+    t0 = time.perf_counter()
+    for (b, hq) in units:
+        K64, V64 = cache[(b, hq // wdict["group"])]
+        orc.decode_step_unit(qs[b, hq], K64, V64, wdict["P"], wdict["alpha"], wdict["scale"], "topk", wdict["kv_dtype"],
+                             k_pages=k_pages)
+    t_units = time.perf_counter() - t0
+    done.put(t_units)
+
+
+def cpu_baseline(inp, w, k_pages, max_units):
+    """The oracle (numpy float64, never tuned for this) over (batch, head) units of the benchmark's own inputs:
+    one thread over every unit, then all host cores (one process per core, units split evenly), no extrapolation
+    unless the workload has more units than `max_units`."""
+    import multiprocessing as mp
+    import shutil
+    import tempfile
+    import numpy as np
+    import torch
+    from oracle import entmaxkv_oracle as orc
+    from paper_2605_21649_amd import synth
+    from tests.helpers import to_f64
+    from threadpoolctl import threadpool_limits
+    B, Hq, P = w.batch, w.n_q_heads, w.page_size
+    all_units = [(b, h) for b in range(B) for h in range(Hq)]
+    units = all_units[: max(1, min(max_units, len(all_units)))]
+    try:
+        cores = len(os.sched_getaffinity(0))
+    except AttributeError:
+        cores = os.cpu_count()
+    # raw cache values of the KV heads involved, for the worker processes (bf16 bit patterns: 2 bytes per element)
+    shm = "/dev/shm" if os.path.isdir("/dev/shm") and shutil.disk_usage("/dev/shm").free > (8 << 30) else None
+    tmpdir = tempfile.mkdtemp(prefix="ekv_cpu_", dir=shm)
+    try:
+        for key in sorted({(b, hq // w.group) for (b, hq) in units}):
+            k_t, v_t = synth.logical_kv(inp, w, key[0], key[1])
+            kv = torch.stack([k_t, v_t]).cpu()
+            raw = kv.view(torch.int16).numpy().view(np.uint16) if w.kv_dtype == "bf16" else kv.numpy()
+            np.save(os.path.join(tmpdir, "kv_%d_%d.npy" % key), raw)
+            del k_t, v_t, kv, raw
+        np.save(os.path.join(tmpdir, "q.npy"), to_f64(inp["q"]))
+        # ---- one thread, every unit
+        t_one, kv_key, K64, V64 = 0.0, None, None, None
+        with threadpool_limits(1):
+            for (b, hq) in units:
+                if kv_key != (b, hq // w.group):                   # heads of one group share the K/V conversion
+                    K64 = V64 = None
+                    k_t, v_t = synth.logical_kv(inp, w, b, hq // w.group)
+                    K64, V64 = to_f64(k_t), to_f64(v_t)
+                    kv_key = (b, hq // w.group)
+                    del k_t, v_t
+                q64 = to_f64(inp["q"][b, hq])
+                t0 = time.perf_counter()
+                orc.decode_step_unit(q64, K64, V64, P, w.alpha, w.score_scale, "topk", w.kv_dtype, k_pages=k_pages)
+                t_one += time.perf_counter() - t0
+        K64 = V64 = None
+        # ---- all cores: one process per core (fresh interpreters that never touch the GPU), units split evenly
+        n_proc = max(1, min(cores, len(units)))
+        chunks = [units[i * len(units) // n_proc:(i + 1) * len(units) // n_proc] for i in range(n_proc)]
+        ctx = mp.get_context("spawn")
+        ready, go, done = ctx.Semaphore(0), ctx.Event(), ctx.Queue()
+        wdict = dict(group=w.group, kv_dtype=w.kv_dtype, P=P, alpha=w.alpha, scale=w.score_scale)
+        procs = [ctx.Process(target=_cpu_worker, args=((c, wdict, k_pages, tmpdir, ready, go, done),)) for c in chunks]
+        for pr in procs:
+            pr.start()
+        for _ in procs:
+            ready.acquire()
+        t0 = time.perf_counter()
+        go.set()
+        busy = [done.get() for _ in procs]
+        t_all = time.perf_counter() - t0
+        for pr in procs:
+            pr.join()
+    finally:
+        shutil.rmtree(tmpdir, ignore_errors=True)
+    scale_up = len(all_units) / len(units)
+    note = "" if len(units) == len(all_units) else f"; {len(units)} of {len(all_units)} units timed, values scaled by {scale_up:.2f}"
+    return {
+        "value": round(t_all * scale_up * 1e6, 1), "unit": "us", "cores": n_proc, "kind": "oracle",
+        "one_thread": {"value": round(t_one * scale_up * 1e6, 1), "unit": "us", "cores": 1},
+        "host_cores_available": cores,
+        "sample": f"float64 numpy oracle, whole top-k step (stats + box score + top-k + sparse entmax) of "
+                  f"{len(units)} (batch, head) units of the benchmark's own inputs: {t_one:.1f} s on one thread, "
+                  f"{t_all:.1f} s wall with {n_proc} single-threaded processes (slowest process busy {max(busy):.1f} s)" + note,
+    }
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -328,6 +448,9 @@ def main():
                                                            st.n_sel, st.ws_topk))
     t_dec = R.back_to_back(lambda st: ekv.ekv_decode_sparse(st.cfg, st.inp["q"], st.cache(), st.page_idx, st.n_sel,
                                                             st.out, st.tau, st.supp, st.ws_sparse))
+    ex_pass1 = ekv.decode_extras(score_pass_only=True)
+    t_dec_scores = R.back_to_back(lambda st: ekv.ekv_decode_sparse(st.cfg, st.inp["q"], st.cache(), st.page_idx, st.n_sel,
+                                                                   st.out, st.tau, st.supp, st.ws_sparse, extras=ex_pass1))
     kernel_alg_bytes = {
         "stats_append": None,
         "score_pages(box)": bytes_meta + B * Hq * M * 4,                 # metadata read + scores written
@@ -366,6 +489,26 @@ def main():
         "algorithmic_bytes_per_launch": int(roof_bytes), "avg_launch_us": round(roof_us, 2),
         "timing": "HIP events around 60 back-to-back launches on the launch stream, %d rotating copies" % args.copies,
     }
+    roofline["traffic_source"] = PMC_TRAFFIC_SOURCE if roofline["traffic"] is not None else None
+    # The sparse entmax decode itself (a7): its HBM-bound kernel is the score pass (gather of the selected K pages,
+    # scores and group maxima written), timed alone through the score_pass_only measurement flag; `call` is the
+    # whole entry point (score pass + solve, which also reads the V rows of the support).
+    a7_bytes = bytes_k + bytes_z / 2 + B * Hq * sel_tokens / 64 * 4        # K pages read, z and group maxima written
+    a7_ach = a7_bytes / (t_dec_scores * 1e-6) / 1e9
+    call_ach = kernel_alg_bytes["decode_sparse"] / (t_dec * 1e-6) / 1e9
+    roofline_a7 = {
+        "bound": "hbm", "kernel": "decode_scores_mfma_kernel<1, 0, %d> (score pass of ekv_decode_sparse)" % P,
+        "achieved": round(a7_ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(a7_ach / HBM_PEAK_GBS, 4),
+        "traffic": PMC_TRAFFIC_DECODE_SCORES_C4 if (args.workload == "C4" and abs(args.budget - 0.02) < 1e-9) else None,
+        "algorithmic_bytes_per_launch": int(a7_bytes), "avg_launch_us": round(t_dec_scores, 2),
+        "call": {"entry_point": "ekv_decode_sparse (score pass + solve)", "avg_us": round(t_dec, 2),
+                 "algorithmic_bytes": int(kernel_alg_bytes["decode_sparse"]), "GBps": round(call_ach, 1),
+                 "frac": round(call_ach / HBM_PEAK_GBS, 4)},
+        "timing": "HIP events around 60 back-to-back launches on the launch stream, %d rotating copies" % args.copies,
+    }
+    roofline_a7["traffic_source"] = PMC_TRAFFIC_SOURCE if roofline_a7["traffic"] is not None else None
+    kernels["decode_sparse(score pass only)"] = {"launch_us": round(t_dec_scores, 2), "algorithmic_bytes": int(a7_bytes),
+                                                 "GBps": round(a7_ach, 1), "kernels": 1}
     dom_name = stage_names[int(np.argmax(stage_mean))]
 
     result = {
@@ -388,36 +531,60 @@ def main():
         "dense_equivalent_GBps": round(dense_bytes / (us_wall * 1e-6) / 1e9, 1),
         "selected_pages_mean": n_sel_mean, "support_mean": supp_mean,
         "roofline": roofline,
+        "roofline_a7": roofline_a7,
         "kernels": kernels,
     }
 
     # ---------------------------------------------------------------- the other rows, same run
     if not args.no_extras:
         extras = {}
-        # context for the roofline fractions: what a plain device copy (torch's elementwise copy kernel,
-        # 1 GiB read + 1 GiB written) moves on this GPU
-        src = torch.empty(256 * 1024 * 1024, dtype=torch.float32, device=dev).normal_()
-        dst = torch.empty_like(src)
-        for _ in range(2):
-            dst.copy_(src)
-        a, b = R.ev(), R.ev()
-        a.record()
-        for _ in range(5):
-            dst.copy_(src)
-        b.record()
-        torch.cuda.synchronize()
-        extras["plain_copy_GBps_measured"] = round(2 * src.numel() * 4 / (a.elapsed_time(b) * 1e-3 / 5) / 1e9, 1)
-        # ... and what a plain read-only kernel reaches (torch's reduction over the same 1 GiB)
-        for _ in range(2):
-            src.sum()
-        a, b = R.ev(), R.ev()
-        a.record()
-        for _ in range(5):
-            src.sum()
-        b.record()
-        torch.cuda.synchronize()
-        extras["plain_read_torch_sum_GBps_measured"] = round(src.numel() * 4 / (a.elapsed_time(b) * 1e-3 / 5) / 1e9, 1)
-        del src, dst
+        # The ceiling a read-only kernel reaches on this GPU (ekv_probe_read: pages of the K pools of the rotating
+        # copies, 16-byte loads, nothing else), next to the published peak: the whole pool as a linear stream and
+        # in permuted page order, and exactly the pages the sparse decode gathers (same list order, 4 KiB blocks of
+        # (page, KV head)) -- bare, and with the score pass's second lookup and 256 B of output per wavefront.
+        page_bytes = P * d * e
+        if page_bytes in (4096, 8192):
+            n_blocks = st0.inp["k_pool"].shape[0] * Hkv               # (page, KV head) blocks of one pool
+            sink = torch.zeros(64, dtype=torch.int32, device=dev)
+            gperm = torch.Generator(device=dev).manual_seed(123)
+            ids_lin = torch.arange(n_blocks, dtype=torch.int32, device=dev)
+            ids_perm = torch.randperm(n_blocks, generator=gperm, device=dev).to(torch.int32)
+            # blocks of the step's own selection: physical page of every selected logical page, this head's KV head
+            hkv_of = (torch.arange(Hq, device=dev) // w.group).view(1, Hq, 1)
+            sel = st0.page_idx[:, :, :k_pages].long()
+            phys = torch.gather(st0.inp["block_table"].long().unsqueeze(1).expand(B, Hq, M), 2, sel)
+            ids_sel = (phys * Hkv + hkv_of).reshape(-1).to(torch.int32).contiguous()
+            out_probe = torch.empty((ids_sel.numel() + 3) // 4 * 64, dtype=torch.float32, device=dev)
+
+            def probe_rate(ids, lookup=None, out=None, reps=20):
+                nn = ids.numel()
+                us = R.back_to_back(lambda st: ekv.ekv_probe_read(st.inp["k_pool"], ids, nn, page_bytes, sink,
+                                                                  lookup=lookup, out=out), reps=reps, warm=3)
+                return {"us": round(us, 2), "bytes": int(nn * page_bytes), "GBps": round(nn * page_bytes / (us * 1e-6) / 1e9, 1)}
+            extras["read_ceiling"] = {
+                "kernel": "ekv_probe_read (probe_read_kernel): read-only, four pages per wavefront",
+                "whole_pool_linear": probe_rate(ids_lin, reps=8),
+                "whole_pool_permuted_pages": probe_rate(ids_perm, reps=8),
+                "selected_pages_of_the_step": probe_rate(ids_sel),
+                "selected_pages_with_lookup_and_output": probe_rate(ids_sel, lookup=ids_lin, out=out_probe),
+                "note": "the last row has the memory behaviour of the decode's score pass (two dependent lookups, "
+                        "256 B written per 64 tokens) without its arithmetic",
+            }
+            del ids_lin, ids_perm, ids_sel, out_probe, phys, sel
+        # the sparse decode against the CAPACITY of its page lists (max_sel_pages): the same lists of k pages in
+        # buffers of 1x, 2x and 8x that capacity -- the launch is sized by the device-side lengths, not by the capacity
+        by_cap = {}
+        for mult in (1, 2, 8):
+            cap_m = min(M, k_pages * mult)
+            cfg_m = ekv.make_config(B, Hq, Hkv, d, P, w.kv_dtype, w.alpha, w.score_scale, M, cap_m)
+            idx_m = torch.zeros(B, Hq, cap_m, dtype=torch.int32, device=dev)
+            idx_m[:, :, :k_pages] = st0.page_idx[:, :, :k_pages]
+            ws_m = torch.empty(max(256, ekv.ekv_workspace_bytes(cfg_m, ekv.EKV_OP_DECODE_SPARSE)), dtype=torch.uint8, device=dev)
+            by_cap[f"{mult}x"] = round(R.back_to_back(
+                lambda st: ekv.ekv_decode_sparse(cfg_m, st.inp["q"], st.cache(), idx_m, st0.n_sel, st0.out, st0.tau,
+                                                 st0.supp, ws_m), reps=40), 2)
+            del idx_m, ws_m
+        extras["decode_sparse_us_by_list_capacity"] = by_cap
         side = max(10, args.steps // 4)
         if R.fused_append:                                     # the same step with the append as its own launch
             R.fused_append = False
@@ -672,39 +839,7 @@ def main():
 
     # ---------------------------------------------------------------- CPU baseline: the oracle, as it stands
     if not args.no_cpu_baseline:
-        from oracle import entmaxkv_oracle as orc
-        from tests.helpers import to_f64
-        from threadpoolctl import threadpool_limits
-        threadpool_limits(1)                                   # one thread, so that `cores` is exact
-        inp = R.inp
-        all_units = [(b, h) for b in range(B) for h in range(Hq)]
-        units = all_units[: max(1, min(args.cpu_units, len(all_units)))]
-        t_cpu = 0.0
-        kv_key, K64, V64 = None, None, None
-        for (b, hq) in units:
-            hkv = hq // w.group
-            if kv_key != (b, hkv):                             # heads of one group share the K/V conversion
-                K64 = V64 = None
-                k_t, v_t = synth.logical_kv(inp, w, b, hkv)
-                K64, V64 = to_f64(k_t), to_f64(v_t)
-                kv_key = (b, hkv)
-                del k_t, v_t
-            q64 = to_f64(inp["q"][b, hq])
-            t0 = time.perf_counter()
-            orc.decode_step_unit(q64, K64, V64, P, w.alpha, w.score_scale, "topk", w.kv_dtype, k_pages=k_pages)
-            t_cpu += time.perf_counter() - t0
-        K64 = V64 = None
-        per_unit = t_cpu / len(units)
-        try:
-            cores = len(os.sched_getaffinity(0))
-        except AttributeError:
-            cores = os.cpu_count()
-        result["cpu_baseline"] = {
-            "value": round(per_unit * B * Hq * 1e6, 1), "unit": "us", "cores": 1, "host_cores_available": cores,
-            "kind": "oracle",
-            "sample": f"float64 numpy oracle, whole top-k step (stats+score+select+sparse entmax) of {len(units)} of "
-                      f"{B * Hq} (b,head) units, single thread, {t_cpu:.1f} s measured; value = per-unit time x {B * Hq} units",
-        }
+        result["cpu_baseline"] = cpu_baseline(R.inp, w, k_pages, args.cpu_units)
 
     # ---------------------------------------------------------------- the 128K-token batch workload, same steps
     if not args.no_extras and args.workload == "C4":
@@ -725,6 +860,25 @@ def main():
         d3 = w3.batch * w3.n_kv_heads * w3.context * 2 * w3.head_dim * 2
         row["dense_full_GBps"] = round((d3 / 2 + w3.batch * w3.n_q_heads * w3.context * 8) / (us3d * 1e-6) / 1e9, 1)
         row["speedup_topk_vs_dense"] = round(us3d / us3, 2)
+
+        def quality(Rq, step_fn):
+            """delta, rho, R of the selection of `step_fn` against the dense decode (GPU side outputs), copy 0."""
+            s_ = Rq.copies[0]
+            o_f, t_f, n_f = torch.zeros_like(s_.out), torch.zeros_like(s_.tau), torch.zeros_like(s_.supp)
+            ekv.ekv_decode_full(s_.cfg, s_.inp["q"], s_.cache(), o_f, t_f, n_f, Rq.full_ws())
+            step_fn(s_)
+            km_, ks_ = torch.zeros_like(s_.tau), torch.zeros_like(s_.supp)
+            ekv.ekv_decode_sparse(s_.cfg, s_.inp["q"], s_.cache(), s_.page_idx, s_.n_sel, s_.out, s_.tau, s_.supp,
+                                  s_.ws_sparse, extras=ekv.decode_extras(tau_ref=t_f, kept_mass_ref=km_, kept_supp_ref=ks_))
+            torch.cuda.synchronize()
+            return {"pages_per_head_mean": float(s_.n_sel.float().mean()), "pages_per_head_max": int(s_.n_sel.max()),
+                    "coverage": round(float(s_.n_sel.float().mean()) / Rq.w.pages_per_seq, 4),
+                    "support_full_mean": float(n_f.float().mean()),
+                    "delta_mean": round(float((1.0 - km_).mean()), 6),
+                    "rho_mean": round(float((ks_.float() / n_f.float()).mean()), 4),
+                    "R_mean": round(float(((s_.out - o_f).norm(dim=-1) / o_f.norm(dim=-1)).mean()), 6)}
+        # this workload's planted support is clustered (8 spans of 8 tokens per head): selection quality, top-k 2 %
+        row["topk_quality"] = quality(R3, R3.step_topk)
         R3.release()
         del R3
         # at 128K the adaptive selector keeps 5-16 % of the pages of this data: its lists get that room
@@ -737,6 +891,7 @@ def main():
         row["gauss_selected_pages_mean"] = float(R3g.copies[0].n_sel.float().mean())
         row["gauss_overflow_heads"] = int(R3g.copies[0].overflow.sum())
         row["speedup_gauss_vs_dense"] = round(us3d / us3g, 2)
+        row["gauss_quality"] = quality(R3g, R3g.step_gauss)
         result["other_rows"]["C3-128k"] = row
         R3g.release()
         del R3g

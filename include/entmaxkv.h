@@ -229,7 +229,10 @@ ekv_status ekv_select_box_threshold(const ekv_config* cfg, const float* box, con
  *       threshold.  Any value (wrong, infinite, NaN) is safe; tau, supp and out do not depend on it
  *       beyond float32 rounding of the last iterate.
  *   solve_evals int32 [B][Hq]: number of evaluations of the mass sum_j (z_j - tau)_+^beta the solve
- *       took (a measure of what a seed saves). */
+ *       took (a measure of what a seed saves).
+ *   score_pass_only: measurement aid.  Non-zero: only the first pass runs (gather of the K pages, scores and group
+ *       maxima into the workspace); out, tau, supp and every other output are left untouched.  It lets the
+ *       HBM-bound kernel of the decode be timed on its own. */
 typedef struct {
   int32_t* support_tokens;
   int32_t support_cap;
@@ -239,6 +242,7 @@ typedef struct {
   float* lse;
   const float* tau_seed;
   int32_t* solve_evals;
+  int32_t score_pass_only;
 } ekv_decode_extras;
 
 /* a7 -- sparse alpha-entmax attention over the selected pages (Sec. 4.1, Sec. 4.4).

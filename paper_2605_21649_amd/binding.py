@@ -47,7 +47,7 @@ class ekv_stats_view(ctypes.Structure):
 class ekv_decode_extras(ctypes.Structure):
     _fields_ = [("support_tokens", c_void_p), ("support_cap", c_int32), ("tau_ref", c_void_p),
                 ("kept_mass_ref", c_void_p), ("kept_supp_ref", c_void_p), ("lse", c_void_p),
-                ("tau_seed", c_void_p), ("solve_evals", c_void_p)]
+                ("tau_seed", c_void_p), ("solve_evals", c_void_p), ("score_pass_only", c_int32)]
 
 
 class EkvError(RuntimeError):
@@ -144,10 +144,10 @@ def stats_view(box, gauss, box8=None):
 
 
 def decode_extras(support_tokens=None, tau_ref=None, kept_mass_ref=None, kept_supp_ref=None, lse=None,
-                  tau_seed=None, solve_evals=None):
+                  tau_seed=None, solve_evals=None, score_pass_only=False):
     cap = support_tokens.shape[-1] if support_tokens is not None else 0
     return ekv_decode_extras(_ptr(support_tokens), cap, _ptr(tau_ref), _ptr(kept_mass_ref), _ptr(kept_supp_ref),
-                             _ptr(lse), _ptr(tau_seed), _ptr(solve_evals))
+                             _ptr(lse), _ptr(tau_seed), _ptr(solve_evals), 1 if score_pass_only else 0)
 
 
 def ekv_workspace_bytes(cfg, op):

@@ -20,6 +20,7 @@ constexpr int kScoreThreads = 256;
 constexpr int kSolveThreads = 1024;
 constexpr int kSolveWaves = kSolveThreads / 64;
 constexpr int kListCap = 4096;          // candidate entries held in LDS (u, pos, row): 48 KB
+constexpr int kPreR = kPreGroups / kSolveThreads;    // group maxima a thread of the solve holds at most
 constexpr int kRoundLoads = 16;         // loads per lane and compaction round
 constexpr int kRoundTokens = kSolveThreads * kRoundLoads;
 
@@ -70,6 +71,23 @@ __device__ __forceinline__ int unit_slots(const ScoreArgs& A, int u) {
 template <int THREADS, typename F>
 __device__ __forceinline__ void block_exclusive_prefix(int U, F&& count_of, int* pre, int* wsum) {
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  if (U <= THREADS) {
+    // one unit per thread (the usual launch): a wavefront scan, the wavefront totals, two barriers; every workgroup
+    // of the launch runs this before its first load, so it is kept to a few dozen instructions
+    const int c = tid < U ? count_of(tid) : 0;
+    int inc = c;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) { const int t = __shfl_up(inc, d); if (lane >= d) inc += t; }
+    if (lane == 63) wsum[w] = inc;
+    __syncthreads();
+    int base = inc - c;
+#pragma unroll
+    for (int i = 0; i < THREADS / 64; ++i) base += i < w ? wsum[i] : 0;
+    if (tid < U) pre[tid] = base;
+    if (tid == U - 1) pre[U] = base + c;
+    __syncthreads();
+    return;
+  }
   for (int u = tid; u < U; u += THREADS) pre[u] = count_of(u);
   __syncthreads();
   const int upt = (U + THREADS - 1) / THREADS;          // a contiguous segment per thread
@@ -100,10 +118,12 @@ struct WaveItems { int begin, end, unit; };
 template <typename P>
 __device__ __forceinline__ WaveItems wave_item_range(const P pre, int U, int w) {
   const int total = uniform(pre[U]);
-  const uint32_t W = gridDim.x * kScoreWaves, gw = blockIdx.x * kScoreWaves + w;
+  const int W = gridDim.x * kScoreWaves, gw = blockIdx.x * kScoreWaves + w;
+  // balanced contiguous partition: the first total % W wavefronts take one item more
+  const int per = total / W, rem = total - per * W;
   WaveItems r;
-  r.begin = (int)((uint64_t)gw * (uint32_t)total / W);
-  r.end = (int)((uint64_t)(gw + 1) * (uint32_t)total / W);
+  r.begin = gw * per + min(gw, rem);
+  r.end = r.begin + per + (gw < rem ? 1 : 0);
   int lo = 0, hi = U;                                   // pre[lo] <= begin < pre[hi] whenever begin < total
   while (hi - lo > 1) {
     const int mid = (lo + hi) >> 1;
@@ -383,6 +403,7 @@ __global__ __launch_bounds__(kFilterThreads) void filter_level_kernel(const Filt
   const int row = blockIdx.x, tid = threadIdx.x;
   const int gp = pmax_pages(A.P);
   const int n_chunks = (filter_n_slots<DENSE>(A, row) + gp - 1) / gp;
+  if (n_chunks <= kPreGroups) return;                         // short row: the solve reads its group maxima itself
   const float* pm = A.pmax + (size_t)row * A.n_chunks_max;
   float mx = -INFINITY;
   for (int i0 = 0; i0 < n_chunks; i0 += kFilterThreads * 16) {
@@ -434,7 +455,7 @@ __global__ __launch_bounds__(kFilterThreads) void filter_compact_kernel(const Fi
   const int n_slots = filter_n_slots<DENSE>(A, row);
   const int n_cand = n_slots * A.P, n_chunks = (n_slots + gp - 1) / gp;
   const int c0 = slice * kFilterSliceChunks;
-  if (c0 >= n_chunks) return;
+  if (c0 >= n_chunks || n_chunks <= kPreGroups) return;      // past the row's end, or a short row (see the level pass)
   const float zmax = A.frow[2 * row], thr = A.frow[2 * row + 1];
   const float* zr = A.zbuf + (size_t)row * A.zstride;
   const float* pm = A.pmax + (size_t)row * A.n_chunks_max;
@@ -706,13 +727,30 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
   // warm start (optional): requested with the first loads, used once zmax is known
   const float seed_z = A.ex.tau_seed != nullptr ? A.ex.tau_seed[bh] : NAN;
   float zmax, thr_f = 0.f;
-  float mypm = -INFINITY;                   // this thread's group maximum (rows of at most 1024 groups)
-  if (A.fcount != nullptr) {
+  // Rows of at most kPreGroups groups: thread t holds the maxima of the gpt consecutive groups gpt*t .. gpt*t+gpt-1
+  // (gpt = 1 up to 1024 groups)
+  float mypm[kPreR];
+#pragma unroll
+  for (int k = 0; k < kPreR; ++k) mypm[k] = -INFINITY;
+  const bool pre = n_chunks <= kPreGroups;
+  const int gpt = (n_chunks + kSolveThreads - 1) / kSolveThreads;
+  // The filter passes are launched when the list CAPACITY allows longer rows than that; whether this row took them
+  // is decided here, from its actual length (they leave shorter rows alone).
+  const bool filt = A.fcount != nullptr && !pre;
+  if (filt) {
     zmax = n_cand > 0 ? A.frow[2 * bh] : -INFINITY;
     thr_f = n_cand > 0 ? A.frow[2 * bh + 1] : 0.f;
+  } else if (pre) {
+    float mx = -INFINITY;
+#pragma unroll
+    for (int k = 0; k < kPreR; ++k) {
+      const int g = gpt * tid + k;
+      if (k < gpt && g < n_chunks) { mypm[k] = pm[g]; mx = fmaxf(mx, mypm[k]); }
+    }
+    zmax = block_max(mx, sh.red1);
   } else {
     float mx = -INFINITY;
-    for (int i = tid; i < n_chunks; i += kSolveThreads) { mypm = pm[i]; mx = fmaxf(mx, mypm); }
+    for (int i = tid; i < n_chunks; i += kSolveThreads) mx = fmaxf(mx, pm[i]);
     zmax = block_max(mx, sh.red1);
   }
   if (!(zmax > -INFINITY)) {                // no valid candidate at all
@@ -733,24 +771,28 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
   // a lower bound of the mass at every slice boundary (an entry of slice j lies at least j-i slices above
   // boundary i), hence a tighter valid threshold: it becomes the starting point of the solve, and, if the
   // candidates did not fit in LDS, the threshold of one more compaction pass.
-  float thr = A.fcount != nullptr ? thr_f : zmax - 1.0f - 4e-6f * fmaxf(1.f, fabsf(zmax));
-  // Short rows: the group maxima (one per thread) give a first certified bound of tau -- every group
+  float thr = filt ? thr_f : zmax - 1.0f - 4e-6f * fmaxf(1.f, fabsf(zmax));
+  // Short rows: the group maxima (held by the threads) give a first certified bound of tau -- every group
   // counted in a bin holds at least its maximum there -- and only the groups whose maximum exceeds it are
   // read at all: their scores are fetched through an ordered list of group numbers, so that a row of any
-  // length up to 1024 groups normally takes one round of loads.
-  const bool pre = A.fcount == nullptr && n_chunks <= kSolveThreads;
+  // length up to kPreGroups groups normally takes one round of loads.
   if (pre) {
     const float step = (zmax - thr) * (1.0f / 64.0f), inv_step = 64.0f / (zmax - thr);
     if (tid < 64) sh.hist[tid] = 0;
     __syncthreads();
-    if (mypm > thr) atomicAdd(&sh.hist[min(63, (int)((mypm - thr) * inv_step))], 1);
+#pragma unroll
+    for (int k = 0; k < kPreR; ++k)
+      if (mypm[k] > thr) atomicAdd(&sh.hist[min(63, (int)((mypm[k] - thr) * inv_step))], 1);
     __syncthreads();
     thr += (float)certified_level<64>(sh.hist, step, beta, ibeta, sh.flags) * step;
     if (A.ex.tau_seed != nullptr) {
       // A seed above that bound becomes the candidate threshold if the group maxima alone already put a
       // mass of 1 above it (then the full mass there is >= 1, i.e. the seed is a lower bound of tau).
       const bool try_seed = seed_z > thr && seed_z < zmax;            // false for NaN
-      float f = (try_seed && mypm > seed_z) ? pow_beta(mypm - seed_z, beta, ibeta) : 0.f;
+      float f = 0.f;
+#pragma unroll
+      for (int k = 0; k < kPreR; ++k)
+        if (try_seed && mypm[k] > seed_z) f += pow_beta(mypm[k] - seed_z, beta, ibeta);
       f = block_sum(f, sh.red1);
       if (try_seed && f >= 1.0001f) thr = seed_z;
     }
@@ -764,7 +806,7 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
   int n_list = 0, parity = 0;
   bool in_lds = true;
   bool prefilled = false;
-  if (A.fcount != nullptr) {
+  if (filt) {
     // survivors of the filter passes: gather the per-slice lists, in slice order, if they fit
     const int n_slices = (n_chunks + kFilterSliceChunks - 1) / kFilterSliceChunks;
     const int cs = tid < n_slices ? A.fcount[(size_t)bh * A.n_slices_max + tid] : 0;
@@ -792,15 +834,22 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
     __syncthreads();
   }
   if (pre) {
+    // ordered list of the groups above the bound: thread t owns consecutive groups, so (thread, k) order is group order
     int* glist = reinterpret_cast<int*>(sh.list_row);        // free until the solve is done
-    const bool gp = mypm > thr;
-    const uint64_t gmk = __ballot(gp);
-    if (lane == 0) sh.wcount[parity][w] = __popcll(gmk);
+    int mine = 0;
+#pragma unroll
+    for (int k = 0; k < kPreR; ++k) mine += mypm[k] > thr ? 1 : 0;
+    int inc = mine;
+#pragma unroll
+    for (int dlt = 1; dlt < 64; dlt <<= 1) { const int t = __shfl_up(inc, dlt); if (lane >= dlt) inc += t; }
+    if (lane == 63) sh.wcount[parity][w] = inc;
     __syncthreads();
-    int goff = 0, n_pass = 0;
+    int goff = inc - mine, n_pass = 0;
     for (int i = 0; i < kSolveWaves; ++i) { const int ci = sh.wcount[parity][i]; if (i < w) goff += ci; n_pass += ci; }
     parity ^= 1;
-    if (gp) glist[goff + __popcll(gmk & lt)] = tid;
+#pragma unroll
+    for (int k = 0; k < kPreR; ++k)
+      if (mypm[k] > thr) glist[goff++] = gpt * tid + k;
     n_pass = __builtin_amdgcn_readfirstlane(n_pass);
     __syncthreads();
     // wavefront w of a round owns `per` consecutive list entries: (round, w, load, lane) is candidate order
@@ -1350,11 +1399,12 @@ static int device_compute_units() {
   }
   return cus[dev];
 }
-// Workgroups per compute unit in a pass-1 launch.  Eight are resident at a time; launching up to four times that
-// (when there is that much work) measured 5 % faster than a grid of resident workgroups only -- a wavefront that
-// starts fresh streams better than one that loops -- while workgroups without work cost about half a microsecond
-// per thousand.  Every workgroup reads the U lengths, so launches with many units get fewer.
-static int score_wgs_per_cu(int U) { return U <= 64 ? 32 : U <= 256 ? 16 : 8; }
+// Workgroups per compute unit in a pass-1 launch.  Eight are resident at a time; launching twice that (when there
+// is that much work) measured 3-5 % faster than a grid of resident workgroups only -- a wavefront that starts fresh
+// streams better than one that loops -- while workgroups that find no work cost about half a microsecond per
+// thousand, which bounds what a list capacity far above the lists' lengths can cost.  Every workgroup reads the U
+// lengths, so launches with many units get fewer.
+static int score_wgs_per_cu(int U) { return U <= 256 ? 16 : 8; }
 
 template <int G, int MODE>
 static void launch_scores(const Dims& dm, ScoreArgs sa, int32_t* pre_ws, hipStream_t st) {
@@ -1390,7 +1440,7 @@ size_t decode_ws_carve(const Dims& dm, bool dense, void* base, DecodeWorkspace* 
   const size_t zstride = slots * dm.P;
   const int n_chunks_max = (int)((slots + pmax_pages(dm.P) - 1) / pmax_pages(dm.P));
   size_t n_slices = ((size_t)n_chunks_max + kFilterSliceChunks - 1) / kFilterSliceChunks;
-  if (zstride < (size_t)kFilterMinTokens || n_slices > (size_t)kFilterMaxSlices) n_slices = 0;
+  if (n_chunks_max <= kPreGroups || n_slices > (size_t)kFilterMaxSlices) n_slices = 0;
   size_t off = 0;
   auto take = [&](size_t bytes) { const size_t o = off; off += (bytes + 255) & ~(size_t)255; return o; };
   const size_t o_z = take(rows * zstride * sizeof(float));
@@ -1440,6 +1490,7 @@ void launch_decode(const Dims& dm, bool dense, bool grouped, const void* q, cons
       case 4: launch_scores<4, kAllPages>(dm, sa, ws.unit_pre, st); break;
       default: launch_scores<8, kAllPages>(dm, sa, ws.unit_pre, st); break;
     }
+    if (ex.score_pass_only) return;
     if (ws.fcount != nullptr) {
       hipLaunchKernelGGL((filter_level_kernel<true>), dim3(dm.B * dm.Hq), fblock, 0, st, fa);
       hipLaunchKernelGGL((filter_compact_kernel<true>), fgrid, fblock, 0, st, fa);
@@ -1458,6 +1509,7 @@ void launch_decode(const Dims& dm, bool dense, bool grouped, const void* q, cons
       sa.U = dm.B * dm.Hq;
       launch_scores<1, kPerHead>(dm, sa, ws.unit_pre, st);
     }
+    if (ex.score_pass_only) return;
     if (ws.fcount != nullptr) {
       hipLaunchKernelGGL((filter_level_kernel<false>), dim3(dm.B * dm.Hq), fblock, 0, st, fa);
       hipLaunchKernelGGL((filter_compact_kernel<false>), fgrid, fblock, 0, st, fa);

@@ -22,7 +22,7 @@ __host__ __device__ inline int pmax_pages(int P) { return P >= 64 ? 1 : 64 / P; 
 
 // Long rows are pre-filtered by multi-workgroup passes before the single-workgroup solve.
 constexpr int kFilterSliceChunks = 512;   // pmax entries (groups of <= 64 tokens) per workgroup of the filter
-constexpr int kFilterMinTokens = 65536;   // rows that can be at least this long take the filter passes
+constexpr int kPreGroups = 4096;          // rows of at most this many groups are solved without the filter passes
 constexpr int kFilterMaxSlices = 1024;    // ... unless they would need more slices than this
 constexpr int kFilterSliceCap = 4096;     // candidates kept per slice (the solve holds this many in LDS)
 

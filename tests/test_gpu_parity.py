@@ -633,18 +633,26 @@ LONG = [synth.C2.scaled(name="C2-long-bf16", context=100000, ragged=7, n_q_heads
         # nearly flat scores: more than 4096 tokens above the certified bound -> the solve cannot take the
         # filtered lists and falls back to streaming the row from that bound
         synth.C1.scaled(name="C1-long-flat", context=66000, n_planted=0, scale=0.02 / math.sqrt(128.0),
+                        n_q_heads=2, n_kv_heads=2),
+        # rows of more than 4096 groups of 64 tokens: these take the multi-workgroup filter passes (the rows above
+        # are solved from the group maxima by one workgroup, two maxima per thread)
+        synth.C2.scaled(name="C2-filter-bf16", context=300000, ragged=11, n_q_heads=4, n_kv_heads=2),
+        synth.C1.scaled(name="C1-filter-f32", context=270000, ragged=3, n_q_heads=2, n_kv_heads=2,
+                        scale=1.0 / math.sqrt(128.0)),
+        synth.C1.scaled(name="C1-filter-flat", context=264000, n_planted=0, scale=0.02 / math.sqrt(128.0),
                         n_q_heads=2, n_kv_heads=2)]
 
 
 @pytest.mark.parametrize("w", LONG, ids=[w.name for w in LONG])
 def test_decode_long_rows_take_the_filter_passes(w):
-    """Rows of 65536 candidates or more are pre-filtered by the multi-workgroup passes (dense, and sparse
-    with a large selection); results must meet the same bars as the short-row path."""
+    """Long rows: up to 4096 groups (262 144 tokens) one workgroup solves them from the group maxima, several per
+    thread; longer ones are pre-filtered by the multi-workgroup passes (dense, and sparse with a large selection).
+    Results must meet the same bars as the short-row path."""
     inp = get_inputs(w)
     M = w.pages_per_seq
     n = w.context - w.ragged
     n_pages = -(-n // w.page_size)
-    cap = min(M, -(-66000 // w.page_size))                 # a selection of >= 66000 tokens
+    cap = min(M, -(-(263000 if "filter" in w.name else 66000) // w.page_size))   # a selection of that many tokens
     st = DeviceState(w, inp, cap=cap)
     dev = st.box.device
     supp_tok = torch.full((w.batch, w.n_q_heads, 8192), -1, device=dev, dtype=torch.int32)
@@ -1367,3 +1375,49 @@ def test_select_gauss_many_short_rows():
             ok, bad = sets_equal_up_to_cut(got, pages, g, cut, 1e-5 * max(1.0, abs(cut)))
             assert ok, (b, hq, bad[:5], len(pages), len(got))
             assert np.all(np.diff(got) > 0)
+
+
+# ---------------------------------------------------------------------------- list capacity
+def test_decode_does_not_depend_on_the_capacity_of_the_page_lists():
+    """The same page lists in buffers of 1x, 3x and 8x their length (max_sel_pages): the launches are sized by the
+    device-side lengths, so every output is identical bit for bit -- per-head lists, one list per KV head, softmax
+    over the lists -- and equal to the oracle's decode of those lists.  Ragged lengths, one empty list."""
+    w = W2
+    inp = get_inputs(w)
+    k = 50
+    dev = torch.device("cuda")
+    rng = np.random.default_rng(21)
+    n_pages = -(-int(inp["seq_lens"][0]) // w.page_size)
+    lens = rng.integers(1, k + 1, size=(w.batch, w.n_q_heads)); lens[0, 3] = 0; lens[0, 0] = k
+    lists = {(b, h): np.sort(rng.choice(n_pages, lens[b, h], replace=False)) for b in range(w.batch) for h in range(w.n_q_heads)}
+    results = []
+    for mult in (1, 3, 8):
+        cap = k * mult
+        st = DeviceState(w, inp, cap=cap)
+        st.page_idx.fill_(n_pages + 7)                         # slots past the lengths hold an out-of-range page
+        for (b, h), pg in lists.items():
+            st.page_idx[b, h, : len(pg)] = torch.from_numpy(pg.astype(np.int32)).to(dev)
+        st.n_sel.copy_(torch.from_numpy(lens.astype(np.int32)))
+        toks = torch.full((w.batch, w.n_q_heads, 512), -1, device=dev, dtype=torch.int32)
+        ekv.ekv_decode_sparse(st.cfg, st.inp["q"], st.cache(), st.page_idx, st.n_sel, st.out, st.tau, st.supp,
+                              st.workspace(ekv.EKV_OP_DECODE_SPARSE), extras=ekv.decode_extras(support_tokens=toks))
+        r = [st.out.clone(), st.tau.clone(), st.supp.clone(), toks.clone()]
+        # one list per KV head: the lists of the group's first head
+        g_idx = st.page_idx[:, :: w.group].contiguous(); g_n = st.n_sel[:, :: w.group].contiguous()
+        ekv.ekv_decode_sparse_group(st.cfg, st.inp["q"], st.cache(), g_idx, g_n, st.out, st.tau, st.supp,
+                                    st.workspace(ekv.EKV_OP_DECODE_SPARSE))
+        r += [st.out.clone(), st.tau.clone(), st.supp.clone()]
+        lse = torch.zeros_like(st.tau)
+        ekv.ekv_decode_sparse_softmax(st.cfg, st.inp["q"], st.cache(), st.page_idx, st.n_sel, st.out, lse,
+                                      st.workspace(ekv.EKV_OP_DECODE_SPARSE_SOFTMAX))
+        r += [st.out.clone(), lse.clone()]
+        torch.cuda.synchronize()
+        results.append(r)
+    for other in results[1:]:
+        for i, (a, b_) in enumerate(zip(results[0], other)):
+            assert torch.equal(a.view(torch.uint8), b_.view(torch.uint8)), i
+    out, tau, supp, toks = [t.cpu().numpy() for t in results[0][:4]]
+    assert supp[0, 3] == 0 and np.isposinf(tau[0, 3]) and not out[0, 3].any()
+    for (b, hq) in [(0, 0), (0, 7), (0, 30)]:
+        q, K, V = unit_kv(inp, w, b, hq)
+        check_decode_of_gpu_list(w, q, K, V, lists[(b, hq)], out[b, hq], tau[b, hq], supp[b, hq], toks[b, hq])
