@@ -782,7 +782,7 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
     __syncthreads();
 #pragma unroll
     for (int k = 0; k < kPreR; ++k)
-      if (mypm[k] > thr) atomicAdd(&sh.hist[min(63, (int)((mypm[k] - thr) * inv_step))], 1);
+      if (k < gpt && mypm[k] > thr) atomicAdd(&sh.hist[min(63, (int)((mypm[k] - thr) * inv_step))], 1);
     __syncthreads();
     thr += (float)certified_level<64>(sh.hist, step, beta, ibeta, sh.flags) * step;
     if (A.ex.tau_seed != nullptr) {
@@ -836,20 +836,31 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
   if (pre) {
     // ordered list of the groups above the bound: thread t owns consecutive groups, so (thread, k) order is group order
     int* glist = reinterpret_cast<int*>(sh.list_row);        // free until the solve is done
-    int mine = 0;
+    int goff, n_pass = 0;
+    if (gpt == 1) {                                          // one group per thread (rows up to 65 536 tokens): a ballot
+      const bool gp = mypm[0] > thr;
+      const uint64_t gmk = __ballot(gp);
+      if (lane == 0) sh.wcount[parity][w] = __popcll(gmk);
+      __syncthreads();
+      goff = 0;
+      for (int i = 0; i < kSolveWaves; ++i) { const int ci = sh.wcount[parity][i]; if (i < w) goff += ci; n_pass += ci; }
+      if (gp) glist[goff + __popcll(gmk & lt)] = tid;
+    } else {
+      int mine = 0;
 #pragma unroll
-    for (int k = 0; k < kPreR; ++k) mine += mypm[k] > thr ? 1 : 0;
-    int inc = mine;
+      for (int k = 0; k < kPreR; ++k) mine += mypm[k] > thr ? 1 : 0;
+      int inc = mine;
 #pragma unroll
-    for (int dlt = 1; dlt < 64; dlt <<= 1) { const int t = __shfl_up(inc, dlt); if (lane >= dlt) inc += t; }
-    if (lane == 63) sh.wcount[parity][w] = inc;
-    __syncthreads();
-    int goff = inc - mine, n_pass = 0;
-    for (int i = 0; i < kSolveWaves; ++i) { const int ci = sh.wcount[parity][i]; if (i < w) goff += ci; n_pass += ci; }
+      for (int dlt = 1; dlt < 64; dlt <<= 1) { const int t = __shfl_up(inc, dlt); if (lane >= dlt) inc += t; }
+      if (lane == 63) sh.wcount[parity][w] = inc;
+      __syncthreads();
+      goff = inc - mine;
+      for (int i = 0; i < kSolveWaves; ++i) { const int ci = sh.wcount[parity][i]; if (i < w) goff += ci; n_pass += ci; }
+#pragma unroll
+      for (int k = 0; k < kPreR; ++k)
+        if (mypm[k] > thr) glist[goff++] = gpt * tid + k;
+    }
     parity ^= 1;
-#pragma unroll
-    for (int k = 0; k < kPreR; ++k)
-      if (mypm[k] > thr) glist[goff++] = gpt * tid + k;
     n_pass = __builtin_amdgcn_readfirstlane(n_pass);
     __syncthreads();
     // wavefront w of a round owns `per` consecutive list entries: (round, w, load, lane) is candidate order
