@@ -66,46 +66,6 @@ __device__ __forceinline__ int unit_slots(const ScoreArgs& A, int u) {
   return clampi(A.n_sel[u], 0, A.cap);
 }
 
-// Exclusive prefix over `U` counts produced by `count_of(u)`, written to pre[0..U] (pre[U] = total); `wsum` holds
-// one int per wavefront.  Called by every thread of the workgroup.
-template <int THREADS, typename F>
-__device__ __forceinline__ void block_exclusive_prefix(int U, F&& count_of, int* pre, int* wsum) {
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  if (U <= THREADS) {
-    // one unit per thread (the usual launch): a wavefront scan, the wavefront totals, two barriers; every workgroup
-    // of the launch runs this before its first load, so it is kept to a few dozen instructions
-    const int c = tid < U ? count_of(tid) : 0;
-    int inc = c;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) { const int t = __shfl_up(inc, d); if (lane >= d) inc += t; }
-    if (lane == 63) wsum[w] = inc;
-    __syncthreads();
-    int base = inc - c;
-#pragma unroll
-    for (int i = 0; i < THREADS / 64; ++i) base += i < w ? wsum[i] : 0;
-    if (tid < U) pre[tid] = base;
-    if (tid == U - 1) pre[U] = base + c;
-    __syncthreads();
-    return;
-  }
-  for (int u = tid; u < U; u += THREADS) pre[u] = count_of(u);
-  __syncthreads();
-  const int upt = (U + THREADS - 1) / THREADS;          // a contiguous segment per thread
-  const int s0 = min(tid * upt, U), s1 = min(s0 + upt, U);
-  int s = 0;
-  for (int u = s0; u < s1; ++u) s += pre[u];
-  int inc = s;
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) { const int t = __shfl_up(inc, d); if (lane >= d) inc += t; }
-  if (lane == 63) wsum[w] = inc;
-  __syncthreads();
-  int base = inc - s;
-  for (int i = 0; i < w; ++i) base += wsum[i];
-  for (int u = s0; u < s1; ++u) { const int c = pre[u]; pre[u] = base; base += c; }
-  if (tid == THREADS - 1) pre[U] = base;                // the last segment ends at U
-  __syncthreads();
-}
-
 template <int MODE>
 __global__ __launch_bounds__(1024) void unit_prefix_kernel(const ScoreArgs A, int32_t* pre_out) {
   __shared__ int wsum[16];
