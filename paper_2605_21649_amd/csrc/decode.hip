@@ -248,7 +248,6 @@ void decode_scores_mfma_kernel(const ScoreArgs A) {
     };
     auto consume = [&](int ck, const uint4 (&a)[4]) {
       const int pg = ck / KEEP, t = ck % KEEP;
-      if (ck % 4 == 0) open_item(pg);
       const int slot = slot0 + pg % GP;
       const bool slot_ok = slot < n_slots;             // wave-uniform
       const int tok0 = __builtin_amdgcn_readlane(l_lp, pg) * PT + 16 * t + j;
@@ -262,7 +261,8 @@ void decode_scores_mfma_kernel(const ScoreArgs A) {
           const f32x4_t zero = {0.f, 0.f, 0.f, 0.f};
           const f32x4_t c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a[s]),
                                                                     __builtin_bit_cast(bf16x8_t, bq[cs]), zero, 0, 0, 0);
-          float v = kq == 0 ? c[0] : kq == 1 ? c[1] : kq == 2 ? c[2] : c[3];
+          const float v01 = (kq & 1) ? c[1] : c[0], v23 = (kq & 1) ? c[3] : c[2];   // c[kq] in two selects
+          float v = (kq & 2) ? v23 : v01;
           v += dpp_move<0xB1>(v);
           v += dpp_move<0x4E>(v);
           const float z = valid ? A.zscale * v : -INFINITY;
@@ -289,17 +289,30 @@ void decode_scores_mfma_kernel(const ScoreArgs A) {
       }
     };
 
-    // two chunks in flight, alternating register sets (n_ck is a multiple of 4)
+    // two chunks in flight, alternating register sets (n_ck is a multiple of 4).  Loads return in issue order, so the
+    // query of a new item (every fourth chunk) is requested BEFORE the next chunk's K loads: waiting for it then
+    // leaves those in flight.
+    // Every request in the loop is unconditional (a load behind a branch makes the wait at the join drain the queue);
+    // the last pair of chunks is taken after the loop.
     uint4 a0[4], a1[4];
     request(0, a0);
-    for (int ck = 0; ck < n_ck; ck += 2) {
+    int ck = 0;
+    for (; ck + 2 < n_ck; ck += 2) {
+      if (ck % 4 == 0) open_item(ck / KEEP);
+      __builtin_amdgcn_sched_barrier(0);
       request(ck + 1, a1);
       __builtin_amdgcn_sched_barrier(0);
       consume(ck, a0);
-      if (ck + 2 < n_ck) request(ck + 2, a0);
+      request(ck + 2, a0);
       __builtin_amdgcn_sched_barrier(0);
       consume(ck + 1, a1);
     }
+    if (ck % 4 == 0) open_item(ck / KEEP);
+    __builtin_amdgcn_sched_barrier(0);
+    request(ck + 1, a1);
+    __builtin_amdgcn_sched_barrier(0);
+    consume(ck, a0);
+    consume(ck + 1, a1);
   }
 }
 
