@@ -571,6 +571,14 @@ def main():
                         "256 B written per 64 tokens) without its arithmetic",
             }
             del ids_lin, ids_perm, ids_sel, out_probe, phys, sel
+        # Fusing two dependent stages into one launch needs a hand-off between workgroups inside the kernel; what
+        # that costs here against a plain launch of the same shape (512 workgroups x 4 KiB: the top-k histogram
+        # kernel's shape), by mechanism (ekv_probe_handoff)
+        hd = torch.zeros(512 * 1024, dtype=torch.float32, device=dev)
+        hc = torch.zeros(1, dtype=torch.int32, device=dev); ho = torch.zeros(1, dtype=torch.float32, device=dev)
+        extras["handoff_inside_a_launch_us"] = {
+            name: round(R.back_to_back(lambda st: ekv.ekv_probe_handoff(hd, hc, ho, 512, mode), reps=30, warm=3), 2)
+            for mode, name in ((0, "no_handoff"), (1, "device_fence_last_arriver"), (2, "write_through_atomics_last_arriver"))}
         # the sparse decode against the CAPACITY of its page lists (max_sel_pages): the same lists of k pages in
         # buffers of 1x, 2x and 8x that capacity -- the launch is sized by the device-side lengths, not by the capacity
         by_cap = {}

@@ -308,6 +308,16 @@ ekv_status ekv_decode_sparse_softmax(const ekv_config* cfg, const void* q,
 ekv_status ekv_probe_read(const void* base, const int32_t* page_ids, const int32_t* lookup, int32_t n_pages,
                           int32_t page_bytes, float* out, void* sink, void* stream);
 
+/* Measurement aid, no part of the method: what handing data from workgroup to workgroup inside ONE launch costs on
+ * the GPU at hand, compared with a kernel boundary -- the question behind every "fuse these two dependent stages"
+ * idea.  n_workgroups (2..65536) workgroups write 4 KiB each into `data` (device float [n_workgroups * 1024]); mode 0:
+ * nothing more; mode 1: device-scope fence + acquire-release counter, the last workgroup to arrive fences and reads
+ * 8 KiB written by others; mode 2: no fences, device-scope atomic (write-through) stores, relaxed counter, atomic
+ * loads by the last arriver.  `counter`: device uint32, zero before the first call (each launch leaves it at zero);
+ * `out`: device float, receives a checksum (accumulated).  Asynchronous on `stream`. */
+ekv_status ekv_probe_handoff(float* data, uint32_t* counter, float* out, int32_t n_workgroups, int32_t mode,
+                             void* stream);
+
 /* Bytes of workspace `op` needs under cfg (host computation, no HIP calls). */
 ekv_status ekv_workspace_bytes(const ekv_config* cfg, int32_t op, size_t* bytes);
 

@@ -25,8 +25,8 @@ EXPORTS = ["ekv_stats_build", "ekv_stats_append", "ekv_score_pages", "ekv_append
            "ekv_select_gauss",
            "ekv_select_box_threshold", "ekv_decode_sparse", "ekv_decode_sparse_group", "ekv_decode_full",
            "ekv_decode_sparse_softmax", "ekv_workspace_bytes", "ekv_probe_read", "ekv_decode_sparse_static",
-           "ekv_status_string", "ekv_last_hip_error", "ekv_version"]
-_STATUS_CALLS = EXPORTS[:14]      # entry points that return ekv_status
+           "ekv_probe_handoff", "ekv_status_string", "ekv_last_hip_error", "ekv_version"]
+_STATUS_CALLS = EXPORTS[:15]      # entry points that return ekv_status
 
 
 class ekv_config(ctypes.Structure):
@@ -94,6 +94,7 @@ def load_library():
     lib.ekv_select_box_threshold.argtypes = [P(ekv_config), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                              c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
     lib.ekv_probe_read.argtypes = [c_void_p, c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p]
+    lib.ekv_probe_handoff.argtypes = [c_void_p, c_void_p, c_void_p, c_int32, c_int32, c_void_p]
     for name in _STATUS_CALLS:
         getattr(lib, name).restype = c_int32
     _lib = lib
@@ -237,3 +238,7 @@ def ekv_decode_sparse_static(cfg, q, cache, page_idx, n_sel, out, tau, supp, ext
     ex = byref(extras) if extras is not None else None
     _check(load_library().ekv_decode_sparse_static(byref(cfg), _ptr(q), byref(cache), _ptr(page_idx), _ptr(n_sel),
                                                    _ptr(out), _ptr(tau), _ptr(supp), ex, _stream(stream)))
+
+
+def ekv_probe_handoff(data, counter, out, n_workgroups, mode, stream=None):
+    _check(load_library().ekv_probe_handoff(_ptr(data), _ptr(counter), _ptr(out), n_workgroups, mode, _stream(stream)))

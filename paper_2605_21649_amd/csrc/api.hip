@@ -366,4 +366,12 @@ ekv_status ekv_probe_read(const void* base, const int32_t* page_ids, const int32
   return finish((hipStream_t)stream);
 }
 
+ekv_status ekv_probe_handoff(float* data, uint32_t* counter, float* out, int32_t n_workgroups, int32_t mode,
+                             void* stream) {
+  if (!ok_ptr4(data) || !ok_ptr4(counter) || !ok_ptr4(out)) return EKV_ERR_INVALID_ARG;
+  if (n_workgroups < 2 || n_workgroups > 65536 || mode < 0 || mode > 2) return EKV_ERR_INVALID_ARG;
+  launch_probe_handoff(data, counter, out, n_workgroups, mode, (hipStream_t)stream);
+  return finish((hipStream_t)stream);
+}
+
 }  // extern "C"

@@ -72,6 +72,8 @@ void launch_select_box_threshold(const Dims& dm, const float* box, const int32_t
 void launch_probe_read(const void* base, const int32_t* page_ids, const int32_t* lookup, int n_pages, int page_bytes,
                        float* out, uint32_t* sink, hipStream_t st);
 
+void launch_probe_handoff(float* data, uint32_t* counter, float* out, int n_workgroups, int mode, hipStream_t st);
+
 size_t select_topk_ws_bytes(const Dims& dm);
 size_t select_box_ws_bytes(const Dims& dm);
 bool select_box_supported(const Dims& dm);

@@ -52,4 +52,47 @@ void launch_probe_read(const void* base, const int32_t* page_ids, const int32_t*
     hipLaunchKernelGGL((probe_read_kernel<8>), grid, block, 0, st, (const uint4*)base, page_ids, lookup, n_pages, out, sink);
 }
 
+// Hand-off probe: what it costs to pass data between workgroups INSIDE one launch (the alternative to a kernel
+// boundary when two dependent stages are to be fused).  Every workgroup writes 4 KiB; then, by `mode`:
+//   0  nothing more (the reference);
+//   1  device-scope fence, an acquire-release counter, the last workgroup to arrive fences and reads 8 KiB that
+//      other workgroups wrote (the classic last-arriver reduction);
+//   2  the same without fences: the data is written with device-scope atomic stores (write-through), the counter
+//      is relaxed, the last arriver reads with device-scope atomic loads.
+// The counter is left at zero for the next launch.
+__global__ __launch_bounds__(256) void probe_handoff_kernel(float* data, uint32_t* counter, float* out, int mode) {
+  __shared__ bool last;
+  constexpr int kWords = 1024;
+  float* mine = data + (size_t)blockIdx.x * kWords;
+  for (int i = threadIdx.x; i < kWords; i += 256) {
+    const float v = (float)(blockIdx.x + i);
+    if (mode == 2) __hip_atomic_store(mine + i, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else mine[i] = v;
+  }
+  if (mode == 0) return;
+  if (mode == 1) __threadfence();
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const uint32_t old = __hip_atomic_fetch_add(counter, 1u, mode == 1 ? __ATOMIC_ACQ_REL : __ATOMIC_RELAXED,
+                                                __HIP_MEMORY_SCOPE_AGENT);
+    last = old == gridDim.x - 1;
+  }
+  __syncthreads();
+  if (!last) return;
+  if (mode == 1) __threadfence();
+  const size_t n_all = (size_t)gridDim.x * kWords;
+  float s = 0.f;
+  for (int i = threadIdx.x; i < 2048; i += 256) {
+    const float* p = data + ((size_t)i * 257) % n_all;
+    s += mode == 2 ? __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : *p;
+  }
+  s = wave_sum(s);
+  if ((threadIdx.x & 63) == 0) atomicAdd(out, s);
+  if (threadIdx.x == 0) *counter = 0;
+}
+
+void launch_probe_handoff(float* data, uint32_t* counter, float* out, int n_workgroups, int mode, hipStream_t st) {
+  hipLaunchKernelGGL(probe_handoff_kernel, dim3(n_workgroups), dim3(256), 0, st, data, counter, out, mode);
+}
+
 }  // namespace ekv
