@@ -930,6 +930,26 @@ def main():
                             "softmax_over_topk_lists_us": result["other_rows"]["softmax_sparse_us"],
                             "speedup_topk_vs_dense": result["other_rows"]["speedup_vs_dense"]}
         result["other_rows"]["latency_by_context_B1"] = sweep
+        # decode latency against the size of the support: one sequence of 262 144 tokens of the headline's shape with
+        # the score scale lowered so that attention gets flatter (sparse: top-k 2 % = 5248 candidate tokens per head)
+        by_support = {}
+        for mult in (1.0, 0.25, 0.12, 0.06, 0.04):
+            wf = synth.WORKLOADS["C4"].scaled(name=f"C4-shape-262144-scale-x{mult}", context=262144,
+                                              scale=mult / math.sqrt(synth.WORKLOADS["C4"].head_dim))
+            Rf = Runner(wf, args.budget, args.copies, args.q_page, dev, cap_frac=args.cap_frac,
+                        fused_append=not args.two_launch_append)
+            stf = Rf.copies[0]
+            Rf.step_topk(stf)
+            u_sp = Rf.time_call(lambda st_: ekv.ekv_decode_sparse(st_.cfg, st_.inp["q"], st_.cache(), stf.page_idx, stf.n_sel,
+                                                                  st_.out, st_.tau, st_.supp, st_.ws_sparse), reps=10)
+            supp_sp = float(stf.supp.float().mean())
+            u_dn, _, _ = Rf.run_timed(Rf.step_dense, max(5, side // 2), 3, stages=False)
+            by_support[f"scale_x{mult}"] = {"sparse_support_mean": supp_sp, "decode_sparse_us": round(u_sp, 2),
+                                            "dense_support_mean": float(stf.supp.float().mean()),
+                                            "dense_full_us": round(u_dn, 2)}
+            Rf.release()
+            del Rf, stf
+        result["other_rows"]["decode_us_by_support_size_256k"] = by_support
         # the alpha and baseline sweep workload (batch 8, 256K tokens per sequence, pages of 32): top-k at a matched
         # budget of 4096 tokens per head under alpha = 1.25 / 1.5 / 2 against the dense decode of the same alpha, and
         # softmax over the same lists (its dropped mass next to entmax's)

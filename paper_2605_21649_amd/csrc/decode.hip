@@ -20,6 +20,7 @@ constexpr int kScoreThreads = 256;
 constexpr int kSolveThreads = 1024;
 constexpr int kSolveWaves = kSolveThreads / 64;
 constexpr int kListCap = 4096;          // candidate entries held in LDS (u, pos, row): 48 KB
+constexpr int kSpillCap = 65536;        // entries of a row's overflow list in the workspace (longer lists: the row is streamed)
 constexpr int kPreR = kPreGroups / kSolveThreads;    // group maxima a thread of the solve holds at most
 constexpr int kRoundLoads = 16;         // loads per lane and compaction round
 constexpr int kRoundTokens = kSolveThreads * kRoundLoads;
@@ -640,6 +641,8 @@ struct SolveArgs {
   const int32_t* fcount; const float* frow; const float* flist_u; const int32_t* flist_pos; int n_slices_max;
   int grouped;
   int HkvPool;
+  // per-row overflow list in the workspace for candidate lists beyond the LDS list (null / 0 when rows cannot have one)
+  float* spill_u; int32_t* spill_pos; int spill_cap;
 };
 
 // V row index (phys*Hkv + hkv)*P + tok of candidate position `pos`.
@@ -675,6 +678,32 @@ __device__ __forceinline__ void reduce_output(float (&acc)[8], SolveShared& sh, 
     float s = 0.f;
     for (int i = 0; i < kSolveWaves; ++i) s += sh.obuf[i][tid];
     out[tid] = s;
+  }
+}
+
+// Weighted sum of the V rows of the `tot` support entries in LDS (weight list_u[e], row list_row[e]): 64 row
+// slots x 16 lanes, eight independent 16-byte loads in flight per lane (clamped entries carry weight 0).  A row
+// slot adds its entries in ascending order.
+template <typename T>
+__device__ __forceinline__ void gather_support(const T* __restrict__ v_pool, const SolveShared& sh, int tot, float (&acc)[8]) {
+  const int rs = threadIdx.x >> 4, c = threadIdx.x & 15;
+  constexpr int kSlots = kSolveThreads / 16;
+  for (int e0 = 0; e0 < tot; e0 += 8 * kSlots) {
+    Raw8<T> vr[8]; float pw[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int e = e0 + kSlots * j + rs;
+      const int ec = min(e, tot - 1);
+      pw[j] = e < tot ? sh.list_u[ec] : 0.f;
+      load_raw8(v_pool + (size_t)sh.list_row[ec] * kD + 8 * c, vr[j]);
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      float vv[8];
+      widen8(vr[j], vv);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i] = fmaf(pw[j], vv[i], acc[i]);
+    }
   }
 }
 
@@ -778,7 +807,10 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
   const bool can_skip = (chunk_tokens & 63) == 0 && n_cand > 4 * kRoundTokens;
   int n_list = 0, parity = 0;
   bool in_lds = true;
+  bool in_spill = false;          // the candidate list outgrew LDS and lives in this row's overflow list
   bool prefilled = false;
+  float* const su = A.spill_u != nullptr ? A.spill_u + (size_t)bh * A.spill_cap : nullptr;
+  int32_t* const sp = A.spill_pos != nullptr ? A.spill_pos + (size_t)bh * A.spill_cap : nullptr;
   if (filt) {
     // survivors of the filter passes: gather the per-slice lists, in slice order, if they fit
     const int n_slices = (n_chunks + kFilterSliceChunks - 1) / kFilterSliceChunks;
@@ -803,13 +835,31 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
       n_list = tot;
       prefilled = true;
       lo_u = fminf(thr - zmax, -1e-7f);
+    } else if (!bad && su != nullptr && tot <= A.spill_cap) {
+      // too many survivors for LDS: concatenate the per-slice lists, in slice order, into the row's overflow list
+      int* start = reinterpret_cast<int*>(sh.list_row);
+      if (tid < n_slices) { start[2 * tid] = base + inc - cs; start[2 * tid + 1] = cs; }
+      __syncthreads();
+      for (int sl = w; sl < n_slices; sl += kSolveWaves) {
+        const int o0 = start[2 * sl], cnt = start[2 * sl + 1];
+        const float* lu = A.flist_u + ((size_t)bh * A.n_slices_max + sl) * kFilterSliceCap;
+        const int32_t* lp = A.flist_pos + ((size_t)bh * A.n_slices_max + sl) * kFilterSliceCap;
+        for (int e = lane; e < cnt; e += 64) { su[o0 + e] = lu[e]; sp[o0 + e] = lp[e]; }
+      }
+      n_list = tot;
+      prefilled = true;
+      in_lds = false; in_spill = true;
+      lo_u = fminf(thr - zmax, -1e-7f);
     }
     __syncthreads();
   }
   if (pre) {
     // ordered list of the groups above the bound: thread t owns consecutive groups, so (thread, k) order is group order
     int* glist = reinterpret_cast<int*>(sh.list_row);        // free until the solve is done
-    int goff, n_pass = 0;
+    int n_pass = 0;
+    for (int refine = 0;; ++refine) {
+    int goff;
+    n_pass = 0;
     if (gpt == 1) {                                          // one group per thread (rows up to 65 536 tokens): a ballot
       const bool gp = mypm[0] > thr;
       const uint64_t gmk = __ballot(gp);
@@ -836,21 +886,28 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
     parity ^= 1;
     n_pass = __builtin_amdgcn_readfirstlane(n_pass);
     __syncthreads();
+    // The usual row is done here: a few dozen groups pass.  A flat row, where most groups still pass, has its group
+    // maxima crowded into the last few of the 64 steps below the maximum; the same certificate on a histogram of
+    // [bound, maximum] resolves them (twice at most: 1/64^3 of the first width), and the list is rebuilt.
+    if (n_pass <= kSolveWaves * kRoundLoads || refine == 2) break;
+    const float step2 = (zmax - thr) * (1.0f / 64.0f), inv_step2 = 64.0f / (zmax - thr);
+    if (tid < 64) sh.hist[tid] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < kPreR; ++k)
+      if (k < gpt && mypm[k] > thr) atomicAdd(&sh.hist[min(63, (int)((mypm[k] - thr) * inv_step2))], 1);
+    __syncthreads();
+    const int level2 = certified_level<64>(sh.hist, step2, beta, ibeta, sh.flags);
+    if (level2 == 0) break;
+    thr += (float)level2 * step2;
+    }
     // wavefront w of a round owns `per` consecutive list entries: (round, w, load, lane) is candidate order
-    for (int j0 = 0; j0 < n_pass; j0 += kSolveWaves * kRoundLoads) {
-      const int rem = min(n_pass - j0, kSolveWaves * kRoundLoads);
+    constexpr int kRoundGroups = kSolveWaves * kRoundLoads;
+    // second half of a round: mask, count, exchange the counts (one barrier), ordered compaction into the list
+    auto compact_round = [&](int j0, float (&v)[kRoundLoads], const int (&vpos)[kRoundLoads]) {
+      const int rem = min(n_pass - j0, kRoundGroups);
       const int per = (rem + kSolveWaves - 1) / kSolveWaves;
       const int jw = j0 + w * per, jend = j0 + rem;
-      float v[kRoundLoads]; int vpos[kRoundLoads];
-#pragma unroll
-      for (int i = 0; i < kRoundLoads; ++i) {
-        v[i] = -INFINITY; vpos[i] = 0;
-        if (i < per) {                                   // wave-uniform
-          const int g = glist[min(jw + i, n_pass - 1)];
-          vpos[i] = g * chunk_tokens + lane;
-          v[i] = zr[min(vpos[i], n_cand - 1)];
-        }
-      }
       int c = 0;
 #pragma unroll
       for (int i = 0; i < kRoundLoads; ++i) {
@@ -864,22 +921,72 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
       for (int i = 0; i < kSolveWaves; ++i) { const int ci = sh.wcount[parity][i]; if (i < w) off += ci; tot += ci; }
       n_list += tot;
       parity ^= 1;
-      if (n_list > kListCap) in_lds = false;
-      if (in_lds) {
+      if (in_lds && n_list > kListCap) {
+        // The list outgrows LDS: it continues in the row's overflow list, to which the entries of the earlier rounds
+        // move first (the barrier above ordered their LDS writes).
+        in_lds = false;
+        if (su != nullptr) {
+          in_spill = true;
+          for (int e = tid; e < n_list - tot; e += kSolveThreads) { su[e] = sh.list_u[e]; sp[e] = sh.list_pos[e]; }
+        }
+      }
+      if (in_spill && n_list > A.spill_cap) in_spill = false;
+      auto emit = [&](auto* du, auto* dp) {
 #pragma unroll
         for (int i = 0; i < kRoundLoads; ++i) {
           const bool in = v[i] > thr;
           const uint64_t mk = __ballot(in);
           if (in) {
             const int o = off + __popcll(mk & lt);
-            sh.list_u[o] = v[i] - zmax;
-            sh.list_pos[o] = vpos[i];
+            du[o] = v[i] - zmax;
+            dp[o] = vpos[i];
           }
           off += __popcll(mk);
         }
+      };
+      if (in_lds) emit(sh.list_u, sh.list_pos);
+      else if (in_spill) emit(su, sp);
+    };
+    if (n_pass <= kRoundGroups) {
+      // the usual case, one round: only the loads the round needs
+      const int per = (n_pass + kSolveWaves - 1) / kSolveWaves;
+      const int jw = w * per;
+      float v[kRoundLoads]; int vpos[kRoundLoads];
+#pragma unroll
+      for (int i = 0; i < kRoundLoads; ++i) {
+        v[i] = -INFINITY; vpos[i] = 0;
+        if (i < per) {                                   // wave-uniform
+          const int g = glist[min(jw + i, max(n_pass - 1, 0))];
+          vpos[i] = g * chunk_tokens + lane;
+          v[i] = zr[min(vpos[i], n_cand - 1)];
+        }
+      }
+      if (n_pass > 0) compact_round(0, v, vpos);
+    } else {
+      // Many groups pass (a flat row): the loads of the next round are requested before the current round is
+      // compacted, all of them unconditionally (entries past the end repeat the last group and are masked), so that
+      // the waits can leave one round in flight.
+      auto request = [&](int j0, float (&v)[kRoundLoads], int (&vpos)[kRoundLoads]) {
+        const int rem = max(min(n_pass - j0, kRoundGroups), 1);
+        const int per = (rem + kSolveWaves - 1) / kSolveWaves;
+        const int jw = j0 + w * per;
+#pragma unroll
+        for (int i = 0; i < kRoundLoads; ++i) {
+          const int g = glist[clampi(jw + i, 0, n_pass - 1)];
+          vpos[i] = g * chunk_tokens + lane;
+          v[i] = zr[min(vpos[i], n_cand - 1)];
+        }
+      };
+      float va[kRoundLoads], vb[kRoundLoads]; int pa[kRoundLoads], pb[kRoundLoads];
+      request(0, va, pa);
+      for (int j0 = 0; j0 < n_pass; j0 += 2 * kRoundGroups) {
+        request(j0 + kRoundGroups, vb, pb);
+        compact_round(j0, va, pa);
+        request(j0 + 2 * kRoundGroups, va, pa);
+        if (j0 + kRoundGroups < n_pass) compact_round(j0 + kRoundGroups, vb, pb);
       }
     }
-    if (in_lds) lo_u = fminf(thr - zmax, -1e-7f);
+    if (in_lds || in_spill) lo_u = fminf(thr - zmax, -1e-7f);
   }
   for (int pass = 0; pass < 3 && !prefilled && !pre; ++pass) {
     const float width = zmax - thr, slice = width * (1.0f / 64.0f), inv_slice = 64.0f / width;
@@ -1062,18 +1169,10 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
       n_sup += tot;
     }
     __syncthreads();
-    // weighted value sum: 64 row slots x 16 lanes, one independent 16-byte load per support token
-    const int rs = tid >> 4, c = tid & 15;
     float acc[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[i] = 0.f;
-    for (int e = rs; e < n_sup; e += kSolveThreads / 16) {
-      const float p = sh.list_u[e];
-      float vv[8];
-      load8<T>(v_pool + (size_t)sh.list_row[e] * kD + 8 * c, vv);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) acc[i] = fmaf(p, vv[i], acc[i]);
-    }
+    gather_support<T>(v_pool, sh, n_sup, acc);
     reduce_output(acc, sh, out);
     if (A.ex.support_tokens != nullptr) {
       int32_t* dst = A.ex.support_tokens + (size_t)bh * A.ex.support_cap;
@@ -1081,72 +1180,66 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
         dst[e] = token_of<DENSE>(A, lrow, sh.list_pos[e]);
     }
   } else {
-    // the candidates do not fit in LDS: stream the score row for every evaluation
-    const RowSrc rsrc{zr, n_cand, zmax};
-    tau_u = solve_tau(rsrc, lo_u, seed_u, beta, ibeta, sh, supp, evals);
-    const int rs = tid >> 4, c = tid & 15;
+    // The candidates do not fit in LDS.  They are iterated where they are: in the row's overflow list (every
+    // evaluation of the mass reads that list), or -- a row so flat that even that list is too small -- in the score
+    // row itself.  The support is then gathered in rounds of 4096 candidates (wavefront w owns 256 consecutive ones):
+    // the support tokens of a round are compacted into LDS (weight, V row, position) -- at most 4096, so they always
+    // fit -- and their V rows summed by the 64 row slots with batched independent loads.
     float acc[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[i] = 0.f;
-    // Rounds of 4096 candidates (wavefront w owns 256 consecutive ones): the support tokens of a round are
-    // compacted into LDS (weight, V row) -- at most 4096, so they always fit -- and gathered by the 64 row slots
-    // with independent loads.  (A loop over all candidates with one score load per iteration and row slot waited
-    // for memory n_cand / 64 times: 2 ms for a row of 262 144.)
-    for (int base = 0; base < n_cand; base += 4 * kSolveThreads) {
-      float xs[4];
+    int n_out = 0;
+    auto finish = [&](const auto& src) {
+      tau_u = solve_tau(src, lo_u, seed_u, beta, ibeta, sh, supp, evals);
+      for (int base = 0; base < src.n; base += 4 * kSolveThreads) {
+        float xs[4]; int ps[4]; uint32_t rw[4];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) xs[i] = zr[min(base + w * 256 + i * 64 + lane, n_cand - 1)];
-      int cw = 0;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        xs[i] = base + w * 256 + i * 64 + lane < n_cand ? xs[i] - zmax - tau_u : -1.f;
-        cw += __popcll(__ballot(xs[i] > 0.f));
-      }
-      if (lane == 0) sh.wcount[parity][w] = cw;
-      __syncthreads();                                   // also: the previous round's gather is done
-      int off = 0, tot = 0;
-      for (int i = 0; i < kSolveWaves; ++i) { const int ci = sh.wcount[parity][i]; if (i < w) off += ci; tot += ci; }
-      parity ^= 1;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const bool in = xs[i] > 0.f;
-        const uint64_t mk = __ballot(in);
-        if (in) {
-          const int o = off + __popcll(mk & lt);
-          sh.list_u[o] = pow_beta(xs[i], beta, ibeta);
-          sh.list_row[o] = v_row_of<DENSE>(A, b, lrow, hkv, base + w * 256 + i * 64 + lane);
+        for (int i = 0; i < 4; ++i) {
+          const int idx = min(base + w * 256 + i * 64 + lane, src.n - 1);
+          xs[i] = src.get_u(idx); ps[i] = src.get_pos(idx);
         }
-        off += __popcll(mk);
-      }
-      __syncthreads();
-      for (int e = rs; e < tot; e += kSolveThreads / 16) {
-        const float p = sh.list_u[e];
-        float vv[8];
-        load8<T>(v_pool + (size_t)sh.list_row[e] * kD + 8 * c, vv);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) acc[i] = fmaf(p, vv[i], acc[i]);
+        for (int i = 0; i < 4; ++i) rw[i] = v_row_of<DENSE>(A, b, lrow, hkv, min(ps[i], n_cand - 1));   // unconditional
+        int cw = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          xs[i] = base + w * 256 + i * 64 + lane < src.n ? xs[i] - tau_u : -1.f;
+          cw += __popcll(__ballot(xs[i] > 0.f));
+        }
+        if (lane == 0) sh.wcount[parity][w] = cw;
+        __syncthreads();                                   // also: the previous round's gather is done
+        int off = 0, tot = 0;
+        for (int i = 0; i < kSolveWaves; ++i) { const int ci = sh.wcount[parity][i]; if (i < w) off += ci; tot += ci; }
+        parity ^= 1;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const bool in = xs[i] > 0.f;
+          const uint64_t mk = __ballot(in);
+          if (in) {
+            const int o = off + __popcll(mk & lt);
+            sh.list_u[o] = pow_beta(xs[i], beta, ibeta);
+            sh.list_row[o] = rw[i];
+            sh.list_pos[o] = ps[i];
+          }
+          off += __popcll(mk);
+        }
+        __syncthreads();
+        gather_support<T>(v_pool, sh, tot, acc);
+        if (A.ex.support_tokens != nullptr) {
+          int32_t* dst = A.ex.support_tokens + (size_t)bh * A.ex.support_cap;
+          for (int e = tid; e < tot && n_out + e < A.ex.support_cap; e += kSolveThreads)
+            dst[n_out + e] = token_of<DENSE>(A, lrow, sh.list_pos[e]);
+        }
+        n_out += tot;
       }
+    };
+    if (in_spill) {
+      __syncthreads();                                     // the overflow list is complete and visible to the workgroup
+      finish(ListSrc{su, sp, n_list});
+    } else {
+      finish(RowSrc{zr, n_cand, zmax});
     }
     reduce_output(acc, sh, out);
-    if (A.ex.support_tokens != nullptr) {
-      int32_t* dst = A.ex.support_tokens + (size_t)bh * A.ex.support_cap;
-      int base = 0;
-      for (int i0 = 0; i0 < n_cand; i0 += kSolveThreads) {
-        const int i = i0 + tid;
-        const bool in = i < n_cand && zr[i] - zmax > tau_u;
-        const uint64_t mk = __ballot(in);
-        __syncthreads();
-        if (lane == 0) sh.wcount[0][w] = __popcll(mk);
-        __syncthreads();
-        int off = base, tot = 0;
-        for (int k = 0; k < kSolveWaves; ++k) { const int ck = sh.wcount[0][k]; if (k < w) off += ck; tot += ck; }
-        if (in) {
-          off += __popcll(mk & lt);
-          if (off < A.ex.support_cap) dst[off] = token_of<DENSE>(A, lrow, i);
-        }
-        base += tot;
-      }
-    }
   }
   const float tau = tau_u + zmax;
   if (tid == 0) {
@@ -1430,6 +1523,10 @@ size_t decode_ws_carve(const Dims& dm, bool dense, void* base, DecodeWorkspace* 
   const size_t o_z = take(rows * zstride * sizeof(float));
   const size_t o_pm = take(rows * n_chunks_max * sizeof(float));
   const size_t o_pre = take((rows + 1) * sizeof(int32_t));
+  // overflow list of a row whose candidates outgrow the solve's LDS list: (u, position) per entry
+  const size_t spill_cap = zstride > (size_t)kListCap ? (zstride < (size_t)kSpillCap ? zstride : (size_t)kSpillCap) : 0;
+  const size_t o_su = spill_cap ? take(rows * spill_cap * sizeof(float)) : 0;
+  const size_t o_sp = spill_cap ? take(rows * spill_cap * sizeof(int32_t)) : 0;
   size_t o_fc = 0, o_fr = 0, o_fu = 0, o_fp = 0;
   if (n_slices) {
     o_fc = take(rows * n_slices * sizeof(int32_t));
@@ -1441,6 +1538,9 @@ size_t decode_ws_carve(const Dims& dm, bool dense, void* base, DecodeWorkspace* 
     char* p = (char*)base;
     ws->z = (float*)(p + o_z); ws->pmax = (float*)(p + o_pm); ws->unit_pre = (int32_t*)(p + o_pre);
     ws->zstride = zstride; ws->n_chunks_max = n_chunks_max; ws->n_slices_max = (int)n_slices;
+    ws->spill_u = spill_cap ? (float*)(p + o_su) : nullptr;
+    ws->spill_pos = spill_cap ? (int32_t*)(p + o_sp) : nullptr;
+    ws->spill_cap = (int)spill_cap;
     ws->fcount = n_slices ? (int32_t*)(p + o_fc) : nullptr;
     ws->frow = n_slices ? (float*)(p + o_fr) : nullptr;
     ws->flist_u = n_slices ? (float*)(p + o_fu) : nullptr;
@@ -1461,6 +1561,7 @@ void launch_decode(const Dims& dm, bool dense, bool grouped, const void* q, cons
   so.n_slices_max = ws.n_slices_max;
   so.grouped = grouped ? 1 : 0;
   so.HkvPool = dm.HkvPool;
+  so.spill_u = ws.spill_u; so.spill_pos = ws.spill_pos; so.spill_cap = ws.spill_cap;
   FilterArgs fa{c.seq_lens, n_sel, ws.z, ws.pmax, ws.fcount, ws.frow, ws.flist_u, ws.flist_pos,
                 dm.Hq, dm.Hkv, grouped ? 1 : 0, dm.P, ws.n_slices_max, dense ? dm.Mmax : dm.cap, ws.n_chunks_max,
                 ws.zstride, dm.beta, dm.ibeta};

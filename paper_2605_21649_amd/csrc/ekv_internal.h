@@ -30,6 +30,9 @@ struct DecodeWorkspace {
   float* z;        // [B*Hq][zstride] candidate scores z_j (or -inf where masked)
   float* pmax;     // [B*Hq][n_chunks_max] maxima of z per pmax_pages(P) page slots
   int32_t* unit_pre;  // [B*Hq + 1] item prefix of pass 1 (used when the units do not fit in LDS)
+  float* spill_u;      // [B*Hq][spill_cap] overflow of the solve's candidate list (z - zmax), null when rows are short
+  int32_t* spill_pos;  // [B*Hq][spill_cap] positions of those candidates
+  int spill_cap;
   size_t zstride;  // floats per (b,h) row of z
   int n_chunks_max;
   // filter passes; all null / 0 when the rows are short

@@ -39,10 +39,13 @@ def test_workspace_sizes():
     cfg = good_cfg()
     sparse = ekv.ekv_workspace_bytes(cfg, ekv.EKV_OP_DECODE_SPARSE)
     full = ekv.ekv_workspace_bytes(cfg, ekv.EKV_OP_DECODE_FULL)
-    # scores: 4 B per candidate token and query head, plus one maximum per 64 tokens; rows of 65536
-    # tokens or more add the filter lists (32 KiB per 32768-token slice and head)
-    assert sparse >= 32 * 2622 * 16 * 4 and sparse < 1.1 * 32 * 2622 * 16 * 4
-    assert full >= 32 * 65536 * 16 * 4 and full < 1.3 * 32 * 65536 * 16 * 4
+    # scores: 4 B per candidate token and query head, plus one maximum per 64 tokens; rows that can exceed the
+    # solve's 4096-entry list add an overflow list of min(row, 65536) (value, position) entries per head; rows of more
+    # than 262144 tokens add the filter lists (32 KiB per 32768-token slice and head)
+    scores, spill = 32 * 2622 * 16 * 4, 32 * 2622 * 16 * 8
+    assert scores + spill <= sparse < 1.1 * scores + spill
+    spill = 32 * 65536 * 8
+    assert full >= 32 * 65536 * 16 * 4 + spill and full < 1.3 * 32 * 65536 * 16 * 4 + spill
     assert ekv.ekv_workspace_bytes(cfg, ekv.EKV_OP_SELECT_GAUSS) > 0
 
 

@@ -640,6 +640,17 @@ LONG = [synth.C2.scaled(name="C2-long-bf16", context=100000, ragged=7, n_q_heads
         synth.C1.scaled(name="C1-filter-f32", context=270000, ragged=3, n_q_heads=2, n_kv_heads=2,
                         scale=1.0 / math.sqrt(128.0)),
         synth.C1.scaled(name="C1-filter-flat", context=264000, n_planted=0, scale=0.02 / math.sqrt(128.0),
+                        n_q_heads=2, n_kv_heads=2),
+        # moderately flat rows, supports of hundreds to thousands of tokens.  Nearly every 64-token group holds a
+        # candidate, so the solve fetches the groups in many rounds (the next round requested while the current one is
+        # compacted); with a support of ~900 the candidates still fit the LDS list, with ~5000 they continue in the
+        # row's overflow list in the workspace, and the row of 300 000 tokens reaches that list through the filter
+        # passes' per-slice lists.
+        synth.C1.scaled(name="C1-wide-900", context=100000, ragged=5, n_planted=0, scale=0.15 / math.sqrt(128.0),
+                        n_q_heads=2, n_kv_heads=2),
+        synth.C1.scaled(name="C1-wide-5000", context=100000, ragged=5, n_planted=0, scale=0.05 / math.sqrt(128.0),
+                        n_q_heads=2, n_kv_heads=2),
+        synth.C1.scaled(name="C1-filter-wide-6000", context=300000, ragged=9, n_planted=0, scale=0.05 / math.sqrt(128.0),
                         n_q_heads=2, n_kv_heads=2)]
 
 
@@ -682,7 +693,14 @@ def test_decode_long_rows_take_the_filter_passes(w):
         ref = orc.entmax_attention(q, K, V, w.alpha, w.score_scale)
         tok = orc.pages_to_tokens(lists[(b, hq)], w.page_size, K.shape[0])
         ref_s = orc.entmax_attention(q, K, V, w.alpha, w.score_scale, tok)
-        if flat:
+        if "wide" in w.name:
+            lo, hi = {"900": (500, 2000), "5000": (4096, 8192), "6000": (4096, 8192)}[w.name.rsplit("-", 1)[1]]
+            assert lo < len(ref["support"]) < hi and (hi < 4096 or len(ref_s["support"]) > 2500)
+            check_decode_unit(w, out_f[b, hq].cpu().numpy(), float(tau_f[b, hq]), int(supp_f[b, hq]),
+                              full_tokens[b, hq], ref, boundary_expected=True)
+            check_decode_unit(w, st.out[b, hq].cpu().numpy(), float(st.tau[b, hq]), int(st.supp[b, hq]),
+                              sp_tokens[b, hq], ref_s, boundary_expected=True)
+        elif flat:
             assert len(ref["support"]) > 4096 and len(ref_s["support"]) > 4096
             # supports larger than the token list the test asked for: counts, tau and outputs under the usual rule
             for got_tau, got_supp, got_out, r in ((tau_f, supp_f, out_f, ref), (st.tau, st.supp, st.out, ref_s)):
