@@ -405,8 +405,33 @@ __global__ __launch_bounds__(kFilterThreads) void filter_level_kernel(const Filt
         atomicAdd(&hist[min(63, (int)((v[k] - thr0) * inv_step))], 1);
   }
   __syncthreads();
-  const int level = certified_level<64>(hist, step, A.beta, A.ibeta, flags);
-  if (tid == 0) { A.frow[2 * row] = zmax; A.frow[2 * row + 1] = thr0 + (float)level * step; }
+  int level = certified_level<64>(hist, step, A.beta, A.ibeta, flags);
+  float thr = thr0 + (float)level * step;
+  // A flat row crowds its group maxima into the last few steps below the maximum, and most groups still pass: the
+  // same certificate on a histogram of [bound, maximum] resolves them (twice at most).
+  for (int refine = 0; refine < 2; ++refine) {
+    int above = 0;
+    for (int g = level; g < 64; ++g) above += hist[g];
+    if (above <= 1024) break;
+    __syncthreads();                                          // every thread has read the counts
+    const float w2 = zmax - thr, step2 = w2 * (1.0f / 64.0f), inv_step2 = 64.0f / w2;
+    if (tid < 64) hist[tid] = 0;
+    __syncthreads();
+    for (int i0 = 0; i0 < n_chunks; i0 += kFilterThreads * 16) {
+      float v[16];
+#pragma unroll
+      for (int k = 0; k < 16; ++k) v[k] = pm[min(i0 + k * kFilterThreads + tid, n_chunks - 1)];
+#pragma unroll
+      for (int k = 0; k < 16; ++k)
+        if (i0 + k * kFilterThreads + tid < n_chunks && v[k] > thr)
+          atomicAdd(&hist[min(63, (int)((v[k] - thr) * inv_step2))], 1);
+    }
+    __syncthreads();
+    level = certified_level<64>(hist, step2, A.beta, A.ibeta, flags);
+    if (level == 0) break;
+    thr += (float)level * step2;
+  }
+  if (tid == 0) { A.frow[2 * row] = zmax; A.frow[2 * row + 1] = thr; }
 }
 
 // Scores of up to four groups of a wavefront at once (lane = token of the group), -inf where masked.
