@@ -122,7 +122,7 @@ __device__ __forceinline__ void page_mass(float muY, float sY, float cnt, float&
 
 // Iteration state of one (b,h): the point the next evaluation is taken at, and its bracket.
 // `step` is the Newton step that led to tau (0: none yet, or the point came from a fallback).
-struct GaussState { float tau, lo, hi; int done; float step; };
+struct GaussState { float tau, lo, hi; int done; float step; int order; };   // order of the update that gave `step`
 
 // workspace: state[2][BH], init partials [BH][S][4], eval partials [2][BH][S][3],
 //            hottest page (a mu, a sigma, count) of every wavefront of the init launch [BH][S*4][3],
@@ -186,31 +186,45 @@ __global__ __launch_bounds__(kGaussEvalThreads) void gauss_init_kernel(const flo
   }
 }
 
-// Scalar solve of n * sd^NB * h_NB((m - tau)/sd) = 1 (the pooled single-Gaussian model): a starting point
-// for the real iteration, so a loose tolerance is enough.  Starts from the leading-order tail estimate
-// t0 = -sqrt(2 ln(n sd^NB)) and iterates Newton on the logarithm; two consecutive steps s1, s2 of a quadratically
-// converging iteration leave an error of about |s2|^3 / s1^2, which ends the loop without a confirming
-// evaluation (every workgroup of the first evaluation launch waits for this serial chain).
+// The single pooled Gaussian is a poor model when the page moments change along the sequence (a relevant segment,
+// a recency trend, two populations one after the other): its variance then holds the spread BETWEEN the parts and
+// its root can lie more than 1 above tau_hat, too far for the two evaluation launches.  The init launch already
+// leaves the pooled moments of every slice of the sequence; the mixture of those (one Gaussian per slice, one slice
+// per lane) follows such structure at the cost of the scalar iteration it replaces: Newton on log F_mix from the
+// pooled model's leading-order tail estimate, kept inside the bracket the signs of log F_mix give (secant, then
+// bisection towards `lo`, when a step leaves it).  On homogeneous pages the slices repeat the pooled moments and
+// the root is the pooled one.  `n, m, sd`: this lane's slice (n = 0: none); `pn, pm, psd`: the pooled moments.
 template <int NB>
-__device__ float pooled_guess(float n, float m, float sd, float lo) {
-  if (!(sd > 1e-20f)) return lo;
-  float sp = n;
+__device__ float slice_mixture_guess(float n, float m, float sd, float pn, float pm, float psd, float lo) {
+  if (!(psd > 1e-20f)) return lo;
+  float sp = pn;
 #pragma unroll
-  for (int i = 0; i < NB; ++i) sp *= sd;
-  float tau = sp > 1.f ? m + sd * sqrtf(2.f * __logf(sp)) : lo;
+  for (int i = 0; i < NB; ++i) sp *= psd;
+  float tau = sp > 1.f ? pm + psd * sqrtf(2.f * __logf(sp)) : lo;
   tau = fmaxf(tau, lo);
-  float prev = 0.f;
-  for (int it = 0; it < 8; ++it) {
-    float f, d;
-    page_mass<NB>(m - tau, sd, n, f, d);
-    d *= (float)NB;
-    if (!(f > 0.f && d > 0.f)) break;
-    const float next = fmaxf(tau + f * __logf(f) / d, lo);
+  float blo = lo, bhi = INFINITY, glo = 0.f, ghi = 0.f, prev = 0.f;
+  for (int it = 0; it < 12; ++it) {
+    float f = 0.f, d = 0.f;
+    if (n > 0.f) page_mass<NB>(m - tau, sd, n, f, d);
+    f = wave_sum(f); d = (float)NB * wave_sum(d);            // wave-uniform from here on
+    float next;
+    bool newton = false;
+    if (f > 0.f && d > 0.f) {
+      const float g = __logf(f);
+      if (g > 0.f) { blo = tau; glo = g; } else { bhi = tau; ghi = g; }
+      next = fmaxf(tau + f * g / d, lo);                     // a step below the left end goes to the left end
+      newton = next >= blo && next < bhi;
+      if (!newton) next = bhi < INFINITY && glo > 0.f ? blo + (bhi - blo) * glo / (glo - ghi) : 0.5f * (blo + fminf(bhi, tau));
+    } else {
+      bhi = tau; ghi = -80.f;                                // nothing of the mixture reaches tau: go down
+      next = 0.5f * (blo + tau);
+    }
+    next = fmaxf(next, lo);
     const float step = fabsf(next - tau);
-    const bool close = step <= 1e-3f * sd ||
-                       (prev != 0.f && step <= 0.25f * prev && step * step * step <= 2e-3f * sd * prev * prev);
+    const bool close = step <= 1e-3f * psd ||
+                       (newton && prev != 0.f && step <= 0.25f * prev && step * step * step <= 2e-3f * psd * prev * prev);
     tau = next;
-    prev = step;
+    prev = newton ? step : 0.f;
     if (close) break;
   }
   return tau;
@@ -262,37 +276,51 @@ __device__ float raise_to_hot_pages(float tau, const HotPages& h) {
   return tau;
 }
 
-// Advance the iteration state with the result (F, D = -dF/dtau) of the evaluation at st.tau.
-// The update is Halley's on log F (the paper names Newton or Halley; the third moment it needs comes with the
-// other two), Newton's on log F where Halley's denominator is not positive.
-// Stopping: F = 1 to float32 resolution; or a step below the resolution of tau; or two consecutive such steps
-// s1, s2 with |s2| <= |s1|/20: an iteration of order >= 2 shrinks the error at least as e' = K e^2 with
-// K = |s2|/s1^2, so after the second step it is at most about |s2|^3/s1^2 -- accepted when that is below 1e-7
-// (relative to max(1, |tau|)), without evaluating F at the new point.
+// Advance the iteration state with the result (F, D = -dF/dtau, D2 = d2F/dtau2) of the evaluation at st.tau.
+// The update works on g = log F, which is close to a parabola wherever Gaussian tails make up F: the step is the
+// root of g's local quadratic model nearest to Newton's (Halley's method in its irrational form; the paper names
+// Newton or Halley, and the third moment this needs comes with the other two), then Halley's rational step,
+// then Newton's on log F and on F, then bisection, whichever first stays inside the bracket.  A start 2.8 above
+// the root of a two-population mixture comes within 3e-2 in one such step and 4e-8 in two (float64 simulation;
+// the rational form: 8e-2, 3e-6).
+// Stopping: F = 1 to float32 resolution; or a step below the resolution of tau; or two consecutive smooth steps
+// s1, s2 with |s2| <= |s1|/20 whose implied remaining error is below 1e-7 (relative to max(1, |tau|)) without
+// evaluating F at the new point: an iteration of order 2 shrinks the error as e' = K e^2 with K = |s2|/s1^2, so
+// after the second step it is about |s2|^3/s1^2; when both steps are third-order ones, e' = K e^3 with
+// K = |s2|/|s1|^3 and the remaining error is about s2^4/|s1|^3, taken with a factor 10.
 __device__ __forceinline__ GaussState advance_state(GaussState st, float F, float D, float D2) {
   if (st.done) return st;
   if (fabsf(F - 1.0f) <= 2e-6f) { st.done = 1; return st; }         // float32 resolution of F: tau is the root
   if (F >= 1.0f) st.lo = st.tau; else st.hi = st.tau;
   float next = st.tau;
-  bool ok = false, smooth = false;
+  bool ok = false;
+  int order = 0;
   if (F > 0.f && D > 0.f) {
-    // g = log F:  g' = -D/F,  g'' = D2/F - (D/F)^2.  Halley: -2 g g' / (2 g'^2 - g g''); Newton: -g / g'
+    // g = log F:  g' = -D/F < 0,  g'' = D2/F - (D/F)^2
     const float g = __logf(F), g1 = -D / F, g2 = D2 / F - g1 * g1;
-    const float den = 2.f * g1 * g1 - g * g2;
-    if (den > 0.f) {
-      next = st.tau - 2.f * g * g1 / den;
+    const float disc = g1 * g1 - 2.f * g * g2;
+    if (disc > 0.f) {                                               // g + g' d + g'' d^2 / 2 = 0, the root next to -g/g'
+      next = st.tau - 2.f * g / (g1 - sqrtf(disc));
       ok = next > st.lo && next < st.hi;
     }
-    if (!ok) { next = st.tau - g / g1; ok = next > st.lo && next < st.hi; }           // Newton on log F
-    smooth = ok;
-    if (!ok) { next = st.tau + (F - 1.0f) / D; ok = next > st.lo && next < st.hi; }   // Newton on F
+    if (!ok) {                                                      // Halley: -2 g g' / (2 g'^2 - g g'')
+      const float den = 2.f * g1 * g1 - g * g2;
+      if (den > 0.f) { next = st.tau - 2.f * g * g1 / den; ok = next > st.lo && next < st.hi; }
+    }
+    if (ok) order = 3;
+    if (!ok) { next = st.tau - g / g1; ok = next > st.lo && next < st.hi; if (ok) order = 2; }   // Newton on log F
+    if (!ok) { next = st.tau + (F - 1.0f) / D; ok = next > st.lo && next < st.hi; }             // Newton on F
   }
   if (!ok) next = st.hi < INFINITY ? 0.5f * (st.lo + st.hi) : st.lo + 1.0f;
   const float step = next - st.tau, scale = fmaxf(1.f, fabsf(next));
-  if (fabsf(step) <= 3e-7f * scale) st.done = 1;
-  if (smooth && st.step != 0.f && fabsf(step) <= 0.05f * fabsf(st.step) &&
-      fabsf(step) * step * step <= 1e-7f * scale * st.step * st.step) st.done = 1;
-  st.step = smooth ? step : 0.f;
+  const float as = fabsf(step), ap = fabsf(st.step);
+  if (as <= 3e-7f * scale) st.done = 1;
+  if (order >= 2 && st.order >= 2 && as <= 0.05f * ap) {
+    if (as * as * as <= 1e-7f * scale * ap * ap) st.done = 1;
+    if (order == 3 && st.order == 3 && 10.f * as * as * as * as <= 1e-7f * scale * ap * ap * ap) st.done = 1;
+  }
+  st.step = step;
+  st.order = order;
   st.tau = next;
   return st;
 }
@@ -348,17 +376,20 @@ __global__ __launch_bounds__(kGaussEvalThreads) void gauss_eval_kernel(const flo
       const float* o = ws.init_part + ((size_t)bh * ws.S + tid) * 4;
       mx = o[0]; s0 = o[1]; s1 = o[2]; s2 = o[3];
     }
+    // this lane's slice as one Gaussian of the start's mixture (lanes of wavefront 0; S <= 64)
+    const float sl_n = s0, sl_m = s0 > 0.f ? s1 / s0 : 0.f;
+    const float sl_sd = s0 > 0.f ? sqrtf(fmaxf(s2 / s0 - sl_m * sl_m, 0.f)) : 0.f;
     if (tid < 64) { mx = wave_max(mx); s0 = wave_sum(s0); s1 = wave_sum(s1); s2 = wave_sum(s2); }
     if (tid == 0) { bc[0] = mx; bc[1] = s0; bc[2] = s1; bc[3] = s2; }
     __syncthreads();
     mx = bc[0]; s0 = bc[1]; s1 = bc[2]; s2 = bc[3];
     const float mean = s1 / s0;
     const float var = fmaxf(s2 / s0 - mean * mean, 0.f);
-    st.lo = mx - 1.0f; st.hi = INFINITY; st.done = 0; st.step = 0.f;
+    st.lo = mx - 1.0f; st.hi = INFINITY; st.done = 0; st.step = 0.f; st.order = 0;
     // the scalar start iteration runs on one wavefront only (the others would just repeat it)
     float tau0 = 0.f;
     if (tid < 64) {
-      tau0 = pooled_guess<NB>(s0, mean, sqrtf(var), st.lo);
+      tau0 = slice_mixture_guess<NB>(sl_n, sl_m, sl_sd, s0, mean, sqrtf(var), st.lo);
       tau0 = raise_to_hot_pages<NB>(tau0, hot);
     }
     __syncthreads();

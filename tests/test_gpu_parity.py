@@ -220,7 +220,7 @@ def test_select_topk_long_context(M, k):
 
 def test_select_gauss_long_context():
     """Gaussian selector with 65536 pages per head (keys held in registers, 64 per lane)."""
-    P, B, Hq, M = 16, 1, 6, 65536
+    P, B, Hq, M = 16, 1, 8, 65536
     cap = 3000
     cfg = ekv.make_config(B, Hq, Hq, 128, P, "bf16", 1.5, 0.1, M, cap)
     dev = torch.device("cuda")
@@ -233,6 +233,10 @@ def test_select_gauss_long_context():
     mu[0, 3, rng.choice(M, 3, replace=False)] += 9.0; sg[0, 3] *= 0.02   # three pages carry all the mass
     sg[0, 4] = (np.abs(rng.normal(size=M)) * 0.6 + 0.05).astype(np.float32)   # page deviations from 0.05 to ~2
     mu[0, 5] = (1.0 + 0.25 * rng.standard_t(3, size=M)).astype(np.float32)   # heavy-tailed page means
+    # two populations interleaved at random (no slice of the sequence sees one alone), and a trend along the sequence
+    hi6 = rng.random(M) < 0.5
+    mu[0, 6] = np.where(hi6, 4.0 + 0.125 * rng.normal(size=M), 1.0 + 0.25 * rng.normal(size=M)).astype(np.float32)
+    mu[0, 7] += np.linspace(0.0, 1.5, M, dtype=np.float32)
     seq_lens = torch.full((B,), M * P - 7, dtype=torch.int32, device=dev)
     t = lambda a: torch.from_numpy(a).to(dev)
     tau_hat = torch.zeros(B, Hq, device=dev); page_idx = torch.zeros(B, Hq, cap, dtype=torch.int32, device=dev)
