@@ -785,8 +785,9 @@ def main():
         extras["randn_gauss_selector_by_context"] = {"q_page": args.q_page, "margin": 0.0, "rows": tab}
         # the Gaussian-aware selector alone on page moments that are NOT homogeneous (what attention sinks or a few
         # relevant pages produce): a few pages far above the bulk are caught by the start of the root iteration
-        # (hottest page of every wavefront), so the fixed launches still converge; a bimodal population is not, and
-        # its heads are finished by one workgroup each
+        # (hottest page of every wavefront) and structure along the sequence by the per-slice mixture the start is
+        # taken from, so the fixed launches still converge; of two populations interleaved at random a rare head needs
+        # one more evaluation, done by its gathering workgroup alone
         gsel = {}
         gm = torch.Generator().manual_seed(17)
         base_mu = torch.randn(B, Hq, M, generator=gm)
@@ -794,8 +795,11 @@ def main():
         hot64 = base_mu.clone(); hot64[:, :, torch.randperm(M, generator=gm)[:64]] += 8.0
         hot4 = base_mu.clone(); hot4[:, :, torch.randperm(M, generator=gm)[:4]] += 6.0
         bimodal = torch.cat([torch.randn(B, Hq, M // 2, generator=gm), 3 + 0.5 * torch.randn(B, Hq, M - M // 2, generator=gm)], dim=-1)
+        shuffled = bimodal[:, :, torch.randperm(M, generator=gm)].contiguous()
+        trend = base_mu + torch.linspace(0, 4, M)
         for name, mu_t in (("homogeneous", base_mu), ("4_pages_plus_6_sigma", hot4), ("64_pages_plus_8_sigma", hot64),
-                           ("bimodal", bimodal)):
+                           ("bimodal", bimodal), ("bimodal_interleaved", shuffled),
+                           ("trend_plus_4_sigma_along_the_sequence", trend)):
             mu_d, sg_d = mu_t.to(dev).contiguous(), one_sg.to(dev)
             gsel[name] = round(R.time_call(lambda st: ekv.ekv_select_gauss(st0.cfg, mu_d, sg_d, st0.inp["seq_lens"], args.q_page,
                                                                            0.0, st0.tau_hat, st0.page_idx, st0.n_sel,
