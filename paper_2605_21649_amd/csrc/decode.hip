@@ -914,7 +914,7 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
     // The usual row is done here: a few dozen groups pass.  A flat row, where most groups still pass, has its group
     // maxima crowded into the last few of the 64 steps below the maximum; the same certificate on a histogram of
     // [bound, maximum] resolves them (twice at most: 1/64^3 of the first width), and the list is rebuilt.
-    if (n_pass <= kSolveWaves * kRoundLoads || refine == 2) break;
+    if (__builtin_expect(n_pass <= kSolveWaves * kRoundLoads || refine == 2, 1)) break;
     const float step2 = (zmax - thr) * (1.0f / 64.0f), inv_step2 = 64.0f / (zmax - thr);
     if (tid < 64) sh.hist[tid] = 0;
     __syncthreads();
@@ -946,7 +946,7 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
       for (int i = 0; i < kSolveWaves; ++i) { const int ci = sh.wcount[parity][i]; if (i < w) off += ci; tot += ci; }
       n_list += tot;
       parity ^= 1;
-      if (in_lds && n_list > kListCap) {
+      if (__builtin_expect(in_lds && n_list > kListCap, 0)) {
         // The list outgrows LDS: it continues in the row's overflow list, to which the entries of the earlier rounds
         // move first (the barrier above ordered their LDS writes).
         in_lds = false;
@@ -969,10 +969,10 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
           off += __popcll(mk);
         }
       };
-      if (in_lds) emit(sh.list_u, sh.list_pos);
+      if (__builtin_expect(in_lds, 1)) emit(sh.list_u, sh.list_pos);
       else if (in_spill) emit(su, sp);
     };
-    if (n_pass <= kRoundGroups) {
+    if (__builtin_expect(n_pass <= kRoundGroups, 1)) {
       // the usual case, one round: only the loads the round needs
       const int per = (n_pass + kSolveWaves - 1) / kSolveWaves;
       const int jw = w * per;
@@ -1080,7 +1080,7 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
   // 16-lane rows -- and the other fifteen leave; nothing below this point needs a barrier then.
   const bool block_extras = (A.ex.tau_ref != nullptr && (A.ex.kept_mass_ref != nullptr || A.ex.kept_supp_ref != nullptr)) ||
                             (DENSE && A.ex.lse != nullptr);
-  if (in_lds && n_list <= kWaveList && !block_extras) {
+  if (__builtin_expect(in_lds && n_list <= kWaveList && !block_extras, 1)) {
     if (w != 0) return;
     constexpr int KW = kWaveList / 64;
     float u[KW]; int pos[KW]; uint32_t row[KW];
