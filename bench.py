@@ -646,8 +646,17 @@ def main():
             us_b, _, _ = R.run_timed(R.step_topk, side, 5, stages=False)
             R.k_pages = k_pages
             sel_b = B * Hq * kp * P
+            # the score pass of the sparse decode alone at this budget (every copy holds this budget's lists now): its
+            # fixed costs (the dependent lookups in front of a wavefront's first K load, the last wavefronts of the
+            # launch) weigh less the more there is to read
+            t_sp = R.back_to_back(lambda st: ekv.ekv_decode_sparse(st.cfg, st.inp["q"], st.cache(), st.page_idx, st.n_sel,
+                                                                   st.out, st.tau, st.supp, st.ws_sparse, extras=ex_pass1))
+            sp_bytes = sel_b * d * e + sel_b * 4 + sel_b / 64 * 4
             extras[f"topk_{frac:.0%}"] = {
                 "pages_per_head": kp, "step_us": round(us_b, 2),
+                "decode_score_pass_us": round(t_sp, 2),
+                "decode_score_pass_GBps": round(sp_bytes / (t_sp * 1e-6) / 1e9, 1),
+                "decode_score_pass_frac_of_hbm_peak": round(sp_bytes / (t_sp * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
                 "effective_kv_GBps": round((bytes_meta + bytes_scores + sel_b * (d * e + 8)) / (us_b * 1e-6) / 1e9, 1),
                 "delta_mean": round(float((1 - kept_mass).mean()), 6),
                 "rho_mean": round(float((kept_supp.float() / supp_f.float()).mean()), 4),
