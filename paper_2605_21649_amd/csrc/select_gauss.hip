@@ -121,8 +121,9 @@ __device__ __forceinline__ void page_mass(float muY, float sY, float cnt, float&
 }
 
 // Iteration state of one (b,h): the point the next evaluation is taken at, and its bracket.
-// `step` is the Newton step that led to tau (0: none yet, or the point came from a fallback).
-struct GaussState { float tau, lo, hi; int done; float step; int order; };   // order of the update that gave `step`
+// `step` is the step that led to tau and `order` the order of the update that produced it (3: a Halley-type step,
+// 2: Newton on log F, 0: none yet, or the point came from a fallback).
+struct GaussState { float tau, lo, hi; int done; float step; int order; };
 
 // workspace: state[2][BH], init partials [BH][S][4], eval partials [2][BH][S][3],
 //            hottest page (a mu, a sigma, count) of every wavefront of the init launch [BH][S*4][3],
