@@ -224,7 +224,7 @@ ekv_status ekv_select_box_threshold(const ekv_config* cfg, const float* box, con
  *   tau_seed f32 [B][Hq] (input): a guess of tau for a warm start -- the Gaussian-aware estimate
  *       tau-hat of the same query (Sec. 4.3 uses it as the solver's starting point), or the threshold
  *       of an earlier solve.  It only chooses where the exact solve starts: the first evaluation is taken
- *       at the seed when it lies inside the certified bracket, and, on rows of at most 65 536 candidates,
+ *       at the seed when it lies inside the certified bracket, and, on rows of at most 262 144 candidates,
  *       a seed that the group maxima certify as a lower bound of tau also serves as the candidate
  *       threshold.  Any value (wrong, infinite, NaN) is safe; tau, supp and out do not depend on it
  *       beyond float32 rounding of the last iterate.
