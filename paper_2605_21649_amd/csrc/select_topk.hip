@@ -304,19 +304,15 @@ __global__ __launch_bounds__(kSelThreads) void topk_find_kernel(const float* __r
     if (ab < (uint32_t)k && (uint32_t)k <= below) { s_bin = bin; s_cnt = (int)(below - ab); }
   }
   __syncthreads();
-  const int b1 = s_bin, m = s_cnt;
-  const int k_rem = k - (int)tot_above[b1];            // rank of the answer inside bin b1 (1-based)
-  if (m > kTkMembers) {                                // too many (near-)ties for the ranking list:
-    if (tid == 0) ws.head[bh].redo = 1;                // this head is done here by the single-workgroup
-    __shared__ SelectShared sh;                        // algorithm and skipped by the compaction launch
-    topk_single<0>(box, seq_lens, k_pages, page_idx, n_sel, Hq, P, Mmax, cap, sh);
-    return;
-  }
+  const int b1 = s_bin;
+  int m = s_cnt;
+  const int k_bin = k - (int)tot_above[b1];            // rank of the answer inside bin b1 (1-based)
+  int k_rem = k_bin;                                   // ... inside the list of members that is ranked below
   // Members of bin b1.  In slice s they sit at positions [above_s[b1], above_s[b1 - 1]) of its prefix list
   // (above_s[-1] := pages of the slice): copied from there when the range ends inside the list.  A slice
   // whose range does not (more than kTkPrefix of its pages at or above the bin: the top pages crowd into a
   // few slices, or the budget is very large) has its 4096 scores scanned instead.
-  __shared__ int s_lo[kTkMaxSlices], s_cnt_s[kTkMaxSlices], s_start[kTkMaxSlices + 1];
+  __shared__ int s_lo[kTkMaxSlices], s_cnt_s[kTkMaxSlices], s_start[kTkMaxSlices + 1], s_all[kTkMaxSlices];
   __shared__ unsigned long long s_scan_mask;             // slices to scan (kTkMaxSlices <= 64: the first wavefront's ballot)
   static_assert(kTkMaxSlices <= 64, "one ballot covers the slices");
   if (tid < 64) {
@@ -327,7 +323,7 @@ __global__ __launch_bounds__(kSelThreads) void topk_find_kernel(const float* __r
       const int valid_s = max(0, min(kTkSlice, M - tid * kTkSlice));
       const int hi_s = b1 == 0 ? valid_s : (int)ab[b1 - 1];
       scan = hi_s > kTkPrefix && hi_s > lo_s;
-      s_lo[tid] = lo_s; s_cnt_s[tid] = scan ? 0 : hi_s - lo_s;
+      s_lo[tid] = lo_s; s_cnt_s[tid] = scan ? 0 : hi_s - lo_s; s_all[tid] = max(hi_s - lo_s, 0);
     }
     const unsigned long long mask = __ballot(scan);
     if (tid == 0) s_scan_mask = mask;
@@ -341,34 +337,134 @@ __global__ __launch_bounds__(kSelThreads) void topk_find_kernel(const float* __r
     if (tid == 0) { s_start[S] = run; s_m = run; }       // the scanned slices append behind the copied ones
   }
   __syncthreads();
-  for (int sl = tid >> 6; sl < S; sl += kSelWaves) {
-    const uint32_t* pk = ws.prefix_key + ((size_t)bh * S + sl) * kTkPrefix + s_lo[sl];
-    const int32_t* pp = ws.prefix_page + ((size_t)bh * S + sl) * kTkPrefix + s_lo[sl];
-    for (int e = tid & 63; e < s_cnt_s[sl]; e += 64) {
-      const int slot = s_start[sl] + e;
-      if (slot < kTkMembers) { mem_key[slot] = pk[e]; mem_page[slot] = pp[e]; }
-    }
-  }
-  for (unsigned long long todo = s_scan_mask; todo != 0; todo &= todo - 1) {     // workgroup-uniform, usually empty
-    const int sl = __builtin_ctzll(todo);
-    constexpr int PER = kTkSlice / kSelThreads;        // 4 scores per thread
-    float raw[PER];
-#pragma unroll
-    for (int i = 0; i < PER; ++i) raw[i] = s[min(sl * kTkSlice + tid + i * kSelThreads, M - 1)];
-#pragma unroll
-    for (int i = 0; i < PER; ++i) {
-      const int p = sl * kTkSlice + tid + i * kSelThreads;
-      const uint32_t kk = float_to_key(raw[i]);
-      if (p < M && topk_bin(kk, hd.lo, hd.shift) == b1) {
-        const int slot = atomicAdd(&s_m, 1);           // arrival order is irrelevant: ranks below are exact
-        if (slot < kTkMembers) { mem_key[slot] = kk; mem_page[slot] = p; }
+  // Every member of bin b1, wherever it is kept: fn(has, key, page, slice) is called by whole wavefronts (`has` says
+  // whether this lane holds a member); a wavefront is inside one slice at a time.
+  auto for_each_member = [&](auto&& fn) {
+    for (int sl = tid >> 6; sl < S; sl += kSelWaves) {
+      const uint32_t* pk = ws.prefix_key + ((size_t)bh * S + sl) * kTkPrefix + s_lo[sl];
+      const int32_t* pp = ws.prefix_page + ((size_t)bh * S + sl) * kTkPrefix + s_lo[sl];
+      const int cnt = s_cnt_s[sl];
+      for (int e0 = 0; e0 < cnt; e0 += 64) {
+        const int e = e0 + (tid & 63);
+        const bool has = e < cnt;
+        fn(has, has ? pk[e] : 0u, has ? pp[e] : 0, sl);
       }
+    }
+    for (unsigned long long todo = s_scan_mask; todo != 0; todo &= todo - 1) {     // workgroup-uniform, usually empty
+      const int sl = __builtin_ctzll(todo);
+      constexpr int PER = kTkSlice / kSelThreads;        // 4 scores per thread
+      float raw[PER];
+#pragma unroll
+      for (int i = 0; i < PER; ++i) raw[i] = s[min(sl * kTkSlice + tid + i * kSelThreads, M - 1)];
+#pragma unroll
+      for (int i = 0; i < PER; ++i) {
+        const int p = sl * kTkSlice + tid + i * kSelThreads;
+        const uint32_t kk = float_to_key(raw[i]);
+        fn(p < M && topk_bin(kk, hd.lo, hd.shift) == b1, kk, p, sl);
+      }
+    }
+  };
+  bool all_equal = false;
+  if (m <= kTkMembers) {
+    // the usual case: the members fit the ranking list (arrival order is irrelevant: the ranks below are exact)
+    for (int sl = tid >> 6; sl < S; sl += kSelWaves) {
+      const uint32_t* pk = ws.prefix_key + ((size_t)bh * S + sl) * kTkPrefix + s_lo[sl];
+      const int32_t* pp = ws.prefix_page + ((size_t)bh * S + sl) * kTkPrefix + s_lo[sl];
+      for (int e = tid & 63; e < s_cnt_s[sl]; e += 64) {
+        const int slot = s_start[sl] + e;
+        if (slot < kTkMembers) { mem_key[slot] = pk[e]; mem_page[slot] = pp[e]; }
+      }
+    }
+    for (unsigned long long todo = s_scan_mask; todo != 0; todo &= todo - 1) {     // workgroup-uniform, usually empty
+      const int sl = __builtin_ctzll(todo);
+      constexpr int PER = kTkSlice / kSelThreads;        // 4 scores per thread
+      float raw[PER];
+#pragma unroll
+      for (int i = 0; i < PER; ++i) raw[i] = s[min(sl * kTkSlice + tid + i * kSelThreads, M - 1)];
+#pragma unroll
+      for (int i = 0; i < PER; ++i) {
+        const int p = sl * kTkSlice + tid + i * kSelThreads;
+        const uint32_t kk = float_to_key(raw[i]);
+        if (p < M && topk_bin(kk, hd.lo, hd.shift) == b1) {
+          const int slot = atomicAdd(&s_m, 1);
+          if (slot < kTkMembers) { mem_key[slot] = kk; mem_page[slot] = p; }
+        }
+      }
+    }
+  } else {
+    // More members than the ranking list holds: many scores that are equal or nearly so.  The members are streamed
+    // (not stored) once for their smallest and largest key and a histogram of the bits below the bin's: if all keys
+    // are equal that key is the answer and the per-slice counts are already known; otherwise the sub-bin of the
+    // k-th key usually holds few enough members to rank, collected by a second pass that also counts, per slice,
+    // the members of the higher sub-bins.  Only a sub-bin that is still too large sends the head to the
+    // single-workgroup algorithm (which the compaction launch then skips).
+    __shared__ uint32_t s_kmin, s_kmax;
+    __shared__ int s_sub, s_above2, wsum2[kSelWaves];
+    const bool edge = b1 == 0 || b1 == kBins - 1;        // clamped bins: keys outside the sampled range, no sub-bins
+    const int sub_shift = max(hd.shift - kDigitBits, 0);
+    const uint32_t sub_mask = hd.shift >= kDigitBits ? (uint32_t)(kBins - 1) : ((1u << hd.shift) - 1u);
+    auto sub_of = [&](uint32_t kk) { return (int)(((kk - hd.lo) >> sub_shift) & sub_mask); };
+    tot_above[2 * tid] = 0; tot_above[2 * tid + 1] = 0;  // reused as the sub-bin histogram
+    if (tid == 0) { s_kmin = 0xffffffffu; s_kmax = 0u; s_sub = -1; s_above2 = 0; }
+    __syncthreads();
+    for_each_member([&](bool has, uint32_t kk, int, int) {
+      uint32_t lo_k = has ? kk : 0xffffffffu, hi_k = has ? kk : 0u;
+      for (int d = 32; d >= 1; d >>= 1) {
+        lo_k = min(lo_k, (uint32_t)__shfl_xor((int)lo_k, d));
+        hi_k = max(hi_k, (uint32_t)__shfl_xor((int)hi_k, d));
+      }
+      if ((tid & 63) == 0 && lo_k <= hi_k) { atomicMin(&s_kmin, lo_k); atomicMax(&s_kmax, hi_k); }
+      if (has && !edge) atomicAdd(&tot_above[sub_of(kk)], 1u);
+    });
+    __syncthreads();
+    all_equal = s_kmin == s_kmax;
+    if (all_equal) {
+      if (tid == 0) s_keyt = s_kmin;
+      if (tid < S) { s_gt[tid] = 0; s_eq[tid] = s_all[tid]; }
+    } else {
+      // sub-bin of the k_rem-th largest member: thread t owns sub-bins 2t and 2t+1; counts above by a suffix scan
+      int sub = -1, above2 = 0, m2 = m;
+      if (!edge) {
+        const uint32_t c0 = tot_above[2 * tid], c1 = tot_above[2 * tid + 1];
+        int inc = (int)(c0 + c1);
+        const int tot = inc;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) { const int t = __shfl_down(inc, d); if ((tid & 63) + d < 64) inc += t; }
+        if ((tid & 63) == 0) wsum2[tid >> 6] = inc;
+        __syncthreads();
+        int higher = 0;
+        for (int i = (tid >> 6) + 1; i < kSelWaves; ++i) higher += wsum2[i];
+        const int ab1 = higher + inc - tot;              // members in sub-bins above 2t+1
+        const int ab0 = ab1 + (int)c1;                   // ... above 2t
+        if (ab1 < k_rem && k_rem <= ab1 + (int)c1) { s_sub = 2 * tid + 1; s_above2 = ab1; s_cnt = (int)c1; }
+        if (ab0 < k_rem && k_rem <= ab0 + (int)c0) { s_sub = 2 * tid; s_above2 = ab0; s_cnt = (int)c0; }
+        __syncthreads();
+        sub = s_sub; above2 = s_above2; m2 = s_cnt;
+      }
+      if (sub < 0 || m2 > kTkMembers) {
+        if (tid == 0) ws.head[bh].redo = 1;
+        __shared__ SelectShared sh;
+        topk_single<0>(box, seq_lens, k_pages, page_idx, n_sel, Hq, P, Mmax, cap, sh);
+        return;
+      }
+      if (tid == 0) s_m = 0;
+      __syncthreads();
+      for_each_member([&](bool has, uint32_t kk, int page, int sl) {
+        const int sb = has ? sub_of(kk) : -1;
+        const unsigned long long up = __ballot(has && sb > sub);
+        if ((tid & 63) == 0 && up) atomicAdd(&s_gt[sl], __popcll(up));     // a wavefront is inside one slice
+        if (has && sb == sub) {
+          const int slot = atomicAdd(&s_m, 1);
+          if (slot < kTkMembers) { mem_key[slot] = kk; mem_page[slot] = page; }
+        }
+      });
+      m = m2; k_rem -= above2;
     }
   }
   __syncthreads();
   // exact rank of every member: larger key first, lower page first among equal keys
   // (16 lanes share a member and split the others among them; 64 members per sweep of the workgroup)
-  for (int i0 = 0; i0 < m; i0 += kSelThreads / 16) {
+  for (int i0 = 0; i0 < (all_equal ? 0 : m); i0 += kSelThreads / 16) {
     const int i = min(i0 + (tid >> 4), m - 1), l = tid & 15;
     const uint32_t kk = mem_key[i]; const int pp = mem_page[i];
     int rank = 0;
@@ -388,7 +484,7 @@ __global__ __launch_bounds__(kSelThreads) void topk_find_kernel(const float* __r
   }
   __syncthreads();
   const uint32_t key_t = s_keyt;
-  if (tid < m) {
+  if (!all_equal && tid < m) {
     const uint32_t kk = mem_key[tid];
     const int sl = mem_page[tid] / kTkSlice;
     if (kk > key_t) atomicAdd(&s_gt[sl], 1);
@@ -405,7 +501,7 @@ __global__ __launch_bounds__(kSelThreads) void topk_find_kernel(const float* __r
       const int tg = __shfl_up(gt_inc, d), te = __shfl_up(eq_inc, d);
       if (tid >= d) { gt_inc += tg; eq_inc += te; }
     }
-    const int k_eq = k_rem - __shfl(gt_inc, 63);       // pages equal to key_t that are taken
+    const int k_eq = k_bin - __shfl(gt_inc, 63);       // pages equal to key_t that are taken
     const int eq_before = eq_inc - eq_s;
     const int take_eq = max(0, min(eq_s, k_eq - eq_before));
     int off_inc = ab_s + gt_s + take_eq;

@@ -189,8 +189,10 @@ def test_select_topk_on_shared_scores(w):
                                  (270000, 5400)])       # beyond 64 slices: one workgroup per head reads the keys from memory
 def test_select_topk_long_context(M, k):
     """More than 16384 pages: the selection is split over slices of 4096 pages and several launches.
-    Synthetic float32 scores (no cache needed); heads with massive ties take the redo path."""
-    P, B, Hq = 16, 1, 8
+    Synthetic float32 scores (no cache needed); heads with massive ties at the cut: one value (known without ranking),
+    thousands of near-equal values inside one histogram bin (ranked inside a sub-bin), two values with thousands of
+    pages each inside one bin (the single-workgroup fallback)."""
+    P, B, Hq = 16, 1, 10
     Mmax = -(-M // 64) * 64
     cfg = ekv.make_config(B, Hq, Hq, 128, P, "bf16", 1.5, 0.1, Mmax, k)
     dev = torch.device("cuda")
@@ -203,6 +205,10 @@ def test_select_topk_long_context(M, k):
     scores[0, 5, ::2] = scores[0, 5, 1::2]                         # every value twice
     scores[0, 6] += np.linspace(0.0, 18.0, Mmax, dtype=np.float32)  # trend along the sequence: the top pages crowd the last slices
     scores[0, 7, rng.choice(M, 40, replace=False)] += 60.0         # a few pages far above the sampled range
+    n_cl = min(5000, M // 3)
+    scores[0, 8, rng.choice(M, n_cl, replace=False)] = (25.0 + 1e-3 * rng.random(n_cl)).astype(np.float32)   # a dense cluster
+    two = rng.choice(M, 2 * (n_cl // 2), replace=False)
+    scores[0, 9, two[: n_cl // 2]] = 25.0; scores[0, 9, two[n_cl // 2:]] = 25.001              # two crowded values
     box = torch.from_numpy(scores).to(dev)
     seq_lens = torch.full((B,), M * P - 5, dtype=torch.int32, device=dev)
     page_idx = torch.full((B, Hq, k), -1, dtype=torch.int32, device=dev)
