@@ -824,6 +824,9 @@ def main():
                     "last_5_percent_plus_10_sigma": base_s + 30 * (ramp > 0.95),
                     "first_1024_pages_plus_10_sigma": base_s + 30 * (ramp < 1024 / M),
                     "16_distinct_values": torch.round(base_s).clamp(10, 25)}
+        near = base_s.clone()                                    # 5000 pages within 1e-3 of each other, where the cut falls
+        near[:, :, torch.randperm(M, generator=gm)[:5000].to(dev)] = (25.0 + 1e-3 * torch.rand(5000, generator=gm)).to(dev)
+        shapes_t["5000_pages_within_1e-3_at_the_cut"] = near
         for name, box_t in shapes_t.items():
             box_t = box_t.contiguous()
             tsel[name] = round(R.back_to_back(lambda st: ekv.ekv_select_topk(st0.cfg, box_t, st0.inp["seq_lens"], k_pages,
