@@ -224,11 +224,13 @@ def test_select_topk_long_context(M, k):
             np.testing.assert_array_equal(idx[0, hq, : ns[0, hq]], ref)
 
 
-def test_select_gauss_long_context():
-    """Gaussian selector with 65536 pages per head (keys held in registers, 64 per lane)."""
+@pytest.mark.parametrize("alpha", [1.5, 1.25, 2.0, 4.0 / 3.0], ids=["a1.5", "a1.25", "a2", "a4/3"])
+def test_select_gauss_long_context(alpha):
+    """Gaussian selector with 65536 pages per head (keys held in registers, 64 per lane), page populations of several
+    shapes, every order beta = 1/(alpha-1) of the moments."""
     P, B, Hq, M = 16, 1, 8, 65536
     cap = 3000
-    cfg = ekv.make_config(B, Hq, Hq, 128, P, "bf16", 1.5, 0.1, M, cap)
+    cfg = ekv.make_config(B, Hq, Hq, 128, P, "bf16", alpha, 0.1, M, cap)
     dev = torch.device("cuda")
     rng = np.random.default_rng(99)
     mu = (rng.normal(size=(B, Hq, M)) * 0.25 + 1.0).astype(np.float32)
@@ -253,7 +255,7 @@ def test_select_gauss_long_context():
         ekv.ekv_select_gauss(cfg, t(mu), t(sg), seq_lens, q_page, margin, tau_hat, page_idx, n_sel, ovf, ws)
         torch.cuda.synchronize()
         for hq in range(Hq):
-            pages, th, o, g = orc.gauss_select(mu[0, hq].astype(np.float64), sg[0, hq].astype(np.float64), cnt, 1.5,
+            pages, th, o, g = orc.gauss_select(mu[0, hq].astype(np.float64), sg[0, hq].astype(np.float64), cnt, alpha,
                                                q_page, margin, cap=cap)
             assert abs(float(tau_hat[0, hq]) - th) <= 4e-6 * max(1.0, abs(th)), (float(tau_hat[0, hq]), th)
             assert int(ovf[0, hq]) == int(o)
