@@ -663,7 +663,10 @@ LONG = [synth.C2.scaled(name="C2-long-bf16", context=100000, ragged=7, n_q_heads
         synth.C1.scaled(name="C1-wide-5000", context=100000, ragged=5, n_planted=0, scale=0.05 / math.sqrt(128.0),
                         n_q_heads=2, n_kv_heads=2),
         synth.C1.scaled(name="C1-filter-wide-6000", context=300000, ragged=9, n_planted=0, scale=0.05 / math.sqrt(128.0),
-                        n_q_heads=2, n_kv_heads=2)]
+                        n_q_heads=2, n_kv_heads=2),
+        # the same through the matrix-core score pass: bf16 cache, pages of 32, two query heads per KV head, beta = 4
+        synth.C5.scaled(name="C5-wide-a125-6000", batch=1, context=100000, ragged=5, n_planted=0,
+                        scale=0.5 / math.sqrt(128.0), n_q_heads=2, n_kv_heads=1, alpha=1.25)]
 
 
 @pytest.mark.parametrize("w", LONG, ids=[w.name for w in LONG])
