@@ -972,44 +972,21 @@ __global__ __launch_bounds__(kSolveThreads) void decode_solve_kernel(const Solve
       if (__builtin_expect(in_lds, 1)) emit(sh.list_u, sh.list_pos);
       else if (in_spill) emit(su, sp);
     };
-    if (__builtin_expect(n_pass <= kRoundGroups, 1)) {
-      // the usual case, one round: only the loads the round needs
-      const int per = (n_pass + kSolveWaves - 1) / kSolveWaves;
-      const int jw = w * per;
+    for (int j0 = 0; j0 < n_pass; j0 += kRoundGroups) {     // one round in the usual case
+      const int rem = min(n_pass - j0, kRoundGroups);
+      const int per = (rem + kSolveWaves - 1) / kSolveWaves;
+      const int jw = j0 + w * per;
       float v[kRoundLoads]; int vpos[kRoundLoads];
 #pragma unroll
       for (int i = 0; i < kRoundLoads; ++i) {
         v[i] = -INFINITY; vpos[i] = 0;
         if (i < per) {                                   // wave-uniform
-          const int g = glist[min(jw + i, max(n_pass - 1, 0))];
+          const int g = glist[min(jw + i, n_pass - 1)];
           vpos[i] = g * chunk_tokens + lane;
           v[i] = zr[min(vpos[i], n_cand - 1)];
         }
       }
-      if (n_pass > 0) compact_round(0, v, vpos);
-    } else {
-      // Many groups pass (a flat row): the loads of the next round are requested before the current round is
-      // compacted, all of them unconditionally (entries past the end repeat the last group and are masked), so that
-      // the waits can leave one round in flight.
-      auto request = [&](int j0, float (&v)[kRoundLoads], int (&vpos)[kRoundLoads]) {
-        const int rem = max(min(n_pass - j0, kRoundGroups), 1);
-        const int per = (rem + kSolveWaves - 1) / kSolveWaves;
-        const int jw = j0 + w * per;
-#pragma unroll
-        for (int i = 0; i < kRoundLoads; ++i) {
-          const int g = glist[clampi(jw + i, 0, n_pass - 1)];
-          vpos[i] = g * chunk_tokens + lane;
-          v[i] = zr[min(vpos[i], n_cand - 1)];
-        }
-      };
-      float va[kRoundLoads], vb[kRoundLoads]; int pa[kRoundLoads], pb[kRoundLoads];
-      request(0, va, pa);
-      for (int j0 = 0; j0 < n_pass; j0 += 2 * kRoundGroups) {
-        request(j0 + kRoundGroups, vb, pb);
-        compact_round(j0, va, pa);
-        request(j0 + 2 * kRoundGroups, va, pa);
-        if (j0 + kRoundGroups < n_pass) compact_round(j0 + kRoundGroups, vb, pb);
-      }
+      compact_round(j0, v, vpos);
     }
     if (in_lds || in_spill) lo_u = fminf(thr - zmax, -1e-7f);
   }
@@ -1506,14 +1483,17 @@ static int device_compute_units() {
 // streams better than one that loops -- while workgroups that find no work cost about half a microsecond per
 // thousand, which bounds what a list capacity far above the lists' lengths can cost.  Every workgroup reads the U
 // lengths, so launches with many units get fewer.
-static int score_wgs_per_cu(int U) { return U <= 256 ? 16 : 8; }
+// When every page is a candidate the launch is large whatever the lists hold, and one item per wavefront, left to
+// the hardware's scheduling, measured 2-3 % faster than eight per wavefront (five alternating pairs at 1M tokens:
+// 417-459 against 431-467 us): such launches get up to 128 workgroups per compute unit.
+static int score_wgs_per_cu(int U, bool all_pages) { return U > 256 ? 8 : all_pages ? 128 : 16; }
 
 template <int G, int MODE>
 static void launch_scores(const Dims& dm, ScoreArgs sa, int32_t* pre_ws, hipStream_t st) {
   const int gp = pmax_pages(dm.P);
   const long long max_items = (long long)sa.U * (((MODE == kAllPages ? dm.Mmax : dm.cap) + gp - 1) / gp);
   long long wgs = (max_items + kScoreWaves - 1) / kScoreWaves;
-  const long long wg_cap = (long long)device_compute_units() * score_wgs_per_cu(sa.U);
+  const long long wg_cap = (long long)device_compute_units() * score_wgs_per_cu(sa.U, MODE == kAllPages);
   if (wgs > wg_cap) wgs = wg_cap;
   if (wgs < 1) wgs = 1;
   dim3 grid((unsigned)wgs), block(kScoreThreads);
