@@ -1485,8 +1485,12 @@ static int device_compute_units() {
 // lengths, so launches with many units get fewer.
 // When every page is a candidate the launch is large whatever the lists hold, and one item per wavefront, left to
 // the hardware's scheduling, measured 2-3 % faster than eight per wavefront (five alternating pairs at 1M tokens:
-// 417-459 against 431-467 us): such launches get up to 128 workgroups per compute unit.
-static int score_wgs_per_cu(int U, bool all_pages) { return U > 256 ? 8 : all_pages ? 128 : 16; }
+// 417-459 against 431-467 us; 64 sequences of 8K tokens, 512 units: 222 against 237 us): such launches get up to
+// 128 workgroups per compute unit (32 when the units are so many that reading their lengths is a cost of its own).
+static int score_wgs_per_cu(int U, bool all_pages) {
+  if (all_pages) return U <= 1024 ? 128 : 32;
+  return U <= 256 ? 16 : 8;
+}
 
 template <int G, int MODE>
 static void launch_scores(const Dims& dm, ScoreArgs sa, int32_t* pre_ws, hipStream_t st) {
