@@ -35,7 +35,7 @@ HBM_PEAK_GBS = 8000.0
 #   without the append: 256.12 + 8.00;  score pass of the sparse decode: PMC_TRAFFIC_DECODE_SCORES_C4
 PMC_TRAFFIC_SOURCE = "profiles/bench_topk_step_C4.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a plain copy)"
 PMC_TRAFFIC_SCORE_PAGES_C4 = {True: int((256.32 + 8.02) * 1024 * 1024), False: int((256.12 + 8.00) * 1024 * 1024)}
-PMC_TRAFFIC_DECODE_SCORES_C4 = int((166.70 + 2.88) * 1024 * 1024)
+PMC_TRAFFIC_DECODE_SCORES_C4 = int((166.69 + 2.88) * 1024 * 1024)
 
 # the append runs inside the scoring launch (ekv_append_score_pages) unless --two-launch-append is given
 STAGE_NAMES = {"topk": ["append_own_launch", "append+score_box", "select_topk", "decode_sparse"],
