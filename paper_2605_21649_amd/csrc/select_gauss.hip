@@ -38,6 +38,8 @@ constexpr int kGaussMaxSplits = 64;
 // workgroups read the state and leave), about what the rare continuation inside the gather kernel costs, so
 // there are no spare ones.
 constexpr int kGaussIters = 2;
+constexpr int kGaussSinglePages = 8192;    // heads of at most this many pages, in launches of at most ...
+constexpr int kGaussSingleRows = 512;      // ... this many heads, are selected by one launch
 constexpr int kGaussWaves = kGaussEvalThreads / 64;
 
 template <int IV, int N>
@@ -196,7 +198,7 @@ __global__ __launch_bounds__(kGaussEvalThreads) void gauss_init_kernel(const flo
 // bisection towards `lo`, when a step leaves it).  On homogeneous pages the slices repeat the pooled moments and
 // the root is the pooled one.  `n, m, sd`: this lane's slice (n = 0: none); `pn, pm, psd`: the pooled moments.
 template <int NB>
-__device__ float slice_mixture_guess(float n, float m, float sd, float pn, float pm, float psd, float lo) {
+__device__ __forceinline__ float slice_mixture_guess(float n, float m, float sd, float pn, float pm, float psd, float lo) {
   if (!(psd > 1e-20f)) return lo;
   float sp = pn;
 #pragma unroll
@@ -252,7 +254,7 @@ __device__ __forceinline__ HotPages load_hot_pages(const float* __restrict__ hot
 }
 
 template <int NB>
-__device__ float raise_to_hot_pages(float tau, const HotPages& h) {
+__device__ __forceinline__ float raise_to_hot_pages(float tau, const HotPages& h) {
   float lo = -INFINITY, hi = INFINITY, glo = 0.f, ghi = 0.f;
   for (int it = 0; it < 10; ++it) {
     float f = 0.f, d = 0.f;
@@ -459,7 +461,12 @@ __global__ __launch_bounds__(kGaussEvalThreads) void gauss_eval_kernel(const flo
 // convergence over all pages; if the final threshold is below the speculative one the pages are re-examined;
 // nothing passed -> the single best page; more than cap pages -> the cap best estimates (lower index on
 // ties), flagged.
-template <int NB, int ITEMS>
+// SINGLE: the whole selection in this one launch, for heads of a few thousand pages, where the four launches above
+// are nothing but their own latencies (33 us whatever the length): the workgroup takes the pooled moments itself
+// (its sixteen wavefronts own contiguous ranges of the pages and play the slices of the start's mixture, each with
+// its hottest page), iterates alone over all pages -- an evaluation costs half a microsecond per 1024 pages -- and
+// selects from the page estimates directly.
+template <int NB, int ITEMS, bool SINGLE>
 __global__ __launch_bounds__(kSelThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void gauss_gather_kernel(
     const float* __restrict__ mu, const float* __restrict__ sigma, const int32_t* __restrict__ seq_lens,
     GaussWs ws, ZqTable zq, float margin, float a, float* __restrict__ tau_hat, int32_t* __restrict__ page_idx,
@@ -475,14 +482,75 @@ __global__ __launch_bounds__(kSelThreads) __attribute__((amdgpu_waves_per_eu(4, 
   const int M = (n + P - 1) / P;
   int32_t* out = page_idx + (size_t)bh * cap;
   if (M <= 0) { if (tid == 0) { n_sel[bh] = 0; overflow[bh] = 0; tau_hat[bh] = 0.f; } return; }
-  const GaussState st1 = ws.state[(size_t)((kGaussIters - 1) & 1) * BH + bh];
-  float F, D, D2;
-  sum_eval_partials(ws, kGaussIters - 1, bh, BH, bc, F, D, D2);
-  GaussState st = advance_state(st1, F, (float)NB * D, (float)NB * D2);
-  int count = -1;
   const float cnt_last = (float)(n - (M - 1) * P);
   const float* mu_r = mu + (size_t)bh * Mmax;
   const float* sg_r = sigma + (size_t)bh * Mmax;
+  GaussState st, st1;
+  if (SINGLE) {
+    __shared__ float w_part[kSelWaves][7];                  // per wavefront: max a*mu, count, sum, sum of squares, hottest page
+    const int per_w = (M + kSelWaves - 1) / kSelWaves;      // wavefront w owns the pages [w per_w, (w+1) per_w)
+    const int p_lo = w * per_w, p_hi = min(p_lo + per_w, M);
+    float mx = -INFINITY, s0 = 0.f, s1 = 0.f, s2 = 0.f;
+    float hk = -INFINITY, hm = 0.f, hs = 1.f, hc = 0.f;
+    for (int p0 = p_lo + lane; p0 - lane < p_hi; p0 += 4 * 64) {
+      float mv[4], sv[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int p = min(p0 + j * 64, M - 1);
+        mv[j] = mu_r[p]; sv[j] = sg_r[p];
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int p = p0 + j * 64;
+        if (p < p_hi) {
+          const float m = a * mv[j], sd = a * sv[j];
+          const float c = p == M - 1 ? cnt_last : (float)P;
+          mx = fmaxf(mx, m); s0 += c; s1 = fmaf(c, m, s1); s2 = fmaf(c, fmaf(m, m, sd * sd), s2);
+          const float key = fmaf(2.f, sd, m);
+          if (key > hk) { hk = key; hm = m; hs = sd; hc = c; }
+        }
+      }
+    }
+    {
+      const float kmax = wave_max(hk);
+      const uint64_t who = __ballot(hc > 0.f && hk == kmax);
+      const int src = who ? __builtin_ctzll(who) : 0;
+      const float wm = __shfl(hm, src), wsd = __shfl(hs, src), wc = who ? __shfl(hc, src) : 0.f;
+      mx = wave_max(mx); s0 = wave_sum(s0); s1 = wave_sum(s1); s2 = wave_sum(s2);
+      if (lane == 0) {
+        w_part[w][0] = mx; w_part[w][1] = s0; w_part[w][2] = s1; w_part[w][3] = s2;
+        w_part[w][4] = wm; w_part[w][5] = wsd; w_part[w][6] = wc;
+      }
+    }
+    __syncthreads();
+    if (tid < 64) {
+      const bool has = tid < kSelWaves;
+      float pmx = has ? w_part[tid][0] : -INFINITY, c0 = has ? w_part[tid][1] : 0.f;
+      float c1 = has ? w_part[tid][2] : 0.f, c2 = has ? w_part[tid][3] : 0.f;
+      const float sl_n = c0, sl_m = c0 > 0.f ? c1 / c0 : 0.f;
+      const float sl_sd = c0 > 0.f ? sqrtf(fmaxf(c2 / c0 - sl_m * sl_m, 0.f)) : 0.f;
+      HotPages hot;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) { hot.m[j] = 0.f; hot.s[j] = 1.f; hot.c[j] = 0.f; }
+      if (has) { hot.m[0] = w_part[tid][4]; hot.s[0] = w_part[tid][5]; hot.c[0] = w_part[tid][6]; }
+      pmx = wave_max(pmx); c0 = wave_sum(c0); c1 = wave_sum(c1); c2 = wave_sum(c2);
+      const float mean = c1 / c0;
+      const float var = fmaxf(c2 / c0 - mean * mean, 0.f);
+      const float lo0 = pmx - 1.0f;
+      float tau0 = slice_mixture_guess<NB>(sl_n, sl_m, sl_sd, c0, mean, sqrtf(var), lo0);
+      tau0 = raise_to_hot_pages<NB>(tau0, hot);
+      if (tid == 0) { bc[0] = tau0; bc[1] = lo0; }
+    }
+    __syncthreads();
+    st.tau = bc[0]; st.lo = bc[1]; st.hi = INFINITY; st.done = 0; st.step = 0.f; st.order = 0;
+    st1 = st;
+  } else {
+    st1 = ws.state[(size_t)((kGaussIters - 1) & 1) * BH + bh];
+    float F, D, D2;
+    sum_eval_partials(ws, kGaussIters - 1, bh, BH, bc, F, D, D2);
+    st = advance_state(st1, F, (float)NB * D, (float)NB * D2);
+  }
+  int count = -1;
   for (int it = 0; it < 64 && !st.done; ++it) {            // finish the root iteration alone
     float f = 0.f, d = 0.f, d2 = 0.f;
     for (int p0 = tid; p0 < M; p0 += 4 * kSelThreads) {      // four pages per batch of loads
@@ -507,7 +575,7 @@ __global__ __launch_bounds__(kSelThreads) __attribute__((amdgpu_waves_per_eu(4, 
     const float D2s = block_sum(d2, red_f);
     st = advance_state(st, Fs, (float)NB * Ds, (float)NB * D2s);
   }
-  if (st.tau - margin >= spec_threshold(st1.tau, margin)) {   // the candidates are complete
+  if (!SINGLE && st.tau - margin >= spec_threshold(st1.tau, margin)) {   // the candidates are complete
     const float thr = st.tau - margin;
     const int NSS = ws.S * kGaussWaves;                      // candidate lists of this head (<= 256)
     const int c = tid < NSS ? ws.sel_cnt[(size_t)bh * NSS + tid] : 0;
@@ -630,14 +698,23 @@ static void launch_gauss_NB(const Dims& dm, const float* mu, const float* sigma,
                             const ZqTable& zq, float margin, float* tau_hat, int32_t* page_idx, int32_t* n_sel,
                             int32_t* overflow, const GaussWs& ws, hipStream_t st) {
   const int BH = dm.B * dm.Hq;
+  dim3 hgrid(BH), hblock(kSelThreads);
+  if (BH <= kGaussSingleRows && dm.Mmax <= kGaussSinglePages) {     // short heads: one launch does it all
+    if (dm.Mmax <= 4 * kSelThreads)
+      hipLaunchKernelGGL((gauss_gather_kernel<NB, 4, true>), hgrid, hblock, 0, st, mu, sigma, seq_lens, ws, zq, margin,
+                         dm.a, tau_hat, page_idx, n_sel, overflow, dm.Hq, dm.P, dm.Mmax, dm.cap, BH);
+    else
+      hipLaunchKernelGGL((gauss_gather_kernel<NB, 16, true>), hgrid, hblock, 0, st, mu, sigma, seq_lens, ws, zq, margin,
+                         dm.a, tau_hat, page_idx, n_sel, overflow, dm.Hq, dm.P, dm.Mmax, dm.cap, BH);
+    return;
+  }
   dim3 egrid(ws.S, BH), eblock(kGaussEvalThreads);
   hipLaunchKernelGGL(gauss_init_kernel, egrid, eblock, 0, st, mu, sigma, seq_lens, ws, dm.a, dm.Hq, dm.P, dm.Mmax);
   for (int k = 0; k < kGaussIters; ++k)
     hipLaunchKernelGGL(gauss_eval_kernel<NB>, egrid, eblock, 0, st, mu, sigma, seq_lens, ws, k, zq, margin, dm.a,
                        dm.Hq, dm.P, dm.Mmax, BH);
-  dim3 hgrid(BH), hblock(kSelThreads);
 #define EKV_GGATHER(ITEMS)                                                                                          \
-  hipLaunchKernelGGL((gauss_gather_kernel<NB, ITEMS>), hgrid, hblock, 0, st, mu, sigma, seq_lens, ws, zq, margin, dm.a, \
+  hipLaunchKernelGGL((gauss_gather_kernel<NB, ITEMS, false>), hgrid, hblock, 0, st, mu, sigma, seq_lens, ws, zq, margin, dm.a, \
                      tau_hat, page_idx, n_sel, overflow, dm.Hq, dm.P, dm.Mmax, dm.cap, BH)
   if (dm.Mmax <= 4 * kSelThreads) EKV_GGATHER(4);
   else if (dm.Mmax <= 16 * kSelThreads) EKV_GGATHER(16);
