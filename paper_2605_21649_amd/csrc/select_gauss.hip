@@ -224,8 +224,8 @@ __device__ __forceinline__ float slice_mixture_guess(float n, float m, float sd,
     }
     next = fmaxf(next, lo);
     const float step = fabsf(next - tau);
-    const bool close = step <= 1e-3f * psd ||
-                       (newton && prev != 0.f && step <= 0.25f * prev && step * step * step <= 2e-3f * psd * prev * prev);
+    const bool close = step <= 1e-2f * psd ||
+                       (newton && prev != 0.f && step <= 0.25f * prev && step * step * step <= 2e-2f * psd * prev * prev);
     tau = next;
     prev = newton ? step : 0.f;
     if (close) break;
@@ -270,7 +270,7 @@ __device__ __forceinline__ float raise_to_hot_pages(float tau, const HotPages& h
     if (it == 0 && !(f > 1.0f)) break;                     // the pooled start is not below the hot pages' root
     if (!(f > 0.f && d > 0.f)) { if (lo > -INFINITY) tau = lo; break; }
     const float g = __logf(f);
-    if (fabsf(g) <= 2e-3f) break;
+    if (fabsf(g) <= 2e-2f) break;
     if (g > 0.f) { lo = tau; glo = g; } else { hi = tau; ghi = g; }
     float next = tau + f * g / d;
     if (!(next > lo && next < hi)) next = lo + (hi - lo) * glo / (glo - ghi);
