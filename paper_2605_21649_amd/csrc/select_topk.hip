@@ -441,24 +441,46 @@ __global__ __launch_bounds__(kSelThreads) void topk_find_kernel(const float* __r
         __syncthreads();
         sub = s_sub; above2 = s_above2; m2 = s_cnt;
       }
-      if (sub < 0 || m2 > kTkMembers) {
+      // second pass: per slice, the members of the higher sub-bins; the members of the k-th key's sub-bin are
+      // collected for ranking if they fit -- if they do not, they may still all be one value (then their per-slice
+      // counts are all that is needed)
+      const bool collect = sub >= 0 && m2 <= kTkMembers;
+      if (tid == 0) { s_m = 0; s_kmin = 0xffffffffu; s_kmax = 0u; }
+      __syncthreads();
+      if (sub >= 0) {
+        for_each_member([&](bool has, uint32_t kk, int page, int sl) {
+          const int sb = has ? sub_of(kk) : -1;
+          const unsigned long long up = __ballot(has && sb > sub);
+          if ((tid & 63) == 0 && up) atomicAdd(&s_gt[sl], __popcll(up));     // a wavefront is inside one slice
+          const bool mine = has && sb == sub;
+          if (collect) {
+            if (mine) {
+              const int slot = atomicAdd(&s_m, 1);
+              if (slot < kTkMembers) { mem_key[slot] = kk; mem_page[slot] = page; }
+            }
+          } else {
+            uint32_t lo_k = mine ? kk : 0xffffffffu, hi_k = mine ? kk : 0u;
+            for (int d = 32; d >= 1; d >>= 1) {
+              lo_k = min(lo_k, (uint32_t)__shfl_xor((int)lo_k, d));
+              hi_k = max(hi_k, (uint32_t)__shfl_xor((int)hi_k, d));
+            }
+            const unsigned long long eqm = __ballot(mine);
+            if ((tid & 63) == 0 && eqm) { atomicMin(&s_kmin, lo_k); atomicMax(&s_kmax, hi_k); atomicAdd(&s_eq[sl], __popcll(eqm)); }
+          }
+        });
+        __syncthreads();
+      }
+      if (collect) {
+        m = m2; k_rem -= above2;
+      } else if (sub >= 0 && s_kmin == s_kmax) {
+        all_equal = true;                                  // one value fills the sub-bin: it is the k-th key
+        if (tid == 0) s_keyt = s_kmin;
+      } else {
         if (tid == 0) ws.head[bh].redo = 1;
         __shared__ SelectShared sh;
         topk_single<0>(box, seq_lens, k_pages, page_idx, n_sel, Hq, P, Mmax, cap, sh);
         return;
       }
-      if (tid == 0) s_m = 0;
-      __syncthreads();
-      for_each_member([&](bool has, uint32_t kk, int page, int sl) {
-        const int sb = has ? sub_of(kk) : -1;
-        const unsigned long long up = __ballot(has && sb > sub);
-        if ((tid & 63) == 0 && up) atomicAdd(&s_gt[sl], __popcll(up));     // a wavefront is inside one slice
-        if (has && sb == sub) {
-          const int slot = atomicAdd(&s_m, 1);
-          if (slot < kTkMembers) { mem_key[slot] = kk; mem_page[slot] = page; }
-        }
-      });
-      m = m2; k_rem -= above2;
     }
   }
   __syncthreads();

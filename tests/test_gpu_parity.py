@@ -191,7 +191,7 @@ def test_select_topk_long_context(M, k):
     """More than 16384 pages: the selection is split over slices of 4096 pages and several launches.
     Synthetic float32 scores (no cache needed); heads with massive ties at the cut: one value (known without ranking),
     thousands of near-equal values inside one histogram bin (ranked inside a sub-bin), two values with thousands of
-    pages each inside one bin (the single-workgroup fallback)."""
+    pages each inside one bin (a sub-bin filled by one value)."""
     P, B, Hq = 16, 1, 10
     Mmax = -(-M // 64) * 64
     cfg = ekv.make_config(B, Hq, Hq, 128, P, "bf16", 1.5, 0.1, Mmax, k)
