@@ -191,8 +191,9 @@ def test_select_topk_long_context(M, k):
     """More than 16384 pages: the selection is split over slices of 4096 pages and several launches.
     Synthetic float32 scores (no cache needed); heads with massive ties at the cut: one value (known without ranking),
     thousands of near-equal values inside one histogram bin (ranked inside a sub-bin), two values with thousands of
-    pages each inside one bin (a sub-bin filled by one value)."""
-    P, B, Hq = 16, 1, 10
+    pages each inside one bin (a sub-bin filled by one value), thousands of pages on a handful of adjacent float32
+    values (the single-workgroup fallback)."""
+    P, B, Hq = 16, 1, 11
     Mmax = -(-M // 64) * 64
     cfg = ekv.make_config(B, Hq, Hq, 128, P, "bf16", 1.5, 0.1, Mmax, k)
     dev = torch.device("cuda")
@@ -209,6 +210,7 @@ def test_select_topk_long_context(M, k):
     scores[0, 8, rng.choice(M, n_cl, replace=False)] = (25.0 + 1e-3 * rng.random(n_cl)).astype(np.float32)   # a dense cluster
     two = rng.choice(M, 2 * (n_cl // 2), replace=False)
     scores[0, 9, two[: n_cl // 2]] = 25.0; scores[0, 9, two[n_cl // 2:]] = 25.001              # two crowded values
+    scores[0, 10, rng.choice(M, n_cl, replace=False)] = (25.0 + 3e-5 * rng.random(n_cl)).astype(np.float32)  # ~16 adjacent values
     box = torch.from_numpy(scores).to(dev)
     seq_lens = torch.full((B,), M * P - 5, dtype=torch.int32, device=dev)
     page_idx = torch.full((B, Hq, k), -1, dtype=torch.int32, device=dev)
