@@ -75,8 +75,8 @@ typedef struct {
   float alpha;               /* entmax alpha (paper Eq. 2)                                         */
   float scale;               /* score multiplier; the paper's 1/sqrt(d) (Eq. 1)                    */
   int32_t max_pages_per_seq; /* Mmax: row length of block_table and of the per-page score arrays   */
-  int32_t max_sel_pages;     /* cap: row length of page_idx; also sizes the decode calls' launch   */
-                             /* grid, so keep it near what the selectors return                    */
+  int32_t max_sel_pages;     /* cap: row length of page_idx.  It sizes workspaces only: the time   */
+                             /* of the decode calls follows the lists' device-side lengths         */
   int32_t pool_kv_heads;     /* KV heads per physical page of the pools; 0 means n_kv_heads.  A     */
                              /* config may cover only heads [h0, h0 + n_kv_heads) of a cache with   */
                              /* more heads (to run independent head groups on separate streams):    */
