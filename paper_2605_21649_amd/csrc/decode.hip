@@ -514,7 +514,7 @@ struct SolveShared {
   int flags[64];
 };
 
-// Candidate source: the compacted LDS list, or (when it does not fit) the score row itself.
+// Candidate source: the compacted list (in LDS, or the row's overflow list in the workspace), or the score row itself.
 struct ListSrc {
   const float* u; const int32_t* pos; int n;
   __device__ __forceinline__ float get_u(int i) const { return u[i]; }
